@@ -1,0 +1,178 @@
+/*
+ * nkv.h -- C ABI of the MI355X (gfx950) NestedKV prefill compression pass.
+ *
+ * The pass runs once after a prompt is prefilled (paper Section 2, Appendix A
+ * "Inference pipeline").  For every prompt p, layer l and KV head h it
+ *   1. scores each cached key by its cosine anomaly against a stable, an
+ *      episodic (block) and a current (sliding window) anchor and combines the
+ *      three readings with the head-adaptive blend and the surprise gate
+ *      (Sections 2.1-2.4)                                   -> nkv_score
+ *   2. lets the heads of a layer compete for the layer's budget under a
+ *      per-head safeguard (Section 2.6, Appendix A)         -> nkv_budget
+ *   3. keeps each head's B_h best positions and packs their K/V rows
+ *      (Section 2.5)                                        -> nkv_select_compact
+ *
+ * General rules
+ *   - Every tensor pointer is a DEVICE pointer owned by the caller; structs,
+ *     cu_seqlens and r_per_prompt are HOST memory read during the call only.
+ *   - Tensors are dense, row-major, innermost dimension fastest:
+ *       keys   [L][H][T][d]     values [L][H][T][dv]     scores [L][H][T]
+ *     T = cu_seqlens[n_prompts] is the total token count; prompt p owns the
+ *     token rows [cu_seqlens[p], cu_seqlens[p+1]) of every (layer, head).
+ *     A "unit" is one (prompt, layer, head); units are numbered
+ *     u = (p * L + l) * H + h.
+ *   - Calls only enqueue work on `hip_stream` (a hipStream_t, NULL = default
+ *     stream) and never synchronise or allocate; the library keeps no state.
+ *     Scratch memory is the caller's `ws` (device, 256-byte aligned, at least
+ *     nkv_workspace_bytes() bytes); its contents are undefined afterwards.
+ *   - Return value: NKV_OK or a negative nkv_status.  Argument errors are
+ *     detected on the host before anything is enqueued.  Inputs must be finite;
+ *     behaviour on NaN/Inf keys or scores is undefined (but never out of bounds).
+ *   - The library is the only implementation: there is no CPU fallback.
+ */
+#ifndef NKV_H
+#define NKV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum nkv_status {
+    NKV_OK = 0,
+    NKV_EINVAL = -1,       /* null pointer, bad parameter value, r outside [0,1]      */
+    NKV_ESHAPE = -2,       /* bad L/H/d/dv, non-monotone cu_seqlens, empty prompt     */
+    NKV_EWORKSPACE = -3,   /* ws is NULL, misaligned or smaller than required         */
+    NKV_EHIP = -4,         /* a HIP call failed (launch error)                        */
+    NKV_EUNSUPPORTED = -5  /* valid request outside what the kernels cover            */
+} nkv_status;
+
+enum { NKV_DTYPE_F32 = 0, NKV_DTYPE_BF16 = 1 };
+enum { NKV_GATE_SURPRISE = 0, NKV_GATE_ONLY_AVERAGE = 1, NKV_GATE_ONLY_MAX = 2 };
+enum { NKV_SURPRISE_NORMALISED = 0, NKV_SURPRISE_RAW = 1 };
+enum { NKV_FLAG_GENERIC_KERNELS = 1u };   /* force the shape-generic scoring kernels */
+
+#define NKV_MAX_PROMPTS 64        /* prompts per call                                   */
+#define NKV_MAX_HEAD_DIM 1024     /* d and dv; both must be multiples of 8              */
+#define NKV_MAX_HEADS 32          /* KV heads per layer                                 */
+#define NKV_PIN 3.0e38f           /* score written to pinned sink positions             */
+
+/*
+ * Fixed policy constants (Appendix A "Hyperparameters").  nkv_params_default()
+ * fills in the paper's values; struct_size must be sizeof(nkv_params).
+ */
+typedef struct nkv_params {
+    uint32_t struct_size;
+    int32_t  window;          /* W = 64, current-memory window (Section 2.2)                       */
+    int32_t  block_div;       /* 32  \  episodic block size b = clip(floor(N/div), min, max),      */
+    int32_t  block_min;       /* 128  } N = that prompt's length (Section 2.2)                     */
+    int32_t  block_max;       /* 256 /                                                             */
+    int32_t  n_sink;          /* 4 leading positions pinned to NKV_PIN (Section 2.3)               */
+    int32_t  gate_mode;       /* NKV_GATE_*: surprise gate, or the "only average" / "only max"     */
+                              /* ablations of Section 3.4                                          */
+    int32_t  surprise_mode;   /* NORMALISED: min-max within the head, mean-centre, rectify, then   */
+                              /* gate (Appendix A); RAW: gate the std itself (Section 2.4 literal) */
+    uint32_t flags;           /* NKV_FLAG_*                                                        */
+    int32_t  reserved;
+    double   top_frac;        /* p = 0.10: top/bottom sets hold max(1, floor(p*N)) tokens          */
+    double   prior[3];        /* (0.4, 0.4, 0.2): stable, episodic, current (Section 2.4)          */
+    double   beta;            /* 3.0  blend temperature                                            */
+    double   tau;             /* 0.60 gate threshold                                               */
+    double   kappa;           /* 10.0 gate sharpness                                               */
+    double   safeguard;       /* 0.20: each head first keeps floor(safeguard * k0) own tokens      */
+    double   near_tol;        /* 1e-5: half-width of the band nkv_select_compact counts around a   */
+                              /* head's selection threshold                                        */
+} nkv_params;
+
+typedef struct nkv_shape {
+    int32_t L;                /* layers                                              */
+    int32_t H;                /* KV heads per layer                                  */
+    int32_t d;                /* key head dim                                        */
+    int32_t dv;               /* value head dim                                      */
+    int32_t dtype;            /* NKV_DTYPE_* of keys and values                      */
+    int32_t n_prompts;        /* 1..NKV_MAX_PROMPTS                                  */
+    const int32_t *cu_seqlens;/* HOST, n_prompts + 1 entries, cu[0] = 0, increasing  */
+} nkv_shape;
+
+/* Fills *p with the paper's constants.  Returns NKV_EINVAL if p is NULL. */
+int nkv_params_default(nkv_params *p);
+
+/* Host-side closed forms, the same ones the kernels are launched with.
+ *   nkv_block_size : b = clip(floor(N / block_div), block_min, block_max)      (Section 2.2)
+ *   nkv_k0         : floor((1 - r) * N + 1e-9), positions a head keeps before competition (Appendix A)
+ *   nkv_m_safe     : floor(safeguard * k0 + 1e-9)                              (Appendix A)
+ *   nkv_m_p        : max(1, floor(top_frac * N + 1e-9))                        (Section 2.4)
+ * They return -1 on invalid arguments. */
+int64_t nkv_block_size(int64_t N, const nkv_params *p);
+int64_t nkv_k0(int64_t N, double r);
+int64_t nkv_m_safe(int64_t k0, double safeguard);
+int64_t nkv_m_p(int64_t N, double top_frac);
+
+/* Rows nkv_select_compact will write: sum over prompts of L * H * k0(N_p, r_p)
+ * (the budgets of a layer always add up to H * k0, Section 2.6). */
+int nkv_packed_rows(const nkv_shape *shape, const double *r_per_prompt, int64_t *rows);
+
+/* Bytes of scratch that cover any of the three calls below for this shape. */
+int nkv_workspace_bytes(const nkv_shape *shape, const nkv_params *params, size_t *bytes);
+
+/*
+ * Scores (Sections 2.1-2.4).  keys -> scores[L][H][T] fp32: per prompt and head
+ * the routed score a* in [0,1], with the first min(n_sink, N) positions of every
+ * prompt set to NKV_PIN.  fp32 arithmetic on the stored key values.
+ */
+int nkv_score(const void *keys, const nkv_shape *shape, const nkv_params *params,
+              float *scores, void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
+ * The three per-scale anomalies before any normalisation (Section 2.3):
+ * a_raw[3][L][H][T] fp32 = a_s, a_e, a_c = -cos(k_hat, anchor).  This is the
+ * first stage of nkv_score made visible for inspection.
+ */
+int nkv_score_raw(const void *keys, const nkv_shape *shape, const nkv_params *params,
+                  float *a_raw, void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
+ * Head-wise memory competition (Section 2.6, Appendix A).  For prompt p with
+ * eviction ratio r_per_prompt[p] in [0,1]: k0 = nkv_k0(N_p, r), every head keeps
+ * its own nkv_m_safe(k0) best tokens, the other H*(k0 - m_safe) slots of a layer
+ * go to the best remaining (head, token) pairs; k_per_head[u] = B_h, and the B_h
+ * of a layer add up to H*k0.  Order: higher score, then lower head, then lower
+ * token index.  Exact integer work on the fp32 scores given.
+ */
+int nkv_budget(const float *scores, const nkv_shape *shape, const nkv_params *params,
+               const double *r_per_prompt, int32_t *k_per_head, void *ws, size_t ws_bytes,
+               void *hip_stream);
+
+/*
+ * Compression operator (Section 2.5).  For every unit u keep the k_per_head[u]
+ * positions with the highest score (ties: lower index) and copy their K and V
+ * rows unchanged, in ascending token order:
+ *   head_off[u]                  first output row of unit u; head_off[P*L*H] = total rows  (int64)
+ *   kept_idx [rows]              prompt-local token index of every output row              (int32)
+ *   packed_k [rows][d], packed_v [rows][dv]   bitwise copies of the kept rows
+ * `row_capacity` is the number of rows the three output buffers can hold; rows
+ * beyond it are not written (head_off still reports the true offsets).
+ * k_per_head[u] outside [0, N_p] is clamped.  If near_threshold_count is not
+ * NULL it receives the number of tokens whose score lies within params->near_tol
+ * of their head's selection threshold (the B_h-th highest score), summed over all
+ * units with 0 < B_h < N_p; these are the positions whose fate can change under
+ * score perturbations of that size.
+ */
+int nkv_select_compact(const void *keys, const void *values, const float *scores,
+                       const int32_t *k_per_head, const nkv_shape *shape, const nkv_params *params,
+                       void *packed_k, void *packed_v, int32_t *kept_idx, int64_t *head_off,
+                       int64_t row_capacity, int64_t *near_threshold_count,
+                       void *ws, size_t ws_bytes, void *hip_stream);
+
+/* Static, human-readable text for a status code. */
+const char *nkv_strerror(int status);
+
+/* Library version, major * 10000 + minor * 100 + patch. */
+int nkv_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* NKV_H */

@@ -1,0 +1,242 @@
+"""Python binding of libnkv, the MI355X (gfx950) NestedKV prefill compression pass.
+
+Argument marshalling only: every step of the pass runs in the HIP kernels behind the C ABI declared in
+``include/nkv.h``; the functions here have the same names as the C entry points.  torch is used to own
+device memory and streams.  There is no fallback: if ``libnkv.so`` has not been built
+(``python -m paper_2605_26678_amd.build``) importing the library raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import Optional, Sequence, Tuple
+
+from . import build as _build
+
+NKV_OK = 0
+NKV_EINVAL, NKV_ESHAPE, NKV_EWORKSPACE, NKV_EHIP, NKV_EUNSUPPORTED = -1, -2, -3, -4, -5
+DTYPE_F32, DTYPE_BF16 = 0, 1
+FLAG_GENERIC_KERNELS = 1
+PIN = 3.0e38
+
+EXPORTS = ("nkv_params_default", "nkv_block_size", "nkv_k0", "nkv_m_safe", "nkv_m_p", "nkv_packed_rows",
+           "nkv_workspace_bytes", "nkv_score", "nkv_score_raw", "nkv_budget", "nkv_select_compact",
+           "nkv_strerror", "nkv_version")
+
+
+class nkv_params(C.Structure):
+    _fields_ = [("struct_size", C.c_uint32), ("window", C.c_int32), ("block_div", C.c_int32),
+                ("block_min", C.c_int32), ("block_max", C.c_int32), ("n_sink", C.c_int32),
+                ("gate_mode", C.c_int32), ("surprise_mode", C.c_int32), ("flags", C.c_uint32),
+                ("reserved", C.c_int32), ("top_frac", C.c_double), ("prior", C.c_double * 3),
+                ("beta", C.c_double), ("tau", C.c_double), ("kappa", C.c_double), ("safeguard", C.c_double),
+                ("near_tol", C.c_double)]
+
+
+class nkv_shape(C.Structure):
+    _fields_ = [("L", C.c_int32), ("H", C.c_int32), ("d", C.c_int32), ("dv", C.c_int32), ("dtype", C.c_int32),
+                ("n_prompts", C.c_int32), ("cu_seqlens", C.POINTER(C.c_int32))]
+
+
+class NkvError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {strerror(status)} ({status})")
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """The loaded C-ABI library.  Raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        path = _build.library_path()
+        if not os.path.exists(path):
+            raise ImportError(f"{path} is missing: build it with `python -m paper_2605_26678_amd.build`")
+        L = C.CDLL(path)
+        vp, i64, f64 = C.c_void_p, C.c_int64, C.c_double
+        L.nkv_params_default.argtypes = [C.POINTER(nkv_params)]
+        L.nkv_block_size.argtypes = [i64, C.POINTER(nkv_params)]
+        L.nkv_block_size.restype = i64
+        L.nkv_k0.argtypes = [i64, f64]
+        L.nkv_k0.restype = i64
+        L.nkv_m_safe.argtypes = [i64, f64]
+        L.nkv_m_safe.restype = i64
+        L.nkv_m_p.argtypes = [i64, f64]
+        L.nkv_m_p.restype = i64
+        L.nkv_packed_rows.argtypes = [C.POINTER(nkv_shape), C.POINTER(f64), C.POINTER(i64)]
+        L.nkv_workspace_bytes.argtypes = [C.POINTER(nkv_shape), C.POINTER(nkv_params), C.POINTER(C.c_size_t)]
+        L.nkv_score.argtypes = [vp, C.POINTER(nkv_shape), C.POINTER(nkv_params), vp, vp, C.c_size_t, vp]
+        L.nkv_score_raw.argtypes = [vp, C.POINTER(nkv_shape), C.POINTER(nkv_params), vp, vp, C.c_size_t, vp]
+        L.nkv_budget.argtypes = [vp, C.POINTER(nkv_shape), C.POINTER(nkv_params), C.POINTER(f64), vp, vp,
+                                 C.c_size_t, vp]
+        L.nkv_select_compact.argtypes = [vp, vp, vp, vp, C.POINTER(nkv_shape), C.POINTER(nkv_params), vp, vp, vp,
+                                         vp, i64, vp, vp, C.c_size_t, vp]
+        L.nkv_strerror.argtypes = [C.c_int]
+        L.nkv_strerror.restype = C.c_char_p
+        L.nkv_version.restype = C.c_int
+        for name in EXPORTS:
+            getattr(L, name)
+        _lib = L
+    return _lib
+
+
+def strerror(status: int) -> str:
+    return lib().nkv_strerror(int(status)).decode()
+
+
+def params_default(**overrides) -> nkv_params:
+    p = nkv_params()
+    rc = lib().nkv_params_default(C.byref(p))
+    if rc:
+        raise NkvError(rc, "nkv_params_default")
+    for k, v in overrides.items():
+        if k == "prior":
+            p.prior = (C.c_double * 3)(*v)
+        else:
+            if not hasattr(p, k):
+                raise AttributeError(k)
+            setattr(p, k, v)
+    return p
+
+
+def block_size(N: int, params: Optional[nkv_params] = None) -> int:
+    p = params or params_default()
+    return int(lib().nkv_block_size(int(N), C.byref(p)))
+
+
+def k0(N: int, r: float) -> int:
+    return int(lib().nkv_k0(int(N), float(r)))
+
+
+def m_safe(k0_: int, safeguard: float = 0.20) -> int:
+    return int(lib().nkv_m_safe(int(k0_), float(safeguard)))
+
+
+def m_p(N: int, top_frac: float = 0.10) -> int:
+    return int(lib().nkv_m_p(int(N), float(top_frac)))
+
+
+class Shape:
+    """Host-side description of keys[L][H][T][d] / values[L][H][T][dv] holding one or more prompts."""
+
+    def __init__(self, L: int, H: int, d: int, dv: int, dtype: int, cu_seqlens: Sequence[int]):
+        self.cu = (C.c_int32 * len(cu_seqlens))(*[int(x) for x in cu_seqlens])
+        self.c = nkv_shape(int(L), int(H), int(d), int(dv), int(dtype), len(cu_seqlens) - 1, self.cu)
+        self.L, self.H, self.d, self.dv, self.dtype = int(L), int(H), int(d), int(dv), int(dtype)
+        self.n_prompts = len(cu_seqlens) - 1
+        self.T = int(cu_seqlens[-1])
+        self.cu_seqlens = [int(x) for x in cu_seqlens]
+
+    @property
+    def n_units(self) -> int:
+        return self.n_prompts * self.L * self.H
+
+
+def _ptr(t) -> int:
+    return 0 if t is None else int(t.data_ptr())
+
+
+def _stream(stream) -> int:
+    if stream is None:
+        import torch
+        return int(torch.cuda.current_stream().cuda_stream)
+    return int(getattr(stream, "cuda_stream", stream))
+
+
+def packed_rows(shape: Shape, r_per_prompt: Sequence[float]) -> int:
+    r = (C.c_double * shape.n_prompts)(*[float(x) for x in r_per_prompt])
+    out = C.c_int64(0)
+    rc = lib().nkv_packed_rows(C.byref(shape.c), r, C.byref(out))
+    if rc:
+        raise NkvError(rc, "nkv_packed_rows")
+    return int(out.value)
+
+
+def workspace_bytes(shape: Shape, params: Optional[nkv_params] = None) -> int:
+    p = params or params_default()
+    out = C.c_size_t(0)
+    rc = lib().nkv_workspace_bytes(C.byref(shape.c), C.byref(p), C.byref(out))
+    if rc:
+        raise NkvError(rc, "nkv_workspace_bytes")
+    return int(out.value)
+
+
+def score(keys, shape: Shape, params: nkv_params, scores, ws, stream=None) -> None:
+    """keys [L,H,T,d] (device) -> scores [L,H,T] fp32 (device), enqueued on ``stream``."""
+    rc = lib().nkv_score(_ptr(keys), C.byref(shape.c), C.byref(params), _ptr(scores), _ptr(ws),
+                         0 if ws is None else ws.numel() * ws.element_size(), _stream(stream))
+    if rc:
+        raise NkvError(rc, "nkv_score")
+
+
+def score_raw(keys, shape: Shape, params: nkv_params, a_raw, ws, stream=None) -> None:
+    """keys -> a_raw [3,L,H,T] fp32: the per-scale anomalies before normalisation."""
+    rc = lib().nkv_score_raw(_ptr(keys), C.byref(shape.c), C.byref(params), _ptr(a_raw), _ptr(ws),
+                             0 if ws is None else ws.numel() * ws.element_size(), _stream(stream))
+    if rc:
+        raise NkvError(rc, "nkv_score_raw")
+
+
+def budget(scores, shape: Shape, params: nkv_params, r_per_prompt: Sequence[float], k_per_head, ws=None,
+           stream=None) -> None:
+    """scores [L,H,T] -> k_per_head [P,L,H] int32."""
+    r = (C.c_double * shape.n_prompts)(*[float(x) for x in r_per_prompt])
+    rc = lib().nkv_budget(_ptr(scores), C.byref(shape.c), C.byref(params), r, _ptr(k_per_head), _ptr(ws),
+                          0 if ws is None else ws.numel() * ws.element_size(), _stream(stream))
+    if rc:
+        raise NkvError(rc, "nkv_budget")
+
+
+def select_compact(keys, values, scores, k_per_head, shape: Shape, params: nkv_params, packed_k, packed_v,
+                   kept_idx, head_off, row_capacity: int, near_threshold_count=None, ws=None, stream=None) -> None:
+    """Top-B_h selection, ordered compaction and K/V gather; see ``nkv_select_compact`` in nkv.h."""
+    rc = lib().nkv_select_compact(_ptr(keys), _ptr(values), _ptr(scores), _ptr(k_per_head), C.byref(shape.c),
+                                  C.byref(params), _ptr(packed_k), _ptr(packed_v), _ptr(kept_idx), _ptr(head_off),
+                                  int(row_capacity), _ptr(near_threshold_count), _ptr(ws),
+                                  0 if ws is None else ws.numel() * ws.element_size(), _stream(stream))
+    if rc:
+        raise NkvError(rc, "nkv_select_compact")
+
+
+@dataclass
+class Compressed:
+    scores: "object"        # [L,H,T] fp32
+    k_per_head: "object"    # [P,L,H] int32
+    head_off: "object"      # [P*L*H+1] int64
+    kept_idx: "object"      # [rows] int32
+    packed_k: "object"      # [rows,d]
+    packed_v: "object"      # [rows,dv]
+    near_count: "object"    # [1] int64
+
+
+class Compressor:
+    """Owns the device buffers of one workload shape and runs the three calls back to back."""
+
+    def __init__(self, shape: Shape, r_per_prompt: Sequence[float], params: Optional[nkv_params] = None,
+                 device="cuda:0", kv_dtype=None):
+        import torch
+        self.torch = torch
+        self.shape, self.params = shape, params or params_default()
+        self.r = [float(x) for x in r_per_prompt]
+        self.rows = packed_rows(shape, self.r)
+        dev = torch.device(device)
+        kv_dtype = kv_dtype or (torch.float32 if shape.dtype == DTYPE_F32 else torch.bfloat16)
+        self.ws = torch.empty(max(workspace_bytes(shape, self.params), 256), dtype=torch.uint8, device=dev)
+        self.scores = torch.empty(shape.L, shape.H, shape.T, dtype=torch.float32, device=dev)
+        self.k_per_head = torch.empty(shape.n_prompts, shape.L, shape.H, dtype=torch.int32, device=dev)
+        self.head_off = torch.empty(shape.n_units + 1, dtype=torch.int64, device=dev)
+        self.kept_idx = torch.empty(max(self.rows, 1), dtype=torch.int32, device=dev)
+        self.packed_k = torch.empty(max(self.rows, 1), shape.d, dtype=kv_dtype, device=dev)
+        self.packed_v = torch.empty(max(self.rows, 1), shape.dv, dtype=kv_dtype, device=dev)
+        self.near = torch.zeros(1, dtype=torch.int64, device=dev)
+
+    def run(self, keys, values, stream=None) -> Compressed:
+        score(keys, self.shape, self.params, self.scores, self.ws, stream)
+        budget(self.scores, self.shape, self.params, self.r, self.k_per_head, None, stream)
+        select_compact(keys, values, self.scores, self.k_per_head, self.shape, self.params, self.packed_k,
+                       self.packed_v, self.kept_idx, self.head_off, self.rows, self.near, None, stream)
+        return Compressed(self.scores, self.k_per_head, self.head_off, self.kept_idx[:self.rows],
+                          self.packed_k[:self.rows], self.packed_v[:self.rows], self.near)

@@ -1,0 +1,301 @@
+// extern "C" entry points of libnkv: argument checks, workspace layout, launches.  See include/nkv.h.
+#include <math.h>
+#include <string.h>
+
+#include "nkv_internal.h"
+
+namespace nkv {
+namespace {
+
+constexpr size_t kAlign = 256;
+size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+
+int check_params(const nkv_params *p)
+{
+    if (!p || p->struct_size != sizeof(nkv_params)) return NKV_EINVAL;
+    if (p->window < 1 || p->block_div < 1 || p->block_min < 1 || p->block_max < p->block_min) return NKV_EINVAL;
+    if (p->n_sink < 0) return NKV_EINVAL;
+    if (p->gate_mode < 0 || p->gate_mode > 2 || p->surprise_mode < 0 || p->surprise_mode > 1) return NKV_EINVAL;
+    if (!(p->top_frac > 0.0 && p->top_frac <= 1.0)) return NKV_EINVAL;
+    for (int k = 0; k < 3; ++k)
+        if (!(p->prior[k] >= 0.0) || !isfinite(p->prior[k])) return NKV_EINVAL;
+    if (!(p->prior[0] + p->prior[1] + p->prior[2] > 0.0)) return NKV_EINVAL;
+    if (!isfinite(p->beta) || !isfinite(p->tau) || !isfinite(p->kappa)) return NKV_EINVAL;
+    if (!(p->safeguard >= 0.0 && p->safeguard <= 1.0)) return NKV_EINVAL;
+    if (!(p->near_tol >= 0.0) || !isfinite(p->near_tol)) return NKV_EINVAL;
+    return NKV_OK;
+}
+
+int check_shape(const nkv_shape *s)
+{
+    if (!s || !s->cu_seqlens) return NKV_EINVAL;
+    if (s->dtype != NKV_DTYPE_F32 && s->dtype != NKV_DTYPE_BF16) return NKV_EINVAL;
+    if (s->L < 1 || s->H < 1 || s->H > NKV_MAX_HEADS || (int64_t)s->L * s->H > 65535) return NKV_ESHAPE;
+    if (s->d < 8 || s->d > NKV_MAX_HEAD_DIM || s->d % 8) return NKV_ESHAPE;
+    if (s->dv < 8 || s->dv > NKV_MAX_HEAD_DIM || s->dv % 8) return NKV_ESHAPE;
+    if (s->n_prompts < 1 || s->n_prompts > NKV_MAX_PROMPTS) return NKV_ESHAPE;
+    if (s->cu_seqlens[0] != 0) return NKV_ESHAPE;
+    for (int p = 0; p < s->n_prompts; ++p)
+        if (s->cu_seqlens[p + 1] <= s->cu_seqlens[p]) return NKV_ESHAPE;
+    const int64_t T = s->cu_seqlens[s->n_prompts];
+    if ((int64_t)s->H * T >= (1ll << 31)) return NKV_ESHAPE;          // per-layer counters are 32-bit
+    if ((int64_t)s->L * s->H * T >= (1ll << 40)) return NKV_ESHAPE;
+    return NKV_OK;
+}
+
+int esize_of(int dtype) { return dtype == NKV_DTYPE_F32 ? 4 : 2; }
+
+void fill_tab(const nkv_shape *s, const nkv_params *p, PromptTab *tab)
+{
+    memset(tab, 0, sizeof(*tab));
+    tab->n = s->n_prompts;
+    tab->T = s->cu_seqlens[s->n_prompts];
+    int blk = 0;
+    for (int i = 0; i < s->n_prompts; ++i) {
+        const int64_t N = s->cu_seqlens[i + 1] - s->cu_seqlens[i];
+        tab->tok_off[i] = s->cu_seqlens[i];
+        tab->b[i] = (int32_t)nkv_block_size(N, p);
+        tab->blk_off[i] = blk;
+        blk += (int)((N + tab->b[i] - 1) / tab->b[i]);
+        tab->m_p[i] = (int32_t)nkv_m_p(N, p->top_frac);
+    }
+    tab->tok_off[s->n_prompts] = tab->T;
+    tab->blk_off[s->n_prompts] = blk;
+}
+
+// Workspace of the scoring call, in floats from the (aligned) start.
+struct ScoreWs {
+    size_t a_raw, rnorm, bsum, ssum, total_bytes;
+};
+
+ScoreWs score_ws(const nkv_shape *s, const PromptTab &tab, bool with_a_raw)
+{
+    const size_t rows = (size_t)s->L * s->H * tab.T;
+    const size_t LH = (size_t)s->L * s->H;
+    ScoreWs w;
+    size_t off = 0;
+    w.a_raw = off;  off += with_a_raw ? align_up(3 * rows * 4) : 0;
+    w.rnorm = off;  off += align_up(rows * 4);
+    w.bsum = off;   off += align_up(LH * tab.blk_off[tab.n] * s->d * 4);
+    w.ssum = off;   off += align_up(LH * tab.n * s->d * 4);
+    w.total_bytes = off;
+    return w;
+}
+
+int check_ws(const void *ws, size_t have, size_t need)
+{
+    if (need == 0) return NKV_OK;
+    if (!ws || ((uintptr_t)ws % kAlign) != 0 || have < need) return NKV_EWORKSPACE;
+    return NKV_OK;
+}
+
+int run_raw(const void *keys, const nkv_shape *s, const nkv_params *p, const PromptTab &tab, float *a_raw,
+            char *ws, const ScoreWs &lay, hipStream_t st)
+{
+    const int LH = s->L * s->H;
+    hipError_t e;
+    if (!(p->flags & NKV_FLAG_GENERIC_KERNELS) && fast_score_supported(s->dtype, s->d, p->window, tab))
+        e = launch_score_fast(keys, LH, s->d, tab, a_raw, (float *)(ws + lay.bsum), (float *)(ws + lay.ssum), st);
+    else
+        e = launch_score_generic(keys, s->dtype, LH, s->d, p->window, tab, a_raw, (float *)(ws + lay.rnorm),
+                                 (float *)(ws + lay.bsum), (float *)(ws + lay.ssum), st);
+    return e == hipSuccess ? NKV_OK : NKV_EHIP;
+}
+
+}  // namespace
+}  // namespace nkv
+
+using namespace nkv;
+
+extern "C" {
+
+int nkv_params_default(nkv_params *p)
+{
+    if (!p) return NKV_EINVAL;
+    memset(p, 0, sizeof(*p));
+    p->struct_size = (uint32_t)sizeof(nkv_params);
+    p->window = 64;
+    p->block_div = 32;
+    p->block_min = 128;
+    p->block_max = 256;
+    p->n_sink = 4;
+    p->gate_mode = NKV_GATE_SURPRISE;
+    p->surprise_mode = NKV_SURPRISE_NORMALISED;
+    p->top_frac = 0.10;
+    p->prior[0] = 0.4; p->prior[1] = 0.4; p->prior[2] = 0.2;
+    p->beta = 3.0;
+    p->tau = 0.60;
+    p->kappa = 10.0;
+    p->safeguard = 0.20;
+    p->near_tol = 1e-5;
+    return NKV_OK;
+}
+
+int64_t nkv_block_size(int64_t N, const nkv_params *p)
+{
+    if (!p || N < 1 || p->block_div < 1 || p->block_min < 1 || p->block_max < p->block_min) return -1;
+    int64_t b = N / p->block_div;
+    if (b < p->block_min) b = p->block_min;
+    if (b > p->block_max) b = p->block_max;
+    return b;
+}
+
+int64_t nkv_k0(int64_t N, double r)
+{
+    if (N < 0 || !(r >= 0.0 && r <= 1.0)) return -1;
+    int64_t k = (int64_t)floor((1.0 - r) * (double)N + 1e-9);
+    return k > N ? N : k;
+}
+
+int64_t nkv_m_safe(int64_t k0, double safeguard)
+{
+    if (k0 < 0 || !(safeguard >= 0.0 && safeguard <= 1.0)) return -1;
+    int64_t m = (int64_t)floor(safeguard * (double)k0 + 1e-9);
+    return m > k0 ? k0 : m;
+}
+
+int64_t nkv_m_p(int64_t N, double top_frac)
+{
+    if (N < 1 || !(top_frac > 0.0 && top_frac <= 1.0)) return -1;
+    int64_t m = (int64_t)floor(top_frac * (double)N + 1e-9);
+    if (m < 1) m = 1;
+    return m > N ? N : m;
+}
+
+int nkv_packed_rows(const nkv_shape *shape, const double *r_per_prompt, int64_t *rows)
+{
+    if (!r_per_prompt || !rows) return NKV_EINVAL;
+    int rc = check_shape(shape);
+    if (rc) return rc;
+    int64_t n = 0;
+    for (int p = 0; p < shape->n_prompts; ++p) {
+        const int64_t k0 = nkv_k0(shape->cu_seqlens[p + 1] - shape->cu_seqlens[p], r_per_prompt[p]);
+        if (k0 < 0) return NKV_EINVAL;
+        n += (int64_t)shape->L * shape->H * k0;
+    }
+    *rows = n;
+    return NKV_OK;
+}
+
+int nkv_workspace_bytes(const nkv_shape *shape, const nkv_params *params, size_t *bytes)
+{
+    if (!bytes) return NKV_EINVAL;
+    int rc = check_shape(shape);
+    if (rc) return rc;
+    rc = check_params(params);
+    if (rc) return rc;
+    PromptTab tab;
+    fill_tab(shape, params, &tab);
+    *bytes = score_ws(shape, tab, true).total_bytes;     // budget and select need none
+    return NKV_OK;
+}
+
+int nkv_score_raw(const void *keys, const nkv_shape *shape, const nkv_params *params, float *a_raw, void *ws,
+                  size_t ws_bytes, void *hip_stream)
+{
+    if (!keys || !a_raw) return NKV_EINVAL;
+    int rc = check_shape(shape);
+    if (rc) return rc;
+    rc = check_params(params);
+    if (rc) return rc;
+    if ((uintptr_t)keys % 16) return NKV_EINVAL;
+    PromptTab tab;
+    fill_tab(shape, params, &tab);
+    const ScoreWs lay = score_ws(shape, tab, false);
+    rc = check_ws(ws, ws_bytes, lay.total_bytes);
+    if (rc) return rc;
+    return run_raw(keys, shape, params, tab, a_raw, (char *)ws, lay, (hipStream_t)hip_stream);
+}
+
+int nkv_score(const void *keys, const nkv_shape *shape, const nkv_params *params, float *scores, void *ws,
+              size_t ws_bytes, void *hip_stream)
+{
+    if (!keys || !scores) return NKV_EINVAL;
+    int rc = check_shape(shape);
+    if (rc) return rc;
+    rc = check_params(params);
+    if (rc) return rc;
+    if ((uintptr_t)keys % 16) return NKV_EINVAL;
+    PromptTab tab;
+    fill_tab(shape, params, &tab);
+    const ScoreWs lay = score_ws(shape, tab, true);
+    rc = check_ws(ws, ws_bytes, lay.total_bytes);
+    if (rc) return rc;
+    hipStream_t st = (hipStream_t)hip_stream;
+    float *a_raw = (float *)((char *)ws + lay.a_raw);
+    rc = run_raw(keys, shape, params, tab, a_raw, (char *)ws, lay, st);
+    if (rc) return rc;
+    LearnerConsts lc;
+    const double psum = params->prior[0] + params->prior[1] + params->prior[2];
+    (void)psum;
+    for (int k = 0; k < 3; ++k) lc.log_prior[k] = log(params->prior[k]);   // log 0 = -inf: scale switched off
+    lc.beta = params->beta;
+    lc.tau = (float)params->tau;
+    lc.kappa = (float)params->kappa;
+    lc.n_sink = params->n_sink;
+    lc.gate_mode = params->gate_mode;
+    lc.surprise_mode = params->surprise_mode;
+    return launch_finalize(a_raw, shape->L, shape->H, tab, lc, scores, st) == hipSuccess ? NKV_OK : NKV_EHIP;
+}
+
+int nkv_budget(const float *scores, const nkv_shape *shape, const nkv_params *params, const double *r_per_prompt,
+               int32_t *k_per_head, void *ws, size_t ws_bytes, void *hip_stream)
+{
+    (void)ws; (void)ws_bytes;
+    if (!scores || !r_per_prompt || !k_per_head) return NKV_EINVAL;
+    int rc = check_shape(shape);
+    if (rc) return rc;
+    rc = check_params(params);
+    if (rc) return rc;
+    PromptTab tab;
+    fill_tab(shape, params, &tab);
+    for (int p = 0; p < shape->n_prompts; ++p) {
+        const int64_t N = shape->cu_seqlens[p + 1] - shape->cu_seqlens[p];
+        const int64_t k0 = nkv_k0(N, r_per_prompt[p]);
+        if (k0 < 0) return NKV_EINVAL;
+        tab.k0[p] = (int32_t)k0;
+        tab.m_safe[p] = (int32_t)nkv_m_safe(k0, params->safeguard);
+    }
+    return launch_budget(scores, shape->L, shape->H, tab, k_per_head, (hipStream_t)hip_stream) == hipSuccess
+               ? NKV_OK : NKV_EHIP;
+}
+
+int nkv_select_compact(const void *keys, const void *values, const float *scores, const int32_t *k_per_head,
+                       const nkv_shape *shape, const nkv_params *params, void *packed_k, void *packed_v,
+                       int32_t *kept_idx, int64_t *head_off, int64_t row_capacity, int64_t *near_threshold_count,
+                       void *ws, size_t ws_bytes, void *hip_stream)
+{
+    (void)ws; (void)ws_bytes;
+    if (!keys || !values || !scores || !k_per_head || !head_off || row_capacity < 0) return NKV_EINVAL;
+    if (row_capacity > 0 && (!packed_k || !packed_v || !kept_idx)) return NKV_EINVAL;
+    int rc = check_shape(shape);
+    if (rc) return rc;
+    rc = check_params(params);
+    if (rc) return rc;
+    if ((uintptr_t)keys % 16 || (uintptr_t)values % 16 || (uintptr_t)packed_k % 16 || (uintptr_t)packed_v % 16)
+        return NKV_EINVAL;
+    PromptTab tab;
+    fill_tab(shape, params, &tab);
+    return launch_select_compact(keys, values, scores, k_per_head, shape->L, shape->H, shape->d, shape->dv,
+                                 esize_of(shape->dtype), tab, (float)params->near_tol, packed_k, packed_v,
+                                 kept_idx, head_off, row_capacity, near_threshold_count,
+                                 (hipStream_t)hip_stream) == hipSuccess
+               ? NKV_OK : NKV_EHIP;
+}
+
+const char *nkv_strerror(int status)
+{
+    switch (status) {
+    case NKV_OK: return "ok";
+    case NKV_EINVAL: return "invalid argument (null pointer, misaligned tensor, parameter or ratio out of range)";
+    case NKV_ESHAPE: return "invalid shape (L, H, d, dv, prompt count or cu_seqlens)";
+    case NKV_EWORKSPACE: return "workspace missing, misaligned or too small";
+    case NKV_EHIP: return "HIP runtime error while enqueuing kernels";
+    case NKV_EUNSUPPORTED: return "request not covered by the kernels";
+    default: return "unknown status";
+    }
+}
+
+int nkv_version(void) { return 100; }
+
+}  // extern "C"

@@ -1,0 +1,198 @@
+// Outer learner: from the three raw anomalies of a head to its final scores
+// (paper Section 2.3 min-max, Section 2.4 reliability gaps / blend / surprise / gate, sink pinning).
+//
+// One workgroup of 1024 threads per unit (prompt, layer, head).  The head's 3*N floats (384 KB at
+// N = 32768) stay resident in L2 while the workgroup walks them seven times:
+//   pass 1      min / max of each scale
+//   pass 2..5   byte-wise radix select (most significant digit first) of the m_p-th largest and the
+//               m_p-th smallest value of each scale, six selects at once in LDS histograms
+//   pass 6      sums above / below those thresholds (fp64), and min / max / sum of the surprise
+//   pass 7      blend, gate, route, pin, write
+// The sum of the m largest values is  sum(a > T) + (m - count(a > T)) * T  with T the m-th largest,
+// which does not depend on how ties at T are broken.  Min-max is affine and increasing, so the
+// selects run on the raw anomalies and the gap is rescaled afterwards.
+#include "nkv_device.h"
+
+namespace nkv {
+namespace {
+
+constexpr int kThreads = 1024;
+
+struct HeadStats {
+    float lo[3], inv_range[3];     // inv_range = 0 when the scale is flat
+    float w[3];
+    float s_lo, s_inv_range, s_mean;
+};
+
+__device__ __forceinline__ void normalised(const float a[3], const HeadStats &hs, float at[3])
+{
+#pragma unroll
+    for (int k = 0; k < 3; ++k) at[k] = (a[k] - hs.lo[k]) * hs.inv_range[k];
+}
+
+// population standard deviation of three numbers
+__device__ __forceinline__ float std3(const float at[3])
+{
+    const float m = (at[0] + at[1] + at[2]) * (1.0f / 3.0f);
+    const float x = at[0] - m, y = at[1] - m, z = at[2] - m;
+    return sqrtf((x * x + y * y + z * z) * (1.0f / 3.0f));
+}
+
+__global__ __launch_bounds__(kThreads) void finalize_kernel(const float *__restrict__ a_raw, int L, int H,
+                                                            PromptTab tab, LearnerConsts lc,
+                                                            float *__restrict__ scores)
+{
+    __shared__ uint32_t hist[6][256];
+    __shared__ uint32_t sel_prefix[6], sel_want[6];
+    __shared__ float fscratch[16];
+    __shared__ double dscratch[16];
+    __shared__ HeadStats hs;
+
+    const int u = blockIdx.x;                    // (p * L + l) * H + h
+    const int h = u % H, l = (u / H) % L, p = u / (H * L);
+    const int N = tab.tok_off[p + 1] - tab.tok_off[p];
+    const int64_t rows = (int64_t)L * H * tab.T;
+    const int64_t base = ((int64_t)l * H + h) * tab.T + tab.tok_off[p];
+    const float *a[3] = {a_raw + base, a_raw + rows + base, a_raw + 2 * rows + base};
+    const int tid = threadIdx.x;
+
+    // ---- pass 1: min / max per scale ----
+    float lo[3], hi[3];
+#pragma unroll
+    for (int k = 0; k < 3; ++k) {
+        float mn = INFINITY, mx = -INFINITY;
+        for (int i = tid; i < N; i += kThreads) {
+            const float v = a[k][i];
+            mn = fminf(mn, v);
+            mx = fmaxf(mx, v);
+        }
+        lo[k] = block_min(mn, fscratch);
+        hi[k] = block_max(mx, fscratch);
+    }
+    if (tid == 0) {
+#pragma unroll
+        for (int k = 0; k < 3; ++k) {
+            const float range = hi[k] - lo[k];
+            hs.lo[k] = lo[k];
+            hs.inv_range[k] = range < kFlat ? 0.f : 1.0f / range;
+        }
+    }
+    if (tid < 6) { sel_prefix[tid] = 0u; sel_want[tid] = (uint32_t)min(tab.m_p[p], N); }
+    __syncthreads();
+
+    // ---- passes 2..5: six radix selects; select s = 2*k + e, e = 0 top (m-th largest), 1 bottom ----
+    for (int pass = 0; pass < 4; ++pass) {
+        const int shift = 24 - 8 * pass;
+        for (int j = tid; j < 6 * 256; j += kThreads) (&hist[0][0])[j] = 0u;
+        __syncthreads();
+        uint32_t pre[6];
+#pragma unroll
+        for (int s = 0; s < 6; ++s) pre[s] = sel_prefix[s];
+        for (int i = tid; i < N; i += kThreads) {
+#pragma unroll
+            for (int k = 0; k < 3; ++k) {
+                const uint32_t key = ord_key(a[k][i]);
+                const uint32_t hi_bits = pass == 0 ? 0u : key >> (shift + 8);
+                const uint32_t dig = (key >> shift) & 255u;
+#pragma unroll
+                for (int e = 0; e < 2; ++e) {
+                    const uint32_t want_hi = pass == 0 ? 0u : pre[2 * k + e] >> (shift + 8);
+                    if (hi_bits == want_hi) atomicAdd(&hist[2 * k + e][dig], 1u);
+                }
+            }
+        }
+        __syncthreads();
+        if (tid < 6) {
+            uint32_t want = sel_want[tid];
+            const uint32_t dig = radix_pick(hist[tid], want, (tid & 1) == 0);
+            sel_want[tid] = want;
+            sel_prefix[tid] |= dig << shift;
+        }
+        __syncthreads();
+    }
+
+    // ---- pass 6: sums beyond the thresholds; surprise statistics ----
+    const int m = min(tab.m_p[p], N);
+    HeadStats st = hs;
+    double sums[6];
+    {
+        uint32_t thr[6];
+#pragma unroll
+        for (int s = 0; s < 6; ++s) { thr[s] = sel_prefix[s]; sums[s] = 0.0; }
+        float smin = INFINITY, smax = -INFINITY;
+        double ssum = 0.0;
+        for (int i = tid; i < N; i += kThreads) {
+            float av[3], at[3];
+#pragma unroll
+            for (int k = 0; k < 3; ++k) {
+                av[k] = a[k][i];
+                const uint32_t key = ord_key(av[k]);
+                if (key > thr[2 * k]) sums[2 * k] += (double)av[k];
+                if (key < thr[2 * k + 1]) sums[2 * k + 1] += (double)av[k];
+            }
+            normalised(av, st, at);
+            const float s = std3(at);
+            smin = fminf(smin, s);
+            smax = fmaxf(smax, s);
+            ssum += (double)s;
+        }
+#pragma unroll
+        for (int s = 0; s < 6; ++s) sums[s] = block_sum(sums[s], dscratch);
+        smin = block_min(smin, fscratch);
+        smax = block_max(smax, fscratch);
+        ssum = block_sum(ssum, dscratch);
+        if (tid == 0) {
+            double z[3], zmax = -INFINITY, zsum = 0.0;
+#pragma unroll
+            for (int k = 0; k < 3; ++k) {
+                // ties at the threshold: sel_want of them belong to the set
+                const double top = sums[2 * k] + (double)sel_want[2 * k] * (double)key_value(thr[2 * k]);
+                const double bot = sums[2 * k + 1] + (double)sel_want[2 * k + 1] * (double)key_value(thr[2 * k + 1]);
+                const double delta = (top - bot) / (double)m * (double)st.inv_range[k];
+                z[k] = lc.log_prior[k] + lc.beta * delta;
+                zmax = fmax(zmax, z[k]);
+            }
+#pragma unroll
+            for (int k = 0; k < 3; ++k) { z[k] = exp(z[k] - zmax); zsum += z[k]; }
+#pragma unroll
+            for (int k = 0; k < 3; ++k) hs.w[k] = (float)(z[k] / zsum);
+            const float srange = smax - smin;
+            hs.s_lo = smin;
+            hs.s_inv_range = srange < kFlat ? 0.f : 1.0f / srange;
+            hs.s_mean = (float)((ssum / (double)N - (double)smin) * (double)hs.s_inv_range);
+        }
+        __syncthreads();
+    }
+
+    // ---- pass 7: blend, gate, route, pin ----
+    st = hs;
+    float *out = scores + base;
+    for (int i = tid; i < N; i += kThreads) {
+        float av[3], at[3];
+#pragma unroll
+        for (int k = 0; k < 3; ++k) av[k] = a[k][i];
+        normalised(av, st, at);
+        const float blend = st.w[0] * at[0] + st.w[1] * at[1] + st.w[2] * at[2];
+        const float win = fmaxf(at[0], fmaxf(at[1], at[2]));
+        float s = std3(at);
+        if (lc.surprise_mode == NKV_SURPRISE_NORMALISED)
+            s = fmaxf((s - st.s_lo) * st.s_inv_range - st.s_mean, 0.f);
+        const float alpha = 1.0f / (1.0f + expf(-lc.kappa * (s - lc.tau)));
+        float star;
+        if (lc.gate_mode == NKV_GATE_ONLY_AVERAGE) star = blend;
+        else if (lc.gate_mode == NKV_GATE_ONLY_MAX) star = win;
+        else star = (1.0f - alpha) * blend + alpha * win;
+        out[i] = i < lc.n_sink ? NKV_PIN : star;
+    }
+}
+
+}  // namespace
+
+hipError_t launch_finalize(const float *a_raw, int L, int H, const PromptTab &tab, const LearnerConsts &lc,
+                           float *scores, hipStream_t st)
+{
+    finalize_kernel<<<(unsigned)(tab.n * L * H), kThreads, 0, st>>>(a_raw, L, H, tab, lc, scores);
+    return hipGetLastError();
+}
+
+}  // namespace nkv

@@ -1,0 +1,59 @@
+// Internal declarations shared by the HIP sources of libnkv (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "nkv.h"
+
+namespace nkv {
+
+// Per-prompt integers, passed to kernels by value (kernel argument segment).
+struct PromptTab {
+    int32_t n;                               // prompts
+    int32_t T;                               // total tokens
+    int32_t tok_off[NKV_MAX_PROMPTS + 1];    // first token row of the prompt (cu_seqlens)
+    int32_t b[NKV_MAX_PROMPTS];              // episodic block size of the prompt
+    int32_t blk_off[NKV_MAX_PROMPTS + 1];    // blocks before this prompt (per head)
+    int32_t m_p[NKV_MAX_PROMPTS];            // size of the top / bottom sets
+    int32_t k0[NKV_MAX_PROMPTS];             // filled for nkv_budget only
+    int32_t m_safe[NKV_MAX_PROMPTS];         // filled for nkv_budget only
+};
+
+// Scalars of the outer learner in the precision the kernels use them.
+struct LearnerConsts {
+    double log_prior[3];
+    double beta;
+    float tau, kappa;
+    int32_t n_sink, gate_mode, surprise_mode;
+};
+
+constexpr float kEps = 1e-12f;    // clamp of vector norms
+constexpr float kFlat = 1e-6f;    // a min-max range below this carries no ranking
+
+// ---- scoring, shape-generic kernels (any d multiple of 8, any window / block size, fp32 or bf16) ----
+hipError_t launch_score_generic(const void *keys, int dtype, int LH, int d, int window, const PromptTab &tab,
+                                float *a_raw, float *rnorm, float *bsum, float *ssum, hipStream_t st);
+
+// ---- scoring, streaming kernels for bf16 keys, d in {64,128}, window 64, block size <= 256 ----
+bool fast_score_supported(int dtype, int d, int window, const PromptTab &tab);
+size_t fast_score_ws_floats(int LH, int d, const PromptTab &tab);
+hipError_t launch_score_fast(const void *keys, int LH, int d, const PromptTab &tab, float *a_raw,
+                             float *bsum, float *ssum, hipStream_t st);
+
+// ---- per-head statistics, blend weights, gate and final scores ----
+hipError_t launch_finalize(const float *a_raw, int L, int H, const PromptTab &tab, const LearnerConsts &lc,
+                           float *scores, hipStream_t st);
+
+// ---- head-wise budgets ----
+hipError_t launch_budget(const float *scores, int L, int H, const PromptTab &tab, int32_t *k_per_head,
+                         hipStream_t st);
+
+// ---- selection, ordered compaction, gather ----
+hipError_t launch_select_compact(const void *keys, const void *values, const float *scores,
+                                 const int32_t *k_per_head, int L, int H, int d, int dv, int esize,
+                                 const PromptTab &tab, float near_tol, void *packed_k, void *packed_v,
+                                 int32_t *kept_idx, int64_t *head_off, int64_t row_capacity,
+                                 int64_t *near_count, hipStream_t st);
+
+}  // namespace nkv

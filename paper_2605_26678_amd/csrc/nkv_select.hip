@@ -1,0 +1,208 @@
+// Compression operator (paper Section 2.5): per unit keep the B_h best positions (ties: lower index),
+// in ascending token order, and copy their K / V rows unchanged into a dense ragged cache.
+//
+//   head_off_kernel : exclusive scan of the clamped budgets -> first output row of every unit
+//   select_kernel   : one workgroup per unit.  Byte-wise radix select of the B_h-th highest score
+//                     (threshold key T, and how many of the tokens tied at T are kept), then an ordered
+//                     stream compaction: a block-wide scan of (score > T, score == T) flags gives each
+//                     kept token its output slot; kept_idx is written in ascending order.
+//   gather_kernel   : flat over output rows; each row is a straight 16-byte-vector copy of one K row
+//                     and one V row.
+#include "nkv_device.h"
+
+namespace nkv {
+namespace {
+
+constexpr int kThreads = 1024;
+constexpr int kWaves = kThreads / kWave;
+
+__device__ __forceinline__ int unit_len(const PromptTab &tab, int L, int H, int u)
+{
+    const int p = u / (H * L);
+    return tab.tok_off[p + 1] - tab.tok_off[p];
+}
+
+// Inclusive scan across the workgroup of a 64-bit value holding two 32-bit counters.
+// Returns the inclusive prefix; *total receives the workgroup sum.  `scratch` holds kWaves + 1 entries.
+__device__ __forceinline__ unsigned long long block_scan_incl(unsigned long long v, unsigned long long *scratch,
+                                                              unsigned long long *total)
+{
+    const int lane = threadIdx.x & (kWave - 1), w = threadIdx.x / kWave;
+#pragma unroll
+    for (int o = 1; o < kWave; o <<= 1) {
+        const unsigned long long t = __shfl_up(v, o, kWave);
+        if (lane >= o) v += t;
+    }
+    __syncthreads();
+    if (lane == kWave - 1) scratch[w] = v;
+    __syncthreads();
+    unsigned long long before = 0, all = 0;
+    for (int i = 0; i < kWaves; ++i) {
+        const unsigned long long s = scratch[i];
+        if (i < w) before += s;
+        all += s;
+    }
+    *total = all;
+    return v + before;
+}
+
+__global__ __launch_bounds__(kThreads) void head_off_kernel(const int32_t *__restrict__ k_per_head, int L, int H,
+                                                            PromptTab tab, int64_t *__restrict__ head_off,
+                                                            int64_t *__restrict__ near_count)
+{
+    __shared__ unsigned long long scratch[kWaves + 1];
+    const int n_units = tab.n * L * H;
+    unsigned long long carry = 0;
+    if (threadIdx.x == 0 && near_count) *near_count = 0;
+    for (int u0 = 0; u0 < n_units; u0 += kThreads) {
+        const int u = u0 + threadIdx.x;
+        unsigned long long v = 0;
+        if (u < n_units) v = (unsigned long long)min(max(k_per_head[u], 0), unit_len(tab, L, H, u));
+        unsigned long long total;
+        const unsigned long long incl = block_scan_incl(v, scratch, &total);
+        if (u < n_units) head_off[u] = (int64_t)(carry + incl - v);
+        carry += total;
+    }
+    if (threadIdx.x == 0) head_off[n_units] = (int64_t)carry;
+}
+
+__global__ __launch_bounds__(kThreads) void select_kernel(const float *__restrict__ scores,
+                                                          const int32_t *__restrict__ k_per_head, int L, int H,
+                                                          PromptTab tab, float near_tol,
+                                                          const int64_t *__restrict__ head_off,
+                                                          int64_t row_capacity, int32_t *__restrict__ kept_idx,
+                                                          int64_t *__restrict__ near_count)
+{
+    __shared__ uint32_t hist[256];
+    __shared__ uint32_t s_prefix, s_want;
+    __shared__ unsigned long long scratch[kWaves + 1];
+    __shared__ unsigned long long near_acc[16];
+
+    const int u = blockIdx.x;
+    const int h = u % H, l = (u / H) % L, p = u / (H * L);
+    const int N = tab.tok_off[p + 1] - tab.tok_off[p];
+    const int B = min(max(k_per_head[u], 0), N);
+    if (B == 0) return;
+    const float *sc = scores + ((int64_t)l * H + h) * tab.T + tab.tok_off[p];
+    const int tid = threadIdx.x;
+    const int64_t out0 = head_off[u];
+
+    uint32_t T = 0u, rem = 0u;                       // B == N: every key >= 0 is kept
+    if (B < N) {
+        if (tid == 0) { s_prefix = 0u; s_want = (uint32_t)B; }
+        __syncthreads();
+        for (int pass = 0; pass < 4; ++pass) {
+            const int shift = 24 - 8 * pass;
+            if (tid < 256) hist[tid] = 0u;
+            __syncthreads();
+            const uint32_t pre = s_prefix;
+            for (int i = tid; i < N; i += kThreads) {
+                const uint32_t key = ord_key(sc[i]);
+                if (pass == 0 || (key >> (shift + 8)) == (pre >> (shift + 8)))
+                    atomicAdd(&hist[(key >> shift) & 255u], 1u);
+            }
+            __syncthreads();
+            if (tid == 0) {
+                uint32_t want = s_want;
+                const uint32_t dig = radix_pick(hist, want, 1);
+                s_want = want;
+                s_prefix |= dig << shift;
+            }
+            __syncthreads();
+        }
+        T = s_prefix;
+        rem = s_want;
+        if (near_count) {                            // tokens within near_tol of the threshold score
+            const float tv = key_value(T);
+            unsigned long long c = 0;
+            for (int i = tid; i < N; i += kThreads) c += fabsf(sc[i] - tv) <= near_tol ? 1ull : 0ull;
+            c = block_sum(c, near_acc);
+            if (tid == 0) atomicAdd((unsigned long long *)near_count, c);
+        }
+    }
+
+    // ordered compaction
+    uint32_t carry_gt = 0u, carry_eq = 0u;
+    for (int i0 = 0; i0 < N; i0 += kThreads) {
+        const int i = i0 + tid;
+        uint32_t gt = 0u, eq = 0u;
+        if (i < N) {
+            const uint32_t key = ord_key(sc[i]);
+            if (B == N) gt = 1u;
+            else { gt = key > T ? 1u : 0u; eq = key == T ? 1u : 0u; }
+        }
+        const unsigned long long v = ((unsigned long long)gt << 32) | eq;
+        unsigned long long total;
+        const unsigned long long incl = block_scan_incl(v, scratch, &total);
+        const uint32_t gt_before = carry_gt + (uint32_t)(incl >> 32) - gt;
+        const uint32_t eq_before = carry_eq + (uint32_t)(incl & 0xffffffffu) - eq;
+        if (gt || (eq && eq_before < rem)) {
+            const int64_t row = out0 + gt_before + min(eq_before, rem);
+            if (row < row_capacity) kept_idx[row] = i;
+        }
+        carry_gt += (uint32_t)(total >> 32);
+        carry_eq += (uint32_t)(total & 0xffffffffu);
+    }
+}
+
+constexpr int kRowsPerGroup = 32;
+
+// 16-byte vectors; krow16 / vrow16 = vectors per K / V row.
+__global__ __launch_bounds__(256) void gather_kernel(const uint4 *__restrict__ keys, const uint4 *__restrict__ values,
+                                                     int L, int H, int krow16, int vrow16, PromptTab tab,
+                                                     const int64_t *__restrict__ head_off,
+                                                     const int32_t *__restrict__ kept_idx, int64_t row_capacity,
+                                                     uint4 *__restrict__ packed_k, uint4 *__restrict__ packed_v)
+{
+    __shared__ int64_t src[kRowsPerGroup];
+    const int n_units = tab.n * L * H;
+    const int64_t rows = min(head_off[n_units], row_capacity);
+    const int64_t r0 = (int64_t)blockIdx.x * kRowsPerGroup;
+    if (r0 >= rows) return;
+    const int nr = (int)min((int64_t)kRowsPerGroup, rows - r0);
+    if ((int)threadIdx.x < nr) {
+        const int64_t r = r0 + threadIdx.x;
+        int lo = 0, hi = n_units;                   // largest u with head_off[u] <= r
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (head_off[mid] <= r) lo = mid; else hi = mid;
+        }
+        const int u = lo;
+        const int h = u % H, l = (u / H) % L, p = u / (H * L);
+        src[threadIdx.x] = ((int64_t)l * H + h) * tab.T + tab.tok_off[p] + kept_idx[r];
+    }
+    __syncthreads();
+    for (int j = threadIdx.x; j < nr * krow16; j += blockDim.x) {
+        const int r = j / krow16, c = j - r * krow16;
+        packed_k[(r0 + r) * krow16 + c] = keys[src[r] * krow16 + c];
+    }
+    for (int j = threadIdx.x; j < nr * vrow16; j += blockDim.x) {
+        const int r = j / vrow16, c = j - r * vrow16;
+        packed_v[(r0 + r) * vrow16 + c] = values[src[r] * vrow16 + c];
+    }
+}
+
+}  // namespace
+
+hipError_t launch_select_compact(const void *keys, const void *values, const float *scores,
+                                 const int32_t *k_per_head, int L, int H, int d, int dv, int esize,
+                                 const PromptTab &tab, float near_tol, void *packed_k, void *packed_v,
+                                 int32_t *kept_idx, int64_t *head_off, int64_t row_capacity,
+                                 int64_t *near_count, hipStream_t st)
+{
+    const int n_units = tab.n * L * H;
+    head_off_kernel<<<1, kThreads, 0, st>>>(k_per_head, L, H, tab, head_off, near_count);
+    select_kernel<<<(unsigned)n_units, kThreads, 0, st>>>(scores, k_per_head, L, H, tab, near_tol, head_off,
+                                                          row_capacity, kept_idx, near_count);
+    // no unit keeps more than its prompt length, so the row count is bounded by L*H*T as well
+    const int64_t max_rows = row_capacity < (int64_t)L * H * tab.T ? row_capacity : (int64_t)L * H * tab.T;
+    if (max_rows > 0) {
+        const unsigned groups = (unsigned)((max_rows + kRowsPerGroup - 1) / kRowsPerGroup);
+        gather_kernel<<<groups, 256, 0, st>>>((const uint4 *)keys, (const uint4 *)values, L, H, d * esize / 16,
+                                              dv * esize / 16, tab, head_off, kept_idx, row_capacity,
+                                              (uint4 *)packed_k, (uint4 *)packed_v);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace nkv

@@ -1,0 +1,240 @@
+"""Parity of the HIP path (through the C ABI) against the CPU oracle on the same seeded inputs.
+
+Bars are defined in tests/parity_util.py.  Sizes: the small workloads are compared in full; the 16k / 32k /
+ragged workloads run at full size in the launch configuration bench.py times and are compared on sampled
+layers, which the oracle computes one by one."""
+import numpy as np
+import pytest
+import torch
+
+import nkv_inputs
+import oracle
+import paper_2605_26678_amd as nkv
+from parity_util import (SCORE_TOL, bits, compare_end_to_end, compare_stages, oracle_params, run_gpu, shape_of)
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+
+def _kv(w, device=DEV):
+    K, V = nkv_inputs.make_kv(w, device)
+    return K.contiguous(), V.contiguous()
+
+
+def _report(name, st):
+    print(f"\n[{name}] worst score err {st['worst']:.2e}; units {st['units']}; positions kept by one side only "
+          f"{st['flipped']}; budget moved by {st['budget_moved']}; near-threshold (GPU count) {st['near_gpu']}")
+
+
+# ------------------------------------------------------------------ the named workloads
+def test_tiny_fp32_full():
+    w = nkv_inputs.WORKLOADS["tiny"]
+    K, V = _kv(w)
+    compare_stages(w, K, V, 0.5, label="tiny")
+    _report("tiny", compare_end_to_end(w, K, V, 0.5, label="tiny"))
+
+
+@pytest.mark.parametrize("r", [0.5, 0.75])
+def test_llama1b_4k_full(r):
+    w = nkv_inputs.WORKLOADS["llama1b_4k"]
+    K, V = _kv(w)
+    compare_stages(w, K, V, r, label=f"llama1b r={r}")
+    _report(f"llama1b_4k r={r}", compare_end_to_end(w, K, V, r, label="llama1b"))
+
+
+@pytest.mark.parametrize("r", [0.75, 0.95])
+def test_qwen4b_16k_sampled_layers(r):
+    w = nkv_inputs.WORKLOADS["qwen4b_16k"]
+    K, V = _kv(w)
+    _report(f"qwen4b_16k r={r}", compare_end_to_end(w, K, V, r, layers=[0, 17, 35], label="qwen16k"))
+
+
+def test_qwen4b_32k_headline_sampled_layers():
+    w = nkv_inputs.WORKLOADS["qwen4b_32k"]
+    K, V = _kv(w)
+    _report("qwen4b_32k r=0.75", compare_end_to_end(w, K, V, 0.75, layers=[0, 20, 35], label="qwen32k"))
+
+
+def test_ragged_batch_sampled_layers():
+    w = nkv_inputs.WORKLOADS["llama3b_ragged"]
+    K, V = _kv(w)
+    _report("llama3b_ragged r=0.95", compare_end_to_end(w, K, V, 0.95, layers=[0, 27], label="ragged"))
+
+
+# ------------------------------------------------------------------ shape sweep, ragged tails, degenerate cases
+SWEEP = [
+    # name, L, H, d, prompt_lens, dtype, dv
+    ("one_token", 1, 1, 64, [1], "bf16", 0),
+    ("below_sinks", 1, 2, 64, [3], "bf16", 0),
+    ("below_window", 2, 2, 128, [37], "bf16", 0),
+    ("one_short_block", 1, 3, 128, [100], "bf16", 0),
+    ("block_tail", 2, 2, 128, [130], "bf16", 0),
+    ("odd_len_64", 1, 4, 64, [1000], "bf16", 0),
+    ("b_between", 1, 2, 128, [6400], "bf16", 0),          # b = 200, not a multiple of 64
+    ("b_255", 1, 1, 128, [8191], "bf16", 0),
+    ("ragged_small", 2, 2, 128, [5, 700, 64, 4133, 129], "bf16", 0),
+    ("dv_differs", 1, 2, 128, [777], "bf16", 64),
+    ("fp32_d64", 1, 2, 64, [900], "fp32", 0),
+    ("fp32_ragged", 1, 2, 128, [300, 513], "fp32", 0),
+    ("wide_head", 1, 1, 256, [600], "bf16", 0),
+    ("d_40", 1, 2, 40, [500], "fp32", 24),
+]
+
+
+@pytest.mark.parametrize("case", SWEEP, ids=[c[0] for c in SWEEP])
+@pytest.mark.parametrize("r", [0.5, 0.9])
+def test_shape_sweep(case, r):
+    name, L, H, d, lens, dtype, dv = case
+    w = nkv_inputs.small_workload(name, L, H, d, lens, dtype=dtype, dv=dv, n_out=min(8, max(min(lens) - 4, 0)))
+    K, V = _kv(w)
+    compare_stages(w, K, V, r, label=name)
+    compare_end_to_end(w, K, V, r, label=name)
+
+
+@pytest.mark.parametrize("r", [0.0, 1.0])
+def test_keep_everything_and_keep_nothing(r):
+    w = nkv_inputs.small_workload("extremes", 2, 2, 128, [300, 77])
+    K, V = _kv(w)
+    ref = compare_stages(w, K, V, r, label=f"r={r}")
+    out, shape = run_gpu(w, K, V, r)
+    if r == 0.0:                                    # every token kept, packed == input, bit for bit
+        for p, (lo, hi) in enumerate(zip(w.cu_seqlens[:-1], w.cu_seqlens[1:])):
+            for l in range(w.L):
+                for h in range(w.H):
+                    u = (p * w.L + l) * w.H + h
+                    o = int(out.head_off[u])
+                    assert np.array_equal(bits(out.packed_k[o:o + hi - lo]), bits(K[l, h, lo:hi]))
+                    assert np.array_equal(bits(out.packed_v[o:o + hi - lo]), bits(V[l, h, lo:hi]))
+    else:
+        assert int(out.head_off[-1]) == 0 and out.kept_idx.numel() == 0
+
+
+def test_constant_keys_ties_resolve_by_index():
+    w = nkv_inputs.small_workload("const", 1, 2, 64, [40])
+    K = torch.full((1, 2, 40, 64), 0.37, dtype=torch.bfloat16, device=DEV)
+    V = torch.randn(1, 2, 40, 64, device=DEV).to(torch.bfloat16)
+    out, _ = run_gpu(w, K, V, 0.5)
+    assert out.k_per_head.reshape(-1).tolist() == [36, 4]
+    assert out.kept_idx.tolist() == list(range(36)) + [0, 1, 2, 3]
+    assert torch.all(out.scores[:, :, 4:] == 0)
+
+
+def test_heavy_ties_stage_parity():
+    """Quantised scores (many exact ties, also across heads) fed straight into budget and selection."""
+    rng = np.random.default_rng(0)
+    w = nkv_inputs.small_workload("ties", 2, 4, 64, [257, 1500])
+    K, V = _kv(w)
+    sc = (np.round(rng.random((w.L, w.H, w.T)) * 8) / 8).astype(np.float32)
+    sc[:, :, 0:4] = oracle.PIN
+    sc[:, :, 257:261] = oracle.PIN
+    sc[0, 1, 10:40] = -0.0                           # -0 ties with +0
+    op = oracle.Params()
+    for r in (0.3, 0.75, 0.97):
+        ref = oracle.compress(K.float().cpu().numpy(), bits(K), bits(V), w.cu_seqlens, [r, r], op, scores=sc)
+        out, _ = run_gpu(w, K, V, r, scores=torch.from_numpy(sc).to(DEV))
+        assert np.array_equal(out.k_per_head.cpu().numpy(), ref.k_per_head)
+        assert np.array_equal(out.kept_idx.cpu().numpy(), ref.kept_idx)
+        assert np.array_equal(bits(out.packed_k), ref.packed_k) and np.array_equal(bits(out.packed_v), ref.packed_v)
+
+
+def test_given_budgets_are_clamped_and_capacity_is_respected():
+    w = nkv_inputs.small_workload("clamp", 1, 2, 64, [50])
+    K, V = _kv(w)
+    sc = torch.rand(1, 2, 50, device=DEV)
+    kph = torch.tensor([[[60, -3]]], dtype=torch.int32, device=DEV)     # clamped to 50 and 0
+    shape, p = shape_of(w), nkv.params_default()
+    pk = torch.full((40, 64), 7.0, dtype=torch.bfloat16, device=DEV)
+    pv = torch.full((40, 64), 7.0, dtype=torch.bfloat16, device=DEV)
+    idx = torch.full((40,), -7, dtype=torch.int32, device=DEV)
+    off = torch.empty(3, dtype=torch.int64, device=DEV)
+    nkv.select_compact(K, V, sc, kph, shape, p, pk, pv, idx, off, 30)   # capacity below the 50 rows needed
+    torch.cuda.synchronize()
+    assert off.tolist() == [0, 50, 50]
+    assert idx[:30].tolist() == list(range(30)) and torch.all(idx[30:] == -7)
+    assert np.array_equal(bits(pk[:30]), bits(K[0, 0, :30])) and torch.all(pk[30:] == 7.0)
+
+
+# ------------------------------------------------------------------ parameters and variants
+VARIANTS = [
+    dict(gate_mode=1), dict(gate_mode=2), dict(surprise_mode=1), dict(beta=0.0),
+    dict(prior=(1.0, 0.0, 0.0), beta=0.0, gate_mode=1), dict(n_sink=0), dict(n_sink=9),
+    dict(window=16), dict(window=200), dict(block_min=32, block_max=96, block_div=8),
+    dict(block_min=300, block_max=512), dict(top_frac=0.25, safeguard=0.5), dict(safeguard=1.0),
+    dict(kappa=25.0, tau=0.2),
+]
+
+
+@pytest.mark.parametrize("over", VARIANTS, ids=[",".join(f"{k}={v}" for k, v in o.items()) for o in VARIANTS])
+def test_parameter_variants(over):
+    w = nkv_inputs.small_workload("variants", 1, 3, 128, [1111, 300])
+    K, V = _kv(w)
+    params = nkv.params_default(**over)
+    compare_stages(w, K, V, 0.6, params=params, label=str(over))
+    compare_end_to_end(w, K, V, 0.6, params=params, label=str(over))
+
+
+def test_generic_and_streaming_kernels_agree_with_oracle():
+    """The shape-generic scoring kernels, forced by flag, meet the same bar on a streaming-eligible shape."""
+    w = nkv_inputs.small_workload("generic", 2, 2, 128, [2000, 321])
+    K, V = _kv(w)
+    compare_end_to_end(w, K, V, 0.5, params=nkv.params_default(flags=nkv.FLAG_GENERIC_KERNELS), label="generic")
+    compare_end_to_end(w, K, V, 0.5, label="default")
+
+
+def test_raw_anomalies_match_oracle():
+    w = nkv_inputs.small_workload("raw", 1, 2, 128, [1500, 200])
+    K, _ = _kv(w)
+    shape, p = shape_of(w), nkv.params_default()
+    a = torch.empty(3, w.L, w.H, w.T, dtype=torch.float32, device=DEV)
+    ws = torch.empty(nkv.workspace_bytes(shape, p), dtype=torch.uint8, device=DEV)
+    nkv.score_raw(K, shape, p, a, ws)
+    torch.cuda.synchronize()
+    a = a.cpu().numpy()
+    for pi, (lo, hi) in enumerate(zip(w.cu_seqlens[:-1], w.cu_seqlens[1:])):
+        _, dbg = oracle.score_layer(K[0, :, lo:hi].float().cpu().numpy(), debug=("a_raw",))
+        np.testing.assert_allclose(a[:, 0, :, lo:hi], dbg["a_raw"], atol=2e-6)
+
+
+def test_scale_invariance_on_device():
+    """Scaling each key by its own power of two leaves the scores bit-identical (Section 2.1)."""
+    w = nkv_inputs.small_workload("scale", 1, 2, 128, [1024])
+    K, V = _kv(w)
+    g = torch.Generator(device=DEV)
+    g.manual_seed(5)
+    sc = torch.exp2(torch.randint(-5, 6, (1, 2, 1024, 1), device=DEV, generator=g).float()).to(torch.bfloat16)
+    out0, _ = run_gpu(w, K, V, 0.5)
+    out1, _ = run_gpu(w, (K * sc).contiguous(), V, 0.5)
+    assert torch.equal(out0.scores, out1.scores)
+    assert torch.equal(out0.kept_idx, out1.kept_idx)
+
+
+def test_deterministic_and_untouched_neighbours():
+    """Two runs give identical bits; nothing is written outside the output tensors (canaries)."""
+    w = nkv_inputs.small_workload("det", 2, 2, 128, [3000, 500])
+    K, V = _kv(w)
+    shape, p = shape_of(w), nkv.params_default()
+    rows = nkv.packed_rows(shape, [0.7, 0.7])
+    pad = 64
+    results = []
+    for _ in range(2):
+        scores = torch.full((w.L * w.H * w.T + 2 * pad,), -5.0, device=DEV)
+        pk = torch.full(((rows + 2) * w.d,), 3.0, dtype=torch.bfloat16, device=DEV)
+        pv = torch.full(((rows + 2) * w.d,), 3.0, dtype=torch.bfloat16, device=DEV)
+        idx = torch.full((rows + 2 * pad,), -9, dtype=torch.int32, device=DEV)
+        kph = torch.full((shape.n_units + 2 * pad,), -9, dtype=torch.int32, device=DEV)
+        off = torch.full((shape.n_units + 1 + 2 * pad,), -9, dtype=torch.int64, device=DEV)
+        ws = torch.empty(nkv.workspace_bytes(shape, p), dtype=torch.uint8, device=DEV)
+        s_view = scores[pad:-pad]
+        nkv.score(K, shape, p, s_view, ws)
+        nkv.budget(s_view, shape, p, [0.7, 0.7], kph[pad:-pad])
+        nkv.select_compact(K, V, s_view, kph[pad:-pad], shape, p, pk[w.d:-w.d], pv[w.d:-w.d], idx[pad:-pad],
+                           off[pad:-pad], rows)
+        torch.cuda.synchronize()
+        for t, val in ((scores, -5.0), (idx, -9), (kph, -9), (off, -9)):
+            assert torch.all(t[:pad] == val) and torch.all(t[-pad:] == val)
+        assert torch.all(pk[:w.d] == 3.0) and torch.all(pk[-w.d:] == 3.0)
+        assert torch.all(pv[:w.d] == 3.0) and torch.all(pv[-w.d:] == 3.0)
+        results.append([t.clone() for t in (scores, pk.view(torch.int16), pv.view(torch.int16), idx, kph, off)])
+    for a, b in zip(*results):
+        assert torch.equal(a, b)
