@@ -1,0 +1,176 @@
+#!/usr/bin/env python3
+"""Benchmark of the NestedKV prefill compression pass on one MI355X.
+
+A step is one pass of the whole hot path -- nkv_score, nkv_budget, nkv_select_compact back to back on one
+stream -- over one batch of synthetic keys/values that are already resident in HBM.  The default workload is
+the headline one: Qwen3-4B-shaped long prefill, 36 layers x 8 KV heads x 32768 tokens x 128, bf16, r = 0.75.
+
+Prints ONE JSON line: prompt tokens compressed per second, the roofline record of the dominant kernel
+(algorithmic bytes per launch over its HIP-event duration, against 8 TB/s), and the CPU oracle timed on this
+machine's host cores on the same inputs.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import re
+import statistics
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+
+
+def algorithmic_bytes(d, dv, esize, r):
+    """Bytes the method has to move per (head, token): keys once, scores out and in twice, kept rows in and
+    out, kept indices out.  Per kernel and in total."""
+    keep = 1.0 - r
+    scan = esize * d                      # read every key once
+    gather = 2.0 * keep * esize * (d + dv)
+    total = scan + 4 + 4 + 4 + 4 * keep + gather
+    return {"scan": float(scan), "gather": float(gather), "total": float(total)}
+
+
+def read_traffic(kernel, workload):
+    """HBM bytes per launch from the committed rocprofv3 counter summary, if there is one."""
+    path = os.path.join(ROOT, "profiles", f"{kernel}_{workload}_pmc.txt")
+    try:
+        m = re.search(r"^hbm_bytes_per_launch\s*[:=]\s*([0-9.eE+]+)", open(path).read(), re.M)
+        return float(m.group(1)) if m else None
+    except OSError:
+        return None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="qwen4b_32k")
+    ap.add_argument("--ratio", type=float, default=None)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-layers", type=int, default=0, help="layers the oracle is timed on (0 = choose)")
+    ap.add_argument("--generic", action="store_true", help="force the shape-generic scoring kernels")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no sharding, no collectives); use --gpus 1", file=sys.stderr)
+        return 2
+
+    import torch
+    import nkv_inputs
+    import paper_2605_26678_amd as nkv
+
+    nkv.lib()                                   # fails loudly if the HIP library is missing
+    w = nkv_inputs.WORKLOADS[args.workload]
+    r = args.ratio if args.ratio is not None else w.ratios[0]
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    K, V = nkv_inputs.make_kv(w, dev)
+    shape = nkv.Shape(w.L, w.H, w.d, w.d_v, nkv.DTYPE_F32 if w.dtype == "fp32" else nkv.DTYPE_BF16, w.cu_seqlens)
+    params = nkv.params_default(flags=nkv.FLAG_GENERIC_KERNELS if args.generic else 0)
+    r_list = [r] * shape.n_prompts
+    comp = nkv.Compressor(shape, r_list, params)
+    stream = torch.cuda.current_stream()
+
+    for _ in range(args.warmup):
+        comp.run(K, V, stream)
+    torch.cuda.synchronize()
+
+    # timed region: K steps, every kernel of interest bracketed by its own event pair
+    evs = [{name: (nkv.HipEvent(), nkv.HipEvent()) for name in nkv.KERNELS} for _ in range(args.steps)]
+    step_ev = [(nkv.HipEvent(), nkv.HipEvent()) for _ in range(args.steps)]
+    base_params = comp.params
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        comp.params = nkv.with_kernel_timers(base_params, evs[i])
+        step_ev[i][0].record(stream)
+        comp.run(K, V, stream)
+        step_ev[i][1].record(stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    comp.params = base_params
+
+    ms_per_step = wall * 1e3 / args.steps
+    step_ms = [a.elapsed_ms(b) for a, b in step_ev]
+    kern_ms = {name: statistics.fmean(evs[i][name][0].elapsed_ms(evs[i][name][1]) for i in range(args.steps))
+               for name in nkv.KERNELS}
+    tokens = w.T
+    value = tokens / (wall / args.steps)
+
+    esize = 4 if w.dtype == "fp32" else 2
+    ab = algorithmic_bytes(w.d, w.d_v, esize, r)
+    head_tokens = w.L * w.H * w.T
+    dominant = max(("scan", "gather"), key=lambda k: kern_ms[k])
+    achieved = ab[dominant] * head_tokens / (kern_ms[dominant] * 1e-3) / 1e9
+    roofline = {"bound": "hbm", "kernel": dominant, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                "traffic": read_traffic(dominant, w.name),
+                "bytes_per_launch": ab[dominant] * head_tokens,
+                "kernel_ms": {k: round(v, 4) for k, v in kern_ms.items()},
+                "whole_pass": {"algorithmic_bytes": ab["total"] * head_tokens,
+                               "achieved": round(ab["total"] * head_tokens / (statistics.median(step_ms) * 1e-3) / 1e9, 1),
+                               "frac": round(ab["total"] * head_tokens / (statistics.median(step_ms) * 1e-3) / 1e9
+                                             / HBM_PEAK_GBS, 4),
+                               "median_step_ms": round(statistics.median(step_ms), 4)}}
+
+    # copy yardstick: what a plain 16-byte-vector copy reaches on this machine
+    src = K.view(torch.uint8).reshape(-1)[: min(K.numel() * K.element_size(), 1 << 30)]
+    dst = torch.empty_like(src)
+    for _ in range(2):
+        nkv.copy_probe(dst, src, stream)
+    a, b = nkv.HipEvent(), nkv.HipEvent()
+    a.record(stream)
+    for _ in range(10):
+        nkv.copy_probe(dst, src, stream)
+    b.record(stream)
+    torch.cuda.synchronize()
+    roofline["copy_probe_GBs"] = round(2 * src.numel() * 10 / (a.elapsed_ms(b) * 1e-3) / 1e9, 1)
+    del src, dst
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        import numpy as np
+        import oracle
+        sys.path.insert(0, os.path.join(ROOT, "tests"))
+        from parity_util import oracle_params
+        op = oracle_params(base_params)
+        n_layers = args.cpu_layers or w.L
+        cu = w.cu_seqlens
+        spent = 0.0
+        done = 0
+        for l in range(n_layers):
+            Kl = K[l].float().cpu().numpy()
+            Kb = K[l].cpu().view(torch.int16).numpy() if esize == 2 else K[l].cpu().view(torch.int32).numpy()
+            Vb = V[l].cpu().view(torch.int16).numpy() if esize == 2 else V[l].cpu().view(torch.int32).numpy()
+            t = time.perf_counter()
+            oracle.compress(Kl[None], Kb[None], Vb[None], cu, r_list, op)
+            spent += time.perf_counter() - t
+            done += 1
+            if spent > 30.0:
+                break
+        threads = int(os.environ.get("OMP_NUM_THREADS", "0")) or (os.cpu_count() or 1)
+        cpu = {"value": round(tokens / (spent * w.L / done), 1), "unit": "prompt tokens/s", "cores": threads,
+               "kind": "oracle", "seconds": round(spent, 2),
+               "sample": f"{done} of {w.L} layers of the same workload (all heads, all prompts), scaled by L/{done}; "
+                         f"OpenMP over the {w.H} heads of a layer for scoring, the rest single-threaded"}
+
+    out = {"metric": "prompt tokens compressed/sec (all layers+heads)", "value": round(value, 1),
+           "unit": "prompt tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+           "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
+           "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+           "config": {"workload": f"{w.name}: {w.L} layers x {w.H} KV heads x {list(w.prompt_lens)} tokens x d={w.d}, "
+                                  f"{w.dtype} K/V, r={r}", "ratio": r, "kv_dtype": w.dtype,
+                      "scoring_kernels": "generic" if args.generic else "default",
+                      "inputs": nkv_inputs.recipe(w)},
+           "roofline": roofline, "cpu_baseline": cpu}
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -53,6 +53,15 @@ enum { NKV_DTYPE_F32 = 0, NKV_DTYPE_BF16 = 1 };
 enum { NKV_GATE_SURPRISE = 0, NKV_GATE_ONLY_AVERAGE = 1, NKV_GATE_ONLY_MAX = 2 };
 enum { NKV_SURPRISE_NORMALISED = 0, NKV_SURPRISE_RAW = 1 };
 enum { NKV_FLAG_GENERIC_KERNELS = 1u };   /* force the shape-generic scoring kernels */
+/* Kernels a caller can ask to have timed, see nkv_params.prof_start. */
+enum {
+    NKV_KERNEL_SCAN = 0,       /* key-streaming anomaly kernel of nkv_score / nkv_score_raw   */
+    NKV_KERNEL_FINALIZE = 1,   /* per-head statistics, blend, gate of nkv_score               */
+    NKV_KERNEL_BUDGET = 2,     /* nkv_budget                                                  */
+    NKV_KERNEL_SELECT = 3,     /* threshold search + ordered compaction of nkv_select_compact */
+    NKV_KERNEL_GATHER = 4,     /* K/V row copies of nkv_select_compact                        */
+    NKV_KERNEL_COUNT = 5
+};
 
 #define NKV_MAX_PROMPTS 64        /* prompts per call                                   */
 #define NKV_MAX_HEAD_DIM 1024     /* d and dv; both must be multiples of 8              */
@@ -84,6 +93,11 @@ typedef struct nkv_params {
     double   safeguard;       /* 0.20: each head first keeps floor(safeguard * k0) own tokens      */
     double   near_tol;        /* 1e-5: half-width of the band nkv_select_compact counts around a   */
                               /* head's selection threshold                                        */
+    /* Optional timing: if prof_start[k] and prof_stop[k] are both non-NULL hipEvent_t handles, the    */
+    /* call that launches kernel k (NKV_KERNEL_*) records them on its stream right before and right    */
+    /* after that launch.  The caller owns the events and reads them after synchronising.              */
+    void    *prof_start[NKV_KERNEL_COUNT];
+    void    *prof_stop[NKV_KERNEL_COUNT];
 } nkv_params;
 
 typedef struct nkv_shape {
@@ -165,6 +179,13 @@ int nkv_select_compact(const void *keys, const void *values, const float *scores
                        void *packed_k, void *packed_v, int32_t *kept_idx, int64_t *head_off,
                        int64_t row_capacity, int64_t *near_threshold_count,
                        void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
+ * Plain device-to-device copy of `bytes` bytes (a multiple of 16, both pointers 16-byte aligned) by a
+ * grid-stride kernel of 16-byte loads and stores.  Not part of the pass: it is the yardstick the
+ * benchmark measures attainable HBM bandwidth with and calibrates hardware byte counters against.
+ */
+int nkv_copy_probe(void *dst, const void *src, size_t bytes, void *hip_stream);
 
 /* Static, human-readable text for a status code. */
 const char *nkv_strerror(int status);

@@ -22,7 +22,8 @@ PIN = 3.0e38
 
 EXPORTS = ("nkv_params_default", "nkv_block_size", "nkv_k0", "nkv_m_safe", "nkv_m_p", "nkv_packed_rows",
            "nkv_workspace_bytes", "nkv_score", "nkv_score_raw", "nkv_budget", "nkv_select_compact",
-           "nkv_strerror", "nkv_version")
+           "nkv_copy_probe", "nkv_strerror", "nkv_version")
+KERNELS = ("scan", "finalize", "budget", "select", "gather")
 
 
 class nkv_params(C.Structure):
@@ -31,7 +32,7 @@ class nkv_params(C.Structure):
                 ("gate_mode", C.c_int32), ("surprise_mode", C.c_int32), ("flags", C.c_uint32),
                 ("reserved", C.c_int32), ("top_frac", C.c_double), ("prior", C.c_double * 3),
                 ("beta", C.c_double), ("tau", C.c_double), ("kappa", C.c_double), ("safeguard", C.c_double),
-                ("near_tol", C.c_double)]
+                ("near_tol", C.c_double), ("prof_start", C.c_void_p * 5), ("prof_stop", C.c_void_p * 5)]
 
 
 class nkv_shape(C.Structure):
@@ -74,6 +75,7 @@ def lib() -> C.CDLL:
                                  C.c_size_t, vp]
         L.nkv_select_compact.argtypes = [vp, vp, vp, vp, C.POINTER(nkv_shape), C.POINTER(nkv_params), vp, vp, vp,
                                          vp, i64, vp, vp, C.c_size_t, vp]
+        L.nkv_copy_probe.argtypes = [vp, vp, C.c_size_t, vp]
         L.nkv_strerror.argtypes = [C.c_int]
         L.nkv_strerror.restype = C.c_char_p
         L.nkv_version.restype = C.c_int
@@ -199,6 +201,72 @@ def select_compact(keys, values, scores, k_per_head, shape: Shape, params: nkv_p
                                   0 if ws is None else ws.numel() * ws.element_size(), _stream(stream))
     if rc:
         raise NkvError(rc, "nkv_select_compact")
+
+
+def copy_probe(dst, src, stream=None) -> None:
+    """Plain device copy src -> dst (same byte size), the bandwidth yardstick."""
+    rc = lib().nkv_copy_probe(_ptr(dst), _ptr(src), src.numel() * src.element_size(), _stream(stream))
+    if rc:
+        raise NkvError(rc, "nkv_copy_probe")
+
+
+_hip = None
+
+
+def _hiprt() -> C.CDLL:
+    global _hip
+    if _hip is None:
+        h = C.CDLL("libamdhip64.so")
+        h.hipEventCreate.argtypes = [C.POINTER(C.c_void_p)]
+        h.hipEventDestroy.argtypes = [C.c_void_p]
+        h.hipEventRecord.argtypes = [C.c_void_p, C.c_void_p]
+        h.hipEventSynchronize.argtypes = [C.c_void_p]
+        h.hipEventElapsedTime.argtypes = [C.POINTER(C.c_float), C.c_void_p, C.c_void_p]
+        _hip = h
+    return _hip
+
+
+class HipEvent:
+    """A raw hipEvent_t, recorded by the library (kernel timing) or by the caller on a given stream."""
+
+    def __init__(self):
+        self.handle = C.c_void_p()
+        rc = _hiprt().hipEventCreate(C.byref(self.handle))
+        if rc:
+            raise RuntimeError(f"hipEventCreate failed: {rc}")
+
+    def record(self, stream=None) -> None:
+        rc = _hiprt().hipEventRecord(self.handle, _stream(stream))
+        if rc:
+            raise RuntimeError(f"hipEventRecord failed: {rc}")
+
+    def synchronize(self) -> None:
+        _hiprt().hipEventSynchronize(self.handle)
+
+    def elapsed_ms(self, later: "HipEvent") -> float:
+        ms = C.c_float(0)
+        rc = _hiprt().hipEventElapsedTime(C.byref(ms), self.handle, later.handle)
+        if rc:
+            raise RuntimeError(f"hipEventElapsedTime failed: {rc}")
+        return float(ms.value)
+
+    def __del__(self):
+        try:
+            if self.handle:
+                _hiprt().hipEventDestroy(self.handle)
+        except Exception:
+            pass
+
+
+def with_kernel_timers(params: nkv_params, timers: dict) -> nkv_params:
+    """A copy of ``params`` that asks the library to record ``timers[name] = (start, stop)`` HipEvents around
+    the launch of the named kernel (names in KERNELS)."""
+    q = nkv_params.from_buffer_copy(params)
+    for name, (a, b) in timers.items():
+        k = KERNELS.index(name)
+        q.prof_start[k] = a.handle
+        q.prof_stop[k] = b.handle
+    return q
 
 
 @dataclass

@@ -93,12 +93,14 @@ int run_raw(const void *keys, const nkv_shape *s, const nkv_params *p, const Pro
             char *ws, const ScoreWs &lay, hipStream_t st)
 {
     const int LH = s->L * s->H;
+    const Prof prof{p->prof_start, p->prof_stop};
     hipError_t e;
     if (!(p->flags & NKV_FLAG_GENERIC_KERNELS) && fast_score_supported(s->dtype, s->d, p->window, tab))
-        e = launch_score_fast(keys, LH, s->d, tab, a_raw, (float *)(ws + lay.bsum), (float *)(ws + lay.ssum), st);
+        e = launch_score_fast(keys, LH, s->d, tab, a_raw, (float *)(ws + lay.bsum), (float *)(ws + lay.ssum),
+                              prof, st);
     else
         e = launch_score_generic(keys, s->dtype, LH, s->d, p->window, tab, a_raw, (float *)(ws + lay.rnorm),
-                                 (float *)(ws + lay.bsum), (float *)(ws + lay.ssum), st);
+                                 (float *)(ws + lay.bsum), (float *)(ws + lay.ssum), prof, st);
     return e == hipSuccess ? NKV_OK : NKV_EHIP;
 }
 
@@ -235,7 +237,8 @@ int nkv_score(const void *keys, const nkv_shape *shape, const nkv_params *params
     lc.n_sink = params->n_sink;
     lc.gate_mode = params->gate_mode;
     lc.surprise_mode = params->surprise_mode;
-    return launch_finalize(a_raw, shape->L, shape->H, tab, lc, scores, st) == hipSuccess ? NKV_OK : NKV_EHIP;
+    const Prof prof{params->prof_start, params->prof_stop};
+    return launch_finalize(a_raw, shape->L, shape->H, tab, lc, scores, prof, st) == hipSuccess ? NKV_OK : NKV_EHIP;
 }
 
 int nkv_budget(const float *scores, const nkv_shape *shape, const nkv_params *params, const double *r_per_prompt,
@@ -256,7 +259,8 @@ int nkv_budget(const float *scores, const nkv_shape *shape, const nkv_params *pa
         tab.k0[p] = (int32_t)k0;
         tab.m_safe[p] = (int32_t)nkv_m_safe(k0, params->safeguard);
     }
-    return launch_budget(scores, shape->L, shape->H, tab, k_per_head, (hipStream_t)hip_stream) == hipSuccess
+    const Prof prof{params->prof_start, params->prof_stop};
+    return launch_budget(scores, shape->L, shape->H, tab, k_per_head, prof, (hipStream_t)hip_stream) == hipSuccess
                ? NKV_OK : NKV_EHIP;
 }
 
@@ -279,8 +283,14 @@ int nkv_select_compact(const void *keys, const void *values, const float *scores
     return launch_select_compact(keys, values, scores, k_per_head, shape->L, shape->H, shape->d, shape->dv,
                                  esize_of(shape->dtype), tab, (float)params->near_tol, packed_k, packed_v,
                                  kept_idx, head_off, row_capacity, near_threshold_count,
-                                 (hipStream_t)hip_stream) == hipSuccess
+                                 Prof{params->prof_start, params->prof_stop}, (hipStream_t)hip_stream) == hipSuccess
                ? NKV_OK : NKV_EHIP;
+}
+
+int nkv_copy_probe(void *dst, const void *src, size_t bytes, void *hip_stream)
+{
+    if (!dst || !src || bytes % 16 || (uintptr_t)dst % 16 || (uintptr_t)src % 16) return NKV_EINVAL;
+    return launch_copy_probe(dst, src, bytes, (hipStream_t)hip_stream) == hipSuccess ? NKV_OK : NKV_EHIP;
 }
 
 const char *nkv_strerror(int status)

@@ -134,9 +134,11 @@ __global__ __launch_bounds__(kThreads) void budget_kernel(const float *__restric
 }  // namespace
 
 hipError_t launch_budget(const float *scores, int L, int H, const PromptTab &tab, int32_t *k_per_head,
-                         hipStream_t st)
+                         const Prof &prof, hipStream_t st)
 {
+    prof.begin(NKV_KERNEL_BUDGET, st);
     budget_kernel<<<(unsigned)(tab.n * L), kThreads, 0, st>>>(scores, L, H, tab, k_per_head);
+    prof.end(NKV_KERNEL_BUDGET, st);
     return hipGetLastError();
 }
 

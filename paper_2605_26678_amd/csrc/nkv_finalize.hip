@@ -189,9 +189,11 @@ __global__ __launch_bounds__(kThreads) void finalize_kernel(const float *__restr
 }  // namespace
 
 hipError_t launch_finalize(const float *a_raw, int L, int H, const PromptTab &tab, const LearnerConsts &lc,
-                           float *scores, hipStream_t st)
+                           float *scores, const Prof &prof, hipStream_t st)
 {
+    prof.begin(NKV_KERNEL_FINALIZE, st);
     finalize_kernel<<<(unsigned)(tab.n * L * H), kThreads, 0, st>>>(a_raw, L, H, tab, lc, scores);
+    prof.end(NKV_KERNEL_FINALIZE, st);
     return hipGetLastError();
 }
 

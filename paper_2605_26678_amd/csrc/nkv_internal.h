@@ -28,32 +28,50 @@ struct LearnerConsts {
     int32_t n_sink, gate_mode, surprise_mode;
 };
 
+// Optional event pair around one kernel launch (nkv_params.prof_start / prof_stop).
+struct Prof {
+    void *const *start = nullptr;
+    void *const *stop = nullptr;
+    void begin(int k, hipStream_t st) const
+    {
+        if (start && start[k] && stop[k]) (void)hipEventRecord((hipEvent_t)start[k], st);
+    }
+    void end(int k, hipStream_t st) const
+    {
+        if (start && start[k] && stop[k]) (void)hipEventRecord((hipEvent_t)stop[k], st);
+    }
+};
+
 constexpr float kEps = 1e-12f;    // clamp of vector norms
 constexpr float kFlat = 1e-6f;    // a min-max range below this carries no ranking
 
 // ---- scoring, shape-generic kernels (any d multiple of 8, any window / block size, fp32 or bf16) ----
 hipError_t launch_score_generic(const void *keys, int dtype, int LH, int d, int window, const PromptTab &tab,
-                                float *a_raw, float *rnorm, float *bsum, float *ssum, hipStream_t st);
+                                float *a_raw, float *rnorm, float *bsum, float *ssum, const Prof &prof,
+                                hipStream_t st);
 
 // ---- scoring, streaming kernels for bf16 keys, d in {64,128}, window 64, block size <= 256 ----
 bool fast_score_supported(int dtype, int d, int window, const PromptTab &tab);
 size_t fast_score_ws_floats(int LH, int d, const PromptTab &tab);
 hipError_t launch_score_fast(const void *keys, int LH, int d, const PromptTab &tab, float *a_raw,
-                             float *bsum, float *ssum, hipStream_t st);
+                             float *bsum, float *ssum, const Prof &prof, hipStream_t st);
 
 // ---- per-head statistics, blend weights, gate and final scores ----
 hipError_t launch_finalize(const float *a_raw, int L, int H, const PromptTab &tab, const LearnerConsts &lc,
-                           float *scores, hipStream_t st);
+                           float *scores, const Prof &prof, hipStream_t st);
 
 // ---- head-wise budgets ----
 hipError_t launch_budget(const float *scores, int L, int H, const PromptTab &tab, int32_t *k_per_head,
-                         hipStream_t st);
+                         const Prof &prof, hipStream_t st);
 
 // ---- selection, ordered compaction, gather ----
 hipError_t launch_select_compact(const void *keys, const void *values, const float *scores,
                                  const int32_t *k_per_head, int L, int H, int d, int dv, int esize,
                                  const PromptTab &tab, float near_tol, void *packed_k, void *packed_v,
                                  int32_t *kept_idx, int64_t *head_off, int64_t row_capacity,
-                                 int64_t *near_count, hipStream_t st);
+                                 int64_t *near_count, const Prof &prof, hipStream_t st);
+
+// ---- plain copy, the bandwidth yardstick ----
+hipError_t launch_copy_probe(void *dst, const void *src, size_t bytes, hipStream_t st);
 
 }  // namespace nkv

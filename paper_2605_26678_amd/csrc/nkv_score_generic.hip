@@ -126,7 +126,7 @@ __global__ __launch_bounds__(256) void anomaly_kernel(const T *__restrict__ keys
 
 template <typename T>
 hipError_t run(const T *keys, int LH, int d, int window, const PromptTab &tab, float *a_raw, float *rnorm,
-               float *bsum, float *ssum, hipStream_t st)
+               float *bsum, float *ssum, const Prof &prof, hipStream_t st)
 {
     const int64_t rows = (int64_t)LH * tab.T;
     const unsigned row_grid = (unsigned)((rows + 3) / 4);
@@ -134,6 +134,7 @@ hipError_t run(const T *keys, int LH, int d, int window, const PromptTab &tab, f
     bsum_kernel<T><<<dim3(tab.blk_off[tab.n], LH), 256, 0, st>>>(keys, rnorm, d, tab, bsum);
     ssum_kernel<<<dim3(tab.n, LH), 256, 0, st>>>(bsum, d, tab, ssum);
     const int nq = (d + kWave - 1) / kWave;
+    prof.begin(NKV_KERNEL_SCAN, st);
 #define NKV_ANOM(NQ) anomaly_kernel<T, NQ><<<row_grid, 256, 0, st>>>(keys, rnorm, bsum, ssum, LH, d, window, tab, a_raw)
     if (nq <= 1) NKV_ANOM(1);
     else if (nq <= 2) NKV_ANOM(2);
@@ -141,17 +142,19 @@ hipError_t run(const T *keys, int LH, int d, int window, const PromptTab &tab, f
     else if (nq <= 8) NKV_ANOM(8);
     else NKV_ANOM(16);
 #undef NKV_ANOM
+    prof.end(NKV_KERNEL_SCAN, st);
     return hipGetLastError();
 }
 
 }  // namespace
 
 hipError_t launch_score_generic(const void *keys, int dtype, int LH, int d, int window, const PromptTab &tab,
-                                float *a_raw, float *rnorm, float *bsum, float *ssum, hipStream_t st)
+                                float *a_raw, float *rnorm, float *bsum, float *ssum, const Prof &prof,
+                                hipStream_t st)
 {
     if (dtype == NKV_DTYPE_F32)
-        return run<float>((const float *)keys, LH, d, window, tab, a_raw, rnorm, bsum, ssum, st);
-    return run<uint16_t>((const uint16_t *)keys, LH, d, window, tab, a_raw, rnorm, bsum, ssum, st);
+        return run<float>((const float *)keys, LH, d, window, tab, a_raw, rnorm, bsum, ssum, prof, st);
+    return run<uint16_t>((const uint16_t *)keys, LH, d, window, tab, a_raw, rnorm, bsum, ssum, prof, st);
 }
 
 }  // namespace nkv

@@ -182,25 +182,45 @@ __global__ __launch_bounds__(256) void gather_kernel(const uint4 *__restrict__ k
     }
 }
 
+__global__ __launch_bounds__(256) void copy_kernel(uint4 *__restrict__ dst, const uint4 *__restrict__ src, size_t n)
+{
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) dst[i] = src[i];
+}
+
 }  // namespace
+
+hipError_t launch_copy_probe(void *dst, const void *src, size_t bytes, hipStream_t st)
+{
+    const size_t n = bytes / 16;
+    if (n == 0) return hipSuccess;
+    const size_t want = (n + 255) / 256;
+    const unsigned groups = (unsigned)(want < 256 * 32 ? want : 256 * 32);     // 32 workgroups per CU
+    copy_kernel<<<groups, 256, 0, st>>>((uint4 *)dst, (const uint4 *)src, n);
+    return hipGetLastError();
+}
 
 hipError_t launch_select_compact(const void *keys, const void *values, const float *scores,
                                  const int32_t *k_per_head, int L, int H, int d, int dv, int esize,
                                  const PromptTab &tab, float near_tol, void *packed_k, void *packed_v,
                                  int32_t *kept_idx, int64_t *head_off, int64_t row_capacity,
-                                 int64_t *near_count, hipStream_t st)
+                                 int64_t *near_count, const Prof &prof, hipStream_t st)
 {
     const int n_units = tab.n * L * H;
     head_off_kernel<<<1, kThreads, 0, st>>>(k_per_head, L, H, tab, head_off, near_count);
+    prof.begin(NKV_KERNEL_SELECT, st);
     select_kernel<<<(unsigned)n_units, kThreads, 0, st>>>(scores, k_per_head, L, H, tab, near_tol, head_off,
                                                           row_capacity, kept_idx, near_count);
+    prof.end(NKV_KERNEL_SELECT, st);
     // no unit keeps more than its prompt length, so the row count is bounded by L*H*T as well
     const int64_t max_rows = row_capacity < (int64_t)L * H * tab.T ? row_capacity : (int64_t)L * H * tab.T;
     if (max_rows > 0) {
         const unsigned groups = (unsigned)((max_rows + kRowsPerGroup - 1) / kRowsPerGroup);
+        prof.begin(NKV_KERNEL_GATHER, st);
         gather_kernel<<<groups, 256, 0, st>>>((const uint4 *)keys, (const uint4 *)values, L, H, d * esize / 16,
                                               dv * esize / 16, tab, head_off, kept_idx, row_capacity,
                                               (uint4 *)packed_k, (uint4 *)packed_v);
+        prof.end(NKV_KERNEL_GATHER, st);
     }
     return hipGetLastError();
 }
