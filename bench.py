@@ -55,6 +55,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-layers", type=int, default=0, help="layers the oracle is timed on (0 = choose)")
     ap.add_argument("--generic", action="store_true", help="force the shape-generic scoring kernels")
+    ap.add_argument("--two-pass", action="store_true", help="stable anomaly in a second pass over the keys")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no sharding, no collectives); use --gpus 1", file=sys.stderr)
@@ -71,7 +72,8 @@ def main():
     torch.cuda.set_device(dev)
     K, V = nkv_inputs.make_kv(w, dev)
     shape = nkv.Shape(w.L, w.H, w.d, w.d_v, nkv.DTYPE_F32 if w.dtype == "fp32" else nkv.DTYPE_BF16, w.cu_seqlens)
-    params = nkv.params_default(flags=nkv.FLAG_GENERIC_KERNELS if args.generic else 0)
+    params = nkv.params_default(flags=(nkv.FLAG_GENERIC_KERNELS if args.generic else 0)
+                                | (nkv.FLAG_TWO_PASS_STABLE if args.two_pass else 0))
     r_list = [r] * shape.n_prompts
     comp = nkv.Compressor(shape, r_list, params)
     stream = torch.cuda.current_stream()

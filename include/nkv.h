@@ -52,7 +52,11 @@ typedef enum nkv_status {
 enum { NKV_DTYPE_F32 = 0, NKV_DTYPE_BF16 = 1 };
 enum { NKV_GATE_SURPRISE = 0, NKV_GATE_ONLY_AVERAGE = 1, NKV_GATE_ONLY_MAX = 2 };
 enum { NKV_SURPRISE_NORMALISED = 0, NKV_SURPRISE_RAW = 1 };
-enum { NKV_FLAG_GENERIC_KERNELS = 1u };   /* force the shape-generic scoring kernels */
+enum {
+    NKV_FLAG_GENERIC_KERNELS = 1u,    /* force the shape-generic scoring kernels                            */
+    NKV_FLAG_TWO_PASS_STABLE = 2u     /* streaming kernels: compute the stable anomaly in a second pass     */
+                                      /* over the keys instead of inside the single fused pass             */
+};
 /* Kernels a caller can ask to have timed, see nkv_params.prof_start. */
 enum {
     NKV_KERNEL_SCAN = 0,       /* key-streaming anomaly kernel of nkv_score / nkv_score_raw   */

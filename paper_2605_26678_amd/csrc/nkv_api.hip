@@ -65,7 +65,7 @@ void fill_tab(const nkv_shape *s, const nkv_params *p, PromptTab *tab)
 
 // Workspace of the scoring call, in floats from the (aligned) start.
 struct ScoreWs {
-    size_t a_raw, rnorm, bsum, ssum, total_bytes;
+    size_t sync, a_raw, rnorm, bsum, ssum, total_bytes;
 };
 
 ScoreWs score_ws(const nkv_shape *s, const PromptTab &tab, bool with_a_raw)
@@ -74,6 +74,7 @@ ScoreWs score_ws(const nkv_shape *s, const PromptTab &tab, bool with_a_raw)
     const size_t LH = (size_t)s->L * s->H;
     ScoreWs w;
     size_t off = 0;
+    w.sync = off;   off += align_up(fast_score_sync_bytes((int)LH, tab));   // first: word 1 counts timed-out waits
     w.a_raw = off;  off += with_a_raw ? align_up(3 * rows * 4) : 0;
     w.rnorm = off;  off += align_up(rows * 4);
     w.bsum = off;   off += align_up(LH * tab.blk_off[tab.n] * s->d * 4);
@@ -97,7 +98,7 @@ int run_raw(const void *keys, const nkv_shape *s, const nkv_params *p, const Pro
     hipError_t e;
     if (!(p->flags & NKV_FLAG_GENERIC_KERNELS) && fast_score_supported(s->dtype, s->d, p->window, tab))
         e = launch_score_fast(keys, LH, s->d, tab, a_raw, (float *)(ws + lay.bsum), (float *)(ws + lay.ssum),
-                              prof, st);
+                              ws + lay.sync, !(p->flags & NKV_FLAG_TWO_PASS_STABLE), prof, st);
     else
         e = launch_score_generic(keys, s->dtype, LH, s->d, p->window, tab, a_raw, (float *)(ws + lay.rnorm),
                                  (float *)(ws + lay.bsum), (float *)(ws + lay.ssum), prof, st);

@@ -179,6 +179,7 @@ def test_generic_and_streaming_kernels_agree_with_oracle():
     w = nkv_inputs.small_workload("generic", 2, 2, 128, [2000, 321])
     K, V = _kv(w)
     compare_end_to_end(w, K, V, 0.5, params=nkv.params_default(flags=nkv.FLAG_GENERIC_KERNELS), label="generic")
+    compare_end_to_end(w, K, V, 0.5, params=nkv.params_default(flags=nkv.FLAG_TWO_PASS_STABLE), label="two-pass")
     compare_end_to_end(w, K, V, 0.5, label="default")
 
 
