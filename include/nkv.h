@@ -157,7 +157,8 @@ int nkv_score_raw(const void *keys, const nkv_shape *shape, const nkv_params *pa
  * its own nkv_m_safe(k0) best tokens, the other H*(k0 - m_safe) slots of a layer
  * go to the best remaining (head, token) pairs; k_per_head[u] = B_h, and the B_h
  * of a layer add up to H*k0.  Order: higher score, then lower head, then lower
- * token index.  Exact integer work on the fp32 scores given.
+ * token index.  Exact integer work on the fp32 scores given.  `ws` may be NULL
+ * (ws_bytes 0): a slower kernel that needs no scratch is used then.
  */
 int nkv_budget(const float *scores, const nkv_shape *shape, const nkv_params *params,
                const double *r_per_prompt, int32_t *k_per_head, void *ws, size_t ws_bytes,

@@ -304,7 +304,7 @@ class Compressor:
 
     def run(self, keys, values, stream=None) -> Compressed:
         score(keys, self.shape, self.params, self.scores, self.ws, stream)
-        budget(self.scores, self.shape, self.params, self.r, self.k_per_head, None, stream)
+        budget(self.scores, self.shape, self.params, self.r, self.k_per_head, self.ws, stream)
         select_compact(keys, values, self.scores, self.k_per_head, self.shape, self.params, self.packed_k,
                        self.packed_v, self.kept_idx, self.head_off, self.rows, self.near, None, stream)
         return Compressed(self.scores, self.k_per_head, self.head_off, self.kept_idx[:self.rows],

@@ -65,7 +65,7 @@ void fill_tab(const nkv_shape *s, const nkv_params *p, PromptTab *tab)
 
 // Workspace of the scoring call, in floats from the (aligned) start.
 struct ScoreWs {
-    size_t sync, a_raw, rnorm, bsum, ssum, total_bytes;
+    size_t sync, a_raw, rnorm, bsum, ssum, stats, total_bytes;
 };
 
 ScoreWs score_ws(const nkv_shape *s, const PromptTab &tab, bool with_a_raw)
@@ -79,6 +79,7 @@ ScoreWs score_ws(const nkv_shape *s, const PromptTab &tab, bool with_a_raw)
     w.rnorm = off;  off += align_up(rows * 4);
     w.bsum = off;   off += align_up(LH * tab.blk_off[tab.n] * s->d * 4);
     w.ssum = off;   off += align_up(LH * tab.n * s->d * 4);
+    w.stats = off;  off += align_up(LH * tab.n * 3 * 4 * 4);                 // per unit and scale: min, 1/range, gap
     w.total_bytes = off;
     return w;
 }
@@ -189,7 +190,8 @@ int nkv_workspace_bytes(const nkv_shape *shape, const nkv_params *params, size_t
     if (rc) return rc;
     PromptTab tab;
     fill_tab(shape, params, &tab);
-    *bytes = score_ws(shape, tab, true).total_bytes;     // budget and select need none
+    const size_t a = score_ws(shape, tab, true).total_bytes, b = align_up(budget_ws_bytes(shape->L, shape->H, tab));
+    *bytes = a > b ? a : b;                              // selection needs none
     return NKV_OK;
 }
 
@@ -239,13 +241,12 @@ int nkv_score(const void *keys, const nkv_shape *shape, const nkv_params *params
     lc.gate_mode = params->gate_mode;
     lc.surprise_mode = params->surprise_mode;
     const Prof prof{params->prof_start, params->prof_stop};
-    return launch_finalize(a_raw, shape->L, shape->H, tab, lc, scores, prof, st) == hipSuccess ? NKV_OK : NKV_EHIP;
+    return launch_finalize(a_raw, shape->L, shape->H, tab, lc, scores, (float *)((char *)ws + lay.stats), prof, st) == hipSuccess ? NKV_OK : NKV_EHIP;
 }
 
 int nkv_budget(const float *scores, const nkv_shape *shape, const nkv_params *params, const double *r_per_prompt,
                int32_t *k_per_head, void *ws, size_t ws_bytes, void *hip_stream)
 {
-    (void)ws; (void)ws_bytes;
     if (!scores || !r_per_prompt || !k_per_head) return NKV_EINVAL;
     int rc = check_shape(shape);
     if (rc) return rc;
@@ -260,8 +261,12 @@ int nkv_budget(const float *scores, const nkv_shape *shape, const nkv_params *pa
         tab.k0[p] = (int32_t)k0;
         tab.m_safe[p] = (int32_t)nkv_m_safe(k0, params->safeguard);
     }
+    if (ws != nullptr) {
+        rc = check_ws(ws, ws_bytes, budget_ws_bytes(shape->L, shape->H, tab));
+        if (rc) return rc;
+    }
     const Prof prof{params->prof_start, params->prof_stop};
-    return launch_budget(scores, shape->L, shape->H, tab, k_per_head, prof, (hipStream_t)hip_stream) == hipSuccess
+    return launch_budget(scores, shape->L, shape->H, tab, k_per_head, ws, prof, (hipStream_t)hip_stream) == hipSuccess
                ? NKV_OK : NKV_EHIP;
 }
 

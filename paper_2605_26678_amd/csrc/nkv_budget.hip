@@ -9,20 +9,215 @@
 //   B. over the pool {x < T_h} + {T_h repeated e_h times}, the key TL of the R-th best entry and how many
 //      entries tied at TL are admitted (in head-then-index order, so heads are served in ascending order);
 //   C. B_h = m_safe + #{pool entries of head h above TL} + its share of the ties at TL.
-// Selects are byte-wise radix selects, most significant digit first, on an order-preserving integer image
-// of the fp32 scores: exact integer work.  One workgroup of 1024 threads per (prompt, layer); the layer's
-// H*N scores (1 MiB at H = 8, N = 32768) are read from L2 nine times.
-#include "nkv_device.h"
+// All selects are radix selects on an order-preserving integer image of the fp32 scores: exact integer work.
+//
+// Two implementations:
+//   * prompts of up to 32768 tokens and layers of up to 8 heads: head_safe_kernel (one workgroup per
+//     (prompt, layer, head), scores in registers, step A plus a 2048-bin histogram of the head's pool on
+//     the top 11 key bits) and layer_budget_kernel (one workgroup per (prompt, layer): the top digit from
+//     the heads' histograms, then two passes over the layer's scores for the 11 middle and 10 low bits,
+//     the last one with one histogram per head, which also yields step C);
+//   * anything else: budget_kernel, one workgroup per (prompt, layer), nine byte-wise passes.
+#include "nkv_blocksel.h"
 
 namespace nkv {
 namespace {
 
 constexpr int kThreads = 1024;
+constexpr int kFastHeads = 8;
 
+struct HeadSafe {                // result of step A for one head
+    uint32_t T, rem, ties, pad;
+};
+
+// ---------------------------------------------------------------------------------------------------
+template <int EPT>
+__global__ __launch_bounds__(kSelThreads) void head_safe_kernel(const float *__restrict__ scores, int L, int H,
+                                                                 PromptTab tab, HeadSafe *__restrict__ safe,
+                                                                 uint32_t *__restrict__ pool_hist)
+{
+    __shared__ SelectScratch sel;
+    __shared__ uint32_t hist0[2048];
+    const int u = blockIdx.x;
+    const int h = u % H, l = (u / H) % L, p = u / (H * L);
+    const int N = tab.tok_off[p + 1] - tab.tok_off[p];
+    const float *sc = scores + ((int64_t)l * H + h) * tab.T + tab.tok_off[p];
+    const int tid = threadIdx.x;
+    const int m_safe = tab.m_safe[p];
+
+    uint32_t key[EPT];
+#pragma unroll
+    for (int j = 0; j < EPT; ++j) {
+        const int i = tid + j * kSelThreads;
+        key[j] = i < N ? ord_key(sc[i]) : 0u;
+    }
+    uint32_t T = 0xFFFFFFFFu, rem = 0u, ties = 0u;
+    if (m_safe > 0) T = block_select<EPT, true>(key, N, (uint32_t)m_safe, sel, rem, ties);
+    for (int j = tid; j < 2048; j += kSelThreads) hist0[j] = 0u;
+    __syncthreads();
+    {
+        uint32_t cur = 0u, cnt = 0u;                         // run-length compressed LDS atomics
+#pragma unroll
+        for (int j = 0; j < EPT; ++j) {
+            if (tid + j * kSelThreads < N && key[j] < T) {
+                const uint32_t d = key[j] >> 21;
+                if (cnt != 0u && d != cur) { atomicAdd(&hist0[cur], cnt); cnt = 0u; }
+                cur = d;
+                ++cnt;
+            }
+        }
+        if (cnt != 0u) atomicAdd(&hist0[cur], cnt);
+        if (tid == 0 && ties > rem) atomicAdd(&hist0[T >> 21], ties - rem);   // unprotected ties at T
+    }
+    __syncthreads();
+    for (int j = tid; j < 2048; j += kSelThreads) pool_hist[(int64_t)u * 2048 + j] = hist0[j];
+    if (tid == 0) safe[u] = HeadSafe{T, rem, ties, 0u};
+}
+
+// Finds the bin holding rank `want` from the top of an NB-bin histogram (NB = 1024 or 2048); 1024 threads.
+// out[0] = bin, out[1] = rank inside the bin.  Contains barriers.
+template <int NB>
+__device__ __forceinline__ void block_pick_top(const uint32_t *hist, uint32_t want, uint32_t *wsum, uint32_t *out)
+{
+    constexpr int PER = NB / kThreads;
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    uint32_t c[PER], group = 0u;
+#pragma unroll
+    for (int q = 0; q < PER; ++q) { c[q] = hist[tid * PER + q]; group += c[q]; }
+    uint32_t incl = group;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const uint32_t t = __shfl_down(incl, o, 64);
+        if (lane + o < 64) incl += t;
+    }
+    if (lane == 0) wsum[w] = incl;
+    __syncthreads();
+    for (int ww = w + 1; ww < kThreads / 64; ++ww) incl += wsum[ww];
+    uint32_t cum = incl - group;
+    if (cum < want && want <= incl) {
+#pragma unroll
+        for (int q = PER - 1; q >= 0; --q) {
+            if (cum < want && want <= cum + c[q]) { out[0] = (uint32_t)(tid * PER + q); out[1] = want - cum; }
+            cum += c[q];
+        }
+    }
+    __syncthreads();
+}
+
+__global__ __launch_bounds__(kThreads) void layer_budget_kernel(const float *__restrict__ scores, int L, int H,
+                                                                PromptTab tab, const HeadSafe *__restrict__ safe,
+                                                                const uint32_t *__restrict__ pool_hist,
+                                                                int32_t *__restrict__ k_per_head)
+{
+    __shared__ uint32_t hist[2048];
+    __shared__ uint32_t hist2[kFastHeads][1024];
+    __shared__ uint32_t cnt_gt[kFastHeads];
+    __shared__ uint32_t Th[kFastHeads], extra[kFastHeads];
+    __shared__ uint32_t wsum[16], pick[2];
+
+    const int pl = blockIdx.x, l = pl % L, p = pl / L;
+    const int N = tab.tok_off[p + 1] - tab.tok_off[p];
+    const int k0 = tab.k0[p], m_safe = tab.m_safe[p];
+    const int tid = threadIdx.x;
+    const uint32_t R = (uint32_t)H * (uint32_t)(k0 - m_safe);
+    int32_t *out = k_per_head + (int64_t)pl * H;
+    if (R == 0u) {
+        if (tid < H) out[tid] = m_safe;
+        return;
+    }
+    const HeadSafe *hsafe = safe + (int64_t)pl * H;
+    const float *sc = scores + (int64_t)l * H * tab.T + tab.tok_off[p];          // head h at sc + h*T
+    if (tid < H) {
+        Th[tid] = hsafe[tid].T;
+        extra[tid] = hsafe[tid].ties - hsafe[tid].rem;
+        cnt_gt[tid] = 0u;
+    }
+    // top 11 bits: add up the heads' pool histograms
+    for (int j = tid; j < 2048; j += kThreads) {
+        uint32_t s = 0u;
+        for (int h = 0; h < H; ++h) s += pool_hist[((int64_t)pl * H + h) * 2048 + j];
+        hist[j] = s;
+    }
+    __syncthreads();
+    block_pick_top<2048>(hist, R, wsum, pick);
+    const uint32_t d0 = pick[0];
+    uint32_t want = pick[1];
+    __syncthreads();
+
+    // middle 11 bits among pool entries whose top digit is d0
+    for (int j = tid; j < 2048; j += kThreads) hist[j] = 0u;
+    __syncthreads();
+    for (int h = 0; h < H; ++h) {
+        const float *s = sc + (int64_t)h * tab.T;
+        const uint32_t th = Th[h];
+        for (int i = tid; i < N; i += kThreads) {
+            const uint32_t key = ord_key(s[i]);
+            if (key < th && (key >> 21) == d0) atomicAdd(&hist[(key >> 10) & 2047u], 1u);
+        }
+        if (tid == 0 && extra[h] > 0u && (th >> 21) == d0) atomicAdd(&hist[(th >> 10) & 2047u], extra[h]);
+    }
+    __syncthreads();
+    block_pick_top<2048>(hist, want, wsum, pick);
+    const uint32_t pre22 = (d0 << 11) | pick[0];
+    want = pick[1];
+    __syncthreads();
+
+    // low 10 bits, one histogram per head; entries above the 22-bit prefix are counted per head
+    for (int j = tid; j < H * 1024; j += kThreads) (&hist2[0][0])[j] = 0u;
+    __syncthreads();
+    for (int h = 0; h < H; ++h) {
+        const float *s = sc + (int64_t)h * tab.T;
+        const uint32_t th = Th[h];
+        uint32_t gt = 0u;
+        for (int i = tid; i < N; i += kThreads) {
+            const uint32_t key = ord_key(s[i]);
+            if (key < th) {
+                const uint32_t hi = key >> 10;
+                if (hi > pre22) ++gt;
+                else if (hi == pre22) atomicAdd(&hist2[h][key & 1023u], 1u);
+            }
+        }
+        gt = wave_sum(gt);
+        if ((tid & 63) == 0 && gt != 0u) atomicAdd(&cnt_gt[h], gt);
+        if (tid == 0 && extra[h] > 0u) {
+            if ((th >> 10) > pre22) atomicAdd(&cnt_gt[h], extra[h]);
+            else if ((th >> 10) == pre22) atomicAdd(&hist2[h][th & 1023u], extra[h]);
+        }
+    }
+    __syncthreads();
+    hist[tid] = 0u;                                           // kThreads == 1024 bins
+    {
+        uint32_t s = 0u;
+        for (int h = 0; h < H; ++h) s += hist2[h][tid];
+        hist[tid] = s;
+    }
+    __syncthreads();
+    block_pick_top<1024>(hist, want, wsum, pick);
+    const uint32_t d2 = pick[0];
+    // entries of each head above the layer threshold inside the last digit's range
+    for (int h = 0; h < H; ++h) {
+        uint32_t above = tid > (int)d2 ? hist2[h][tid] : 0u;
+        above = wave_sum(above);
+        if ((tid & 63) == 0 && above != 0u) atomicAdd(&cnt_gt[h], above);
+    }
+    __syncthreads();
+    if (tid == 0) {
+        uint32_t remaining = pick[1];                         // ties at the layer threshold still to admit
+        for (int h = 0; h < H; ++h) {
+            const uint32_t eq = hist2[h][d2];
+            const uint32_t take = min(remaining, eq);
+            remaining -= take;
+            out[h] = (int32_t)((uint32_t)m_safe + cnt_gt[h] + take);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------------
+// Shape-generic version: any prompt length, up to NKV_MAX_HEADS heads.
 __global__ __launch_bounds__(kThreads) void budget_kernel(const float *__restrict__ scores, int L, int H,
                                                           PromptTab tab, int32_t *__restrict__ k_per_head)
 {
-    __shared__ uint32_t hist[NKV_MAX_HEADS][256];      // 64 KB
+    __shared__ uint32_t hist[NKV_MAX_HEADS][256];      // 32 KB
     __shared__ uint32_t Th[NKV_MAX_HEADS];             // key of the m_safe-th best score of the head
     __shared__ uint32_t want_h[NKV_MAX_HEADS];         // running rank, ends as #protected among ties at Th
     __shared__ uint32_t ties_h[NKV_MAX_HEADS];         // #scores of the head equal to Th
@@ -37,7 +232,6 @@ __global__ __launch_bounds__(kThreads) void budget_kernel(const float *__restric
     const int64_t R = (int64_t)H * (k0 - m_safe);
     const float *sc = scores + (int64_t)l * H * tab.T + tab.tok_off[p];   // head h at sc + h*T
     const int tid = threadIdx.x;
-    const int64_t total = (int64_t)H * N;
 
     // ---- A: per-head safeguard thresholds ----
     if (tid < H) { Th[tid] = 0xFFFFFFFFu; want_h[tid] = (uint32_t)m_safe; ties_h[tid] = 0u; }
@@ -48,11 +242,13 @@ __global__ __launch_bounds__(kThreads) void budget_kernel(const float *__restric
             const int shift = 24 - 8 * pass;
             for (int j = tid; j < H * 256; j += kThreads) (&hist[0][0])[j] = 0u;
             __syncthreads();
-            for (int64_t e = tid; e < total; e += kThreads) {
-                const int h = (int)(e / N), i = (int)(e - (int64_t)h * N);
-                const uint32_t key = ord_key(sc[(int64_t)h * tab.T + i]);
-                if (pass == 0 || (key >> (shift + 8)) == (Th[h] >> (shift + 8)))
-                    atomicAdd(&hist[h][(key >> shift) & 255u], 1u);
+            for (int h = 0; h < H; ++h) {
+                const uint32_t th = Th[h];
+                for (int i = tid; i < N; i += kThreads) {
+                    const uint32_t key = ord_key(sc[(int64_t)h * tab.T + i]);
+                    if (pass == 0 || (key >> (shift + 8)) == (th >> (shift + 8)))
+                        atomicAdd(&hist[h][(key >> shift) & 255u], 1u);
+                }
             }
             __syncthreads();
             if (tid < H) {
@@ -75,17 +271,19 @@ __global__ __launch_bounds__(kThreads) void budget_kernel(const float *__restric
             if (tid < 256) lhist[tid] = 0u;
             __syncthreads();
             const uint32_t pre = TL;
-            for (int64_t e = tid; e < total; e += kThreads) {
-                const int h = (int)(e / N), i = (int)(e - (int64_t)h * N);
-                const uint32_t key = ord_key(sc[(int64_t)h * tab.T + i]);
-                if (key < Th[h] && (pass == 0 || (key >> (shift + 8)) == (pre >> (shift + 8))))
-                    atomicAdd(&lhist[(key >> shift) & 255u], 1u);
+            for (int h = 0; h < H; ++h) {
+                const uint32_t th = Th[h];
+                for (int i = tid; i < N; i += kThreads) {
+                    const uint32_t key = ord_key(sc[(int64_t)h * tab.T + i]);
+                    if (key < th && (pass == 0 || (key >> (shift + 8)) == (pre >> (shift + 8))))
+                        atomicAdd(&lhist[(key >> shift) & 255u], 1u);
+                }
             }
             if (tid < H) {                               // unprotected ties at the head's own threshold
-                const uint32_t extra = ties_h[tid] - (m_safe > 0 ? want_h[tid] : 0u);
+                const uint32_t ex = ties_h[tid] - (m_safe > 0 ? want_h[tid] : 0u);
                 const uint32_t key = Th[tid];
-                if (m_safe > 0 && extra > 0u && (pass == 0 || (key >> (shift + 8)) == (pre >> (shift + 8))))
-                    atomicAdd(&lhist[(key >> shift) & 255u], extra);
+                if (m_safe > 0 && ex > 0u && (pass == 0 || (key >> (shift + 8)) == (pre >> (shift + 8))))
+                    atomicAdd(&lhist[(key >> shift) & 255u], ex);
             }
             __syncthreads();
             if (tid == 0) {
@@ -103,12 +301,14 @@ __global__ __launch_bounds__(kThreads) void budget_kernel(const float *__restric
     __syncthreads();
     if (R > 0) {
         const uint32_t tl = TL;
-        for (int64_t e = tid; e < total; e += kThreads) {
-            const int h = (int)(e / N), i = (int)(e - (int64_t)h * N);
-            const uint32_t key = ord_key(sc[(int64_t)h * tab.T + i]);
-            if (key < Th[h]) {
-                if (key > tl) atomicAdd(&cnt_gt[h], 1u);
-                else if (key == tl) atomicAdd(&cnt_eq[h], 1u);
+        for (int h = 0; h < H; ++h) {
+            const uint32_t th = Th[h];
+            for (int i = tid; i < N; i += kThreads) {
+                const uint32_t key = ord_key(sc[(int64_t)h * tab.T + i]);
+                if (key < th) {
+                    if (key > tl) atomicAdd(&cnt_gt[h], 1u);
+                    else if (key == tl) atomicAdd(&cnt_eq[h], 1u);
+                }
             }
         }
     }
@@ -118,10 +318,10 @@ __global__ __launch_bounds__(kThreads) void budget_kernel(const float *__restric
         for (int h = 0; h < H; ++h) {
             uint32_t b = (uint32_t)m_safe;
             if (R > 0) {
-                const uint32_t extra = m_safe > 0 ? ties_h[h] - want_h[h] : 0u;
+                const uint32_t ex = m_safe > 0 ? ties_h[h] - want_h[h] : 0u;
                 uint32_t gt = cnt_gt[h], eq = cnt_eq[h];
-                if (Th[h] > TL) gt += extra;
-                else if (Th[h] == TL) eq += extra;
+                if (Th[h] > TL) gt += ex;
+                else if (Th[h] == TL) eq += ex;
                 const uint32_t take = min(remaining, eq);
                 remaining -= take;
                 b += gt + take;
@@ -133,11 +333,30 @@ __global__ __launch_bounds__(kThreads) void budget_kernel(const float *__restric
 
 }  // namespace
 
-hipError_t launch_budget(const float *scores, int L, int H, const PromptTab &tab, int32_t *k_per_head,
+size_t budget_ws_bytes(int L, int H, const PromptTab &tab)
+{
+    const size_t units = (size_t)tab.n * L * H;
+    return units * sizeof(HeadSafe) + units * 2048 * sizeof(uint32_t);
+}
+
+hipError_t launch_budget(const float *scores, int L, int H, const PromptTab &tab, int32_t *k_per_head, void *ws,
                          const Prof &prof, hipStream_t st)
 {
+    int nmax = 0;
+    for (int p = 0; p < tab.n; ++p) nmax = max(nmax, tab.tok_off[p + 1] - tab.tok_off[p]);
+    const unsigned units = (unsigned)(tab.n * L * H);
     prof.begin(NKV_KERNEL_BUDGET, st);
-    budget_kernel<<<(unsigned)(tab.n * L), kThreads, 0, st>>>(scores, L, H, tab, k_per_head);
+    if (ws != nullptr && H <= kFastHeads && nmax <= 32 * kSelThreads) {
+        HeadSafe *safe = (HeadSafe *)ws;
+        uint32_t *pool_hist = (uint32_t *)(safe + units);
+        if (nmax <= 4 * kSelThreads) head_safe_kernel<4><<<units, kSelThreads, 0, st>>>(scores, L, H, tab, safe, pool_hist);
+        else if (nmax <= 8 * kSelThreads) head_safe_kernel<8><<<units, kSelThreads, 0, st>>>(scores, L, H, tab, safe, pool_hist);
+        else if (nmax <= 16 * kSelThreads) head_safe_kernel<16><<<units, kSelThreads, 0, st>>>(scores, L, H, tab, safe, pool_hist);
+        else head_safe_kernel<32><<<units, kSelThreads, 0, st>>>(scores, L, H, tab, safe, pool_hist);
+        layer_budget_kernel<<<(unsigned)(tab.n * L), kThreads, 0, st>>>(scores, L, H, tab, safe, pool_hist, k_per_head);
+    } else {
+        budget_kernel<<<(unsigned)(tab.n * L), kThreads, 0, st>>>(scores, L, H, tab, k_per_head);
+    }
     prof.end(NKV_KERNEL_BUDGET, st);
     return hipGetLastError();
 }

@@ -11,7 +11,7 @@
 // The sum of the m largest values is  sum(a > T) + (m - count(a > T)) * T  with T the m-th largest,
 // which does not depend on how ties at T are broken.  Min-max is affine and increasing, so the
 // selects run on the raw anomalies and the gap is rescaled afterwards.
-#include "nkv_device.h"
+#include "nkv_blocksel.h"
 
 namespace nkv {
 namespace {
@@ -36,6 +36,19 @@ __device__ __forceinline__ float std3(const float at[3])
     const float m = (at[0] + at[1] + at[2]) * (1.0f / 3.0f);
     const float x = at[0] - m, y = at[1] - m, z = at[2] - m;
     return sqrtf((x * x + y * y + z * z) * (1.0f / 3.0f));
+}
+
+// blend, surprise, gate and route of one token from its three normalised readings (Section 2.4)
+__device__ __forceinline__ float routed_score(const float at[3], const HeadStats &st, const LearnerConsts &lc)
+{
+    const float blend = st.w[0] * at[0] + st.w[1] * at[1] + st.w[2] * at[2];
+    const float win = fmaxf(at[0], fmaxf(at[1], at[2]));
+    float s = std3(at);
+    if (lc.surprise_mode == NKV_SURPRISE_NORMALISED) s = fmaxf((s - st.s_lo) * st.s_inv_range - st.s_mean, 0.f);
+    const float alpha = 1.0f / (1.0f + expf(-lc.kappa * (s - lc.tau)));
+    if (lc.gate_mode == NKV_GATE_ONLY_AVERAGE) return blend;
+    if (lc.gate_mode == NKV_GATE_ONLY_MAX) return win;
+    return (1.0f - alpha) * blend + alpha * win;
 }
 
 __global__ __launch_bounds__(kThreads) void finalize_kernel(const float *__restrict__ a_raw, int L, int H,
@@ -172,27 +185,173 @@ __global__ __launch_bounds__(kThreads) void finalize_kernel(const float *__restr
 #pragma unroll
         for (int k = 0; k < 3; ++k) av[k] = a[k][i];
         normalised(av, st, at);
-        const float blend = st.w[0] * at[0] + st.w[1] * at[1] + st.w[2] * at[2];
-        const float win = fmaxf(at[0], fmaxf(at[1], at[2]));
-        float s = std3(at);
-        if (lc.surprise_mode == NKV_SURPRISE_NORMALISED)
-            s = fmaxf((s - st.s_lo) * st.s_inv_range - st.s_mean, 0.f);
-        const float alpha = 1.0f / (1.0f + expf(-lc.kappa * (s - lc.tau)));
-        float star;
-        if (lc.gate_mode == NKV_GATE_ONLY_AVERAGE) star = blend;
-        else if (lc.gate_mode == NKV_GATE_ONLY_MAX) star = win;
-        else star = (1.0f - alpha) * blend + alpha * win;
+        const float star = routed_score(at, st, lc);
         out[i] = i < lc.n_sink ? NKV_PIN : star;
+    }
+}
+
+
+// ------------------------------------------------------------------------------------------------------
+// Units of up to 1024 * EPT tokens: two kernels with the values held in registers.
+//   scale_stats_kernel : one workgroup per (unit, scale): min, max and the reliability gap of that scale
+//   route_kernel       : one workgroup per unit: weights, surprise statistics, routed score, pinning
+// ------------------------------------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t block_min_u32(uint32_t v, uint32_t *scratch)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = min(v, (uint32_t)__shfl_xor((int)v, o, 64));
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) scratch[threadIdx.x >> 6] = v;
+    __syncthreads();
+    uint32_t r = scratch[0];
+    for (int i = 1; i < (int)(blockDim.x >> 6); ++i) r = min(r, scratch[i]);
+    return r;
+}
+__device__ __forceinline__ uint32_t block_max_u32(uint32_t v, uint32_t *scratch)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = max(v, (uint32_t)__shfl_xor((int)v, o, 64));
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) scratch[threadIdx.x >> 6] = v;
+    __syncthreads();
+    uint32_t r = scratch[0];
+    for (int i = 1; i < (int)(blockDim.x >> 6); ++i) r = max(r, scratch[i]);
+    return r;
+}
+
+// stats[(u * 3 + k) * 4 + {0, 1, 2}] = min, 1 / range (0 if flat), reliability gap of scale k of unit u
+template <int EPT>
+__global__ __launch_bounds__(kSelThreads) void scale_stats_kernel(const float *__restrict__ a_raw, int L, int H,
+                                                                   PromptTab tab, float *__restrict__ stats)
+{
+    __shared__ SelectScratch sel;
+    __shared__ uint32_t uscratch[16];
+    __shared__ double dscratch[16];
+    const int k = blockIdx.x, u = blockIdx.y;
+    const int h = u % H, l = (u / H) % L, p = u / (H * L);
+    const int N = tab.tok_off[p + 1] - tab.tok_off[p];
+    const int64_t rows = (int64_t)L * H * tab.T;
+    const float *a = a_raw + (int64_t)k * rows + ((int64_t)l * H + h) * tab.T + tab.tok_off[p];
+    const int tid = threadIdx.x;
+
+    uint32_t key[EPT];
+    uint32_t kmin = 0xffffffffu, kmax = 0u;
+#pragma unroll
+    for (int j = 0; j < EPT; ++j) {
+        const int i = tid + j * kSelThreads;
+        key[j] = i < N ? ord_key(a[i]) : 0u;
+        if (i < N) { kmin = min(kmin, key[j]); kmax = max(kmax, key[j]); }
+    }
+    kmin = block_min_u32(kmin, uscratch);
+    kmax = block_max_u32(kmax, uscratch);
+    const uint32_t m = (uint32_t)min(tab.m_p[p], N);
+    uint32_t rem_top, rem_bot, ties;
+    const uint32_t t_top = block_select<EPT, true>(key, N, m, sel, rem_top, ties);
+    const uint32_t t_bot = block_select<EPT, false>(key, N, m, sel, rem_bot, ties);
+    double s_top = 0.0, s_bot = 0.0;
+#pragma unroll
+    for (int j = 0; j < EPT; ++j) {
+        if (tid + j * kSelThreads < N) {
+            const double v = (double)key_value(key[j]);
+            if (key[j] > t_top) s_top += v;
+            if (key[j] < t_bot) s_bot += v;
+        }
+    }
+    s_top = block_sum(s_top, dscratch);
+    s_bot = block_sum(s_bot, dscratch);
+    if (tid == 0) {
+        const float lo = key_value(kmin), range = key_value(kmax) - lo;
+        const float inv = range < kFlat ? 0.f : 1.0f / range;
+        // ties at the threshold: rem of them belong to the set
+        const double top = s_top + (double)rem_top * (double)key_value(t_top);
+        const double bot = s_bot + (double)rem_bot * (double)key_value(t_bot);
+        float *o = stats + ((int64_t)u * 3 + k) * 4;
+        o[0] = lo;
+        o[1] = inv;
+        o[2] = (float)((top - bot) / (double)m * (double)inv);
+    }
+}
+
+__global__ __launch_bounds__(kSelThreads) void route_kernel(const float *__restrict__ a_raw, int L, int H,
+                                                            PromptTab tab, LearnerConsts lc,
+                                                            const float *__restrict__ stats,
+                                                            float *__restrict__ scores)
+{
+    __shared__ float fscratch[16];
+    __shared__ double dscratch[16];
+    __shared__ HeadStats hs;
+    const int u = blockIdx.x;
+    const int h = u % H, l = (u / H) % L, p = u / (H * L);
+    const int N = tab.tok_off[p + 1] - tab.tok_off[p];
+    const int64_t rows = (int64_t)L * H * tab.T;
+    const int64_t base = ((int64_t)l * H + h) * tab.T + tab.tok_off[p];
+    const float *a0 = a_raw + base, *a1 = a_raw + rows + base, *a2 = a_raw + 2 * rows + base;
+    const int tid = threadIdx.x;
+
+    if (tid == 0) {
+        double z[3], zmax = -INFINITY, zsum = 0.0;
+#pragma unroll
+        for (int k = 0; k < 3; ++k) {
+            const float *st = stats + ((int64_t)u * 3 + k) * 4;
+            hs.lo[k] = st[0];
+            hs.inv_range[k] = st[1];
+            z[k] = lc.log_prior[k] + lc.beta * (double)st[2];
+            zmax = fmax(zmax, z[k]);
+        }
+#pragma unroll
+        for (int k = 0; k < 3; ++k) { z[k] = exp(z[k] - zmax); zsum += z[k]; }
+#pragma unroll
+        for (int k = 0; k < 3; ++k) hs.w[k] = (float)(z[k] / zsum);
+    }
+    __syncthreads();
+    HeadStats st = hs;
+    float smin = INFINITY, smax = -INFINITY;
+    double ssum = 0.0;
+    for (int i = tid; i < N; i += kSelThreads) {
+        const float av[3] = {a0[i], a1[i], a2[i]};
+        float at[3];
+        normalised(av, st, at);
+        const float s = std3(at);
+        smin = fminf(smin, s);
+        smax = fmaxf(smax, s);
+        ssum += (double)s;
+    }
+    smin = block_min(smin, fscratch);
+    smax = block_max(smax, fscratch);
+    ssum = block_sum(ssum, dscratch);
+    const float srange = smax - smin;
+    st.s_lo = smin;
+    st.s_inv_range = srange < kFlat ? 0.f : 1.0f / srange;
+    st.s_mean = (float)((ssum / (double)N - (double)smin) * (double)st.s_inv_range);
+
+    float *out = scores + base;
+    for (int i = tid; i < N; i += kSelThreads) {
+        const float av[3] = {a0[i], a1[i], a2[i]};
+        float at[3];
+        normalised(av, st, at);
+        out[i] = i < lc.n_sink ? NKV_PIN : routed_score(at, st, lc);
     }
 }
 
 }  // namespace
 
 hipError_t launch_finalize(const float *a_raw, int L, int H, const PromptTab &tab, const LearnerConsts &lc,
-                           float *scores, const Prof &prof, hipStream_t st)
+                           float *scores, float *stats, const Prof &prof, hipStream_t st)
 {
+    int nmax = 0;
+    for (int p = 0; p < tab.n; ++p) nmax = max(nmax, tab.tok_off[p + 1] - tab.tok_off[p]);
+    const unsigned units = (unsigned)(tab.n * L * H);
     prof.begin(NKV_KERNEL_FINALIZE, st);
-    finalize_kernel<<<(unsigned)(tab.n * L * H), kThreads, 0, st>>>(a_raw, L, H, tab, lc, scores);
+    if (nmax <= 32 * kSelThreads) {
+        const dim3 grid(3, units);
+        if (nmax <= 4 * kSelThreads) scale_stats_kernel<4><<<grid, kSelThreads, 0, st>>>(a_raw, L, H, tab, stats);
+        else if (nmax <= 8 * kSelThreads) scale_stats_kernel<8><<<grid, kSelThreads, 0, st>>>(a_raw, L, H, tab, stats);
+        else if (nmax <= 16 * kSelThreads) scale_stats_kernel<16><<<grid, kSelThreads, 0, st>>>(a_raw, L, H, tab, stats);
+        else scale_stats_kernel<32><<<grid, kSelThreads, 0, st>>>(a_raw, L, H, tab, stats);
+        route_kernel<<<units, kSelThreads, 0, st>>>(a_raw, L, H, tab, lc, stats, scores);
+    } else {
+        finalize_kernel<<<units, kThreads, 0, st>>>(a_raw, L, H, tab, lc, scores);
+    }
     prof.end(NKV_KERNEL_FINALIZE, st);
     return hipGetLastError();
 }

@@ -59,10 +59,12 @@ hipError_t launch_score_fast(const void *keys, int LH, int d, const PromptTab &t
 
 // ---- per-head statistics, blend weights, gate and final scores ----
 hipError_t launch_finalize(const float *a_raw, int L, int H, const PromptTab &tab, const LearnerConsts &lc,
-                           float *scores, const Prof &prof, hipStream_t st);
+                           float *scores, float *stats, const Prof &prof, hipStream_t st);
 
 // ---- head-wise budgets ----
-hipError_t launch_budget(const float *scores, int L, int H, const PromptTab &tab, int32_t *k_per_head,
+size_t budget_ws_bytes(int L, int H, const PromptTab &tab);
+// ws == nullptr selects the shape-generic kernel, which needs no scratch
+hipError_t launch_budget(const float *scores, int L, int H, const PromptTab &tab, int32_t *k_per_head, void *ws,
                          const Prof &prof, hipStream_t st);
 
 // ---- selection, ordered compaction, gather ----

@@ -8,7 +8,7 @@
 //                     kept token its output slot; kept_idx is written in ascending order.
 //   gather_kernel   : flat over output rows; each row is a straight 16-byte-vector copy of one K row
 //                     and one V row.
-#include "nkv_device.h"
+#include "nkv_blocksel.h"
 
 namespace nkv {
 namespace {
@@ -145,6 +145,96 @@ __global__ __launch_bounds__(kThreads) void select_kernel(const float *__restric
     }
 }
 
+
+// Units of up to 1024 * EPT tokens: scores in registers (element tid + j*1024 in slot j).  One radix select,
+// then an ordered compaction without per-chunk barriers: every wavefront ballots its 64 consecutive tokens
+// of chunk j, the (chunk, wave) population counts are scanned once in token order, and each kept token's
+// output slot is its group's offset plus the number of kept lanes below it.
+template <int EPT>
+__global__ __launch_bounds__(kSelThreads) void select_fast_kernel(const float *__restrict__ scores,
+                                                                  const int32_t *__restrict__ k_per_head, int L,
+                                                                  int H, PromptTab tab, float near_tol,
+                                                                  const int64_t *__restrict__ head_off,
+                                                                  int64_t row_capacity,
+                                                                  int32_t *__restrict__ kept_idx,
+                                                                  int64_t *__restrict__ near_count)
+{
+    __shared__ SelectScratch sel;
+    __shared__ unsigned long long group_cnt[EPT * kWaves];           // (gt << 32 | eq) per (chunk, wave)
+    __shared__ unsigned long long near_acc[16];
+
+    const int u = blockIdx.x;
+    const int h = u % H, l = (u / H) % L, p = u / (H * L);
+    const int N = tab.tok_off[p + 1] - tab.tok_off[p];
+    const int B = min(max(k_per_head[u], 0), N);
+    if (B == 0) return;
+    const float *sc = scores + ((int64_t)l * H + h) * tab.T + tab.tok_off[p];
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int64_t out0 = head_off[u];
+
+    uint32_t key[EPT];
+#pragma unroll
+    for (int j = 0; j < EPT; ++j) {
+        const int i = tid + j * kSelThreads;
+        key[j] = i < N ? ord_key(sc[i]) : 0u;
+    }
+    uint32_t T = 0u, rem = 0u, ties = 0u;                             // B == N: every token is kept
+    if (B < N) {
+        T = block_select<EPT, true>(key, N, (uint32_t)B, sel, rem, ties);
+        if (near_count) {                                             // tokens within near_tol of the threshold score
+            const float tv = key_value(T);
+            unsigned long long c = 0;
+#pragma unroll
+            for (int j = 0; j < EPT; ++j)
+                if (tid + j * kSelThreads < N && fabsf(key_value(key[j]) - tv) <= near_tol) ++c;
+            c = block_sum(c, near_acc);
+            if (tid == 0) atomicAdd((unsigned long long *)near_count, c);
+        }
+    }
+    // population of every (chunk, wave) group
+#pragma unroll
+    for (int j = 0; j < EPT; ++j) {
+        const bool in = tid + j * kSelThreads < N;
+        const bool gt = in && (B == N || key[j] > T);
+        const bool eq = in && B < N && key[j] == T;
+        const unsigned long long mg = __ballot(gt), me = __ballot(eq);
+        if (lane == 0) group_cnt[j * kWaves + w] = ((unsigned long long)__popcll(mg) << 32) | (unsigned long long)__popcll(me);
+    }
+    __syncthreads();
+    if (w == 0) {                                                     // exclusive scan over the groups in token order
+        constexpr int PER = EPT * kWaves / 64;
+        unsigned long long v[PER], tot = 0;
+#pragma unroll
+        for (int q = 0; q < PER; ++q) { v[q] = group_cnt[lane * PER + q]; tot += v[q]; }
+        unsigned long long incl = tot;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const unsigned long long t = __shfl_up(incl, o, 64);
+            if (lane >= o) incl += t;
+        }
+        unsigned long long run = incl - tot;
+#pragma unroll
+        for (int q = 0; q < PER; ++q) { group_cnt[lane * PER + q] = run; run += v[q]; }
+    }
+    __syncthreads();
+    const unsigned long long below = (1ull << lane) - 1ull;
+#pragma unroll
+    for (int j = 0; j < EPT; ++j) {
+        const int i = tid + j * kSelThreads;
+        const bool in = i < N;
+        const bool gt = in && (B == N || key[j] > T);
+        const bool eq = in && B < N && key[j] == T;
+        const unsigned long long mg = __ballot(gt), me = __ballot(eq);
+        const unsigned long long base = group_cnt[j * kWaves + w];
+        const uint32_t gt_before = (uint32_t)(base >> 32) + (uint32_t)__popcll(mg & below);
+        const uint32_t eq_before = (uint32_t)(base & 0xffffffffu) + (uint32_t)__popcll(me & below);
+        if (gt || (eq && eq_before < rem)) {
+            const int64_t row = out0 + gt_before + min(eq_before, rem);
+            if (row < row_capacity) kept_idx[row] = i;
+        }
+    }
+}
+
 constexpr int kRowsPerGroup = 32;
 
 // 16-byte vectors; krow16 / vrow16 = vectors per K / V row.
@@ -208,9 +298,20 @@ hipError_t launch_select_compact(const void *keys, const void *values, const flo
 {
     const int n_units = tab.n * L * H;
     head_off_kernel<<<1, kThreads, 0, st>>>(k_per_head, L, H, tab, head_off, near_count);
+    int nmax = 0;
+    for (int p = 0; p < tab.n; ++p) nmax = max(nmax, tab.tok_off[p + 1] - tab.tok_off[p]);
     prof.begin(NKV_KERNEL_SELECT, st);
-    select_kernel<<<(unsigned)n_units, kThreads, 0, st>>>(scores, k_per_head, L, H, tab, near_tol, head_off,
-                                                          row_capacity, kept_idx, near_count);
+#define NKV_SELECT_FAST(EPT)                                                                                 \
+    select_fast_kernel<EPT><<<(unsigned)n_units, kSelThreads, 0, st>>>(scores, k_per_head, L, H, tab, near_tol, \
+                                                                       head_off, row_capacity, kept_idx, near_count)
+    if (nmax <= 4 * kSelThreads) NKV_SELECT_FAST(4);
+    else if (nmax <= 8 * kSelThreads) NKV_SELECT_FAST(8);
+    else if (nmax <= 16 * kSelThreads) NKV_SELECT_FAST(16);
+    else if (nmax <= 32 * kSelThreads) NKV_SELECT_FAST(32);
+    else
+        select_kernel<<<(unsigned)n_units, kThreads, 0, st>>>(scores, k_per_head, L, H, tab, near_tol, head_off,
+                                                              row_capacity, kept_idx, near_count);
+#undef NKV_SELECT_FAST
     prof.end(NKV_KERNEL_SELECT, st);
     // no unit keeps more than its prompt length, so the row count is bounded by L*H*T as well
     const int64_t max_rows = row_capacity < (int64_t)L * H * tab.T ? row_capacity : (int64_t)L * H * tab.T;

@@ -55,7 +55,7 @@ def check_scores(g: np.ndarray, o: np.ndarray, what: str) -> float:
 
 
 def run_gpu(w: nkv_inputs.Workload, K: torch.Tensor, V: torch.Tensor, r, params=None, scores=None,
-            k_per_head=None):
+            k_per_head=None, use_ws=True):
     """The three ABI calls on cuda:0.  ``scores`` / ``k_per_head`` (device tensors) replace the library's own
     for stage-wise parity.  Returns the Compressed record (device tensors) after synchronising."""
     params = params or nkv.params_default()
@@ -67,7 +67,7 @@ def run_gpu(w: nkv_inputs.Workload, K: torch.Tensor, V: torch.Tensor, r, params=
     else:
         comp.scores.copy_(scores)
     if k_per_head is None:
-        nkv.budget(comp.scores, shape, params, r, comp.k_per_head)
+        nkv.budget(comp.scores, shape, params, r, comp.k_per_head, comp.ws if use_ws else None)
         rows = comp.rows
     else:
         comp.k_per_head.copy_(k_per_head)

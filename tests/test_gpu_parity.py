@@ -79,6 +79,8 @@ SWEEP = [
     ("fp32_ragged", 1, 2, 128, [300, 513], "fp32", 0),
     ("wide_head", 1, 1, 256, [600], "bf16", 0),
     ("d_40", 1, 2, 40, [500], "fp32", 24),
+    ("long_prompt", 1, 2, 64, [40000], "bf16", 0),        # beyond the register-resident per-head kernels
+    ("many_heads", 1, 12, 64, [600, 90], "bf16", 0),      # beyond the 8-head layer budget kernel
 ]
 
 
@@ -136,6 +138,14 @@ def test_heavy_ties_stage_parity():
         assert np.array_equal(out.k_per_head.cpu().numpy(), ref.k_per_head)
         assert np.array_equal(out.kept_idx.cpu().numpy(), ref.kept_idx)
         assert np.array_equal(bits(out.packed_k), ref.packed_k) and np.array_equal(bits(out.packed_v), ref.packed_v)
+
+
+def test_budget_without_workspace_uses_the_generic_kernel():
+    w = nkv_inputs.small_workload("nows", 2, 4, 64, [3000, 200])
+    K, V = _kv(w)
+    a, _ = run_gpu(w, K, V, 0.8)
+    b, _ = run_gpu(w, K, V, 0.8, use_ws=False)
+    assert torch.equal(a.k_per_head, b.k_per_head) and torch.equal(a.kept_idx, b.kept_idx)
 
 
 def test_given_budgets_are_clamped_and_capacity_is_respected():
