@@ -74,6 +74,21 @@ __global__ __launch_bounds__(kSelThreads) void head_safe_kernel(const float *__r
     if (tid == 0) safe[u] = HeadSafe{T, rem, ties, 0u};
 }
 
+// Calls f(key) for every score of s[0..N), the workgroup striding over the row with eight independent loads
+// in flight per thread (the scores sit in L2 / memory; one load at a time would be latency-bound).
+template <typename F> __device__ __forceinline__ void for_each_key(const float *__restrict__ s, int N, F f)
+{
+    constexpr int U = 8;
+    for (int i0 = threadIdx.x; i0 < N; i0 += U * kThreads) {
+        float v[U];
+#pragma unroll
+        for (int q = 0; q < U; ++q) v[q] = i0 + q * kThreads < N ? s[i0 + q * kThreads] : 0.f;
+#pragma unroll
+        for (int q = 0; q < U; ++q)
+            if (i0 + q * kThreads < N) f(ord_key(v[q]));
+    }
+}
+
 // Finds the bin holding rank `want` from the top of an NB-bin histogram (NB = 1024 or 2048); 1024 threads.
 // out[0] = bin, out[1] = rank inside the bin.  Contains barriers.
 template <int NB>
@@ -150,10 +165,9 @@ __global__ __launch_bounds__(kThreads) void layer_budget_kernel(const float *__r
     for (int h = 0; h < H; ++h) {
         const float *s = sc + (int64_t)h * tab.T;
         const uint32_t th = Th[h];
-        for (int i = tid; i < N; i += kThreads) {
-            const uint32_t key = ord_key(s[i]);
+        for_each_key(s, N, [&](uint32_t key) {
             if (key < th && (key >> 21) == d0) atomicAdd(&hist[(key >> 10) & 2047u], 1u);
-        }
+        });
         if (tid == 0 && extra[h] > 0u && (th >> 21) == d0) atomicAdd(&hist[(th >> 10) & 2047u], extra[h]);
     }
     __syncthreads();
@@ -169,14 +183,13 @@ __global__ __launch_bounds__(kThreads) void layer_budget_kernel(const float *__r
         const float *s = sc + (int64_t)h * tab.T;
         const uint32_t th = Th[h];
         uint32_t gt = 0u;
-        for (int i = tid; i < N; i += kThreads) {
-            const uint32_t key = ord_key(s[i]);
+        for_each_key(s, N, [&](uint32_t key) {
             if (key < th) {
                 const uint32_t hi = key >> 10;
                 if (hi > pre22) ++gt;
                 else if (hi == pre22) atomicAdd(&hist2[h][key & 1023u], 1u);
             }
-        }
+        });
         gt = wave_sum(gt);
         if ((tid & 63) == 0 && gt != 0u) atomicAdd(&cnt_gt[h], gt);
         if (tid == 0 && extra[h] > 0u) {

@@ -307,14 +307,25 @@ __global__ __launch_bounds__(kSelThreads) void route_kernel(const float *__restr
     HeadStats st = hs;
     float smin = INFINITY, smax = -INFINITY;
     double ssum = 0.0;
-    for (int i = tid; i < N; i += kSelThreads) {
-        const float av[3] = {a0[i], a1[i], a2[i]};
-        float at[3];
-        normalised(av, st, at);
-        const float s = std3(at);
-        smin = fminf(smin, s);
-        smax = fmaxf(smax, s);
-        ssum += (double)s;
+    constexpr int U = 4;                                  // independent loads in flight per thread and scale
+    for (int i0 = tid; i0 < N; i0 += U * kSelThreads) {
+        float av[U][3];
+#pragma unroll
+        for (int q = 0; q < U; ++q) {
+            const int i = min(i0 + q * kSelThreads, N - 1);
+            av[q][0] = a0[i]; av[q][1] = a1[i]; av[q][2] = a2[i];
+        }
+#pragma unroll
+        for (int q = 0; q < U; ++q) {
+            if (i0 + q * kSelThreads < N) {
+                float at[3];
+                normalised(av[q], st, at);
+                const float s = std3(at);
+                smin = fminf(smin, s);
+                smax = fmaxf(smax, s);
+                ssum += (double)s;
+            }
+        }
     }
     smin = block_min(smin, fscratch);
     smax = block_max(smax, fscratch);
@@ -325,11 +336,22 @@ __global__ __launch_bounds__(kSelThreads) void route_kernel(const float *__restr
     st.s_mean = (float)((ssum / (double)N - (double)smin) * (double)st.s_inv_range);
 
     float *out = scores + base;
-    for (int i = tid; i < N; i += kSelThreads) {
-        const float av[3] = {a0[i], a1[i], a2[i]};
-        float at[3];
-        normalised(av, st, at);
-        out[i] = i < lc.n_sink ? NKV_PIN : routed_score(at, st, lc);
+    for (int i0 = tid; i0 < N; i0 += U * kSelThreads) {
+        float av[U][3];
+#pragma unroll
+        for (int q = 0; q < U; ++q) {
+            const int i = min(i0 + q * kSelThreads, N - 1);
+            av[q][0] = a0[i]; av[q][1] = a1[i]; av[q][2] = a2[i];
+        }
+#pragma unroll
+        for (int q = 0; q < U; ++q) {
+            const int i = i0 + q * kSelThreads;
+            if (i < N) {
+                float at[3];
+                normalised(av[q], st, at);
+                out[i] = i < lc.n_sink ? NKV_PIN : routed_score(at, st, lc);
+            }
+        }
     }
 }
 
