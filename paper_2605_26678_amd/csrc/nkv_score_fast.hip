@@ -298,6 +298,44 @@ void scan_kernel(const uint16_t *__restrict__ keys, PromptTab tab, float *__rest
         }
     }
 
+
+    // ---- stable anchor: the workgroup that completes the unit adds the block totals up right away ----
+    // (before its own window loop, so that the sum is ready long before anybody needs it)
+    float *S_unit = ssum + ((int64_t)lh * tab.n + p) * D;
+    const __amdgpu_buffer_rsrc_t srs = __builtin_amdgcn_make_buffer_rsrc(S_unit, 0, D * 4, 0x00020000);
+    if (FUSED) __syncthreads();                                       // s_last is known; lds_T is free again
+    if (FUSED && s_last) {                                            // uniform over the workgroup
+        // thread = (slice, 4 dims): slice s adds blocks s, s + NS, s + 2 NS, ... with several loads in
+        // flight; the slices are then added in order.  The order depends on the shape only.
+        constexpr int VPR = D / 4, NS = 64 * NW / VPR;
+        const __amdgpu_buffer_rsrc_t brs = __builtin_amdgcn_make_buffer_rsrc(bsum_unit, 0, unblk * D * 4, 0x00020000);
+        const int vec = threadIdx.x % VPR, slice = threadIdx.x / VPR;
+        float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int bb = slice; bb < unblk; bb += 4 * NS) {
+            float4 v[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i)                               // blocks past the end read as zeros
+                v[i] = agent_load16(brs, (bb + i * NS) * D * 4 + vec * 16);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) { acc.x += v[i].x; acc.y += v[i].y; acc.z += v[i].z; acc.w += v[i].w; }
+        }
+        float *part = &lds_T[0][0][0];                                // NS * D floats fit (see the static_assert)
+        static_assert(NS * D <= NW * SG * D, "partial sums of the unit do not fit the LDS scratch");
+        reinterpret_cast<float4 *>(part)[slice * VPR + vec] = acc;
+        __syncthreads();
+        if (threadIdx.x < VPR) {
+            float4 tot = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+            for (int sl = 0; sl < NS; ++sl) {
+                const float4 v = reinterpret_cast<const float4 *>(part)[sl * VPR + vec];
+                tot.x += v.x; tot.y += v.y; tot.z += v.z; tot.w += v.w;
+            }
+            agent_store16(srs, vec * 16, tot);
+            wait_own_accesses();
+            if (threadIdx.x == 0) __hip_atomic_store(ucnt + 1, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
+
     // ---- slide the window over this lane's tokens; episodic and current dots ----
     float wd_m = 0.f, wn_m = 1.f, bd_m = 0.f, rn_m = 0.f;
     constexpr int GR = 4;                                             // tokens per software-pipeline stage
@@ -345,41 +383,7 @@ void scan_kernel(const uint16_t *__restrict__ keys, PromptTab tab, float *__rest
     }
     if (!FUSED) return;
 
-    // ---- stable anchor: last workgroup of the unit adds the block totals up, the others wait ----
-    float *S_unit = ssum + ((int64_t)lh * tab.n + p) * D;
-    __syncthreads();
-    const __amdgpu_buffer_rsrc_t srs = __builtin_amdgcn_make_buffer_rsrc(S_unit, 0, D * 4, 0x00020000);
-    if (s_last) {                                                     // uniform over the workgroup
-        // thread = (slice, 4 dims): slice s adds blocks s, s + NS, s + 2 NS, ... with several loads in
-        // flight; the slices are then added in order.  The order depends on the shape only.
-        constexpr int VPR = D / 4, NS = 64 * NW / VPR;
-        const __amdgpu_buffer_rsrc_t brs = __builtin_amdgcn_make_buffer_rsrc(bsum_unit, 0, unblk * D * 4, 0x00020000);
-        const int vec = threadIdx.x % VPR, slice = threadIdx.x / VPR;
-        float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-        for (int bb = slice; bb < unblk; bb += 4 * NS) {
-            float4 v[4];
-#pragma unroll
-            for (int i = 0; i < 4; ++i)                               // blocks past the end read as zeros
-                v[i] = agent_load16(brs, (bb + i * NS) * D * 4 + vec * 16);
-#pragma unroll
-            for (int i = 0; i < 4; ++i) { acc.x += v[i].x; acc.y += v[i].y; acc.z += v[i].z; acc.w += v[i].w; }
-        }
-        float *part = &lds_T[0][0][0];                                // NS * D floats fit (see the static_assert)
-        static_assert(NS * D <= NW * SG * D, "partial sums of the unit do not fit the LDS scratch");
-        reinterpret_cast<float4 *>(part)[slice * VPR + vec] = acc;
-        __syncthreads();
-        if (threadIdx.x < VPR) {
-            float4 tot = make_float4(0.f, 0.f, 0.f, 0.f);
-#pragma unroll
-            for (int sl = 0; sl < NS; ++sl) {
-                const float4 v = reinterpret_cast<const float4 *>(part)[sl * VPR + vec];
-                tot.x += v.x; tot.y += v.y; tot.z += v.z; tot.w += v.w;
-            }
-            agent_store16(srs, vec * 16, tot);
-            wait_own_accesses();
-            if (threadIdx.x == 0) __hip_atomic_store(ucnt + 1, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
-    }
+    // ---- stable anomaly: wait for the unit's sum (normally long since there), one more dot per token ----
     if (w == 0) {                                                     // one wave polls, the others sit at the barrier
         uint32_t spins = 0;
         while (__hip_atomic_load(ucnt + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0u) {
