@@ -9,25 +9,41 @@
 // the block (the current-memory window of the block's first tokens reaches back that far) are split
 // evenly over the wavefronts, which only need their norms and partial sums.
 //
-// Per chunk: 1/||k|| per token (sum of squares reduced over the LPR lanes with DPP) and the partial sums
-// T[g] = sum of k_hat over the sub-group's tokens.  Partial sums go through LDS: they give the chunk and
-// block totals (episodic anchor; the block totals are also the partial sums of the stable anchor) and the
-// window sum in front of every sub-group.  The window sum then slides token by token,
+// Arithmetic.  The kernel is bound by vector-ALU issue, not by memory, so every phase is written for a
+// low instruction count:
+//   * ||k||^2 comes from the packed bf16 pairs directly (v_dot2c_f32_bf16: two exact products and an fp32
+//     accumulation per instruction), without unpacking;
+//   * a quantity that every token needs summed over the LPR lanes of its row (norms, dots) is reduced for
+//     all TPT rows of a lane at once by a transposing butterfly: each step halves the number of live
+//     values, and lane c ends up with the total of row c.  This costs ~2 instructions per row instead of
+//     log2(LPR) + 1, and the result lands in the lane that reports the token;
+//   * 1/||k|| is computed once per token and handed to the row's lanes through LDS.
+//
+// Per chunk: 1/||k|| per token and the partial sums T[g] = sum of k_hat over the sub-group's tokens.
+// Partial sums go through LDS: they give the chunk and block totals (episodic anchor; the block totals
+// are also the partial sums of the stable anchor) and the window sum in front of every sub-group.  The
+// window sum then slides token by token,
 //     W_i = W_{i-1} - k_hat_{i-64} + k_hat_i,
 // re-seeded exactly at every sub-group boundary (every TPT tokens) from the partial sums, so no long
 // running sum and no cancellation beyond TPT steps.  k_hat_{i-64} sits at the same lane position of the
-// previous chunk, which the wavefront re-loads (an L1/L2 hit: a neighbouring wavefront has just read it).
+// previous chunk, which the wavefront re-loads (an L2 hit: a neighbouring wavefront has just read it).
 // Cosines do not depend on the anchor's length, so sums stand in for means everywhere.
 //
+// Placement.  The chip's compute units sit in 8 dies (XCDs) with one L2 each, and consecutive workgroups
+// start on different dies.  Blocks are therefore not taken in launch order: every die has its own ticket
+// counter and walks its own contiguous eighth of each (layer, head)'s blocks, so the halo and the
+// re-loaded rows of a block were fetched by the same L2 moments before.  All dies work on the same
+// (layer, head) at the same time.  A die that runs out of tickets takes them from the next die's counter.
+//
 // The stable anchor needs every key of the prompt before the first a_s can be computed.  Two ways:
-//   fused   : workgroups take tickets in start order; all blocks of a (layer, head, prompt) unit have
-//             consecutive tickets.  Each workgroup publishes its block total and bumps the unit's arrival
-//             counter; the last one to arrive adds the block totals up in block order (deterministic),
-//             publishes the sum and raises the unit's flag; the others wait for the flag with their chunk
-//             still in registers, then compute a_s.  A waiting workgroup only ever waits for workgroups
-//             with tickets of the same unit, all of which have started or can start as long as the chip
-//             can hold one unit's workgroups at once -- the host checks that before choosing this path.
-//             Waits are bounded; a timeout is recorded in the sync area and the kernel still ends.
+//   fused   : all blocks of a (layer, head, prompt) unit are ticketed close together.  Each workgroup
+//             publishes its block total and bumps the unit's arrival counter; the last one to arrive adds
+//             the block totals up in block order (deterministic), publishes the sum and raises the unit's
+//             flag; the others wait for the flag with their chunk still in registers, then compute a_s.
+//             A waiting workgroup only ever waits for workgroups of the same unit, all of which have
+//             started or can start as long as the chip can hold one unit's workgroups at once -- the host
+//             checks that before choosing this path.  Waits are bounded; a timeout is recorded in the
+//             sync area and the kernel still ends.
 //   2-pass  : stable_kernel re-reads the keys after ssum_kernel (any prompt length).
 #include "nkv_device.h"
 
@@ -49,6 +65,104 @@ template <int LPR> __device__ __forceinline__ float row_sum(float v)
     return v;
 }
 
+// ---- transposing butterfly ---------------------------------------------------------------------------
+// merge_k(x, y): lanes whose bit k of the lane index is 0 receive x + x(partner), the others y + y(partner),
+// partner = lane ^ (1 << k).  Two values go in, one comes out, and which of the two a lane keeps is decided
+// by one bit of its index; after log2(LPR) merges lane c holds the complete sum of the value with index c.
+//
+// Bits 2 and 3 use DPP row rotations with a bank mask (a bank is 4 lanes): the first add is written by all
+// lanes, the second only by the banks whose lanes keep x.  row_ror:n hands lane i the value of lane
+// (i - n) mod 16.  The compiler does not track DPP read-after-write hazards inside inline assembly; the
+// leading s_nop covers inputs written by the instruction just before the block, and inside a block no DPP
+// source is written by the block itself.
+__device__ __forceinline__ void merge_bit2_x4(float (&r)[4], float x0, float x1, float x2, float x3, float y0,
+                                              float y1, float y2, float y3)
+{
+    asm("s_nop 1\n\t"
+        "v_add_f32_dpp %0, %8, %8 row_ror:4 row_mask:0xf bank_mask:0xf\n\t"
+        "v_add_f32_dpp %1, %9, %9 row_ror:4 row_mask:0xf bank_mask:0xf\n\t"
+        "v_add_f32_dpp %2, %10, %10 row_ror:4 row_mask:0xf bank_mask:0xf\n\t"
+        "v_add_f32_dpp %3, %11, %11 row_ror:4 row_mask:0xf bank_mask:0xf\n\t"
+        "v_add_f32_dpp %0, %4, %4 row_ror:12 row_mask:0xf bank_mask:0x5\n\t"
+        "v_add_f32_dpp %1, %5, %5 row_ror:12 row_mask:0xf bank_mask:0x5\n\t"
+        "v_add_f32_dpp %2, %6, %6 row_ror:12 row_mask:0xf bank_mask:0x5\n\t"
+        "v_add_f32_dpp %3, %7, %7 row_ror:12 row_mask:0xf bank_mask:0x5"
+        : "=&v"(r[0]), "=&v"(r[1]), "=&v"(r[2]), "=&v"(r[3])
+        : "v"(x0), "v"(x1), "v"(x2), "v"(x3), "v"(y0), "v"(y1), "v"(y2), "v"(y3));
+}
+
+__device__ __forceinline__ void merge_bit3_x4(float (&r)[4], float x0, float x1, float x2, float x3, float y0,
+                                              float y1, float y2, float y3)
+{
+    asm("s_nop 1\n\t"
+        "v_add_f32_dpp %0, %8, %8 row_ror:8 row_mask:0xf bank_mask:0xf\n\t"
+        "v_add_f32_dpp %1, %9, %9 row_ror:8 row_mask:0xf bank_mask:0xf\n\t"
+        "v_add_f32_dpp %2, %10, %10 row_ror:8 row_mask:0xf bank_mask:0xf\n\t"
+        "v_add_f32_dpp %3, %11, %11 row_ror:8 row_mask:0xf bank_mask:0xf\n\t"
+        "v_add_f32_dpp %0, %4, %4 row_ror:8 row_mask:0xf bank_mask:0x3\n\t"
+        "v_add_f32_dpp %1, %5, %5 row_ror:8 row_mask:0xf bank_mask:0x3\n\t"
+        "v_add_f32_dpp %2, %6, %6 row_ror:8 row_mask:0xf bank_mask:0x3\n\t"
+        "v_add_f32_dpp %3, %7, %7 row_ror:8 row_mask:0xf bank_mask:0x3"
+        : "=&v"(r[0]), "=&v"(r[1]), "=&v"(r[2]), "=&v"(r[3])
+        : "v"(x0), "v"(x1), "v"(x2), "v"(x3), "v"(y0), "v"(y1), "v"(y2), "v"(y3));
+}
+
+// Bits 0 and 1 stay inside a quad, below the granularity of a bank mask: select, then one DPP add.
+__device__ __forceinline__ float merge_bit0(float x, float y)
+{
+    const bool hi = (threadIdx.x & 1) != 0;
+    const float keep = hi ? y : x, send = hi ? x : y;
+    return keep + dpp_mov<0xB1>(send);
+}
+__device__ __forceinline__ float merge_bit1(float x, float y)
+{
+    const bool hi = (threadIdx.x & 2) != 0;
+    const float keep = hi ? y : x, send = hi ? x : y;
+    return keep + dpp_mov<0x4E>(send);
+}
+
+// Four values whose indices differ in bits 0 and 1 -> the one value of this lane.
+__device__ __forceinline__ float merge_low4(const float (&b)[4])
+{
+    return merge_bit1(merge_bit0(b[0], b[1]), merge_bit0(b[2], b[3]));
+}
+
+// v[j], j < LPR: partial sums of row j held by this lane.  Returns the full sum of row c = lane % LPR.
+template <int LPR> __device__ __forceinline__ float transpose_reduce(const float (&v)[LPR])
+{
+    float a[4];
+    merge_bit2_x4(a, v[0], v[1], v[2], v[3], v[4], v[5], v[6], v[7]);
+    if constexpr (LPR == 16) {
+        float a2[4], b[4];
+        merge_bit2_x4(a2, v[8], v[9], v[10], v[11], v[12], v[13], v[14], v[15]);
+        merge_bit3_x4(b, a[0], a[1], a[2], a[3], a2[0], a2[1], a2[2], a2[3]);
+        return merge_low4(b);
+    } else {
+        return merge_low4(a);
+    }
+}
+
+// The same butterfly fed four rows at a time (rows 4s .. 4s+3 in step s), so that a loop that produces
+// its rows in order never holds more than eight partial values per quantity.
+template <int LPR> struct StreamReduce {
+    float hold[4], half[4];
+    template <int S> __device__ __forceinline__ void push(const float (&p)[4], float &out)
+    {
+        if constexpr (S == 0 || S == 2) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) hold[i] = p[i];
+        } else if constexpr (S == 1) {
+            merge_bit2_x4(half, hold[0], hold[1], hold[2], hold[3], p[0], p[1], p[2], p[3]);
+            if constexpr (LPR == 8) out = merge_low4(half);
+        } else {
+            float a2[4], b[4];
+            merge_bit2_x4(a2, hold[0], hold[1], hold[2], hold[3], p[0], p[1], p[2], p[3]);
+            merge_bit3_x4(b, half[0], half[1], half[2], half[3], a2[0], a2[1], a2[2], a2[3]);
+            out = merge_low4(b);
+        }
+    }
+};
+
 using u32x4 = unsigned int __attribute__((ext_vector_type(4)));
 
 // 16-byte load through a buffer descriptor: the address is one 32-bit byte offset per lane plus an
@@ -64,6 +178,35 @@ __device__ __forceinline__ void unpack8(const u32x4 &r, float k[8])
     k[2] = __uint_as_float(r.y << 16); k[3] = __uint_as_float(r.y & 0xffff0000u);
     k[4] = __uint_as_float(r.z << 16); k[5] = __uint_as_float(r.z & 0xffff0000u);
     k[6] = __uint_as_float(r.w << 16); k[7] = __uint_as_float(r.w & 0xffff0000u);
+}
+
+// Sum of the squares of the eight bf16 values of a packed row piece: four dot-product instructions, each
+// adding two exact bf16 x bf16 products to an fp32 accumulator.
+__device__ __forceinline__ float sumsq8(const u32x4 &r)
+{
+    float acc = 0.f;
+    asm("v_dot2c_f32_bf16 %0, %1, %1\n\t"
+        "v_dot2c_f32_bf16 %0, %2, %2\n\t"
+        "v_dot2c_f32_bf16 %0, %3, %3\n\t"
+        "v_dot2c_f32_bf16 %0, %4, %4"
+        : "+v"(acc)
+        : "v"(r.x), "v"(r.y), "v"(r.z), "v"(r.w));
+    return acc;
+}
+
+// The same for a value that compiler-generated DPP instructions read next: the compiler does not see the
+// write inside the assembly, so the two wait states a DPP read needs after it are spent here.
+__device__ __forceinline__ float sumsq8_for_dpp(const u32x4 &r)
+{
+    float acc = 0.f;
+    asm("v_dot2c_f32_bf16 %0, %1, %1\n\t"
+        "v_dot2c_f32_bf16 %0, %2, %2\n\t"
+        "v_dot2c_f32_bf16 %0, %3, %3\n\t"
+        "v_dot2c_f32_bf16 %0, %4, %4\n\t"
+        "s_nop 1"
+        : "+v"(acc)
+        : "v"(r.x), "v"(r.y), "v"(r.z), "v"(r.w));
+    return acc;
 }
 
 // Makes the compiler forget what it knows about a packed row, so that the unpacked floats of one phase
@@ -95,10 +238,6 @@ __device__ __forceinline__ void agent_store(float *p, float v)
 {
     __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
-__device__ __forceinline__ float agent_load(const float *p)
-{
-    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
 
 // 16-byte agent-scope accesses through a buffer descriptor (cache policy bit 4 = sc1 on gfx94x/gfx950).
 __device__ __forceinline__ float4 agent_load16(__amdgpu_buffer_rsrc_t rsrc, int byte_off)
@@ -119,39 +258,62 @@ __device__ __forceinline__ void wait_own_accesses() { asm volatile("s_waitcnt vm
 
 constexpr int kMaxChunks = 4;                    // chunks per block: block size <= 256
 constexpr uint32_t kSpinLimit = 1u << 22;        // ~1 s of polling before a wait gives up
+constexpr int kDies = 8;                         // ticket counters (one per XCD of an MI355X)
 
-constexpr int kUnitStride = 64;                  // words between the counters of two units
+// Sync area of the fused path (all zero before the launch), in 32-bit words.
+constexpr int kTicketStride = 32;                // one 128-byte line per die's ticket counter
+constexpr int kTimeoutWord = kDies * kTicketStride;
+constexpr int kUnitBase = kTimeoutWord + 32;     // per-unit counters start here
+constexpr int kUnitStride = 64;                  // words per unit: arrivals at +0, flag at +32 (own line)
 
-// Sync area of the fused path (all zero before the launch).
-struct ScanSync {
-    uint32_t ticket;
-    uint32_t timeouts;
-    uint32_t pad[62];
-    uint32_t unit[1];                            // [units][kUnitStride]: arrivals, flag, padding to 256 bytes
-};
+// Blocks [seg_lo(x), seg_lo(x + 1)) of every (layer, head) belong to die x.
+__device__ __forceinline__ int seg_lo(int nblk, int x) { return (int)(((int64_t)x * nblk) / kDies); }
 
-// NW wavefronts = chunks per block.  grid: one workgroup per (layer*head, block); 1-D when FUSED.
+// NW wavefronts = chunks per block.  grid: one workgroup per (layer*head, block), 1-D.
 template <int D, int NW, bool FUSED>
-__global__ __launch_bounds__(64 * NW, NW == 4 ? 3 : 4)
+__global__ __launch_bounds__(64 * NW, 3)
 void scan_kernel(const uint16_t *__restrict__ keys, PromptTab tab, float *__restrict__ a_raw,
-                 float *__restrict__ bsum, float *__restrict__ ssum, ScanSync *__restrict__ sync, int64_t rows)
+                 float *__restrict__ bsum, float *__restrict__ ssum, uint32_t *__restrict__ sync, int LH,
+                 int64_t rows)
 {
     constexpr int LPR = D / 8, SG = 64 / LPR, TPT = LPR;
     constexpr int HT = (TPT + NW - 1) / NW;                           // halo tokens per lane
+    constexpr int NST = TPT / 4;                                      // 4-row steps per lane
     __shared__ float lds_rn[NW + 1][64];                              // [0]: halo chunk, [1 + w]: chunk w
     __shared__ float lds_T[NW][SG][D];                                // partial sums of the chunks
     __shared__ float lds_Th[NW][SG][D];                               // partial sums of the halo chunk
     __shared__ float lds_C[NW][D];                                    // chunk totals
-    __shared__ int s_ticket, s_last;
+    __shared__ int s_lh, s_blk, s_last;
 
     const int nblk = tab.blk_off[tab.n];
-    int wg = blockIdx.x;
+    int lh, blk;
     if (FUSED) {
-        if (threadIdx.x == 0) s_ticket = (int)atomicAdd(&sync->ticket, 1u);
+        // take a ticket from this die's counter, or from the next die's that still has work
+        if (threadIdx.x == 0) {
+            const int die = (int)(__builtin_amdgcn_s_getreg((3 << 11) | 20) & (kDies - 1));   // XCC_ID[3:0]
+            int got_lh = -1, got_blk = 0;
+            for (int i = 0; i < kDies && got_lh < 0; ++i) {
+                const int x = (die + i) & (kDies - 1);
+                const int lo = seg_lo(nblk, x), len = seg_lo(nblk, x + 1) - lo;
+                if (len == 0) continue;
+                const uint32_t t = __hip_atomic_fetch_add(sync + x * kTicketStride, 1u, __ATOMIC_RELAXED,
+                                                          __HIP_MEMORY_SCOPE_AGENT);
+                if (t < (uint32_t)len * (uint32_t)LH) {
+                    got_lh = (int)(t / (uint32_t)len);
+                    got_blk = lo + (int)(t % (uint32_t)len);
+                }
+            }
+            s_lh = got_lh;
+            s_blk = got_blk;
+        }
         __syncthreads();
-        wg = s_ticket;
+        lh = s_lh;
+        blk = s_blk;
+        if (lh < 0) return;                                           // more workgroups than blocks: cannot happen
+    } else {
+        lh = blockIdx.x / nblk;
+        blk = blockIdx.x - lh * nblk;
     }
-    const int lh = wg / nblk, blk = wg - lh * nblk;
     const int p = prompt_of_block(tab, blk);
     const int b = tab.b[p];
     const int N = tab.tok_off[p + 1] - tab.tok_off[p];
@@ -176,49 +338,52 @@ void scan_kernel(const uint16_t *__restrict__ keys, PromptTab tab, float *__rest
     const int halo_off = (blk_lo - 64 + g * TPT + HT * w) * kRowBytes + c * 16;
 #pragma unroll
     for (int jj = 0; jj < HT; ++jj) hraw[jj] = row_load(rsrc, halo_off + jj * kRowBytes);
-    float rn[TPT], T[8], kn_mine = 1.f;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) T[e] = 0.f;
-#pragma unroll
-    for (int j = 0; j < TPT; ++j) {
-        float k[8];
-        unpack8(raw[j], k);
-        float ss = 0.f;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) ss = fmaf(k[e], k[e], ss);
-        ss = row_sum<LPR>(ss);
-        rn[j] = (t0 + j < blk_hi) ? inv_norm(ss) : 0.f;
-        if (j == c) kn_mine = ss < 1e-24f ? sqrtf(ss) * 1e12f : 1.f;   // ||k_hat|| of this lane's own token
-#pragma unroll
-        for (int e = 0; e < 8; ++e) T[e] = fmaf(rn[j], k[e], T[e]);
-        if ((j & 3) == 3) __builtin_amdgcn_sched_barrier(0);          // bound the unpacked temporaries
-    }
-    store8(&lds_T[w][g][c * 8], T);
+
+    // ---- norms: one token per lane (lane (g, c) reports token g*TPT + c = lane of the chunk) ----
+    float rn_m, kn_m;
     {
-        float mine = 0.f;                                             // lane (g, c) owns token g*TPT + c
+        float ss[TPT];
 #pragma unroll
-        for (int j = 0; j < TPT; ++j) mine = (j == c) ? rn[j] : mine;
-        lds_rn[1 + w][lane] = mine;
+        for (int j = 0; j < TPT; ++j) ss[j] = sumsq8(raw[j]);
+        const float ss_m = transpose_reduce<LPR>(ss);
+        rn_m = (blk_lo + 64 * w + lane < blk_hi) ? inv_norm(ss_m) : 0.f;
+        kn_m = ss_m < 1e-24f ? sqrtf(ss_m) * 1e12f : 1.f;             // ||k_hat|| of this lane's own token
+        lds_rn[1 + w][lane] = rn_m;
     }
+    // ---- halo share: norms and partial sums ----
+    float T[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) T[e] = 0.f;
 #pragma unroll
     for (int jj = 0; jj < HT; ++jj) {
-        float k[8];
-        unpack8(hraw[jj], k);
-        float ss = 0.f;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) ss = fmaf(k[e], k[e], ss);
-        ss = row_sum<LPR>(ss);
+        const float ssh = row_sum<LPR>(sumsq8_for_dpp(hraw[jj]));
         const int q = HT * w + jj;
         const bool ok = q < TPT && blk_lo - 64 + g * TPT + q >= 0;
-        const float r = ok ? inv_norm(ss) : 0.f;
+        const float r = ok ? inv_norm(ssh) : 0.f;
+        float k[8];
+        unpack8(hraw[jj], k);
 #pragma unroll
         for (int e = 0; e < 8; ++e) T[e] = fmaf(r, k[e], T[e]);
         if (c == jj && q < TPT) lds_rn[0][g * TPT + q] = r;
-        if ((jj & 3) == 3) __builtin_amdgcn_sched_barrier(0);
     }
     store8(&lds_Th[w][g][c * 8], T);
+    // ---- partial sums of the chunk: the row's 1/||k|| comes back from LDS (same wave: in order) ----
+#pragma unroll
+    for (int e = 0; e < 8; ++e) T[e] = 0.f;
+#pragma unroll
+    for (int s = 0; s < NST; ++s) {
+        const float4 r4 = *reinterpret_cast<const float4 *>(&lds_rn[1 + w][g * TPT + 4 * s]);
+        const float rr[4] = {r4.x, r4.y, r4.z, r4.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            float k[8];
+            unpack8(raw[4 * s + i], k);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) T[e] = fmaf(rr[i], k[e], T[e]);
+        }
+        __builtin_amdgcn_sched_barrier(0);                            // bound the unpacked temporaries
+    }
+    store8(&lds_T[w][g][c * 8], T);
     __syncthreads();
 
     // ---- chunk totals; window sum in front of this lane's first token ----
@@ -283,7 +448,7 @@ void scan_kernel(const uint16_t *__restrict__ keys, PromptTab tab, float *__rest
     // Everything other workgroups read (block totals, the unit's sum, counters) is written and read with
     // agent-scope accesses, which go to the level of the memory hierarchy all compute units share; ordering
     // then only needs this wave's own stores to have completed, not a write-back of the whole L2.
-    uint32_t *ucnt = FUSED ? &sync->unit[kUnitStride * ((int64_t)lh * tab.n + p)] : nullptr;
+    uint32_t *ucnt = FUSED ? sync + kUnitBase + kUnitStride * ((int64_t)lh * tab.n + p) : nullptr;
     if (w == 0) {
         if (g == 0) {
 #pragma unroll
@@ -297,7 +462,6 @@ void scan_kernel(const uint16_t *__restrict__ keys, PromptTab tab, float *__rest
             }
         }
     }
-
 
     // ---- stable anchor: the workgroup that completes the unit adds the block totals up right away ----
     // (before its own window loop, so that the sum is ready long before anybody needs it)
@@ -332,92 +496,108 @@ void scan_kernel(const uint16_t *__restrict__ keys, PromptTab tab, float *__rest
             }
             agent_store16(srs, vec * 16, tot);
             wait_own_accesses();
-            if (threadIdx.x == 0) __hip_atomic_store(ucnt + 1, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (threadIdx.x == 0) __hip_atomic_store(ucnt + 32, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
     }
 
-    // ---- slide the window over this lane's tokens; episodic and current dots ----
-    float wd_m = 0.f, wn_m = 1.f, bd_m = 0.f, rn_m = 0.f;
-    constexpr int GR = 4;                                             // tokens per software-pipeline stage
+    // ---- slide the window over this lane's tokens: current-memory dots ----
+    // Four rows per step: their leaving rows (same lane position, previous chunk) are loaded one step
+    // ahead; the per-lane partial dots of the four rows enter the transposing butterfly.
+    float wd_m = 0.f, wn_m = 1.f;
+    {
+        StreamReduce<LPR> red_wd, red_wn;
 #pragma unroll
-    for (int j = 0; j < TPT; ++j) forget(raw[j]);
-    u32x4 pnext[GR];
+        for (int j = 0; j < TPT; ++j) forget(raw[j]);
+        u32x4 pnext[4];
 #pragma unroll
-    for (int i = 0; i < GR; ++i) pnext[i] = row_load(rsrc, lane_off + (i - 64) * kRowBytes);
+        for (int i = 0; i < 4; ++i) pnext[i] = row_load(rsrc, lane_off + (i - 64) * kRowBytes);
 #pragma unroll
-    for (int j0 = 0; j0 < TPT; j0 += GR) {
-        u32x4 pcur[GR];
+        for (int s = 0; s < NST; ++s) {
+            u32x4 pcur[4];
 #pragma unroll
-        for (int i = 0; i < GR; ++i) pcur[i] = pnext[i];
-        if (j0 + GR < TPT) {                                          // re-load the next stage's leaving tokens
+            for (int i = 0; i < 4; ++i) pcur[i] = pnext[i];
+            if (s + 1 < NST) {                                        // re-load the next step's leaving rows
 #pragma unroll
-            for (int i = 0; i < GR; ++i) pnext[i] = row_load(rsrc, lane_off + (j0 + GR + i - 64) * kRowBytes);
-        }
-#pragma unroll
-        for (int i = 0; i < GR; ++i) {
-            const int j = j0 + i;
-            const float rnp = lds_rn[w][g * TPT + j];                 // 0 where the leaving token does not exist
-            float kp[8], k[8];
-            unpack8(pcur[i], kp);
-            unpack8(raw[j], k);
-            float wd = 0.f, wn = 0.f, bd = 0.f;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                W[e] = fmaf(-rnp, kp[e], W[e]);
-                W[e] = fmaf(rn[j], k[e], W[e]);
-                wd = fmaf(k[e], W[e], wd);
-                wn = fmaf(W[e], W[e], wn);
-                bd = fmaf(k[e], Bs[e], bd);
+                for (int i = 0; i < 4; ++i) pnext[i] = row_load(rsrc, lane_off + (4 * s + 4 + i - 64) * kRowBytes);
             }
-            wd = row_sum<LPR>(wd);
-            wn = row_sum<LPR>(wn);
-            bd = row_sum<LPR>(bd);
-            if (j == c) { wd_m = wd; wn_m = wn; bd_m = bd; rn_m = rn[j]; }
+            const float4 r4 = *reinterpret_cast<const float4 *>(&lds_rn[1 + w][g * TPT + 4 * s]);
+            const float4 q4 = *reinterpret_cast<const float4 *>(&lds_rn[w][g * TPT + 4 * s]);
+            const float rr[4] = {r4.x, r4.y, r4.z, r4.w};
+            const float rp[4] = {q4.x, q4.y, q4.z, q4.w};             // 0 where the leaving token does not exist
+            float pw[4], pn[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                float kp[8], k[8];
+                unpack8(pcur[i], kp);
+                unpack8(raw[4 * s + i], k);
+                float wd = 0.f, wn = 0.f;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    W[e] = fmaf(-rp[i], kp[e], W[e]);
+                    W[e] = fmaf(rr[i], k[e], W[e]);
+                    wd = fmaf(k[e], W[e], wd);
+                    wn = fmaf(W[e], W[e], wn);
+                }
+                pw[i] = wd; pn[i] = wn;
+            }
+            if (s == 0) { red_wd.template push<0>(pw, wd_m); red_wn.template push<0>(pn, wn_m); }
+            if (s == 1) { red_wd.template push<1>(pw, wd_m); red_wn.template push<1>(pn, wn_m); }
+            if constexpr (LPR == 16) {
+                if (s == 2) { red_wd.template push<2>(pw, wd_m); red_wn.template push<2>(pn, wn_m); }
+                if (s == 3) { red_wd.template push<3>(pw, wd_m); red_wn.template push<3>(pn, wn_m); }
+            }
+            __builtin_amdgcn_sched_barrier(0);                        // one step at a time
         }
-        __builtin_amdgcn_sched_barrier(0);                            // one stage at a time
     }
     const int tok = blk_lo + 64 * w + lane;                           // lane (g, c) reports token g*TPT + c
-    if (tok < blk_hi) {
-        a_raw[rows + row0 + tok] = neg_cos(rn_m * bd_m, kn_mine, bsq);
-        a_raw[2 * rows + row0 + tok] = neg_cos(rn_m * wd_m, kn_mine, wn_m);
-    }
-    if (!FUSED) return;
+    if (tok < blk_hi) a_raw[2 * rows + row0 + tok] = neg_cos(rn_m * wd_m, kn_m, wn_m);
 
-    // ---- stable anomaly: wait for the unit's sum (normally long since there), one more dot per token ----
-    if (w == 0) {                                                     // one wave polls, the others sit at the barrier
-        uint32_t spins = 0;
-        while (__hip_atomic_load(ucnt + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0u) {
-            if (++spins > kSpinLimit) {
-                if (lane == 0) atomicAdd(&sync->timeouts, 1u);
-                break;
-            }
-            __builtin_amdgcn_s_sleep(16);
-        }
-    }
-    __syncthreads();
+    // ---- episodic and stable dots against the two fixed anchors ----
+    // The unit's sum is normally long since there when a workgroup gets here.
     float S[8];
-    {
+    float ssq = 1.f;
+    if (FUSED) {
+        if (w == 0) {                                                 // one wave polls, the others sit at the barrier
+            uint32_t spins = 0;
+            while (__hip_atomic_load(ucnt + 32, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0u) {
+                if (++spins > kSpinLimit) {
+                    if (lane == 0) atomicAdd(sync + kTimeoutWord, 1u);
+                    break;
+                }
+                __builtin_amdgcn_s_sleep(16);
+            }
+        }
+        __syncthreads();
         const float4 s0 = agent_load16(srs, c * 32), s1 = agent_load16(srs, c * 32 + 16);
         S[0] = s0.x; S[1] = s0.y; S[2] = s0.z; S[3] = s0.w; S[4] = s1.x; S[5] = s1.y; S[6] = s1.z; S[7] = s1.w;
-    }
-    float ssq = 0.f, sd_m = 0.f;
+        ssq = 0.f;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) ssq = fmaf(S[e], S[e], ssq);
-    ssq = row_sum<LPR>(ssq);
+        for (int e = 0; e < 8; ++e) ssq = fmaf(S[e], S[e], ssq);
+        ssq = row_sum<LPR>(ssq);
+    }
 #pragma unroll
     for (int j = 0; j < TPT; ++j) forget(raw[j]);
+    float bd[TPT], sd[TPT];
 #pragma unroll
     for (int j = 0; j < TPT; ++j) {
         float k[8];
         unpack8(raw[j], k);
-        float sd = 0.f;
+        float accb = 0.f, accs = 0.f;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) sd = fmaf(k[e], S[e], sd);
-        sd = row_sum<LPR>(sd);
-        if (j == c) sd_m = sd;
+        for (int e = 0; e < 8; ++e) {
+            accb = fmaf(k[e], Bs[e], accb);
+            if (FUSED) accs = fmaf(k[e], S[e], accs);
+        }
+        bd[j] = accb;
+        sd[j] = accs;
         if ((j & 3) == 3) __builtin_amdgcn_sched_barrier(0);
     }
-    if (tok < blk_hi) a_raw[row0 + tok] = neg_cos(rn_m * sd_m, kn_mine, ssq);
+    const float bd_m = transpose_reduce<LPR>(bd);
+    if (tok < blk_hi) a_raw[rows + row0 + tok] = neg_cos(rn_m * bd_m, kn_m, bsq);
+    if (FUSED) {
+        const float sd_m = transpose_reduce<LPR>(sd);
+        if (tok < blk_hi) a_raw[row0 + tok] = neg_cos(rn_m * sd_m, kn_m, ssq);
+    }
 }
 
 __global__ void zero_kernel(uint32_t *p, int n)
@@ -481,11 +661,11 @@ __global__ __launch_bounds__(256) void stable_kernel(const uint16_t *__restrict_
 
 template <int D, int NW, bool FUSED>
 void launch_scan(const uint16_t *keys, int LH, const PromptTab &tab, float *a_raw, float *bsum, float *ssum,
-                 ScanSync *sync, hipStream_t st)
+                 uint32_t *sync, hipStream_t st)
 {
     const int64_t rows = (int64_t)LH * tab.T;
     scan_kernel<D, NW, FUSED><<<(unsigned)(tab.blk_off[tab.n] * LH), 64 * NW, 0, st>>>(keys, tab, a_raw, bsum, ssum,
-                                                                                      sync, rows);
+                                                                                      sync, LH, rows);
 }
 
 template <int D, int NW, bool FUSED> int resident_workgroups()
@@ -502,6 +682,8 @@ template <int D, int NW, bool FUSED> int resident_workgroups()
     return cached;
 }
 
+int sync_words(int LH, const PromptTab &tab) { return kUnitBase + kUnitStride * LH * tab.n; }
+
 template <int D, int NW>
 hipError_t run_nw(const uint16_t *keys, int LH, const PromptTab &tab, float *a_raw, float *bsum, float *ssum,
                   void *sync_area, bool allow_fused, const Prof &prof, hipStream_t st)
@@ -511,10 +693,10 @@ hipError_t run_nw(const uint16_t *keys, int LH, const PromptTab &tab, float *a_r
     // fused only if the chip can hold two units' worth of workgroups at once (see the header comment)
     const bool fused = allow_fused && 2 * max_unit_blocks <= resident_workgroups<D, NW, true>();
     if (fused) {
-        const int words = 64 + kUnitStride * LH * tab.n;
+        const int words = sync_words(LH, tab);
         zero_kernel<<<(words + 255) / 256, 256, 0, st>>>((uint32_t *)sync_area, words);
         prof.begin(NKV_KERNEL_SCAN, st);
-        launch_scan<D, NW, true>(keys, LH, tab, a_raw, bsum, ssum, (ScanSync *)sync_area, st);
+        launch_scan<D, NW, true>(keys, LH, tab, a_raw, bsum, ssum, (uint32_t *)sync_area, st);
         prof.end(NKV_KERNEL_SCAN, st);
     } else {
         prof.begin(NKV_KERNEL_SCAN, st);
@@ -550,7 +732,7 @@ bool fast_score_supported(int dtype, int d, int window, const PromptTab &tab)
     return true;
 }
 
-size_t fast_score_sync_bytes(int LH, const PromptTab &tab) { return (size_t)(64 + kUnitStride * LH * tab.n) * 4; }
+size_t fast_score_sync_bytes(int LH, const PromptTab &tab) { return (size_t)sync_words(LH, tab) * 4; }
 
 hipError_t launch_score_fast(const void *keys, int LH, int d, const PromptTab &tab, float *a_raw, float *bsum,
                              float *ssum, void *sync_area, bool allow_fused, const Prof &prof, hipStream_t st)
