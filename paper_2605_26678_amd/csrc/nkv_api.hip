@@ -74,7 +74,7 @@ ScoreWs score_ws(const nkv_shape *s, const PromptTab &tab, bool with_a_raw)
     const size_t LH = (size_t)s->L * s->H;
     ScoreWs w;
     size_t off = 0;
-    w.sync = off;   off += align_up(fast_score_sync_bytes((int)LH, tab));   // first: word 1 counts timed-out waits
+    w.sync = off;   off += align_up(fast_score_sync_bytes());
     w.a_raw = off;  off += with_a_raw ? align_up(3 * rows * 4) : 0;
     w.rnorm = off;  off += align_up(rows * 4);
     w.bsum = off;   off += align_up(LH * tab.blk_off[tab.n] * s->d * 4);

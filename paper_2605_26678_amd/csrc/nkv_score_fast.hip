@@ -36,15 +36,19 @@
 // (layer, head) at the same time.  A die that runs out of tickets takes them from the next die's counter.
 //
 // The stable anchor needs every key of the prompt before the first a_s can be computed.  Two ways:
-//   fused   : all blocks of a (layer, head, prompt) unit are ticketed close together.  Each workgroup
-//             publishes its block total and bumps the unit's arrival counter; the last one to arrive adds
-//             the block totals up in block order (deterministic), publishes the sum and raises the unit's
-//             flag; the others wait for the flag with their chunk still in registers, then compute a_s.
-//             A waiting workgroup only ever waits for workgroups of the same unit, all of which have
-//             started or can start as long as the chip can hold one unit's workgroups at once -- the host
-//             checks that before choosing this path.  Waits are bounded; a timeout is recorded in the
-//             sync area and the kernel still ends.
-//   2-pass  : stable_kernel re-reads the keys after ssum_kernel (any prompt length).
+//   fused   : all blocks of a (layer, head, prompt) unit are ticketed close together.  The block totals
+//             and the unit sums live in memory that is filled with a NaN bit pattern before the launch, so
+//             a 32-bit word that has been written is recognisable by itself and no flags, counters or
+//             waits for completed stores are needed.  Each workgroup stores its block total (agent scope)
+//             and goes on to its window loop.  The workgroup that holds the unit's last block polls all
+//             block totals of the unit right after storing its own, adds them up in block order and
+//             stores the unit sum.  After its window loop every workgroup polls the unit sum with its
+//             chunk still in registers, then computes a_s.  A waiting workgroup only ever waits for
+//             workgroups of the same unit, all of which have started or can start as long as the chip can
+//             hold one unit's workgroups at once -- the host checks that before choosing this path.
+//             Waits are bounded; a timeout is recorded in the sync area and the kernel still ends.
+//   2-pass  : block totals go to memory, ssum_kernel adds them up and stable_kernel re-reads the keys
+//             (any prompt length).
 #include "nkv_device.h"
 
 namespace nkv {
@@ -233,38 +237,39 @@ __device__ __forceinline__ float neg_cos(float dot_scaled, float knorm, float an
     return -dot_scaled / (fmaxf(knorm, kEps) * fmaxf(sqrtf(anchor_sq), kEps));
 }
 
-// Accesses other workgroups must see / have written: performed at agent (device) scope.
-__device__ __forceinline__ void agent_store(float *p, float v)
-{
-    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
+// ---- self-validating words (fused path) ----------------------------------------------------------------
+// Block totals and unit sums are finite floats; memory that still holds kUnwritten has not been stored to.
+// Validity is judged per 32-bit word, the unit every store writes atomically.
+constexpr uint32_t kUnwritten = 0xFFFFFFFFu;
 
-// 16-byte agent-scope accesses through a buffer descriptor (cache policy bit 4 = sc1 on gfx94x/gfx950).
-__device__ __forceinline__ float4 agent_load16(__amdgpu_buffer_rsrc_t rsrc, int byte_off)
+// 16-byte agent-scope accesses through a buffer descriptor (cache policy bit 4 = sc1 on gfx94x/gfx950): they
+// go to the level of the memory hierarchy that all compute units of the device share.
+// The compiler barrier keeps a polling loop from having its load hoisted: to the compiler the intrinsic is a
+// plain read of memory this thread never writes.
+__device__ __forceinline__ u32x4 agent_load16(__amdgpu_buffer_rsrc_t rsrc, int byte_off)
 {
-    const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rsrc, byte_off, 0, 16);
-    return make_float4(__uint_as_float(v.x), __uint_as_float(v.y), __uint_as_float(v.z), __uint_as_float(v.w));
+    asm volatile("" ::: "memory");
+    return __builtin_amdgcn_raw_buffer_load_b128(rsrc, byte_off, 0, 16);
 }
-__device__ __forceinline__ void agent_store16(__amdgpu_buffer_rsrc_t rsrc, int byte_off, float4 f)
+__device__ __forceinline__ void agent_store16(__amdgpu_buffer_rsrc_t rsrc, int byte_off, float a, float b, float c,
+                                              float d)
 {
-    const u32x4 v = {__float_as_uint(f.x), __float_as_uint(f.y), __float_as_uint(f.z), __float_as_uint(f.w)};
+    const u32x4 v = {__float_as_uint(a), __float_as_uint(b), __float_as_uint(c), __float_as_uint(d)};
     __builtin_amdgcn_raw_buffer_store_b128(v, rsrc, byte_off, 0, 16);
 }
-
-// Waits until every memory access this wave has issued so far has completed; also keeps the compiler from
-// moving memory accesses across it.  Agent-scope stores are visible to the whole device once complete, so
-// "agent_store ...; wait_own_accesses(); agent-scope atomic" publishes data without an L2 write-back.
-__device__ __forceinline__ void wait_own_accesses() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+__device__ __forceinline__ bool all_written(const u32x4 &v)
+{
+    return v.x != kUnwritten && v.y != kUnwritten && v.z != kUnwritten && v.w != kUnwritten;
+}
 
 constexpr int kMaxChunks = 4;                    // chunks per block: block size <= 256
 constexpr uint32_t kSpinLimit = 1u << 22;        // ~1 s of polling before a wait gives up
 constexpr int kDies = 8;                         // ticket counters (one per XCD of an MI355X)
 
-// Sync area of the fused path (all zero before the launch), in 32-bit words.
+// Sync area of the fused path (all zero before the launch), in 32-bit words: ticket counters, timeouts.
 constexpr int kTicketStride = 32;                // one 128-byte line per die's ticket counter
 constexpr int kTimeoutWord = kDies * kTicketStride;
-constexpr int kUnitBase = kTimeoutWord + 32;     // per-unit counters start here
-constexpr int kUnitStride = 64;                  // words per unit: arrivals at +0, flag at +32 (own line)
+constexpr int kSyncWords = kTimeoutWord + 32;
 
 // Blocks [seg_lo(x), seg_lo(x + 1)) of every (layer, head) belong to die x.
 __device__ __forceinline__ int seg_lo(int nblk, int x) { return (int)(((int64_t)x * nblk) / kDies); }
@@ -283,7 +288,8 @@ void scan_kernel(const uint16_t *__restrict__ keys, PromptTab tab, float *__rest
     __shared__ float lds_T[NW][SG][D];                                // partial sums of the chunks
     __shared__ float lds_Th[NW][SG][D];                               // partial sums of the halo chunk
     __shared__ float lds_C[NW][D];                                    // chunk totals
-    __shared__ int s_lh, s_blk, s_last;
+    __shared__ float lds_S[D];                                        // the unit's sum, once complete
+    __shared__ int s_lh, s_blk;
 
     const int nblk = tab.blk_off[tab.n];
     int lh, blk;
@@ -443,83 +449,80 @@ void scan_kernel(const uint16_t *__restrict__ keys, PromptTab tab, float *__rest
 #pragma unroll
     for (int e = 0; e < 8; ++e) bsq = fmaf(Bs[e], Bs[e], bsq);
     bsq = row_sum<LPR>(bsq);
+    const int unblk = tab.blk_off[p + 1] - tab.blk_off[p];
     float *bsum_unit = bsum + ((int64_t)lh * nblk + tab.blk_off[p]) * D;      // block totals of this unit
-    const int ublk = blk - tab.blk_off[p], unblk = tab.blk_off[p + 1] - tab.blk_off[p];
-    // Everything other workgroups read (block totals, the unit's sum, counters) is written and read with
-    // agent-scope accesses, which go to the level of the memory hierarchy all compute units share; ordering
-    // then only needs this wave's own stores to have completed, not a write-back of the whole L2.
-    uint32_t *ucnt = FUSED ? sync + kUnitBase + kUnitStride * ((int64_t)lh * tab.n + p) : nullptr;
-    if (w == 0) {
-        if (g == 0) {
-#pragma unroll
-            for (int e = 0; e < 8; ++e) agent_store(bsum_unit + (int64_t)ublk * D + c * 8 + e, Bs[e]);
-        }
-        if (FUSED) {
-            wait_own_accesses();
-            if (lane == 0) {
-                const uint32_t arrived = __hip_atomic_fetch_add(ucnt, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                s_last = arrived == (uint32_t)unblk - 1u ? 1 : 0;
-            }
-        }
-    }
-
-    // ---- stable anchor: the workgroup that completes the unit adds the block totals up right away ----
-    // (before its own window loop, so that the sum is ready long before anybody needs it)
     float *S_unit = ssum + ((int64_t)lh * tab.n + p) * D;
-    const __amdgpu_buffer_rsrc_t srs = __builtin_amdgcn_make_buffer_rsrc(S_unit, 0, D * 4, 0x00020000);
-    if (FUSED) __syncthreads();                                       // s_last is known; lds_T is free again
-    if (FUSED && s_last) {                                            // uniform over the workgroup
-        // thread = (slice, 4 dims): slice s adds blocks s, s + NS, s + 2 NS, ... with several loads in
-        // flight; the slices are then added in order.  The order depends on the shape only.
-        constexpr int VPR = D / 4, NS = 64 * NW / VPR;
+    if (FUSED) {
+        // One wave stores the block total: vector memory instructions complete in order as far as the
+        // compiler can rely on, so the wave that issues the stores waits for them at its next load; the
+        // other waves do not.  The duty rotates with the block index.
         const __amdgpu_buffer_rsrc_t brs = __builtin_amdgcn_make_buffer_rsrc(bsum_unit, 0, unblk * D * 4, 0x00020000);
-        const int vec = threadIdx.x % VPR, slice = threadIdx.x / VPR;
-        float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-        for (int bb = slice; bb < unblk; bb += 4 * NS) {
-            float4 v[4];
-#pragma unroll
-            for (int i = 0; i < 4; ++i)                               // blocks past the end read as zeros
-                v[i] = agent_load16(brs, (bb + i * NS) * D * 4 + vec * 16);
-#pragma unroll
-            for (int i = 0; i < 4; ++i) { acc.x += v[i].x; acc.y += v[i].y; acc.z += v[i].z; acc.w += v[i].w; }
+        if (w == blk % NW && g == 0) {
+            const int off = ((blk - tab.blk_off[p]) * D + c * 8) * 4;
+            agent_store16(brs, off, Bs[0], Bs[1], Bs[2], Bs[3]);
+            agent_store16(brs, off + 16, Bs[4], Bs[5], Bs[6], Bs[7]);
         }
-        float *part = &lds_T[0][0][0];                                // NS * D floats fit (see the static_assert)
-        static_assert(NS * D <= NW * SG * D, "partial sums of the unit do not fit the LDS scratch");
-        reinterpret_cast<float4 *>(part)[slice * VPR + vec] = acc;
-        __syncthreads();
-        if (threadIdx.x < VPR) {
+        if (blk == tab.blk_off[p + 1] - 1) {                          // uniform: this workgroup adds the unit up
+            // thread = (slice, 4 dims): slice s adds blocks s, s + NS, s + 2 NS, ... , KB of them in flight at
+            // a time; the slices are then added in order.  The order depends on the shape only.
+            constexpr int VPR = D / 4, NS = 64 * NW / VPR, KB = 8;
+            const int vec = threadIdx.x % VPR, slice = threadIdx.x / VPR;
             float4 tot = make_float4(0.f, 0.f, 0.f, 0.f);
+            uint32_t spins = 0;
+            for (int b0 = slice; b0 < unblk; b0 += KB * NS) {         // same trip count for the lanes of a wave
+                u32x4 v[KB];
+                for (;;) {
+                    bool ok = true;
 #pragma unroll
-            for (int sl = 0; sl < NS; ++sl) {
-                const float4 v = reinterpret_cast<const float4 *>(part)[sl * VPR + vec];
-                tot.x += v.x; tot.y += v.y; tot.z += v.z; tot.w += v.w;
+                    for (int i = 0; i < KB; ++i) {                    // blocks past the end read as zeros
+                        v[i] = agent_load16(brs, ((b0 + i * NS) * D + vec * 4) * 4);
+                        ok = ok && all_written(v[i]);
+                    }
+                    if (__all(ok)) break;
+                    if (++spins > kSpinLimit) {
+                        if (lane == 0) atomicAdd(sync + kTimeoutWord, 1u);
+                        break;
+                    }
+                    __builtin_amdgcn_s_sleep(8);
+                }
+#pragma unroll
+                for (int i = 0; i < KB; ++i) {
+                    tot.x += __uint_as_float(v[i].x); tot.y += __uint_as_float(v[i].y);
+                    tot.z += __uint_as_float(v[i].z); tot.w += __uint_as_float(v[i].w);
+                }
             }
-            agent_store16(srs, vec * 16, tot);
-            wait_own_accesses();
-            if (threadIdx.x == 0) __hip_atomic_store(ucnt + 32, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            float *part = &lds_T[0][0][0];                            // NS * D floats fit (see the static_assert)
+            static_assert(NS * D <= NW * SG * D, "partial sums of the unit do not fit the LDS scratch");
+            __syncthreads();                                          // everybody is done with lds_T
+            reinterpret_cast<float4 *>(part)[slice * VPR + vec] = tot;
+            __syncthreads();
+            if (threadIdx.x < VPR) {
+                float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+                for (int sl = 0; sl < NS; ++sl) {
+                    const float4 q = reinterpret_cast<const float4 *>(part)[sl * VPR + vec];
+                    t.x += q.x; t.y += q.y; t.z += q.z; t.w += q.w;
+                }
+                const __amdgpu_buffer_rsrc_t srs = __builtin_amdgcn_make_buffer_rsrc(S_unit, 0, D * 4, 0x00020000);
+                agent_store16(srs, vec * 16, t.x, t.y, t.z, t.w);
+            }
         }
+    } else if (w == 0 && g == 0) {
+        store8(bsum + ((int64_t)lh * nblk + blk) * D + c * 8, Bs);
     }
 
     // ---- slide the window over this lane's tokens: current-memory dots ----
-    // Four rows per step: their leaving rows (same lane position, previous chunk) are loaded one step
-    // ahead; the per-lane partial dots of the four rows enter the transposing butterfly.
+    // Four rows per step; a leaving row (same lane position, previous chunk) is loaded four rows ahead; the per-lane partial dots of the four rows enter the transposing butterfly.
     float wd_m = 0.f, wn_m = 1.f;
     {
         StreamReduce<LPR> red_wd, red_wn;
 #pragma unroll
         for (int j = 0; j < TPT; ++j) forget(raw[j]);
-        u32x4 pnext[4];
+        u32x4 pl[4];                                                  // leaving rows, four rows ahead
 #pragma unroll
-        for (int i = 0; i < 4; ++i) pnext[i] = row_load(rsrc, lane_off + (i - 64) * kRowBytes);
+        for (int i = 0; i < 4; ++i) pl[i] = row_load(rsrc, lane_off + (i - 64) * kRowBytes);
 #pragma unroll
         for (int s = 0; s < NST; ++s) {
-            u32x4 pcur[4];
-#pragma unroll
-            for (int i = 0; i < 4; ++i) pcur[i] = pnext[i];
-            if (s + 1 < NST) {                                        // re-load the next step's leaving rows
-#pragma unroll
-                for (int i = 0; i < 4; ++i) pnext[i] = row_load(rsrc, lane_off + (4 * s + 4 + i - 64) * kRowBytes);
-            }
             const float4 r4 = *reinterpret_cast<const float4 *>(&lds_rn[1 + w][g * TPT + 4 * s]);
             const float4 q4 = *reinterpret_cast<const float4 *>(&lds_rn[w][g * TPT + 4 * s]);
             const float rr[4] = {r4.x, r4.y, r4.z, r4.w};
@@ -528,7 +531,8 @@ void scan_kernel(const uint16_t *__restrict__ keys, PromptTab tab, float *__rest
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 float kp[8], k[8];
-                unpack8(pcur[i], kp);
+                unpack8(pl[i], kp);
+                if (s + 1 < NST) pl[i] = row_load(rsrc, lane_off + (4 * s + 4 + i - 64) * kRowBytes);
                 unpack8(raw[4 * s + i], k);
                 float wd = 0.f, wn = 0.f;
 #pragma unroll
@@ -539,6 +543,7 @@ void scan_kernel(const uint16_t *__restrict__ keys, PromptTab tab, float *__rest
                     wn = fmaf(W[e], W[e], wn);
                 }
                 pw[i] = wd; pn[i] = wn;
+                __builtin_amdgcn_sched_barrier(0);                    // one row at a time
             }
             if (s == 0) { red_wd.template push<0>(pw, wd_m); red_wn.template push<0>(pn, wn_m); }
             if (s == 1) { red_wd.template push<1>(pw, wd_m); red_wn.template push<1>(pn, wn_m); }
@@ -557,24 +562,38 @@ void scan_kernel(const uint16_t *__restrict__ keys, PromptTab tab, float *__rest
     float S[8];
     float ssq = 1.f;
     if (FUSED) {
-        if (w == 0) {                                                 // one wave polls, the others sit at the barrier
+        if (w == 0) {                                                 // LPR lanes poll, the other waves sit at the barrier
+            const __amdgpu_buffer_rsrc_t srs = __builtin_amdgcn_make_buffer_rsrc(S_unit, 0, D * 4, 0x00020000);
+            u32x4 v0, v1;
             uint32_t spins = 0;
-            while (__hip_atomic_load(ucnt + 32, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0u) {
+            for (;;) {
+                bool ok = true;
+                if (lane < LPR) {
+                    v0 = agent_load16(srs, lane * 32);
+                    v1 = agent_load16(srs, lane * 32 + 16);
+                    ok = all_written(v0) && all_written(v1);
+                }
+                if (__all(ok)) break;
                 if (++spins > kSpinLimit) {
                     if (lane == 0) atomicAdd(sync + kTimeoutWord, 1u);
                     break;
                 }
-                __builtin_amdgcn_s_sleep(16);
+                __builtin_amdgcn_s_sleep(8);
+            }
+            if (lane < LPR) {
+                *reinterpret_cast<u32x4 *>(&lds_S[lane * 8]) = v0;
+                *reinterpret_cast<u32x4 *>(&lds_S[lane * 8 + 4]) = v1;
             }
         }
         __syncthreads();
-        const float4 s0 = agent_load16(srs, c * 32), s1 = agent_load16(srs, c * 32 + 16);
-        S[0] = s0.x; S[1] = s0.y; S[2] = s0.z; S[3] = s0.w; S[4] = s1.x; S[5] = s1.y; S[6] = s1.z; S[7] = s1.w;
+        load8(&lds_S[c * 8], S);
         ssq = 0.f;
 #pragma unroll
         for (int e = 0; e < 8; ++e) ssq = fmaf(S[e], S[e], ssq);
         ssq = row_sum<LPR>(ssq);
     }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) asm volatile("" : "+v"(Bs[e]));
 #pragma unroll
     for (int j = 0; j < TPT; ++j) forget(raw[j]);
     float bd[TPT], sd[TPT];
@@ -600,10 +619,11 @@ void scan_kernel(const uint16_t *__restrict__ keys, PromptTab tab, float *__rest
     }
 }
 
-__global__ void zero_kernel(uint32_t *p, int n)
+// 16-byte fill, grid-stride
+__global__ __launch_bounds__(256) void fill_kernel(uint4 *p, size_t n16, uint32_t value)
 {
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) p[i] = 0u;
+    const uint4 v = make_uint4(value, value, value, value);
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += (size_t)gridDim.x * blockDim.x) p[i] = v;
 }
 
 // grid (prompts, L*H): stable anchor (up to length) = sum of the prompt's block totals, in block order
@@ -682,7 +702,6 @@ template <int D, int NW, bool FUSED> int resident_workgroups()
     return cached;
 }
 
-int sync_words(int LH, const PromptTab &tab) { return kUnitBase + kUnitStride * LH * tab.n; }
 
 template <int D, int NW>
 hipError_t run_nw(const uint16_t *keys, int LH, const PromptTab &tab, float *a_raw, float *bsum, float *ssum,
@@ -693,8 +712,11 @@ hipError_t run_nw(const uint16_t *keys, int LH, const PromptTab &tab, float *a_r
     // fused only if the chip can hold two units' worth of workgroups at once (see the header comment)
     const bool fused = allow_fused && 2 * max_unit_blocks <= resident_workgroups<D, NW, true>();
     if (fused) {
-        const int words = sync_words(LH, tab);
-        zero_kernel<<<(words + 255) / 256, 256, 0, st>>>((uint32_t *)sync_area, words);
+        // tickets and timeouts start at zero, block totals and unit sums as "unwritten"
+        const size_t nb = (size_t)LH * tab.blk_off[tab.n] * D / 4, ns = (size_t)LH * tab.n * D / 4;
+        fill_kernel<<<1, 256, 0, st>>>((uint4 *)sync_area, kSyncWords / 4, 0u);
+        fill_kernel<<<(unsigned)min((nb + 255) / 256, (size_t)2048), 256, 0, st>>>((uint4 *)bsum, nb, kUnwritten);
+        fill_kernel<<<(unsigned)min((ns + 255) / 256, (size_t)2048), 256, 0, st>>>((uint4 *)ssum, ns, kUnwritten);
         prof.begin(NKV_KERNEL_SCAN, st);
         launch_scan<D, NW, true>(keys, LH, tab, a_raw, bsum, ssum, (uint32_t *)sync_area, st);
         prof.end(NKV_KERNEL_SCAN, st);
@@ -732,7 +754,7 @@ bool fast_score_supported(int dtype, int d, int window, const PromptTab &tab)
     return true;
 }
 
-size_t fast_score_sync_bytes(int LH, const PromptTab &tab) { return (size_t)sync_words(LH, tab) * 4; }
+size_t fast_score_sync_bytes() { return (size_t)kSyncWords * 4; }
 
 hipError_t launch_score_fast(const void *keys, int LH, int d, const PromptTab &tab, float *a_raw, float *bsum,
                              float *ssum, void *sync_area, bool allow_fused, const Prof &prof, hipStream_t st)
