@@ -338,12 +338,9 @@ void scan_kernel(const uint16_t *__restrict__ keys, PromptTab tab, float *__rest
     const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<uint16_t *>(keys) + row0 * D, 0, N * kRowBytes, 0x00020000);
     const int lane_off = t0 * kRowBytes + c * 16;
-    u32x4 raw[TPT], hraw[HT];
+    u32x4 raw[TPT];
 #pragma unroll
     for (int j = 0; j < TPT; ++j) raw[j] = row_load(rsrc, lane_off + j * kRowBytes);
-    const int halo_off = (blk_lo - 64 + g * TPT + HT * w) * kRowBytes + c * 16;
-#pragma unroll
-    for (int jj = 0; jj < HT; ++jj) hraw[jj] = row_load(rsrc, halo_off + jj * kRowBytes);
 
     // ---- norms: one token per lane (lane (g, c) reports token g*TPT + c = lane of the chunk) ----
     float rn_m, kn_m;
@@ -356,23 +353,7 @@ void scan_kernel(const uint16_t *__restrict__ keys, PromptTab tab, float *__rest
         kn_m = ss_m < 1e-24f ? sqrtf(ss_m) * 1e12f : 1.f;             // ||k_hat|| of this lane's own token
         lds_rn[1 + w][lane] = rn_m;
     }
-    // ---- halo share: norms and partial sums ----
     float T[8];
-#pragma unroll
-    for (int e = 0; e < 8; ++e) T[e] = 0.f;
-#pragma unroll
-    for (int jj = 0; jj < HT; ++jj) {
-        const float ssh = row_sum<LPR>(sumsq8_for_dpp(hraw[jj]));
-        const int q = HT * w + jj;
-        const bool ok = q < TPT && blk_lo - 64 + g * TPT + q >= 0;
-        const float r = ok ? inv_norm(ssh) : 0.f;
-        float k[8];
-        unpack8(hraw[jj], k);
-#pragma unroll
-        for (int e = 0; e < 8; ++e) T[e] = fmaf(r, k[e], T[e]);
-        if (c == jj && q < TPT) lds_rn[0][g * TPT + q] = r;
-    }
-    store8(&lds_Th[w][g][c * 8], T);
     // ---- partial sums of the chunk: the row's 1/||k|| comes back from LDS (same wave: in order) ----
 #pragma unroll
     for (int e = 0; e < 8; ++e) T[e] = 0.f;
@@ -402,18 +383,9 @@ void scan_kernel(const uint16_t *__restrict__ keys, PromptTab tab, float *__rest
         for (int gg = 0; gg < SG; ++gg) {
             float cv[8], pv[8];
             load8(&lds_T[w][gg][c * 8], cv);
-            if (w == 0) {
+            if (w == 0) {                                             // the halo's share is added further down
 #pragma unroll
                 for (int e = 0; e < 8; ++e) pv[e] = 0.f;
-                if (gg >= g) {
-#pragma unroll
-                    for (int ww = 0; ww < NW; ++ww) {
-                        float hv[8];
-                        load8(&lds_Th[ww][gg][c * 8], hv);
-#pragma unroll
-                        for (int e = 0; e < 8; ++e) pv[e] += hv[e];
-                    }
-                }
             } else {
                 load8(&lds_T[w - 1][gg][c * 8], pv);
             }
@@ -503,17 +475,56 @@ void scan_kernel(const uint16_t *__restrict__ keys, PromptTab tab, float *__rest
                     const float4 q = reinterpret_cast<const float4 *>(part)[sl * VPR + vec];
                     t.x += q.x; t.y += q.y; t.z += q.z; t.w += q.w;
                 }
-                const __amdgpu_buffer_rsrc_t srs = __builtin_amdgcn_make_buffer_rsrc(S_unit, 0, D * 4, 0x00020000);
-                agent_store16(srs, vec * 16, t.x, t.y, t.z, t.w);
+                const __amdgpu_buffer_rsrc_t out = __builtin_amdgcn_make_buffer_rsrc(S_unit, 0, D * 4, 0x00020000);
+                agent_store16(out, vec * 16, t.x, t.y, t.z, t.w);
             }
         }
     } else if (w == 0 && g == 0) {
         store8(bsum + ((int64_t)lh * nblk + blk) * D + c * 8, Bs);
     }
 
+    // ---- halo share: norms and partial sums (after the block total is on its way: only the window needs
+    // them; the rows were fetched by the previous block's workgroup a moment ago, on the same die) ----
+    u32x4 hraw[HT];
+    const int halo_off = (blk_lo - 64 + g * TPT + HT * w) * kRowBytes + c * 16;
+#pragma unroll
+    for (int jj = 0; jj < HT; ++jj) hraw[jj] = row_load(rsrc, halo_off + jj * kRowBytes);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) T[e] = 0.f;
+#pragma unroll
+    for (int jj = 0; jj < HT; ++jj) {
+        const float ssh = row_sum<LPR>(sumsq8_for_dpp(hraw[jj]));
+        const int q = HT * w + jj;
+        const bool ok = q < TPT && blk_lo - 64 + g * TPT + q >= 0;
+        const float r = ok ? inv_norm(ssh) : 0.f;
+        float k[8];
+        unpack8(hraw[jj], k);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) T[e] = fmaf(r, k[e], T[e]);
+        if (c == jj && q < TPT) lds_rn[0][g * TPT + q] = r;
+    }
+    store8(&lds_Th[w][g][c * 8], T);
+    __syncthreads();
+    if (w == 0) {                                                     // previous chunk of wave 0 = the halo chunk
+#pragma unroll
+        for (int gg = 0; gg < SG; ++gg) {
+            if (gg >= g) {
+#pragma unroll
+                for (int ww = 0; ww < NW; ++ww) {
+                    float hv[8];
+                    load8(&lds_Th[ww][gg][c * 8], hv);
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) W[e] += hv[e];
+                }
+            }
+        }
+    }
+
     // ---- slide the window over this lane's tokens: current-memory dots ----
     // Four rows per step; a leaving row (same lane position, previous chunk) is loaded four rows ahead; the per-lane partial dots of the four rows enter the transposing butterfly.
     float wd_m = 0.f, wn_m = 1.f;
+    const __amdgpu_buffer_rsrc_t srs = __builtin_amdgcn_make_buffer_rsrc(S_unit, 0, D * 4, 0x00020000);
+    u32x4 sv0 = {kUnwritten, kUnwritten, kUnwritten, kUnwritten}, sv1 = sv0;
     {
         StreamReduce<LPR> red_wd, red_wn;
 #pragma unroll
@@ -527,6 +538,10 @@ void scan_kernel(const uint16_t *__restrict__ keys, PromptTab tab, float *__rest
             const float4 q4 = *reinterpret_cast<const float4 *>(&lds_rn[w][g * TPT + 4 * s]);
             const float rr[4] = {r4.x, r4.y, r4.z, r4.w};
             const float rp[4] = {q4.x, q4.y, q4.z, q4.w};             // 0 where the leaving token does not exist
+            if (FUSED && s == NST - 1 && w == 0 && lane < LPR) {      // first look at the unit sum, a step early
+                sv0 = agent_load16(srs, lane * 32);
+                sv1 = agent_load16(srs, lane * 32 + 16);
+            }
             float pw[4], pn[4];
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
@@ -563,26 +578,23 @@ void scan_kernel(const uint16_t *__restrict__ keys, PromptTab tab, float *__rest
     float ssq = 1.f;
     if (FUSED) {
         if (w == 0) {                                                 // LPR lanes poll, the other waves sit at the barrier
-            const __amdgpu_buffer_rsrc_t srs = __builtin_amdgcn_make_buffer_rsrc(S_unit, 0, D * 4, 0x00020000);
-            u32x4 v0, v1;
             uint32_t spins = 0;
             for (;;) {
-                bool ok = true;
-                if (lane < LPR) {
-                    v0 = agent_load16(srs, lane * 32);
-                    v1 = agent_load16(srs, lane * 32 + 16);
-                    ok = all_written(v0) && all_written(v1);
-                }
+                const bool ok = lane >= LPR || (all_written(sv0) && all_written(sv1));
                 if (__all(ok)) break;
                 if (++spins > kSpinLimit) {
                     if (lane == 0) atomicAdd(sync + kTimeoutWord, 1u);
                     break;
                 }
                 __builtin_amdgcn_s_sleep(8);
+                if (lane < LPR) {
+                    sv0 = agent_load16(srs, lane * 32);
+                    sv1 = agent_load16(srs, lane * 32 + 16);
+                }
             }
             if (lane < LPR) {
-                *reinterpret_cast<u32x4 *>(&lds_S[lane * 8]) = v0;
-                *reinterpret_cast<u32x4 *>(&lds_S[lane * 8 + 4]) = v1;
+                *reinterpret_cast<u32x4 *>(&lds_S[lane * 8]) = sv0;
+                *reinterpret_cast<u32x4 *>(&lds_S[lane * 8 + 4]) = sv1;
             }
         }
         __syncthreads();
