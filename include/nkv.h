@@ -54,8 +54,10 @@ enum { NKV_GATE_SURPRISE = 0, NKV_GATE_ONLY_AVERAGE = 1, NKV_GATE_ONLY_MAX = 2 }
 enum { NKV_SURPRISE_NORMALISED = 0, NKV_SURPRISE_RAW = 1 };
 enum {
     NKV_FLAG_GENERIC_KERNELS = 1u,    /* force the shape-generic scoring kernels                            */
-    NKV_FLAG_TWO_PASS_STABLE = 2u     /* streaming kernels: compute the stable anomaly in a second pass     */
+    NKV_FLAG_TWO_PASS_STABLE = 2u,    /* streaming kernels: compute the stable anomaly in a second pass     */
                                       /* over the keys instead of inside the single fused pass             */
+    NKV_FLAG_DEFER_STABLE = 4u        /* streaming kernels, fused pass: no workgroup waits for its unit's   */
+                                      /* sum; every block takes the deferred route (exercises that route)   */
 };
 /* Kernels a caller can ask to have timed, see nkv_params.prof_start. */
 enum {

@@ -74,7 +74,7 @@ ScoreWs score_ws(const nkv_shape *s, const PromptTab &tab, bool with_a_raw)
     const size_t LH = (size_t)s->L * s->H;
     ScoreWs w;
     size_t off = 0;
-    w.sync = off;   off += align_up(fast_score_sync_bytes());
+    w.sync = off;   off += align_up(fast_score_sync_bytes((int)LH, tab));
     w.a_raw = off;  off += with_a_raw ? align_up(3 * rows * 4) : 0;
     w.rnorm = off;  off += align_up(rows * 4);
     w.bsum = off;   off += align_up(LH * tab.blk_off[tab.n] * s->d * 4);
@@ -99,7 +99,9 @@ int run_raw(const void *keys, const nkv_shape *s, const nkv_params *p, const Pro
     hipError_t e;
     if (!(p->flags & NKV_FLAG_GENERIC_KERNELS) && fast_score_supported(s->dtype, s->d, p->window, tab))
         e = launch_score_fast(keys, LH, s->d, tab, a_raw, (float *)(ws + lay.bsum), (float *)(ws + lay.ssum),
-                              ws + lay.sync, !(p->flags & NKV_FLAG_TWO_PASS_STABLE), prof, st);
+                              ws + lay.sync,
+                              (p->flags & NKV_FLAG_TWO_PASS_STABLE) ? kScanTwoPass
+                              : (p->flags & NKV_FLAG_DEFER_STABLE)  ? kScanDeferAll : kScanFused, prof, st);
     else
         e = launch_score_generic(keys, s->dtype, LH, s->d, p->window, tab, a_raw, (float *)(ws + lay.rnorm),
                                  (float *)(ws + lay.bsum), (float *)(ws + lay.ssum), prof, st);

@@ -40,13 +40,18 @@
 //             and the unit sums live in memory that is filled with a NaN bit pattern before the launch, so
 //             a 32-bit word that has been written is recognisable by itself and no flags, counters or
 //             waits for completed stores are needed.  Each workgroup stores its block total (agent scope)
-//             and goes on to its window loop.  The workgroup that holds the unit's last block polls all
-//             block totals of the unit right after storing its own, adds them up in block order and
-//             stores the unit sum.  After its window loop every workgroup polls the unit sum with its
-//             chunk still in registers, then computes a_s.  A waiting workgroup only ever waits for
-//             workgroups of the same unit, all of which have started or can start as long as the chip can
-//             hold one unit's workgroups at once -- the host checks that before choosing this path.
-//             Waits are bounded; a timeout is recorded in the sync area and the kernel still ends.
+//             and goes on to its window loop.  Every unit has one more ticket, queued right behind the
+//             unit's blocks on one die: the workgroup that draws it does nothing but poll the unit's block
+//             totals, add them up in block order and store the unit sum.  After its window loop every
+//             block's workgroup polls the unit sum with its chunk still in registers, then computes a_s.
+//             Nobody waits without bound: a block's workgroup that does not find the unit sum within a
+//             few dozen polls puts its block on a list and leaves without a_s, and a small kernel
+//             afterwards computes a_s of the listed blocks from a second read of their keys with the same
+//             arithmetic, so the result does not depend on who computed it.  The summing workgroups wait
+//             only for block totals, which are stored before any waiting.  So the path is correct
+//             whatever the order and placement in which the hardware starts workgroups; that every die's
+//             window of resident workgroups normally covers a unit's blocks (the host checks it) only
+//             keeps the list short.
 //   2-pass  : block totals go to memory, ssum_kernel adds them up and stable_kernel re-reads the keys
 //             (any prompt length).
 #include "nkv_device.h"
@@ -263,23 +268,32 @@ __device__ __forceinline__ bool all_written(const u32x4 &v)
 }
 
 constexpr int kMaxChunks = 4;                    // chunks per block: block size <= 256
-constexpr uint32_t kSpinLimit = 1u << 22;        // ~1 s of polling before a wait gives up
+constexpr uint32_t kSpinLimit = 1u << 22;        // polls of a summing workgroup before it gives up (~seconds)
+constexpr int kPollLimit = 48;                   // polls of a block's workgroup before it defers its a_s (~0.1 ms)
 constexpr int kDies = 8;                         // ticket counters (one per XCD of an MI355X)
 
-// Sync area of the fused path (all zero before the launch), in 32-bit words: ticket counters, timeouts.
+// Sync area of the fused path (the first kSyncWords are zero before the launch), in 32-bit words.
 constexpr int kTicketStride = 32;                // one 128-byte line per die's ticket counter
-constexpr int kTimeoutWord = kDies * kTicketStride;
-constexpr int kSyncWords = kTimeoutWord + 32;
+constexpr int kTimeoutWord = kDies * kTicketStride;      // summing workgroups that gave up (never, in practice)
+constexpr int kDeferCountWord = kTimeoutWord + 1;        // blocks on the list
+constexpr int kSyncWords = kTimeoutWord + 32;            // the list (one word per block) follows
 
 // Blocks [seg_lo(x), seg_lo(x + 1)) of every (layer, head) belong to die x.
 __device__ __forceinline__ int seg_lo(int nblk, int x) { return (int)(((int64_t)x * nblk) / kDies); }
+
+// Queue of die x: for lh = 0, 1, ...: the len blocks of its segment, then -- if lh % kDies == x -- one
+// "add the unit up" item per prompt.  First ticket of lh in that queue:
+__device__ __forceinline__ uint32_t queue_start(int lh, int len, int n_prompts, int x)
+{
+    return (uint32_t)lh * (uint32_t)len + (uint32_t)n_prompts * ((uint32_t)(lh + kDies - 1 - x) / kDies);
+}
 
 // NW wavefronts = chunks per block.  grid: one workgroup per (layer*head, block), 1-D.
 template <int D, int NW, bool FUSED>
 __global__ __launch_bounds__(64 * NW, 3)
 void scan_kernel(const uint16_t *__restrict__ keys, PromptTab tab, float *__restrict__ a_raw,
                  float *__restrict__ bsum, float *__restrict__ ssum, uint32_t *__restrict__ sync, int LH,
-                 int64_t rows)
+                 int64_t rows, int poll_limit)
 {
     constexpr int LPR = D / 8, SG = 64 / LPR, TPT = LPR;
     constexpr int HT = (TPT + NW - 1) / NW;                           // halo tokens per lane
@@ -289,7 +303,7 @@ void scan_kernel(const uint16_t *__restrict__ keys, PromptTab tab, float *__rest
     __shared__ float lds_Th[NW][SG][D];                               // partial sums of the halo chunk
     __shared__ float lds_C[NW][D];                                    // chunk totals
     __shared__ float lds_S[D];                                        // the unit's sum, once complete
-    __shared__ int s_lh, s_blk;
+    __shared__ int s_lh, s_blk, s_sum, s_have;
 
     const int nblk = tab.blk_off[tab.n];
     int lh, blk;
@@ -297,25 +311,86 @@ void scan_kernel(const uint16_t *__restrict__ keys, PromptTab tab, float *__rest
         // take a ticket from this die's counter, or from the next die's that still has work
         if (threadIdx.x == 0) {
             const int die = (int)(__builtin_amdgcn_s_getreg((3 << 11) | 20) & (kDies - 1));   // XCC_ID[3:0]
-            int got_lh = -1, got_blk = 0;
+            int got_lh = -1, got_blk = 0, got_sum = -1;
             for (int i = 0; i < kDies && got_lh < 0; ++i) {
                 const int x = (die + i) & (kDies - 1);
                 const int lo = seg_lo(nblk, x), len = seg_lo(nblk, x + 1) - lo;
-                if (len == 0) continue;
+                const uint32_t items = queue_start(LH, len, tab.n, x);
+                if (items == 0u) continue;
                 const uint32_t t = __hip_atomic_fetch_add(sync + x * kTicketStride, 1u, __ATOMIC_RELAXED,
                                                           __HIP_MEMORY_SCOPE_AGENT);
-                if (t < (uint32_t)len * (uint32_t)LH) {
-                    got_lh = (int)(t / (uint32_t)len);
-                    got_blk = lo + (int)(t % (uint32_t)len);
+                if (t < items) {
+                    // lh of ticket t: a first guess from the average number of items per lh, then exact
+                    int l = min(LH - 1, (int)(t * (uint32_t)kDies / ((uint32_t)kDies * len + tab.n)));
+                    while (l > 0 && queue_start(l, len, tab.n, x) > t) --l;
+                    while (l + 1 < LH && queue_start(l + 1, len, tab.n, x) <= t) ++l;
+                    const int r = (int)(t - queue_start(l, len, tab.n, x));
+                    got_lh = l;
+                    if (r < len) got_blk = lo + r;
+                    else got_sum = r - len;                           // prompt whose unit sum is to be formed
                 }
             }
             s_lh = got_lh;
             s_blk = got_blk;
+            s_sum = got_sum;
         }
         __syncthreads();
         lh = s_lh;
         blk = s_blk;
-        if (lh < 0) return;                                           // more workgroups than blocks: cannot happen
+        if (lh < 0) return;                                           // more workgroups than tickets: cannot happen
+        if (s_sum >= 0) {                                             // uniform: this workgroup adds a unit up
+            // thread = (slice, 4 dims): slice s adds blocks s, s + NS, s + 2 NS, ..., KB of them per round;
+            // the slices are then added in order.  The order depends on the shape only.  A thread keeps
+            // polling only the words it has not seen written yet.
+            const int p = s_sum;
+            const int unblk = tab.blk_off[p + 1] - tab.blk_off[p];
+            const __amdgpu_buffer_rsrc_t brs = __builtin_amdgcn_make_buffer_rsrc(
+                bsum + ((int64_t)lh * nblk + tab.blk_off[p]) * D, 0, unblk * D * 4, 0x00020000);
+            constexpr int VPR = D / 4, NS = 64 * NW / VPR, KB = 16;
+            const int vec = threadIdx.x % VPR, slice = threadIdx.x / VPR;
+            float4 tot = make_float4(0.f, 0.f, 0.f, 0.f);
+            uint32_t spins = 0;
+            for (int b0 = slice; b0 < unblk; b0 += KB * NS) {
+                u32x4 v[KB];
+#pragma unroll
+                for (int i = 0; i < KB; ++i) v[i] = u32x4{kUnwritten, kUnwritten, kUnwritten, kUnwritten};
+                for (;;) {
+                    bool ok = true;
+#pragma unroll
+                    for (int i = 0; i < KB; ++i)                      // blocks past the end read as zeros
+                        if (!all_written(v[i])) v[i] = agent_load16(brs, ((b0 + i * NS) * D + vec * 4) * 4);
+#pragma unroll
+                    for (int i = 0; i < KB; ++i) ok = ok && all_written(v[i]);
+                    if (ok) break;
+                    if (++spins > kSpinLimit) {
+                        atomicAdd(sync + kTimeoutWord, 1u);
+                        break;
+                    }
+                    __builtin_amdgcn_s_sleep(4);
+                }
+#pragma unroll
+                for (int i = 0; i < KB; ++i) {
+                    tot.x += __uint_as_float(v[i].x); tot.y += __uint_as_float(v[i].y);
+                    tot.z += __uint_as_float(v[i].z); tot.w += __uint_as_float(v[i].w);
+                }
+            }
+            float *part = &lds_T[0][0][0];                            // NS * D floats fit (see the static_assert)
+            static_assert(NS * D <= NW * SG * D, "partial sums of the unit do not fit the LDS scratch");
+            reinterpret_cast<float4 *>(part)[slice * VPR + vec] = tot;
+            __syncthreads();
+            if (threadIdx.x < VPR) {
+                float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+                for (int sl = 0; sl < NS; ++sl) {
+                    const float4 q = reinterpret_cast<const float4 *>(part)[sl * VPR + vec];
+                    t.x += q.x; t.y += q.y; t.z += q.z; t.w += q.w;
+                }
+                const __amdgpu_buffer_rsrc_t out = __builtin_amdgcn_make_buffer_rsrc(
+                    ssum + ((int64_t)lh * tab.n + p) * D, 0, D * 4, 0x00020000);
+                agent_store16(out, vec * 16, t.x, t.y, t.z, t.w);
+            }
+            return;
+        }
     } else {
         lh = blockIdx.x / nblk;
         blk = blockIdx.x - lh * nblk;
@@ -338,9 +413,12 @@ void scan_kernel(const uint16_t *__restrict__ keys, PromptTab tab, float *__rest
     const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<uint16_t *>(keys) + row0 * D, 0, N * kRowBytes, 0x00020000);
     const int lane_off = t0 * kRowBytes + c * 16;
-    u32x4 raw[TPT];
+    u32x4 raw[TPT], hraw[HT];
 #pragma unroll
     for (int j = 0; j < TPT; ++j) raw[j] = row_load(rsrc, lane_off + j * kRowBytes);
+    const int halo_off = (blk_lo - 64 + g * TPT + HT * w) * kRowBytes + c * 16;
+#pragma unroll
+    for (int jj = 0; jj < HT; ++jj) hraw[jj] = row_load(rsrc, halo_off + jj * kRowBytes);
 
     // ---- norms: one token per lane (lane (g, c) reports token g*TPT + c = lane of the chunk) ----
     float rn_m, kn_m;
@@ -434,61 +512,11 @@ void scan_kernel(const uint16_t *__restrict__ keys, PromptTab tab, float *__rest
             agent_store16(brs, off, Bs[0], Bs[1], Bs[2], Bs[3]);
             agent_store16(brs, off + 16, Bs[4], Bs[5], Bs[6], Bs[7]);
         }
-        if (blk == tab.blk_off[p + 1] - 1) {                          // uniform: this workgroup adds the unit up
-            // thread = (slice, 4 dims): slice s adds blocks s, s + NS, s + 2 NS, ... , KB of them in flight at
-            // a time; the slices are then added in order.  The order depends on the shape only.
-            constexpr int VPR = D / 4, NS = 64 * NW / VPR, KB = 8;
-            const int vec = threadIdx.x % VPR, slice = threadIdx.x / VPR;
-            float4 tot = make_float4(0.f, 0.f, 0.f, 0.f);
-            uint32_t spins = 0;
-            for (int b0 = slice; b0 < unblk; b0 += KB * NS) {         // same trip count for the lanes of a wave
-                u32x4 v[KB];
-                for (;;) {
-                    bool ok = true;
-#pragma unroll
-                    for (int i = 0; i < KB; ++i) {                    // blocks past the end read as zeros
-                        v[i] = agent_load16(brs, ((b0 + i * NS) * D + vec * 4) * 4);
-                        ok = ok && all_written(v[i]);
-                    }
-                    if (__all(ok)) break;
-                    if (++spins > kSpinLimit) {
-                        if (lane == 0) atomicAdd(sync + kTimeoutWord, 1u);
-                        break;
-                    }
-                    __builtin_amdgcn_s_sleep(8);
-                }
-#pragma unroll
-                for (int i = 0; i < KB; ++i) {
-                    tot.x += __uint_as_float(v[i].x); tot.y += __uint_as_float(v[i].y);
-                    tot.z += __uint_as_float(v[i].z); tot.w += __uint_as_float(v[i].w);
-                }
-            }
-            float *part = &lds_T[0][0][0];                            // NS * D floats fit (see the static_assert)
-            static_assert(NS * D <= NW * SG * D, "partial sums of the unit do not fit the LDS scratch");
-            __syncthreads();                                          // everybody is done with lds_T
-            reinterpret_cast<float4 *>(part)[slice * VPR + vec] = tot;
-            __syncthreads();
-            if (threadIdx.x < VPR) {
-                float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
-#pragma unroll
-                for (int sl = 0; sl < NS; ++sl) {
-                    const float4 q = reinterpret_cast<const float4 *>(part)[sl * VPR + vec];
-                    t.x += q.x; t.y += q.y; t.z += q.z; t.w += q.w;
-                }
-                const __amdgpu_buffer_rsrc_t out = __builtin_amdgcn_make_buffer_rsrc(S_unit, 0, D * 4, 0x00020000);
-                agent_store16(out, vec * 16, t.x, t.y, t.z, t.w);
-            }
-        }
     } else if (w == 0 && g == 0) {
         store8(bsum + ((int64_t)lh * nblk + blk) * D + c * 8, Bs);
     }
 
-    // ---- halo share: norms and partial sums (after the block total is on its way: only the window needs
-    // them; the rows were fetched by the previous block's workgroup a moment ago, on the same die) ----
-    u32x4 hraw[HT];
-    const int halo_off = (blk_lo - 64 + g * TPT + HT * w) * kRowBytes + c * 16;
-#pragma unroll
-    for (int jj = 0; jj < HT; ++jj) hraw[jj] = row_load(rsrc, halo_off + jj * kRowBytes);
+    // ---- halo share: norms and partial sums (after the block total is on its way: only the window needs them) ----
 #pragma unroll
     for (int e = 0; e < 8; ++e) T[e] = 0.f;
 #pragma unroll
@@ -576,29 +604,36 @@ void scan_kernel(const uint16_t *__restrict__ keys, PromptTab tab, float *__rest
     // The unit's sum is normally long since there when a workgroup gets here.
     float S[8];
     float ssq = 1.f;
+    bool have_S = false;
     if (FUSED) {
         if (w == 0) {                                                 // LPR lanes poll, the other waves sit at the barrier
-            uint32_t spins = 0;
-            for (;;) {
+            bool got = false;
+            for (int polls = 0; poll_limit >= 0; ++polls) {           // poll_limit < 0: defer without looking
                 const bool ok = lane >= LPR || (all_written(sv0) && all_written(sv1));
-                if (__all(ok)) break;
-                if (++spins > kSpinLimit) {
-                    if (lane == 0) atomicAdd(sync + kTimeoutWord, 1u);
-                    break;
-                }
+                got = __all(ok);
+                if (got || polls >= poll_limit) break;
                 __builtin_amdgcn_s_sleep(8);
                 if (lane < LPR) {
                     sv0 = agent_load16(srs, lane * 32);
                     sv1 = agent_load16(srs, lane * 32 + 16);
                 }
             }
-            if (lane < LPR) {
+            if (got && lane < LPR) {
                 *reinterpret_cast<u32x4 *>(&lds_S[lane * 8]) = sv0;
                 *reinterpret_cast<u32x4 *>(&lds_S[lane * 8 + 4]) = sv1;
             }
+            if (lane == 0) {
+                s_have = got ? 1 : 0;
+                if (!got) sync[kSyncWords + atomicAdd(sync + kDeferCountWord, 1u)] = (uint32_t)(lh * nblk + blk);
+            }
         }
         __syncthreads();
-        load8(&lds_S[c * 8], S);
+        have_S = s_have != 0;
+        if (have_S) load8(&lds_S[c * 8], S);
+        else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) S[e] = 0.f;
+        }
         ssq = 0.f;
 #pragma unroll
         for (int e = 0; e < 8; ++e) ssq = fmaf(S[e], S[e], ssq);
@@ -625,7 +660,61 @@ void scan_kernel(const uint16_t *__restrict__ keys, PromptTab tab, float *__rest
     }
     const float bd_m = transpose_reduce<LPR>(bd);
     if (tok < blk_hi) a_raw[rows + row0 + tok] = neg_cos(rn_m * bd_m, kn_m, bsq);
-    if (FUSED) {
+    if (FUSED && have_S) {
+        const float sd_m = transpose_reduce<LPR>(sd);
+        if (tok < blk_hi) a_raw[row0 + tok] = neg_cos(rn_m * sd_m, kn_m, ssq);
+    }
+}
+
+// a_s of the blocks whose workgroups did not wait for their unit's sum.  One workgroup per listed block at a
+// time, one wave per chunk, same lane layout, same instruction sequences for the norm, the dot and the
+// cosine as scan_kernel, so the values are the ones scan_kernel would have stored.
+template <int D, int NW>
+__global__ __launch_bounds__(64 * NW) void deferred_stable_kernel(const uint16_t *__restrict__ keys, PromptTab tab,
+                                                                  const float *__restrict__ ssum,
+                                                                  const uint32_t *__restrict__ sync,
+                                                                  float *__restrict__ a_raw)
+{
+    constexpr int LPR = D / 8, TPT = LPR, kRowBytes = D * 2;
+    const int nblk = tab.blk_off[tab.n];
+    const uint32_t count = sync[kDeferCountWord];
+    const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int g = lane / LPR, c = lane % LPR;
+    for (uint32_t i = blockIdx.x; i < count; i += gridDim.x) {
+        const int id = (int)sync[kSyncWords + i], lh = id / nblk, blk = id - lh * nblk;
+        const int p = prompt_of_block(tab, blk);
+        const int b = tab.b[p], N = tab.tok_off[p + 1] - tab.tok_off[p];
+        const int blk_lo = (blk - tab.blk_off[p]) * b, blk_hi = min(blk_lo + b, N);
+        const int64_t row0 = (int64_t)lh * tab.T + tab.tok_off[p];
+        const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<uint16_t *>(keys) + row0 * D, 0, N * kRowBytes, 0x00020000);
+        const int lane_off = (blk_lo + 64 * w + g * TPT) * kRowBytes + c * 16;
+        u32x4 raw[TPT];
+#pragma unroll
+        for (int j = 0; j < TPT; ++j) raw[j] = row_load(rsrc, lane_off + j * kRowBytes);
+        float ss[TPT];
+#pragma unroll
+        for (int j = 0; j < TPT; ++j) ss[j] = sumsq8(raw[j]);
+        const float ss_m = transpose_reduce<LPR>(ss);
+        const int tok = blk_lo + 64 * w + lane;
+        const float rn_m = tok < blk_hi ? inv_norm(ss_m) : 0.f;
+        const float kn_m = ss_m < 1e-24f ? sqrtf(ss_m) * 1e12f : 1.f;
+        float S[8];
+        load8(ssum + ((int64_t)lh * tab.n + p) * D + c * 8, S);
+        float ssq = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) ssq = fmaf(S[e], S[e], ssq);
+        ssq = row_sum<LPR>(ssq);
+        float sd[TPT];
+#pragma unroll
+        for (int j = 0; j < TPT; ++j) {
+            float k[8];
+            unpack8(raw[j], k);
+            float acc = 0.f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc = fmaf(k[e], S[e], acc);
+            sd[j] = acc;
+        }
         const float sd_m = transpose_reduce<LPR>(sd);
         if (tok < blk_hi) a_raw[row0 + tok] = neg_cos(rn_m * sd_m, kn_m, ssq);
     }
@@ -693,11 +782,11 @@ __global__ __launch_bounds__(256) void stable_kernel(const uint16_t *__restrict_
 
 template <int D, int NW, bool FUSED>
 void launch_scan(const uint16_t *keys, int LH, const PromptTab &tab, float *a_raw, float *bsum, float *ssum,
-                 uint32_t *sync, hipStream_t st)
+                 uint32_t *sync, int poll_limit, hipStream_t st)
 {
     const int64_t rows = (int64_t)LH * tab.T;
-    scan_kernel<D, NW, FUSED><<<(unsigned)(tab.blk_off[tab.n] * LH), 64 * NW, 0, st>>>(keys, tab, a_raw, bsum, ssum,
-                                                                                      sync, LH, rows);
+    const unsigned groups = (unsigned)(tab.blk_off[tab.n] * LH + (FUSED ? tab.n * LH : 0));    // + one per unit sum
+    scan_kernel<D, NW, FUSED><<<groups, 64 * NW, 0, st>>>(keys, tab, a_raw, bsum, ssum, sync, LH, rows, poll_limit);
 }
 
 template <int D, int NW, bool FUSED> int resident_workgroups()
@@ -717,12 +806,15 @@ template <int D, int NW, bool FUSED> int resident_workgroups()
 
 template <int D, int NW>
 hipError_t run_nw(const uint16_t *keys, int LH, const PromptTab &tab, float *a_raw, float *bsum, float *ssum,
-                  void *sync_area, bool allow_fused, const Prof &prof, hipStream_t st)
+                  void *sync_area, int mode, const Prof &prof, hipStream_t st)
 {
     int max_unit_blocks = 0;
     for (int p = 0; p < tab.n; ++p) max_unit_blocks = max(max_unit_blocks, tab.blk_off[p + 1] - tab.blk_off[p]);
     // fused only if the chip can hold two units' worth of workgroups at once (see the header comment)
-    const bool fused = allow_fused && 2 * max_unit_blocks <= resident_workgroups<D, NW, true>();
+    // (ticket arithmetic is 32-bit: keep the number of tickets far below 2^32 / 8)
+    const int64_t tickets = (int64_t)LH * (tab.blk_off[tab.n] + tab.n);
+    const bool allow_fused = mode != kScanTwoPass, defer_all = mode == kScanDeferAll;
+    const bool fused = allow_fused && tickets < (1ll << 28) && 2 * max_unit_blocks <= resident_workgroups<D, NW, true>();
     if (fused) {
         // tickets and timeouts start at zero, block totals and unit sums as "unwritten"
         const size_t nb = (size_t)LH * tab.blk_off[tab.n] * D / 4, ns = (size_t)LH * tab.n * D / 4;
@@ -730,11 +822,14 @@ hipError_t run_nw(const uint16_t *keys, int LH, const PromptTab &tab, float *a_r
         fill_kernel<<<(unsigned)min((nb + 255) / 256, (size_t)2048), 256, 0, st>>>((uint4 *)bsum, nb, kUnwritten);
         fill_kernel<<<(unsigned)min((ns + 255) / 256, (size_t)2048), 256, 0, st>>>((uint4 *)ssum, ns, kUnwritten);
         prof.begin(NKV_KERNEL_SCAN, st);
-        launch_scan<D, NW, true>(keys, LH, tab, a_raw, bsum, ssum, (uint32_t *)sync_area, st);
+        launch_scan<D, NW, true>(keys, LH, tab, a_raw, bsum, ssum, (uint32_t *)sync_area,
+                                 defer_all ? -1 : kPollLimit, st);
         prof.end(NKV_KERNEL_SCAN, st);
+        deferred_stable_kernel<D, NW><<<defer_all ? 4096 : 256, 64 * NW, 0, st>>>(keys, tab, ssum,
+                                                                                  (const uint32_t *)sync_area, a_raw);
     } else {
         prof.begin(NKV_KERNEL_SCAN, st);
-        launch_scan<D, NW, false>(keys, LH, tab, a_raw, bsum, ssum, nullptr, st);
+        launch_scan<D, NW, false>(keys, LH, tab, a_raw, bsum, ssum, nullptr, 0, st);
         prof.end(NKV_KERNEL_SCAN, st);
         ssum_kernel<D><<<dim3(tab.n, LH), D, 0, st>>>(bsum, tab, ssum);
         stable_kernel<D><<<dim3((tab.T + 255) / 256, LH), 256, 0, st>>>(keys, tab, ssum, a_raw);
@@ -744,15 +839,15 @@ hipError_t run_nw(const uint16_t *keys, int LH, const PromptTab &tab, float *a_r
 
 template <int D>
 hipError_t run(const uint16_t *keys, int LH, const PromptTab &tab, float *a_raw, float *bsum, float *ssum,
-               void *sync_area, bool allow_fused, const Prof &prof, hipStream_t st)
+               void *sync_area, int mode, const Prof &prof, hipStream_t st)
 {
     int bmax = 0;
     for (int p = 0; p < tab.n; ++p) bmax = max(bmax, tab.b[p]);
     switch ((bmax + 63) / 64) {
-    case 1: return run_nw<D, 1>(keys, LH, tab, a_raw, bsum, ssum, sync_area, allow_fused, prof, st);
-    case 2: return run_nw<D, 2>(keys, LH, tab, a_raw, bsum, ssum, sync_area, allow_fused, prof, st);
-    case 3: return run_nw<D, 3>(keys, LH, tab, a_raw, bsum, ssum, sync_area, allow_fused, prof, st);
-    default: return run_nw<D, 4>(keys, LH, tab, a_raw, bsum, ssum, sync_area, allow_fused, prof, st);
+    case 1: return run_nw<D, 1>(keys, LH, tab, a_raw, bsum, ssum, sync_area, mode, prof, st);
+    case 2: return run_nw<D, 2>(keys, LH, tab, a_raw, bsum, ssum, sync_area, mode, prof, st);
+    case 3: return run_nw<D, 3>(keys, LH, tab, a_raw, bsum, ssum, sync_area, mode, prof, st);
+    default: return run_nw<D, 4>(keys, LH, tab, a_raw, bsum, ssum, sync_area, mode, prof, st);
     }
 }
 
@@ -766,13 +861,16 @@ bool fast_score_supported(int dtype, int d, int window, const PromptTab &tab)
     return true;
 }
 
-size_t fast_score_sync_bytes() { return (size_t)kSyncWords * 4; }
+size_t fast_score_sync_bytes(int LH, const PromptTab &tab)
+{
+    return ((size_t)kSyncWords + (size_t)LH * tab.blk_off[tab.n]) * 4;       // counters + the list of deferred blocks
+}
 
 hipError_t launch_score_fast(const void *keys, int LH, int d, const PromptTab &tab, float *a_raw, float *bsum,
-                             float *ssum, void *sync_area, bool allow_fused, const Prof &prof, hipStream_t st)
+                             float *ssum, void *sync_area, int mode, const Prof &prof, hipStream_t st)
 {
-    if (d == 128) return run<128>((const uint16_t *)keys, LH, tab, a_raw, bsum, ssum, sync_area, allow_fused, prof, st);
-    return run<64>((const uint16_t *)keys, LH, tab, a_raw, bsum, ssum, sync_area, allow_fused, prof, st);
+    if (d == 128) return run<128>((const uint16_t *)keys, LH, tab, a_raw, bsum, ssum, sync_area, mode, prof, st);
+    return run<64>((const uint16_t *)keys, LH, tab, a_raw, bsum, ssum, sync_area, mode, prof, st);
 }
 
 }  // namespace nkv

@@ -190,6 +190,7 @@ def test_generic_and_streaming_kernels_agree_with_oracle():
     K, V = _kv(w)
     compare_end_to_end(w, K, V, 0.5, params=nkv.params_default(flags=nkv.FLAG_GENERIC_KERNELS), label="generic")
     compare_end_to_end(w, K, V, 0.5, params=nkv.params_default(flags=nkv.FLAG_TWO_PASS_STABLE), label="two-pass")
+    compare_end_to_end(w, K, V, 0.5, params=nkv.params_default(flags=nkv.FLAG_DEFER_STABLE), label="deferred")
     compare_end_to_end(w, K, V, 0.5, label="default")
 
 
@@ -249,3 +250,25 @@ def test_deterministic_and_untouched_neighbours():
         results.append([t.clone() for t in (scores, pk.view(torch.int16), pv.view(torch.int16), idx, kph, off)])
     for a, b in zip(*results):
         assert torch.equal(a, b)
+
+
+def test_deferred_stable_route_gives_the_same_bits():
+    """A block whose workgroup does not wait for its unit's sum gets its stable anomaly from a later kernel;
+    which of the two routes a block takes depends on timing, so both must produce identical scores."""
+    for name, L, H, d, lens in (("defer128", 2, 3, 128, [3000, 500, 129]), ("defer64", 1, 4, 64, [2500, 64])):
+        w = nkv_inputs.small_workload(name, L, H, d, lens)
+        K, V = _kv(w)
+        a, _ = run_gpu(w, K, V, 0.6)
+        b, _ = run_gpu(w, K, V, 0.6, params=nkv.params_default(flags=nkv.FLAG_DEFER_STABLE))
+        assert torch.equal(a.scores, b.scores) and torch.equal(a.kept_idx, b.kept_idx)
+
+
+def test_ragged_batch_is_reproducible():
+    """The ragged serving shape, several times over: identical bits every time (no wait may run out)."""
+    w = nkv_inputs.WORKLOADS["llama3b_ragged"]
+    K, V = _kv(w)
+    ref, _ = run_gpu(w, K, V, 0.95)
+    assert not torch.isnan(ref.scores).any()
+    for _ in range(6):
+        out, _ = run_gpu(w, K, V, 0.95)
+        assert torch.equal(out.scores, ref.scores) and torch.equal(out.kept_idx, ref.kept_idx)
