@@ -52,7 +52,11 @@ __global__ __launch_bounds__(kSelThreads) void head_safe_kernel(const float *__r
         key[j] = i < N ? ord_key(sc[i]) : 0u;
     }
     uint32_t T = 0xFFFFFFFFu, rem = 0u, ties = 0u;
-    if (m_safe > 0) T = block_select<EPT, true>(key, N, (uint32_t)m_safe, sel, rem, ties);
+    if (m_safe > 0) {
+        uint32_t kmin, kmax;
+        block_key_range<EPT>(key, N, sel, kmin, kmax);
+        T = block_select<EPT, true>(key, N, (uint32_t)m_safe, sel, kmin, kmax, rem, ties);
+    }
     for (int j = tid; j < 2048; j += kSelThreads) hist0[j] = 0u;
     __syncthreads();
     {

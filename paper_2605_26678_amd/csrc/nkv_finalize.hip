@@ -196,36 +196,12 @@ __global__ __launch_bounds__(kThreads) void finalize_kernel(const float *__restr
 //   scale_stats_kernel : one workgroup per (unit, scale): min, max and the reliability gap of that scale
 //   route_kernel       : one workgroup per unit: weights, surprise statistics, routed score, pinning
 // ------------------------------------------------------------------------------------------------------
-__device__ __forceinline__ uint32_t block_min_u32(uint32_t v, uint32_t *scratch)
-{
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v = min(v, (uint32_t)__shfl_xor((int)v, o, 64));
-    __syncthreads();
-    if ((threadIdx.x & 63) == 0) scratch[threadIdx.x >> 6] = v;
-    __syncthreads();
-    uint32_t r = scratch[0];
-    for (int i = 1; i < (int)(blockDim.x >> 6); ++i) r = min(r, scratch[i]);
-    return r;
-}
-__device__ __forceinline__ uint32_t block_max_u32(uint32_t v, uint32_t *scratch)
-{
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v = max(v, (uint32_t)__shfl_xor((int)v, o, 64));
-    __syncthreads();
-    if ((threadIdx.x & 63) == 0) scratch[threadIdx.x >> 6] = v;
-    __syncthreads();
-    uint32_t r = scratch[0];
-    for (int i = 1; i < (int)(blockDim.x >> 6); ++i) r = max(r, scratch[i]);
-    return r;
-}
-
 // stats[(u * 3 + k) * 4 + {0, 1, 2}] = min, 1 / range (0 if flat), reliability gap of scale k of unit u
 template <int EPT>
 __global__ __launch_bounds__(kSelThreads) void scale_stats_kernel(const float *__restrict__ a_raw, int L, int H,
                                                                    PromptTab tab, float *__restrict__ stats)
 {
     __shared__ SelectScratch sel;
-    __shared__ uint32_t uscratch[16];
     __shared__ double dscratch[16];
     const int k = blockIdx.x, u = blockIdx.y;
     const int h = u % H, l = (u / H) % L, p = u / (H * L);
@@ -235,19 +211,16 @@ __global__ __launch_bounds__(kSelThreads) void scale_stats_kernel(const float *_
     const int tid = threadIdx.x;
 
     uint32_t key[EPT];
-    uint32_t kmin = 0xffffffffu, kmax = 0u;
 #pragma unroll
     for (int j = 0; j < EPT; ++j) {
         const int i = tid + j * kSelThreads;
         key[j] = i < N ? ord_key(a[i]) : 0u;
-        if (i < N) { kmin = min(kmin, key[j]); kmax = max(kmax, key[j]); }
     }
-    kmin = block_min_u32(kmin, uscratch);
-    kmax = block_max_u32(kmax, uscratch);
+    uint32_t kmin, kmax;
+    block_key_range<EPT>(key, N, sel, kmin, kmax);
     const uint32_t m = (uint32_t)min(tab.m_p[p], N);
-    uint32_t rem_top, rem_bot, ties;
-    const uint32_t t_top = block_select<EPT, true>(key, N, m, sel, rem_top, ties);
-    const uint32_t t_bot = block_select<EPT, false>(key, N, m, sel, rem_bot, ties);
+    uint32_t rem_top, rem_bot, t_top, t_bot;
+    block_select_both<EPT>(key, N, m, sel, kmin, kmax, t_top, rem_top, t_bot, rem_bot);
     double s_top = 0.0, s_bot = 0.0;
 #pragma unroll
     for (int j = 0; j < EPT; ++j) {

@@ -180,7 +180,9 @@ __global__ __launch_bounds__(kSelThreads) void select_fast_kernel(const float *_
     }
     uint32_t T = 0u, rem = 0u, ties = 0u;                             // B == N: every token is kept
     if (B < N) {
-        T = block_select<EPT, true>(key, N, (uint32_t)B, sel, rem, ties);
+        uint32_t kmin, kmax;
+        block_key_range<EPT>(key, N, sel, kmin, kmax);
+        T = block_select<EPT, true>(key, N, (uint32_t)B, sel, kmin, kmax, rem, ties);
         if (near_count) {                                             // tokens within near_tol of the threshold score
             const float tv = key_value(T);
             unsigned long long c = 0;
