@@ -26,7 +26,8 @@
 //     W_i = W_{i-1} - k_hat_{i-64} + k_hat_i,
 // re-seeded exactly at every sub-group boundary (every TPT tokens) from the partial sums, so no long
 // running sum and no cancellation beyond TPT steps.  k_hat_{i-64} sits at the same lane position of the
-// previous chunk, which the wavefront re-loads (an L2 hit: a neighbouring wavefront has just read it).
+// previous chunk, i.e. in the registers of the wavefront in front: it is handed over through LDS, four rows
+// per step (the first wavefront slides over the halo rows, which also pass through LDS).
 // Cosines do not depend on the anchor's length, so sums stand in for means everywhere.
 //
 // Placement.  The chip's compute units sit in 8 dies (XCDs) with one L2 each, and consecutive workgroups
@@ -299,10 +300,11 @@ void scan_kernel(const uint16_t *__restrict__ keys, PromptTab tab, float *__rest
     constexpr int HT = (TPT + NW - 1) / NW;                           // halo tokens per lane
     constexpr int NST = TPT / 4;                                      // 4-row steps per lane
     __shared__ float lds_rn[NW + 1][64];                              // [0]: halo chunk, [1 + w]: chunk w
-    __shared__ float lds_T[NW][SG][D];                                // partial sums of the chunks
-    __shared__ float lds_Th[NW][SG][D];                               // partial sums of the halo chunk
+    __shared__ float lds_T[NW][SG][D];                                // partial sums of the chunks, later of the halo chunk
+    __shared__ u32x4 lds_h[TPT][64];                                  // halo rows, by the window row that needs them
     __shared__ float lds_C[NW][D];                                    // chunk totals
     __shared__ float lds_S[D];                                        // the unit's sum, once complete
+    __shared__ u32x4 lds_x[2][NW > 1 ? NW - 1 : 1][4][64];            // rows on their way to the next wave
     __shared__ int s_lh, s_blk, s_sum, s_have;
 
     const int nblk = tab.blk_off[tab.n];
@@ -530,8 +532,13 @@ void scan_kernel(const uint16_t *__restrict__ keys, PromptTab tab, float *__rest
 #pragma unroll
         for (int e = 0; e < 8; ++e) T[e] = fmaf(r, k[e], T[e]);
         if (c == jj && q < TPT) lds_rn[0][g * TPT + q] = r;
+        if (q < TPT) lds_h[q][lane] = hraw[jj];                       // wave 0 slides over these rows
     }
-    store8(&lds_Th[w][g][c * 8], T);
+    store8(&lds_T[w][g][c * 8], T);
+    if (NW > 1 && w < NW - 1) {                                       // rows 0..3 for the next wave's first window step
+#pragma unroll
+        for (int i = 0; i < 4; ++i) lds_x[0][w][i][lane] = raw[i];
+    }
     __syncthreads();
     if (w == 0) {                                                     // previous chunk of wave 0 = the halo chunk
 #pragma unroll
@@ -540,7 +547,7 @@ void scan_kernel(const uint16_t *__restrict__ keys, PromptTab tab, float *__rest
 #pragma unroll
                 for (int ww = 0; ww < NW; ++ww) {
                     float hv[8];
-                    load8(&lds_Th[ww][gg][c * 8], hv);
+                    load8(&lds_T[ww][gg][c * 8], hv);
 #pragma unroll
                     for (int e = 0; e < 8; ++e) W[e] += hv[e];
                 }
@@ -549,7 +556,7 @@ void scan_kernel(const uint16_t *__restrict__ keys, PromptTab tab, float *__rest
     }
 
     // ---- slide the window over this lane's tokens: current-memory dots ----
-    // Four rows per step; a leaving row (same lane position, previous chunk) is loaded four rows ahead; the per-lane partial dots of the four rows enter the transposing butterfly.
+    // Four rows per step; the per-lane partial dots of the four rows enter the transposing butterfly.
     float wd_m = 0.f, wn_m = 1.f;
     const __amdgpu_buffer_rsrc_t srs = __builtin_amdgcn_make_buffer_rsrc(S_unit, 0, D * 4, 0x00020000);
     u32x4 sv0 = {kUnwritten, kUnwritten, kUnwritten, kUnwritten}, sv1 = sv0;
@@ -557,11 +564,20 @@ void scan_kernel(const uint16_t *__restrict__ keys, PromptTab tab, float *__rest
         StreamReduce<LPR> red_wd, red_wn;
 #pragma unroll
         for (int j = 0; j < TPT; ++j) forget(raw[j]);
-        u32x4 pl[4];                                                  // leaving rows, four rows ahead
-#pragma unroll
-        for (int i = 0; i < 4; ++i) pl[i] = row_load(rsrc, lane_off + (i - 64) * kRowBytes);
+        // Leaving rows come through LDS: wave 0 slides over the halo rows every wave stored while it worked on
+        // its share of the halo; the other waves get theirs from the wave in front of them, four rows per
+        // step, double-buffered: one barrier per step separates the writes of a buffer from its reads
+        // and its reads from the writes two steps later.
 #pragma unroll
         for (int s = 0; s < NST; ++s) {
+            if (NW > 1) {
+                if (s > 0) __syncthreads();
+                if (s + 1 < NST && w < NW - 1) {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) lds_x[(s + 1) & 1][w][i][lane] = raw[4 * s + 4 + i];
+                }
+            }
+            const u32x4 *leaving = w == 0 ? &lds_h[4 * s][lane] : &lds_x[s & 1][NW > 1 ? w - 1 : 0][0][lane];
             const float4 r4 = *reinterpret_cast<const float4 *>(&lds_rn[1 + w][g * TPT + 4 * s]);
             const float4 q4 = *reinterpret_cast<const float4 *>(&lds_rn[w][g * TPT + 4 * s]);
             const float rr[4] = {r4.x, r4.y, r4.z, r4.w};
@@ -574,8 +590,8 @@ void scan_kernel(const uint16_t *__restrict__ keys, PromptTab tab, float *__rest
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 float kp[8], k[8];
-                unpack8(pl[i], kp);
-                if (s + 1 < NST) pl[i] = row_load(rsrc, lane_off + (4 * s + 4 + i - 64) * kRowBytes);
+                const u32x4 pl = leaving[i * 64];
+                unpack8(pl, kp);
                 unpack8(raw[4 * s + i], k);
                 float wd = 0.f, wn = 0.f;
 #pragma unroll
