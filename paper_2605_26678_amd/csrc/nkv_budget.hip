@@ -49,7 +49,8 @@ __global__ __launch_bounds__(kSelThreads) void head_safe_kernel(const float *__r
 #pragma unroll
     for (int j = 0; j < EPT; ++j) {
         const int i = tid + j * kSelThreads;
-        key[j] = i < N ? ord_key(sc[i]) : 0u;
+        const float v = sc[min(i, N - 1)];                      // unconditional: the loads of a thread pipeline
+        key[j] = i < N ? ord_key(v) : 0u;
     }
     uint32_t T = 0xFFFFFFFFu, rem = 0u, ties = 0u;
     if (m_safe > 0) {

@@ -202,7 +202,7 @@ __global__ __launch_bounds__(kSelThreads) void scale_stats_kernel(const float *_
                                                                    PromptTab tab, float *__restrict__ stats)
 {
     __shared__ SelectScratch sel;
-    __shared__ double dscratch[16];
+    __shared__ double dscratch[32];
     const int k = blockIdx.x, u = blockIdx.y;
     const int h = u % H, l = (u / H) % L, p = u / (H * L);
     const int N = tab.tok_off[p + 1] - tab.tok_off[p];
@@ -214,25 +214,31 @@ __global__ __launch_bounds__(kSelThreads) void scale_stats_kernel(const float *_
 #pragma unroll
     for (int j = 0; j < EPT; ++j) {
         const int i = tid + j * kSelThreads;
-        key[j] = i < N ? ord_key(a[i]) : 0u;
+        const float v = a[min(i, N - 1)];                      // unconditional: the loads of a thread pipeline
+        key[j] = i < N ? ord_key(v) : 0u;
     }
     uint32_t kmin, kmax;
     block_key_range<EPT>(key, N, sel, kmin, kmax);
     const uint32_t m = (uint32_t)min(tab.m_p[p], N);
     uint32_t rem_top, rem_bot, t_top, t_bot;
     block_select_both<EPT>(key, N, m, sel, kmin, kmax, t_top, rem_top, t_bot, rem_bot);
-    double s_top = 0.0, s_bot = 0.0;
+    // sums beyond the thresholds: per thread in fp32 (a handful of terms of magnitude <= 1), across the
+    // workgroup in fp64
+    float p_top = 0.f, p_bot = 0.f;
 #pragma unroll
     for (int j = 0; j < EPT; ++j) {
-        if (tid + j * kSelThreads < N) {
-            const double v = (double)key_value(key[j]);
-            if (key[j] > t_top) s_top += v;
-            if (key[j] < t_bot) s_bot += v;
-        }
+        const bool in = N == EPT * kSelThreads || tid + j * kSelThreads < N;
+        const float v = key_value(key[j]);
+        p_top += in && key[j] > t_top ? v : 0.f;
+        p_bot += in && key[j] < t_bot ? v : 0.f;
     }
-    s_top = block_sum(s_top, dscratch);
-    s_bot = block_sum(s_bot, dscratch);
+    double s_top = wave_sum((double)p_top), s_bot = wave_sum((double)p_bot);
+    if ((tid & 63) == 0) { dscratch[tid >> 6] = s_top; dscratch[16 + (tid >> 6)] = s_bot; }
+    __syncthreads();
     if (tid == 0) {
+        s_top = 0.0;
+        s_bot = 0.0;
+        for (int i = 0; i < kSelThreads / 64; ++i) { s_top += dscratch[i]; s_bot += dscratch[16 + i]; }
         const float lo = key_value(kmin), range = key_value(kmax) - lo;
         const float inv = range < kFlat ? 0.f : 1.0f / range;
         // ties at the threshold: rem of them belong to the set

@@ -280,7 +280,7 @@ constexpr int kDeferCountWord = kTimeoutWord + 1;        // blocks on the list
 constexpr int kSyncWords = kTimeoutWord + 32;            // the list (one word per block) follows
 
 // Blocks [seg_lo(x), seg_lo(x + 1)) of every (layer, head) belong to die x.
-__device__ __forceinline__ int seg_lo(int nblk, int x) { return (int)(((int64_t)x * nblk) / kDies); }
+__device__ __forceinline__ int seg_lo(int nblk, int x) { return (int)(((uint32_t)x * (uint32_t)nblk) / kDies); }
 
 // Queue of die x: for lh = 0, 1, ...: the len blocks of its segment, then -- if lh % kDies == x -- one
 // "add the unit up" item per prompt.  First ticket of lh in that queue:
@@ -310,8 +310,9 @@ void scan_kernel(const uint16_t *__restrict__ keys, PromptTab tab, float *__rest
     const int nblk = tab.blk_off[tab.n];
     int lh, blk;
     if (FUSED) {
-        // take a ticket from this die's counter, or from the next die's that still has work
-        if (threadIdx.x == 0) {
+        // take a ticket from this die's counter, or from the next die's that still has work.  The first wave
+        // does it with the ticket in a scalar register, so that decoding it is scalar arithmetic.
+        if (threadIdx.x < 64) {
             const int die = (int)(__builtin_amdgcn_s_getreg((3 << 11) | 20) & (kDies - 1));   // XCC_ID[3:0]
             int got_lh = -1, got_blk = 0, got_sum = -1;
             for (int i = 0; i < kDies && got_lh < 0; ++i) {
@@ -319,8 +320,10 @@ void scan_kernel(const uint16_t *__restrict__ keys, PromptTab tab, float *__rest
                 const int lo = seg_lo(nblk, x), len = seg_lo(nblk, x + 1) - lo;
                 const uint32_t items = queue_start(LH, len, tab.n, x);
                 if (items == 0u) continue;
-                const uint32_t t = __hip_atomic_fetch_add(sync + x * kTicketStride, 1u, __ATOMIC_RELAXED,
-                                                          __HIP_MEMORY_SCOPE_AGENT);
+                uint32_t t = 0u;
+                if (threadIdx.x == 0)
+                    t = __hip_atomic_fetch_add(sync + x * kTicketStride, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                t = (uint32_t)__builtin_amdgcn_readfirstlane((int)t);
                 if (t < items) {
                     // lh of ticket t: a first guess from the average number of items per lh, then exact
                     int l = min(LH - 1, (int)(t * (uint32_t)kDies / ((uint32_t)kDies * len + tab.n)));
@@ -332,9 +335,11 @@ void scan_kernel(const uint16_t *__restrict__ keys, PromptTab tab, float *__rest
                     else got_sum = r - len;                           // prompt whose unit sum is to be formed
                 }
             }
-            s_lh = got_lh;
-            s_blk = got_blk;
-            s_sum = got_sum;
+            if (threadIdx.x == 0) {
+                s_lh = got_lh;
+                s_blk = got_blk;
+                s_sum = got_sum;
+            }
         }
         __syncthreads();
         lh = s_lh;
