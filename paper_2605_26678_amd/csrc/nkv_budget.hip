@@ -79,18 +79,25 @@ __global__ __launch_bounds__(kSelThreads) void head_safe_kernel(const float *__r
     if (tid == 0) safe[u] = HeadSafe{T, rem, ties, 0u};
 }
 
-// Calls f(key) for every score of s[0..N), the workgroup striding over the row with eight independent loads
-// in flight per thread (the scores sit in L2 / memory; one load at a time would be latency-bound).
-template <typename F> __device__ __forceinline__ void for_each_key(const float *__restrict__ s, int N, F f)
+// Calls f(h, key) for every score of the H <= kFastHeads heads of a layer (head h at s + h * stride, N scores
+// each), the workgroup striding over the rows with U loads per head in flight per thread (the scores sit in
+// L2 / memory; few loads at a time would be latency-bound).
+template <typename F>
+__device__ __forceinline__ void for_each_key(const float *__restrict__ s, int64_t stride, int H, int N, F f)
 {
-    constexpr int U = 8;
+    constexpr int U = 4;
     for (int i0 = threadIdx.x; i0 < N; i0 += U * kThreads) {
-        float v[U];
+        float v[kFastHeads][U];
 #pragma unroll
-        for (int q = 0; q < U; ++q) v[q] = i0 + q * kThreads < N ? s[i0 + q * kThreads] : 0.f;
+        for (int h = 0; h < kFastHeads; ++h)
 #pragma unroll
-        for (int q = 0; q < U; ++q)
-            if (i0 + q * kThreads < N) f(ord_key(v[q]));
+            for (int q = 0; q < U; ++q)
+                v[h][q] = h < H ? s[h * stride + min(i0 + q * kThreads, N - 1)] : 0.f;
+#pragma unroll
+        for (int h = 0; h < kFastHeads; ++h)
+#pragma unroll
+            for (int q = 0; q < U; ++q)
+                if (h < H && i0 + q * kThreads < N) f(h, ord_key(v[h][q]));
     }
 }
 
@@ -167,14 +174,13 @@ __global__ __launch_bounds__(kThreads) void layer_budget_kernel(const float *__r
     // middle 11 bits among pool entries whose top digit is d0
     for (int j = tid; j < 2048; j += kThreads) hist[j] = 0u;
     __syncthreads();
-    for (int h = 0; h < H; ++h) {
-        const float *s = sc + (int64_t)h * tab.T;
-        const uint32_t th = Th[h];
-        for_each_key(s, N, [&](uint32_t key) {
-            if (key < th && (key >> 21) == d0) atomicAdd(&hist[(key >> 10) & 2047u], 1u);
-        });
-        if (tid == 0 && extra[h] > 0u && (th >> 21) == d0) atomicAdd(&hist[(th >> 10) & 2047u], extra[h]);
-    }
+    uint32_t th[kFastHeads];
+#pragma unroll
+    for (int h = 0; h < kFastHeads; ++h) th[h] = h < H ? Th[h] : 0u;
+    for_each_key(sc, tab.T, H, N, [&](int h, uint32_t key) {
+        if (key < th[h] && (key >> 21) == d0) atomicAdd(&hist[(key >> 10) & 2047u], 1u);
+    });
+    if (tid < H && extra[tid] > 0u && (Th[tid] >> 21) == d0) atomicAdd(&hist[(Th[tid] >> 10) & 2047u], extra[tid]);
     __syncthreads();
     block_pick_top<2048>(hist, want, wsum, pick);
     const uint32_t pre22 = (d0 << 11) | pick[0];
@@ -184,23 +190,26 @@ __global__ __launch_bounds__(kThreads) void layer_budget_kernel(const float *__r
     // low 10 bits, one histogram per head; entries above the 22-bit prefix are counted per head
     for (int j = tid; j < H * 1024; j += kThreads) (&hist2[0][0])[j] = 0u;
     __syncthreads();
-    for (int h = 0; h < H; ++h) {
-        const float *s = sc + (int64_t)h * tab.T;
-        const uint32_t th = Th[h];
-        uint32_t gt = 0u;
-        for_each_key(s, N, [&](uint32_t key) {
-            if (key < th) {
-                const uint32_t hi = key >> 10;
-                if (hi > pre22) ++gt;
-                else if (hi == pre22) atomicAdd(&hist2[h][key & 1023u], 1u);
-            }
-        });
-        gt = wave_sum(gt);
-        if ((tid & 63) == 0 && gt != 0u) atomicAdd(&cnt_gt[h], gt);
-        if (tid == 0 && extra[h] > 0u) {
-            if ((th >> 10) > pre22) atomicAdd(&cnt_gt[h], extra[h]);
-            else if ((th >> 10) == pre22) atomicAdd(&hist2[h][th & 1023u], extra[h]);
+    uint32_t gt[kFastHeads];
+#pragma unroll
+    for (int h = 0; h < kFastHeads; ++h) gt[h] = 0u;
+    for_each_key(sc, tab.T, H, N, [&](int h, uint32_t key) {
+        if (key < th[h]) {
+            const uint32_t hi = key >> 10;
+            if (hi > pre22) ++gt[h];
+            else if (hi == pre22) atomicAdd(&hist2[h][key & 1023u], 1u);
         }
+    });
+#pragma unroll
+    for (int h = 0; h < kFastHeads; ++h) {
+        if (h < H) {
+            const uint32_t g = wave_sum(gt[h]);
+            if ((tid & 63) == 0 && g != 0u) atomicAdd(&cnt_gt[h], g);
+        }
+    }
+    if (tid < H && extra[tid] > 0u) {
+        if ((Th[tid] >> 10) > pre22) atomicAdd(&cnt_gt[tid], extra[tid]);
+        else if ((Th[tid] >> 10) == pre22) atomicAdd(&hist2[tid][Th[tid] & 1023u], extra[tid]);
     }
     __syncthreads();
     hist[tid] = 0u;                                           // kThreads == 1024 bins

@@ -217,6 +217,18 @@ __global__ __launch_bounds__(kSelThreads) void scale_stats_kernel(const float *_
         const float v = a[min(i, N - 1)];                      // unconditional: the loads of a thread pipeline
         key[j] = i < N ? ord_key(v) : 0u;
     }
+    // Warm the L2 of this die for the workgroup that will follow on this compute unit: only one workgroup of
+    // this size fits a compute unit, so nothing else overlaps its load phase with this one's arithmetic.
+    // Workgroups go to the dies round-robin, so the one 256 places further on lands on this die again.
+    {
+        const int id = blockIdx.y * 3 + blockIdx.x + 256, kn = id % 3, un = id / 3;
+        if (un < (int)gridDim.y) {
+            const int hn = un % H, ln = (un / H) % L, pn = un / (H * L);
+            const int Nn = tab.tok_off[pn + 1] - tab.tok_off[pn];
+            const float *an = a_raw + (int64_t)kn * rows + ((int64_t)ln * H + hn) * tab.T + tab.tok_off[pn];
+            if (tid * 32 < Nn) (void)*(const volatile float *)(an + tid * 32);   // one word per 128-byte line
+        }
+    }
     uint32_t kmin, kmax;
     block_key_range<EPT>(key, N, sel, kmin, kmax);
     const uint32_t m = (uint32_t)min(tab.m_p[p], N);
