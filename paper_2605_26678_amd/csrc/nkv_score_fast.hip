@@ -32,9 +32,10 @@
 //
 // Placement.  The chip's compute units sit in 8 dies (XCDs) with one L2 each, and consecutive workgroups
 // start on different dies.  Blocks are therefore not taken in launch order: every die has its own ticket
-// counter and walks its own contiguous eighth of each (layer, head)'s blocks, so the halo and the
-// re-loaded rows of a block were fetched by the same L2 moments before.  All dies work on the same
-// (layer, head) at the same time.  A die that runs out of tickets takes them from the next die's counter.
+// counter and walks its own share of each (layer, head)'s blocks -- runs of 16 consecutive blocks, dealt to
+// the dies round-robin -- so the halo of a block was fetched by the same L2 moments before.  All dies work
+// on the same (layer, head) at the same time.  A die that runs out of tickets takes them from the next
+// die's counter.
 //
 // The stable anchor needs every key of the prompt before the first a_s can be computed.  Two ways:
 //   fused   : all blocks of a (layer, head, prompt) unit are ticketed close together.  The block totals
@@ -279,8 +280,18 @@ constexpr int kTimeoutWord = kDies * kTicketStride;      // summing workgroups t
 constexpr int kDeferCountWord = kTimeoutWord + 1;        // blocks on the list
 constexpr int kSyncWords = kTimeoutWord + 32;            // the list (one word per block) follows
 
-// Blocks [seg_lo(x), seg_lo(x + 1)) of every (layer, head) belong to die x.
-__device__ __forceinline__ int seg_lo(int nblk, int x) { return (int)(((uint32_t)x * (uint32_t)nblk) / kDies); }
+// The blocks of a (layer, head) are dealt to the dies in runs of kRun consecutive blocks, round-robin: runs
+// keep a block's halo on the die of the block before it (15 times out of 16), dealing them round-robin
+// gives every die the same mix of prompts when a batch holds prompts of different lengths.
+constexpr int kRun = 16;
+// number of blocks of one (layer, head) that belong to die x
+__device__ __forceinline__ int die_blocks(int nblk, int x)
+{
+    const int cycles = nblk / (kRun * kDies), rem = nblk - cycles * kRun * kDies;
+    return cycles * kRun + min(max(rem - x * kRun, 0), kRun);
+}
+// the r-th of them
+__device__ __forceinline__ int die_block(int x, int r) { return ((r / kRun) * kDies + x) * kRun + r % kRun; }
 
 // Queue of die x: for lh = 0, 1, ...: the len blocks of its segment, then -- if lh % kDies == x -- one
 // "add the unit up" item per prompt.  First ticket of lh in that queue:
@@ -317,7 +328,7 @@ void scan_kernel(const uint16_t *__restrict__ keys, PromptTab tab, float *__rest
             int got_lh = -1, got_blk = 0, got_sum = -1;
             for (int i = 0; i < kDies && got_lh < 0; ++i) {
                 const int x = (die + i) & (kDies - 1);
-                const int lo = seg_lo(nblk, x), len = seg_lo(nblk, x + 1) - lo;
+                const int len = die_blocks(nblk, x);
                 const uint32_t items = queue_start(LH, len, tab.n, x);
                 if (items == 0u) continue;
                 uint32_t t = 0u;
@@ -331,7 +342,7 @@ void scan_kernel(const uint16_t *__restrict__ keys, PromptTab tab, float *__rest
                     while (l + 1 < LH && queue_start(l + 1, len, tab.n, x) <= t) ++l;
                     const int r = (int)(t - queue_start(l, len, tab.n, x));
                     got_lh = l;
-                    if (r < len) got_blk = lo + r;
+                    if (r < len) got_blk = die_block(x, r);
                     else got_sum = r - len;                           // prompt whose unit sum is to be formed
                 }
             }
