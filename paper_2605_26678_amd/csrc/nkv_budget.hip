@@ -33,12 +33,12 @@ struct HeadSafe {                // result of step A for one head
 // ---------------------------------------------------------------------------------------------------
 template <int EPT>
 __global__ __launch_bounds__(kSelThreads) void head_safe_kernel(const float *__restrict__ scores, int L, int H,
-                                                                 PromptTab tab, HeadSafe *__restrict__ safe,
+                                                                 PromptTab tab, int u0, HeadSafe *__restrict__ safe,
                                                                  uint32_t *__restrict__ pool_hist)
 {
     __shared__ SelectScratch sel;
     __shared__ uint32_t hist0[2048];
-    const int u = blockIdx.x;
+    const int u = u0 + blockIdx.x;
     const int h = u % H, l = (u / H) % L, p = u / (H * L);
     const int N = tab.tok_off[p + 1] - tab.tok_off[p];
     const float *sc = scores + ((int64_t)l * H + h) * tab.T + tab.tok_off[p];
@@ -376,10 +376,12 @@ hipError_t launch_budget(const float *scores, int L, int H, const PromptTab &tab
     if (ws != nullptr && H <= kFastHeads && nmax <= 32 * kSelThreads) {
         HeadSafe *safe = (HeadSafe *)ws;
         uint32_t *pool_hist = (uint32_t *)(safe + units);
-        if (nmax <= 4 * kSelThreads) head_safe_kernel<4><<<units, kSelThreads, 0, st>>>(scores, L, H, tab, safe, pool_hist);
-        else if (nmax <= 8 * kSelThreads) head_safe_kernel<8><<<units, kSelThreads, 0, st>>>(scores, L, H, tab, safe, pool_hist);
-        else if (nmax <= 16 * kSelThreads) head_safe_kernel<16><<<units, kSelThreads, 0, st>>>(scores, L, H, tab, safe, pool_hist);
-        else head_safe_kernel<32><<<units, kSelThreads, 0, st>>>(scores, L, H, tab, safe, pool_hist);
+        for_each_length_class(tab, L * H, [&](int ept, int u0, int n) {
+            if (ept == 4) head_safe_kernel<4><<<n, kSelThreads, 0, st>>>(scores, L, H, tab, u0, safe, pool_hist);
+            else if (ept == 8) head_safe_kernel<8><<<n, kSelThreads, 0, st>>>(scores, L, H, tab, u0, safe, pool_hist);
+            else if (ept == 16) head_safe_kernel<16><<<n, kSelThreads, 0, st>>>(scores, L, H, tab, u0, safe, pool_hist);
+            else head_safe_kernel<32><<<n, kSelThreads, 0, st>>>(scores, L, H, tab, u0, safe, pool_hist);
+        });
         layer_budget_kernel<<<(unsigned)(tab.n * L), kThreads, 0, st>>>(scores, L, H, tab, safe, pool_hist, k_per_head);
     } else {
         budget_kernel<<<(unsigned)(tab.n * L), kThreads, 0, st>>>(scores, L, H, tab, k_per_head);

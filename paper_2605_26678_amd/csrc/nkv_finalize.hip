@@ -199,11 +199,11 @@ __global__ __launch_bounds__(kThreads) void finalize_kernel(const float *__restr
 // stats[(u * 3 + k) * 4 + {0, 1, 2}] = min, 1 / range (0 if flat), reliability gap of scale k of unit u
 template <int EPT>
 __global__ __launch_bounds__(kSelThreads) void scale_stats_kernel(const float *__restrict__ a_raw, int L, int H,
-                                                                   PromptTab tab, float *__restrict__ stats)
+                                                                   PromptTab tab, int u0, float *__restrict__ stats)
 {
     __shared__ SelectScratch sel;
     __shared__ double dscratch[32];
-    const int k = blockIdx.x, u = blockIdx.y;
+    const int k = blockIdx.x, u = u0 + blockIdx.y;
     const int h = u % H, l = (u / H) % L, p = u / (H * L);
     const int N = tab.tok_off[p + 1] - tab.tok_off[p];
     const int64_t rows = (int64_t)L * H * tab.T;
@@ -221,8 +221,8 @@ __global__ __launch_bounds__(kSelThreads) void scale_stats_kernel(const float *_
     // this size fits a compute unit, so nothing else overlaps its load phase with this one's arithmetic.
     // Workgroups go to the dies round-robin, so the one 256 places further on lands on this die again.
     {
-        const int id = blockIdx.y * 3 + blockIdx.x + 256, kn = id % 3, un = id / 3;
-        if (un < (int)gridDim.y) {
+        const int id = blockIdx.y * 3 + blockIdx.x + 256, kn = id % 3, un = u0 + id / 3;
+        if (un < u0 + (int)gridDim.y) {
             const int hn = un % H, ln = (un / H) % L, pn = un / (H * L);
             const int Nn = tab.tok_off[pn + 1] - tab.tok_off[pn];
             const float *an = a_raw + (int64_t)kn * rows + ((int64_t)ln * H + hn) * tab.T + tab.tok_off[pn];
@@ -356,11 +356,13 @@ hipError_t launch_finalize(const float *a_raw, int L, int H, const PromptTab &ta
     const unsigned units = (unsigned)(tab.n * L * H);
     prof.begin(NKV_KERNEL_FINALIZE, st);
     if (nmax <= 32 * kSelThreads) {
-        const dim3 grid(3, units);
-        if (nmax <= 4 * kSelThreads) scale_stats_kernel<4><<<grid, kSelThreads, 0, st>>>(a_raw, L, H, tab, stats);
-        else if (nmax <= 8 * kSelThreads) scale_stats_kernel<8><<<grid, kSelThreads, 0, st>>>(a_raw, L, H, tab, stats);
-        else if (nmax <= 16 * kSelThreads) scale_stats_kernel<16><<<grid, kSelThreads, 0, st>>>(a_raw, L, H, tab, stats);
-        else scale_stats_kernel<32><<<grid, kSelThreads, 0, st>>>(a_raw, L, H, tab, stats);
+        for_each_length_class(tab, L * H, [&](int ept, int u0, int n) {
+            const dim3 grid(3, (unsigned)n);
+            if (ept == 4) scale_stats_kernel<4><<<grid, kSelThreads, 0, st>>>(a_raw, L, H, tab, u0, stats);
+            else if (ept == 8) scale_stats_kernel<8><<<grid, kSelThreads, 0, st>>>(a_raw, L, H, tab, u0, stats);
+            else if (ept == 16) scale_stats_kernel<16><<<grid, kSelThreads, 0, st>>>(a_raw, L, H, tab, u0, stats);
+            else scale_stats_kernel<32><<<grid, kSelThreads, 0, st>>>(a_raw, L, H, tab, u0, stats);
+        });
         route_kernel<<<units, kSelThreads, 0, st>>>(a_raw, L, H, tab, lc, stats, scores);
     } else {
         finalize_kernel<<<units, kThreads, 0, st>>>(a_raw, L, H, tab, lc, scores);

@@ -58,6 +58,22 @@ hipError_t launch_score_fast(const void *keys, int LH, int d, const PromptTab &t
                              float *bsum, float *ssum, void *sync_area, int mode, const Prof &prof,
                              hipStream_t st);
 
+// Units are numbered prompt by prompt, so the units of consecutive prompts of similar length form one
+// range.  Calls f(ept, unit0, units) for every maximal run of prompts whose lengths need the same number
+// ept in {4, 8, 16, 32} of values per thread in the 1024-thread per-unit kernels (N <= 1024 * ept).
+template <typename F> inline void for_each_length_class(const PromptTab &tab, int LH, F f)
+{
+    auto cls = [](int N) { return N <= 4096 ? 4 : N <= 8192 ? 8 : N <= 16384 ? 16 : 32; };
+    int p = 0;
+    while (p < tab.n) {
+        const int c = cls(tab.tok_off[p + 1] - tab.tok_off[p]);
+        int q = p + 1;
+        while (q < tab.n && cls(tab.tok_off[q + 1] - tab.tok_off[q]) == c) ++q;
+        f(c, p * LH, (q - p) * LH);
+        p = q;
+    }
+}
+
 // ---- per-head statistics, blend weights, gate and final scores ----
 hipError_t launch_finalize(const float *a_raw, int L, int H, const PromptTab &tab, const LearnerConsts &lc,
                            float *scores, float *stats, const Prof &prof, hipStream_t st);

@@ -153,7 +153,7 @@ __global__ __launch_bounds__(kThreads) void select_kernel(const float *__restric
 template <int EPT>
 __global__ __launch_bounds__(kSelThreads) void select_fast_kernel(const float *__restrict__ scores,
                                                                   const int32_t *__restrict__ k_per_head, int L,
-                                                                  int H, PromptTab tab, float near_tol,
+                                                                  int H, PromptTab tab, int u0, float near_tol,
                                                                   const int64_t *__restrict__ head_off,
                                                                   int64_t row_capacity,
                                                                   int32_t *__restrict__ kept_idx,
@@ -163,7 +163,7 @@ __global__ __launch_bounds__(kSelThreads) void select_fast_kernel(const float *_
     __shared__ unsigned long long group_cnt[EPT * kWaves];           // (gt << 32 | eq) per (chunk, wave)
     __shared__ unsigned long long near_acc[16];
 
-    const int u = blockIdx.x;
+    const int u = u0 + blockIdx.x;
     const int h = u % H, l = (u / H) % L, p = u / (H * L);
     const int N = tab.tok_off[p + 1] - tab.tok_off[p];
     const int B = min(max(k_per_head[u], 0), N);
@@ -304,13 +304,16 @@ hipError_t launch_select_compact(const void *keys, const void *values, const flo
     int nmax = 0;
     for (int p = 0; p < tab.n; ++p) nmax = max(nmax, tab.tok_off[p + 1] - tab.tok_off[p]);
     prof.begin(NKV_KERNEL_SELECT, st);
-#define NKV_SELECT_FAST(EPT)                                                                                 \
-    select_fast_kernel<EPT><<<(unsigned)n_units, kSelThreads, 0, st>>>(scores, k_per_head, L, H, tab, near_tol, \
-                                                                       head_off, row_capacity, kept_idx, near_count)
-    if (nmax <= 4 * kSelThreads) NKV_SELECT_FAST(4);
-    else if (nmax <= 8 * kSelThreads) NKV_SELECT_FAST(8);
-    else if (nmax <= 16 * kSelThreads) NKV_SELECT_FAST(16);
-    else if (nmax <= 32 * kSelThreads) NKV_SELECT_FAST(32);
+#define NKV_SELECT_FAST(EPT)                                                                              \
+    select_fast_kernel<EPT><<<(unsigned)n, kSelThreads, 0, st>>>(scores, k_per_head, L, H, tab, u0, near_tol, \
+                                                                 head_off, row_capacity, kept_idx, near_count)
+    if (nmax <= 32 * kSelThreads)
+        for_each_length_class(tab, L * H, [&](int ept, int u0, int n) {
+            if (ept == 4) NKV_SELECT_FAST(4);
+            else if (ept == 8) NKV_SELECT_FAST(8);
+            else if (ept == 16) NKV_SELECT_FAST(16);
+            else NKV_SELECT_FAST(32);
+        });
     else
         select_kernel<<<(unsigned)n_units, kThreads, 0, st>>>(scores, k_per_head, L, H, tab, near_tol, head_off,
                                                               row_capacity, kept_idx, near_count);
