@@ -32,8 +32,8 @@
 //
 // Placement.  The chip's compute units sit in 8 dies (XCDs) with one L2 each, and consecutive workgroups
 // start on different dies.  Blocks are therefore not taken in launch order: every die has its own ticket
-// counter and walks its own share of each (layer, head)'s blocks -- runs of 16 consecutive blocks, dealt to
-// the dies round-robin -- so the halo of a block was fetched by the same L2 moments before.  All dies work
+// counter and walks its own share of each (layer, head)'s blocks -- runs of up to 16 consecutive blocks,
+// dealt to the dies round-robin -- so the halo of a block was fetched by the same L2 moments before.  All dies work
 // on the same (layer, head) at the same time.  A die that runs out of tickets takes them from the next
 // die's counter.
 //
@@ -280,18 +280,19 @@ constexpr int kTimeoutWord = kDies * kTicketStride;      // summing workgroups t
 constexpr int kDeferCountWord = kTimeoutWord + 1;        // blocks on the list
 constexpr int kSyncWords = kTimeoutWord + 32;            // the list (one word per block) follows
 
-// The blocks of a (layer, head) are dealt to the dies in runs of kRun consecutive blocks, round-robin: runs
-// keep a block's halo on the die of the block before it (15 times out of 16), dealing them round-robin
-// gives every die the same mix of prompts when a batch holds prompts of different lengths.
-constexpr int kRun = 16;
+// The blocks of a (layer, head) are dealt to the dies in runs of consecutive blocks, round-robin: runs keep a
+// block's halo on the die of the block before it, dealing them round-robin gives every die the same mix of
+// prompts when a batch holds prompts of different lengths.  A run is 16 blocks, fewer when there are not
+// enough blocks to give every die a run.
+__device__ __forceinline__ int run_length(int nblk) { return max(1, min(16, nblk / kDies)); }
 // number of blocks of one (layer, head) that belong to die x
-__device__ __forceinline__ int die_blocks(int nblk, int x)
+__device__ __forceinline__ int die_blocks(int nblk, int run, int x)
 {
-    const int cycles = nblk / (kRun * kDies), rem = nblk - cycles * kRun * kDies;
-    return cycles * kRun + min(max(rem - x * kRun, 0), kRun);
+    const int cycles = nblk / (run * kDies), rem = nblk - cycles * run * kDies;
+    return cycles * run + min(max(rem - x * run, 0), run);
 }
 // the r-th of them
-__device__ __forceinline__ int die_block(int x, int r) { return ((r / kRun) * kDies + x) * kRun + r % kRun; }
+__device__ __forceinline__ int die_block(int run, int x, int r) { return ((r / run) * kDies + x) * run + r % run; }
 
 // Queue of die x: for lh = 0, 1, ...: the len blocks of its segment, then -- if lh % kDies == x -- one
 // "add the unit up" item per prompt.  First ticket of lh in that queue:
@@ -328,7 +329,7 @@ void scan_kernel(const uint16_t *__restrict__ keys, PromptTab tab, float *__rest
             int got_lh = -1, got_blk = 0, got_sum = -1;
             for (int i = 0; i < kDies && got_lh < 0; ++i) {
                 const int x = (die + i) & (kDies - 1);
-                const int len = die_blocks(nblk, x);
+                const int run = run_length(nblk), len = die_blocks(nblk, run, x);
                 const uint32_t items = queue_start(LH, len, tab.n, x);
                 if (items == 0u) continue;
                 uint32_t t = 0u;
@@ -342,7 +343,7 @@ void scan_kernel(const uint16_t *__restrict__ keys, PromptTab tab, float *__rest
                     while (l + 1 < LH && queue_start(l + 1, len, tab.n, x) <= t) ++l;
                     const int r = (int)(t - queue_start(l, len, tab.n, x));
                     got_lh = l;
-                    if (r < len) got_blk = die_block(x, r);
+                    if (r < len) got_blk = die_block(run, x, r);
                     else got_sum = r - len;                           // prompt whose unit sum is to be formed
                 }
             }
@@ -475,7 +476,7 @@ void scan_kernel(const uint16_t *__restrict__ keys, PromptTab tab, float *__rest
         float own[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e) { W[e] = 0.f; own[e] = 0.f; }
-#pragma unroll
+#pragma unroll 1
         for (int gg = 0; gg < SG; ++gg) {
             float cv[8], pv[8];
             load8(&lds_T[w][gg][c * 8], cv);
@@ -557,7 +558,7 @@ void scan_kernel(const uint16_t *__restrict__ keys, PromptTab tab, float *__rest
     }
     __syncthreads();
     if (w == 0) {                                                     // previous chunk of wave 0 = the halo chunk
-#pragma unroll
+#pragma unroll 1
         for (int gg = 0; gg < SG; ++gg) {
             if (gg >= g) {
 #pragma unroll
