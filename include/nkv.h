@@ -56,8 +56,10 @@ enum {
     NKV_FLAG_GENERIC_KERNELS = 1u,    /* force the shape-generic scoring kernels                            */
     NKV_FLAG_TWO_PASS_STABLE = 2u,    /* streaming kernels: compute the stable anomaly in a second pass     */
                                       /* over the keys instead of inside the single fused pass             */
-    NKV_FLAG_DEFER_STABLE = 4u        /* streaming kernels, fused pass: no workgroup waits for its unit's   */
+    NKV_FLAG_DEFER_STABLE = 4u,       /* streaming kernels, fused pass: no workgroup waits for its unit's   */
                                       /* sum; every block takes the deferred route (exercises that route)   */
+    NKV_FLAG_NO_UNIT_SUMS = 8u        /* as DEFER_STABLE, and the pass forms no unit sum either: all of     */
+                                      /* them come from the kernel that fills in missing ones (exercises it) */
 };
 /* Kernels a caller can ask to have timed, see nkv_params.prof_start. */
 enum {

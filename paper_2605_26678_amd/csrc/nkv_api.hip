@@ -100,7 +100,8 @@ int run_raw(const void *keys, const nkv_shape *s, const nkv_params *p, const Pro
     if (!(p->flags & NKV_FLAG_GENERIC_KERNELS) && fast_score_supported(s->dtype, s->d, p->window, tab))
         e = launch_score_fast(keys, LH, s->d, tab, a_raw, (float *)(ws + lay.bsum), (float *)(ws + lay.ssum),
                               ws + lay.sync,
-                              (p->flags & NKV_FLAG_TWO_PASS_STABLE) ? kScanTwoPass
+                              (p->flags & NKV_FLAG_TWO_PASS_STABLE)  ? kScanTwoPass
+                              : (p->flags & NKV_FLAG_NO_UNIT_SUMS)  ? kScanRepairAll
                               : (p->flags & NKV_FLAG_DEFER_STABLE)  ? kScanDeferAll : kScanFused, prof, st);
     else
         e = launch_score_generic(keys, s->dtype, LH, s->d, p->window, tab, a_raw, (float *)(ws + lay.rnorm),

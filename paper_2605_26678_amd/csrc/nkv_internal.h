@@ -53,7 +53,9 @@ hipError_t launch_score_generic(const void *keys, int dtype, int LH, int d, int 
 // ---- scoring, streaming kernels for bf16 keys, d in {64,128}, window 64, block size <= 256 ----
 bool fast_score_supported(int dtype, int d, int window, const PromptTab &tab);
 size_t fast_score_sync_bytes(int LH, const PromptTab &tab);
-enum { kScanFused = 0, kScanTwoPass = 1, kScanDeferAll = 2 };   // how the stable anomaly is obtained
+// How the stable anomaly is obtained.  kScanDeferAll: fused pass, but every block takes the deferred route;
+// kScanRepairAll: in addition no unit sum is formed inside the pass, all come from the repair kernel.
+enum { kScanFused = 0, kScanTwoPass = 1, kScanDeferAll = 2, kScanRepairAll = 3 };
 hipError_t launch_score_fast(const void *keys, int LH, int d, const PromptTab &tab, float *a_raw,
                              float *bsum, float *ssum, void *sync_area, int mode, const Prof &prof,
                              hipStream_t st);

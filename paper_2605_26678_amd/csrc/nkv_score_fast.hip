@@ -239,9 +239,11 @@ __device__ __forceinline__ void store8(float *dst, const float v[8])
 // 1 / max(||k||, 1e-12) from the sum of squares.
 __device__ __forceinline__ float inv_norm(float ss) { return ss < 1e-24f ? 1e12f : __builtin_amdgcn_rsqf(ss); }
 
+// -cos from <k_hat, anchor>, ||k_hat|| and ||anchor||^2, norms clamped at 1e-12: the hardware's reciprocal
+// and reciprocal square root (1 ulp each) instead of a division and a square root.
 __device__ __forceinline__ float neg_cos(float dot_scaled, float knorm, float anchor_sq)
 {
-    return -dot_scaled / (fmaxf(knorm, kEps) * fmaxf(sqrtf(anchor_sq), kEps));
+    return -dot_scaled * __builtin_amdgcn_rcpf(fmaxf(knorm, kEps)) * __builtin_amdgcn_rsqf(fmaxf(anchor_sq, kEps * kEps));
 }
 
 // ---- self-validating words (fused path) ----------------------------------------------------------------
@@ -301,12 +303,70 @@ __device__ __forceinline__ uint32_t queue_start(int lh, int len, int n_prompts, 
     return (uint32_t)lh * (uint32_t)len + (uint32_t)n_prompts * ((uint32_t)(lh + kDies - 1 - x) / kDies);
 }
 
+// Adds the block totals of one (layer, head, prompt) unit up and stores the unit's sum; called by a whole
+// workgroup of 64 * NW threads.  thread = (slice, 4 dims): slice s adds blocks s, s + NS, s + 2 NS, ... in that
+// order, then the slices are added in order, so the order of the additions depends on the shape only and
+// every caller gets the same bits.  WAIT: the block totals may still be on their way; a thread keeps polling
+// the words it has not seen written yet, at most spin_limit times (0: do not even look), and if any thread
+// gives up nothing is stored and the call returns false.  part: LDS, 64 * NW / (D / 4) * D floats.
+template <int D, int NW, bool WAIT>
+__device__ __forceinline__ bool add_unit_up(const float *bsum_unit, int unblk, float *ssum_unit, float *part,
+                                            uint32_t spin_limit)
+{
+    const __amdgpu_buffer_rsrc_t brs = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(bsum_unit), 0,
+                                                                         unblk * D * 4, 0x00020000);
+    constexpr int VPR = D / 4, NS = 64 * NW / VPR, KB = 16;
+    const int vec = threadIdx.x % VPR, slice = threadIdx.x / VPR;
+    float4 tot = make_float4(0.f, 0.f, 0.f, 0.f);
+    uint32_t spins = 0;
+    bool gave_up = WAIT && spin_limit == 0u;
+    for (int b0 = slice; b0 < unblk && !gave_up; b0 += KB * NS) {
+        u32x4 v[KB];
+#pragma unroll
+        for (int i = 0; i < KB; ++i) v[i] = u32x4{kUnwritten, kUnwritten, kUnwritten, kUnwritten};
+        for (;;) {
+            bool ok = true;
+#pragma unroll
+            for (int i = 0; i < KB; ++i)                              // blocks past the end read as zeros
+                if (!all_written(v[i])) v[i] = agent_load16(brs, ((b0 + i * NS) * D + vec * 4) * 4);
+            if (!WAIT) break;
+#pragma unroll
+            for (int i = 0; i < KB; ++i) ok = ok && all_written(v[i]);
+            if (ok) break;
+            if (++spins > spin_limit) {
+                gave_up = true;
+                break;
+            }
+            __builtin_amdgcn_s_sleep(4);
+        }
+#pragma unroll
+        for (int i = 0; i < KB; ++i) {
+            tot.x += __uint_as_float(v[i].x); tot.y += __uint_as_float(v[i].y);
+            tot.z += __uint_as_float(v[i].z); tot.w += __uint_as_float(v[i].w);
+        }
+    }
+    if (WAIT && __syncthreads_or(gave_up)) return false;
+    reinterpret_cast<float4 *>(part)[slice * VPR + vec] = tot;
+    __syncthreads();
+    if (threadIdx.x < VPR) {
+        float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+        for (int sl = 0; sl < NS; ++sl) {
+            const float4 q = reinterpret_cast<const float4 *>(part)[sl * VPR + vec];
+            t.x += q.x; t.y += q.y; t.z += q.z; t.w += q.w;
+        }
+        const __amdgpu_buffer_rsrc_t out = __builtin_amdgcn_make_buffer_rsrc(ssum_unit, 0, D * 4, 0x00020000);
+        agent_store16(out, vec * 16, t.x, t.y, t.z, t.w);
+    }
+    return true;
+}
+
 // NW wavefronts = chunks per block.  grid: one workgroup per (layer*head, block), 1-D.
 template <int D, int NW, bool FUSED>
 __global__ __launch_bounds__(64 * NW, 3)
 void scan_kernel(const uint16_t *__restrict__ keys, PromptTab tab, float *__restrict__ a_raw,
                  float *__restrict__ bsum, float *__restrict__ ssum, uint32_t *__restrict__ sync, int LH,
-                 int64_t rows, int poll_limit)
+                 int64_t rows, int poll_limit, uint32_t spin_limit)
 {
     constexpr int LPR = D / 8, SG = 64 / LPR, TPT = LPR;
     constexpr int HT = (TPT + NW - 1) / NW;                           // halo tokens per lane
@@ -358,56 +418,13 @@ void scan_kernel(const uint16_t *__restrict__ keys, PromptTab tab, float *__rest
         blk = s_blk;
         if (lh < 0) return;                                           // more workgroups than tickets: cannot happen
         if (s_sum >= 0) {                                             // uniform: this workgroup adds a unit up
-            // thread = (slice, 4 dims): slice s adds blocks s, s + NS, s + 2 NS, ..., KB of them per round;
-            // the slices are then added in order.  The order depends on the shape only.  A thread keeps
-            // polling only the words it has not seen written yet.
             const int p = s_sum;
-            const int unblk = tab.blk_off[p + 1] - tab.blk_off[p];
-            const __amdgpu_buffer_rsrc_t brs = __builtin_amdgcn_make_buffer_rsrc(
-                bsum + ((int64_t)lh * nblk + tab.blk_off[p]) * D, 0, unblk * D * 4, 0x00020000);
-            constexpr int VPR = D / 4, NS = 64 * NW / VPR, KB = 16;
-            const int vec = threadIdx.x % VPR, slice = threadIdx.x / VPR;
-            float4 tot = make_float4(0.f, 0.f, 0.f, 0.f);
-            uint32_t spins = 0;
-            for (int b0 = slice; b0 < unblk; b0 += KB * NS) {
-                u32x4 v[KB];
-#pragma unroll
-                for (int i = 0; i < KB; ++i) v[i] = u32x4{kUnwritten, kUnwritten, kUnwritten, kUnwritten};
-                for (;;) {
-                    bool ok = true;
-#pragma unroll
-                    for (int i = 0; i < KB; ++i)                      // blocks past the end read as zeros
-                        if (!all_written(v[i])) v[i] = agent_load16(brs, ((b0 + i * NS) * D + vec * 4) * 4);
-#pragma unroll
-                    for (int i = 0; i < KB; ++i) ok = ok && all_written(v[i]);
-                    if (ok) break;
-                    if (++spins > kSpinLimit) {
-                        atomicAdd(sync + kTimeoutWord, 1u);
-                        break;
-                    }
-                    __builtin_amdgcn_s_sleep(4);
-                }
-#pragma unroll
-                for (int i = 0; i < KB; ++i) {
-                    tot.x += __uint_as_float(v[i].x); tot.y += __uint_as_float(v[i].y);
-                    tot.z += __uint_as_float(v[i].z); tot.w += __uint_as_float(v[i].w);
-                }
-            }
-            float *part = &lds_T[0][0][0];                            // NS * D floats fit (see the static_assert)
-            static_assert(NS * D <= NW * SG * D, "partial sums of the unit do not fit the LDS scratch");
-            reinterpret_cast<float4 *>(part)[slice * VPR + vec] = tot;
-            __syncthreads();
-            if (threadIdx.x < VPR) {
-                float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
-#pragma unroll
-                for (int sl = 0; sl < NS; ++sl) {
-                    const float4 q = reinterpret_cast<const float4 *>(part)[sl * VPR + vec];
-                    t.x += q.x; t.y += q.y; t.z += q.z; t.w += q.w;
-                }
-                const __amdgpu_buffer_rsrc_t out = __builtin_amdgcn_make_buffer_rsrc(
-                    ssum + ((int64_t)lh * tab.n + p) * D, 0, D * 4, 0x00020000);
-                agent_store16(out, vec * 16, t.x, t.y, t.z, t.w);
-            }
+            static_assert(64 * NW / (D / 4) * D <= NW * SG * D, "partial sums of the unit do not fit the LDS scratch");
+            if (!add_unit_up<D, NW, true>(bsum + ((int64_t)lh * nblk + tab.blk_off[p]) * D,
+                                          tab.blk_off[p + 1] - tab.blk_off[p], ssum + ((int64_t)lh * tab.n + p) * D,
+                                          &lds_T[0][0][0], spin_limit) &&
+                threadIdx.x == 0)
+                atomicAdd(sync + kTimeoutWord, 1u);
             return;
         }
     } else {
@@ -753,6 +770,24 @@ __global__ __launch_bounds__(64 * NW) void deferred_stable_kernel(const uint16_t
     }
 }
 
+// Unit sums that the scan left unwritten (its summing workgroup gave up waiting, which the scheduling of
+// workgroups makes possible in principle): formed here, after the scan, from the block totals, with the
+// additions in the same order.  grid: one workgroup of 64 * NW threads per (layer*head, prompt).
+template <int D, int NW>
+__global__ __launch_bounds__(64 * NW) void unit_sum_repair_kernel(const float *__restrict__ bsum, PromptTab tab,
+                                                                  float *__restrict__ ssum)
+{
+    __shared__ float part[64 * NW / (D / 4) * D];
+    const int lh = blockIdx.x / tab.n, p = blockIdx.x - lh * tab.n;
+    float *ssum_unit = ssum + ((int64_t)lh * tab.n + p) * D;
+    bool missing = false;
+    for (int i = threadIdx.x; i < D; i += 64 * NW) missing = missing || __float_as_uint(ssum_unit[i]) == kUnwritten;
+    if (!__syncthreads_or(missing)) return;
+    const int nblk = tab.blk_off[tab.n];
+    add_unit_up<D, NW, false>(bsum + ((int64_t)lh * nblk + tab.blk_off[p]) * D, tab.blk_off[p + 1] - tab.blk_off[p],
+                              ssum_unit, part, 0u);
+}
+
 // 16-byte fill, grid-stride
 __global__ __launch_bounds__(256) void fill_kernel(uint4 *p, size_t n16, uint32_t value)
 {
@@ -815,11 +850,12 @@ __global__ __launch_bounds__(256) void stable_kernel(const uint16_t *__restrict_
 
 template <int D, int NW, bool FUSED>
 void launch_scan(const uint16_t *keys, int LH, const PromptTab &tab, float *a_raw, float *bsum, float *ssum,
-                 uint32_t *sync, int poll_limit, hipStream_t st)
+                 uint32_t *sync, int poll_limit, uint32_t spin_limit, hipStream_t st)
 {
     const int64_t rows = (int64_t)LH * tab.T;
     const unsigned groups = (unsigned)(tab.blk_off[tab.n] * LH + (FUSED ? tab.n * LH : 0));    // + one per unit sum
-    scan_kernel<D, NW, FUSED><<<groups, 64 * NW, 0, st>>>(keys, tab, a_raw, bsum, ssum, sync, LH, rows, poll_limit);
+    scan_kernel<D, NW, FUSED><<<groups, 64 * NW, 0, st>>>(keys, tab, a_raw, bsum, ssum, sync, LH, rows, poll_limit,
+                                                          spin_limit);
 }
 
 template <int D, int NW, bool FUSED> int resident_workgroups()
@@ -846,7 +882,8 @@ hipError_t run_nw(const uint16_t *keys, int LH, const PromptTab &tab, float *a_r
     // fused only if the chip can hold two units' worth of workgroups at once (see the header comment)
     // (ticket arithmetic is 32-bit: keep the number of tickets far below 2^32 / 8)
     const int64_t tickets = (int64_t)LH * (tab.blk_off[tab.n] + tab.n);
-    const bool allow_fused = mode != kScanTwoPass, defer_all = mode == kScanDeferAll;
+    const bool allow_fused = mode != kScanTwoPass, no_unit_sums = mode == kScanRepairAll;
+    const bool defer_all = mode == kScanDeferAll || no_unit_sums;
     const bool fused = allow_fused && tickets < (1ll << 28) && 2 * max_unit_blocks <= resident_workgroups<D, NW, true>();
     if (fused) {
         // tickets and timeouts start at zero, block totals and unit sums as "unwritten"
@@ -856,13 +893,14 @@ hipError_t run_nw(const uint16_t *keys, int LH, const PromptTab &tab, float *a_r
         fill_kernel<<<(unsigned)min((ns + 255) / 256, (size_t)2048), 256, 0, st>>>((uint4 *)ssum, ns, kUnwritten);
         prof.begin(NKV_KERNEL_SCAN, st);
         launch_scan<D, NW, true>(keys, LH, tab, a_raw, bsum, ssum, (uint32_t *)sync_area,
-                                 defer_all ? -1 : kPollLimit, st);
+                                 defer_all ? -1 : kPollLimit, no_unit_sums ? 0u : kSpinLimit, st);
         prof.end(NKV_KERNEL_SCAN, st);
+        unit_sum_repair_kernel<D, NW><<<LH * tab.n, 64 * NW, 0, st>>>(bsum, tab, ssum);
         deferred_stable_kernel<D, NW><<<defer_all ? 4096 : 256, 64 * NW, 0, st>>>(keys, tab, ssum,
                                                                                   (const uint32_t *)sync_area, a_raw);
     } else {
         prof.begin(NKV_KERNEL_SCAN, st);
-        launch_scan<D, NW, false>(keys, LH, tab, a_raw, bsum, ssum, nullptr, 0, st);
+        launch_scan<D, NW, false>(keys, LH, tab, a_raw, bsum, ssum, nullptr, 0, 0u, st);
         prof.end(NKV_KERNEL_SCAN, st);
         ssum_kernel<D><<<dim3(tab.n, LH), D, 0, st>>>(bsum, tab, ssum);
         stable_kernel<D><<<dim3((tab.T + 255) / 256, LH), 256, 0, st>>>(keys, tab, ssum, a_raw);

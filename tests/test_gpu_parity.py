@@ -191,6 +191,7 @@ def test_generic_and_streaming_kernels_agree_with_oracle():
     compare_end_to_end(w, K, V, 0.5, params=nkv.params_default(flags=nkv.FLAG_GENERIC_KERNELS), label="generic")
     compare_end_to_end(w, K, V, 0.5, params=nkv.params_default(flags=nkv.FLAG_TWO_PASS_STABLE), label="two-pass")
     compare_end_to_end(w, K, V, 0.5, params=nkv.params_default(flags=nkv.FLAG_DEFER_STABLE), label="deferred")
+    compare_end_to_end(w, K, V, 0.5, params=nkv.params_default(flags=nkv.FLAG_NO_UNIT_SUMS), label="no unit sums")
     compare_end_to_end(w, K, V, 0.5, label="default")
 
 
@@ -261,6 +262,9 @@ def test_deferred_stable_route_gives_the_same_bits():
         a, _ = run_gpu(w, K, V, 0.6)
         b, _ = run_gpu(w, K, V, 0.6, params=nkv.params_default(flags=nkv.FLAG_DEFER_STABLE))
         assert torch.equal(a.scores, b.scores) and torch.equal(a.kept_idx, b.kept_idx)
+        # and a unit sum that the pass itself did not form is filled in afterwards, with the same bits
+        c, _ = run_gpu(w, K, V, 0.6, params=nkv.params_default(flags=nkv.FLAG_NO_UNIT_SUMS))
+        assert torch.equal(a.scores, c.scores) and torch.equal(a.kept_idx, c.kept_idx)
 
 
 def test_ragged_batch_is_reproducible():
