@@ -56,6 +56,8 @@ def main():
     ap.add_argument("--cpu-layers", type=int, default=0, help="layers the oracle is timed on (0 = choose)")
     ap.add_argument("--generic", action="store_true", help="force the shape-generic scoring kernels")
     ap.add_argument("--two-pass", action="store_true", help="stable anomaly in a second pass over the keys")
+    ap.add_argument("--per-layer", action="store_true",
+                    help="a step is L passes with L = 1, one per layer's K/V slice, as a prefill loop would call it")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no sharding, no collectives); use --gpus 1", file=sys.stderr)
@@ -75,32 +77,39 @@ def main():
     params = nkv.params_default(flags=(nkv.FLAG_GENERIC_KERNELS if args.generic else 0)
                                 | (nkv.FLAG_TWO_PASS_STABLE if args.two_pass else 0))
     r_list = [r] * shape.n_prompts
-    comp = nkv.Compressor(shape, r_list, params)
+    if args.per_layer:
+        shape1 = nkv.Shape(1, w.H, w.d, w.d_v, shape.dtype, w.cu_seqlens)
+        calls = [(nkv.Compressor(shape1, r_list, params), K[l], V[l]) for l in range(w.L)]
+    else:
+        calls = [(nkv.Compressor(shape, r_list, params), K, V)]
     stream = torch.cuda.current_stream()
-
     for _ in range(args.warmup):
-        comp.run(K, V, stream)
+        for comp, Kc, Vc in calls:
+            comp.run(Kc, Vc, stream)
     torch.cuda.synchronize()
 
     # timed region: K steps, every kernel of interest bracketed by its own event pair
-    evs = [{name: (nkv.HipEvent(), nkv.HipEvent()) for name in nkv.KERNELS} for _ in range(args.steps)]
+    evs = [[{name: (nkv.HipEvent(), nkv.HipEvent()) for name in nkv.KERNELS} for _ in calls]
+           for _ in range(args.steps)]
     step_ev = [(nkv.HipEvent(), nkv.HipEvent()) for _ in range(args.steps)]
-    base_params = comp.params
+    base_params = params
+    timed = [[nkv.with_kernel_timers(base_params, evs[i][c]) for c in range(len(calls))] for i in range(args.steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
-        comp.params = nkv.with_kernel_timers(base_params, evs[i])
         step_ev[i][0].record(stream)
-        comp.run(K, V, stream)
+        for c, (comp, Kc, Vc) in enumerate(calls):
+            comp.params = timed[i][c]
+            comp.run(Kc, Vc, stream)
         step_ev[i][1].record(stream)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
-    comp.params = base_params
 
     ms_per_step = wall * 1e3 / args.steps
     step_ms = [a.elapsed_ms(b) for a, b in step_ev]
-    kern_ms = {name: statistics.fmean(evs[i][name][0].elapsed_ms(evs[i][name][1]) for i in range(args.steps))
-               for name in nkv.KERNELS}
+    # per step: a kernel's launches added up over the step's calls
+    kern_ms = {name: statistics.fmean(sum(e[name][0].elapsed_ms(e[name][1]) for e in evs[i])
+                                      for i in range(args.steps)) for name in nkv.KERNELS}
     tokens = w.T
     value = tokens / (wall / args.steps)
 
@@ -111,7 +120,7 @@ def main():
     achieved = ab[dominant] * head_tokens / (kern_ms[dominant] * 1e-3) / 1e9
     roofline = {"bound": "hbm", "kernel": dominant, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": read_traffic(dominant, w.name),
+                "traffic": None if args.per_layer else read_traffic(dominant, w.name),
                 "bytes_per_launch": ab[dominant] * head_tokens,
                 "kernel_ms": {k: round(v, 4) for k, v in kern_ms.items()},
                 "whole_pass": {"algorithmic_bytes": ab["total"] * head_tokens,
@@ -168,6 +177,7 @@ def main():
            "config": {"workload": f"{w.name}: {w.L} layers x {w.H} KV heads x {list(w.prompt_lens)} tokens x d={w.d}, "
                                   f"{w.dtype} K/V, r={r}", "ratio": r, "kv_dtype": w.dtype,
                       "scoring_kernels": "generic" if args.generic else "default",
+                      "calls_per_step": len(calls),
                       "inputs": nkv_inputs.recipe(w)},
            "roofline": roofline, "cpu_baseline": cpu}
     print(json.dumps(out))

@@ -116,6 +116,16 @@ typedef struct nkv_shape {
     int32_t dtype;            /* NKV_DTYPE_* of keys and values                      */
     int32_t n_prompts;        /* 1..NKV_MAX_PROMPTS                                  */
     const int32_t *cu_seqlens;/* HOST, n_prompts + 1 entries, cu[0] = 0, increasing  */
+    /* Where the rows of keys / values lie.  NULL: dense [L][H][T][d] (values [L][H][T][dv]), the prompts */
+    /* of a head concatenated along the token axis.  Otherwise HOST, 3 entries {layer, head, prompt} in   */
+    /* elements: token n of prompt p, head h, layer l starts at                                            */
+    /*     l * layer + h * head + p * prompt + n * d         if prompt != 0 (one slab per prompt),         */
+    /*     l * layer + h * head + (cu_seqlens[p] + n) * d    if prompt == 0 (concatenated prompts).        */
+    /* A unit's rows are contiguous in either case.  A cache tensor [B][H][N_max][d] of one layer is       */
+    /* {0, N_max*d, H*N_max*d} with L = 1.  Entries must be multiples of 16 bytes and units must not       */
+    /* overlap (NKV_EINVAL).  scores, a_raw and the packed outputs keep their dense layouts.               */
+    const int64_t *key_strides;
+    const int64_t *value_strides;
 } nkv_shape;
 
 /* Fills *p with the paper's constants.  Returns NKV_EINVAL if p is NULL. */

@@ -40,7 +40,8 @@ class nkv_params(C.Structure):
 
 class nkv_shape(C.Structure):
     _fields_ = [("L", C.c_int32), ("H", C.c_int32), ("d", C.c_int32), ("dv", C.c_int32), ("dtype", C.c_int32),
-                ("n_prompts", C.c_int32), ("cu_seqlens", C.POINTER(C.c_int32))]
+                ("n_prompts", C.c_int32), ("cu_seqlens", C.POINTER(C.c_int32)),
+                ("key_strides", C.POINTER(C.c_int64)), ("value_strides", C.POINTER(C.c_int64))]
 
 
 class NkvError(RuntimeError):
@@ -125,11 +126,17 @@ def m_p(N: int, top_frac: float = 0.10) -> int:
 
 
 class Shape:
-    """Host-side description of keys[L][H][T][d] / values[L][H][T][dv] holding one or more prompts."""
+    """Host-side description of keys[L][H][T][d] / values[L][H][T][dv] holding one or more prompts.
+    ``key_strides`` / ``value_strides``: None for the dense layout, else (layer, head, prompt) strides in
+    elements as ``nkv_shape`` in nkv.h defines them."""
 
-    def __init__(self, L: int, H: int, d: int, dv: int, dtype: int, cu_seqlens: Sequence[int]):
+    def __init__(self, L: int, H: int, d: int, dv: int, dtype: int, cu_seqlens: Sequence[int],
+                 key_strides: Optional[Sequence[int]] = None, value_strides: Optional[Sequence[int]] = None):
         self.cu = (C.c_int32 * len(cu_seqlens))(*[int(x) for x in cu_seqlens])
-        self.c = nkv_shape(int(L), int(H), int(d), int(dv), int(dtype), len(cu_seqlens) - 1, self.cu)
+        self.ks = None if key_strides is None else (C.c_int64 * 3)(*[int(x) for x in key_strides])
+        self.vs = None if value_strides is None else (C.c_int64 * 3)(*[int(x) for x in value_strides])
+        self.c = nkv_shape(int(L), int(H), int(d), int(dv), int(dtype), len(cu_seqlens) - 1, self.cu,
+                           self.ks, self.vs)
         self.L, self.H, self.d, self.dv, self.dtype = int(L), int(H), int(d), int(dv), int(dtype)
         self.n_prompts = len(cu_seqlens) - 1
         self.T = int(cu_seqlens[-1])

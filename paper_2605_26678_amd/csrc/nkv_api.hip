@@ -26,6 +26,49 @@ int check_params(const nkv_params *p)
     return NKV_OK;
 }
 
+int esize_of(int dtype) { return dtype == NKV_DTYPE_F32 ? 4 : 2; }
+
+// strides: NULL (dense [L][H][T][row]) or {layer, head, prompt} in elements
+int fill_map(const nkv_shape *s, const int64_t *strides, int row, RowMap *m)
+{
+    const int64_t T = s->cu_seqlens[s->n_prompts];
+    m->H = s->H;
+    m->d = row;
+    if (!strides) {
+        m->layer = (int64_t)s->H * T * row;
+        m->head = T * row;
+        m->prompt = 0;
+        return NKV_OK;
+    }
+    const int epv = 16 / esize_of(s->dtype);
+    for (int i = 0; i < 3; ++i)
+        if (strides[i] < 0 || strides[i] % epv) return NKV_EINVAL;
+    // a slab must hold its unit: the longest prompt for per-prompt slabs, all prompts for concatenated ones
+    int64_t nmax = 0;
+    for (int p = 0; p < s->n_prompts; ++p)
+        nmax = nmax > s->cu_seqlens[p + 1] - s->cu_seqlens[p] ? nmax : s->cu_seqlens[p + 1] - s->cu_seqlens[p];
+    // No two units may overlap: with the axes of extent > 1 ordered by stride, each stride must cover the
+    // whole extent of the axis below it (the innermost one a unit's rows).
+    int64_t st[3] = {strides[0], strides[1], strides[2]}, ext[3] = {s->L, s->H, strides[2] ? s->n_prompts : 1};
+    for (int i = 0; i < 3; ++i)
+        for (int j = i + 1; j < 3; ++j)
+            if (st[j] < st[i]) {
+                const int64_t a = st[i], e = ext[i];
+                st[i] = st[j]; ext[i] = ext[j];
+                st[j] = a; ext[j] = e;
+            }
+    int64_t cover = (strides[2] ? nmax : T) * row;
+    for (int i = 0; i < 3; ++i) {
+        if (ext[i] <= 1) continue;
+        if (st[i] < cover) return NKV_EINVAL;
+        cover = st[i] * ext[i];
+    }
+    m->layer = strides[0];
+    m->head = strides[1];
+    m->prompt = strides[2];
+    return NKV_OK;
+}
+
 int check_shape(const nkv_shape *s)
 {
     if (!s || !s->cu_seqlens) return NKV_EINVAL;
@@ -40,10 +83,11 @@ int check_shape(const nkv_shape *s)
     const int64_t T = s->cu_seqlens[s->n_prompts];
     if ((int64_t)s->H * T >= (1ll << 31)) return NKV_ESHAPE;          // per-layer counters are 32-bit
     if ((int64_t)s->L * s->H * T >= (1ll << 40)) return NKV_ESHAPE;
-    return NKV_OK;
+    RowMap m;
+    int rc = fill_map(s, s->key_strides, s->d, &m);
+    if (rc) return rc;
+    return fill_map(s, s->value_strides, s->dv, &m);
 }
-
-int esize_of(int dtype) { return dtype == NKV_DTYPE_F32 ? 4 : 2; }
 
 void fill_tab(const nkv_shape *s, const nkv_params *p, PromptTab *tab)
 {
@@ -96,15 +140,18 @@ int run_raw(const void *keys, const nkv_shape *s, const nkv_params *p, const Pro
 {
     const int LH = s->L * s->H;
     const Prof prof{p->prof_start, p->prof_stop};
+    RowMap km;
+    const int rc = fill_map(s, s->key_strides, s->d, &km);
+    if (rc) return rc;
     hipError_t e;
     if (!(p->flags & NKV_FLAG_GENERIC_KERNELS) && fast_score_supported(s->dtype, s->d, p->window, tab))
-        e = launch_score_fast(keys, LH, s->d, tab, a_raw, (float *)(ws + lay.bsum), (float *)(ws + lay.ssum),
+        e = launch_score_fast(keys, km, LH, s->d, tab, a_raw, (float *)(ws + lay.bsum), (float *)(ws + lay.ssum),
                               ws + lay.sync,
                               (p->flags & NKV_FLAG_TWO_PASS_STABLE)  ? kScanTwoPass
                               : (p->flags & NKV_FLAG_NO_UNIT_SUMS)  ? kScanRepairAll
                               : (p->flags & NKV_FLAG_DEFER_STABLE)  ? kScanDeferAll : kScanFused, prof, st);
     else
-        e = launch_score_generic(keys, s->dtype, LH, s->d, p->window, tab, a_raw, (float *)(ws + lay.rnorm),
+        e = launch_score_generic(keys, km, s->dtype, LH, s->d, p->window, tab, a_raw, (float *)(ws + lay.rnorm),
                                  (float *)(ws + lay.bsum), (float *)(ws + lay.ssum), prof, st);
     return e == hipSuccess ? NKV_OK : NKV_EHIP;
 }
@@ -289,7 +336,12 @@ int nkv_select_compact(const void *keys, const void *values, const float *scores
         return NKV_EINVAL;
     PromptTab tab;
     fill_tab(shape, params, &tab);
-    return launch_select_compact(keys, values, scores, k_per_head, shape->L, shape->H, shape->d, shape->dv,
+    RowMap km, vm;
+    rc = fill_map(shape, shape->key_strides, shape->d, &km);
+    if (rc) return rc;
+    rc = fill_map(shape, shape->value_strides, shape->dv, &vm);
+    if (rc) return rc;
+    return launch_select_compact(keys, values, km, vm, scores, k_per_head, shape->L, shape->H, shape->d, shape->dv,
                                  esize_of(shape->dtype), tab, (float)params->near_tol, packed_k, packed_v,
                                  kept_idx, head_off, row_capacity, near_threshold_count,
                                  Prof{params->prof_start, params->prof_stop}, (hipStream_t)hip_stream) == hipSuccess

@@ -20,6 +20,20 @@ struct PromptTab {
     int32_t m_safe[NKV_MAX_PROMPTS];         // filled for nkv_budget only
 };
 
+// Where the rows of a (layer, head, prompt) unit start inside the keys (or values) tensor, in elements.
+// The rows of a unit are always contiguous (row n at +n*d).  prompt == 0: the prompts of a head are
+// concatenated along the token axis (unit p starts tok_off[p] rows into the head); otherwise every prompt has
+// its own slab and unit p starts p * prompt elements into the head.
+struct RowMap {
+    int64_t layer, head, prompt;
+    int32_t H, d;
+    __host__ __device__ int64_t unit(int lh, int p, const PromptTab &tab) const
+    {
+        const int l = lh / H, h = lh - l * H;
+        return l * layer + h * head + (prompt != 0 ? p * prompt : (int64_t)tab.tok_off[p] * d);
+    }
+};
+
 // Scalars of the outer learner in the precision the kernels use them.
 struct LearnerConsts {
     double log_prior[3];
@@ -46,7 +60,7 @@ constexpr float kEps = 1e-12f;    // clamp of vector norms
 constexpr float kFlat = 1e-6f;    // a min-max range below this carries no ranking
 
 // ---- scoring, shape-generic kernels (any d multiple of 8, any window / block size, fp32 or bf16) ----
-hipError_t launch_score_generic(const void *keys, int dtype, int LH, int d, int window, const PromptTab &tab,
+hipError_t launch_score_generic(const void *keys, const RowMap &km, int dtype, int LH, int d, int window, const PromptTab &tab,
                                 float *a_raw, float *rnorm, float *bsum, float *ssum, const Prof &prof,
                                 hipStream_t st);
 
@@ -56,7 +70,7 @@ size_t fast_score_sync_bytes(int LH, const PromptTab &tab);
 // How the stable anomaly is obtained.  kScanDeferAll: fused pass, but every block takes the deferred route;
 // kScanRepairAll: in addition no unit sum is formed inside the pass, all come from the repair kernel.
 enum { kScanFused = 0, kScanTwoPass = 1, kScanDeferAll = 2, kScanRepairAll = 3 };
-hipError_t launch_score_fast(const void *keys, int LH, int d, const PromptTab &tab, float *a_raw,
+hipError_t launch_score_fast(const void *keys, const RowMap &km, int LH, int d, const PromptTab &tab, float *a_raw,
                              float *bsum, float *ssum, void *sync_area, int mode, const Prof &prof,
                              hipStream_t st);
 
@@ -87,7 +101,8 @@ hipError_t launch_budget(const float *scores, int L, int H, const PromptTab &tab
                          const Prof &prof, hipStream_t st);
 
 // ---- selection, ordered compaction, gather ----
-hipError_t launch_select_compact(const void *keys, const void *values, const float *scores,
+hipError_t launch_select_compact(const void *keys, const void *values, const RowMap &km, const RowMap &vm,
+                                 const float *scores,
                                  const int32_t *k_per_head, int L, int H, int d, int dv, int esize,
                                  const PromptTab &tab, float near_tol, void *packed_k, void *packed_v,
                                  int32_t *kept_idx, int64_t *head_off, int64_t row_capacity,

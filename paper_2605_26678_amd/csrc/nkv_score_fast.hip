@@ -364,7 +364,7 @@ __device__ __forceinline__ bool add_unit_up(const float *bsum_unit, int unblk, f
 // NW wavefronts = chunks per block.  grid: one workgroup per (layer*head, block), 1-D.
 template <int D, int NW, bool FUSED>
 __global__ __launch_bounds__(64 * NW, 3)
-void scan_kernel(const uint16_t *__restrict__ keys, PromptTab tab, float *__restrict__ a_raw,
+void scan_kernel(const uint16_t *__restrict__ keys, RowMap km, PromptTab tab, float *__restrict__ a_raw,
                  float *__restrict__ bsum, float *__restrict__ ssum, uint32_t *__restrict__ sync, int LH,
                  int64_t rows, int poll_limit, uint32_t spin_limit)
 {
@@ -447,7 +447,7 @@ void scan_kernel(const uint16_t *__restrict__ keys, PromptTab tab, float *__rest
     // the prompt that lie outside this block get weight 0 below.
     constexpr int kRowBytes = D * 2;
     const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<uint16_t *>(keys) + row0 * D, 0, N * kRowBytes, 0x00020000);
+        const_cast<uint16_t *>(keys) + km.unit(lh, p, tab), 0, N * kRowBytes, 0x00020000);
     const int lane_off = t0 * kRowBytes + c * 16;
     u32x4 raw[TPT], hraw[HT];
 #pragma unroll
@@ -720,7 +720,8 @@ void scan_kernel(const uint16_t *__restrict__ keys, PromptTab tab, float *__rest
 // time, one wave per chunk, same lane layout, same instruction sequences for the norm, the dot and the
 // cosine as scan_kernel, so the values are the ones scan_kernel would have stored.
 template <int D, int NW>
-__global__ __launch_bounds__(64 * NW) void deferred_stable_kernel(const uint16_t *__restrict__ keys, PromptTab tab,
+__global__ __launch_bounds__(64 * NW) void deferred_stable_kernel(const uint16_t *__restrict__ keys, RowMap km,
+                                                                  PromptTab tab,
                                                                   const float *__restrict__ ssum,
                                                                   const uint32_t *__restrict__ sync,
                                                                   float *__restrict__ a_raw)
@@ -737,7 +738,7 @@ __global__ __launch_bounds__(64 * NW) void deferred_stable_kernel(const uint16_t
         const int blk_lo = (blk - tab.blk_off[p]) * b, blk_hi = min(blk_lo + b, N);
         const int64_t row0 = (int64_t)lh * tab.T + tab.tok_off[p];
         const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
-            const_cast<uint16_t *>(keys) + row0 * D, 0, N * kRowBytes, 0x00020000);
+            const_cast<uint16_t *>(keys) + km.unit(lh, p, tab), 0, N * kRowBytes, 0x00020000);
         const int lane_off = (blk_lo + 64 * w + g * TPT) * kRowBytes + c * 16;
         u32x4 raw[TPT];
 #pragma unroll
@@ -808,7 +809,7 @@ __global__ __launch_bounds__(D) void ssum_kernel(const float *__restrict__ bsum,
 
 // Stable anomaly a_s by a second touch of the keys.  grid (ceil(T/256), L*H), 4 waves of 64 tokens.
 template <int D>
-__global__ __launch_bounds__(256) void stable_kernel(const uint16_t *__restrict__ keys, PromptTab tab,
+__global__ __launch_bounds__(256) void stable_kernel(const uint16_t *__restrict__ keys, RowMap km, PromptTab tab,
                                                      const float *__restrict__ ssum, float *__restrict__ a_raw)
 {
     constexpr int LPR = D / 8, TPT = LPR;
@@ -817,15 +818,15 @@ __global__ __launch_bounds__(256) void stable_kernel(const uint16_t *__restrict_
     const int g = lane / LPR, c = lane % LPR;
     const int tg0 = blockIdx.x * 256 + wv * 64;                      // first global token of this wave
     if (tg0 >= tab.T) return;
-    const uint4 *kbase = reinterpret_cast<const uint4 *>(keys) + (int64_t)lh * tab.T * LPR;
     float sd_m = 0.f, ss_m = 0.f, sq_m = 1.f;
 #pragma unroll
     for (int j = 0; j < TPT; ++j) {
         const int tg = tg0 + g * TPT + j;
         const bool ok = tg < tab.T;
-        const uint4 r4 = ok ? kbase[(int64_t)tg * LPR + c] : make_uint4(0u, 0u, 0u, 0u);
-        const u32x4 raw = {r4.x, r4.y, r4.z, r4.w};
         const int p = prompt_of_token(tab, ok ? tg : tab.T - 1);
+        const uint4 *row = reinterpret_cast<const uint4 *>(keys + km.unit(lh, p, tab) + (int64_t)(tg - tab.tok_off[p]) * D);
+        const uint4 r4 = ok ? row[c] : make_uint4(0u, 0u, 0u, 0u);
+        const u32x4 raw = {r4.x, r4.y, r4.z, r4.w};
         float sv[8], k[8];
         load8(ssum + ((int64_t)lh * tab.n + p) * D + c * 8, sv);
         unpack8(raw, k);
@@ -849,12 +850,12 @@ __global__ __launch_bounds__(256) void stable_kernel(const uint16_t *__restrict_
 }
 
 template <int D, int NW, bool FUSED>
-void launch_scan(const uint16_t *keys, int LH, const PromptTab &tab, float *a_raw, float *bsum, float *ssum,
+void launch_scan(const uint16_t *keys, const RowMap &km, int LH, const PromptTab &tab, float *a_raw, float *bsum, float *ssum,
                  uint32_t *sync, int poll_limit, uint32_t spin_limit, hipStream_t st)
 {
     const int64_t rows = (int64_t)LH * tab.T;
     const unsigned groups = (unsigned)(tab.blk_off[tab.n] * LH + (FUSED ? tab.n * LH : 0));    // + one per unit sum
-    scan_kernel<D, NW, FUSED><<<groups, 64 * NW, 0, st>>>(keys, tab, a_raw, bsum, ssum, sync, LH, rows, poll_limit,
+    scan_kernel<D, NW, FUSED><<<groups, 64 * NW, 0, st>>>(keys, km, tab, a_raw, bsum, ssum, sync, LH, rows, poll_limit,
                                                           spin_limit);
 }
 
@@ -874,7 +875,7 @@ template <int D, int NW, bool FUSED> int resident_workgroups()
 
 
 template <int D, int NW>
-hipError_t run_nw(const uint16_t *keys, int LH, const PromptTab &tab, float *a_raw, float *bsum, float *ssum,
+hipError_t run_nw(const uint16_t *keys, const RowMap &km, int LH, const PromptTab &tab, float *a_raw, float *bsum, float *ssum,
                   void *sync_area, int mode, const Prof &prof, hipStream_t st)
 {
     int max_unit_blocks = 0;
@@ -892,33 +893,33 @@ hipError_t run_nw(const uint16_t *keys, int LH, const PromptTab &tab, float *a_r
         fill_kernel<<<(unsigned)min((nb + 255) / 256, (size_t)2048), 256, 0, st>>>((uint4 *)bsum, nb, kUnwritten);
         fill_kernel<<<(unsigned)min((ns + 255) / 256, (size_t)2048), 256, 0, st>>>((uint4 *)ssum, ns, kUnwritten);
         prof.begin(NKV_KERNEL_SCAN, st);
-        launch_scan<D, NW, true>(keys, LH, tab, a_raw, bsum, ssum, (uint32_t *)sync_area,
+        launch_scan<D, NW, true>(keys, km, LH, tab, a_raw, bsum, ssum, (uint32_t *)sync_area,
                                  defer_all ? -1 : kPollLimit, no_unit_sums ? 0u : kSpinLimit, st);
         prof.end(NKV_KERNEL_SCAN, st);
         unit_sum_repair_kernel<D, NW><<<LH * tab.n, 64 * NW, 0, st>>>(bsum, tab, ssum);
-        deferred_stable_kernel<D, NW><<<defer_all ? 4096 : 256, 64 * NW, 0, st>>>(keys, tab, ssum,
+        deferred_stable_kernel<D, NW><<<defer_all ? 4096 : 256, 64 * NW, 0, st>>>(keys, km, tab, ssum,
                                                                                   (const uint32_t *)sync_area, a_raw);
     } else {
         prof.begin(NKV_KERNEL_SCAN, st);
-        launch_scan<D, NW, false>(keys, LH, tab, a_raw, bsum, ssum, nullptr, 0, 0u, st);
+        launch_scan<D, NW, false>(keys, km, LH, tab, a_raw, bsum, ssum, nullptr, 0, 0u, st);
         prof.end(NKV_KERNEL_SCAN, st);
         ssum_kernel<D><<<dim3(tab.n, LH), D, 0, st>>>(bsum, tab, ssum);
-        stable_kernel<D><<<dim3((tab.T + 255) / 256, LH), 256, 0, st>>>(keys, tab, ssum, a_raw);
+        stable_kernel<D><<<dim3((tab.T + 255) / 256, LH), 256, 0, st>>>(keys, km, tab, ssum, a_raw);
     }
     return hipGetLastError();
 }
 
 template <int D>
-hipError_t run(const uint16_t *keys, int LH, const PromptTab &tab, float *a_raw, float *bsum, float *ssum,
+hipError_t run(const uint16_t *keys, const RowMap &km, int LH, const PromptTab &tab, float *a_raw, float *bsum, float *ssum,
                void *sync_area, int mode, const Prof &prof, hipStream_t st)
 {
     int bmax = 0;
     for (int p = 0; p < tab.n; ++p) bmax = max(bmax, tab.b[p]);
     switch ((bmax + 63) / 64) {
-    case 1: return run_nw<D, 1>(keys, LH, tab, a_raw, bsum, ssum, sync_area, mode, prof, st);
-    case 2: return run_nw<D, 2>(keys, LH, tab, a_raw, bsum, ssum, sync_area, mode, prof, st);
-    case 3: return run_nw<D, 3>(keys, LH, tab, a_raw, bsum, ssum, sync_area, mode, prof, st);
-    default: return run_nw<D, 4>(keys, LH, tab, a_raw, bsum, ssum, sync_area, mode, prof, st);
+    case 1: return run_nw<D, 1>(keys, km, LH, tab, a_raw, bsum, ssum, sync_area, mode, prof, st);
+    case 2: return run_nw<D, 2>(keys, km, LH, tab, a_raw, bsum, ssum, sync_area, mode, prof, st);
+    case 3: return run_nw<D, 3>(keys, km, LH, tab, a_raw, bsum, ssum, sync_area, mode, prof, st);
+    default: return run_nw<D, 4>(keys, km, LH, tab, a_raw, bsum, ssum, sync_area, mode, prof, st);
     }
 }
 
@@ -937,11 +938,11 @@ size_t fast_score_sync_bytes(int LH, const PromptTab &tab)
     return ((size_t)kSyncWords + (size_t)LH * tab.blk_off[tab.n]) * 4;       // counters + the list of deferred blocks
 }
 
-hipError_t launch_score_fast(const void *keys, int LH, int d, const PromptTab &tab, float *a_raw, float *bsum,
+hipError_t launch_score_fast(const void *keys, const RowMap &km, int LH, int d, const PromptTab &tab, float *a_raw, float *bsum,
                              float *ssum, void *sync_area, int mode, const Prof &prof, hipStream_t st)
 {
-    if (d == 128) return run<128>((const uint16_t *)keys, LH, tab, a_raw, bsum, ssum, sync_area, mode, prof, st);
-    return run<64>((const uint16_t *)keys, LH, tab, a_raw, bsum, ssum, sync_area, mode, prof, st);
+    if (d == 128) return run<128>((const uint16_t *)keys, km, LH, tab, a_raw, bsum, ssum, sync_area, mode, prof, st);
+    return run<64>((const uint16_t *)keys, km, LH, tab, a_raw, bsum, ssum, sync_area, mode, prof, st);
 }
 
 }  // namespace nkv

@@ -14,13 +14,15 @@ namespace nkv {
 namespace {
 
 template <typename T>
-__global__ __launch_bounds__(256) void rnorm_kernel(const T *__restrict__ keys, int64_t rows, int d,
-                                                    float *__restrict__ rnorm)
+__global__ __launch_bounds__(256) void rnorm_kernel(const T *__restrict__ keys, RowMap km, PromptTab tab,
+                                                    int64_t rows, int d, float *__restrict__ rnorm)
 {
     const int lane = threadIdx.x & (kWave - 1);
     const int64_t row = (int64_t)blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
     if (row >= rows) return;
-    const T *k = keys + row * d;
+    const int lh = (int)(row / tab.T), tg = (int)(row - (int64_t)lh * tab.T);
+    const int p = prompt_of_token(tab, tg);
+    const T *k = keys + km.unit(lh, p, tab) + (int64_t)(tg - tab.tok_off[p]) * d;
     float ss = 0.f;
     for (int c = lane; c < d; c += kWave) {
         float x = load_elem<T>(k + c);
@@ -32,8 +34,9 @@ __global__ __launch_bounds__(256) void rnorm_kernel(const T *__restrict__ keys, 
 
 // grid (blocks per head, L*H); thread c owns dims c, c+256, ...
 template <typename T>
-__global__ __launch_bounds__(256) void bsum_kernel(const T *__restrict__ keys, const float *__restrict__ rnorm,
-                                                   int d, PromptTab tab, float *__restrict__ bsum)
+__global__ __launch_bounds__(256) void bsum_kernel(const T *__restrict__ keys, RowMap km,
+                                                   const float *__restrict__ rnorm, int d, PromptTab tab,
+                                                   float *__restrict__ bsum)
 {
     const int blk = blockIdx.x, lh = blockIdx.y;
     const int p = prompt_of_block(tab, blk);
@@ -42,9 +45,10 @@ __global__ __launch_bounds__(256) void bsum_kernel(const T *__restrict__ keys, c
     const int lo = (blk - tab.blk_off[p]) * b;
     const int hi = min(lo + b, n);
     const int64_t row0 = (int64_t)lh * tab.T + tab.tok_off[p];
+    const T *unit = keys + km.unit(lh, p, tab);
     for (int c = threadIdx.x; c < d; c += blockDim.x) {
         float s = 0.f;
-        for (int t = lo; t < hi; ++t) s = fmaf(rnorm[row0 + t], load_elem<T>(keys + (row0 + t) * d + c), s);
+        for (int t = lo; t < hi; ++t) s = fmaf(rnorm[row0 + t], load_elem<T>(unit + (int64_t)t * d + c), s);
         bsum[((int64_t)lh * tab.blk_off[tab.n] + blk) * d + c] = s;
     }
 }
@@ -65,7 +69,8 @@ __global__ __launch_bounds__(256) void ssum_kernel(const float *__restrict__ bsu
 
 // One wavefront per token; lane owns dims lane, lane+64, ... (NQ of them).
 template <typename T, int NQ>
-__global__ __launch_bounds__(256) void anomaly_kernel(const T *__restrict__ keys, const float *__restrict__ rnorm,
+__global__ __launch_bounds__(256) void anomaly_kernel(const T *__restrict__ keys, RowMap km,
+                                                      const float *__restrict__ rnorm,
                                                       const float *__restrict__ bsum,
                                                       const float *__restrict__ ssum, int LH, int d, int window,
                                                       PromptTab tab, float *__restrict__ a_raw)
@@ -80,6 +85,7 @@ __global__ __launch_bounds__(256) void anomaly_kernel(const T *__restrict__ keys
     const int i = tg - tab.tok_off[p];
     const int blk = tab.blk_off[p] + i / tab.b[p];
     const int64_t row0 = (int64_t)lh * tab.T + tab.tok_off[p];
+    const T *unit = keys + km.unit(lh, p, tab);
     const float *S = ssum + ((int64_t)lh * tab.n + p) * d;
     const float *Bs = bsum + ((int64_t)lh * tab.blk_off[tab.n] + blk) * d;
 
@@ -88,13 +94,13 @@ __global__ __launch_bounds__(256) void anomaly_kernel(const T *__restrict__ keys
 #pragma unroll
     for (int q = 0; q < NQ; ++q) {
         const int c = lane + q * kWave;
-        kh[q] = c < d ? rn * load_elem<T>(keys + row * d + c) : 0.f;
+        kh[q] = c < d ? rn * load_elem<T>(unit + (int64_t)i * d + c) : 0.f;
         acc[q] = 0.f;
     }
     const int lo = max(0, i - window + 1);
     for (int j = lo; j <= i; ++j) {
         const float rj = rnorm[row0 + j];
-        const T *kj = keys + (row0 + j) * d;
+        const T *kj = unit + (int64_t)j * d;
 #pragma unroll
         for (int q = 0; q < NQ; ++q) {
             const int c = lane + q * kWave;
@@ -125,17 +131,17 @@ __global__ __launch_bounds__(256) void anomaly_kernel(const T *__restrict__ keys
 }
 
 template <typename T>
-hipError_t run(const T *keys, int LH, int d, int window, const PromptTab &tab, float *a_raw, float *rnorm,
+hipError_t run(const T *keys, const RowMap &km, int LH, int d, int window, const PromptTab &tab, float *a_raw, float *rnorm,
                float *bsum, float *ssum, const Prof &prof, hipStream_t st)
 {
     const int64_t rows = (int64_t)LH * tab.T;
     const unsigned row_grid = (unsigned)((rows + 3) / 4);
-    rnorm_kernel<T><<<row_grid, 256, 0, st>>>(keys, rows, d, rnorm);
-    bsum_kernel<T><<<dim3(tab.blk_off[tab.n], LH), 256, 0, st>>>(keys, rnorm, d, tab, bsum);
+    rnorm_kernel<T><<<row_grid, 256, 0, st>>>(keys, km, tab, rows, d, rnorm);
+    bsum_kernel<T><<<dim3(tab.blk_off[tab.n], LH), 256, 0, st>>>(keys, km, rnorm, d, tab, bsum);
     ssum_kernel<<<dim3(tab.n, LH), 256, 0, st>>>(bsum, d, tab, ssum);
     const int nq = (d + kWave - 1) / kWave;
     prof.begin(NKV_KERNEL_SCAN, st);
-#define NKV_ANOM(NQ) anomaly_kernel<T, NQ><<<row_grid, 256, 0, st>>>(keys, rnorm, bsum, ssum, LH, d, window, tab, a_raw)
+#define NKV_ANOM(NQ) anomaly_kernel<T, NQ><<<row_grid, 256, 0, st>>>(keys, km, rnorm, bsum, ssum, LH, d, window, tab, a_raw)
     if (nq <= 1) NKV_ANOM(1);
     else if (nq <= 2) NKV_ANOM(2);
     else if (nq <= 4) NKV_ANOM(4);
@@ -148,13 +154,13 @@ hipError_t run(const T *keys, int LH, int d, int window, const PromptTab &tab, f
 
 }  // namespace
 
-hipError_t launch_score_generic(const void *keys, int dtype, int LH, int d, int window, const PromptTab &tab,
+hipError_t launch_score_generic(const void *keys, const RowMap &km, int dtype, int LH, int d, int window, const PromptTab &tab,
                                 float *a_raw, float *rnorm, float *bsum, float *ssum, const Prof &prof,
                                 hipStream_t st)
 {
     if (dtype == NKV_DTYPE_F32)
-        return run<float>((const float *)keys, LH, d, window, tab, a_raw, rnorm, bsum, ssum, prof, st);
-    return run<uint16_t>((const uint16_t *)keys, LH, d, window, tab, a_raw, rnorm, bsum, ssum, prof, st);
+        return run<float>((const float *)keys, km, LH, d, window, tab, a_raw, rnorm, bsum, ssum, prof, st);
+    return run<uint16_t>((const uint16_t *)keys, km, LH, d, window, tab, a_raw, rnorm, bsum, ssum, prof, st);
 }
 
 }  // namespace nkv

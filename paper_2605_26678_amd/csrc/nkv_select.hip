@@ -240,14 +240,15 @@ __global__ __launch_bounds__(kSelThreads) void select_fast_kernel(const float *_
 
 constexpr int kRowsPerGroup = 32;
 
-// 16-byte vectors; krow16 / vrow16 = vectors per K / V row.
+// 16-byte vectors; krow16 / vrow16 = vectors per K / V row, epv = elements per vector.
 __global__ __launch_bounds__(256) void gather_kernel(const uint4 *__restrict__ keys, const uint4 *__restrict__ values,
+                                                     RowMap km, RowMap vm, int epv,
                                                      int L, int H, int krow16, int vrow16, PromptTab tab,
                                                      const int64_t *__restrict__ head_off,
                                                      const int32_t *__restrict__ kept_idx, int64_t row_capacity,
                                                      uint4 *__restrict__ packed_k, uint4 *__restrict__ packed_v)
 {
-    __shared__ int64_t src[kRowsPerGroup];
+    __shared__ int64_t srck[kRowsPerGroup], srcv[kRowsPerGroup];       // first vector of the source rows
     const int n_units = tab.n * L * H;
     const int64_t rows = min(head_off[n_units], row_capacity);
     const int64_t r0 = (int64_t)blockIdx.x * kRowsPerGroup;
@@ -262,16 +263,18 @@ __global__ __launch_bounds__(256) void gather_kernel(const uint4 *__restrict__ k
         }
         const int u = lo;
         const int h = u % H, l = (u / H) % L, p = u / (H * L);
-        src[threadIdx.x] = ((int64_t)l * H + h) * tab.T + tab.tok_off[p] + kept_idx[r];
+        const int64_t i = kept_idx[r];
+        srck[threadIdx.x] = km.unit(l * H + h, p, tab) / epv + i * krow16;
+        srcv[threadIdx.x] = vm.unit(l * H + h, p, tab) / epv + i * vrow16;
     }
     __syncthreads();
     for (int j = threadIdx.x; j < nr * krow16; j += blockDim.x) {
         const int r = j / krow16, c = j - r * krow16;
-        packed_k[(r0 + r) * krow16 + c] = keys[src[r] * krow16 + c];
+        packed_k[(r0 + r) * krow16 + c] = keys[srck[r] + c];
     }
     for (int j = threadIdx.x; j < nr * vrow16; j += blockDim.x) {
         const int r = j / vrow16, c = j - r * vrow16;
-        packed_v[(r0 + r) * vrow16 + c] = values[src[r] * vrow16 + c];
+        packed_v[(r0 + r) * vrow16 + c] = values[srcv[r] + c];
     }
 }
 
@@ -293,7 +296,8 @@ hipError_t launch_copy_probe(void *dst, const void *src, size_t bytes, hipStream
     return hipGetLastError();
 }
 
-hipError_t launch_select_compact(const void *keys, const void *values, const float *scores,
+hipError_t launch_select_compact(const void *keys, const void *values, const RowMap &km, const RowMap &vm,
+                                 const float *scores,
                                  const int32_t *k_per_head, int L, int H, int d, int dv, int esize,
                                  const PromptTab &tab, float near_tol, void *packed_k, void *packed_v,
                                  int32_t *kept_idx, int64_t *head_off, int64_t row_capacity,
@@ -324,7 +328,8 @@ hipError_t launch_select_compact(const void *keys, const void *values, const flo
     if (max_rows > 0) {
         const unsigned groups = (unsigned)((max_rows + kRowsPerGroup - 1) / kRowsPerGroup);
         prof.begin(NKV_KERNEL_GATHER, st);
-        gather_kernel<<<groups, 256, 0, st>>>((const uint4 *)keys, (const uint4 *)values, L, H, d * esize / 16,
+        gather_kernel<<<groups, 256, 0, st>>>((const uint4 *)keys, (const uint4 *)values, km, vm, 16 / esize, L, H,
+                                              d * esize / 16,
                                               dv * esize / 16, tab, head_off, kept_idx, row_capacity,
                                               (uint4 *)packed_k, (uint4 *)packed_v);
         prof.end(NKV_KERNEL_GATHER, st);

@@ -70,6 +70,13 @@ def test_argument_errors_are_reported_before_any_device_work():
                        ("beta", float("nan")), ("struct_size", 8), ("n_sink", -1)):
         q = nkv.params_default(**{field: val})
         assert L.nkv_score(fake, C.byref(good.c), C.byref(q), fake, fake, 1 << 30, 0) == nkv.NKV_EINVAL, field
+    # strided layouts: misaligned strides, overlapping units
+    for ks in ((64 * 100 * 2 + 4, 64 * 100, 0), (0, 64 * 99, 0), (0, 64 * 100, 64 * 100), (-8, 64 * 100, 0)):
+        bad = nkv.Shape(1, 2, 64, 64, 1, [0, 60, 100], key_strides=ks)
+        assert L.nkv_score(fake, C.byref(bad.c), C.byref(p), fake, fake, 1 << 30, 0) == nkv.NKV_EINVAL, ks
+    ok = nkv.Shape(3, 2, 64, 64, 1, [0, 60, 100], key_strides=(64 * 128 * 4, 64 * 128, 64 * 128 * 2),
+                   value_strides=(64 * 300, 64 * 100, 0))
+    assert nkv.workspace_bytes(ok) > 0
     r_bad = (C.c_double * 1)(1.5)
     assert L.nkv_budget(fake, C.byref(good.c), C.byref(p), r_bad, fake, 0, 0, 0) == nkv.NKV_EINVAL
     assert L.nkv_budget(fake, C.byref(good.c), C.byref(p), None, fake, 0, 0, 0) == nkv.NKV_EINVAL

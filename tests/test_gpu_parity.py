@@ -276,3 +276,70 @@ def test_ragged_batch_is_reproducible():
     for _ in range(6):
         out, _ = run_gpu(w, K, V, 0.95)
         assert torch.equal(out.scores, ref.scores) and torch.equal(out.kept_idx, ref.kept_idx)
+
+
+# ------------------------------------------------------------------ strided K/V (a framework's own cache tensors)
+def _run_with_layout(w, K, V, r, shape, params=None):
+    params = params or nkv.params_default()
+    comp = nkv.Compressor(shape, [r] * shape.n_prompts, params)
+    out = comp.run(K, V)
+    torch.cuda.synchronize()
+    return out
+
+
+@pytest.mark.parametrize("flags", [0, nkv.FLAG_TWO_PASS_STABLE, nkv.FLAG_GENERIC_KERNELS, nkv.FLAG_NO_UNIT_SUMS])
+def test_strided_layouts_give_the_same_bits(flags):
+    """Keys and values that live in slabs of their own -- one [H][N_max][d] slab per prompt, as a framework's
+    per-layer cache tensor has them, or heads padded apart -- give the outputs of the dense layout bit for bit
+    (the dense layout itself is compared with the oracle elsewhere); the padding holds NaNs and is never read."""
+    w = nkv_inputs.small_workload("strided", 2, 3, 128, [700, 1333])
+    K, V = _kv(w)
+    params = nkv.params_default(flags=flags)
+    ref, _ = run_gpu(w, K, V, 0.6, params=params)
+    L, H, d, cu = w.L, w.H, w.d, w.cu_seqlens
+    nmax = 1400
+    # [L][P][H][nmax][d]: per-prompt slabs, right-padded
+    Kp = torch.full((L, 2, H, nmax, d), float("nan"), dtype=K.dtype, device=DEV)
+    Vp = torch.full((L, 2, H, nmax, d), float("nan"), dtype=V.dtype, device=DEV)
+    for p in range(2):
+        Kp[:, p, :, :cu[p + 1] - cu[p]] = K[:, :, cu[p]:cu[p + 1]]
+        Vp[:, p, :, :cu[p + 1] - cu[p]] = V[:, :, cu[p]:cu[p + 1]]
+    st = (2 * H * nmax * d, nmax * d, H * nmax * d)
+    shape = nkv.Shape(L, H, d, d, nkv.DTYPE_BF16, cu, key_strides=st, value_strides=st)
+    out = _run_with_layout(w, Kp, Vp, 0.6, shape, params)
+    for name in ("scores", "k_per_head", "head_off", "kept_idx"):
+        assert torch.equal(getattr(out, name), getattr(ref, name)), name
+    assert np.array_equal(bits(out.packed_k), bits(ref.packed_k)) and np.array_equal(bits(out.packed_v), bits(ref.packed_v))
+    # concatenated prompts, heads padded apart; values dense
+    T = w.T
+    Kh = torch.full((L, H, T + 24, d), float("nan"), dtype=K.dtype, device=DEV)
+    Kh[:, :, :T] = K
+    shape = nkv.Shape(L, H, d, d, nkv.DTYPE_BF16, cu, key_strides=(H * (T + 24) * d, (T + 24) * d, 0))
+    out = _run_with_layout(w, Kh, V, 0.6, shape, params)
+    assert torch.equal(out.scores, ref.scores) and torch.equal(out.kept_idx, ref.kept_idx)
+    assert np.array_equal(bits(out.packed_k), bits(ref.packed_k)) and np.array_equal(bits(out.packed_v), bits(ref.packed_v))
+
+
+def test_layer_by_layer_calls_equal_the_batched_call():
+    """The pass is independent per layer (Section 2, "independently at each layer"): calling it with L = 1 on
+    each layer's slice, as a prefill loop would right after the layer's keys exist, gives the rows of the
+    one call over all layers."""
+    w = nkv_inputs.small_workload("per_layer", 3, 4, 128, [2100, 260])
+    K, V = _kv(w)
+    ref, _ = run_gpu(w, K, V, 0.75)
+    shape1 = nkv.Shape(1, w.H, w.d, w.d_v, nkv.DTYPE_BF16, w.cu_seqlens)
+    comp = nkv.Compressor(shape1, [0.75] * 2)
+    for l in range(w.L):
+        out = comp.run(K[l], V[l])
+        torch.cuda.synchronize()
+        assert torch.equal(out.scores[0], ref.scores[l])
+        assert torch.equal(out.k_per_head[:, 0], ref.k_per_head[:, l])
+        for p in range(2):
+            for h in range(w.H):
+                u1, u = p * w.H + h, (p * w.L + l) * w.H + h
+                a, b = int(out.head_off[u1]), int(out.head_off[u1 + 1])
+                o = int(ref.head_off[u])
+                assert b - a == int(ref.head_off[u + 1]) - o
+                assert torch.equal(out.kept_idx[a:b], ref.kept_idx[o:o + b - a])
+                assert np.array_equal(bits(out.packed_k[a:b]), bits(ref.packed_k[o:o + b - a]))
+                assert np.array_equal(bits(out.packed_v[a:b]), bits(ref.packed_v[o:o + b - a]))
