@@ -45,6 +45,89 @@ def read_traffic(kernel, workload):
         return None
 
 
+def bench_decode(args):
+    """--mode decode: a step is one new token's attention (all layers, all query heads) over a compressed
+    cache of the workload's shape -- a synthetic ragged cache with head-wise lengths that add up to
+    H * floor((1 - r) N) per layer, resident in HBM."""
+    import numpy as np
+    import torch
+    import nkv_inputs
+    import paper_2605_26678_amd as nkv
+
+    nkv.lib()
+    w = nkv_inputs.WORKLOADS[args.workload]
+    r = args.ratio if args.ratio is not None else w.ratios[0]
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    K, V = nkv_inputs.make_kv(w, dev)
+    lens = nkv_inputs.synthetic_head_lengths(w, r)
+    pk, pv, head_off = nkv_inputs.synthetic_cache(w, K, V, lens)
+    Hq = args.q_heads or 4 * w.H
+    q = nkv_inputs.make_queries(w, Hq, K)
+    del K, V
+    rows, P = int(pk.shape[0]), len(w.prompt_lens)
+    shape = nkv.Shape(w.L, w.H, w.d, w.d_v, nkv.DTYPE_F32 if w.dtype == "fp32" else nkv.DTYPE_BF16, w.cu_seqlens)
+    params = nkv.params_default()
+    scale = 1.0 / float(np.sqrt(w.d))
+    ws = torch.empty(max(nkv.decode_workspace_bytes(shape, Hq, rows), 256), dtype=torch.uint8, device=dev)
+    out = torch.empty(P, w.L, Hq, w.d_v, dtype=torch.float32, device=dev)
+    lse = torch.empty(P, w.L, Hq, dtype=torch.float32, device=dev)
+    stream = torch.cuda.current_stream()
+    for _ in range(args.warmup):
+        nkv.decode_attention(q, pk, pv, head_off, rows, shape, params, Hq, scale, out, lse, ws, stream)
+    torch.cuda.synchronize()
+    evs = [{"decode": (nkv.HipEvent(), nkv.HipEvent())} for _ in range(args.steps)]
+    timed = [nkv.with_kernel_timers(params, e) for e in evs]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        nkv.decode_attention(q, pk, pv, head_off, rows, shape, timed[i], Hq, scale, out, lse, ws, stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    kern_ms = statistics.fmean(e["decode"][0].elapsed_ms(e["decode"][1]) for e in evs)
+    esize = 4 if w.dtype == "fp32" else 2
+    nbytes = float(rows) * (w.d + w.d_v) * esize                 # every retained K and V row once
+    achieved = nbytes / (kern_ms * 1e-3) / 1e9
+    roofline = {"bound": "hbm", "kernel": "decode", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                "traffic": read_traffic("decode", w.name), "bytes_per_launch": nbytes,
+                "kernel_ms": {"decode": round(kern_ms, 4)}}
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle.decode import decode_attention as oracle_decode
+        ho = head_off.cpu().numpy()
+        spent, done_rows, u = 0.0, 0, 0
+        G = Hq // w.H
+        while spent < 15.0 and u < ho.shape[0] - 1:
+            a, b = int(ho[u]), int(ho[u + 1])
+            pl, h = divmod(u, w.H)
+            p_, l_ = divmod(pl, w.L)
+            qq = q[p_, l_, h * G:(h + 1) * G].float().cpu().numpy()[None, None]
+            kk, vv = pk[a:b].float().cpu().numpy(), pv[a:b].float().cpu().numpy()
+            t = time.perf_counter()
+            oracle_decode(qq, kk, vv, np.array([0, b - a]), 1, scale)
+            spent += time.perf_counter() - t
+            done_rows += b - a
+            u += 1
+        cpu = {"value": round(P / (spent * rows / max(done_rows, 1)), 3), "unit": "decoded tokens/s (attention only)",
+               "cores": 1, "kind": "oracle", "seconds": round(spent, 2),
+               "sample": f"the first {u} of {ho.shape[0] - 1} (prompt, layer, KV head) units, {done_rows} of {rows} "
+                         f"rows, scaled by rows; numpy fp64, one thread apart from numpy's own"}
+    out_line = {"metric": "decoded tokens/sec, attention over the compressed cache (all layers+heads)",
+                "value": round(P / (wall / args.steps), 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+                "warmup": args.warmup, "ms_per_step": round(wall * 1e3 / args.steps, 4), "higher_is_better": True,
+                "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+                "config": {"workload": f"decode over {w.name}: {w.L} layers x {w.H} KV heads x {Hq} query heads, "
+                                       f"{rows} retained rows of {list(w.prompt_lens)} tokens (r={r}), d={w.d}, "
+                                       f"{w.dtype} cache", "ratio": r, "kv_dtype": w.dtype,
+                           "cache": "synthetic ragged cache: per layer the heads' lengths add up to "
+                                    "H*floor((1-r)N), a fifth each plus a multinomial share",
+                           "inputs": nkv_inputs.recipe(w)},
+                "roofline": roofline, "cpu_baseline": cpu}
+    print(json.dumps(out_line))
+    return 0
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -58,10 +141,15 @@ def main():
     ap.add_argument("--two-pass", action="store_true", help="stable anomaly in a second pass over the keys")
     ap.add_argument("--per-layer", action="store_true",
                     help="a step is L passes with L = 1, one per layer's K/V slice, as a prefill loop would call it")
+    ap.add_argument("--mode", choices=("pass", "decode"), default="pass",
+                    help="pass: the compression pass (default); decode: attention over the compressed cache")
+    ap.add_argument("--q-heads", type=int, default=0, help="decode mode: query heads (default 4 per KV head)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no sharding, no collectives); use --gpus 1", file=sys.stderr)
         return 2
+    if args.mode == "decode":
+        return bench_decode(args)
 
     import torch
     import nkv_inputs
@@ -89,7 +177,7 @@ def main():
     torch.cuda.synchronize()
 
     # timed region: K steps, every kernel of interest bracketed by its own event pair
-    evs = [[{name: (nkv.HipEvent(), nkv.HipEvent()) for name in nkv.KERNELS} for _ in calls]
+    evs = [[{name: (nkv.HipEvent(), nkv.HipEvent()) for name in nkv.PASS_KERNELS} for _ in calls]
            for _ in range(args.steps)]
     step_ev = [(nkv.HipEvent(), nkv.HipEvent()) for _ in range(args.steps)]
     base_params = params
@@ -109,7 +197,7 @@ def main():
     step_ms = [a.elapsed_ms(b) for a, b in step_ev]
     # per step: a kernel's launches added up over the step's calls
     kern_ms = {name: statistics.fmean(sum(e[name][0].elapsed_ms(e[name][1]) for e in evs[i])
-                                      for i in range(args.steps)) for name in nkv.KERNELS}
+                                      for i in range(args.steps)) for name in nkv.PASS_KERNELS}
     tokens = w.T
     value = tokens / (wall / args.steps)
 

@@ -68,7 +68,8 @@ enum {
     NKV_KERNEL_BUDGET = 2,     /* nkv_budget                                                  */
     NKV_KERNEL_SELECT = 3,     /* threshold search + ordered compaction of nkv_select_compact */
     NKV_KERNEL_GATHER = 4,     /* K/V row copies of nkv_select_compact                        */
-    NKV_KERNEL_COUNT = 5
+    NKV_KERNEL_DECODE = 5,     /* attention over the retained rows of nkv_decode_attention    */
+    NKV_KERNEL_COUNT = 6
 };
 
 #define NKV_MAX_PROMPTS 64        /* prompts per call                                   */
@@ -198,6 +199,26 @@ int nkv_select_compact(const void *keys, const void *values, const float *scores
                        void *packed_k, void *packed_v, int32_t *kept_idx, int64_t *head_off,
                        int64_t row_capacity, int64_t *near_threshold_count,
                        void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
+ * Decode-side consumer of the compressed cache (Appendix A: retained keys and values are
+ * unchanged, so ordinary attention runs over them; Section 3.5 measures the per-token decode
+ * latency).  One new token's queries against the output of nkv_select_compact, grouped-query
+ * attention with G = n_q_heads / H query heads per KV head: for unit u = (p, l, h) and g < G,
+ *   s_i = scale * <q[p][l][h*G+g], packed_k[i]>,  i = head_off[u] .. head_off[u+1]-1
+ *   out[p][l][h*G+g] = sum_i softmax(s)_i * packed_v[i]                    fp32 [P][L][n_q_heads][dv]
+ *   lse[p][l][h*G+g] = log sum_i exp(s_i)   (optional, may be NULL)        fp32 [P][L][n_q_heads]
+ * q is [P][L][n_q_heads][d] in the dtype of the cache.  `rows` is the number of rows packed_k /
+ * packed_v hold; head_off entries are clamped to it.  A unit without rows gives out = 0,
+ * lse = -inf.  shape->key_strides / value_strides are not used (the packed cache is dense).
+ * fp32 arithmetic: exact bf16 products accumulated in fp32, base-2 exponentials of the hardware.
+ * Scratch: nkv_decode_workspace_bytes (0 for shapes outside bf16, d = dv in {64,128}, G <= 8,
+ * which take a slower kernel).  Asynchronous on hip_stream.
+ */
+int nkv_decode_workspace_bytes(const nkv_shape *shape, int32_t n_q_heads, int64_t rows, size_t *bytes);
+int nkv_decode_attention(const void *q, const void *packed_k, const void *packed_v, const int64_t *head_off,
+                         int64_t rows, const nkv_shape *shape, const nkv_params *params, int32_t n_q_heads,
+                         double scale, float *out, float *lse, void *ws, size_t ws_bytes, void *hip_stream);
 
 /*
  * Plain device-to-device copy of `bytes` bytes (a multiple of 16, both pointers 16-byte aligned) by a

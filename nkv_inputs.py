@@ -175,3 +175,68 @@ def recipe(w: Workload) -> dict:
         "drift": "0.02 rad per 512 tokens, continuous" if w.drift else "none",
         "values": "N(0,1)", "seed": w.seed,
     }
+
+
+# ---------------------------------------------------------------------------------------------------------
+# Inputs of the decode-side consumer (attention of one new token over a compressed cache).
+
+def make_queries(w: Workload, n_q_heads: int, K: torch.Tensor) -> torch.Tensor:
+    """q [P, L, n_q_heads, d] in the workload's dtype, one new token per prompt: Gaussian noise plus half of
+    one randomly chosen key of the KV head the query head reads (j // G), so that the attention is peaked on
+    a few positions the way a retrieving head's is.  K is keys[L, H, T, d] of the workload (any device)."""
+    P, G = len(w.prompt_lens), n_q_heads // w.H
+    g = _gen(K.device, w.seed, 424242)
+    q = torch.randn(P, w.L, n_q_heads, w.d, dtype=torch.float32, device=K.device, generator=g)
+    cu = w.cu_seqlens
+    for p in range(P):
+        j = torch.randint(0, int(w.prompt_lens[p]), (w.L, n_q_heads), device=K.device, generator=g) + cu[p]
+        heads = (torch.arange(n_q_heads, device=K.device) // G)[None, :].expand(w.L, n_q_heads)
+        layers = torch.arange(w.L, device=K.device)[:, None].expand(w.L, n_q_heads)
+        q[p] += 0.5 * K[layers, heads, j].to(torch.float32)
+    return q.to(w.torch_dtype())
+
+
+def synthetic_head_lengths(w: Workload, r: float, seed: int = 0) -> torch.Tensor:
+    """lens [P, L, H] (int64, CPU): retained rows per head with the structure head-wise budgets have -- every
+    head of a layer gets a fifth of n = floor((1 - r) N) and the other four fifths of H * n are dealt to the
+    heads by a seeded multinomial draw, so the lengths of a layer are ragged and add up to H * n."""
+    P = len(w.prompt_lens)
+    g = _gen(torch.device("cpu"), w.seed, seed, 515151)
+    lens = torch.zeros(P, w.L, w.H, dtype=torch.int64)
+    for p in range(P):
+        N = int(w.prompt_lens[p])
+        n = int((1.0 - r) * N + 1e-9)
+        base = n // 5
+        rest = w.H * (n - base)
+        for l in range(w.L):
+            share = torch.rand(w.H, generator=g) + 0.25
+            part = torch.floor(share / share.sum() * rest).to(torch.int64)
+            part[0] += rest - int(part.sum())
+            lens[p, l] = torch.clamp(base + part, max=N)
+    return lens
+
+
+def synthetic_cache(w: Workload, K: torch.Tensor, V: torch.Tensor, lens: torch.Tensor, seed: int = 0):
+    """A ragged cache with the layout the compression operator writes, without running it: for unit
+    (p, l, h) a seeded random subset of lens[p, l, h] positions in ascending order, their K and V rows copied.
+    Returns packed_k [rows, d], packed_v [rows, d_v], head_off [P*L*H + 1] int64 (on K's device)."""
+    P = len(w.prompt_lens)
+    g = _gen(K.device, w.seed, seed, 616161)
+    cu = w.cu_seqlens
+    flat = lens.reshape(-1)
+    head_off = torch.zeros(flat.numel() + 1, dtype=torch.int64)
+    head_off[1:] = torch.cumsum(flat, 0)
+    rows = int(head_off[-1])
+    pk = torch.empty(rows, w.d, dtype=K.dtype, device=K.device)
+    pv = torch.empty(rows, w.d_v, dtype=V.dtype, device=K.device)
+    u = 0
+    for p in range(P):
+        N = int(w.prompt_lens[p])
+        for l in range(w.L):
+            for h in range(w.H):
+                n, o = int(flat[u]), int(head_off[u])
+                idx = torch.sort(torch.randperm(N, device=K.device, generator=g)[:n]).values + cu[p]
+                pk[o:o + n] = K[l, h, idx]
+                pv[o:o + n] = V[l, h, idx]
+                u += 1
+    return pk, pv, head_off.to(K.device)

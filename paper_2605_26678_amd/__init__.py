@@ -25,8 +25,9 @@ PIN = 3.0e38
 
 EXPORTS = ("nkv_params_default", "nkv_block_size", "nkv_k0", "nkv_m_safe", "nkv_m_p", "nkv_packed_rows",
            "nkv_workspace_bytes", "nkv_score", "nkv_score_raw", "nkv_budget", "nkv_select_compact",
-           "nkv_copy_probe", "nkv_strerror", "nkv_version")
-KERNELS = ("scan", "finalize", "budget", "select", "gather")
+           "nkv_decode_workspace_bytes", "nkv_decode_attention", "nkv_copy_probe", "nkv_strerror", "nkv_version")
+KERNELS = ("scan", "finalize", "budget", "select", "gather", "decode")
+PASS_KERNELS = KERNELS[:5]          # the kernels of the compression pass itself
 
 
 class nkv_params(C.Structure):
@@ -35,7 +36,7 @@ class nkv_params(C.Structure):
                 ("gate_mode", C.c_int32), ("surprise_mode", C.c_int32), ("flags", C.c_uint32),
                 ("reserved", C.c_int32), ("top_frac", C.c_double), ("prior", C.c_double * 3),
                 ("beta", C.c_double), ("tau", C.c_double), ("kappa", C.c_double), ("safeguard", C.c_double),
-                ("near_tol", C.c_double), ("prof_start", C.c_void_p * 5), ("prof_stop", C.c_void_p * 5)]
+                ("near_tol", C.c_double), ("prof_start", C.c_void_p * 6), ("prof_stop", C.c_void_p * 6)]
 
 
 class nkv_shape(C.Structure):
@@ -79,6 +80,9 @@ def lib() -> C.CDLL:
                                  C.c_size_t, vp]
         L.nkv_select_compact.argtypes = [vp, vp, vp, vp, C.POINTER(nkv_shape), C.POINTER(nkv_params), vp, vp, vp,
                                          vp, i64, vp, vp, C.c_size_t, vp]
+        L.nkv_decode_workspace_bytes.argtypes = [C.POINTER(nkv_shape), C.c_int32, i64, C.POINTER(C.c_size_t)]
+        L.nkv_decode_attention.argtypes = [vp, vp, vp, vp, i64, C.POINTER(nkv_shape), C.POINTER(nkv_params),
+                                           C.c_int32, f64, vp, vp, vp, C.c_size_t, vp]
         L.nkv_copy_probe.argtypes = [vp, vp, C.c_size_t, vp]
         L.nkv_strerror.argtypes = [C.c_int]
         L.nkv_strerror.restype = C.c_char_p
@@ -211,6 +215,26 @@ def select_compact(keys, values, scores, k_per_head, shape: Shape, params: nkv_p
                                   0 if ws is None else ws.numel() * ws.element_size(), _stream(stream))
     if rc:
         raise NkvError(rc, "nkv_select_compact")
+
+
+def decode_workspace_bytes(shape: Shape, n_q_heads: int, rows: int) -> int:
+    out = C.c_size_t(0)
+    rc = lib().nkv_decode_workspace_bytes(C.byref(shape.c), int(n_q_heads), int(rows), C.byref(out))
+    if rc:
+        raise NkvError(rc, "nkv_decode_workspace_bytes")
+    return int(out.value)
+
+
+def decode_attention(q, packed_k, packed_v, head_off, rows: int, shape: Shape, params: nkv_params, n_q_heads: int,
+                     scale: float, out, lse=None, ws=None, stream=None) -> None:
+    """One new token's attention over the compressed cache: q [P,L,Hq,d] -> out [P,L,Hq,dv] fp32 (and lse
+    [P,L,Hq]); see ``nkv_decode_attention`` in nkv.h."""
+    rc = lib().nkv_decode_attention(_ptr(q), _ptr(packed_k), _ptr(packed_v), _ptr(head_off), int(rows),
+                                    C.byref(shape.c), C.byref(params), int(n_q_heads), float(scale), _ptr(out),
+                                    _ptr(lse), _ptr(ws), 0 if ws is None else ws.numel() * ws.element_size(),
+                                    _stream(stream))
+    if rc:
+        raise NkvError(rc, "nkv_decode_attention")
 
 
 def copy_probe(dst, src, stream=None) -> None:

@@ -348,6 +348,40 @@ int nkv_select_compact(const void *keys, const void *values, const float *scores
                ? NKV_OK : NKV_EHIP;
 }
 
+int nkv_decode_workspace_bytes(const nkv_shape *shape, int32_t n_q_heads, int64_t rows, size_t *bytes)
+{
+    if (!bytes || rows < 0) return NKV_EINVAL;
+    int rc = check_shape(shape);
+    if (rc) return rc;
+    if (n_q_heads < shape->H || n_q_heads % shape->H) return NKV_EINVAL;
+    *bytes = decode_ws_bytes(shape->dtype, shape->d, shape->dv, n_q_heads / shape->H,
+                             (int64_t)shape->n_prompts * shape->L * shape->H, rows);
+    return NKV_OK;
+}
+
+int nkv_decode_attention(const void *q, const void *packed_k, const void *packed_v, const int64_t *head_off,
+                         int64_t rows, const nkv_shape *shape, const nkv_params *params, int32_t n_q_heads,
+                         double scale, float *out, float *lse, void *ws, size_t ws_bytes, void *hip_stream)
+{
+    if (!q || !head_off || !out || rows < 0 || !isfinite(scale)) return NKV_EINVAL;
+    if (rows > 0 && (!packed_k || !packed_v)) return NKV_EINVAL;
+    int rc = check_shape(shape);
+    if (rc) return rc;
+    rc = check_params(params);
+    if (rc) return rc;
+    if (n_q_heads < shape->H || n_q_heads % shape->H) return NKV_EINVAL;
+    if ((uintptr_t)q % 16 || (uintptr_t)packed_k % 16 || (uintptr_t)packed_v % 16) return NKV_EINVAL;
+    const int G = n_q_heads / shape->H;
+    const int64_t n_units = (int64_t)shape->n_prompts * shape->L * shape->H;
+    if (n_units * G >= (1ll << 31) || rows / 256 + n_units >= (1ll << 31)) return NKV_ESHAPE;
+    rc = check_ws(ws, ws_bytes, decode_ws_bytes(shape->dtype, shape->d, shape->dv, G, n_units, rows));
+    if (rc) return rc;
+    return launch_decode(q, packed_k, packed_v, head_off, shape->dtype, (int)n_units, G, shape->d, shape->dv, rows,
+                         scale, out, lse, ws, Prof{params->prof_start, params->prof_stop},
+                         (hipStream_t)hip_stream) == hipSuccess
+               ? NKV_OK : NKV_EHIP;
+}
+
 int nkv_copy_probe(void *dst, const void *src, size_t bytes, void *hip_stream)
 {
     if (!dst || !src || bytes % 16 || (uintptr_t)dst % 16 || (uintptr_t)src % 16) return NKV_EINVAL;

@@ -108,6 +108,13 @@ hipError_t launch_select_compact(const void *keys, const void *values, const Row
                                  int32_t *kept_idx, int64_t *head_off, int64_t row_capacity,
                                  int64_t *near_count, const Prof &prof, hipStream_t st);
 
+// ---- decode-side consumer: attention of one new token over the packed cache ----
+bool decode_fast_supported(int dtype, int d, int dv, int G);
+size_t decode_ws_bytes(int dtype, int d, int dv, int G, int64_t n_units, int64_t rows);
+hipError_t launch_decode(const void *q, const void *pk, const void *pv, const int64_t *head_off, int dtype,
+                         int n_units, int G, int d, int dv, int64_t rows, double scale, float *out, float *lse,
+                         void *ws, const Prof &prof, hipStream_t st);
+
 // ---- plain copy, the bandwidth yardstick ----
 hipError_t launch_copy_probe(void *dst, const void *src, size_t bytes, hipStream_t st);
 
