@@ -72,7 +72,7 @@ __device__ __forceinline__ int64_t clamp_row(int64_t r, int64_t rows) { return r
 __global__ __launch_bounds__(1024) void decode_plan_kernel(const int64_t *__restrict__ head_off, int n_units,
                                                            int64_t rows, int32_t *__restrict__ chunk_off)
 {
-    __shared__ int32_t sums[1024];
+    __shared__ int32_t sums[16];                                      // per-wave totals
     const int per = (n_units + 1023) / 1024;
     const int u0 = min(threadIdx.x * per, n_units), u1 = min(u0 + per, n_units);
     int32_t mine = 0;
@@ -80,19 +80,24 @@ __global__ __launch_bounds__(1024) void decode_plan_kernel(const int64_t *__rest
         const int64_t len = clamp_row(head_off[u + 1], rows) - clamp_row(head_off[u], rows);
         mine += (int32_t)((max(len, (int64_t)0) + kChunk - 1) / kChunk);
     }
-    sums[threadIdx.x] = mine;
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        int32_t run = 0;
-        for (int i = 0; i < 1024; ++i) {
-            const int32_t v = sums[i];
-            sums[i] = run;
-            run += v;
-        }
-        chunk_off[n_units] = run;
+    // exclusive scan of the 1024 per-thread counts: inside every wave by shuffles, then over the 16 wave totals
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    int32_t incl = mine;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const int32_t t = __shfl_up(incl, o, 64);
+        if (lane >= o) incl += t;
     }
+    if (lane == 63) sums[wv] = incl;
     __syncthreads();
-    int32_t run = sums[threadIdx.x];
+    int32_t before = 0, total = 0;
+    for (int i = 0; i < 16; ++i) {
+        const int32_t t = sums[i];
+        if (i < wv) before += t;
+        total += t;
+    }
+    if (threadIdx.x == 0) chunk_off[n_units] = total;
+    int32_t run = before + incl - mine;
     for (int u = u0; u < u1; ++u) {
         chunk_off[u] = run;
         const int64_t len = clamp_row(head_off[u + 1], rows) - clamp_row(head_off[u], rows);
@@ -228,18 +233,43 @@ __global__ __launch_bounds__(kDecThreads) void decode_chunk_kernel(const uint16_
     }
 }
 
-// grid: n_units * G workgroups of D threads
+// grid: n_units * G workgroups of D threads (D = 64 or 128: one or two waves)
 template <int D>
 __global__ __launch_bounds__(D) void decode_combine_kernel(const float *__restrict__ part,
                                                            const int32_t *__restrict__ chunk_off, int G,
                                                            float *__restrict__ out, float *__restrict__ lse)
 {
+    __shared__ float red[D / 64];
     const int u = blockIdx.x / G, g = blockIdx.x - u * G, e = threadIdx.x;
     const int c0 = chunk_off[u], c1 = chunk_off[u + 1];
+    // the largest running maximum: chunks spread over the threads, then one reduction
     float mm = kNone;
-    for (int ch = c0; ch < c1; ++ch) mm = fmaxf(mm, part[((int64_t)ch * G + g) * (D + 2)]);
+    for (int ch = c0 + e; ch < c1; ch += D) mm = fmaxf(mm, part[((int64_t)ch * G + g) * (D + 2)]);
+    mm = wave_max(mm);
+    if ((e & 63) == 0) red[e >> 6] = mm;
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < D / 64; ++i) mm = fmaxf(mm, red[i]);
+    // weighted sums, four chunks' loads in flight at a time; the order of the additions is fixed
     float ll = 0.f, oo = 0.f;
-    for (int ch = c0; ch < c1; ++ch) {
+    int ch = c0;
+    for (; ch + 4 <= c1; ch += 4) {
+        float pm[4], pl[4], po[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const float *src = part + ((int64_t)(ch + i) * G + g) * (D + 2);
+            pm[i] = src[0];
+            pl[i] = src[1];
+            po[i] = src[2 + e];
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const float f = __builtin_amdgcn_exp2f(pm[i] - mm);
+            ll = fmaf(f, pl[i], ll);
+            oo = fmaf(f, po[i], oo);
+        }
+    }
+    for (; ch < c1; ++ch) {
         const float *src = part + ((int64_t)ch * G + g) * (D + 2);
         const float f = __builtin_amdgcn_exp2f(src[0] - mm);
         ll = fmaf(f, src[1], ll);
