@@ -281,8 +281,6 @@ int nkv_score(const void *keys, const nkv_shape *shape, const nkv_params *params
     rc = run_raw(keys, shape, params, tab, a_raw, (char *)ws, lay, st);
     if (rc) return rc;
     LearnerConsts lc;
-    const double psum = params->prior[0] + params->prior[1] + params->prior[2];
-    (void)psum;
     for (int k = 0; k < 3; ++k) lc.log_prior[k] = log(params->prior[k]);   // log 0 = -inf: scale switched off
     lc.beta = params->beta;
     lc.tau = (float)params->tau;
