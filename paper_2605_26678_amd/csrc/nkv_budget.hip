@@ -32,7 +32,7 @@ struct HeadSafe {                // result of step A for one head
 
 // ---------------------------------------------------------------------------------------------------
 template <int EPT>
-__global__ __launch_bounds__(kSelThreads) void head_safe_kernel(const float *__restrict__ scores, int L, int H,
+__global__ __launch_bounds__(kSelThreads, 8) void head_safe_kernel(const float *__restrict__ scores, int L, int H,
                                                                  PromptTab tab, int u0, HeadSafe *__restrict__ safe,
                                                                  uint32_t *__restrict__ pool_hist)
 {

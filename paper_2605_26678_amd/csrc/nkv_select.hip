@@ -151,7 +151,7 @@ __global__ __launch_bounds__(kThreads) void select_kernel(const float *__restric
 // of chunk j, the (chunk, wave) population counts are scanned once in token order, and each kept token's
 // output slot is its group's offset plus the number of kept lanes below it.
 template <int EPT>
-__global__ __launch_bounds__(kSelThreads) void select_fast_kernel(const float *__restrict__ scores,
+__global__ __launch_bounds__(kSelThreads, 8) void select_fast_kernel(const float *__restrict__ scores,
                                                                   const int32_t *__restrict__ k_per_head, int L,
                                                                   int H, PromptTab tab, int u0, float near_tol,
                                                                   const int64_t *__restrict__ head_off,
