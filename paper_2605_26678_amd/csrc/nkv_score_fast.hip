@@ -30,20 +30,21 @@
 // per step (the first wavefront slides over the halo rows, which also pass through LDS).
 // Cosines do not depend on the anchor's length, so sums stand in for means everywhere.
 //
-// Placement.  The chip's compute units sit in 8 dies (XCDs) with one L2 each, and consecutive workgroups
-// start on different dies.  Blocks are therefore not taken in launch order: every die has its own ticket
-// counter and walks its own share of each (layer, head)'s blocks -- runs of up to 16 consecutive blocks,
-// dealt to the dies round-robin -- so the halo of a block was fetched by the same L2 moments before.  All dies work
-// on the same (layer, head) at the same time.  A die that runs out of tickets takes them from the next
-// die's counter.
+// Placement.  The chip's compute units sit in 8 dies (XCDs) with one L2 each; workgroups are started in
+// launch order and consecutive ones go to different dies.  Blocks are therefore not taken in launch order:
+// workgroup i is item i / 8 of the queue of die i % 8, and a die's queue walks that die's share of each
+// (layer, head)'s blocks -- runs of up to 16 consecutive blocks, dealt to the dies round-robin -- so the halo
+// of a block was fetched by the same L2 moments before.  All dies work on the same (layer, head) at the same
+// time.  The assignment is pure arithmetic on the launch index (no counter to fetch before the first load
+// can be issued); should the hardware place a workgroup on another die, only that locality is lost.
 //
 // The stable anchor needs every key of the prompt before the first a_s can be computed.  Two ways:
-//   fused   : all blocks of a (layer, head, prompt) unit are ticketed close together.  The block totals
+//   fused   : all blocks of a (layer, head, prompt) unit are started close together.  The block totals
 //             and the unit sums live in memory that is filled with a NaN bit pattern before the launch, so
 //             a 32-bit word that has been written is recognisable by itself and no flags, counters or
 //             waits for completed stores are needed.  Each workgroup stores its block total (agent scope)
-//             and goes on to its window loop.  Every unit has one more ticket, queued right behind the
-//             unit's blocks on one die: the workgroup that draws it does nothing but poll the unit's block
+//             and goes on to its window loop.  Every unit has one more item, queued right behind the
+//             unit's blocks on one die: the workgroup that gets it does nothing but poll the unit's block
 //             totals, add them up in block order and store the unit sum.  After its window loop every
 //             block's workgroup polls the unit sum with its chunk still in registers, then computes a_s.
 //             Nobody waits without bound: a block's workgroup that does not find the unit sum within a
@@ -274,21 +275,24 @@ __device__ __forceinline__ bool all_written(const u32x4 &v)
 constexpr int kMaxChunks = 4;                    // chunks per block: block size <= 256
 constexpr uint32_t kSpinLimit = 1u << 22;        // polls of a summing workgroup before it gives up (~seconds)
 constexpr int kPollLimit = 48;                   // polls of a block's workgroup before it defers its a_s (~0.1 ms)
-constexpr int kDies = 8;                         // ticket counters (one per XCD of an MI355X)
+constexpr int kDies = 8;                         // queues (one per XCD of an MI355X)
 
 // Sync area of the fused path (the first kSyncWords are zero before the launch), in 32-bit words.
-constexpr int kTicketStride = 32;                // one 128-byte line per die's ticket counter
-constexpr int kTimeoutWord = kDies * kTicketStride;      // summing workgroups that gave up (never, in practice)
-constexpr int kDeferCountWord = kTimeoutWord + 1;        // blocks on the list
-constexpr int kSyncWords = kTimeoutWord + 32;            // the list (one word per block) follows
+constexpr int kTimeoutWord = 0;                  // summing workgroups that gave up (never, in practice)
+constexpr int kDeferCountWord = 1;               // blocks on the list
+constexpr int kSyncWords = 32;                   // the list (one word per block) follows
 
 // The blocks of a (layer, head) are dealt to the dies in runs of consecutive blocks, round-robin: runs keep a
 // block's halo on the die of the block before it, dealing them round-robin gives every die the same mix of
 // prompts when a batch holds prompts of different lengths.  A run is 16 blocks, fewer when there are not
 // enough blocks to give every die a run.
-__device__ __forceinline__ int run_length(int nblk) { return max(1, min(16, nblk / kDies)); }
+__host__ __device__ __forceinline__ int run_length(int nblk)
+{
+    const int r = nblk / kDies;
+    return r < 1 ? 1 : (r > 16 ? 16 : r);
+}
 // number of blocks of one (layer, head) that belong to die x
-__device__ __forceinline__ int die_blocks(int nblk, int run, int x)
+__host__ __device__ __forceinline__ int die_blocks(int nblk, int run, int x)
 {
     const int cycles = nblk / (run * kDies), rem = nblk - cycles * run * kDies;
     return cycles * run + min(max(rem - x * run, 0), run);
@@ -297,8 +301,8 @@ __device__ __forceinline__ int die_blocks(int nblk, int run, int x)
 __device__ __forceinline__ int die_block(int run, int x, int r) { return ((r / run) * kDies + x) * run + r % run; }
 
 // Queue of die x: for lh = 0, 1, ...: the len blocks of its segment, then -- if lh % kDies == x -- one
-// "add the unit up" item per prompt.  First ticket of lh in that queue:
-__device__ __forceinline__ uint32_t queue_start(int lh, int len, int n_prompts, int x)
+// "add the unit up" item per prompt.  First item of lh in that queue:
+__host__ __device__ __forceinline__ uint32_t queue_start(int lh, int len, int n_prompts, int x)
 {
     return (uint32_t)lh * (uint32_t)len + (uint32_t)n_prompts * ((uint32_t)(lh + kDies - 1 - x) / kDies);
 }
@@ -377,48 +381,28 @@ void scan_kernel(const uint16_t *__restrict__ keys, RowMap km, PromptTab tab, fl
     __shared__ float lds_C[NW][D];                                    // chunk totals
     __shared__ float lds_S[D];                                        // the unit's sum, once complete
     __shared__ u32x4 lds_x[2][NW > 1 ? NW - 1 : 1][4][64];            // rows on their way to the next wave
-    __shared__ int s_lh, s_blk, s_sum, s_have;
+    __shared__ int s_have;
 
     const int nblk = tab.blk_off[tab.n];
     int lh, blk;
     if (FUSED) {
-        // take a ticket from this die's counter, or from the next die's that still has work.  The first wave
-        // does it with the ticket in a scalar register, so that decoding it is scalar arithmetic.
-        if (threadIdx.x < 64) {
-            const int die = (int)(__builtin_amdgcn_s_getreg((3 << 11) | 20) & (kDies - 1));   // XCC_ID[3:0]
-            int got_lh = -1, got_blk = 0, got_sum = -1;
-            for (int i = 0; i < kDies && got_lh < 0; ++i) {
-                const int x = (die + i) & (kDies - 1);
-                const int run = run_length(nblk), len = die_blocks(nblk, run, x);
-                const uint32_t items = queue_start(LH, len, tab.n, x);
-                if (items == 0u) continue;
-                uint32_t t = 0u;
-                if (threadIdx.x == 0)
-                    t = __hip_atomic_fetch_add(sync + x * kTicketStride, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                t = (uint32_t)__builtin_amdgcn_readfirstlane((int)t);
-                if (t < items) {
-                    // lh of ticket t: a first guess from the average number of items per lh, then exact
-                    int l = min(LH - 1, (int)(t * (uint32_t)kDies / ((uint32_t)kDies * len + tab.n)));
-                    while (l > 0 && queue_start(l, len, tab.n, x) > t) --l;
-                    while (l + 1 < LH && queue_start(l + 1, len, tab.n, x) <= t) ++l;
-                    const int r = (int)(t - queue_start(l, len, tab.n, x));
-                    got_lh = l;
-                    if (r < len) got_blk = die_block(run, x, r);
-                    else got_sum = r - len;                           // prompt whose unit sum is to be formed
-                }
-            }
-            if (threadIdx.x == 0) {
-                s_lh = got_lh;
-                s_blk = got_blk;
-                s_sum = got_sum;
-            }
-        }
-        __syncthreads();
-        lh = s_lh;
-        blk = s_blk;
-        if (lh < 0) return;                                           // more workgroups than tickets: cannot happen
-        if (s_sum >= 0) {                                             // uniform: this workgroup adds a unit up
-            const int p = s_sum;
+        // Static assignment: workgroups are started in launch order and go to the dies round-robin, so
+        // workgroup i is item i / 8 of the queue of die i % 8 (if it lands on another die the result is the
+        // same, only the halo comes from memory).  Everything here is scalar arithmetic on the launch index.
+        const int x = (int)(blockIdx.x & (kDies - 1));
+        const uint32_t t = blockIdx.x >> 3;
+        const int run = run_length(nblk), len = die_blocks(nblk, run, x);
+        if (t >= queue_start(LH, len, tab.n, x)) return;              // the dies' queues differ slightly in length
+        // lh of item t: a first guess from the average number of items per lh, then exact
+        int l = min(LH - 1, (int)(t * (uint32_t)kDies / ((uint32_t)kDies * len + tab.n)));
+        while (l > 0 && queue_start(l, len, tab.n, x) > t) --l;
+        while (l + 1 < LH && queue_start(l + 1, len, tab.n, x) <= t) ++l;
+        const int r = (int)(t - queue_start(l, len, tab.n, x));
+        lh = l;
+        blk = r < len ? die_block(run, x, r) : 0;
+        const int sum_of = r < len ? -1 : r - len;                    // prompt whose unit sum is to be formed
+        if (sum_of >= 0) {                                            // uniform: this workgroup adds a unit up
+            const int p = sum_of;
             static_assert(64 * NW / (D / 4) * D <= NW * SG * D, "partial sums of the unit do not fit the LDS scratch");
             if (!add_unit_up<D, NW, true>(bsum + ((int64_t)lh * nblk + tab.blk_off[p]) * D,
                                           tab.blk_off[p + 1] - tab.blk_off[p], ssum + ((int64_t)lh * tab.n + p) * D,
@@ -854,7 +838,16 @@ void launch_scan(const uint16_t *keys, const RowMap &km, int LH, const PromptTab
                  uint32_t *sync, int poll_limit, uint32_t spin_limit, hipStream_t st)
 {
     const int64_t rows = (int64_t)LH * tab.T;
-    const unsigned groups = (unsigned)(tab.blk_off[tab.n] * LH + (FUSED ? tab.n * LH : 0));    // + one per unit sum
+    unsigned groups = (unsigned)(tab.blk_off[tab.n] * LH);
+    if (FUSED) {                                                      // 8 queues of (nearly) equal length, interleaved
+        const int nblk = tab.blk_off[tab.n], run = run_length(nblk);
+        uint32_t longest = 0;
+        for (int x = 0; x < kDies; ++x) {
+            const uint32_t items = queue_start(LH, die_blocks(nblk, run, x), tab.n, x);
+            longest = items > longest ? items : longest;
+        }
+        groups = longest * kDies;
+    }
     scan_kernel<D, NW, FUSED><<<groups, 64 * NW, 0, st>>>(keys, km, tab, a_raw, bsum, ssum, sync, LH, rows, poll_limit,
                                                           spin_limit);
 }
@@ -881,13 +874,13 @@ hipError_t run_nw(const uint16_t *keys, const RowMap &km, int LH, const PromptTa
     int max_unit_blocks = 0;
     for (int p = 0; p < tab.n; ++p) max_unit_blocks = max(max_unit_blocks, tab.blk_off[p + 1] - tab.blk_off[p]);
     // fused only if the chip can hold two units' worth of workgroups at once (see the header comment)
-    // (ticket arithmetic is 32-bit: keep the number of tickets far below 2^32 / 8)
-    const int64_t tickets = (int64_t)LH * (tab.blk_off[tab.n] + tab.n);
+    // (queue arithmetic is 32-bit: keep the number of items far below 2^32 / 8)
+    const int64_t items = (int64_t)LH * (tab.blk_off[tab.n] + tab.n);
     const bool allow_fused = mode != kScanTwoPass, no_unit_sums = mode == kScanRepairAll;
     const bool defer_all = mode == kScanDeferAll || no_unit_sums;
-    const bool fused = allow_fused && tickets < (1ll << 28) && 2 * max_unit_blocks <= resident_workgroups<D, NW, true>();
+    const bool fused = allow_fused && items < (1ll << 28) && 2 * max_unit_blocks <= resident_workgroups<D, NW, true>();
     if (fused) {
-        // tickets and timeouts start at zero, block totals and unit sums as "unwritten"
+        // the counters start at zero, block totals and unit sums as "unwritten"
         const size_t nb = (size_t)LH * tab.blk_off[tab.n] * D / 4, ns = (size_t)LH * tab.n * D / 4;
         fill_kernel<<<1, 256, 0, st>>>((uint4 *)sync_area, kSyncWords / 4, 0u);
         fill_kernel<<<(unsigned)min((nb + 255) / 256, (size_t)2048), 256, 0, st>>>((uint4 *)bsum, nb, kUnwritten);
