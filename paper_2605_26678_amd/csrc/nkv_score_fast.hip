@@ -575,11 +575,11 @@ void scan_kernel(const uint16_t *__restrict__ keys, RowMap km, PromptTab tab, fl
 
     // ---- slide the window over this lane's tokens: current-memory dots ----
     // Four rows per step; the per-lane partial dots of the four rows enter the transposing butterfly.
-    float wd_m = 0.f, wn_m = 1.f;
+    float wd_m = 0.f, wn_m = 1.f, bd_m = 0.f;
     const __amdgpu_buffer_rsrc_t srs = __builtin_amdgcn_make_buffer_rsrc(S_unit, 0, D * 4, 0x00020000);
     u32x4 sv0 = {kUnwritten, kUnwritten, kUnwritten, kUnwritten}, sv1 = sv0;
     {
-        StreamReduce<LPR> red_wd, red_wn;
+        StreamReduce<LPR> red_wd, red_wn, red_bd;                     // the episodic dot rides along: same unpacked row
 #pragma unroll
         for (int j = 0; j < TPT; ++j) forget(raw[j]);
         // Leaving rows come through LDS: wave 0 slides over the halo rows every wave stored while it worked on
@@ -604,38 +604,42 @@ void scan_kernel(const uint16_t *__restrict__ keys, RowMap km, PromptTab tab, fl
                 sv0 = agent_load16(srs, lane * 32);
                 sv1 = agent_load16(srs, lane * 32 + 16);
             }
-            float pw[4], pn[4];
+            float pw[4], pn[4], pb[4];
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 float kp[8], k[8];
                 const u32x4 pl = leaving[i * 64];
                 unpack8(pl, kp);
                 unpack8(raw[4 * s + i], k);
-                float wd = 0.f, wn = 0.f;
+                float wd = 0.f, wn = 0.f, bd = 0.f;
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
                     W[e] = fmaf(-rp[i], kp[e], W[e]);
                     W[e] = fmaf(rr[i], k[e], W[e]);
                     wd = fmaf(k[e], W[e], wd);
                     wn = fmaf(W[e], W[e], wn);
+                    bd = fmaf(k[e], Bs[e], bd);
                 }
-                pw[i] = wd; pn[i] = wn;
+                pw[i] = wd; pn[i] = wn; pb[i] = bd;
                 __builtin_amdgcn_sched_barrier(0);                    // one row at a time
             }
-            if (s == 0) { red_wd.template push<0>(pw, wd_m); red_wn.template push<0>(pn, wn_m); }
-            if (s == 1) { red_wd.template push<1>(pw, wd_m); red_wn.template push<1>(pn, wn_m); }
+            if (s == 0) { red_wd.template push<0>(pw, wd_m); red_wn.template push<0>(pn, wn_m); red_bd.template push<0>(pb, bd_m); }
+            if (s == 1) { red_wd.template push<1>(pw, wd_m); red_wn.template push<1>(pn, wn_m); red_bd.template push<1>(pb, bd_m); }
             if constexpr (LPR == 16) {
-                if (s == 2) { red_wd.template push<2>(pw, wd_m); red_wn.template push<2>(pn, wn_m); }
-                if (s == 3) { red_wd.template push<3>(pw, wd_m); red_wn.template push<3>(pn, wn_m); }
+                if (s == 2) { red_wd.template push<2>(pw, wd_m); red_wn.template push<2>(pn, wn_m); red_bd.template push<2>(pb, bd_m); }
+                if (s == 3) { red_wd.template push<3>(pw, wd_m); red_wn.template push<3>(pn, wn_m); red_bd.template push<3>(pb, bd_m); }
             }
             __builtin_amdgcn_sched_barrier(0);                        // one step at a time
         }
     }
     const int tok = blk_lo + 64 * w + lane;                           // lane (g, c) reports token g*TPT + c
-    if (tok < blk_hi) a_raw[2 * rows + row0 + tok] = neg_cos(rn_m * wd_m, kn_m, wn_m);
+    if (tok < blk_hi) {
+        a_raw[2 * rows + row0 + tok] = neg_cos(rn_m * wd_m, kn_m, wn_m);
+        a_raw[rows + row0 + tok] = neg_cos(rn_m * bd_m, kn_m, bsq);
+    }
 
-    // ---- episodic and stable dots against the two fixed anchors ----
-    // The unit's sum is normally long since there when a workgroup gets here.
+    // ---- stable dots against the unit's sum ----
+    // The sum is normally there when a workgroup gets here.
     float S[8];
     float ssq = 1.f;
     bool have_S = false;
@@ -673,28 +677,20 @@ void scan_kernel(const uint16_t *__restrict__ keys, RowMap km, PromptTab tab, fl
         for (int e = 0; e < 8; ++e) ssq = fmaf(S[e], S[e], ssq);
         ssq = row_sum<LPR>(ssq);
     }
-#pragma unroll
-    for (int e = 0; e < 8; ++e) asm volatile("" : "+v"(Bs[e]));
-#pragma unroll
-    for (int j = 0; j < TPT; ++j) forget(raw[j]);
-    float bd[TPT], sd[TPT];
-#pragma unroll
-    for (int j = 0; j < TPT; ++j) {
-        float k[8];
-        unpack8(raw[j], k);
-        float accb = 0.f, accs = 0.f;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            accb = fmaf(k[e], Bs[e], accb);
-            if (FUSED) accs = fmaf(k[e], S[e], accs);
-        }
-        bd[j] = accb;
-        sd[j] = accs;
-        if ((j & 3) == 3) __builtin_amdgcn_sched_barrier(0);
-    }
-    const float bd_m = transpose_reduce<LPR>(bd);
-    if (tok < blk_hi) a_raw[rows + row0 + tok] = neg_cos(rn_m * bd_m, kn_m, bsq);
     if (FUSED && have_S) {
+#pragma unroll
+        for (int j = 0; j < TPT; ++j) forget(raw[j]);
+        float sd[TPT];
+#pragma unroll
+        for (int j = 0; j < TPT; ++j) {
+            float k[8];
+            unpack8(raw[j], k);
+            float accs = 0.f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) accs = fmaf(k[e], S[e], accs);
+            sd[j] = accs;
+            if ((j & 3) == 3) __builtin_amdgcn_sched_barrier(0);
+        }
         const float sd_m = transpose_reduce<LPR>(sd);
         if (tok < blk_hi) a_raw[row0 + tok] = neg_cos(rn_m * sd_m, kn_m, ssq);
     }
