@@ -198,7 +198,7 @@ __global__ __launch_bounds__(kThreads) void finalize_kernel(const float *__restr
 // ------------------------------------------------------------------------------------------------------
 // stats[(u * 3 + k) * 4 + {0, 1, 2}] = min, 1 / range (0 if flat), reliability gap of scale k of unit u
 template <int EPT>
-__global__ __launch_bounds__(kSelThreads, 8) void scale_stats_kernel(const float *__restrict__ a_raw, int L, int H,
+__global__ __launch_bounds__(kSelThreads, EPT <= 16 ? 8 : 4) void scale_stats_kernel(const float *__restrict__ a_raw, int L, int H,
                                                                    PromptTab tab, int u0, float *__restrict__ stats)
 {
     __shared__ SelectScratch sel;
