@@ -769,11 +769,19 @@ __global__ __launch_bounds__(64 * NW) void unit_sum_repair_kernel(const float *_
                               ssum_unit, part, 0u);
 }
 
-// 16-byte fill, grid-stride
-__global__ __launch_bounds__(256) void fill_kernel(uint4 *p, size_t n16, uint32_t value)
+// What the fused pass expects to find in memory, in one launch: counters at zero, block totals and unit sums
+// "unwritten".  16-byte stores, grid-stride over the three areas one after the other.
+__global__ __launch_bounds__(256) void prepare_kernel(uint4 *sync, size_t n_sync, uint4 *bsum, size_t n_bsum,
+                                                      uint4 *ssum, size_t n_ssum)
 {
-    const uint4 v = make_uint4(value, value, value, value);
-    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += (size_t)gridDim.x * blockDim.x) p[i] = v;
+    const uint4 zero = make_uint4(0u, 0u, 0u, 0u);
+    const uint4 none = make_uint4(kUnwritten, kUnwritten, kUnwritten, kUnwritten);
+    const size_t total = n_sync + n_bsum + n_ssum;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
+        if (i < n_sync) sync[i] = zero;
+        else if (i < n_sync + n_bsum) bsum[i - n_sync] = none;
+        else ssum[i - n_sync - n_bsum] = none;
+    }
 }
 
 // grid (prompts, L*H): stable anchor (up to length) = sum of the prompt's block totals, in block order
@@ -878,9 +886,9 @@ hipError_t run_nw(const uint16_t *keys, const RowMap &km, int LH, const PromptTa
     if (fused) {
         // the counters start at zero, block totals and unit sums as "unwritten"
         const size_t nb = (size_t)LH * tab.blk_off[tab.n] * D / 4, ns = (size_t)LH * tab.n * D / 4;
-        fill_kernel<<<1, 256, 0, st>>>((uint4 *)sync_area, kSyncWords / 4, 0u);
-        fill_kernel<<<(unsigned)min((nb + 255) / 256, (size_t)2048), 256, 0, st>>>((uint4 *)bsum, nb, kUnwritten);
-        fill_kernel<<<(unsigned)min((ns + 255) / 256, (size_t)2048), 256, 0, st>>>((uint4 *)ssum, ns, kUnwritten);
+        const size_t n16 = kSyncWords / 4 + nb + ns;
+        prepare_kernel<<<(unsigned)min((n16 + 255) / 256, (size_t)2048), 256, 0, st>>>(
+            (uint4 *)sync_area, kSyncWords / 4, (uint4 *)bsum, nb, (uint4 *)ssum, ns);
         prof.begin(NKV_KERNEL_SCAN, st);
         launch_scan<D, NW, true>(keys, km, LH, tab, a_raw, bsum, ssum, (uint32_t *)sync_area,
                                  defer_all ? -1 : kPollLimit, no_unit_sums ? 0u : kSpinLimit, st);
