@@ -343,3 +343,35 @@ def test_layer_by_layer_calls_equal_the_batched_call():
                 assert torch.equal(out.kept_idx[a:b], ref.kept_idx[o:o + b - a])
                 assert np.array_equal(bits(out.packed_k[a:b]), bits(ref.packed_k[o:o + b - a]))
                 assert np.array_equal(bits(out.packed_v[a:b]), bits(ref.packed_v[o:o + b - a]))
+
+
+def test_the_three_calls_can_be_captured_in_a_hip_graph_and_replayed():
+    """The calls only enqueue kernels on the given stream (no allocation, no synchronisation, no memset
+    nodes), so a serving loop can record them once and replay: every replay, with eager work and
+    synchronisations in between, gives the eager result bit for bit."""
+    w = nkv_inputs.small_workload("graph", 2, 4, 128, [3000, 700])
+    K, V = _kv(w)
+    ref, shape = run_gpu(w, K, V, 0.75)                       # eager, also warms every lazily initialised path
+    ref = [t.clone() for t in (ref.scores, ref.k_per_head, ref.head_off, ref.kept_idx, ref.packed_k.view(torch.int16),
+                               ref.packed_v.view(torch.int16))]
+    comp = nkv.Compressor(shape, [0.75, 0.75])
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        comp.run(K, V, side)                                   # warm-up on the capture stream
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            comp.run(K, V, torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    for rep in range(3):
+        for t in (comp.scores, comp.kept_idx, comp.packed_k, comp.packed_v):
+            t.zero_()                                          # eager work between the replays
+        comp.k_per_head.fill_(-1)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = (comp.scores, comp.k_per_head, comp.head_off, comp.kept_idx[:comp.rows],
+               comp.packed_k[:comp.rows].view(torch.int16), comp.packed_v[:comp.rows].view(torch.int16))
+        for a, b in zip(got, ref):
+            assert torch.equal(a, b), f"replay {rep}"
