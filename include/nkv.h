@@ -58,8 +58,10 @@ enum {
                                       /* over the keys instead of inside the single fused pass             */
     NKV_FLAG_DEFER_STABLE = 4u,       /* streaming kernels, fused pass: no workgroup waits for its unit's   */
                                       /* sum; every block takes the deferred route (exercises that route)   */
-    NKV_FLAG_NO_UNIT_SUMS = 8u        /* as DEFER_STABLE, and the pass forms no unit sum either: all of     */
+    NKV_FLAG_NO_UNIT_SUMS = 8u,       /* as DEFER_STABLE, and the pass forms no unit sum either: all of     */
                                       /* them come from the kernel that fills in missing ones (exercises it) */
+    NKV_FLAG_BUDGET_PER_HEAD = 16u    /* nkv_budget: the kernels that hold a whole head in one workgroup     */
+                                      /* instead of the slice-wise ones                                      */
 };
 /* Kernels a caller can ask to have timed, see nkv_params.prof_start. */
 enum {

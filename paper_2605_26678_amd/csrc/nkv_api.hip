@@ -314,7 +314,8 @@ int nkv_budget(const float *scores, const nkv_shape *shape, const nkv_params *pa
         if (rc) return rc;
     }
     const Prof prof{params->prof_start, params->prof_stop};
-    return launch_budget(scores, shape->L, shape->H, tab, k_per_head, ws, prof, (hipStream_t)hip_stream) == hipSuccess
+    return launch_budget(scores, shape->L, shape->H, tab, k_per_head, ws,
+                         (params->flags & NKV_FLAG_BUDGET_PER_HEAD) != 0, prof, (hipStream_t)hip_stream) == hipSuccess
                ? NKV_OK : NKV_EHIP;
 }
 

@@ -11,7 +11,9 @@
 //   C. B_h = m_safe + #{pool entries of head h above TL} + its share of the ties at TL.
 // All selects are radix selects on an order-preserving integer image of the fp32 scores: exact integer work.
 //
-// Two implementations:
+// Three implementations:
+//   * layers of up to 8 heads, any prompt length: the slice-wise kernels of nkv_budget_wide.hip (the default
+//     for prompts of more than 8192 tokens);
 //   * prompts of up to 32768 tokens and layers of up to 8 heads: head_safe_kernel (one workgroup per
 //     (prompt, layer, head), scores in registers, step A plus a 2048-bin histogram of the head's pool on
 //     the top 11 key bits) and layer_budget_kernel (one workgroup per (prompt, layer): the top digit from
@@ -241,8 +243,10 @@ __global__ __launch_bounds__(kThreads) void layer_budget_kernel(const float *__r
 
 // ---------------------------------------------------------------------------------------------------
 // Shape-generic version: any prompt length, up to NKV_MAX_HEADS heads.
+// only_if (may be NULL): one word per (prompt, layer); layers whose word is zero are left alone.
 __global__ __launch_bounds__(kThreads) void budget_kernel(const float *__restrict__ scores, int L, int H,
-                                                          PromptTab tab, int32_t *__restrict__ k_per_head)
+                                                          PromptTab tab, const uint32_t *__restrict__ only_if,
+                                                          int32_t *__restrict__ k_per_head)
 {
     __shared__ uint32_t hist[NKV_MAX_HEADS][256];      // 32 KB
     __shared__ uint32_t Th[NKV_MAX_HEADS];             // key of the m_safe-th best score of the head
@@ -253,6 +257,7 @@ __global__ __launch_bounds__(kThreads) void budget_kernel(const float *__restric
     __shared__ uint32_t TL, want_l;
 
     const int pl = blockIdx.x;                          // p * L + l
+    if (only_if && only_if[pl] == 0u) return;
     const int l = pl % L, p = pl / L;
     const int N = tab.tok_off[p + 1] - tab.tok_off[p];
     const int k0 = tab.k0[p], m_safe = tab.m_safe[p];
@@ -363,17 +368,27 @@ __global__ __launch_bounds__(kThreads) void budget_kernel(const float *__restric
 size_t budget_ws_bytes(int L, int H, const PromptTab &tab)
 {
     const size_t units = (size_t)tab.n * L * H;
-    return units * sizeof(HeadSafe) + units * 2048 * sizeof(uint32_t);
+    const size_t per_head = units * sizeof(HeadSafe) + units * 2048 * sizeof(uint32_t);
+    const size_t wide = budget_wide_supported(H) ? budget_wide_ws_bytes(L, H, tab) : 0;
+    return per_head > wide ? per_head : wide;
 }
 
 hipError_t launch_budget(const float *scores, int L, int H, const PromptTab &tab, int32_t *k_per_head, void *ws,
-                         const Prof &prof, hipStream_t st)
+                         bool per_head_route, const Prof &prof, hipStream_t st)
 {
     int nmax = 0;
     for (int p = 0; p < tab.n; ++p) nmax = max(nmax, tab.tok_off[p + 1] - tab.tok_off[p]);
     const unsigned units = (unsigned)(tab.n * L * H);
     prof.begin(NKV_KERNEL_BUDGET, st);
-    if (ws != nullptr && H <= kFastHeads && nmax <= 32 * kSelThreads) {
+    // Slice-wise kernels where a head has more than one slice (five small launches); below that the two
+    // per-head launches are quicker.
+    const bool per_head_ok = ws != nullptr && H <= kFastHeads && nmax <= 32 * kSelThreads;
+    if (ws != nullptr && budget_wide_supported(H) && !(per_head_ok && (per_head_route || nmax <= 8192))) {
+        const uint32_t *failed = nullptr;
+        hipError_t e = launch_budget_wide(scores, L, H, tab, k_per_head, ws, &failed, st);
+        if (e != hipSuccess) return e;
+        budget_kernel<<<(unsigned)(tab.n * L), kThreads, 0, st>>>(scores, L, H, tab, failed, k_per_head);
+    } else if (per_head_ok) {
         HeadSafe *safe = (HeadSafe *)ws;
         uint32_t *pool_hist = (uint32_t *)(safe + units);
         for_each_length_class(tab, L * H, [&](int ept, int u0, int n) {
@@ -384,7 +399,7 @@ hipError_t launch_budget(const float *scores, int L, int H, const PromptTab &tab
         });
         layer_budget_kernel<<<(unsigned)(tab.n * L), kThreads, 0, st>>>(scores, L, H, tab, safe, pool_hist, k_per_head);
     } else {
-        budget_kernel<<<(unsigned)(tab.n * L), kThreads, 0, st>>>(scores, L, H, tab, k_per_head);
+        budget_kernel<<<(unsigned)(tab.n * L), kThreads, 0, st>>>(scores, L, H, tab, nullptr, k_per_head);
     }
     prof.end(NKV_KERNEL_BUDGET, st);
     return hipGetLastError();

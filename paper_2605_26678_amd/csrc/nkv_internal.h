@@ -97,8 +97,14 @@ hipError_t launch_finalize(const float *a_raw, int L, int H, const PromptTab &ta
 // ---- head-wise budgets ----
 size_t budget_ws_bytes(int L, int H, const PromptTab &tab);
 // ws == nullptr selects the shape-generic kernel, which needs no scratch
+// per_head_route: use the kernels that hold a head in one workgroup instead of the slice-wise ones
 hipError_t launch_budget(const float *scores, int L, int H, const PromptTab &tab, int32_t *k_per_head, void *ws,
-                         const Prof &prof, hipStream_t st);
+                         bool per_head_route, const Prof &prof, hipStream_t st);
+// slice-wise kernels (nkv_budget_wide.hip)
+bool budget_wide_supported(int H);
+size_t budget_wide_ws_bytes(int L, int H, const PromptTab &tab);
+hipError_t launch_budget_wide(const float *scores, int L, int H, const PromptTab &tab, int32_t *k_per_head, void *ws,
+                              const uint32_t **failed_flags, hipStream_t st);
 
 // ---- selection, ordered compaction, gather ----
 hipError_t launch_select_compact(const void *keys, const void *values, const RowMap &km, const RowMap &vm,

@@ -140,6 +140,16 @@ def test_heavy_ties_stage_parity():
         assert np.array_equal(bits(out.packed_k), ref.packed_k) and np.array_equal(bits(out.packed_v), ref.packed_v)
 
 
+@pytest.mark.parametrize("flags", [0, nkv.FLAG_BUDGET_PER_HEAD])
+def test_budget_routes_meet_the_stage_bar(flags):
+    """Slice-wise and per-head budget kernels on a shape both cover (one prompt of several slices, one short,
+    one of exactly two slices), fed the oracle's scores: bit-exact budgets either way."""
+    w = nkv_inputs.small_workload("budget_routes", 2, 4, 128, [20000, 700, 16384])
+    K, V = _kv(w)
+    for r in (0.5, 0.9, 0.97):
+        compare_stages(w, K, V, r, params=nkv.params_default(flags=flags), label=f"budget flags={flags} r={r}")
+
+
 def test_budget_without_workspace_uses_the_generic_kernel():
     w = nkv_inputs.small_workload("nows", 2, 4, 64, [3000, 200])
     K, V = _kv(w)
