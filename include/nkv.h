@@ -60,8 +60,9 @@ enum {
                                       /* sum; every block takes the deferred route (exercises that route)   */
     NKV_FLAG_NO_UNIT_SUMS = 8u,       /* as DEFER_STABLE, and the pass forms no unit sum either: all of     */
                                       /* them come from the kernel that fills in missing ones (exercises it) */
-    NKV_FLAG_BUDGET_PER_HEAD = 16u    /* nkv_budget: the kernels that hold a whole head in one workgroup     */
+    NKV_FLAG_BUDGET_PER_HEAD = 16u,   /* nkv_budget: the kernels that hold a whole head in one workgroup     */
                                       /* instead of the slice-wise ones                                      */
+    NKV_FLAG_STATS_PER_HEAD = 32u     /* nkv_score: the same choice for the per-head statistics              */
 };
 /* Kernels a caller can ask to have timed, see nkv_params.prof_start. */
 enum {

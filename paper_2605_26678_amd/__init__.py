@@ -22,6 +22,7 @@ FLAG_TWO_PASS_STABLE = 2
 FLAG_DEFER_STABLE = 4
 FLAG_NO_UNIT_SUMS = 8
 FLAG_BUDGET_PER_HEAD = 16
+FLAG_STATS_PER_HEAD = 32
 PIN = 3.0e38
 
 EXPORTS = ("nkv_params_default", "nkv_block_size", "nkv_k0", "nkv_m_safe", "nkv_m_p", "nkv_packed_rows",

@@ -109,7 +109,7 @@ void fill_tab(const nkv_shape *s, const nkv_params *p, PromptTab *tab)
 
 // Workspace of the scoring call, in floats from the (aligned) start.
 struct ScoreWs {
-    size_t sync, a_raw, rnorm, bsum, ssum, stats, total_bytes;
+    size_t sync, a_raw, rnorm, bsum, ssum, stats, wide, total_bytes;
 };
 
 ScoreWs score_ws(const nkv_shape *s, const PromptTab &tab, bool with_a_raw)
@@ -124,6 +124,7 @@ ScoreWs score_ws(const nkv_shape *s, const PromptTab &tab, bool with_a_raw)
     w.bsum = off;   off += align_up(LH * tab.blk_off[tab.n] * s->d * 4);
     w.ssum = off;   off += align_up(LH * tab.n * s->d * 4);
     w.stats = off;  off += align_up(LH * tab.n * 3 * 4 * 4);                 // per unit and scale: min, 1/range, gap
+    w.wide = off;   off += with_a_raw ? align_up(stats_wide_ws_bytes(s->L, s->H, tab)) : 0;
     w.total_bytes = off;
     return w;
 }
@@ -289,7 +290,10 @@ int nkv_score(const void *keys, const nkv_shape *shape, const nkv_params *params
     lc.gate_mode = params->gate_mode;
     lc.surprise_mode = params->surprise_mode;
     const Prof prof{params->prof_start, params->prof_stop};
-    return launch_finalize(a_raw, shape->L, shape->H, tab, lc, scores, (float *)((char *)ws + lay.stats), prof, st) == hipSuccess ? NKV_OK : NKV_EHIP;
+    return launch_finalize(a_raw, shape->L, shape->H, tab, lc, scores, (float *)((char *)ws + lay.stats),
+                           (char *)ws + lay.wide, (params->flags & NKV_FLAG_STATS_PER_HEAD) != 0, prof,
+                           st) == hipSuccess
+               ? NKV_OK : NKV_EHIP;
 }
 
 int nkv_budget(const float *scores, const nkv_shape *shape, const nkv_params *params, const double *r_per_prompt,

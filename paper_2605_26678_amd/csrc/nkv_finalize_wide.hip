@@ -1,0 +1,358 @@
+// Per-head statistics of the three anomaly scales (paper Sections 2.3-2.4: min-max range, reliability gap =
+// mean of the m_p largest minus mean of the m_p smallest normalised anomalies) spread over the whole chip.
+//
+// Same numbers as scale_stats_kernel in nkv_finalize.hip (up to the order of floating-point additions), but a
+// head's anomalies are not held by one workgroup: they are cut into slices of 8192 tokens and every step
+// that touches them runs on one small workgroup per (slice, scale).
+//
+// Anomalies are -cos, so they lie in [-1, 1]; they are binned by value, bin(a) = floor(1023.5 (a + 1)), a
+// monotone map.  "The m largest" is then: all bins above a boundary bin plus the largest few of the boundary
+// bin's entries, and only those entries are looked at exactly; likewise from below.
+//   stats_hist_kernel    (slice, scale)  2048-bin histogram as 16-bit counts; min and max of the slice
+//   stats_pick_kernel    (unit, scale)   the bins that hold the m-th largest and the m-th smallest value
+//   stats_collect_kernel (slice, scale)  sums of the values above the upper / below the lower boundary bin;
+//                                        the boundary bins' entries (as order-preserving keys) into two short
+//                                        lists per slice
+//   stats_finish_kernel  (unit, scale)   one wavefront: exact thresholds inside the boundary bins, the two
+//                                        means, min, 1/range, gap
+// A list that overflows (hundreds of values of one slice in one bin) marks the (unit, scale) and the per-head
+// kernel, launched behind and idle otherwise, computes it.
+#include "nkv_wavesel.h"
+
+namespace nkv {
+namespace {
+
+constexpr int kSlice = 8192;             // tokens per slice (counts of a slice fit 16 bits)
+constexpr int kBins = 2048;
+constexpr int kWideThreads = 256;
+constexpr int kPerThread = kSlice / kWideThreads;
+constexpr int kSeg = 256;                // keys one slice may contribute to a list
+constexpr int kList = 1024;              // keys the finishing wavefront takes per list
+
+struct SliceTab {                        // first slice of every prompt; a prompt has L*H*S_p slices, head-major
+    int32_t off[NKV_MAX_PROMPTS + 1];
+};
+
+struct StatPick {
+    int32_t bTop, bBot;                  // boundary bins
+    uint32_t needTop, needBot;           // how many of their entries belong to the m largest / smallest
+};
+
+struct SlicePart {                       // what one slice contributes besides its histogram and lists
+    float lo, hi;                        // min, max of the slice
+    uint32_t nTop, nBot;                 // entries in the two lists
+    double sTop, sBot;                   // sums above the upper / below the lower boundary bin
+};
+
+__device__ __forceinline__ int anomaly_bin(float a)
+{
+    const float x = (a + 1.0f) * 1023.5f;
+    return x >= 2047.0f ? 2047 : (x > 0.f ? (int)x : 0);
+}
+
+__device__ __forceinline__ void locate(const SliceTab &st, const PromptTab &tab, int id, int &p, int &lh, int &s,
+                                       int &S)
+{
+    p = 0;
+    while (p + 1 < tab.n && id >= st.off[p + 1]) ++p;
+    const int N = tab.tok_off[p + 1] - tab.tok_off[p];
+    S = (N + kSlice - 1) / kSlice;
+    const int local = id - st.off[p];
+    lh = local / S;
+    s = local - lh * S;
+}
+
+// grid (slices, 3)
+__global__ __launch_bounds__(kWideThreads) void stats_hist_kernel(const float *__restrict__ a_raw, int64_t rows,
+                                                                  PromptTab tab, SliceTab st, int n_slices,
+                                                                  uint16_t *__restrict__ part,
+                                                                  SlicePart *__restrict__ sp)
+{
+    __shared__ uint32_t hist[kBins];
+    __shared__ float red[2][kWideThreads / 64];
+    int p, lh, s, S;
+    locate(st, tab, blockIdx.x, p, lh, s, S);
+    const int k = blockIdx.y;
+    const int N = tab.tok_off[p + 1] - tab.tok_off[p];
+    const float *a = a_raw + (int64_t)k * rows + (int64_t)lh * tab.T + tab.tok_off[p];
+    const int tid = threadIdx.x;
+    for (int j = tid; j < kBins; j += kWideThreads) hist[j] = 0u;
+    float v[kPerThread];
+#pragma unroll
+    for (int j = 0; j < kPerThread; ++j) v[j] = a[min(s * kSlice + j * kWideThreads + tid, N - 1)];
+    __syncthreads();
+    float lo = INFINITY, hi = -INFINITY;                             // the clamped duplicates do not change min / max
+#pragma unroll
+    for (int j = 0; j < kPerThread; ++j) {
+        lo = fminf(lo, v[j]);
+        hi = fmaxf(hi, v[j]);
+        if (s * kSlice + j * kWideThreads + tid < N) atomicAdd(&hist[anomaly_bin(v[j])], 1u);
+    }
+    lo = wave_min(lo);
+    hi = wave_max(hi);
+    if ((tid & 63) == 0) { red[0][tid >> 6] = lo; red[1][tid >> 6] = hi; }
+    __syncthreads();
+    const int64_t job_slice = (int64_t)k * n_slices + blockIdx.x;
+    if (tid == 0) {
+        for (int i = 1; i < kWideThreads / 64; ++i) { lo = fminf(lo, red[0][i]); hi = fmaxf(hi, red[1][i]); }
+        sp[job_slice].lo = lo;
+        sp[job_slice].hi = hi;
+    }
+    const uint32_t *h8 = hist + tid * 8;
+    const uint4 out = make_uint4(h8[0] | (h8[1] << 16), h8[2] | (h8[3] << 16), h8[4] | (h8[5] << 16),
+                                 h8[6] | (h8[7] << 16));
+    reinterpret_cast<uint4 *>(part + job_slice * kBins)[tid] = out;
+}
+
+// grid (units, 3); 256 threads, 8 bins each
+__global__ __launch_bounds__(kWideThreads) void stats_pick_kernel(int L, int H, PromptTab tab, SliceTab st,
+                                                                  int n_slices, const uint16_t *__restrict__ part,
+                                                                  StatPick *__restrict__ picks,
+                                                                  uint32_t *__restrict__ failed)
+{
+    __shared__ uint32_t wtot[kWideThreads / 64];
+    const int u = blockIdx.x, k = blockIdx.y;
+    const int lh = u % (L * H), p = u / (L * H);
+    const int N = tab.tok_off[p + 1] - tab.tok_off[p];
+    const int S = (N + kSlice - 1) / kSlice;
+    const uint32_t m = (uint32_t)min(tab.m_p[p], N);
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const uint4 *rows = reinterpret_cast<const uint4 *>(part + ((int64_t)k * n_slices + st.off[p] + (int64_t)lh * S) * kBins);
+    uint32_t c[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) c[i] = 0u;
+    for (int s0 = 0; s0 < S; s0 += 4) {
+        uint4 r[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) r[i] = rows[(int64_t)min(s0 + i, S - 1) * (kBins / 8) + tid];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            if (s0 + i < S) {
+                c[0] += r[i].x & 0xffffu; c[1] += r[i].x >> 16; c[2] += r[i].y & 0xffffu; c[3] += r[i].y >> 16;
+                c[4] += r[i].z & 0xffffu; c[5] += r[i].z >> 16; c[6] += r[i].w & 0xffffu; c[7] += r[i].w >> 16;
+            }
+        }
+    }
+    uint32_t group = 0u;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) group += c[i];
+    uint32_t incl = group;                                           // inclusive prefix from bin 0 upwards
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const uint32_t t = __shfl_up(incl, o, 64);
+        if (lane >= o) incl += t;
+    }
+    if (lane == 63) wtot[w] = incl;
+    __syncthreads();
+    for (int ww = 0; ww < w; ++ww) incl += wtot[ww];
+    const uint32_t below = incl - group;                             // entries in bins below this thread's eight
+    const uint32_t above = (uint32_t)N - incl;                       // entries in bins above them
+    StatPick *out = picks + (int64_t)u * 3 + k;
+    if (below < m && m <= incl) {                                    // the m-th smallest lies in one of my bins
+        uint32_t cum = below;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            if (cum < m && m <= cum + c[i]) { out->bBot = tid * 8 + i; out->needBot = m - cum; }
+            cum += c[i];
+        }
+    }
+    if (above < m && m <= above + group) {                           // the m-th largest lies in one of my bins
+        uint32_t cum = above;
+#pragma unroll
+        for (int i = 7; i >= 0; --i) {
+            if (cum < m && m <= cum + c[i]) { out->bTop = tid * 8 + i; out->needTop = m - cum; }
+            cum += c[i];
+        }
+    }
+    if (tid == 0) failed[(int64_t)u * 3 + k] = 0u;
+}
+
+// grid (slices, 3)
+__global__ __launch_bounds__(kWideThreads) void stats_collect_kernel(const float *__restrict__ a_raw, int64_t rows,
+                                                                     int L, int H, PromptTab tab, SliceTab st,
+                                                                     int n_slices,
+                                                                     const StatPick *__restrict__ picks,
+                                                                     uint32_t *__restrict__ segTop,
+                                                                     uint32_t *__restrict__ segBot,
+                                                                     SlicePart *__restrict__ sp,
+                                                                     uint32_t *__restrict__ failed)
+{
+    __shared__ uint32_t nTop, nBot;
+    __shared__ double red[2][kWideThreads / 64];
+    int p, lh, s, S;
+    locate(st, tab, blockIdx.x, p, lh, s, S);
+    const int k = blockIdx.y;
+    const int N = tab.tok_off[p + 1] - tab.tok_off[p];
+    const float *a = a_raw + (int64_t)k * rows + (int64_t)lh * tab.T + tab.tok_off[p];
+    const int tid = threadIdx.x;
+    float v[kPerThread];
+#pragma unroll
+    for (int j = 0; j < kPerThread; ++j) v[j] = a[min(s * kSlice + j * kWideThreads + tid, N - 1)];
+    const int64_t job = ((int64_t)p * L * H + lh) * 3 + k;
+    const StatPick pk = picks[job];
+    if (tid == 0) { nTop = 0u; nBot = 0u; }
+    __syncthreads();
+    const int64_t job_slice = (int64_t)k * n_slices + blockIdx.x;
+    uint32_t *outTop = segTop + job_slice * kSeg, *outBot = segBot + job_slice * kSeg;
+    float pt = 0.f, pb = 0.f;                                        // a few dozen terms of magnitude <= 1 each
+#pragma unroll
+    for (int j = 0; j < kPerThread; ++j) {
+        if (s * kSlice + j * kWideThreads + tid < N) {
+            const int b = anomaly_bin(v[j]);
+            pt += b > pk.bTop ? v[j] : 0.f;
+            pb += b < pk.bBot ? v[j] : 0.f;
+            if (b == pk.bTop) {
+                const uint32_t at = atomicAdd(&nTop, 1u);
+                if (at < (uint32_t)kSeg) outTop[at] = ord_key(v[j]);
+            }
+            if (b == pk.bBot) {
+                const uint32_t at = atomicAdd(&nBot, 1u);
+                if (at < (uint32_t)kSeg) outBot[at] = ~ord_key(v[j]);     // inverted: the smallest value has the largest key
+            }
+        }
+    }
+    const double st_ = wave_sum((double)pt), sb_ = wave_sum((double)pb);
+    if ((tid & 63) == 0) { red[0][tid >> 6] = st_; red[1][tid >> 6] = sb_; }
+    __syncthreads();
+    if (tid == 0) {
+        double t = 0.0, b = 0.0;
+        for (int i = 0; i < kWideThreads / 64; ++i) { t += red[0][i]; b += red[1][i]; }
+        sp[job_slice].sTop = t;
+        sp[job_slice].sBot = b;
+        sp[job_slice].nTop = nTop;
+        sp[job_slice].nBot = nBot;
+        if (nTop > (uint32_t)kSeg || nBot > (uint32_t)kSeg) failed[job] = 1u;
+    }
+}
+
+// grid (units, 3); one wavefront.  stats[(u * 3 + k) * 4 + {0, 1, 2}] = min, 1 / range (0 if flat), gap
+__global__ __launch_bounds__(64) void stats_finish_kernel(int L, int H, PromptTab tab, SliceTab st, int n_slices,
+                                                          const StatPick *__restrict__ picks,
+                                                          const uint32_t *__restrict__ segTop,
+                                                          const uint32_t *__restrict__ segBot,
+                                                          const SlicePart *__restrict__ sp,
+                                                          uint32_t *__restrict__ failed, float *__restrict__ stats)
+{
+    __shared__ uint32_t keys[2][kList];
+    __shared__ uint32_t hist[256];
+    const int u = blockIdx.x, k = blockIdx.y;
+    const int64_t job = (int64_t)u * 3 + k;
+    if (failed[job]) return;
+    const int lh = u % (L * H), p = u / (L * H);
+    const int N = tab.tok_off[p + 1] - tab.tok_off[p];
+    const int S = (N + kSlice - 1) / kSlice;
+    const uint32_t m = (uint32_t)min(tab.m_p[p], N);
+    const int lane = threadIdx.x;
+    const int64_t slice0 = (int64_t)k * n_slices + st.off[p] + (int64_t)lh * S;
+    const StatPick pk = picks[job];
+    // slices in order: lists, sums, min, max
+    uint32_t nT = 0u, nB = 0u;
+    double sTop = 0.0, sBot = 0.0;
+    float lo = INFINITY, hi = -INFINITY;
+    bool bad = false;
+    for (int s = 0; s < S; ++s) {
+        const SlicePart q = sp[slice0 + s];
+        if (q.nTop > (uint32_t)kSeg || q.nBot > (uint32_t)kSeg || nT + q.nTop > (uint32_t)kList ||
+            nB + q.nBot > (uint32_t)kList) {
+            bad = true;
+            break;
+        }
+        for (uint32_t i = lane; i < q.nTop; i += 64) keys[0][nT + i] = segTop[(slice0 + s) * kSeg + i];
+        for (uint32_t i = lane; i < q.nBot; i += 64) keys[1][nB + i] = segBot[(slice0 + s) * kSeg + i];
+        nT += q.nTop;
+        nB += q.nBot;
+        sTop += q.sTop;
+        sBot += q.sBot;
+        lo = fminf(lo, q.lo);
+        hi = fmaxf(hi, q.hi);
+    }
+    if (bad) {
+        if (lane == 0) failed[job] = 1u;
+        return;
+    }
+    __builtin_amdgcn_wave_barrier();
+    // upper boundary bin: the needTop largest of its entries belong to the m largest
+    uint32_t gt, eq;
+    const uint32_t Tt = wave_select(keys[0], (int)nT, pk.needTop, hist, gt, eq);
+    float part = 0.f;
+    for (uint32_t i = lane; i < nT; i += 64) part += keys[0][i] > Tt ? key_value(keys[0][i]) : 0.f;
+    double top = sTop + wave_sum((double)part) + (double)(pk.needTop - gt) * (double)key_value(Tt);
+    // lower boundary bin, on inverted keys
+    const uint32_t Tb = wave_select(keys[1], (int)nB, pk.needBot, hist, gt, eq);
+    part = 0.f;
+    for (uint32_t i = lane; i < nB; i += 64) part += keys[1][i] > Tb ? key_value(~keys[1][i]) : 0.f;
+    double bot = sBot + wave_sum((double)part) + (double)(pk.needBot - gt) * (double)key_value(~Tb);
+    if (lane == 0) {
+        const float range = hi - lo;
+        const float inv = range < kFlat ? 0.f : 1.0f / range;
+        float *o = stats + job * 4;
+        o[0] = lo;
+        o[1] = inv;
+        o[2] = (float)((top - bot) / (double)m * (double)inv);
+    }
+}
+
+struct WideWs {
+    size_t part, sp, picks, segTop, segBot, failed, total;
+};
+
+size_t align256(size_t x) { return (x + 255) / 256 * 256; }
+
+int fill_slices(int L, int H, const PromptTab &tab, SliceTab *st)
+{
+    int n = 0;
+    for (int p = 0; p < tab.n; ++p) {
+        st->off[p] = n;
+        const int N = tab.tok_off[p + 1] - tab.tok_off[p];
+        n += L * H * ((N + kSlice - 1) / kSlice);
+    }
+    st->off[tab.n] = n;
+    return n;
+}
+
+WideWs wide_ws(int L, int H, const PromptTab &tab)
+{
+    SliceTab st;
+    const size_t slices = 3 * (size_t)fill_slices(L, H, tab, &st), jobs = 3 * (size_t)tab.n * L * H;
+    WideWs w;
+    size_t off = 0;
+    w.part = off;    off += align256(slices * kBins * sizeof(uint16_t));
+    w.sp = off;      off += align256(slices * sizeof(SlicePart));
+    w.picks = off;   off += align256(jobs * sizeof(StatPick));
+    w.segTop = off;  off += align256(slices * kSeg * sizeof(uint32_t));
+    w.segBot = off;  off += align256(slices * kSeg * sizeof(uint32_t));
+    w.failed = off;  off += align256(jobs * sizeof(uint32_t));
+    w.total = off;
+    return w;
+}
+
+}  // namespace
+
+size_t stats_wide_ws_bytes(int L, int H, const PromptTab &tab) { return wide_ws(L, H, tab).total; }
+
+// Enqueues the four kernels; *failed_flags receives the device address of the per-(unit, scale) words that are
+// non-zero where `stats` has not been written.
+hipError_t launch_stats_wide(const float *a_raw, int L, int H, const PromptTab &tab, float *stats, void *ws,
+                             const uint32_t **failed_flags, hipStream_t st)
+{
+    SliceTab stab;
+    const int slices = fill_slices(L, H, tab, &stab);
+    const WideWs lay = wide_ws(L, H, tab);
+    char *base = (char *)ws;
+    uint16_t *part = (uint16_t *)(base + lay.part);
+    SlicePart *sp = (SlicePart *)(base + lay.sp);
+    StatPick *picks = (StatPick *)(base + lay.picks);
+    uint32_t *segTop = (uint32_t *)(base + lay.segTop), *segBot = (uint32_t *)(base + lay.segBot);
+    uint32_t *failed = (uint32_t *)(base + lay.failed);
+    const int64_t rows = (int64_t)L * H * tab.T;
+    const unsigned units = (unsigned)(tab.n * L * H);
+    stats_hist_kernel<<<dim3((unsigned)slices, 3), kWideThreads, 0, st>>>(a_raw, rows, tab, stab, slices, part, sp);
+    stats_pick_kernel<<<dim3(units, 3), kWideThreads, 0, st>>>(L, H, tab, stab, slices, part, picks, failed);
+    stats_collect_kernel<<<dim3((unsigned)slices, 3), kWideThreads, 0, st>>>(a_raw, rows, L, H, tab, stab, slices, picks,
+                                                                            segTop, segBot, sp, failed);
+    stats_finish_kernel<<<dim3(units, 3), 64, 0, st>>>(L, H, tab, stab, slices, picks, segTop, segBot, sp, failed, stats);
+    *failed_flags = failed;
+    return hipGetLastError();
+}
+
+}  // namespace nkv

@@ -91,8 +91,15 @@ template <typename F> inline void for_each_length_class(const PromptTab &tab, in
 }
 
 // ---- per-head statistics, blend weights, gate and final scores ----
+// wide_ws: scratch of stats_wide_ws_bytes() for the slice-wise statistics (NULL: per-head kernels only);
+// per_head_route: do not use the slice-wise kernels
 hipError_t launch_finalize(const float *a_raw, int L, int H, const PromptTab &tab, const LearnerConsts &lc,
-                           float *scores, float *stats, const Prof &prof, hipStream_t st);
+                           float *scores, float *stats, void *wide_ws, bool per_head_route, const Prof &prof,
+                           hipStream_t st);
+// slice-wise statistics (nkv_finalize_wide.hip)
+size_t stats_wide_ws_bytes(int L, int H, const PromptTab &tab);
+hipError_t launch_stats_wide(const float *a_raw, int L, int H, const PromptTab &tab, float *stats, void *ws,
+                             const uint32_t **failed_flags, hipStream_t st);
 
 // ---- head-wise budgets ----
 size_t budget_ws_bytes(int L, int H, const PromptTab &tab);

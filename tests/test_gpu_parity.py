@@ -150,6 +150,19 @@ def test_budget_routes_meet_the_stage_bar(flags):
         compare_stages(w, K, V, r, params=nkv.params_default(flags=flags), label=f"budget flags={flags} r={r}")
 
 
+@pytest.mark.parametrize("flags", [0, nkv.FLAG_STATS_PER_HEAD])
+def test_statistics_routes_meet_the_score_bar(flags):
+    """Slice-wise and per-head statistics kernels on a shape both cover (prompts of three slices, of less than
+    one, and of exactly two), against the oracle; constant keys make every value of a scale fall into one
+    bin, which the slice-wise kernels hand over to the per-head kernel."""
+    w = nkv_inputs.small_workload("stat_routes", 1, 3, 128, [20000, 700, 16384])
+    K, V = _kv(w)
+    compare_end_to_end(w, K, V, 0.75, params=nkv.params_default(flags=flags), label=f"stats flags={flags}")
+    Kc = K.clone()
+    Kc[:, 1] = Kc[:, 1, :1]                                   # head 1: one key repeated
+    compare_end_to_end(w, Kc, V, 0.75, params=nkv.params_default(flags=flags), label=f"stats const flags={flags}")
+
+
 def test_budget_without_workspace_uses_the_generic_kernel():
     w = nkv_inputs.small_workload("nows", 2, 4, 64, [3000, 200])
     K, V = _kv(w)
