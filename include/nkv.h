@@ -62,7 +62,8 @@ enum {
                                       /* them come from the kernel that fills in missing ones (exercises it) */
     NKV_FLAG_BUDGET_PER_HEAD = 16u,   /* nkv_budget: the kernels that hold a whole head in one workgroup     */
                                       /* instead of the slice-wise ones                                      */
-    NKV_FLAG_STATS_PER_HEAD = 32u     /* nkv_score: the same choice for the per-head statistics              */
+    NKV_FLAG_STATS_PER_HEAD = 32u,    /* nkv_score: the same choice for the per-head statistics              */
+    NKV_FLAG_SELECT_PER_HEAD = 64u    /* nkv_select_compact: the same choice for the top-B_h selection       */
 };
 /* Kernels a caller can ask to have timed, see nkv_params.prof_start. */
 enum {
@@ -195,7 +196,8 @@ int nkv_budget(const float *scores, const nkv_shape *shape, const nkv_params *pa
  * NULL it receives the number of tokens whose score lies within params->near_tol
  * of their head's selection threshold (the B_h-th highest score), summed over all
  * units with 0 < B_h < N_p; these are the positions whose fate can change under
- * score perturbations of that size.
+ * score perturbations of that size.  `ws` may be NULL (ws_bytes 0): the selection then runs one workgroup per
+ * unit; with scratch (nkv_workspace_bytes) prompts of more than 16384 tokens are selected slice-wise.
  */
 int nkv_select_compact(const void *keys, const void *values, const float *scores,
                        const int32_t *k_per_head, const nkv_shape *shape, const nkv_params *params,

@@ -23,6 +23,7 @@ FLAG_DEFER_STABLE = 4
 FLAG_NO_UNIT_SUMS = 8
 FLAG_BUDGET_PER_HEAD = 16
 FLAG_STATS_PER_HEAD = 32
+FLAG_SELECT_PER_HEAD = 64
 PIN = 3.0e38
 
 EXPORTS = ("nkv_params_default", "nkv_block_size", "nkv_k0", "nkv_m_safe", "nkv_m_p", "nkv_packed_rows",
@@ -341,6 +342,6 @@ class Compressor:
         score(keys, self.shape, self.params, self.scores, self.ws, stream)
         budget(self.scores, self.shape, self.params, self.r, self.k_per_head, self.ws, stream)
         select_compact(keys, values, self.scores, self.k_per_head, self.shape, self.params, self.packed_k,
-                       self.packed_v, self.kept_idx, self.head_off, self.rows, self.near, None, stream)
+                       self.packed_v, self.kept_idx, self.head_off, self.rows, self.near, self.ws, stream)
         return Compressed(self.scores, self.k_per_head, self.head_off, self.kept_idx[:self.rows],
                           self.packed_k[:self.rows], self.packed_v[:self.rows], self.near)

@@ -242,7 +242,8 @@ int nkv_workspace_bytes(const nkv_shape *shape, const nkv_params *params, size_t
     PromptTab tab;
     fill_tab(shape, params, &tab);
     const size_t a = score_ws(shape, tab, true).total_bytes, b = align_up(budget_ws_bytes(shape->L, shape->H, tab));
-    *bytes = a > b ? a : b;                              // selection needs none
+    const size_t c = align_up(select_wide_ws_bytes(shape->L, shape->H, tab));
+    *bytes = a > b ? (a > c ? a : c) : (b > c ? b : c);
     return NKV_OK;
 }
 
@@ -328,7 +329,6 @@ int nkv_select_compact(const void *keys, const void *values, const float *scores
                        int32_t *kept_idx, int64_t *head_off, int64_t row_capacity, int64_t *near_threshold_count,
                        void *ws, size_t ws_bytes, void *hip_stream)
 {
-    (void)ws; (void)ws_bytes;
     if (!keys || !values || !scores || !k_per_head || !head_off || row_capacity < 0) return NKV_EINVAL;
     if (row_capacity > 0 && (!packed_k || !packed_v || !kept_idx)) return NKV_EINVAL;
     int rc = check_shape(shape);
@@ -344,7 +344,12 @@ int nkv_select_compact(const void *keys, const void *values, const float *scores
     if (rc) return rc;
     rc = fill_map(shape, shape->value_strides, shape->dv, &vm);
     if (rc) return rc;
-    return launch_select_compact(keys, values, km, vm, scores, k_per_head, shape->L, shape->H, shape->d, shape->dv,
+    if (ws != nullptr) {
+        rc = check_ws(ws, ws_bytes, select_wide_ws_bytes(shape->L, shape->H, tab));
+        if (rc) return rc;
+    }
+    return launch_select_compact(keys, values, km, vm, (params->flags & NKV_FLAG_SELECT_PER_HEAD) ? nullptr : ws,
+                                 scores, k_per_head, shape->L, shape->H, shape->d, shape->dv,
                                  esize_of(shape->dtype), tab, (float)params->near_tol, packed_k, packed_v,
                                  kept_idx, head_off, row_capacity, near_threshold_count,
                                  Prof{params->prof_start, params->prof_stop}, (hipStream_t)hip_stream) == hipSuccess

@@ -20,24 +20,15 @@
 //                                            over the lists), ties by head order, B_h
 // A list that does not fit (thousands of equal scores in one bin) marks the layer, and the shape-generic
 // kernel of nkv_budget.hip computes that layer instead.
-#include "nkv_wavesel.h"
+#include "nkv_slices.h"
 
 namespace nkv {
 namespace {
 
-constexpr int kSlice = 8192;             // tokens per slice (counts of a slice fit 16 bits)
-constexpr int kBins = 2048;
-constexpr int kWideThreads = 256;
-constexpr int kPerThread = kSlice / kWideThreads;
 constexpr int kListT = 512;              // keys a head's boundary-bin list holds
 constexpr int kListL = 4096;             // entries a layer's boundary-bin list holds
-constexpr int kSeg = 256;                // keys one slice may contribute to a list
 constexpr int kMaxH = 8;
 constexpr int kMaxSeg = 1024;            // segments of a layer the finishing kernel takes (H * slices per head)
-
-struct SliceTab {                        // first slice of every prompt; a prompt has L*H*S_p slices, head-major
-    int32_t off[NKV_MAX_PROMPTS + 1];
-};
 
 struct LayerPick {
     int32_t bT[kMaxH];                   // boundary bin of the head's protected set (kBins: nothing protected)
@@ -48,50 +39,6 @@ struct LayerPick {
     uint32_t done;                       // budgets already final (R == 0)
     uint32_t pad;
 };
-
-__device__ __forceinline__ int score_bin(float v)
-{
-    const float x = v * 2046.0f;
-    return x >= 2046.0f ? (v > 1.0f ? 2047 : 2046) : (x > 0.f ? (int)x : 0);
-}
-
-// slice id -> prompt, (layer*H + head), slice within the unit
-__device__ __forceinline__ void locate(const SliceTab &st, const PromptTab &tab, int id, int &p, int &lh, int &s,
-                                       int &S)
-{
-    p = 0;
-    while (p + 1 < tab.n && id >= st.off[p + 1]) ++p;
-    const int N = tab.tok_off[p + 1] - tab.tok_off[p];
-    S = (N + kSlice - 1) / kSlice;
-    const int local = id - st.off[p];
-    lh = local / S;
-    s = local - lh * S;
-}
-
-__global__ __launch_bounds__(kWideThreads) void slice_hist_kernel(const float *__restrict__ scores, PromptTab tab,
-                                                                  SliceTab st, uint16_t *__restrict__ part)
-{
-    __shared__ uint32_t hist[kBins];
-    int p, lh, s, S;
-    locate(st, tab, blockIdx.x, p, lh, s, S);
-    const int N = tab.tok_off[p + 1] - tab.tok_off[p];
-    const float *sc = scores + (int64_t)lh * tab.T + tab.tok_off[p];
-    const int tid = threadIdx.x;
-    for (int j = tid; j < kBins; j += kWideThreads) hist[j] = 0u;
-    float v[kPerThread];
-#pragma unroll
-    for (int j = 0; j < kPerThread; ++j) v[j] = sc[min(s * kSlice + j * kWideThreads + tid, N - 1)];
-    __syncthreads();
-#pragma unroll
-    for (int j = 0; j < kPerThread; ++j)
-        if (s * kSlice + j * kWideThreads + tid < N) atomicAdd(&hist[score_bin(v[j])], 1u);
-    __syncthreads();
-    // 8 bins per thread, one 16-byte store
-    const uint32_t *h8 = hist + tid * 8;
-    const uint4 out = make_uint4(h8[0] | (h8[1] << 16), h8[2] | (h8[3] << 16), h8[4] | (h8[5] << 16),
-                                 h8[6] | (h8[7] << 16));
-    reinterpret_cast<uint4 *>(part + (int64_t)blockIdx.x * kBins)[tid] = out;
-}
 
 // Finds the bin holding rank `want` (1-based) from the top of a kBins-bin histogram of which this thread
 // holds bins 2 tid (c0) and 2 tid + 1 (c1); 1024 threads.  out[0] = bin, out[1] = rank inside the bin.
@@ -396,20 +343,6 @@ __global__ __launch_bounds__(1024) void layer_finish_kernel(int L, int H, Prompt
 struct WideWs {
     size_t part, picks, segT, nSegT, segL, nSegL, failed, total;
 };
-
-size_t align256(size_t x) { return (x + 255) / 256 * 256; }
-
-int fill_slices(int L, int H, const PromptTab &tab, SliceTab *st)
-{
-    int n = 0;
-    for (int p = 0; p < tab.n; ++p) {
-        st->off[p] = n;
-        const int N = tab.tok_off[p + 1] - tab.tok_off[p];
-        n += L * H * ((N + kSlice - 1) / kSlice);
-    }
-    st->off[tab.n] = n;
-    return n;
-}
 
 WideWs wide_ws(int L, int H, const PromptTab &tab)
 {

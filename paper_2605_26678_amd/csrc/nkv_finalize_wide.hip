@@ -17,21 +17,12 @@
 //                                        means, min, 1/range, gap
 // A list that overflows (hundreds of values of one slice in one bin) marks the (unit, scale) and the per-head
 // kernel, launched behind and idle otherwise, computes it.
-#include "nkv_wavesel.h"
+#include "nkv_slices.h"
 
 namespace nkv {
 namespace {
 
-constexpr int kSlice = 8192;             // tokens per slice (counts of a slice fit 16 bits)
-constexpr int kBins = 2048;
-constexpr int kWideThreads = 256;
-constexpr int kPerThread = kSlice / kWideThreads;
-constexpr int kSeg = 256;                // keys one slice may contribute to a list
 constexpr int kList = 1024;              // keys the finishing wavefront takes per list
-
-struct SliceTab {                        // first slice of every prompt; a prompt has L*H*S_p slices, head-major
-    int32_t off[NKV_MAX_PROMPTS + 1];
-};
 
 struct StatPick {
     int32_t bTop, bBot;                  // boundary bins
@@ -43,24 +34,6 @@ struct SlicePart {                       // what one slice contributes besides i
     uint32_t nTop, nBot;                 // entries in the two lists
     double sTop, sBot;                   // sums above the upper / below the lower boundary bin
 };
-
-__device__ __forceinline__ int anomaly_bin(float a)
-{
-    const float x = (a + 1.0f) * 1023.5f;
-    return x >= 2047.0f ? 2047 : (x > 0.f ? (int)x : 0);
-}
-
-__device__ __forceinline__ void locate(const SliceTab &st, const PromptTab &tab, int id, int &p, int &lh, int &s,
-                                       int &S)
-{
-    p = 0;
-    while (p + 1 < tab.n && id >= st.off[p + 1]) ++p;
-    const int N = tab.tok_off[p + 1] - tab.tok_off[p];
-    S = (N + kSlice - 1) / kSlice;
-    const int local = id - st.off[p];
-    lh = local / S;
-    s = local - lh * S;
-}
 
 // grid (slices, 3)
 __global__ __launch_bounds__(kWideThreads) void stats_hist_kernel(const float *__restrict__ a_raw, int64_t rows,
@@ -98,10 +71,7 @@ __global__ __launch_bounds__(kWideThreads) void stats_hist_kernel(const float *_
         sp[job_slice].lo = lo;
         sp[job_slice].hi = hi;
     }
-    const uint32_t *h8 = hist + tid * 8;
-    const uint4 out = make_uint4(h8[0] | (h8[1] << 16), h8[2] | (h8[3] << 16), h8[4] | (h8[5] << 16),
-                                 h8[6] | (h8[7] << 16));
-    reinterpret_cast<uint4 *>(part + job_slice * kBins)[tid] = out;
+    store_hist16(hist, part + job_slice * kBins);
 }
 
 // grid (units, 3); 256 threads, 8 bins each
@@ -271,17 +241,23 @@ __global__ __launch_bounds__(64) void stats_finish_kernel(int L, int H, PromptTa
         return;
     }
     __builtin_amdgcn_wave_barrier();
+    // The lists' order depends on the timing of the collecting workgroups, so their entries are added up in
+    // fixed point (2^-40 units, exact for fp32 values of magnitude <= 1 down to that resolution): the sum does
+    // not depend on the order, and the statistics are reproducible bit for bit.
+    constexpr double kFix = 1099511627776.0;                         // 2^40
     // upper boundary bin: the needTop largest of its entries belong to the m largest
     uint32_t gt, eq;
     const uint32_t Tt = wave_select(keys[0], (int)nT, pk.needTop, hist, gt, eq);
-    float part = 0.f;
-    for (uint32_t i = lane; i < nT; i += 64) part += keys[0][i] > Tt ? key_value(keys[0][i]) : 0.f;
-    double top = sTop + wave_sum((double)part) + (double)(pk.needTop - gt) * (double)key_value(Tt);
+    long long part = 0;
+    for (uint32_t i = lane; i < nT; i += 64)
+        part += keys[0][i] > Tt ? __double2ll_rn((double)key_value(keys[0][i]) * kFix) : 0ll;
+    double top = sTop + (double)wave_sum(part) / kFix + (double)(pk.needTop - gt) * (double)key_value(Tt);
     // lower boundary bin, on inverted keys
     const uint32_t Tb = wave_select(keys[1], (int)nB, pk.needBot, hist, gt, eq);
-    part = 0.f;
-    for (uint32_t i = lane; i < nB; i += 64) part += keys[1][i] > Tb ? key_value(~keys[1][i]) : 0.f;
-    double bot = sBot + wave_sum((double)part) + (double)(pk.needBot - gt) * (double)key_value(~Tb);
+    part = 0;
+    for (uint32_t i = lane; i < nB; i += 64)
+        part += keys[1][i] > Tb ? __double2ll_rn((double)key_value(~keys[1][i]) * kFix) : 0ll;
+    double bot = sBot + (double)wave_sum(part) / kFix + (double)(pk.needBot - gt) * (double)key_value(~Tb);
     if (lane == 0) {
         const float range = hi - lo;
         const float inv = range < kFlat ? 0.f : 1.0f / range;
@@ -295,20 +271,6 @@ __global__ __launch_bounds__(64) void stats_finish_kernel(int L, int H, PromptTa
 struct WideWs {
     size_t part, sp, picks, segTop, segBot, failed, total;
 };
-
-size_t align256(size_t x) { return (x + 255) / 256 * 256; }
-
-int fill_slices(int L, int H, const PromptTab &tab, SliceTab *st)
-{
-    int n = 0;
-    for (int p = 0; p < tab.n; ++p) {
-        st->off[p] = n;
-        const int N = tab.tok_off[p + 1] - tab.tok_off[p];
-        n += L * H * ((N + kSlice - 1) / kSlice);
-    }
-    st->off[tab.n] = n;
-    return n;
-}
 
 WideWs wide_ws(int L, int H, const PromptTab &tab)
 {

@@ -114,8 +114,13 @@ hipError_t launch_budget_wide(const float *scores, int L, int H, const PromptTab
                               const uint32_t **failed_flags, hipStream_t st);
 
 // ---- selection, ordered compaction, gather ----
+// wide_ws: scratch of select_wide_ws_bytes() for the slice-wise selection (NULL: per-unit kernels only)
+size_t select_wide_ws_bytes(int L, int H, const PromptTab &tab);
+hipError_t launch_select_wide(const float *scores, const int32_t *k_per_head, int L, int H, const PromptTab &tab,
+                              float near_tol, const int64_t *head_off, int64_t row_capacity, int32_t *kept_idx,
+                              int64_t *near_count, void *ws, const uint32_t **failed_flags, hipStream_t st);
 hipError_t launch_select_compact(const void *keys, const void *values, const RowMap &km, const RowMap &vm,
-                                 const float *scores,
+                                 void *wide_ws, const float *scores,
                                  const int32_t *k_per_head, int L, int H, int d, int dv, int esize,
                                  const PromptTab &tab, float near_tol, void *packed_k, void *packed_v,
                                  int32_t *kept_idx, int64_t *head_off, int64_t row_capacity,

@@ -1,0 +1,360 @@
+// Top-B_h selection with ordered compaction (paper Section 2.5) spread over the whole chip: same kept_idx as
+// select_fast_kernel / select_kernel of nkv_select.hip, but a head's scores are cut into slices of 8192 tokens
+// and every step that touches them runs on one small workgroup per slice (see nkv_slices.h).
+//   slice_hist_kernel   (per slice)  2048-bin value histogram of the slice
+//   sel_pick_kernel     (per unit)   the bin that holds the B_h-th best score; per slice how many scores lie
+//                                    in bins above it
+//   sel_collect_kernel  (per slice)  the keys of that bin -> the slice's segment
+//   sel_finish_kernel   (per unit)   one wavefront: exact threshold T inside the bin, how many of the scores
+//                                    tied at T are kept, and per slice how many kept / tied scores precede it
+//   sel_compact_kernel  (per slice)  ballots over 64 consecutive tokens + a scan over the slice's groups give
+//                                    every kept token its output row; optional count of near-threshold scores
+// A segment that overflows marks the unit and select_kernel, launched behind and idle otherwise, redoes it.
+#include "nkv_slices.h"
+
+namespace nkv {
+namespace {
+
+constexpr int kList = 2048;              // keys the finishing wavefront takes
+
+struct SelPick {
+    int32_t bT;                          // boundary bin; -1: everything is kept; kBins: nothing is kept
+    uint32_t needT;                      // how many entries of the boundary bin are kept
+};
+
+struct SelUnit {
+    uint32_t T, rem;                     // threshold key, how many of the scores tied at T are kept
+    uint32_t mode;                       // 0: threshold; 1: keep all; 2: keep none; 3: failed
+    uint32_t pad;
+};
+
+struct SelSlice {
+    uint32_t above;                      // scores of the slice in bins above the boundary bin
+    uint32_t n;                          // keys in the slice's segment
+    uint32_t gt_before, eq_before;       // kept-for-sure / tied scores of the unit in the slices before this one
+};
+
+// grid: units; 256 threads, 8 bins each
+__global__ __launch_bounds__(kWideThreads) void sel_pick_kernel(const int32_t *__restrict__ k_per_head, int L, int H,
+                                                                PromptTab tab, SliceTab st,
+                                                                const uint16_t *__restrict__ part,
+                                                                SelPick *__restrict__ picks,
+                                                                SelSlice *__restrict__ ss,
+                                                                uint32_t *__restrict__ failed)
+{
+    __shared__ uint32_t wtot[kWideThreads / 64];
+    __shared__ int32_t s_bT;
+    __shared__ uint32_t s_need;
+    const int u = blockIdx.x;
+    const int lh = u % (L * H), p = u / (L * H);
+    const int N = tab.tok_off[p + 1] - tab.tok_off[p];
+    const int S = (N + kSlice - 1) / kSlice;
+    const int B = min(max(k_per_head[u], 0), N);
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int64_t slice0 = (int64_t)st.off[p] + (int64_t)lh * S;
+    if (tid == 0) failed[u] = 0u;
+    if (B == 0 || B == N) {                                          // no threshold to find
+        if (tid == 0) picks[u] = SelPick{B == 0 ? kBins : -1, 0u};
+        for (int s = tid; s < S; s += kWideThreads) ss[slice0 + s].above = B == 0 ? 0u : (uint32_t)min(kSlice, N - s * kSlice);
+        return;
+    }
+    const uint4 *rows = reinterpret_cast<const uint4 *>(part + slice0 * kBins);
+    uint32_t c[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) c[i] = 0u;
+    for (int s0 = 0; s0 < S; s0 += 4) {
+        uint4 r[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) r[i] = rows[(int64_t)min(s0 + i, S - 1) * (kBins / 8) + tid];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            if (s0 + i < S) {
+                c[0] += r[i].x & 0xffffu; c[1] += r[i].x >> 16; c[2] += r[i].y & 0xffffu; c[3] += r[i].y >> 16;
+                c[4] += r[i].z & 0xffffu; c[5] += r[i].z >> 16; c[6] += r[i].w & 0xffffu; c[7] += r[i].w >> 16;
+            }
+        }
+    }
+    uint32_t group = 0u;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) group += c[i];
+    uint32_t incl = group;                                           // inclusive sum from the top bin downwards
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const uint32_t t = __shfl_down(incl, o, 64);
+        if (lane + o < 64) incl += t;
+    }
+    if (lane == 0) wtot[w] = incl;
+    __syncthreads();
+    for (int ww = w + 1; ww < kWideThreads / 64; ++ww) incl += wtot[ww];
+    const uint32_t want = (uint32_t)B;
+    uint32_t cum = incl - group;                                     // scores in bins above this thread's eight
+    if (cum < want && want <= incl) {
+#pragma unroll
+        for (int i = 7; i >= 0; --i) {
+            if (cum < want && want <= cum + c[i]) { s_bT = tid * 8 + i; s_need = want - cum; }
+            cum += c[i];
+        }
+    }
+    __syncthreads();
+    const int bT = s_bT;
+    if (tid == 0) picks[u] = SelPick{bT, s_need};
+    // per slice: scores in bins above bT (wave w takes the slices w, w + 4, ...; lane = 32 bins)
+    for (int s = w; s < S; s += kWideThreads / 64) {
+        const uint16_t *row = part + (slice0 + s) * kBins;
+        uint32_t a = 0u;
+        for (int b = lane; b < kBins; b += 64) a += b > bT ? (uint32_t)row[b] : 0u;
+        a = wave_sum(a);
+        if (lane == 0) ss[slice0 + s].above = a;
+    }
+}
+
+// grid: slices
+__global__ __launch_bounds__(kWideThreads) void sel_collect_kernel(const float *__restrict__ scores, int L, int H,
+                                                                   PromptTab tab, SliceTab st,
+                                                                   const SelPick *__restrict__ picks,
+                                                                   uint32_t *__restrict__ seg,
+                                                                   SelSlice *__restrict__ ss,
+                                                                   uint32_t *__restrict__ failed)
+{
+    __shared__ uint32_t n_hit;
+    int p, lh, s, S;
+    locate(st, tab, blockIdx.x, p, lh, s, S);
+    const int u = p * L * H + lh;
+    const int N = tab.tok_off[p + 1] - tab.tok_off[p];
+    const float *sc = scores + (int64_t)lh * tab.T + tab.tok_off[p];
+    const int tid = threadIdx.x;
+    float v[kPerThread];
+#pragma unroll
+    for (int j = 0; j < kPerThread; ++j) v[j] = sc[min(s * kSlice + j * kWideThreads + tid, N - 1)];
+    const int bT = picks[u].bT;
+    if (tid == 0) n_hit = 0u;
+    __syncthreads();
+    uint32_t *out = seg + (int64_t)blockIdx.x * kSeg;
+    if (bT >= 0 && bT < kBins) {
+#pragma unroll
+        for (int j = 0; j < kPerThread; ++j) {
+            if (s * kSlice + j * kWideThreads + tid < N && score_bin(v[j]) == bT) {
+                const uint32_t at = atomicAdd(&n_hit, 1u);
+                if (at < (uint32_t)kSeg) out[at] = ord_key(v[j]);
+            }
+        }
+    }
+    __syncthreads();
+    if (tid == 0) {
+        ss[blockIdx.x].n = n_hit;
+        if (n_hit > (uint32_t)kSeg) failed[u] = 1u;
+    }
+}
+
+// grid: units; one wavefront
+__global__ __launch_bounds__(64) void sel_finish_kernel(int L, int H, PromptTab tab, SliceTab st,
+                                                        const SelPick *__restrict__ picks,
+                                                        const uint32_t *__restrict__ seg, SelSlice *__restrict__ ss,
+                                                        uint32_t *__restrict__ failed, SelUnit *__restrict__ sel)
+{
+    __shared__ uint32_t keys[kList];
+    __shared__ uint32_t hist[256];
+    const int u = blockIdx.x, lane = threadIdx.x;
+    const int lh = u % (L * H), p = u / (L * H);
+    const int N = tab.tok_off[p + 1] - tab.tok_off[p];
+    const int S = (N + kSlice - 1) / kSlice;
+    const int64_t slice0 = (int64_t)st.off[p] + (int64_t)lh * S;
+    const SelPick pk = picks[u];
+    if (pk.bT < 0 || pk.bT >= kBins) {                               // keep all / keep none
+        uint32_t run = 0u;
+        for (int s = 0; s < S; ++s) {                                // (a few slices; every lane walks them)
+            const uint32_t a = ss[slice0 + s].above;
+            if (lane == 0) { ss[slice0 + s].gt_before = run; ss[slice0 + s].eq_before = 0u; }
+            run += a;
+        }
+        if (lane == 0) sel[u] = SelUnit{0u, 0u, pk.bT < 0 ? 1u : 2u, 0u};
+        return;
+    }
+    bool bad = failed[u] != 0u;
+    uint32_t n = 0u;
+    for (int s = 0; s < S && !bad; ++s) {
+        const uint32_t c = ss[slice0 + s].n;
+        if (c > (uint32_t)kSeg || n + c > (uint32_t)kList) { bad = true; break; }
+        for (uint32_t i = lane; i < c; i += 64) keys[n + i] = seg[(slice0 + s) * kSeg + i];
+        n += c;
+    }
+    if (bad) {
+        if (lane == 0) { failed[u] = 1u; sel[u] = SelUnit{0u, 0u, 3u, 0u}; }
+        return;
+    }
+    __builtin_amdgcn_wave_barrier();
+    uint32_t gt, eq;
+    const uint32_t T = wave_select(keys, (int)n, pk.needT, hist, gt, eq);
+    if (lane == 0) sel[u] = SelUnit{T, pk.needT - gt, 0u, 0u};
+    // per slice: kept-for-sure and tied scores before it
+    uint32_t run_gt = 0u, run_eq = 0u, off = 0u;
+    for (int s = 0; s < S; ++s) {
+        const uint32_t c = ss[slice0 + s].n, above = ss[slice0 + s].above;
+        uint32_t g = 0u, e = 0u;
+        for (uint32_t i = lane; i < c; i += 64) {
+            const uint32_t k = keys[off + i];
+            g += k > T ? 1u : 0u;
+            e += k == T ? 1u : 0u;
+        }
+        g = wave_sum(g);
+        e = wave_sum(e);
+        if (lane == 0) { ss[slice0 + s].gt_before = run_gt; ss[slice0 + s].eq_before = run_eq; }
+        run_gt += above + g;
+        run_eq += e;
+        off += c;
+    }
+}
+
+// grid: slices
+__global__ __launch_bounds__(kWideThreads) void sel_compact_kernel(const float *__restrict__ scores, int L, int H,
+                                                                   PromptTab tab, SliceTab st,
+                                                                   const SelUnit *__restrict__ sel,
+                                                                   const SelSlice *__restrict__ ss,
+                                                                   const int64_t *__restrict__ head_off,
+                                                                   int64_t row_capacity, float near_tol,
+                                                                   int32_t *__restrict__ kept_idx,
+                                                                   int64_t *__restrict__ near_count)
+{
+    constexpr int kGroups = kPerThread * (kWideThreads / 64);        // 64-token groups of a slice, in token order
+    __shared__ uint32_t cnt_gt[kGroups], cnt_eq[kGroups];
+    __shared__ unsigned long long near_acc[kWideThreads / 64];
+    int p, lh, s, S;
+    locate(st, tab, blockIdx.x, p, lh, s, S);
+    const int u = p * L * H + lh;
+    const int N = tab.tok_off[p + 1] - tab.tok_off[p];
+    const float *sc = scores + (int64_t)lh * tab.T + tab.tok_off[p];
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    float v[kPerThread];
+#pragma unroll
+    for (int j = 0; j < kPerThread; ++j) v[j] = sc[min(s * kSlice + j * kWideThreads + tid, N - 1)];
+    const SelUnit su = sel[u];
+    const SelSlice sl = ss[blockIdx.x];
+    if (su.mode >= 2u) return;                                       // nothing kept, or left to the per-unit kernel
+    const bool all = su.mode == 1u;
+    const uint32_t T = su.T, rem = su.rem;
+    // population of every 64-token group (chunk j, wave w) = tokens s*kSlice + j*256 + w*64 ...
+    unsigned long long near = 0;
+    const float tv = key_value(T);
+#pragma unroll
+    for (int j = 0; j < kPerThread; ++j) {
+        const bool in = s * kSlice + j * kWideThreads + tid < N;
+        const uint32_t key = ord_key(v[j]);
+        const bool gt = in && (all || key > T);
+        const bool eq = in && !all && key == T;
+        const unsigned long long mg = __ballot(gt), me = __ballot(eq);
+        if (lane == 0) {
+            cnt_gt[j * (kWideThreads / 64) + w] = (uint32_t)__popcll(mg);
+            cnt_eq[j * (kWideThreads / 64) + w] = (uint32_t)__popcll(me);
+        }
+        if (near_count && in && !all && fabsf(v[j] - tv) <= near_tol) ++near;
+    }
+    __syncthreads();
+    if (w == 0) {                                                    // exclusive scan over the groups: 2 per lane
+        constexpr int PER = kGroups / 64;
+        uint32_t g[PER], e[PER], tg = 0u, te = 0u;
+#pragma unroll
+        for (int q = 0; q < PER; ++q) {
+            g[q] = cnt_gt[lane * PER + q];
+            e[q] = cnt_eq[lane * PER + q];
+            tg += g[q];
+            te += e[q];
+        }
+        uint32_t ig = tg, ie = te;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const uint32_t a = __shfl_up(ig, o, 64), b = __shfl_up(ie, o, 64);
+            if (lane >= o) { ig += a; ie += b; }
+        }
+        uint32_t rg = ig - tg, re = ie - te;
+#pragma unroll
+        for (int q = 0; q < PER; ++q) {
+            cnt_gt[lane * PER + q] = rg;
+            cnt_eq[lane * PER + q] = re;
+            rg += g[q];
+            re += e[q];
+        }
+    }
+    __syncthreads();
+    const int64_t out0 = head_off[u];
+    const unsigned long long below = (1ull << lane) - 1ull;
+#pragma unroll
+    for (int j = 0; j < kPerThread; ++j) {
+        const int i = s * kSlice + j * kWideThreads + tid;
+        const bool in = i < N;
+        const uint32_t key = ord_key(v[j]);
+        const bool gt = in && (all || key > T);
+        const bool eq = in && !all && key == T;
+        const unsigned long long mg = __ballot(gt), me = __ballot(eq);
+        const int grp = j * (kWideThreads / 64) + w;
+        const uint32_t gt_before = sl.gt_before + cnt_gt[grp] + (uint32_t)__popcll(mg & below);
+        const uint32_t eq_before = sl.eq_before + cnt_eq[grp] + (uint32_t)__popcll(me & below);
+        if (gt || (eq && eq_before < rem)) {
+            const int64_t row = out0 + gt_before + min(eq_before, rem);
+            if (row < row_capacity) kept_idx[row] = i;
+        }
+    }
+    if (near_count) {
+        near = wave_sum(near);
+        if (lane == 0) near_acc[w] = near;
+        __syncthreads();
+        if (tid == 0) {
+            unsigned long long t = 0;
+            for (int i = 0; i < kWideThreads / 64; ++i) t += near_acc[i];
+            if (t) atomicAdd((unsigned long long *)near_count, t);
+        }
+    }
+}
+
+struct WideWs {
+    size_t part, picks, ss, seg, sel, failed, total;
+};
+
+WideWs wide_ws(int L, int H, const PromptTab &tab)
+{
+    SliceTab st;
+    const size_t slices = (size_t)fill_slices(L, H, tab, &st), units = (size_t)tab.n * L * H;
+    WideWs w;
+    size_t off = 0;
+    w.part = off;    off += align256(slices * kBins * sizeof(uint16_t));
+    w.picks = off;   off += align256(units * sizeof(SelPick));
+    w.ss = off;      off += align256(slices * sizeof(SelSlice));
+    w.seg = off;     off += align256(slices * kSeg * sizeof(uint32_t));
+    w.sel = off;     off += align256(units * sizeof(SelUnit));
+    w.failed = off;  off += align256(units * sizeof(uint32_t));
+    w.total = off;
+    return w;
+}
+
+}  // namespace
+
+size_t select_wide_ws_bytes(int L, int H, const PromptTab &tab) { return wide_ws(L, H, tab).total; }
+
+// Enqueues the five kernels (head_off must already be on the stream); *failed_flags receives the device address
+// of the per-unit words that are non-zero for units whose kept_idx rows have not been written.  near_count, if
+// given, must have been zeroed on the stream (head_off_kernel does) and excludes the failed units.
+hipError_t launch_select_wide(const float *scores, const int32_t *k_per_head, int L, int H, const PromptTab &tab,
+                              float near_tol, const int64_t *head_off, int64_t row_capacity, int32_t *kept_idx,
+                              int64_t *near_count, void *ws, const uint32_t **failed_flags, hipStream_t st)
+{
+    SliceTab stab;
+    const int slices = fill_slices(L, H, tab, &stab);
+    const WideWs lay = wide_ws(L, H, tab);
+    char *base = (char *)ws;
+    uint16_t *part = (uint16_t *)(base + lay.part);
+    SelPick *picks = (SelPick *)(base + lay.picks);
+    SelSlice *ss = (SelSlice *)(base + lay.ss);
+    uint32_t *seg = (uint32_t *)(base + lay.seg);
+    SelUnit *sel = (SelUnit *)(base + lay.sel);
+    uint32_t *failed = (uint32_t *)(base + lay.failed);
+    const unsigned units = (unsigned)(tab.n * L * H);
+    slice_hist_kernel<<<(unsigned)slices, kWideThreads, 0, st>>>(scores, tab, stab, part);
+    sel_pick_kernel<<<units, kWideThreads, 0, st>>>(k_per_head, L, H, tab, stab, part, picks, ss, failed);
+    sel_collect_kernel<<<(unsigned)slices, kWideThreads, 0, st>>>(scores, L, H, tab, stab, picks, seg, ss, failed);
+    sel_finish_kernel<<<units, 64, 0, st>>>(L, H, tab, stab, picks, seg, ss, failed, sel);
+    sel_compact_kernel<<<(unsigned)slices, kWideThreads, 0, st>>>(scores, L, H, tab, stab, sel, ss, head_off, row_capacity,
+                                                                 near_tol, kept_idx, near_count);
+    *failed_flags = failed;
+    return hipGetLastError();
+}
+
+}  // namespace nkv

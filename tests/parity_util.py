@@ -77,7 +77,7 @@ def run_gpu(w: nkv_inputs.Workload, K: torch.Tensor, V: torch.Tensor, r, params=
             comp.packed_k = torch.empty(rows, shape.d, dtype=K.dtype, device=K.device)
             comp.packed_v = torch.empty(rows, shape.dv, dtype=V.dtype, device=K.device)
     nkv.select_compact(K, V, comp.scores, comp.k_per_head, shape, params, comp.packed_k, comp.packed_v,
-                       comp.kept_idx, comp.head_off, rows, comp.near)
+                       comp.kept_idx, comp.head_off, rows, comp.near, comp.ws if use_ws else None)
     torch.cuda.synchronize()
     return nkv.Compressed(comp.scores, comp.k_per_head, comp.head_off, comp.kept_idx[:rows],
                           comp.packed_k[:rows], comp.packed_v[:rows], comp.near), shape

@@ -163,6 +163,20 @@ def test_statistics_routes_meet_the_score_bar(flags):
     compare_end_to_end(w, Kc, V, 0.75, params=nkv.params_default(flags=flags), label=f"stats const flags={flags}")
 
 
+@pytest.mark.parametrize("flags", [0, nkv.FLAG_SELECT_PER_HEAD])
+def test_selection_routes_meet_the_stage_bar(flags):
+    """Slice-wise and per-unit selection kernels, fed the oracle's scores and budgets: bit-exact kept indices and
+    packed rows either way, for ratios that keep nearly nothing, a quarter, nearly everything, and with one
+    head of constant keys (all of its scores tie; the slice-wise kernels hand it to the per-unit kernel)."""
+    w = nkv_inputs.small_workload("select_routes", 2, 3, 128, [20000, 700, 16384])
+    K, V = _kv(w)
+    for r in (0.999, 0.75, 0.02):
+        compare_stages(w, K, V, r, params=nkv.params_default(flags=flags), label=f"select flags={flags} r={r}")
+    Kc = K.clone()
+    Kc[:, 1] = Kc[:, 1, :1]
+    compare_stages(w, Kc, V, 0.6, params=nkv.params_default(flags=flags), label=f"select const flags={flags}")
+
+
 def test_budget_without_workspace_uses_the_generic_kernel():
     w = nkv_inputs.small_workload("nows", 2, 4, 64, [3000, 200])
     K, V = _kv(w)
