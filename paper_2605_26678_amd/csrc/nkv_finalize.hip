@@ -12,44 +12,12 @@
 // which does not depend on how ties at T are broken.  Min-max is affine and increasing, so the
 // selects run on the raw anomalies and the gap is rescaled afterwards.
 #include "nkv_blocksel.h"
+#include "nkv_learner.h"
 
 namespace nkv {
 namespace {
 
 constexpr int kThreads = 1024;
-
-struct HeadStats {
-    float lo[3], inv_range[3];     // inv_range = 0 when the scale is flat
-    float w[3];
-    float s_lo, s_inv_range, s_mean;
-};
-
-__device__ __forceinline__ void normalised(const float a[3], const HeadStats &hs, float at[3])
-{
-#pragma unroll
-    for (int k = 0; k < 3; ++k) at[k] = (a[k] - hs.lo[k]) * hs.inv_range[k];
-}
-
-// population standard deviation of three numbers
-__device__ __forceinline__ float std3(const float at[3])
-{
-    const float m = (at[0] + at[1] + at[2]) * (1.0f / 3.0f);
-    const float x = at[0] - m, y = at[1] - m, z = at[2] - m;
-    return sqrtf((x * x + y * y + z * z) * (1.0f / 3.0f));
-}
-
-// blend, surprise, gate and route of one token from its three normalised readings (Section 2.4)
-__device__ __forceinline__ float routed_score(const float at[3], const HeadStats &st, const LearnerConsts &lc)
-{
-    const float blend = st.w[0] * at[0] + st.w[1] * at[1] + st.w[2] * at[2];
-    const float win = fmaxf(at[0], fmaxf(at[1], at[2]));
-    float s = std3(at);
-    if (lc.surprise_mode == NKV_SURPRISE_NORMALISED) s = fmaxf((s - st.s_lo) * st.s_inv_range - st.s_mean, 0.f);
-    const float alpha = 1.0f / (1.0f + expf(-lc.kappa * (s - lc.tau)));
-    if (lc.gate_mode == NKV_GATE_ONLY_AVERAGE) return blend;
-    if (lc.gate_mode == NKV_GATE_ONLY_MAX) return win;
-    return (1.0f - alpha) * blend + alpha * win;
-}
 
 __global__ __launch_bounds__(kThreads) void finalize_kernel(const float *__restrict__ a_raw, int L, int H,
                                                             PromptTab tab, LearnerConsts lc,
@@ -282,21 +250,7 @@ __global__ __launch_bounds__(kSelThreads) void route_kernel(const float *__restr
     const float *a0 = a_raw + base, *a1 = a_raw + rows + base, *a2 = a_raw + 2 * rows + base;
     const int tid = threadIdx.x;
 
-    if (tid == 0) {
-        double z[3], zmax = -INFINITY, zsum = 0.0;
-#pragma unroll
-        for (int k = 0; k < 3; ++k) {
-            const float *st = stats + ((int64_t)u * 3 + k) * 4;
-            hs.lo[k] = st[0];
-            hs.inv_range[k] = st[1];
-            z[k] = lc.log_prior[k] + lc.beta * (double)st[2];
-            zmax = fmax(zmax, z[k]);
-        }
-#pragma unroll
-        for (int k = 0; k < 3; ++k) { z[k] = exp(z[k] - zmax); zsum += z[k]; }
-#pragma unroll
-        for (int k = 0; k < 3; ++k) hs.w[k] = (float)(z[k] / zsum);
-    }
+    if (tid == 0) head_weights(stats + (int64_t)u * 12, lc, hs);
     __syncthreads();
     HeadStats st = hs;
     float smin = INFINITY, smax = -INFINITY;
@@ -374,7 +328,12 @@ hipError_t launch_finalize(const float *a_raw, int L, int H, const PromptTab &ta
             else if (ept == 16) scale_stats_kernel<16><<<grid, kSelThreads, 0, st>>>(a_raw, L, H, tab, u0, only_if, stats);
             else scale_stats_kernel<32><<<grid, kSelThreads, 0, st>>>(a_raw, L, H, tab, u0, only_if, stats);
         });
-        route_kernel<<<units, kSelThreads, 0, st>>>(a_raw, L, H, tab, lc, stats, scores);
+        if (only_if != nullptr) {
+            const hipError_t e = launch_route_wide(a_raw, L, H, tab, lc, stats, wide_ws, scores, st);
+            if (e != hipSuccess) return e;
+        } else {
+            route_kernel<<<units, kSelThreads, 0, st>>>(a_raw, L, H, tab, lc, stats, scores);
+        }
     } else {
         finalize_kernel<<<units, kThreads, 0, st>>>(a_raw, L, H, tab, lc, scores);
     }

@@ -10,13 +10,16 @@
 // bin's entries, and only those entries are looked at exactly; likewise from below.
 //   stats_hist_kernel    (slice, scale)  2048-bin histogram as 16-bit counts; min and max of the slice
 //   stats_pick_kernel    (unit, scale)   the bins that hold the m-th largest and the m-th smallest value
-//   stats_collect_kernel (slice, scale)  sums of the values above the upper / below the lower boundary bin;
-//                                        the boundary bins' entries (as order-preserving keys) into two short
-//                                        lists per slice
+//   stats_collect_kernel (slice)         all three scales: sums of the values above the upper / below the lower
+//                                        boundary bin; the boundary bins' entries (as order-preserving keys)
+//                                        into two short lists per slice and scale; and, the ranges being known,
+//                                        min / max / sum of the slice's surprise statistic
 //   stats_finish_kernel  (unit, scale)   one wavefront: exact thresholds inside the boundary bins, the two
 //                                        means, min, 1/range, gap
+//   route_slice_kernel   (slice)         weights, surprise statistics of the head, routed scores, pinning
 // A list that overflows (hundreds of values of one slice in one bin) marks the (unit, scale) and the per-head
 // kernel, launched behind and idle otherwise, computes it.
+#include "nkv_learner.h"
 #include "nkv_slices.h"
 
 namespace nkv {
@@ -27,6 +30,12 @@ constexpr int kList = 1024;              // keys the finishing wavefront takes p
 struct StatPick {
     int32_t bTop, bBot;                  // boundary bins
     uint32_t needTop, needBot;           // how many of their entries belong to the m largest / smallest
+    float lo, inv;                       // min of the (unit, scale) and 1 / range (0 if flat)
+};
+
+struct SliceSurprise {                   // the surprise statistic (Section 2.4) over one slice
+    float lo, hi;
+    double sum;
 };
 
 struct SlicePart {                       // what one slice contributes besides its histogram and lists
@@ -77,6 +86,7 @@ __global__ __launch_bounds__(kWideThreads) void stats_hist_kernel(const float *_
 // grid (units, 3); 256 threads, 8 bins each
 __global__ __launch_bounds__(kWideThreads) void stats_pick_kernel(int L, int H, PromptTab tab, SliceTab st,
                                                                   int n_slices, const uint16_t *__restrict__ part,
+                                                                  const SlicePart *__restrict__ sp,
                                                                   StatPick *__restrict__ picks,
                                                                   uint32_t *__restrict__ failed)
 {
@@ -134,10 +144,26 @@ __global__ __launch_bounds__(kWideThreads) void stats_pick_kernel(int L, int H, 
             cum += c[i];
         }
     }
-    if (tid == 0) failed[(int64_t)u * 3 + k] = 0u;
+    if (w == 0) {                                                    // min, max over the unit's slices
+        float lo = INFINITY, hi = -INFINITY;
+        for (int s = lane; s < S; s += 64) {
+            const SlicePart q = sp[(int64_t)k * n_slices + st.off[p] + (int64_t)lh * S + s];
+            lo = fminf(lo, q.lo);
+            hi = fmaxf(hi, q.hi);
+        }
+        lo = wave_min(lo);
+        hi = wave_max(hi);
+        if (lane == 0) {
+            const float range = hi - lo;
+            out->lo = lo;
+            out->inv = range < kFlat ? 0.f : 1.0f / range;
+            failed[(int64_t)u * 3 + k] = 0u;
+        }
+    }
 }
 
-// grid (slices, 3)
+// grid: slices.  All three scales of the slice in one pass: what stats_finish_kernel needs of each scale, and --
+// the ranges being known -- min, max and sum of the surprise statistic of the slice's tokens.
 __global__ __launch_bounds__(kWideThreads) void stats_collect_kernel(const float *__restrict__ a_raw, int64_t rows,
                                                                      int L, int H, PromptTab tab, SliceTab st,
                                                                      int n_slices,
@@ -145,53 +171,157 @@ __global__ __launch_bounds__(kWideThreads) void stats_collect_kernel(const float
                                                                      uint32_t *__restrict__ segTop,
                                                                      uint32_t *__restrict__ segBot,
                                                                      SlicePart *__restrict__ sp,
+                                                                     SliceSurprise *__restrict__ sur,
                                                                      uint32_t *__restrict__ failed)
 {
-    __shared__ uint32_t nTop, nBot;
-    __shared__ double red[2][kWideThreads / 64];
+    constexpr int HALF = kPerThread / 2;
+    __shared__ uint32_t nTop[3], nBot[3];
+    __shared__ double red[8][kWideThreads / 64];
+    __shared__ float fred[2][kWideThreads / 64];
     int p, lh, s, S;
     locate(st, tab, blockIdx.x, p, lh, s, S);
-    const int k = blockIdx.y;
     const int N = tab.tok_off[p + 1] - tab.tok_off[p];
-    const float *a = a_raw + (int64_t)k * rows + (int64_t)lh * tab.T + tab.tok_off[p];
+    const float *a = a_raw + (int64_t)lh * tab.T + tab.tok_off[p];
     const int tid = threadIdx.x;
-    float v[kPerThread];
+    const int64_t job0 = ((int64_t)p * L * H + lh) * 3;
+    StatPick pk[3];
+    HeadStats hs;
 #pragma unroll
-    for (int j = 0; j < kPerThread; ++j) v[j] = a[min(s * kSlice + j * kWideThreads + tid, N - 1)];
-    const int64_t job = ((int64_t)p * L * H + lh) * 3 + k;
-    const StatPick pk = picks[job];
-    if (tid == 0) { nTop = 0u; nBot = 0u; }
+    for (int k = 0; k < 3; ++k) {
+        pk[k] = picks[job0 + k];
+        hs.lo[k] = pk[k].lo;
+        hs.inv_range[k] = pk[k].inv;
+    }
+    if (tid < 3) { nTop[tid] = 0u; nBot[tid] = 0u; }
     __syncthreads();
-    const int64_t job_slice = (int64_t)k * n_slices + blockIdx.x;
-    uint32_t *outTop = segTop + job_slice * kSeg, *outBot = segBot + job_slice * kSeg;
-    float pt = 0.f, pb = 0.f;                                        // a few dozen terms of magnitude <= 1 each
+    float pt[3] = {0.f, 0.f, 0.f}, pb[3] = {0.f, 0.f, 0.f};          // a few dozen terms of magnitude <= 1 each
+    float smin = INFINITY, smax = -INFINITY;
+    float ssum32 = 0.f;                                              // 32 terms of magnitude <= 0.5
+#pragma unroll 1
+    for (int half = 0; half < 2; ++half) {
+        float v[3][HALF];
 #pragma unroll
-    for (int j = 0; j < kPerThread; ++j) {
-        if (s * kSlice + j * kWideThreads + tid < N) {
-            const int b = anomaly_bin(v[j]);
-            pt += b > pk.bTop ? v[j] : 0.f;
-            pb += b < pk.bBot ? v[j] : 0.f;
-            if (b == pk.bTop) {
-                const uint32_t at = atomicAdd(&nTop, 1u);
-                if (at < (uint32_t)kSeg) outTop[at] = ord_key(v[j]);
-            }
-            if (b == pk.bBot) {
-                const uint32_t at = atomicAdd(&nBot, 1u);
-                if (at < (uint32_t)kSeg) outBot[at] = ~ord_key(v[j]);     // inverted: the smallest value has the largest key
+        for (int k = 0; k < 3; ++k)
+#pragma unroll
+            for (int j = 0; j < HALF; ++j)
+                v[k][j] = a[(int64_t)k * rows + min(s * kSlice + (half * HALF + j) * kWideThreads + tid, N - 1)];
+#pragma unroll
+        for (int j = 0; j < HALF; ++j) {
+            if (s * kSlice + (half * HALF + j) * kWideThreads + tid < N) {
+#pragma unroll
+                for (int k = 0; k < 3; ++k) {
+                    const float x = v[k][j];
+                    const int b = anomaly_bin(x);
+                    pt[k] += b > pk[k].bTop ? x : 0.f;
+                    pb[k] += b < pk[k].bBot ? x : 0.f;
+                    if (b == pk[k].bTop) {
+                        const uint32_t at = atomicAdd(&nTop[k], 1u);
+                        if (at < (uint32_t)kSeg) segTop[((int64_t)k * n_slices + blockIdx.x) * kSeg + at] = ord_key(x);
+                    }
+                    if (b == pk[k].bBot) {                           // inverted: the smallest value has the largest key
+                        const uint32_t at = atomicAdd(&nBot[k], 1u);
+                        if (at < (uint32_t)kSeg) segBot[((int64_t)k * n_slices + blockIdx.x) * kSeg + at] = ~ord_key(x);
+                    }
+                }
+                const float raw[3] = {v[0][j], v[1][j], v[2][j]};
+                float at[3];
+                normalised(raw, hs, at);
+                const float sv = std3(at);
+                smin = fminf(smin, sv);
+                smax = fmaxf(smax, sv);
+                ssum32 += sv;
             }
         }
     }
-    const double st_ = wave_sum((double)pt), sb_ = wave_sum((double)pb);
-    if ((tid & 63) == 0) { red[0][tid >> 6] = st_; red[1][tid >> 6] = sb_; }
+    double ssum = (double)ssum32;
+    const int w = tid >> 6;
+#pragma unroll
+    for (int k = 0; k < 3; ++k) {
+        const double t = wave_sum((double)pt[k]), b = wave_sum((double)pb[k]);
+        if ((tid & 63) == 0) { red[2 * k][w] = t; red[2 * k + 1][w] = b; }
+    }
+    ssum = wave_sum(ssum);
+    smin = wave_min(smin);
+    smax = wave_max(smax);
+    if ((tid & 63) == 0) { red[6][w] = ssum; fred[0][w] = smin; fred[1][w] = smax; }
     __syncthreads();
-    if (tid == 0) {
+    if (tid < 3) {
+        const int k = tid;
         double t = 0.0, b = 0.0;
-        for (int i = 0; i < kWideThreads / 64; ++i) { t += red[0][i]; b += red[1][i]; }
-        sp[job_slice].sTop = t;
-        sp[job_slice].sBot = b;
-        sp[job_slice].nTop = nTop;
-        sp[job_slice].nBot = nBot;
-        if (nTop > (uint32_t)kSeg || nBot > (uint32_t)kSeg) failed[job] = 1u;
+        for (int i = 0; i < kWideThreads / 64; ++i) { t += red[2 * k][i]; b += red[2 * k + 1][i]; }
+        SlicePart *q = sp + (int64_t)k * n_slices + blockIdx.x;
+        q->sTop = t;
+        q->sBot = b;
+        q->nTop = nTop[k];
+        q->nBot = nBot[k];
+        if (nTop[k] > (uint32_t)kSeg || nBot[k] > (uint32_t)kSeg) failed[job0 + k] = 1u;
+    }
+    if (tid == 64) {
+        double t = 0.0;
+        float lo = INFINITY, hi = -INFINITY;
+        for (int i = 0; i < kWideThreads / 64; ++i) { t += red[6][i]; lo = fminf(lo, fred[0][i]); hi = fmaxf(hi, fred[1][i]); }
+        sur[blockIdx.x] = SliceSurprise{lo, hi, t};
+    }
+}
+
+// grid: slices.  Blend, gate, route and pinning of the slice's tokens (Section 2.4); every workgroup forms its
+// head's weights and surprise statistics itself from the few numbers they depend on.
+__global__ __launch_bounds__(kWideThreads) void route_slice_kernel(const float *__restrict__ a_raw, int64_t rows,
+                                                                   int L, int H, PromptTab tab, SliceTab st,
+                                                                   LearnerConsts lc, const float *__restrict__ stats,
+                                                                   const SliceSurprise *__restrict__ sur,
+                                                                   float *__restrict__ scores)
+{
+    __shared__ HeadStats hs;
+    int p, lh, s, S;
+    locate(st, tab, blockIdx.x, p, lh, s, S);
+    const int N = tab.tok_off[p + 1] - tab.tok_off[p];
+    const int64_t base = (int64_t)lh * tab.T + tab.tok_off[p];
+    const float *a = a_raw + base;
+    const int tid = threadIdx.x;
+    constexpr int HALF = kPerThread / 2;
+    float v[3][HALF];
+#pragma unroll
+    for (int k = 0; k < 3; ++k)
+#pragma unroll
+        for (int j = 0; j < HALF; ++j) v[k][j] = a[(int64_t)k * rows + min(s * kSlice + j * kWideThreads + tid, N - 1)];
+    if (tid == 0) {
+        head_weights(stats + ((int64_t)p * L * H + lh) * 12, lc, hs);
+        float smin = INFINITY, smax = -INFINITY;
+        double ssum = 0.0;
+        const SliceSurprise *q = sur + (blockIdx.x - s);
+        for (int i = 0; i < S; ++i) {                                // the head's slices in order
+            smin = fminf(smin, q[i].lo);
+            smax = fmaxf(smax, q[i].hi);
+            ssum += q[i].sum;
+        }
+        const float srange = smax - smin;
+        hs.s_lo = smin;
+        hs.s_inv_range = srange < kFlat ? 0.f : 1.0f / srange;
+        hs.s_mean = (float)((ssum / (double)N - (double)smin) * (double)hs.s_inv_range);
+    }
+    __syncthreads();
+    const HeadStats h = hs;
+    float *out = scores + base;
+#pragma unroll 1
+    for (int half = 0; half < 2; ++half) {
+        if (half == 1) {
+#pragma unroll
+            for (int k = 0; k < 3; ++k)
+#pragma unroll
+                for (int j = 0; j < HALF; ++j)
+                    v[k][j] = a[(int64_t)k * rows + min(s * kSlice + (HALF + j) * kWideThreads + tid, N - 1)];
+        }
+#pragma unroll
+        for (int j = 0; j < HALF; ++j) {
+            const int i = s * kSlice + (half * HALF + j) * kWideThreads + tid;
+            if (i < N) {
+                const float raw[3] = {v[0][j], v[1][j], v[2][j]};
+                float at[3];
+                normalised(raw, h, at);
+                out[i] = i < lc.n_sink ? NKV_PIN : routed_score(at, h, lc);
+            }
+        }
     }
 }
 
@@ -269,7 +399,7 @@ __global__ __launch_bounds__(64) void stats_finish_kernel(int L, int H, PromptTa
 }
 
 struct WideWs {
-    size_t part, sp, picks, segTop, segBot, failed, total;
+    size_t part, sp, sur, picks, segTop, segBot, failed, total;
 };
 
 WideWs wide_ws(int L, int H, const PromptTab &tab)
@@ -280,6 +410,7 @@ WideWs wide_ws(int L, int H, const PromptTab &tab)
     size_t off = 0;
     w.part = off;    off += align256(slices * kBins * sizeof(uint16_t));
     w.sp = off;      off += align256(slices * sizeof(SlicePart));
+    w.sur = off;     off += align256(slices / 3 * sizeof(SliceSurprise));
     w.picks = off;   off += align256(jobs * sizeof(StatPick));
     w.segTop = off;  off += align256(slices * kSeg * sizeof(uint32_t));
     w.segBot = off;  off += align256(slices * kSeg * sizeof(uint32_t));
@@ -309,11 +440,26 @@ hipError_t launch_stats_wide(const float *a_raw, int L, int H, const PromptTab &
     const int64_t rows = (int64_t)L * H * tab.T;
     const unsigned units = (unsigned)(tab.n * L * H);
     stats_hist_kernel<<<dim3((unsigned)slices, 3), kWideThreads, 0, st>>>(a_raw, rows, tab, stab, slices, part, sp);
-    stats_pick_kernel<<<dim3(units, 3), kWideThreads, 0, st>>>(L, H, tab, stab, slices, part, picks, failed);
-    stats_collect_kernel<<<dim3((unsigned)slices, 3), kWideThreads, 0, st>>>(a_raw, rows, L, H, tab, stab, slices, picks,
-                                                                            segTop, segBot, sp, failed);
+    SliceSurprise *sur = (SliceSurprise *)(base + lay.sur);
+    stats_pick_kernel<<<dim3(units, 3), kWideThreads, 0, st>>>(L, H, tab, stab, slices, part, sp, picks, failed);
+    stats_collect_kernel<<<(unsigned)slices, kWideThreads, 0, st>>>(a_raw, rows, L, H, tab, stab, slices, picks, segTop,
+                                                                   segBot, sp, sur, failed);
     stats_finish_kernel<<<dim3(units, 3), 64, 0, st>>>(L, H, tab, stab, slices, picks, segTop, segBot, sp, failed, stats);
     *failed_flags = failed;
+    return hipGetLastError();
+}
+
+// Final scores from the statistics (complete, including what the per-head kernel redid) and the slices'
+// surprise sums left by launch_stats_wide in the same scratch.
+hipError_t launch_route_wide(const float *a_raw, int L, int H, const PromptTab &tab, const LearnerConsts &lc,
+                             const float *stats, void *ws, float *scores, hipStream_t st)
+{
+    SliceTab stab;
+    const int slices = fill_slices(L, H, tab, &stab);
+    const WideWs lay = wide_ws(L, H, tab);
+    const SliceSurprise *sur = (const SliceSurprise *)((char *)ws + lay.sur);
+    route_slice_kernel<<<(unsigned)slices, kWideThreads, 0, st>>>(a_raw, (int64_t)L * H * tab.T, L, H, tab, stab, lc,
+                                                                 stats, sur, scores);
     return hipGetLastError();
 }
 

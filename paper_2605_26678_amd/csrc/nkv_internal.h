@@ -100,6 +100,8 @@ hipError_t launch_finalize(const float *a_raw, int L, int H, const PromptTab &ta
 size_t stats_wide_ws_bytes(int L, int H, const PromptTab &tab);
 hipError_t launch_stats_wide(const float *a_raw, int L, int H, const PromptTab &tab, float *stats, void *ws,
                              const uint32_t **failed_flags, hipStream_t st);
+hipError_t launch_route_wide(const float *a_raw, int L, int H, const PromptTab &tab, const LearnerConsts &lc,
+                             const float *stats, void *ws, float *scores, hipStream_t st);
 
 // ---- head-wise budgets ----
 size_t budget_ws_bytes(int L, int H, const PromptTab &tab);
