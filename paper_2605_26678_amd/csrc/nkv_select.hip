@@ -240,7 +240,7 @@ __global__ __launch_bounds__(kSelThreads, 8) void select_fast_kernel(const float
     }
 }
 
-constexpr int kRowsPerGroup = 32;
+constexpr int kRowsPerGroup = 64;
 
 // 16-byte vectors; krow16 / vrow16 = vectors per K / V row, epv = elements per vector.
 __global__ __launch_bounds__(256) void gather_kernel(const uint4 *__restrict__ keys, const uint4 *__restrict__ values,
