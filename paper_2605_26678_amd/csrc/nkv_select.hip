@@ -272,11 +272,15 @@ __global__ __launch_bounds__(256) void gather_kernel(const uint4 *__restrict__ k
     __syncthreads();
     for (int j = threadIdx.x; j < nr * krow16; j += blockDim.x) {
         const int r = j / krow16, c = j - r * krow16;
-        packed_k[(r0 + r) * krow16 + c] = keys[srck[r] + c];
+        using v4 = unsigned int __attribute__((ext_vector_type(4)));
+        __builtin_nontemporal_store(__builtin_nontemporal_load(reinterpret_cast<const v4 *>(keys) + srck[r] + c),
+                                    reinterpret_cast<v4 *>(packed_k) + (r0 + r) * krow16 + c);
     }
     for (int j = threadIdx.x; j < nr * vrow16; j += blockDim.x) {
         const int r = j / vrow16, c = j - r * vrow16;
-        packed_v[(r0 + r) * vrow16 + c] = values[srcv[r] + c];
+        using v4 = unsigned int __attribute__((ext_vector_type(4)));
+        __builtin_nontemporal_store(__builtin_nontemporal_load(reinterpret_cast<const v4 *>(values) + srcv[r] + c),
+                                    reinterpret_cast<v4 *>(packed_v) + (r0 + r) * vrow16 + c);
     }
 }
 
