@@ -158,10 +158,10 @@ __global__ __launch_bounds__(kDecThreads) void decode_chunk_kernel(const uint16_
             u32x4 kr[U], vr[U];
 #pragma unroll
             for (int i = 0; i < U; ++i)
-                kr[i] = __builtin_amdgcn_raw_buffer_load_b128(krs, (row0 + i * RPW) * kRowBytes + c * 16, 0, 0);
+                kr[i] = __builtin_amdgcn_raw_buffer_load_b128(krs, (row0 + i * RPW) * kRowBytes + c * 16, 0, 2);   // aux 2: non-temporal
 #pragma unroll
             for (int i = 0; i < U; ++i)
-                vr[i] = __builtin_amdgcn_raw_buffer_load_b128(vrs, (row0 + i * RPW) * kRowBytes + c * 16, 0, 0);
+                vr[i] = __builtin_amdgcn_raw_buffer_load_b128(vrs, (row0 + i * RPW) * kRowBytes + c * 16, 0, 2);
             float s[U][G];
 #pragma unroll
             for (int i = 0; i < U; ++i) {
