@@ -81,6 +81,8 @@ SWEEP = [
     ("d_40", 1, 2, 40, [500], "fp32", 24),
     ("long_prompt", 1, 2, 64, [40000], "bf16", 0),        # beyond the register-resident per-head kernels
     ("many_heads", 1, 12, 64, [600, 90], "bf16", 0),      # beyond the 8-head layer budget kernel
+    ("slice_edges", 1, 2, 128, [8193, 16385, 100, 24576], "bf16", 0),   # one token past a slice, exact slices
+    ("slices_d64", 1, 3, 64, [17000], "bf16", 0),
 ]
 
 
