@@ -477,7 +477,7 @@ void scan_kernel(const uint16_t *__restrict__ keys, RowMap km, PromptTab tab, fl
         float own[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e) { W[e] = 0.f; own[e] = 0.f; }
-#pragma unroll 1
+#pragma unroll 2
         for (int gg = 0; gg < SG; ++gg) {
             float cv[8], pv[8];
             load8(&lds_T[w][gg][c * 8], cv);
@@ -559,7 +559,7 @@ void scan_kernel(const uint16_t *__restrict__ keys, RowMap km, PromptTab tab, fl
     }
     __syncthreads();
     if (w == 0) {                                                     // previous chunk of wave 0 = the halo chunk
-#pragma unroll 1
+#pragma unroll 2
         for (int gg = 0; gg < SG; ++gg) {
             if (gg >= g) {
 #pragma unroll
