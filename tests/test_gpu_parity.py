@@ -388,7 +388,7 @@ def test_the_three_calls_can_be_captured_in_a_hip_graph_and_replayed():
     """The calls only enqueue kernels on the given stream (no allocation, no synchronisation, no memset
     nodes), so a serving loop can record them once and replay: every replay, with eager work and
     synchronisations in between, gives the eager result bit for bit."""
-    w = nkv_inputs.small_workload("graph", 2, 4, 128, [3000, 700])
+    w = nkv_inputs.small_workload("graph", 2, 4, 128, [20000, 700])      # slice-wise and per-head kernels
     K, V = _kv(w)
     ref, shape = run_gpu(w, K, V, 0.75)                       # eager, also warms every lazily initialised path
     ref = [t.clone() for t in (ref.scores, ref.k_per_head, ref.head_off, ref.kept_idx, ref.packed_k.view(torch.int16),
