@@ -43,7 +43,7 @@
 //             and the unit sums live in memory that is filled with a NaN bit pattern before the launch, so
 //             a 32-bit word that has been written is recognisable by itself and no flags, counters or
 //             waits for completed stores are needed.  Each workgroup stores its block total (agent scope)
-//             and goes on to its window loop.  Every unit has one more item, queued right behind the
+//             and goes on to its window loop.  Every unit has one more item, queued in front of the
 //             unit's blocks on one die: the workgroup that gets it does nothing but poll the unit's block
 //             totals, add them up in block order and store the unit sum.  After its window loop every
 //             block's workgroup polls the unit sum with its chunk still in registers, then computes a_s.
@@ -300,8 +300,9 @@ __host__ __device__ __forceinline__ int die_blocks(int nblk, int run, int x)
 // the r-th of them
 __device__ __forceinline__ int die_block(int run, int x, int r) { return ((r / run) * kDies + x) * run + r % run; }
 
-// Queue of die x: for lh = 0, 1, ...: the len blocks of its segment, then -- if lh % kDies == x -- one
-// "add the unit up" item per prompt.  First item of lh in that queue:
+// Queue of die x: for lh = 0, 1, ...: if lh % kDies == x one "add the unit up" item per prompt (in front, so
+// that the summing workgroups are already polling when the unit's last block totals arrive), then the len
+// blocks of its segment.  First item of lh in that queue:
 __host__ __device__ __forceinline__ uint32_t queue_start(int lh, int len, int n_prompts, int x)
 {
     return (uint32_t)lh * (uint32_t)len + (uint32_t)n_prompts * ((uint32_t)(lh + kDies - 1 - x) / kDies);
@@ -399,8 +400,9 @@ void scan_kernel(const uint16_t *__restrict__ keys, RowMap km, PromptTab tab, fl
         while (l + 1 < LH && queue_start(l + 1, len, tab.n, x) <= t) ++l;
         const int r = (int)(t - queue_start(l, len, tab.n, x));
         lh = l;
-        blk = r < len ? die_block(run, x, r) : 0;
-        const int sum_of = r < len ? -1 : r - len;                    // prompt whose unit sum is to be formed
+        const int nsum = l % kDies == x ? tab.n : 0;                  // the unit sums of lh come first in the segment
+        blk = r >= nsum ? die_block(run, x, r - nsum) : 0;
+        const int sum_of = r < nsum ? r : -1;                         // prompt whose unit sum is to be formed
         if (sum_of >= 0) {                                            // uniform: this workgroup adds a unit up
             const int p = sum_of;
             static_assert(64 * NW / (D / 4) * D <= NW * SG * D, "partial sums of the unit do not fit the LDS scratch");
