@@ -15,7 +15,7 @@
  * General rules
  *   - Every tensor pointer is a DEVICE pointer owned by the caller; structs,
  *     cu_seqlens and r_per_prompt are HOST memory read during the call only.
- *   - Tensors are dense, row-major, innermost dimension fastest:
+ *   - Tensors are dense (keys / values unless strides are given), row-major, innermost dimension fastest:
  *       keys   [L][H][T][d]     values [L][H][T][dv]     scores [L][H][T]
  *     T = cu_seqlens[n_prompts] is the total token count; prompt p owns the
  *     token rows [cu_seqlens[p], cu_seqlens[p+1]) of every (layer, head).
@@ -25,6 +25,10 @@
  *     stream) and never synchronise or allocate; the library keeps no state.
  *     Scratch memory is the caller's `ws` (device, 256-byte aligned, at least
  *     nkv_workspace_bytes() bytes); its contents are undefined afterwards.
+ *     The calls can be recorded into a HIP graph; nkv_score asks the runtime for a
+ *     kernel's occupancy the first time it runs on a device, so call it once
+ *     outside a capture first.  Keys / values may also be given by strides
+ *     (nkv_shape.key_strides).
  *   - Return value: NKV_OK or a negative nkv_status.  Argument errors are
  *     detected on the host before anything is enqueued.  Inputs must be finite;
  *     behaviour on NaN/Inf keys or scores is undefined (but never out of bounds).
