@@ -27,10 +27,14 @@ struct PromptTab {
 struct RowMap {
     int64_t layer, head, prompt;
     int32_t H, d;
+    __host__ __device__ int64_t unit(int l, int h, int p, const PromptTab &tab) const
+    {
+        return l * layer + h * head + (prompt != 0 ? p * prompt : (int64_t)tab.tok_off[p] * d);
+    }
     __host__ __device__ int64_t unit(int lh, int p, const PromptTab &tab) const
     {
-        const int l = lh / H, h = lh - l * H;
-        return l * layer + h * head + (prompt != 0 ? p * prompt : (int64_t)tab.tok_off[p] * d);
+        const int l = lh / H;
+        return unit(l, lh - l * H, p, tab);
     }
 };
 

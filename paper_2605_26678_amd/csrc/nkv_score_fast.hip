@@ -308,6 +308,24 @@ __host__ __device__ __forceinline__ uint32_t queue_start(int lh, int len, int n_
     return (uint32_t)lh * (uint32_t)len + (uint32_t)n_prompts * ((uint32_t)(lh + kDies - 1 - x) / kDies);
 }
 
+// Constants of one launch of the fused pass, worked out on the host so that a workgroup finds its item without
+// integer divisions (each costs a few hundred cycles in front of the workgroup's first load).
+struct ScanPlan {
+    int32_t nblk, run;
+    int32_t len[kDies];                  // blocks of a (layer, head) that belong to each die
+    float inv_items[kDies];              // kDies / (kDies * len + prompts): items of a die's queue per (layer, head), inverted
+    float inv_run, inv_H;
+};
+
+// a / b for 0 <= a < 2^24, b >= 1, with 1 / b at hand
+__device__ __forceinline__ int div_by(int a, int b, float inv_b)
+{
+    int q = (int)((float)a * inv_b);
+    if (q * b > a) --q;
+    else if ((q + 1) * b <= a) ++q;
+    return q;
+}
+
 // Adds the block totals of one (layer, head, prompt) unit up and stores the unit's sum; called by a whole
 // workgroup of 64 * NW threads.  thread = (slice, 4 dims): slice s adds blocks s, s + NS, s + 2 NS, ... in that
 // order, then the slices are added in order, so the order of the additions depends on the shape only and
@@ -369,7 +387,7 @@ __device__ __forceinline__ bool add_unit_up(const float *bsum_unit, int unblk, f
 // NW wavefronts = chunks per block.  grid: one workgroup per (layer*head, block), 1-D.
 template <int D, int NW, bool FUSED>
 __global__ __launch_bounds__(64 * NW, 3)
-void scan_kernel(const uint16_t *__restrict__ keys, RowMap km, PromptTab tab, float *__restrict__ a_raw,
+void scan_kernel(const uint16_t *__restrict__ keys, RowMap km, PromptTab tab, ScanPlan plan, float *__restrict__ a_raw,
                  float *__restrict__ bsum, float *__restrict__ ssum, uint32_t *__restrict__ sync, int LH,
                  int64_t rows, int poll_limit, uint32_t spin_limit)
 {
@@ -384,24 +402,29 @@ void scan_kernel(const uint16_t *__restrict__ keys, RowMap km, PromptTab tab, fl
     __shared__ u32x4 lds_x[2][NW > 1 ? NW - 1 : 1][4][64];            // rows on their way to the next wave
     __shared__ int s_have;
 
-    const int nblk = tab.blk_off[tab.n];
-    int lh, blk;
+    const int nblk = plan.nblk;
+    int lh, blk, layer, head;
     if (FUSED) {
         // Static assignment: workgroups are started in launch order and go to the dies round-robin, so
         // workgroup i is item i / 8 of the queue of die i % 8 (if it lands on another die the result is the
         // same, only the halo comes from memory).  Everything here is scalar arithmetic on the launch index.
         const int x = (int)(blockIdx.x & (kDies - 1));
         const uint32_t t = blockIdx.x >> 3;
-        const int run = run_length(nblk), len = die_blocks(nblk, run, x);
+        const int run = plan.run, len = plan.len[x];
         if (t >= queue_start(LH, len, tab.n, x)) return;              // the dies' queues differ slightly in length
         // lh of item t: a first guess from the average number of items per lh, then exact
-        int l = min(LH - 1, (int)(t * (uint32_t)kDies / ((uint32_t)kDies * len + tab.n)));
+        int l = min(LH - 1, (int)((float)t * plan.inv_items[x]));
         while (l > 0 && queue_start(l, len, tab.n, x) > t) --l;
         while (l + 1 < LH && queue_start(l + 1, len, tab.n, x) <= t) ++l;
         const int r = (int)(t - queue_start(l, len, tab.n, x));
         lh = l;
         const int nsum = l % kDies == x ? tab.n : 0;                  // the unit sums of lh come first in the segment
-        blk = r >= nsum ? die_block(run, x, r - nsum) : 0;
+        {
+            const int rb = max(r - nsum, 0), cyc = div_by(rb, run, plan.inv_run);          // die_block(run, x, rb)
+            blk = (cyc * kDies + x) * run + (rb - cyc * run);
+        }
+        layer = div_by(lh, km.H, plan.inv_H);
+        head = lh - layer * km.H;
         const int sum_of = r < nsum ? r : -1;                         // prompt whose unit sum is to be formed
         if (sum_of >= 0) {                                            // uniform: this workgroup adds a unit up
             const int p = sum_of;
@@ -416,6 +439,8 @@ void scan_kernel(const uint16_t *__restrict__ keys, RowMap km, PromptTab tab, fl
     } else {
         lh = blockIdx.x / nblk;
         blk = blockIdx.x - lh * nblk;
+        layer = lh / km.H;
+        head = lh - layer * km.H;
     }
     const int p = prompt_of_block(tab, blk);
     const int b = tab.b[p];
@@ -433,7 +458,7 @@ void scan_kernel(const uint16_t *__restrict__ keys, RowMap km, PromptTab tab, fl
     // the prompt that lie outside this block get weight 0 below.
     constexpr int kRowBytes = D * 2;
     const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<uint16_t *>(keys) + km.unit(lh, p, tab), 0, N * kRowBytes, 0x00020000);
+        const_cast<uint16_t *>(keys) + km.unit(layer, head, p, tab), 0, N * kRowBytes, 0x00020000);
     const int lane_off = t0 * kRowBytes + c * 16;
     u32x4 raw[TPT], hraw[HT];
 #pragma unroll
@@ -845,16 +870,20 @@ void launch_scan(const uint16_t *keys, const RowMap &km, int LH, const PromptTab
 {
     const int64_t rows = (int64_t)LH * tab.T;
     unsigned groups = (unsigned)(tab.blk_off[tab.n] * LH);
-    if (FUSED) {                                                      // 8 queues of (nearly) equal length, interleaved
-        const int nblk = tab.blk_off[tab.n], run = run_length(nblk);
-        uint32_t longest = 0;
-        for (int x = 0; x < kDies; ++x) {
-            const uint32_t items = queue_start(LH, die_blocks(nblk, run, x), tab.n, x);
-            longest = items > longest ? items : longest;
-        }
-        groups = longest * kDies;
+    ScanPlan plan;
+    plan.nblk = tab.blk_off[tab.n];
+    plan.run = run_length(plan.nblk);
+    plan.inv_run = 1.0f / (float)plan.run;
+    plan.inv_H = 1.0f / (float)km.H;
+    uint32_t longest = 0;
+    for (int x = 0; x < kDies; ++x) {                                 // 8 queues of (nearly) equal length, interleaved
+        plan.len[x] = die_blocks(plan.nblk, plan.run, x);
+        plan.inv_items[x] = (float)kDies / (float)(kDies * plan.len[x] + tab.n);
+        const uint32_t items = queue_start(LH, plan.len[x], tab.n, x);
+        longest = items > longest ? items : longest;
     }
-    scan_kernel<D, NW, FUSED><<<groups, 64 * NW, 0, st>>>(keys, km, tab, a_raw, bsum, ssum, sync, LH, rows, poll_limit,
+    if (FUSED) groups = longest * kDies;
+    scan_kernel<D, NW, FUSED><<<groups, 64 * NW, 0, st>>>(keys, km, tab, plan, a_raw, bsum, ssum, sync, LH, rows, poll_limit,
                                                           spin_limit);
 }
 
