@@ -98,3 +98,14 @@ def test_input_generator_is_deterministic_and_shaped():
     assert k1.shape == (2, 2, 500, 64) and v1.dtype == torch.bfloat16
     assert torch.equal(k1.view(torch.int16), k2.view(torch.int16)) and torch.equal(v1.view(torch.int16), v2.view(torch.int16))
     assert torch.allclose(k1[0, 0, 0].float().norm(), torch.tensor(10.0), atol=0.1)      # sink-like key
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """This build runs on one GPU: bench.py says so and exits instead of pretending to scale."""
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode != 0 and "ONE GPU" in r.stderr and r.stdout.strip() == ""
