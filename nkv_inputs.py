@@ -89,6 +89,9 @@ WORKLOADS = {
     "llama3b_ragged": Workload(
         "llama3b_ragged", 28, 8, 128, "bf16",
         (4096, 8192, 16384, 32768, 32768, 16384, 8192, 4096), (0.95,), 128, True, True, True, 4),
+    # beyond the paper's longest evaluated prompts (40k cap): the same Qwen3-4B shape at 40k and 128k tokens
+    "qwen4b_40k": Workload("qwen4b_40k", 36, 8, 128, "bf16", (40960,), (0.75,), 128, True, True, True, 5),
+    "qwen4b_128k": Workload("qwen4b_128k", 36, 8, 128, "bf16", (131072,), (0.75,), 128, True, True, True, 6),
 }
 
 

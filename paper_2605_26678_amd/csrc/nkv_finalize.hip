@@ -168,13 +168,11 @@ __global__ __launch_bounds__(kThreads) void finalize_kernel(const float *__restr
 template <int EPT>
 __global__ __launch_bounds__(kSelThreads, EPT <= 16 ? 8 : 4) void scale_stats_kernel(const float *__restrict__ a_raw, int L, int H,
                                                                    PromptTab tab, int u0,
-                                                                   const uint32_t *__restrict__ only_if,
                                                                    float *__restrict__ stats)
 {
     __shared__ SelectScratch sel;
     __shared__ double dscratch[32];
     const int k = blockIdx.x, u = u0 + blockIdx.y;
-    if (only_if && only_if[(int64_t)u * 3 + k] == 0u) return;        // (unit, scale) already done by the slice-wise kernels
     const int h = u % H, l = (u / H) % L, p = u / (H * L);
     const int N = tab.tok_off[p + 1] - tab.tok_off[p];
     const int64_t rows = (int64_t)L * H * tab.T;
@@ -313,27 +311,22 @@ hipError_t launch_finalize(const float *a_raw, int L, int H, const PromptTab &ta
     for (int p = 0; p < tab.n; ++p) nmax = max(nmax, tab.tok_off[p + 1] - tab.tok_off[p]);
     const unsigned units = (unsigned)(tab.n * L * H);
     prof.begin(NKV_KERNEL_FINALIZE, st);
-    if (nmax <= 32 * kSelThreads) {
-        // Slice-wise statistics where a head has more than one slice (four small launches, then the per-head
-        // kernel for what they left); below that the per-head kernel alone is quicker.
-        const uint32_t *only_if = nullptr;
-        if (wide_ws != nullptr && nmax > 8192 && !per_head_route) {
-            const hipError_t e = launch_stats_wide(a_raw, L, H, tab, stats, wide_ws, &only_if, st);
-            if (e != hipSuccess) return e;
-        }
+    if (wide_ws != nullptr && nmax > 8192 && !per_head_route) {
+        // Slice-wise kernels where a head has more than one slice (any length); below that the per-head kernels
+        // are quicker.
+        hipError_t e = launch_stats_wide(a_raw, L, H, tab, stats, wide_ws, st);
+        if (e != hipSuccess) return e;
+        e = launch_route_wide(a_raw, L, H, tab, lc, stats, wide_ws, scores, st);
+        if (e != hipSuccess) return e;
+    } else if (nmax <= 32 * kSelThreads) {
         for_each_length_class(tab, L * H, [&](int ept, int u0, int n) {
             const dim3 grid(3, (unsigned)n);
-            if (ept == 4) scale_stats_kernel<4><<<grid, kSelThreads, 0, st>>>(a_raw, L, H, tab, u0, only_if, stats);
-            else if (ept == 8) scale_stats_kernel<8><<<grid, kSelThreads, 0, st>>>(a_raw, L, H, tab, u0, only_if, stats);
-            else if (ept == 16) scale_stats_kernel<16><<<grid, kSelThreads, 0, st>>>(a_raw, L, H, tab, u0, only_if, stats);
-            else scale_stats_kernel<32><<<grid, kSelThreads, 0, st>>>(a_raw, L, H, tab, u0, only_if, stats);
+            if (ept == 4) scale_stats_kernel<4><<<grid, kSelThreads, 0, st>>>(a_raw, L, H, tab, u0, stats);
+            else if (ept == 8) scale_stats_kernel<8><<<grid, kSelThreads, 0, st>>>(a_raw, L, H, tab, u0, stats);
+            else if (ept == 16) scale_stats_kernel<16><<<grid, kSelThreads, 0, st>>>(a_raw, L, H, tab, u0, stats);
+            else scale_stats_kernel<32><<<grid, kSelThreads, 0, st>>>(a_raw, L, H, tab, u0, stats);
         });
-        if (only_if != nullptr) {
-            const hipError_t e = launch_route_wide(a_raw, L, H, tab, lc, stats, wide_ws, scores, st);
-            if (e != hipSuccess) return e;
-        } else {
-            route_kernel<<<units, kSelThreads, 0, st>>>(a_raw, L, H, tab, lc, stats, scores);
-        }
+        route_kernel<<<units, kSelThreads, 0, st>>>(a_raw, L, H, tab, lc, stats, scores);
     } else {
         finalize_kernel<<<units, kThreads, 0, st>>>(a_raw, L, H, tab, lc, scores);
     }

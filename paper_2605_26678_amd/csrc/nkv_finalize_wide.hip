@@ -326,7 +326,8 @@ __global__ __launch_bounds__(kWideThreads) void route_slice_kernel(const float *
 }
 
 // grid (units, 3); one wavefront.  stats[(u * 3 + k) * 4 + {0, 1, 2}] = min, 1 / range (0 if flat), gap
-__global__ __launch_bounds__(64) void stats_finish_kernel(int L, int H, PromptTab tab, SliceTab st, int n_slices,
+__global__ __launch_bounds__(64) void stats_finish_kernel(const float *__restrict__ a_raw, int64_t rows, int L, int H,
+                                                          PromptTab tab, SliceTab st, int n_slices,
                                                           const StatPick *__restrict__ picks,
                                                           const uint32_t *__restrict__ segTop,
                                                           const uint32_t *__restrict__ segBot,
@@ -337,7 +338,7 @@ __global__ __launch_bounds__(64) void stats_finish_kernel(int L, int H, PromptTa
     __shared__ uint32_t hist[256];
     const int u = blockIdx.x, k = blockIdx.y;
     const int64_t job = (int64_t)u * 3 + k;
-    if (failed[job]) return;
+    bool bad = failed[job] != 0u;
     const int lh = u % (L * H), p = u / (L * H);
     const int N = tab.tok_off[p + 1] - tab.tok_off[p];
     const int S = (N + kSlice - 1) / kSlice;
@@ -349,8 +350,7 @@ __global__ __launch_bounds__(64) void stats_finish_kernel(int L, int H, PromptTa
     uint32_t nT = 0u, nB = 0u;
     double sTop = 0.0, sBot = 0.0;
     float lo = INFINITY, hi = -INFINITY;
-    bool bad = false;
-    for (int s = 0; s < S; ++s) {
+    for (int s = 0; s < S && !bad; ++s) {
         const SlicePart q = sp[slice0 + s];
         if (q.nTop > (uint32_t)kSeg || q.nBot > (uint32_t)kSeg || nT + q.nTop > (uint32_t)kList ||
             nB + q.nBot > (uint32_t)kList) {
@@ -366,15 +366,44 @@ __global__ __launch_bounds__(64) void stats_finish_kernel(int L, int H, PromptTa
         lo = fminf(lo, q.lo);
         hi = fmaxf(hi, q.hi);
     }
-    if (bad) {
-        if (lane == 0) failed[job] = 1u;
-        return;
-    }
-    __builtin_amdgcn_wave_barrier();
     // The lists' order depends on the timing of the collecting workgroups, so their entries are added up in
     // fixed point (2^-40 units, exact for fp32 values of magnitude <= 1 down to that resolution): the sum does
     // not depend on the order, and the statistics are reproducible bit for bit.
     constexpr double kFix = 1099511627776.0;                         // 2^40
+    if (bad) {
+        // More values in one bin than the lists hold (thousands of equal anomalies): this wavefront walks the
+        // head's values itself -- slow, exact, and rare.
+        const float *a = a_raw + (int64_t)k * rows + (int64_t)lh * tab.T + tab.tok_off[p];
+        lo = INFINITY;
+        hi = -INFINITY;
+        for (int i = lane; i < N; i += 64) {
+            lo = fminf(lo, a[i]);
+            hi = fmaxf(hi, a[i]);
+        }
+        lo = wave_min(lo);
+        hi = wave_max(hi);
+        uint32_t gt, eq;
+        const uint32_t Tt = wave_select_fn(N, m, hist, gt, eq, [a](int i) { return ord_key(a[i]); });
+        long long part = 0;
+        for (int i = lane; i < N; i += 64)
+            part += ord_key(a[i]) > Tt ? __double2ll_rn((double)a[i] * kFix) : 0ll;
+        const double top = (double)wave_sum(part) / kFix + (double)(m - gt) * (double)key_value(Tt);
+        const uint32_t Tb = wave_select_fn(N, m, hist, gt, eq, [a](int i) { return ~ord_key(a[i]); });
+        part = 0;
+        for (int i = lane; i < N; i += 64)
+            part += ~ord_key(a[i]) > Tb ? __double2ll_rn((double)a[i] * kFix) : 0ll;
+        const double bot = (double)wave_sum(part) / kFix + (double)(m - gt) * (double)key_value(~Tb);
+        if (lane == 0) {
+            const float range = hi - lo;
+            const float inv = range < kFlat ? 0.f : 1.0f / range;
+            float *o = stats + job * 4;
+            o[0] = lo;
+            o[1] = inv;
+            o[2] = (float)((top - bot) / (double)m * (double)inv);
+        }
+        return;
+    }
+    __builtin_amdgcn_wave_barrier();
     // upper boundary bin: the needTop largest of its entries belong to the m largest
     uint32_t gt, eq;
     const uint32_t Tt = wave_select(keys[0], (int)nT, pk.needTop, hist, gt, eq);
@@ -423,10 +452,9 @@ WideWs wide_ws(int L, int H, const PromptTab &tab)
 
 size_t stats_wide_ws_bytes(int L, int H, const PromptTab &tab) { return wide_ws(L, H, tab).total; }
 
-// Enqueues the four kernels; *failed_flags receives the device address of the per-(unit, scale) words that are
-// non-zero where `stats` has not been written.
+// Enqueues the four kernels that fill `stats`.
 hipError_t launch_stats_wide(const float *a_raw, int L, int H, const PromptTab &tab, float *stats, void *ws,
-                             const uint32_t **failed_flags, hipStream_t st)
+                             hipStream_t st)
 {
     SliceTab stab;
     const int slices = fill_slices(L, H, tab, &stab);
@@ -444,8 +472,8 @@ hipError_t launch_stats_wide(const float *a_raw, int L, int H, const PromptTab &
     stats_pick_kernel<<<dim3(units, 3), kWideThreads, 0, st>>>(L, H, tab, stab, slices, part, sp, picks, failed);
     stats_collect_kernel<<<(unsigned)slices, kWideThreads, 0, st>>>(a_raw, rows, L, H, tab, stab, slices, picks, segTop,
                                                                    segBot, sp, sur, failed);
-    stats_finish_kernel<<<dim3(units, 3), 64, 0, st>>>(L, H, tab, stab, slices, picks, segTop, segBot, sp, failed, stats);
-    *failed_flags = failed;
+    stats_finish_kernel<<<dim3(units, 3), 64, 0, st>>>(a_raw, rows, L, H, tab, stab, slices, picks, segTop, segBot,
+                                                       sp, failed, stats);
     return hipGetLastError();
 }
 

@@ -103,7 +103,7 @@ hipError_t launch_finalize(const float *a_raw, int L, int H, const PromptTab &ta
 // slice-wise statistics (nkv_finalize_wide.hip)
 size_t stats_wide_ws_bytes(int L, int H, const PromptTab &tab);
 hipError_t launch_stats_wide(const float *a_raw, int L, int H, const PromptTab &tab, float *stats, void *ws,
-                             const uint32_t **failed_flags, hipStream_t st);
+                             hipStream_t st);
 hipError_t launch_route_wide(const float *a_raw, int L, int H, const PromptTab &tab, const LearnerConsts &lc,
                              const float *stats, void *ws, float *scores, hipStream_t st);
 
@@ -124,7 +124,7 @@ hipError_t launch_budget_wide(const float *scores, int L, int H, const PromptTab
 size_t select_wide_ws_bytes(int L, int H, const PromptTab &tab);
 hipError_t launch_select_wide(const float *scores, const int32_t *k_per_head, int L, int H, const PromptTab &tab,
                               float near_tol, const int64_t *head_off, int64_t row_capacity, int32_t *kept_idx,
-                              int64_t *near_count, void *ws, const uint32_t **failed_flags, hipStream_t st);
+                              int64_t *near_count, void *ws, hipStream_t st);
 hipError_t launch_select_compact(const void *keys, const void *values, const RowMap &km, const RowMap &vm,
                                  void *wide_ws, const float *scores,
                                  const int32_t *k_per_head, int L, int H, int d, int dv, int esize,

@@ -284,12 +284,14 @@ constexpr int kSyncWords = 32;                   // the list (one word per block
 
 // The blocks of a (layer, head) are dealt to the dies in runs of consecutive blocks, round-robin: runs keep a
 // block's halo on the die of the block before it, dealing them round-robin gives every die the same mix of
-// prompts when a batch holds prompts of different lengths.  A run is 16 blocks, fewer when there are not
-// enough blocks to give every die a run.
+// prompts when a batch holds prompts of different lengths.  A run is at most 16 blocks, and as long as it can
+// be for the blocks to go round the dies a whole number of times (160 blocks: twice round in runs of 10, not
+// once in runs of 16 with two more runs left over for the first two dies).
 __host__ __device__ __forceinline__ int run_length(int nblk)
 {
-    const int r = nblk / kDies;
-    return r < 1 ? 1 : (r > 16 ? 16 : r);
+    const int rounds = (nblk + 16 * kDies - 1) / (16 * kDies);
+    const int r = (nblk + rounds * kDies - 1) / (rounds * kDies);
+    return r < 1 ? 1 : r;
 }
 // number of blocks of one (layer, head) that belong to die x
 __host__ __device__ __forceinline__ int die_blocks(int nblk, int run, int x)
@@ -908,12 +910,14 @@ hipError_t run_nw(const uint16_t *keys, const RowMap &km, int LH, const PromptTa
 {
     int max_unit_blocks = 0;
     for (int p = 0; p < tab.n; ++p) max_unit_blocks = max(max_unit_blocks, tab.blk_off[p + 1] - tab.blk_off[p]);
-    // fused only if the chip can hold two units' worth of workgroups at once (see the header comment)
+    // fused only if the chip can hold a unit's workgroups at once (see the header comment); from half of that
+    // on, workgroups that wait for the unit sum hold up some of those behind them, which still costs less than
+    // a second read of the keys
     // (queue arithmetic is 32-bit: keep the number of items far below 2^32 / 8)
     const int64_t items = (int64_t)LH * (tab.blk_off[tab.n] + tab.n);
     const bool allow_fused = mode != kScanTwoPass, no_unit_sums = mode == kScanRepairAll;
     const bool defer_all = mode == kScanDeferAll || no_unit_sums;
-    const bool fused = allow_fused && items < (1ll << 28) && 2 * max_unit_blocks <= resident_workgroups<D, NW, true>();
+    const bool fused = allow_fused && items < (1ll << 28) && max_unit_blocks <= resident_workgroups<D, NW, true>();
     if (fused) {
         // the counters start at zero, block totals and unit sums as "unwritten"
         const size_t nb = (size_t)LH * tab.blk_off[tab.n] * D / 4, ns = (size_t)LH * tab.n * D / 4;

@@ -71,12 +71,10 @@ __global__ __launch_bounds__(kThreads) void select_kernel(const float *__restric
                                                           PromptTab tab, float near_tol,
                                                           const int64_t *__restrict__ head_off,
                                                           int64_t row_capacity, int32_t *__restrict__ kept_idx,
-                                                          int64_t *__restrict__ near_count,
-                                                          const uint32_t *__restrict__ only_if)
+                                                          int64_t *__restrict__ near_count)
 {
     __shared__ uint32_t hist[256];
     __shared__ uint32_t s_prefix, s_want;
-    if (only_if && only_if[blockIdx.x] == 0u) return;               // unit already done by the slice-wise kernels
     __shared__ unsigned long long scratch[kWaves + 1];
     __shared__ unsigned long long near_acc[16];
 
@@ -318,15 +316,11 @@ hipError_t launch_select_compact(const void *keys, const void *values, const Row
     select_fast_kernel<EPT><<<(unsigned)n, kSelThreads, 0, st>>>(scores, k_per_head, L, H, tab, u0, near_tol, \
                                                                  head_off, row_capacity, kept_idx, near_count)
     // Slice-wise kernels where a head has more than two slices and the caller gave scratch (at two slices the
-    // six launches cost what they save); the per-unit kernel behind them redoes the units they gave up on
-    // (none, normally).
+    // six launches cost what they save).
     if (wide_ws != nullptr && nmax > 16384) {
-        const uint32_t *failed = nullptr;
         const hipError_t e = launch_select_wide(scores, k_per_head, L, H, tab, near_tol, head_off, row_capacity,
-                                                kept_idx, near_count, wide_ws, &failed, st);
+                                                kept_idx, near_count, wide_ws, st);
         if (e != hipSuccess) return e;
-        select_kernel<<<(unsigned)n_units, kThreads, 0, st>>>(scores, k_per_head, L, H, tab, near_tol, head_off,
-                                                              row_capacity, kept_idx, near_count, failed);
     } else if (nmax <= 32 * kSelThreads)
         for_each_length_class(tab, L * H, [&](int ept, int u0, int n) {
             if (ept == 4) NKV_SELECT_FAST(4);
@@ -336,7 +330,7 @@ hipError_t launch_select_compact(const void *keys, const void *values, const Row
         });
     else
         select_kernel<<<(unsigned)n_units, kThreads, 0, st>>>(scores, k_per_head, L, H, tab, near_tol, head_off,
-                                                              row_capacity, kept_idx, near_count, nullptr);
+                                                              row_capacity, kept_idx, near_count);
 #undef NKV_SELECT_FAST
     prof.end(NKV_KERNEL_SELECT, st);
     // no unit keeps more than its prompt length, so the row count is bounded by L*H*T as well

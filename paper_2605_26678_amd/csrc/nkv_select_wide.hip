@@ -9,7 +9,8 @@
 //                                    tied at T are kept, and per slice how many kept / tied scores precede it
 //   sel_compact_kernel  (per slice)  ballots over 64 consecutive tokens + a scan over the slice's groups give
 //                                    every kept token its output row; optional count of near-threshold scores
-// A segment that overflows marks the unit and select_kernel, launched behind and idle otherwise, redoes it.
+// If a segment overflows (thousands of equal scores in one bin), the unit's finishing wavefront walks the head's
+// scores itself.
 #include "nkv_slices.h"
 
 namespace nkv {
@@ -24,7 +25,7 @@ struct SelPick {
 
 struct SelUnit {
     uint32_t T, rem;                     // threshold key, how many of the scores tied at T are kept
-    uint32_t mode;                       // 0: threshold; 1: keep all; 2: keep none; 3: failed
+    uint32_t mode;                       // 0: threshold; 1: keep all; 2: keep none
     uint32_t pad;
 };
 
@@ -147,7 +148,9 @@ __global__ __launch_bounds__(kWideThreads) void sel_collect_kernel(const float *
 }
 
 // grid: units; one wavefront
-__global__ __launch_bounds__(64) void sel_finish_kernel(int L, int H, PromptTab tab, SliceTab st,
+__global__ __launch_bounds__(64) void sel_finish_kernel(const float *__restrict__ scores,
+                                                        const int32_t *__restrict__ k_per_head, int L, int H,
+                                                        PromptTab tab, SliceTab st,
                                                         const SelPick *__restrict__ picks,
                                                         const uint32_t *__restrict__ seg, SelSlice *__restrict__ ss,
                                                         uint32_t *__restrict__ failed, SelUnit *__restrict__ sel)
@@ -179,7 +182,27 @@ __global__ __launch_bounds__(64) void sel_finish_kernel(int L, int H, PromptTab 
         n += c;
     }
     if (bad) {
-        if (lane == 0) { failed[u] = 1u; sel[u] = SelUnit{0u, 0u, 3u, 0u}; }
+        // More scores in one bin than the lists hold (thousands of equal scores): this wavefront walks the
+        // head's scores itself -- slow, exact, and rare.
+        const float *sc = scores + (int64_t)lh * tab.T + tab.tok_off[p];
+        const uint32_t B = (uint32_t)min(max(k_per_head[u], 0), N);
+        uint32_t gt, eq;
+        const uint32_t T = wave_select_fn(N, B, hist, gt, eq, [sc](int i) { return ord_key(sc[i]); });
+        if (lane == 0) sel[u] = SelUnit{T, B - gt, 0u, 0u};
+        uint32_t run_gt = 0u, run_eq = 0u;
+        for (int s = 0; s < S; ++s) {
+            uint32_t g = 0u, e = 0u;
+            for (int i = s * kSlice + lane; i < min((s + 1) * kSlice, N); i += 64) {
+                const uint32_t k = ord_key(sc[i]);
+                g += k > T ? 1u : 0u;
+                e += k == T ? 1u : 0u;
+            }
+            g = wave_sum(g);
+            e = wave_sum(e);
+            if (lane == 0) { ss[slice0 + s].gt_before = run_gt; ss[slice0 + s].eq_before = run_eq; }
+            run_gt += g;
+            run_eq += e;
+        }
         return;
     }
     __builtin_amdgcn_wave_barrier();
@@ -229,7 +252,7 @@ __global__ __launch_bounds__(kWideThreads) void sel_compact_kernel(const float *
     for (int j = 0; j < kPerThread; ++j) v[j] = sc[min(s * kSlice + j * kWideThreads + tid, N - 1)];
     const SelUnit su = sel[u];
     const SelSlice sl = ss[blockIdx.x];
-    if (su.mode >= 2u) return;                                       // nothing kept, or left to the per-unit kernel
+    if (su.mode >= 2u) return;                                       // nothing kept
     const bool all = su.mode == 1u;
     const uint32_t T = su.T, rem = su.rem;
     // population of every 64-token group (chunk j, wave w) = tokens s*kSlice + j*256 + w*64 ...
@@ -329,12 +352,11 @@ WideWs wide_ws(int L, int H, const PromptTab &tab)
 
 size_t select_wide_ws_bytes(int L, int H, const PromptTab &tab) { return wide_ws(L, H, tab).total; }
 
-// Enqueues the five kernels (head_off must already be on the stream); *failed_flags receives the device address
-// of the per-unit words that are non-zero for units whose kept_idx rows have not been written.  near_count, if
-// given, must have been zeroed on the stream (head_off_kernel does) and excludes the failed units.
+// Enqueues the five kernels (head_off must already be on the stream).  near_count, if given, must have been
+// zeroed on the stream (head_off_kernel does).
 hipError_t launch_select_wide(const float *scores, const int32_t *k_per_head, int L, int H, const PromptTab &tab,
                               float near_tol, const int64_t *head_off, int64_t row_capacity, int32_t *kept_idx,
-                              int64_t *near_count, void *ws, const uint32_t **failed_flags, hipStream_t st)
+                              int64_t *near_count, void *ws, hipStream_t st)
 {
     SliceTab stab;
     const int slices = fill_slices(L, H, tab, &stab);
@@ -350,10 +372,9 @@ hipError_t launch_select_wide(const float *scores, const int32_t *k_per_head, in
     slice_hist_kernel<<<(unsigned)slices, kWideThreads, 0, st>>>(scores, tab, stab, part);
     sel_pick_kernel<<<units, kWideThreads, 0, st>>>(k_per_head, L, H, tab, stab, part, picks, ss, failed);
     sel_collect_kernel<<<(unsigned)slices, kWideThreads, 0, st>>>(scores, L, H, tab, stab, picks, seg, ss, failed);
-    sel_finish_kernel<<<units, 64, 0, st>>>(L, H, tab, stab, picks, seg, ss, failed, sel);
+    sel_finish_kernel<<<units, 64, 0, st>>>(scores, k_per_head, L, H, tab, stab, picks, seg, ss, failed, sel);
     sel_compact_kernel<<<(unsigned)slices, kWideThreads, 0, st>>>(scores, L, H, tab, stab, sel, ss, head_off, row_capacity,
                                                                  near_tol, kept_idx, near_count);
-    *failed_flags = failed;
     return hipGetLastError();
 }
 

@@ -5,10 +5,11 @@
 
 namespace nkv {
 
-// `want`-th largest (1-based) of the n keys key[0..n): byte-wise radix select by one wavefront; hist: 256 words
-// of LDS owned by the wave.  Returns the key; gt = how many keys are larger, eq = how many are equal.
-__device__ __forceinline__ uint32_t wave_select(const uint32_t *key, int n, uint32_t want, uint32_t *hist,
-                                                uint32_t &gt, uint32_t &eq)
+// `want`-th largest (1-based) of the n keys key_at(0..n-1): byte-wise radix select by one wavefront; hist: 256
+// words of LDS owned by the wave.  Returns the key; gt = how many keys are larger, eq = how many are equal.
+template <typename F>
+__device__ __forceinline__ uint32_t wave_select_fn(int n, uint32_t want, uint32_t *hist, uint32_t &gt, uint32_t &eq,
+                                                   F key_at)
 {
     const int lane = threadIdx.x & 63;
     uint32_t prefix = 0u;
@@ -17,7 +18,7 @@ __device__ __forceinline__ uint32_t wave_select(const uint32_t *key, int n, uint
         for (int j = lane; j < 256; j += 64) hist[j] = 0u;
         __builtin_amdgcn_wave_barrier();
         for (int i = lane; i < n; i += 64) {
-            const uint32_t k = key[i];
+            const uint32_t k = key_at(i);
             if (pass == 0 || (k >> (shift + 8)) == (prefix >> (shift + 8))) atomicAdd(&hist[(k >> shift) & 255u], 1u);
         }
         __builtin_amdgcn_wave_barrier();
@@ -49,13 +50,20 @@ __device__ __forceinline__ uint32_t wave_select(const uint32_t *key, int n, uint
     }
     uint32_t g = 0u, e = 0u;
     for (int i = lane; i < n; i += 64) {
-        const uint32_t k = key[i];
+        const uint32_t k = key_at(i);
         g += k > prefix ? 1u : 0u;
         e += k == prefix ? 1u : 0u;
     }
     gt = wave_sum(g);
     eq = wave_sum(e);
     return prefix;
+}
+
+// The same over an array (LDS or memory).
+__device__ __forceinline__ uint32_t wave_select(const uint32_t *key, int n, uint32_t want, uint32_t *hist,
+                                                uint32_t &gt, uint32_t &eq)
+{
+    return wave_select_fn(n, want, hist, gt, eq, [key](int i) { return key[i]; });
 }
 
 }  // namespace nkv

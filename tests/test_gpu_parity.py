@@ -83,6 +83,7 @@ SWEEP = [
     ("many_heads", 1, 12, 64, [600, 90], "bf16", 0),      # beyond the 8-head layer budget kernel
     ("slice_edges", 1, 2, 128, [8193, 16385, 100, 24576], "bf16", 0),   # one token past a slice, exact slices
     ("slices_d64", 1, 3, 64, [17000], "bf16", 0),
+    ("nine_slices", 1, 2, 128, [70000, 9000], "bf16", 0), # 274 blocks in the unit: two rounds of the dies' runs
 ]
 
 
@@ -156,7 +157,7 @@ def test_budget_routes_meet_the_stage_bar(flags):
 def test_statistics_routes_meet_the_score_bar(flags):
     """Slice-wise and per-head statistics kernels on a shape both cover (prompts of three slices, of less than
     one, and of exactly two), against the oracle; constant keys make every value of a scale fall into one
-    bin, which the slice-wise kernels hand over to the per-head kernel."""
+    bin, more than the slice-wise kernels' lists hold: their finishing wavefront walks the head itself."""
     w = nkv_inputs.small_workload("stat_routes", 1, 3, 128, [20000, 700, 16384])
     K, V = _kv(w)
     compare_end_to_end(w, K, V, 0.75, params=nkv.params_default(flags=flags), label=f"stats flags={flags}")
@@ -169,7 +170,8 @@ def test_statistics_routes_meet_the_score_bar(flags):
 def test_selection_routes_meet_the_stage_bar(flags):
     """Slice-wise and per-unit selection kernels, fed the oracle's scores and budgets: bit-exact kept indices and
     packed rows either way, for ratios that keep nearly nothing, a quarter, nearly everything, and with one
-    head of constant keys (all of its scores tie; the slice-wise kernels hand it to the per-unit kernel)."""
+    head of constant keys (all of its scores tie: more than the slice-wise kernels' lists hold, so their
+    finishing wavefront walks the head itself)."""
     w = nkv_inputs.small_workload("select_routes", 2, 3, 128, [20000, 700, 16384])
     K, V = _kv(w)
     for r in (0.999, 0.75, 0.02):
