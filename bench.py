@@ -161,7 +161,8 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     K, V = nkv_inputs.make_kv(w, dev)
-    shape = nkv.Shape(w.L, w.H, w.d, w.d_v, nkv.DTYPE_F32 if w.dtype == "fp32" else nkv.DTYPE_BF16, w.cu_seqlens)
+    dtype = {"fp32": nkv.DTYPE_F32, "bf16": nkv.DTYPE_BF16, "fp16": nkv.DTYPE_F16, "fp8": nkv.DTYPE_F8_E4M3}[w.dtype]
+    shape = nkv.Shape(w.L, w.H, w.d, w.d_v, dtype, w.cu_seqlens)
     params = nkv.params_default(flags=(nkv.FLAG_GENERIC_KERNELS if args.generic else 0)
                                 | (nkv.FLAG_TWO_PASS_STABLE if args.two_pass else 0))
     r_list = [r] * shape.n_prompts
@@ -204,7 +205,7 @@ def main():
     tokens = w.T
     value = tokens / (wall / args.steps)
 
-    esize = 4 if w.dtype == "fp32" else 2
+    esize = {"fp32": 4, "bf16": 2, "fp16": 2, "fp8": 1}[w.dtype]
     ab = algorithmic_bytes(w.d, w.d_v, esize, r)
     head_tokens = w.L * w.H * w.T
     dominant = max(("scan", "gather"), key=lambda k: kern_ms[k])

@@ -53,7 +53,14 @@ typedef enum nkv_status {
     NKV_EUNSUPPORTED = -5  /* valid request outside what the kernels cover            */
 } nkv_status;
 
-enum { NKV_DTYPE_F32 = 0, NKV_DTYPE_BF16 = 1 };
+/* Element type of keys and values (and of the packed outputs, whose rows are copies).                  */
+/* F8_E4M3: the 8-bit OCP format with 4 exponent bits (bias 7), 3 mantissa bits, no infinities,         */
+/* S.1111.111 = NaN, largest finite value 448.  The scores are cosines, so a positive scale factor per   */
+/* tensor, per head or per token that a quantised cache carries does not enter and is not asked for     */
+/* (Section 2.1 normalises every key); a per-channel scale would, and is not supported.  Rows of 8-bit   */
+/* elements need d and dv to be multiples of 16.  (The paper's own experiments use bf16 caches; other    */
+/* cache dtypes are its stated future work, Section 5.)                                                  */
+enum { NKV_DTYPE_F32 = 0, NKV_DTYPE_BF16 = 1, NKV_DTYPE_F16 = 2, NKV_DTYPE_F8_E4M3 = 3 };
 enum { NKV_GATE_SURPRISE = 0, NKV_GATE_ONLY_AVERAGE = 1, NKV_GATE_ONLY_MAX = 2 };
 enum { NKV_SURPRISE_NORMALISED = 0, NKV_SURPRISE_RAW = 1 };
 enum {
@@ -222,7 +229,8 @@ int nkv_select_compact(const void *keys, const void *values, const float *scores
  * lse = -inf.  shape->key_strides / value_strides are not used (the packed cache is dense).
  * fp32 arithmetic: exact bf16 products accumulated in fp32, base-2 exponentials of the hardware.
  * Scratch: nkv_decode_workspace_bytes (0 for shapes outside bf16, d = dv in {64,128}, G <= 8,
- * which take a slower kernel).  Asynchronous on hip_stream.
+ * which take a slower kernel).  NKV_DTYPE_F8_E4M3 caches are refused (NKV_EUNSUPPORTED): attention
+ * over them needs the cache's scale factors, which this library never sees.  Asynchronous on hip_stream.
  */
 int nkv_decode_workspace_bytes(const nkv_shape *shape, int32_t n_q_heads, int64_t rows, size_t *bytes);
 int nkv_decode_attention(const void *q, const void *packed_k, const void *packed_v, const int64_t *head_off,

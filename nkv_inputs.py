@@ -47,7 +47,7 @@ class Workload:
     L: int
     H: int
     d: int
-    dtype: str                      # "fp32" | "bf16"
+    dtype: str                      # "fp32" | "bf16" | "fp16" | "fp8" (8-bit E4M3, unscaled: the keys fit its range)
     prompt_lens: Tuple[int, ...]
     ratios: Tuple[float, ...]       # eviction ratios r the workload is run at
     n_out: int
@@ -73,7 +73,8 @@ class Workload:
         return cu
 
     def torch_dtype(self) -> torch.dtype:
-        return torch.float32 if self.dtype == "fp32" else torch.bfloat16
+        return {"fp32": torch.float32, "bf16": torch.bfloat16, "fp16": torch.float16,
+                "fp8": torch.float8_e4m3fn}[self.dtype]
 
 
 WORKLOADS = {
@@ -92,6 +93,8 @@ WORKLOADS = {
     # beyond the paper's longest evaluated prompts (40k cap): the same Qwen3-4B shape at 40k and 128k tokens
     "qwen4b_40k": Workload("qwen4b_40k", 36, 8, 128, "bf16", (40960,), (0.75,), 128, True, True, True, 5),
     "qwen4b_128k": Workload("qwen4b_128k", 36, 8, 128, "bf16", (131072,), (0.75,), 128, True, True, True, 6),
+    # the headline shape with an 8-bit (E4M3) cache
+    "qwen4b_32k_fp8": Workload("qwen4b_32k_fp8", 36, 8, 128, "fp8", (32768,), (0.75,), 128, True, True, True, 3),
 }
 
 

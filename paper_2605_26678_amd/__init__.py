@@ -16,7 +16,7 @@ from . import build as _build
 
 NKV_OK = 0
 NKV_EINVAL, NKV_ESHAPE, NKV_EWORKSPACE, NKV_EHIP, NKV_EUNSUPPORTED = -1, -2, -3, -4, -5
-DTYPE_F32, DTYPE_BF16 = 0, 1
+DTYPE_F32, DTYPE_BF16, DTYPE_F16, DTYPE_F8_E4M3 = 0, 1, 2, 3
 FLAG_GENERIC_KERNELS = 1
 FLAG_TWO_PASS_STABLE = 2
 FLAG_DEFER_STABLE = 4
@@ -328,7 +328,8 @@ class Compressor:
         self.r = [float(x) for x in r_per_prompt]
         self.rows = packed_rows(shape, self.r)
         dev = torch.device(device)
-        kv_dtype = kv_dtype or (torch.float32 if shape.dtype == DTYPE_F32 else torch.bfloat16)
+        kv_dtype = kv_dtype or {DTYPE_F32: torch.float32, DTYPE_BF16: torch.bfloat16, DTYPE_F16: torch.float16,
+                                DTYPE_F8_E4M3: torch.float8_e4m3fn}[shape.dtype]
         self.ws = torch.empty(max(workspace_bytes(shape, self.params), 256), dtype=torch.uint8, device=dev)
         self.scores = torch.empty(shape.L, shape.H, shape.T, dtype=torch.float32, device=dev)
         self.k_per_head = torch.empty(shape.n_prompts, shape.L, shape.H, dtype=torch.int32, device=dev)

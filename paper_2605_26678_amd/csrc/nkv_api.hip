@@ -26,7 +26,7 @@ int check_params(const nkv_params *p)
     return NKV_OK;
 }
 
-int esize_of(int dtype) { return dtype == NKV_DTYPE_F32 ? 4 : 2; }
+int esize_of(int dtype) { return dtype == NKV_DTYPE_F32 ? 4 : dtype == NKV_DTYPE_F8_E4M3 ? 1 : 2; }
 
 // strides: NULL (dense [L][H][T][row]) or {layer, head, prompt} in elements
 int fill_map(const nkv_shape *s, const int64_t *strides, int row, RowMap *m)
@@ -72,7 +72,8 @@ int fill_map(const nkv_shape *s, const int64_t *strides, int row, RowMap *m)
 int check_shape(const nkv_shape *s)
 {
     if (!s || !s->cu_seqlens) return NKV_EINVAL;
-    if (s->dtype != NKV_DTYPE_F32 && s->dtype != NKV_DTYPE_BF16) return NKV_EINVAL;
+    if (s->dtype < NKV_DTYPE_F32 || s->dtype > NKV_DTYPE_F8_E4M3) return NKV_EINVAL;
+    if (s->dtype == NKV_DTYPE_F8_E4M3 && (s->d % 16 || s->dv % 16)) return NKV_ESHAPE;     // rows are 16-byte vectors
     if (s->L < 1 || s->H < 1 || s->H > NKV_MAX_HEADS || (int64_t)s->L * s->H > 65535) return NKV_ESHAPE;
     if (s->d < 8 || s->d > NKV_MAX_HEAD_DIM || s->d % 8) return NKV_ESHAPE;
     if (s->dv < 8 || s->dv > NKV_MAX_HEAD_DIM || s->dv % 8) return NKV_ESHAPE;
@@ -146,7 +147,7 @@ int run_raw(const void *keys, const nkv_shape *s, const nkv_params *p, const Pro
     if (rc) return rc;
     hipError_t e;
     if (!(p->flags & NKV_FLAG_GENERIC_KERNELS) && fast_score_supported(s->dtype, s->d, p->window, tab))
-        e = launch_score_fast(keys, km, LH, s->d, tab, a_raw, (float *)(ws + lay.bsum), (float *)(ws + lay.ssum),
+        e = launch_score_fast(keys, km, s->dtype, LH, s->d, tab, a_raw, (float *)(ws + lay.bsum), (float *)(ws + lay.ssum),
                               ws + lay.sync,
                               (p->flags & NKV_FLAG_TWO_PASS_STABLE)  ? kScanTwoPass
                               : (p->flags & NKV_FLAG_NO_UNIT_SUMS)  ? kScanRepairAll
@@ -362,6 +363,7 @@ int nkv_decode_workspace_bytes(const nkv_shape *shape, int32_t n_q_heads, int64_
     int rc = check_shape(shape);
     if (rc) return rc;
     if (n_q_heads < shape->H || n_q_heads % shape->H) return NKV_EINVAL;
+    if (shape->dtype == NKV_DTYPE_F8_E4M3) return NKV_EUNSUPPORTED;
     *bytes = decode_ws_bytes(shape->dtype, shape->d, shape->dv, n_q_heads / shape->H,
                              (int64_t)shape->n_prompts * shape->L * shape->H, rows);
     return NKV_OK;
@@ -378,6 +380,7 @@ int nkv_decode_attention(const void *q, const void *packed_k, const void *packed
     rc = check_params(params);
     if (rc) return rc;
     if (n_q_heads < shape->H || n_q_heads % shape->H) return NKV_EINVAL;
+    if (shape->dtype == NKV_DTYPE_F8_E4M3) return NKV_EUNSUPPORTED;  // needs the cache's scale factors
     if ((uintptr_t)q % 16 || (uintptr_t)packed_k % 16 || (uintptr_t)packed_v % 16) return NKV_EINVAL;
     const int G = n_q_heads / shape->H;
     const int64_t n_units = (int64_t)shape->n_prompts * shape->L * shape->H;

@@ -407,6 +407,9 @@ hipError_t launch_decode(const void *q, const void *pk, const void *pv, const in
     if (dtype == NKV_DTYPE_F32)
         return run_generic<float>((const float *)q, (const float *)pk, (const float *)pv, head_off, n_units, G, d, dv,
                                   rows, scale_log2, out, lse, prof, st);
+    if (dtype == NKV_DTYPE_F16)
+        return run_generic<f16_t>((const f16_t *)q, (const f16_t *)pk, (const f16_t *)pv, head_off, n_units, G, d, dv,
+                                  rows, scale_log2, out, lse, prof, st);
     return run_generic<uint16_t>((const uint16_t *)q, (const uint16_t *)pk, (const uint16_t *)pv, head_off, n_units, G,
                                  d, dv, rows, scale_log2, out, lse, prof, st);
 }

@@ -26,9 +26,29 @@ __device__ __forceinline__ float key_value(uint32_t k)
 
 __device__ __forceinline__ float bf16_to_f32(uint16_t v) { return __uint_as_float(((uint32_t)v) << 16); }
 
+// Element types that share a storage width are told apart by these wrappers.
+struct f16_t { uint16_t bits; };
+struct f8e4m3_t { uint8_t bits; };
+
+// OCP 8-bit float, 4 exponent bits (bias 7), 3 mantissa bits, no infinities, S.1111.111 = NaN.
+__device__ __forceinline__ float f8e4m3_to_f32(uint8_t v)
+{
+    const uint32_t e = (v >> 3) & 15u, m = v & 7u;
+    uint32_t mag;
+    if (e == 0u) mag = __float_as_uint((float)m * 0.001953125f);            // subnormal: m * 2^-9
+    else if (e == 15u && m == 7u) mag = 0x7fc00000u;
+    else mag = ((e + 120u) << 23) | (m << 20);
+    return __uint_as_float(mag | ((uint32_t)(v & 0x80u) << 24));
+}
+
 template <typename T> __device__ __forceinline__ float load_elem(const T *p);
 template <> __device__ __forceinline__ float load_elem<float>(const float *p) { return *p; }
 template <> __device__ __forceinline__ float load_elem<uint16_t>(const uint16_t *p) { return bf16_to_f32(*p); }
+template <> __device__ __forceinline__ float load_elem<f16_t>(const f16_t *p)
+{
+    return (float)*reinterpret_cast<const _Float16 *>(p);
+}
+template <> __device__ __forceinline__ float load_elem<f8e4m3_t>(const f8e4m3_t *p) { return f8e4m3_to_f32(p->bits); }
 
 // Prompt that owns global token row t (0 <= t < tab.T).
 __device__ __forceinline__ int prompt_of_token(const PromptTab &tab, int t)

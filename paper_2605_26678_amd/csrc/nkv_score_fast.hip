@@ -1,4 +1,4 @@
-// Streaming scoring kernel for bf16 keys, head dim 64 or 128, window 64, episodic block size <= 256
+// Streaming scoring kernel for bf16 or 8-bit (E4M3) keys, head dim 64 or 128, window 64, episodic block size <= 256
 // (paper Sections 2.1-2.3: normalised keys, stable / episodic / current anchors, cosine anomalies).
 //
 // Work decomposition.  One workgroup per (layer, head, episodic block).  The block (<= 256 tokens) is cut
@@ -179,9 +179,32 @@ using u32x4 = unsigned int __attribute__((ext_vector_type(4)));
 
 // 16-byte load through a buffer descriptor: the address is one 32-bit byte offset per lane plus an
 // immediate, and an offset outside [0, num_records) (tokens before the prompt or past its end) reads zeros.
-__device__ __forceinline__ u32x4 row_load(__amdgpu_buffer_rsrc_t rsrc, int byte_off)
+// ES = bytes per key element.  2: bf16, the lane's 16 bytes are the packed row piece the kernels work on.
+// 1: 8-bit E4M3 (4 exponent bits, bias 7, no infinities); the lane's 8 bytes are converted on the way in to
+// that same packed bf16 form -- exactly, 4 significant bits and the exponent range both fit -- so nothing
+// after the load knows the difference.  Conversion: the hardware's pairwise E4M3 -> fp32, then the upper
+// halves of two floats put side by side by a byte permute.
+using u32x2 = unsigned int __attribute__((ext_vector_type(2)));
+using f32x2 = float __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ uint32_t f8x2_to_bf16x2(uint32_t four, bool upper)
 {
-    return __builtin_amdgcn_raw_buffer_load_b128(rsrc, byte_off, 0, 0);
+    const f32x2 f = upper ? __builtin_amdgcn_cvt_pk_f32_fp8((int)four, true)
+                          : __builtin_amdgcn_cvt_pk_f32_fp8((int)four, false);
+    return __builtin_amdgcn_perm(__float_as_uint(f.y), __float_as_uint(f.x), 0x07060302u);
+}
+
+__device__ __forceinline__ u32x4 f8x8_to_bf16x8(const u32x2 &v)
+{
+    const u32x4 r = {f8x2_to_bf16x2(v.x, false), f8x2_to_bf16x2(v.x, true), f8x2_to_bf16x2(v.y, false),
+                     f8x2_to_bf16x2(v.y, true)};
+    return r;
+}
+
+template <int ES> __device__ __forceinline__ u32x4 row_load(__amdgpu_buffer_rsrc_t rsrc, int byte_off)
+{
+    if constexpr (ES == 2) return __builtin_amdgcn_raw_buffer_load_b128(rsrc, byte_off, 0, 0);
+    else return f8x8_to_bf16x8(__builtin_amdgcn_raw_buffer_load_b64(rsrc, byte_off, 0, 0));
 }
 
 __device__ __forceinline__ void unpack8(const u32x4 &r, float k[8])
@@ -387,9 +410,9 @@ __device__ __forceinline__ bool add_unit_up(const float *bsum_unit, int unblk, f
 }
 
 // NW wavefronts = chunks per block.  grid: one workgroup per (layer*head, block), 1-D.
-template <int D, int NW, bool FUSED>
+template <int D, int NW, bool FUSED, int ES>
 __global__ __launch_bounds__(64 * NW, 3)
-void scan_kernel(const uint16_t *__restrict__ keys, RowMap km, PromptTab tab, ScanPlan plan, float *__restrict__ a_raw,
+void scan_kernel(const uint8_t *__restrict__ keys, RowMap km, PromptTab tab, ScanPlan plan, float *__restrict__ a_raw,
                  float *__restrict__ bsum, float *__restrict__ ssum, uint32_t *__restrict__ sync, int LH,
                  int64_t rows, int poll_limit, uint32_t spin_limit)
 {
@@ -458,16 +481,16 @@ void scan_kernel(const uint16_t *__restrict__ keys, RowMap km, PromptTab tab, Sc
     // ---- first touch: the chunk and this wave's share of the halo ----
     // Rows are addressed relative to the prompt's first row; rows outside the prompt read as zeros, rows of
     // the prompt that lie outside this block get weight 0 below.
-    constexpr int kRowBytes = D * 2;
+    constexpr int kRowBytes = D * ES;
     const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<uint16_t *>(keys) + km.unit(layer, head, p, tab), 0, N * kRowBytes, 0x00020000);
-    const int lane_off = t0 * kRowBytes + c * 16;
+        const_cast<uint8_t *>(keys) + km.unit(layer, head, p, tab) * ES, 0, N * kRowBytes, 0x00020000);
+    const int lane_off = t0 * kRowBytes + c * (8 * ES);
     u32x4 raw[TPT], hraw[HT];
 #pragma unroll
-    for (int j = 0; j < TPT; ++j) raw[j] = row_load(rsrc, lane_off + j * kRowBytes);
-    const int halo_off = (blk_lo - 64 + g * TPT + HT * w) * kRowBytes + c * 16;
+    for (int j = 0; j < TPT; ++j) raw[j] = row_load<ES>(rsrc, lane_off + j * kRowBytes);
+    const int halo_off = (blk_lo - 64 + g * TPT + HT * w) * kRowBytes + c * (8 * ES);
 #pragma unroll
-    for (int jj = 0; jj < HT; ++jj) hraw[jj] = row_load(rsrc, halo_off + jj * kRowBytes);
+    for (int jj = 0; jj < HT; ++jj) hraw[jj] = row_load<ES>(rsrc, halo_off + jj * kRowBytes);
 
     // ---- norms: one token per lane (lane (g, c) reports token g*TPT + c = lane of the chunk) ----
     float rn_m, kn_m;
@@ -728,14 +751,14 @@ void scan_kernel(const uint16_t *__restrict__ keys, RowMap km, PromptTab tab, Sc
 // a_s of the blocks whose workgroups did not wait for their unit's sum.  One workgroup per listed block at a
 // time, one wave per chunk, same lane layout, same instruction sequences for the norm, the dot and the
 // cosine as scan_kernel, so the values are the ones scan_kernel would have stored.
-template <int D, int NW>
-__global__ __launch_bounds__(64 * NW) void deferred_stable_kernel(const uint16_t *__restrict__ keys, RowMap km,
+template <int D, int NW, int ES>
+__global__ __launch_bounds__(64 * NW) void deferred_stable_kernel(const uint8_t *__restrict__ keys, RowMap km,
                                                                   PromptTab tab,
                                                                   const float *__restrict__ ssum,
                                                                   const uint32_t *__restrict__ sync,
                                                                   float *__restrict__ a_raw)
 {
-    constexpr int LPR = D / 8, TPT = LPR, kRowBytes = D * 2;
+    constexpr int LPR = D / 8, TPT = LPR, kRowBytes = D * ES;
     const int nblk = tab.blk_off[tab.n];
     const uint32_t count = sync[kDeferCountWord];
     const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -747,11 +770,11 @@ __global__ __launch_bounds__(64 * NW) void deferred_stable_kernel(const uint16_t
         const int blk_lo = (blk - tab.blk_off[p]) * b, blk_hi = min(blk_lo + b, N);
         const int64_t row0 = (int64_t)lh * tab.T + tab.tok_off[p];
         const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
-            const_cast<uint16_t *>(keys) + km.unit(lh, p, tab), 0, N * kRowBytes, 0x00020000);
-        const int lane_off = (blk_lo + 64 * w + g * TPT) * kRowBytes + c * 16;
+            const_cast<uint8_t *>(keys) + km.unit(lh, p, tab) * ES, 0, N * kRowBytes, 0x00020000);
+        const int lane_off = (blk_lo + 64 * w + g * TPT) * kRowBytes + c * (8 * ES);
         u32x4 raw[TPT];
 #pragma unroll
-        for (int j = 0; j < TPT; ++j) raw[j] = row_load(rsrc, lane_off + j * kRowBytes);
+        for (int j = 0; j < TPT; ++j) raw[j] = row_load<ES>(rsrc, lane_off + j * kRowBytes);
         float ss[TPT];
 #pragma unroll
         for (int j = 0; j < TPT; ++j) ss[j] = sumsq8(raw[j]);
@@ -825,8 +848,8 @@ __global__ __launch_bounds__(D) void ssum_kernel(const float *__restrict__ bsum,
 }
 
 // Stable anomaly a_s by a second touch of the keys.  grid (ceil(T/256), L*H), 4 waves of 64 tokens.
-template <int D>
-__global__ __launch_bounds__(256) void stable_kernel(const uint16_t *__restrict__ keys, RowMap km, PromptTab tab,
+template <int D, int ES>
+__global__ __launch_bounds__(256) void stable_kernel(const uint8_t *__restrict__ keys, RowMap km, PromptTab tab,
                                                      const float *__restrict__ ssum, float *__restrict__ a_raw)
 {
     constexpr int LPR = D / 8, TPT = LPR;
@@ -841,9 +864,12 @@ __global__ __launch_bounds__(256) void stable_kernel(const uint16_t *__restrict_
         const int tg = tg0 + g * TPT + j;
         const bool ok = tg < tab.T;
         const int p = prompt_of_token(tab, ok ? tg : tab.T - 1);
-        const uint4 *row = reinterpret_cast<const uint4 *>(keys + km.unit(lh, p, tab) + (int64_t)(tg - tab.tok_off[p]) * D);
-        const uint4 r4 = ok ? row[c] : make_uint4(0u, 0u, 0u, 0u);
-        const u32x4 raw = {r4.x, r4.y, r4.z, r4.w};
+        const uint8_t *row = keys + (km.unit(lh, p, tab) + (int64_t)(tg - tab.tok_off[p]) * D) * ES;
+        u32x4 raw = {0u, 0u, 0u, 0u};
+        if (ok) {
+            if constexpr (ES == 2) raw = reinterpret_cast<const u32x4 *>(row)[c];
+            else raw = f8x8_to_bf16x8(reinterpret_cast<const u32x2 *>(row)[c]);
+        }
         float sv[8], k[8];
         load8(ssum + ((int64_t)lh * tab.n + p) * D + c * 8, sv);
         unpack8(raw, k);
@@ -866,8 +892,8 @@ __global__ __launch_bounds__(256) void stable_kernel(const uint16_t *__restrict_
     }
 }
 
-template <int D, int NW, bool FUSED>
-void launch_scan(const uint16_t *keys, const RowMap &km, int LH, const PromptTab &tab, float *a_raw, float *bsum, float *ssum,
+template <int D, int NW, bool FUSED, int ES>
+void launch_scan(const uint8_t *keys, const RowMap &km, int LH, const PromptTab &tab, float *a_raw, float *bsum, float *ssum,
                  uint32_t *sync, int poll_limit, uint32_t spin_limit, hipStream_t st)
 {
     const int64_t rows = (int64_t)LH * tab.T;
@@ -885,17 +911,17 @@ void launch_scan(const uint16_t *keys, const RowMap &km, int LH, const PromptTab
         longest = items > longest ? items : longest;
     }
     if (FUSED) groups = longest * kDies;
-    scan_kernel<D, NW, FUSED><<<groups, 64 * NW, 0, st>>>(keys, km, tab, plan, a_raw, bsum, ssum, sync, LH, rows, poll_limit,
+    scan_kernel<D, NW, FUSED, ES><<<groups, 64 * NW, 0, st>>>(keys, km, tab, plan, a_raw, bsum, ssum, sync, LH, rows, poll_limit,
                                                           spin_limit);
 }
 
-template <int D, int NW, bool FUSED> int resident_workgroups()
+template <int D, int NW, bool FUSED, int ES> int resident_workgroups()
 {
     static int cached = -1;                                          // per instantiation; benign if raced
     if (cached < 0) {
         int per_cu = 0, dev = 0;
         hipDeviceProp_t prop;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, scan_kernel<D, NW, FUSED>, 64 * NW, 0) != hipSuccess ||
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, scan_kernel<D, NW, FUSED, ES>, 64 * NW, 0) != hipSuccess ||
             hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess)
             return 0;
         cached = per_cu * prop.multiProcessorCount;
@@ -904,8 +930,8 @@ template <int D, int NW, bool FUSED> int resident_workgroups()
 }
 
 
-template <int D, int NW>
-hipError_t run_nw(const uint16_t *keys, const RowMap &km, int LH, const PromptTab &tab, float *a_raw, float *bsum, float *ssum,
+template <int D, int NW, int ES>
+hipError_t run_nw(const uint8_t *keys, const RowMap &km, int LH, const PromptTab &tab, float *a_raw, float *bsum, float *ssum,
                   void *sync_area, int mode, const Prof &prof, hipStream_t st)
 {
     int max_unit_blocks = 0;
@@ -917,7 +943,7 @@ hipError_t run_nw(const uint16_t *keys, const RowMap &km, int LH, const PromptTa
     const int64_t items = (int64_t)LH * (tab.blk_off[tab.n] + tab.n);
     const bool allow_fused = mode != kScanTwoPass, no_unit_sums = mode == kScanRepairAll;
     const bool defer_all = mode == kScanDeferAll || no_unit_sums;
-    const bool fused = allow_fused && items < (1ll << 28) && max_unit_blocks <= resident_workgroups<D, NW, true>();
+    const bool fused = allow_fused && items < (1ll << 28) && max_unit_blocks <= resident_workgroups<D, NW, true, ES>();
     if (fused) {
         // the counters start at zero, block totals and unit sums as "unwritten"
         const size_t nb = (size_t)LH * tab.blk_off[tab.n] * D / 4, ns = (size_t)LH * tab.n * D / 4;
@@ -925,33 +951,33 @@ hipError_t run_nw(const uint16_t *keys, const RowMap &km, int LH, const PromptTa
         prepare_kernel<<<(unsigned)min((n16 + 255) / 256, (size_t)2048), 256, 0, st>>>(
             (uint4 *)sync_area, kSyncWords / 4, (uint4 *)bsum, nb, (uint4 *)ssum, ns);
         prof.begin(NKV_KERNEL_SCAN, st);
-        launch_scan<D, NW, true>(keys, km, LH, tab, a_raw, bsum, ssum, (uint32_t *)sync_area,
+        launch_scan<D, NW, true, ES>(keys, km, LH, tab, a_raw, bsum, ssum, (uint32_t *)sync_area,
                                  defer_all ? -1 : kPollLimit, no_unit_sums ? 0u : kSpinLimit, st);
         prof.end(NKV_KERNEL_SCAN, st);
         unit_sum_repair_kernel<D, NW><<<LH * tab.n, 64 * NW, 0, st>>>(bsum, tab, ssum);
-        deferred_stable_kernel<D, NW><<<defer_all ? 4096 : 256, 64 * NW, 0, st>>>(keys, km, tab, ssum,
+        deferred_stable_kernel<D, NW, ES><<<defer_all ? 4096 : 256, 64 * NW, 0, st>>>(keys, km, tab, ssum,
                                                                                   (const uint32_t *)sync_area, a_raw);
     } else {
         prof.begin(NKV_KERNEL_SCAN, st);
-        launch_scan<D, NW, false>(keys, km, LH, tab, a_raw, bsum, ssum, nullptr, 0, 0u, st);
+        launch_scan<D, NW, false, ES>(keys, km, LH, tab, a_raw, bsum, ssum, nullptr, 0, 0u, st);
         prof.end(NKV_KERNEL_SCAN, st);
         ssum_kernel<D><<<dim3(tab.n, LH), D, 0, st>>>(bsum, tab, ssum);
-        stable_kernel<D><<<dim3((tab.T + 255) / 256, LH), 256, 0, st>>>(keys, km, tab, ssum, a_raw);
+        stable_kernel<D, ES><<<dim3((tab.T + 255) / 256, LH), 256, 0, st>>>(keys, km, tab, ssum, a_raw);
     }
     return hipGetLastError();
 }
 
-template <int D>
-hipError_t run(const uint16_t *keys, const RowMap &km, int LH, const PromptTab &tab, float *a_raw, float *bsum, float *ssum,
+template <int D, int ES>
+hipError_t run(const uint8_t *keys, const RowMap &km, int LH, const PromptTab &tab, float *a_raw, float *bsum, float *ssum,
                void *sync_area, int mode, const Prof &prof, hipStream_t st)
 {
     int bmax = 0;
     for (int p = 0; p < tab.n; ++p) bmax = max(bmax, tab.b[p]);
     switch ((bmax + 63) / 64) {
-    case 1: return run_nw<D, 1>(keys, km, LH, tab, a_raw, bsum, ssum, sync_area, mode, prof, st);
-    case 2: return run_nw<D, 2>(keys, km, LH, tab, a_raw, bsum, ssum, sync_area, mode, prof, st);
-    case 3: return run_nw<D, 3>(keys, km, LH, tab, a_raw, bsum, ssum, sync_area, mode, prof, st);
-    default: return run_nw<D, 4>(keys, km, LH, tab, a_raw, bsum, ssum, sync_area, mode, prof, st);
+    case 1: return run_nw<D, 1, ES>(keys, km, LH, tab, a_raw, bsum, ssum, sync_area, mode, prof, st);
+    case 2: return run_nw<D, 2, ES>(keys, km, LH, tab, a_raw, bsum, ssum, sync_area, mode, prof, st);
+    case 3: return run_nw<D, 3, ES>(keys, km, LH, tab, a_raw, bsum, ssum, sync_area, mode, prof, st);
+    default: return run_nw<D, 4, ES>(keys, km, LH, tab, a_raw, bsum, ssum, sync_area, mode, prof, st);
     }
 }
 
@@ -959,7 +985,7 @@ hipError_t run(const uint16_t *keys, const RowMap &km, int LH, const PromptTab &
 
 bool fast_score_supported(int dtype, int d, int window, const PromptTab &tab)
 {
-    if (dtype != NKV_DTYPE_BF16 || (d != 64 && d != 128) || window != 64) return false;
+    if ((dtype != NKV_DTYPE_BF16 && dtype != NKV_DTYPE_F8_E4M3) || (d != 64 && d != 128) || window != 64) return false;
     for (int p = 0; p < tab.n; ++p)
         if (tab.b[p] > 64 * kMaxChunks) return false;
     return true;
@@ -970,11 +996,16 @@ size_t fast_score_sync_bytes(int LH, const PromptTab &tab)
     return ((size_t)kSyncWords + (size_t)LH * tab.blk_off[tab.n]) * 4;       // counters + the list of deferred blocks
 }
 
-hipError_t launch_score_fast(const void *keys, const RowMap &km, int LH, int d, const PromptTab &tab, float *a_raw, float *bsum,
-                             float *ssum, void *sync_area, int mode, const Prof &prof, hipStream_t st)
+hipError_t launch_score_fast(const void *keys, const RowMap &km, int dtype, int LH, int d, const PromptTab &tab, float *a_raw,
+                             float *bsum, float *ssum, void *sync_area, int mode, const Prof &prof, hipStream_t st)
 {
-    if (d == 128) return run<128>((const uint16_t *)keys, km, LH, tab, a_raw, bsum, ssum, sync_area, mode, prof, st);
-    return run<64>((const uint16_t *)keys, km, LH, tab, a_raw, bsum, ssum, sync_area, mode, prof, st);
+    const uint8_t *k = (const uint8_t *)keys;
+    if (dtype == NKV_DTYPE_F8_E4M3) {
+        if (d == 128) return run<128, 1>(k, km, LH, tab, a_raw, bsum, ssum, sync_area, mode, prof, st);
+        return run<64, 1>(k, km, LH, tab, a_raw, bsum, ssum, sync_area, mode, prof, st);
+    }
+    if (d == 128) return run<128, 2>(k, km, LH, tab, a_raw, bsum, ssum, sync_area, mode, prof, st);
+    return run<64, 2>(k, km, LH, tab, a_raw, bsum, ssum, sync_area, mode, prof, st);
 }
 
 }  // namespace nkv

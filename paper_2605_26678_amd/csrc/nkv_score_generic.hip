@@ -1,5 +1,5 @@
 // Shape-generic scoring kernels: per-scale cosine anomalies a_s, a_e, a_c (paper Sections 2.1-2.3)
-// for any head dim (multiple of 8, <= 1024), any window and block size, fp32 or bf16 keys.
+// for any head dim (multiple of 8, <= 1024), any window and block size, fp32, bf16, fp16 or 8-bit (E4M3) keys.
 //
 // Four small kernels, none of them tuned -- they cover what the streaming kernels do not:
 //   1. rnorm   : 1 / max(||k_i||, eps) per token                       (Section 2.1)
@@ -160,6 +160,10 @@ hipError_t launch_score_generic(const void *keys, const RowMap &km, int dtype, i
 {
     if (dtype == NKV_DTYPE_F32)
         return run<float>((const float *)keys, km, LH, d, window, tab, a_raw, rnorm, bsum, ssum, prof, st);
+    if (dtype == NKV_DTYPE_F16)
+        return run<f16_t>((const f16_t *)keys, km, LH, d, window, tab, a_raw, rnorm, bsum, ssum, prof, st);
+    if (dtype == NKV_DTYPE_F8_E4M3)
+        return run<f8e4m3_t>((const f8e4m3_t *)keys, km, LH, d, window, tab, a_raw, rnorm, bsum, ssum, prof, st);
     return run<uint16_t>((const uint16_t *)keys, km, LH, d, window, tab, a_raw, rnorm, bsum, ssum, prof, st);
 }
 

@@ -33,13 +33,14 @@ def oracle_params(params: nkv.nkv_params) -> oracle.Params:
 
 
 def shape_of(w: nkv_inputs.Workload) -> nkv.Shape:
-    return nkv.Shape(w.L, w.H, w.d, w.d_v, nkv.DTYPE_F32 if w.dtype == "fp32" else nkv.DTYPE_BF16, w.cu_seqlens)
+    dtype = {"fp32": nkv.DTYPE_F32, "bf16": nkv.DTYPE_BF16, "fp16": nkv.DTYPE_F16, "fp8": nkv.DTYPE_F8_E4M3}[w.dtype]
+    return nkv.Shape(w.L, w.H, w.d, w.d_v, dtype, w.cu_seqlens)
 
 
 def bits(t: torch.Tensor) -> np.ndarray:
     """Bit pattern of a CPU/GPU tensor as a numpy integer array."""
     t = t.detach().cpu().contiguous()
-    return t.view(torch.int16 if t.element_size() == 2 else torch.int32).numpy()
+    return t.view({1: torch.uint8, 2: torch.int16, 4: torch.int32}[t.element_size()]).numpy()
 
 
 def check_scores(g: np.ndarray, o: np.ndarray, what: str) -> float:
@@ -129,7 +130,7 @@ def compare_end_to_end(w, K, V, r, params=None, layers=None, label=""):
         Kb, Vb = {l: bits(K[l])}, {l: bits(V[l])}          # only the sampled layers travel to the host
         for p in range(shape.n_prompts):
             lo, hi = cu[p], cu[p + 1]
-            Kl = K[l, :, lo:hi].float().cpu().numpy()
+            Kl = K[l, :, lo:hi].cpu().float().numpy()     # converted on the host, also 8-bit keys
             s, B, kept = oracle_layer(Kl, r_list[p], op)
             what = f"{label} prompt {p} layer {l}"
             stats["worst"] = max(stats["worst"], check_scores(g_scores[l, :, lo:hi], s, what))
@@ -161,7 +162,7 @@ def compare_stages(w, K, V, r, params=None, layers=None, label=""):
     shape = shape_of(w)
     r_list = [r] * shape.n_prompts if np.isscalar(r) else list(r)
     assert layers is None, "stage parity runs on whole (small) workloads"
-    Kf = K.float().cpu().numpy()
+    Kf = K.cpu().float().numpy()
     ref = oracle.compress(Kf, bits(K), bits(V), w.cu_seqlens, r_list, op)
     out, _ = run_gpu(w, K, V, r, params, scores=torch.from_numpy(ref.scores).to(K.device))
     assert np.array_equal(out.k_per_head.cpu().numpy(), ref.k_per_head), f"{label}: budgets differ"

@@ -84,6 +84,16 @@ def test_argument_errors_are_reported_before_any_device_work():
                                 0, 0, 0, 0) == nkv.NKV_EINVAL
     assert L.nkv_select_compact(fake, fake, fake, fake, C.byref(good.c), C.byref(p), 0, fake, fake, fake, 10,
                                 0, 0, 0, 0) == nkv.NKV_EINVAL
+    # 8-bit caches: rows are moved as 16-byte vectors, attention over them is refused
+    f8 = nkv.DTYPE_F8_E4M3
+    assert L.nkv_score(fake, C.byref(nkv.Shape(1, 2, 72, 64, f8, [0, 100]).c), C.byref(p), fake, fake, 1 << 30,
+                       0) == nkv.NKV_ESHAPE
+    assert L.nkv_score(fake, C.byref(nkv.Shape(1, 2, 64, 24, f8, [0, 100]).c), C.byref(p), fake, fake, 1 << 30,
+                       0) == nkv.NKV_ESHAPE
+    assert nkv.workspace_bytes(nkv.Shape(1, 2, 64, 32, f8, [0, 100])) > 0
+    nbytes = C.c_size_t(0)
+    assert L.nkv_decode_workspace_bytes(C.byref(nkv.Shape(1, 2, 64, 64, f8, [0, 100]).c), 4, 50,
+                                        C.byref(nbytes)) == nkv.NKV_EUNSUPPORTED
     with pytest.raises(nkv.NkvError):
         nkv.workspace_bytes(nkv.Shape(1, 2, 64, 64, 1, [0, 0]))
     assert "workspace" in nkv.strerror(nkv.NKV_EWORKSPACE)
@@ -98,6 +108,24 @@ def test_input_generator_is_deterministic_and_shaped():
     assert k1.shape == (2, 2, 500, 64) and v1.dtype == torch.bfloat16
     assert torch.equal(k1.view(torch.int16), k2.view(torch.int16)) and torch.equal(v1.view(torch.int16), v2.view(torch.int16))
     assert torch.allclose(k1[0, 0, 0].float().norm(), torch.tensor(10.0), atol=0.1)      # sink-like key
+
+
+def test_8bit_test_inputs_follow_the_published_format():
+    """The parity tests hand the oracle 8-bit keys converted to fp32 by torch on the host; this pins that
+    conversion to the E4M3 format's definition (sign, 4 exponent bits with bias 7, 3 mantissa bits, no
+    infinities, S.1111.111 = NaN) for all 256 codes, so that the kernels' own decoder is checked against the
+    format and not against a library's reading of it."""
+    import math
+    import torch
+    got = torch.arange(256, dtype=torch.uint8).view(torch.float8_e4m3fn).to(torch.float32).tolist()
+    for code in range(256):
+        s, e, m = code >> 7, (code >> 3) & 15, code & 7
+        if e == 15 and m == 7:
+            assert math.isnan(got[code])
+            continue
+        mag = m / 8.0 * 2.0 ** -6 if e == 0 else (1.0 + m / 8.0) * 2.0 ** (e - 7)
+        assert got[code] == (-mag if s else mag) and math.copysign(1.0, got[code]) == (-1.0 if s else 1.0), code
+    assert max(v for v in got if not math.isnan(v)) == 448.0
 
 
 def test_bench_refuses_more_than_one_gpu():

@@ -64,6 +64,7 @@ CASES = [
     ("generic_dv_differs", 1, 2, 128, 64, [500], "bf16", 4, 0.5),
     ("generic_d40", 1, 2, 40, 24, [300], "fp32", 2, 0.5),
     ("generic_g12", 1, 1, 64, 0, [300], "bf16", 12, 0.5),
+    ("generic_fp16", 1, 2, 128, 0, [600], "fp16", 4, 0.5),
 ]
 
 
@@ -72,7 +73,7 @@ def test_decode_over_the_oracles_compressed_cache(case):
     name, L, H, d, dv, lens, dtype, Hq, r = case
     w = nkv_inputs.small_workload(name, L, H, d, lens, dtype=dtype, dv=dv)
     K, V = nkv_inputs.make_kv(w, "cpu")
-    raw = torch.int16 if dtype == "bf16" else torch.int32
+    raw = torch.int32 if dtype == "fp32" else torch.int16
     comp = oracle.compress(K.float().numpy(), K.view(raw).numpy(), V.view(raw).numpy(), w.cu_seqlens,
                            [r] * len(lens), oracle_params(nkv.params_default()))
     pk = torch.from_numpy(comp.packed_k).view(K.dtype)

@@ -79,6 +79,9 @@ SWEEP = [
     ("fp32_ragged", 1, 2, 128, [300, 513], "fp32", 0),
     ("wide_head", 1, 1, 256, [600], "bf16", 0),
     ("d_40", 1, 2, 40, [500], "fp32", 24),
+    ("fp16_ragged", 2, 2, 128, [700, 300], "fp16", 0),
+    ("fp8_d128", 1, 2, 128, [2000, 130], "fp8", 0),       # 8-bit E4M3 keys and values
+    ("fp8_d64_dv", 2, 3, 64, [900], "fp8", 32),
     ("long_prompt", 1, 2, 64, [40000], "bf16", 0),        # beyond the register-resident per-head kernels
     ("many_heads", 1, 12, 64, [600, 90], "bf16", 0),      # beyond the 8-head layer budget kernel
     ("slice_edges", 1, 2, 128, [8193, 16385, 100, 24576], "bf16", 0),   # one token past a slice, exact slices
@@ -95,6 +98,24 @@ def test_shape_sweep(case, r):
     K, V = _kv(w)
     compare_stages(w, K, V, r, label=name)
     compare_end_to_end(w, K, V, r, label=name)
+
+
+@pytest.mark.parametrize("flags", [0, nkv.FLAG_GENERIC_KERNELS, nkv.FLAG_TWO_PASS_STABLE, nkv.FLAG_DEFER_STABLE])
+def test_8bit_keys_of_every_finite_code(flags):
+    """Keys and values made of uniformly random bytes (every finite E4M3 code, both zeros, subnormals, the
+    largest values; the two NaN codes are replaced): the streaming kernels' load-time conversion, on each of
+    their routes, and the generic kernels' decoder both have to agree with the oracle, which is fed the values
+    the format's definition gives."""
+    w = nkv_inputs.small_workload("fp8_codes", 2, 2, 128, [1500, 200], dtype="fp8")
+    g = torch.Generator().manual_seed(99)
+    def rand_codes(*shape):
+        b = torch.randint(0, 256, shape, dtype=torch.uint8, generator=g)
+        b[(b & 0x7f) == 0x7f] -= 1
+        return b.view(torch.float8_e4m3fn).to(DEV)
+    K, V = rand_codes(w.L, w.H, w.T, w.d), rand_codes(w.L, w.H, w.T, w.d_v)
+    assert len(torch.unique(K.view(torch.uint8))) == 254
+    st = compare_end_to_end(w, K, V, 0.5, params=nkv.params_default(flags=flags), label=f"fp8 codes flags={flags}")
+    _report(f"fp8 codes flags={flags}", st)
 
 
 @pytest.mark.parametrize("r", [0.0, 1.0])
