@@ -139,6 +139,7 @@ def main():
     ap.add_argument("--cpu-layers", type=int, default=0, help="layers the oracle is timed on (0 = choose)")
     ap.add_argument("--generic", action="store_true", help="force the shape-generic scoring kernels")
     ap.add_argument("--two-pass", action="store_true", help="stable anomaly in a second pass over the keys")
+    ap.add_argument("--mfma", action="store_true", help="matrix-core formulation of the fused scan")
     ap.add_argument("--per-layer", action="store_true",
                     help="a step is L passes with L = 1, one per layer's K/V slice, as a prefill loop would call it")
     ap.add_argument("--mode", choices=("pass", "decode"), default="pass",
@@ -164,7 +165,8 @@ def main():
     dtype = {"fp32": nkv.DTYPE_F32, "bf16": nkv.DTYPE_BF16, "fp16": nkv.DTYPE_F16, "fp8": nkv.DTYPE_F8_E4M3}[w.dtype]
     shape = nkv.Shape(w.L, w.H, w.d, w.d_v, dtype, w.cu_seqlens)
     params = nkv.params_default(flags=(nkv.FLAG_GENERIC_KERNELS if args.generic else 0)
-                                | (nkv.FLAG_TWO_PASS_STABLE if args.two_pass else 0))
+                                | (nkv.FLAG_TWO_PASS_STABLE if args.two_pass else 0)
+                                | (nkv.FLAG_MFMA_SCAN if args.mfma else 0))
     r_list = [r] * shape.n_prompts
     if args.per_layer:
         shape1 = nkv.Shape(1, w.H, w.d, w.d_v, shape.dtype, w.cu_seqlens)

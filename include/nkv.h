@@ -74,7 +74,9 @@ enum {
     NKV_FLAG_BUDGET_PER_HEAD = 16u,   /* nkv_budget: the kernels that hold a whole head in one workgroup     */
                                       /* instead of the slice-wise ones                                      */
     NKV_FLAG_STATS_PER_HEAD = 32u,    /* nkv_score: the same choice for the per-head statistics              */
-    NKV_FLAG_SELECT_PER_HEAD = 64u    /* nkv_select_compact: the same choice for the top-B_h selection       */
+    NKV_FLAG_SELECT_PER_HEAD = 64u,   /* nkv_select_compact: the same choice for the top-B_h selection       */
+    NKV_FLAG_MFMA_SCAN = 128u         /* streaming kernels, bf16: the matrix-core formulation of the fused   */
+                                      /* pass                                                                */
 };
 /* Kernels a caller can ask to have timed, see nkv_params.prof_start. */
 enum {

@@ -748,6 +748,406 @@ void scan_kernel(const uint8_t *__restrict__ keys, RowMap km, PromptTab tab, Sca
     }
 }
 
+// ---- matrix-core formulation of the same pass ----------------------------------------------------------
+// Every dot product of the pass is a row of a matrix product with bf16 inputs, which the matrix cores form
+// exactly (bf16 x bf16 products, fp32 sums):
+//   current window   <k_t, sum_{s in [t-63, t]} w_s k_s> = sum_s w_s G[t][s] with the Gram matrix G = K K^T of
+//                    the raw keys and w_s = 1 / ||k_s||: a weighted sum over a 64-wide band of G.  The square of
+//                    the window sum's norm follows the window: P_t = P_{t-1} + 2 c_t - g_t - (2 f_q - g_q),
+//                    q = t - 64, with c_t = <k^_t, window sum at t>, f_q = <k^_q, sum of k^_q .. k^_{q+63}> (the
+//                    same band, forwards) and g = ||k^||^2; P at the token in front of the chunk is the sum over
+//                    a 64 x 64 square of G, which the forward band's pieces add up to.
+//   chunk sums       sum_s w_s k_s, needed as a vector: a product with an identity matrix hands every lane 16
+//                    tokens of one dimension (a transpose), which it then adds up with the weights.
+//   episodic/stable  <k_t, anchor> with the fp32 anchor split into three bf16 terms (8 + 8 + 8 mantissa bits:
+//                    the split is exact), as three rows of a product against the keys.
+// One wave per 64-token chunk; it holds the chunk and the 64 tokens in front of it (128 rows) as operands of
+// v_mfma_f32_32x32x16_bf16: lane (r = lane % 32, h = lane / 32) has dims 16 kk + 8 h .. + 7 of row r of each
+// 32-row set, kk = 0 .. D/16 - 1.  A product's 32 x 32 result leaves lane (n, h) with column n, rows
+// 8 i + 4 h + j in register 4 i + j.  The vector unit only norms the rows (dot instructions on the packed
+// values) and adds weighted result registers; it never unpacks a key.
+using bf16x8 = __bf16 __attribute__((ext_vector_type(8)));
+using f32x16 = float __attribute__((ext_vector_type(16)));
+
+template <int KS> __device__ __forceinline__ f32x16 mm_tile(const u32x4 (&a)[KS], const u32x4 (&b)[KS])
+{
+    f32x16 c = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int kk = 0; kk < KS; ++kk)
+        c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a[kk]), __builtin_bit_cast(bf16x8, b[kk]),
+                                                    c, 0, 0, 0);
+    return c;
+}
+
+// Sum over this lane's 16 rows of w[row] * c[row][n], rows rho = 8 i + 4 h + j restricted by MASK against the
+// lane's column n: 0 all, 1 rho > n, 2 rho <= n, 3 rho >= n, 4 rho < n.  w: the row set's 32 weights in LDS.
+template <int MASK> __device__ __forceinline__ float col_sum(const f32x16 &c, const float *w, int n, int h)
+{
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const float4 w4 = *reinterpret_cast<const float4 *>(w + 8 * i + 4 * h);
+        const float ww[4] = {w4.x, w4.y, w4.z, w4.w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int rho = 8 * i + 4 * h + j;
+            const bool keep = MASK == 0 ? true : MASK == 1 ? rho > n : MASK == 2 ? rho <= n : MASK == 3 ? rho >= n : rho < n;
+            s = fmaf(keep ? ww[j] : 0.f, c[4 * i + j], s);
+        }
+    }
+    return s;
+}
+
+// Sum of squares of this lane's half row, then of the whole row (the other half sits 32 lanes away).
+template <int KS> __device__ __forceinline__ float row_sumsq(const u32x4 (&x)[KS])
+{
+    float acc = 0.f;
+#pragma unroll
+    for (int kk = 0; kk < KS; ++kk)
+        asm("v_dot2c_f32_bf16 %0, %1, %1\n\t"
+            "v_dot2c_f32_bf16 %0, %2, %2\n\t"
+            "v_dot2c_f32_bf16 %0, %3, %3\n\t"
+            "v_dot2c_f32_bf16 %0, %4, %4"
+            : "+v"(acc)
+            : "v"(x[kk].x), "v"(x[kk].y), "v"(x[kk].z), "v"(x[kk].w));
+    return acc + __shfl_xor(acc, 32, 64);
+}
+
+// fp32 -> three bf16 terms whose sum is the value (each takes the next 8 mantissa bits)
+__device__ __forceinline__ void split3(float x, uint16_t &hi, uint16_t &mid, uint16_t &lo)
+{
+    const uint32_t b0 = __float_as_uint(x) & 0xffff0000u;
+    const float r1 = x - __uint_as_float(b0);
+    const uint32_t b1 = __float_as_uint(r1) & 0xffff0000u;
+    const float r2 = r1 - __uint_as_float(b1);
+    hi = (uint16_t)(b0 >> 16);
+    mid = (uint16_t)(b1 >> 16);
+    lo = (uint16_t)(__float_as_uint(r2) >> 16);
+}
+
+// <k, anchor> for the 64 tokens of a chunk (token = lane): the anchor's three terms (terms[3][D] bf16 in LDS,
+// written by this wave) are rows 0-2 and 4-6 of the left operand, so that the result registers 0-2 hold them for
+// columns n in lanes h = 0 (rows 0-2) and h = 1 (rows 4-6) alike; the low half takes the chunk's first 32
+// tokens, the high half the other 32.
+template <int D> __device__ __forceinline__ float anchor_dot(const uint16_t *terms, const u32x4 (&c0)[D / 16],
+                                                             const u32x4 (&c1)[D / 16], int r, int h)
+{
+    constexpr int KS = D / 16;
+    u32x4 a[KS];
+    const bool has = r < 8 && (r & 3) < 3;
+#pragma unroll
+    for (int kk = 0; kk < KS; ++kk) {
+        const u32x4 zero = {0u, 0u, 0u, 0u};
+        a[kk] = has ? *reinterpret_cast<const u32x4 *>(terms + (r & 3) * D + 16 * kk + 8 * h) : zero;
+    }
+    const f32x16 d0 = mm_tile<KS>(a, c0), d1 = mm_tile<KS>(a, c1);
+    return h ? (d1[0] + d1[1]) + d1[2] : (d0[0] + d0[1]) + d0[2];
+}
+
+template <int D, int NW>
+__global__ __launch_bounds__(64 * NW, 2)
+void scan_mfma_kernel(const uint8_t *__restrict__ keys, RowMap km, PromptTab tab, ScanPlan plan, float *__restrict__ a_raw,
+                      float *__restrict__ bsum, float *__restrict__ ssum, uint32_t *__restrict__ sync, int LH, int64_t rows,
+                      int poll_limit, uint32_t spin_limit)
+{
+    constexpr int KS = D / 16, LPR = D / 8, SG = 64 / LPR;
+    __shared__ float lds_rn[NW][128];                                 // 1/||k|| of a wave's 128 rows (0: no such token)
+    __shared__ float lds_wb[NW][64];                                  // the same for the chunk, 0 outside the block
+    __shared__ float lds_C[NW][D];                                    // chunk totals
+    __shared__ __attribute__((aligned(16))) uint16_t lds_terms[NW][3][D];   // an anchor's bf16 terms, per wave
+    __shared__ float lds_S[D];
+    __shared__ float lds_T[NW * SG * D];                              // scratch of a summing workgroup
+    __shared__ int s_have;
+
+    const int nblk = plan.nblk;
+    int lh, blk, layer, head;
+    {
+        const int x = (int)(blockIdx.x & (kDies - 1));
+        const uint32_t t = blockIdx.x >> 3;
+        const int run = plan.run, len = plan.len[x];
+        if (t >= queue_start(LH, len, tab.n, x)) return;
+        int l = min(LH - 1, (int)((float)t * plan.inv_items[x]));
+        while (l > 0 && queue_start(l, len, tab.n, x) > t) --l;
+        while (l + 1 < LH && queue_start(l + 1, len, tab.n, x) <= t) ++l;
+        const int r = (int)(t - queue_start(l, len, tab.n, x));
+        lh = l;
+        const int nsum = l % kDies == x ? tab.n : 0;
+        {
+            const int rb = max(r - nsum, 0), cyc = div_by(rb, run, plan.inv_run);
+            blk = (cyc * kDies + x) * run + (rb - cyc * run);
+        }
+        layer = div_by(lh, km.H, plan.inv_H);
+        head = lh - layer * km.H;
+        const int sum_of = r < nsum ? r : -1;
+        if (sum_of >= 0) {
+            const int p = sum_of;
+            if (!add_unit_up<D, NW, true>(bsum + ((int64_t)lh * nblk + tab.blk_off[p]) * D,
+                                          tab.blk_off[p + 1] - tab.blk_off[p], ssum + ((int64_t)lh * tab.n + p) * D,
+                                          lds_T, spin_limit) &&
+                threadIdx.x == 0)
+                atomicAdd(sync + kTimeoutWord, 1u);
+            return;
+        }
+    }
+    const int p = prompt_of_block(tab, blk);
+    const int b = tab.b[p];
+    const int N = tab.tok_off[p + 1] - tab.tok_off[p];
+    const int blk_lo = (blk - tab.blk_off[p]) * b;
+    const int blk_hi = min(blk_lo + b, N);
+    const int64_t row0 = (int64_t)lh * tab.T + tab.tok_off[p];
+    const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int r = lane & 31, h = lane >> 5;
+    const int t0 = blk_lo + 64 * w;                                   // first token of this wave's chunk
+
+    // ---- first touch: rows t0 - 64 .. t0 + 63 as four sets of 32; rows outside the prompt read as zeros ----
+    constexpr int kRowBytes = D * 2;
+    const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint8_t *>(keys) + km.unit(layer, head, p, tab) * 2, 0, N * kRowBytes, 0x00020000);
+    u32x4 X[4][KS];
+#pragma unroll
+    for (int set = 3; set >= 0; --set) {                              // the chunk first: the block total waits for it
+        const int off = (t0 - 64 + 32 * set + r) * kRowBytes + 16 * h;
+#pragma unroll
+        for (int kk = 0; kk < KS; ++kk) X[set][kk] = row_load<2>(rsrc, off + 32 * kk);
+    }
+
+    // ---- norms ----
+    float rn[4], gd[4], ssv[4];                                       // 1/||k||, ||k^||^2, ||k||^2 of row r of each set
+#pragma unroll
+    for (int set = 0; set < 4; ++set) {
+        ssv[set] = row_sumsq<KS>(X[set]);
+        const int tk = t0 - 64 + 32 * set + r;
+        rn[set] = (tk >= 0 && tk < N) ? inv_norm(ssv[set]) : 0.f;
+        gd[set] = rn[set] * rn[set] * ssv[set];
+        if (h == 0) lds_rn[w][32 * set + r] = rn[set];
+    }
+    if (h == 0) {
+        lds_wb[w][r] = t0 + r < blk_hi ? rn[2] : 0.f;
+        lds_wb[w][32 + r] = t0 + 32 + r < blk_hi ? rn[3] : 0.f;
+    }
+    const float rn_m = h ? rn[3] : rn[2];                             // this lane's own token t0 + lane
+    const float gd_m = h ? gd[3] : gd[2], ss_m = h ? ssv[3] : ssv[2];
+    const float kn_m = ss_m < 1e-24f ? sqrtf(ss_m) * 1e12f : 1.f;     // ||k^|| is 1 unless the norm was clamped
+    __builtin_amdgcn_wave_barrier();
+
+    // ---- chunk total: transpose by an identity product, then the weighted sum over the 16 rows a lane holds ----
+    {
+        u32x4 ident[2];                                               // B[k][n] = (n == k) and (n == 16 + k), k = 8 h + e
+#pragma unroll
+        for (int o = 0; o < 2; ++o) {
+            uint32_t v[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int k0 = 8 * h + 2 * q + 16 * o;
+                v[q] = (r == k0 ? 0x3f80u : 0u) | (r == k0 + 1 ? 0x3f800000u : 0u);
+            }
+            ident[o] = u32x4{v[0], v[1], v[2], v[3]};
+        }
+#pragma unroll
+        for (int q = 0; q < KS / 2; ++q) {                            // dims 32 q + n
+            float part = 0.f;
+#pragma unroll
+            for (int set = 2; set < 4; ++set) {
+                f32x16 c = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+                c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, X[set][2 * q]),
+                                                            __builtin_bit_cast(bf16x8, ident[0]), c, 0, 0, 0);
+                c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, X[set][2 * q + 1]),
+                                                            __builtin_bit_cast(bf16x8, ident[1]), c, 0, 0, 0);
+                part += col_sum<0>(c, &lds_wb[w][32 * (set - 2)], r, h);
+            }
+            part += __shfl_xor(part, 32, 64);
+            if (h == 0) lds_C[w][32 * q + r] = part;
+        }
+    }
+    __syncthreads();
+
+    // ---- block total = episodic anchor (up to length); every wave forms it for itself ----
+    const int nch = (blk_hi - blk_lo + 63) >> 6;
+    const int unblk = tab.blk_off[p + 1] - tab.blk_off[p];
+    float *bsum_unit = bsum + ((int64_t)lh * nblk + tab.blk_off[p]) * D;
+    float *S_unit = ssum + ((int64_t)lh * tab.n + p) * D;
+    float bsq = 0.f;
+    {
+        constexpr int DPL = D / 64;                                   // dims per lane: 64 lanes cover the D dims
+        float Bv[DPL];
+#pragma unroll
+        for (int e = 0; e < DPL; ++e) {
+            const int dim = DPL * lane + e;
+            float s = 0.f;
+#pragma unroll
+            for (int ww = 0; ww < NW; ++ww)
+                if (ww < nch) s += lds_C[ww][dim];
+            Bv[e] = s;
+            bsq = fmaf(s, s, bsq);
+            uint16_t t0b, t1b, t2b;
+            split3(s, t0b, t1b, t2b);
+            lds_terms[w][0][dim] = t0b;
+            lds_terms[w][1][dim] = t1b;
+            lds_terms[w][2][dim] = t2b;
+        }
+        bsq = wave_sum(bsq);
+        if (w == blk % NW) {                                          // one wave stores the block total
+            const __amdgpu_buffer_rsrc_t brs = __builtin_amdgcn_make_buffer_rsrc(bsum_unit, 0, unblk * D * 4, 0x00020000);
+            const int off = ((blk - tab.blk_off[p]) * D + DPL * lane) * 4;
+            if constexpr (DPL == 2) {
+                const float o0 = __shfl_down(Bv[0], 1, 64), o1 = __shfl_down(Bv[1], 1, 64);
+                if ((lane & 1) == 0) agent_store16(brs, off, Bv[0], Bv[1], o0, o1);
+            } else {
+                const float o1 = __shfl_down(Bv[0], 1, 64), o2 = __shfl_down(Bv[0], 2, 64), o3 = __shfl_down(Bv[0], 3, 64);
+                if ((lane & 3) == 0) agent_store16(brs, off, Bv[0], o1, o2, o3);
+            }
+        }
+    }
+    __builtin_amdgcn_wave_barrier();
+    const int tok = t0 + lane;
+    {
+        const float bd = anchor_dot<D>(&lds_terms[w][0][0], X[2], X[3], r, h);
+        if (tok < blk_hi) a_raw[rows + row0 + tok] = neg_cos(rn_m * bd, kn_m, bsq);
+    }
+
+    // ---- current window: bands of the Gram matrix ----
+    {
+        const float *wH0 = &lds_rn[w][0], *wH1 = &lds_rn[w][32], *wC0 = &lds_rn[w][64], *wC1 = &lds_rn[w][96];
+        // backward band of the chunk's tokens
+        float c0 = col_sum<1>(mm_tile<KS>(X[0], X[2]), wH0, r, h);
+        c0 += col_sum<0>(mm_tile<KS>(X[1], X[2]), wH1, r, h);
+        c0 += col_sum<2>(mm_tile<KS>(X[2], X[2]), wC0, r, h);
+        float c1 = col_sum<1>(mm_tile<KS>(X[1], X[3]), wH1, r, h);
+        c1 += col_sum<0>(mm_tile<KS>(X[2], X[3]), wC0, r, h);
+        c1 += col_sum<2>(mm_tile<KS>(X[3], X[3]), wC1, r, h);
+        // forward band of the 64 tokens in front of the chunk
+        float f0 = col_sum<3>(mm_tile<KS>(X[0], X[0]), wH0, r, h);
+        f0 += col_sum<0>(mm_tile<KS>(X[1], X[0]), wH1, r, h);
+        const float sq0 = f0;                                         // the part inside the 64 x 64 square
+        f0 += col_sum<4>(mm_tile<KS>(X[2], X[0]), wC0, r, h);
+        float f1 = col_sum<3>(mm_tile<KS>(X[1], X[1]), wH1, r, h);
+        const float sq1 = f1;
+        f1 += col_sum<0>(mm_tile<KS>(X[2], X[1]), wC0, r, h);
+        f1 += col_sum<4>(mm_tile<KS>(X[3], X[1]), wC1, r, h);
+        float v[6] = {c0, c1, f0, f1, sq0, sq1};
+#pragma unroll
+        for (int i = 0; i < 6; ++i) v[i] += __shfl_xor(v[i], 32, 64);
+        const float c_m = rn_m * (h ? v[1] : v[0]);                   // <k^_t, window sum at t>, t = t0 + lane
+        const float rq = h ? rn[1] : rn[0], gq = h ? gd[1] : gd[0];   // q = t - 64
+        const float f_m = rq * (h ? v[3] : v[2]);
+        // square of the window sum's norm at token t0 - 1: the 64 x 64 square, from its lower triangles
+        float P0 = h ? 2.f * rq * v[5] - gq : 2.f * rq * v[4] - gq;
+        P0 = wave_sum(P0);
+        float d = (2.f * c_m - gd_m) - (2.f * f_m - gq);              // P_t - P_{t-1}
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const float up = __shfl_up(d, o, 64);
+            if (lane >= o) d += up;
+        }
+        if (tok < blk_hi) a_raw[2 * rows + row0 + tok] = neg_cos(c_m, kn_m, P0 + d);
+    }
+
+    // ---- stable dots against the unit's sum ----
+    const __amdgpu_buffer_rsrc_t srs = __builtin_amdgcn_make_buffer_rsrc(S_unit, 0, D * 4, 0x00020000);
+    if (w == 0) {
+        u32x4 sv0 = {kUnwritten, kUnwritten, kUnwritten, kUnwritten}, sv1 = sv0;
+        bool got = false;
+        for (int polls = 0; poll_limit >= 0; ++polls) {
+            if (lane < LPR) {
+                sv0 = agent_load16(srs, lane * 32);
+                sv1 = agent_load16(srs, lane * 32 + 16);
+            }
+            const bool ok = lane >= LPR || (all_written(sv0) && all_written(sv1));
+            got = __all(ok);
+            if (got || polls >= poll_limit) break;
+            __builtin_amdgcn_s_sleep(8);
+        }
+        if (got && lane < LPR) {
+            *reinterpret_cast<u32x4 *>(&lds_S[lane * 8]) = sv0;
+            *reinterpret_cast<u32x4 *>(&lds_S[lane * 8 + 4]) = sv1;
+        }
+        if (lane == 0) {
+            s_have = got ? 1 : 0;
+            if (!got) sync[kSyncWords + atomicAdd(sync + kDeferCountWord, 1u)] = (uint32_t)(lh * nblk + blk);
+        }
+    }
+    __syncthreads();
+    if (s_have != 0) {
+        constexpr int DPL = D / 64;
+        float ssq = 0.f;
+#pragma unroll
+        for (int e = 0; e < DPL; ++e) {
+            const int dim = DPL * lane + e;
+            const float s = lds_S[dim];
+            ssq = fmaf(s, s, ssq);
+            uint16_t t0b, t1b, t2b;
+            split3(s, t0b, t1b, t2b);
+            lds_terms[w][0][dim] = t0b;
+            lds_terms[w][1][dim] = t1b;
+            lds_terms[w][2][dim] = t2b;
+        }
+        ssq = wave_sum(ssq);
+        __builtin_amdgcn_wave_barrier();
+        const float sd = anchor_dot<D>(&lds_terms[w][0][0], X[2], X[3], r, h);
+        if (tok < blk_hi) a_raw[row0 + tok] = neg_cos(rn_m * sd, kn_m, ssq);
+    }
+}
+
+// a_s of the listed blocks for scan_mfma_kernel: the same loads, norms, split and product as there.
+template <int D, int NW>
+__global__ __launch_bounds__(64 * NW, 2) void deferred_stable_mfma_kernel(const uint8_t *__restrict__ keys, RowMap km,
+                                                                          PromptTab tab, const float *__restrict__ ssum,
+                                                                          const uint32_t *__restrict__ sync,
+                                                                          float *__restrict__ a_raw)
+{
+    constexpr int KS = D / 16, kRowBytes = D * 2, DPL = D / 64;
+    __shared__ __attribute__((aligned(16))) uint16_t lds_terms[NW][3][D];
+    const int nblk = tab.blk_off[tab.n];
+    const uint32_t count = sync[kDeferCountWord];
+    const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int r = lane & 31, h = lane >> 5;
+    for (uint32_t i = blockIdx.x; i < count; i += gridDim.x) {
+        const int id = (int)sync[kSyncWords + i], lh = id / nblk, blk = id - lh * nblk;
+        const int p = prompt_of_block(tab, blk);
+        const int b = tab.b[p], N = tab.tok_off[p + 1] - tab.tok_off[p];
+        const int blk_lo = (blk - tab.blk_off[p]) * b, blk_hi = min(blk_lo + b, N);
+        const int64_t row0 = (int64_t)lh * tab.T + tab.tok_off[p];
+        const int t0 = blk_lo + 64 * w;
+        const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<uint8_t *>(keys) + km.unit(lh, p, tab) * 2, 0, N * kRowBytes, 0x00020000);
+        u32x4 X[2][KS];
+        float rn[2], ssv[2];
+#pragma unroll
+        for (int set = 0; set < 2; ++set) {
+            const int off = (t0 + 32 * set + r) * kRowBytes + 16 * h;
+#pragma unroll
+            for (int kk = 0; kk < KS; ++kk) X[set][kk] = row_load<2>(rsrc, off + 32 * kk);
+        }
+#pragma unroll
+        for (int set = 0; set < 2; ++set) {
+            ssv[set] = row_sumsq<KS>(X[set]);
+            const int tk = t0 + 32 * set + r;
+            rn[set] = (tk >= 0 && tk < N) ? inv_norm(ssv[set]) : 0.f;
+        }
+        const float rn_m = h ? rn[1] : rn[0], ss_m = h ? ssv[1] : ssv[0];
+        const float kn_m = ss_m < 1e-24f ? sqrtf(ss_m) * 1e12f : 1.f;
+        const float *S = ssum + ((int64_t)lh * tab.n + p) * D;
+        float ssq = 0.f;
+        __builtin_amdgcn_wave_barrier();                              // the previous block's reads of the terms
+#pragma unroll
+        for (int e = 0; e < DPL; ++e) {
+            const int dim = DPL * lane + e;
+            const float s = S[dim];
+            ssq = fmaf(s, s, ssq);
+            uint16_t t0b, t1b, t2b;
+            split3(s, t0b, t1b, t2b);
+            lds_terms[w][0][dim] = t0b;
+            lds_terms[w][1][dim] = t1b;
+            lds_terms[w][2][dim] = t2b;
+        }
+        ssq = wave_sum(ssq);
+        __builtin_amdgcn_wave_barrier();
+        const float sd = anchor_dot<D>(&lds_terms[w][0][0], X[0], X[1], r, h);
+        const int tok = t0 + lane;
+        if (tok < blk_hi) a_raw[row0 + tok] = neg_cos(rn_m * sd, kn_m, ssq);
+    }
+}
+
 // a_s of the blocks whose workgroups did not wait for their unit's sum.  One workgroup per listed block at a
 // time, one wave per chunk, same lane layout, same instruction sequences for the norm, the dot and the
 // cosine as scan_kernel, so the values are the ones scan_kernel would have stored.
@@ -892,7 +1292,7 @@ __global__ __launch_bounds__(256) void stable_kernel(const uint8_t *__restrict__
     }
 }
 
-template <int D, int NW, bool FUSED, int ES>
+template <int D, int NW, bool FUSED, int ES, bool MFMA = false>
 void launch_scan(const uint8_t *keys, const RowMap &km, int LH, const PromptTab &tab, float *a_raw, float *bsum, float *ssum,
                  uint32_t *sync, int poll_limit, uint32_t spin_limit, hipStream_t st)
 {
@@ -911,8 +1311,12 @@ void launch_scan(const uint8_t *keys, const RowMap &km, int LH, const PromptTab 
         longest = items > longest ? items : longest;
     }
     if (FUSED) groups = longest * kDies;
-    scan_kernel<D, NW, FUSED, ES><<<groups, 64 * NW, 0, st>>>(keys, km, tab, plan, a_raw, bsum, ssum, sync, LH, rows, poll_limit,
-                                                          spin_limit);
+    if constexpr (MFMA)
+        scan_mfma_kernel<D, NW><<<groups, 64 * NW, 0, st>>>(keys, km, tab, plan, a_raw, bsum, ssum, sync, LH, rows,
+                                                            poll_limit, spin_limit);
+    else
+        scan_kernel<D, NW, FUSED, ES><<<groups, 64 * NW, 0, st>>>(keys, km, tab, plan, a_raw, bsum, ssum, sync, LH, rows,
+                                                                  poll_limit, spin_limit);
 }
 
 template <int D, int NW, bool FUSED, int ES> int resident_workgroups()
@@ -930,9 +1334,23 @@ template <int D, int NW, bool FUSED, int ES> int resident_workgroups()
 }
 
 
+template <int D, int NW> int resident_workgroups_mfma()
+{
+    static int cached = -1;
+    if (cached < 0) {
+        int per_cu = 0, dev = 0;
+        hipDeviceProp_t prop;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, scan_mfma_kernel<D, NW>, 64 * NW, 0) != hipSuccess ||
+            hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess)
+            return 0;
+        cached = per_cu * prop.multiProcessorCount;
+    }
+    return cached;
+}
+
 template <int D, int NW, int ES>
 hipError_t run_nw(const uint8_t *keys, const RowMap &km, int LH, const PromptTab &tab, float *a_raw, float *bsum, float *ssum,
-                  void *sync_area, int mode, const Prof &prof, hipStream_t st)
+                  void *sync_area, int mode, bool mfma, const Prof &prof, hipStream_t st)
 {
     int max_unit_blocks = 0;
     for (int p = 0; p < tab.n; ++p) max_unit_blocks = max(max_unit_blocks, tab.blk_off[p + 1] - tab.blk_off[p]);
@@ -944,7 +1362,20 @@ hipError_t run_nw(const uint8_t *keys, const RowMap &km, int LH, const PromptTab
     const bool allow_fused = mode != kScanTwoPass, no_unit_sums = mode == kScanRepairAll;
     const bool defer_all = mode == kScanDeferAll || no_unit_sums;
     const bool fused = allow_fused && items < (1ll << 28) && max_unit_blocks <= resident_workgroups<D, NW, true, ES>();
-    if (fused) {
+    if (ES == 2 && mfma && fused && max_unit_blocks <= resident_workgroups_mfma<D, NW>()) {
+        // the matrix-core formulation of the fused pass (same protocol, its own kernel for the deferred blocks)
+        const size_t nb = (size_t)LH * tab.blk_off[tab.n] * D / 4, ns = (size_t)LH * tab.n * D / 4;
+        const size_t n16 = kSyncWords / 4 + nb + ns;
+        prepare_kernel<<<(unsigned)min((n16 + 255) / 256, (size_t)2048), 256, 0, st>>>(
+            (uint4 *)sync_area, kSyncWords / 4, (uint4 *)bsum, nb, (uint4 *)ssum, ns);
+        prof.begin(NKV_KERNEL_SCAN, st);
+        launch_scan<D, NW, true, 2, true>(keys, km, LH, tab, a_raw, bsum, ssum, (uint32_t *)sync_area,
+                                          defer_all ? -1 : kPollLimit, no_unit_sums ? 0u : kSpinLimit, st);
+        prof.end(NKV_KERNEL_SCAN, st);
+        unit_sum_repair_kernel<D, NW><<<LH * tab.n, 64 * NW, 0, st>>>(bsum, tab, ssum);
+        deferred_stable_mfma_kernel<D, NW><<<defer_all ? 4096 : 256, 64 * NW, 0, st>>>(keys, km, tab, ssum,
+                                                                                       (const uint32_t *)sync_area, a_raw);
+    } else if (fused) {
         // the counters start at zero, block totals and unit sums as "unwritten"
         const size_t nb = (size_t)LH * tab.blk_off[tab.n] * D / 4, ns = (size_t)LH * tab.n * D / 4;
         const size_t n16 = kSyncWords / 4 + nb + ns;
@@ -969,15 +1400,15 @@ hipError_t run_nw(const uint8_t *keys, const RowMap &km, int LH, const PromptTab
 
 template <int D, int ES>
 hipError_t run(const uint8_t *keys, const RowMap &km, int LH, const PromptTab &tab, float *a_raw, float *bsum, float *ssum,
-               void *sync_area, int mode, const Prof &prof, hipStream_t st)
+               void *sync_area, int mode, bool mfma, const Prof &prof, hipStream_t st)
 {
     int bmax = 0;
     for (int p = 0; p < tab.n; ++p) bmax = max(bmax, tab.b[p]);
     switch ((bmax + 63) / 64) {
-    case 1: return run_nw<D, 1, ES>(keys, km, LH, tab, a_raw, bsum, ssum, sync_area, mode, prof, st);
-    case 2: return run_nw<D, 2, ES>(keys, km, LH, tab, a_raw, bsum, ssum, sync_area, mode, prof, st);
-    case 3: return run_nw<D, 3, ES>(keys, km, LH, tab, a_raw, bsum, ssum, sync_area, mode, prof, st);
-    default: return run_nw<D, 4, ES>(keys, km, LH, tab, a_raw, bsum, ssum, sync_area, mode, prof, st);
+    case 1: return run_nw<D, 1, ES>(keys, km, LH, tab, a_raw, bsum, ssum, sync_area, mode, mfma, prof, st);
+    case 2: return run_nw<D, 2, ES>(keys, km, LH, tab, a_raw, bsum, ssum, sync_area, mode, mfma, prof, st);
+    case 3: return run_nw<D, 3, ES>(keys, km, LH, tab, a_raw, bsum, ssum, sync_area, mode, mfma, prof, st);
+    default: return run_nw<D, 4, ES>(keys, km, LH, tab, a_raw, bsum, ssum, sync_area, mode, mfma, prof, st);
     }
 }
 
@@ -997,15 +1428,16 @@ size_t fast_score_sync_bytes(int LH, const PromptTab &tab)
 }
 
 hipError_t launch_score_fast(const void *keys, const RowMap &km, int dtype, int LH, int d, const PromptTab &tab, float *a_raw,
-                             float *bsum, float *ssum, void *sync_area, int mode, const Prof &prof, hipStream_t st)
+                             float *bsum, float *ssum, void *sync_area, int mode, bool mfma, const Prof &prof,
+                             hipStream_t st)
 {
     const uint8_t *k = (const uint8_t *)keys;
     if (dtype == NKV_DTYPE_F8_E4M3) {
-        if (d == 128) return run<128, 1>(k, km, LH, tab, a_raw, bsum, ssum, sync_area, mode, prof, st);
-        return run<64, 1>(k, km, LH, tab, a_raw, bsum, ssum, sync_area, mode, prof, st);
+        if (d == 128) return run<128, 1>(k, km, LH, tab, a_raw, bsum, ssum, sync_area, mode, false, prof, st);
+        return run<64, 1>(k, km, LH, tab, a_raw, bsum, ssum, sync_area, mode, false, prof, st);
     }
-    if (d == 128) return run<128, 2>(k, km, LH, tab, a_raw, bsum, ssum, sync_area, mode, prof, st);
-    return run<64, 2>(k, km, LH, tab, a_raw, bsum, ssum, sync_area, mode, prof, st);
+    if (d == 128) return run<128, 2>(k, km, LH, tab, a_raw, bsum, ssum, sync_area, mode, mfma, prof, st);
+    return run<64, 2>(k, km, LH, tab, a_raw, bsum, ssum, sync_area, mode, mfma, prof, st);
 }
 
 }  // namespace nkv

@@ -118,6 +118,23 @@ def test_8bit_keys_of_every_finite_code(flags):
     _report(f"fp8 codes flags={flags}", st)
 
 
+MFMA_CASES = ["below_window", "one_short_block", "block_tail", "odd_len_64", "b_between", "b_255", "ragged_small",
+              "dv_differs", "slice_edges", "slices_d64", "long_prompt"]
+
+
+@pytest.mark.parametrize("route", [0, nkv.FLAG_DEFER_STABLE, nkv.FLAG_NO_UNIT_SUMS])
+@pytest.mark.parametrize("name", MFMA_CASES)
+def test_matrix_core_scan(name, route):
+    """The matrix-core formulation of the fused scan on the sweep's bf16 shapes, on its three routes (unit sum
+    found in time, every block deferred, every unit sum from the repair kernel), against the oracle."""
+    _, L, H, d, lens, dtype, dv = next(c for c in SWEEP if c[0] == name)
+    w = nkv_inputs.small_workload(name, L, H, d, lens, dtype=dtype, dv=dv, n_out=min(8, max(min(lens) - 4, 0)))
+    K, V = _kv(w)
+    st = compare_end_to_end(w, K, V, 0.5, params=nkv.params_default(flags=nkv.FLAG_MFMA_SCAN | route),
+                            label=f"mfma {name} route={route}")
+    _report(f"mfma {name} route={route}", st)
+
+
 @pytest.mark.parametrize("r", [0.0, 1.0])
 def test_keep_everything_and_keep_nothing(r):
     w = nkv_inputs.small_workload("extremes", 2, 2, 128, [300, 77])
