@@ -174,9 +174,15 @@ def main():
     else:
         calls = [(nkv.Compressor(shape, r_list, params), K, V)]
     stream = torch.cuda.current_stream()
-    for _ in range(args.warmup):
-        for comp, Kc, Vc in calls:
+
+    def run_all(per_call_params=None):
+        for c, (comp, Kc, Vc) in enumerate(calls):
+            if per_call_params is not None:
+                comp.params = per_call_params[c]
             comp.run(Kc, Vc, stream)
+
+    for _ in range(args.warmup):
+        run_all()
     torch.cuda.synchronize()
 
     # Timed region: K steps; the two kernels that can dominate (key scan, K/V gather) are bracketed by their
@@ -188,9 +194,7 @@ def main():
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for i in range(args.steps):
-            for c, (comp, Kc, Vc) in enumerate(calls):
-                comp.params = timed[i][c]
-                comp.run(Kc, Vc, stream)
+            run_all(timed[i])
         torch.cuda.synchronize()
         wall = time.perf_counter() - t0
         # per step: a kernel's launches added up over the step's calls
@@ -247,9 +251,9 @@ def main():
         spent = 0.0
         done = 0
         for l in range(n_layers):
-            Kl = K[l].float().cpu().numpy()
-            Kb = K[l].cpu().view(torch.int16).numpy() if esize == 2 else K[l].cpu().view(torch.int32).numpy()
-            Vb = V[l].cpu().view(torch.int16).numpy() if esize == 2 else V[l].cpu().view(torch.int32).numpy()
+            raw = {1: torch.uint8, 2: torch.int16, 4: torch.int32}[esize]
+            Kl = K[l].cpu().float().numpy()
+            Kb, Vb = K[l].cpu().view(raw).numpy(), V[l].cpu().view(raw).numpy()
             t = time.perf_counter()
             oracle.compress(Kl[None], Kb[None], Vb[None], cu, r_list, op)
             spent += time.perf_counter() - t

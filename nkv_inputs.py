@@ -93,6 +93,8 @@ WORKLOADS = {
     # beyond the paper's longest evaluated prompts (40k cap): the same Qwen3-4B shape at 40k and 128k tokens
     "qwen4b_40k": Workload("qwen4b_40k", 36, 8, 128, "bf16", (40960,), (0.75,), 128, True, True, True, 5),
     "qwen4b_128k": Workload("qwen4b_128k", 36, 8, 128, "bf16", (131072,), (0.75,), 128, True, True, True, 6),
+    # the headline shape with an fp16 cache
+    "qwen4b_32k_fp16": Workload("qwen4b_32k_fp16", 36, 8, 128, "fp16", (32768,), (0.75,), 128, True, True, True, 3),
     # the headline shape with an 8-bit (E4M3) cache
     "qwen4b_32k_fp8": Workload("qwen4b_32k_fp8", 36, 8, 128, "fp8", (32768,), (0.75,), 128, True, True, True, 3),
 }

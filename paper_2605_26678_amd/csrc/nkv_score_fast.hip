@@ -1,4 +1,4 @@
-// Streaming scoring kernel for bf16 or 8-bit (E4M3) keys, head dim 64 or 128, window 64, episodic block size <= 256
+// Streaming scoring kernel for bf16, fp16 or 8-bit (E4M3) keys, head dim 64 or 128, window 64, episodic block size <= 256
 // (paper Sections 2.1-2.3: normalised keys, stable / episodic / current anchors, cosine anomalies).
 //
 // Work decomposition.  One workgroup per (layer, head, episodic block).  The block (<= 256 tokens) is cut
@@ -207,40 +207,75 @@ template <int ES> __device__ __forceinline__ u32x4 row_load(__amdgpu_buffer_rsrc
     else return f8x8_to_bf16x8(__builtin_amdgcn_raw_buffer_load_b64(rsrc, byte_off, 0, 0));
 }
 
-__device__ __forceinline__ void unpack8(const u32x4 &r, float k[8])
+// Key formats of the streaming kernels (template parameter KF).  A packed row piece holds eight 16-bit values:
+// bf16 (also what 8-bit keys are converted to on the way in) or fp16; only unpacking and the sum of squares
+// know which.
+constexpr int kKeyF8 = 1, kKeyBF16 = 2, kKeyF16 = 3;
+template <int KF> constexpr int key_bytes() { return KF == kKeyF8 ? 1 : 2; }
+
+using f16x2 = _Float16 __attribute__((ext_vector_type(2)));
+
+template <int KF> __device__ __forceinline__ void unpack8(const u32x4 &r, float k[8])
 {
-    k[0] = __uint_as_float(r.x << 16); k[1] = __uint_as_float(r.x & 0xffff0000u);
-    k[2] = __uint_as_float(r.y << 16); k[3] = __uint_as_float(r.y & 0xffff0000u);
-    k[4] = __uint_as_float(r.z << 16); k[5] = __uint_as_float(r.z & 0xffff0000u);
-    k[6] = __uint_as_float(r.w << 16); k[7] = __uint_as_float(r.w & 0xffff0000u);
+    if constexpr (KF == kKeyF16) {
+        const uint32_t w[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const f16x2 v = __builtin_bit_cast(f16x2, w[i]);
+            k[2 * i] = (float)v.x;
+            k[2 * i + 1] = (float)v.y;
+        }
+    } else {
+        k[0] = __uint_as_float(r.x << 16); k[1] = __uint_as_float(r.x & 0xffff0000u);
+        k[2] = __uint_as_float(r.y << 16); k[3] = __uint_as_float(r.y & 0xffff0000u);
+        k[4] = __uint_as_float(r.z << 16); k[5] = __uint_as_float(r.z & 0xffff0000u);
+        k[6] = __uint_as_float(r.w << 16); k[7] = __uint_as_float(r.w & 0xffff0000u);
+    }
 }
 
 // Sum of the squares of the eight bf16 values of a packed row piece: four dot-product instructions, each
 // adding two exact bf16 x bf16 products to an fp32 accumulator.
-__device__ __forceinline__ float sumsq8(const u32x4 &r)
+template <int KF> __device__ __forceinline__ float sumsq8(const u32x4 &r)
 {
     float acc = 0.f;
-    asm("v_dot2c_f32_bf16 %0, %1, %1\n\t"
-        "v_dot2c_f32_bf16 %0, %2, %2\n\t"
-        "v_dot2c_f32_bf16 %0, %3, %3\n\t"
-        "v_dot2c_f32_bf16 %0, %4, %4"
-        : "+v"(acc)
-        : "v"(r.x), "v"(r.y), "v"(r.z), "v"(r.w));
+    if constexpr (KF == kKeyF16)
+        asm("v_dot2c_f32_f16 %0, %1, %1\n\t"
+            "v_dot2c_f32_f16 %0, %2, %2\n\t"
+            "v_dot2c_f32_f16 %0, %3, %3\n\t"
+            "v_dot2c_f32_f16 %0, %4, %4"
+            : "+v"(acc)
+            : "v"(r.x), "v"(r.y), "v"(r.z), "v"(r.w));
+    else
+        asm("v_dot2c_f32_bf16 %0, %1, %1\n\t"
+            "v_dot2c_f32_bf16 %0, %2, %2\n\t"
+            "v_dot2c_f32_bf16 %0, %3, %3\n\t"
+            "v_dot2c_f32_bf16 %0, %4, %4"
+            : "+v"(acc)
+            : "v"(r.x), "v"(r.y), "v"(r.z), "v"(r.w));
     return acc;
 }
 
 // The same for a value that compiler-generated DPP instructions read next: the compiler does not see the
 // write inside the assembly, so the two wait states a DPP read needs after it are spent here.
-__device__ __forceinline__ float sumsq8_for_dpp(const u32x4 &r)
+template <int KF> __device__ __forceinline__ float sumsq8_for_dpp(const u32x4 &r)
 {
     float acc = 0.f;
-    asm("v_dot2c_f32_bf16 %0, %1, %1\n\t"
-        "v_dot2c_f32_bf16 %0, %2, %2\n\t"
-        "v_dot2c_f32_bf16 %0, %3, %3\n\t"
-        "v_dot2c_f32_bf16 %0, %4, %4\n\t"
-        "s_nop 1"
-        : "+v"(acc)
-        : "v"(r.x), "v"(r.y), "v"(r.z), "v"(r.w));
+    if constexpr (KF == kKeyF16)
+        asm("v_dot2c_f32_f16 %0, %1, %1\n\t"
+            "v_dot2c_f32_f16 %0, %2, %2\n\t"
+            "v_dot2c_f32_f16 %0, %3, %3\n\t"
+            "v_dot2c_f32_f16 %0, %4, %4\n\t"
+            "s_nop 1"
+            : "+v"(acc)
+            : "v"(r.x), "v"(r.y), "v"(r.z), "v"(r.w));
+    else
+        asm("v_dot2c_f32_bf16 %0, %1, %1\n\t"
+            "v_dot2c_f32_bf16 %0, %2, %2\n\t"
+            "v_dot2c_f32_bf16 %0, %3, %3\n\t"
+            "v_dot2c_f32_bf16 %0, %4, %4\n\t"
+            "s_nop 1"
+            : "+v"(acc)
+            : "v"(r.x), "v"(r.y), "v"(r.z), "v"(r.w));
     return acc;
 }
 
@@ -410,7 +445,7 @@ __device__ __forceinline__ bool add_unit_up(const float *bsum_unit, int unblk, f
 }
 
 // NW wavefronts = chunks per block.  grid: one workgroup per (layer*head, block), 1-D.
-template <int D, int NW, bool FUSED, int ES>
+template <int D, int NW, bool FUSED, int KF>
 __global__ __launch_bounds__(64 * NW, 3)
 void scan_kernel(const uint8_t *__restrict__ keys, RowMap km, PromptTab tab, ScanPlan plan, float *__restrict__ a_raw,
                  float *__restrict__ bsum, float *__restrict__ ssum, uint32_t *__restrict__ sync, int LH,
@@ -481,7 +516,7 @@ void scan_kernel(const uint8_t *__restrict__ keys, RowMap km, PromptTab tab, Sca
     // ---- first touch: the chunk and this wave's share of the halo ----
     // Rows are addressed relative to the prompt's first row; rows outside the prompt read as zeros, rows of
     // the prompt that lie outside this block get weight 0 below.
-    constexpr int kRowBytes = D * ES;
+    constexpr int ES = key_bytes<KF>(), kRowBytes = D * ES;
     const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<uint8_t *>(keys) + km.unit(layer, head, p, tab) * ES, 0, N * kRowBytes, 0x00020000);
     const int lane_off = t0 * kRowBytes + c * (8 * ES);
@@ -497,7 +532,7 @@ void scan_kernel(const uint8_t *__restrict__ keys, RowMap km, PromptTab tab, Sca
     {
         float ss[TPT];
 #pragma unroll
-        for (int j = 0; j < TPT; ++j) ss[j] = sumsq8(raw[j]);
+        for (int j = 0; j < TPT; ++j) ss[j] = sumsq8<KF>(raw[j]);
         const float ss_m = transpose_reduce<LPR>(ss);
         rn_m = (blk_lo + 64 * w + lane < blk_hi) ? inv_norm(ss_m) : 0.f;
         kn_m = ss_m < 1e-24f ? sqrtf(ss_m) * 1e12f : 1.f;             // ||k_hat|| of this lane's own token
@@ -514,7 +549,7 @@ void scan_kernel(const uint8_t *__restrict__ keys, RowMap km, PromptTab tab, Sca
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             float k[8];
-            unpack8(raw[4 * s + i], k);
+            unpack8<KF>(raw[4 * s + i], k);
 #pragma unroll
             for (int e = 0; e < 8; ++e) T[e] = fmaf(rr[i], k[e], T[e]);
         }
@@ -593,12 +628,12 @@ void scan_kernel(const uint8_t *__restrict__ keys, RowMap km, PromptTab tab, Sca
     for (int e = 0; e < 8; ++e) T[e] = 0.f;
 #pragma unroll
     for (int jj = 0; jj < HT; ++jj) {
-        const float ssh = row_sum<LPR>(sumsq8_for_dpp(hraw[jj]));
+        const float ssh = row_sum<LPR>(sumsq8_for_dpp<KF>(hraw[jj]));
         const int q = HT * w + jj;
         const bool ok = q < TPT && blk_lo - 64 + g * TPT + q >= 0;
         const float r = ok ? inv_norm(ssh) : 0.f;
         float k[8];
-        unpack8(hraw[jj], k);
+        unpack8<KF>(hraw[jj], k);
 #pragma unroll
         for (int e = 0; e < 8; ++e) T[e] = fmaf(r, k[e], T[e]);
         if (c == jj && q < TPT) lds_rn[0][g * TPT + q] = r;
@@ -661,8 +696,8 @@ void scan_kernel(const uint8_t *__restrict__ keys, RowMap km, PromptTab tab, Sca
             for (int i = 0; i < 4; ++i) {
                 float kp[8], k[8];
                 const u32x4 pl = leaving[i * 64];
-                unpack8(pl, kp);
-                unpack8(raw[4 * s + i], k);
+                unpack8<KF>(pl, kp);
+                unpack8<KF>(raw[4 * s + i], k);
                 float wd = 0.f, wn = 0.f, bd = 0.f;
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
@@ -736,7 +771,7 @@ void scan_kernel(const uint8_t *__restrict__ keys, RowMap km, PromptTab tab, Sca
 #pragma unroll
         for (int j = 0; j < TPT; ++j) {
             float k[8];
-            unpack8(raw[j], k);
+            unpack8<KF>(raw[j], k);
             float accs = 0.f;
 #pragma unroll
             for (int e = 0; e < 8; ++e) accs = fmaf(k[e], S[e], accs);
@@ -1151,14 +1186,14 @@ __global__ __launch_bounds__(64 * NW, 2) void deferred_stable_mfma_kernel(const 
 // a_s of the blocks whose workgroups did not wait for their unit's sum.  One workgroup per listed block at a
 // time, one wave per chunk, same lane layout, same instruction sequences for the norm, the dot and the
 // cosine as scan_kernel, so the values are the ones scan_kernel would have stored.
-template <int D, int NW, int ES>
+template <int D, int NW, int KF>
 __global__ __launch_bounds__(64 * NW) void deferred_stable_kernel(const uint8_t *__restrict__ keys, RowMap km,
                                                                   PromptTab tab,
                                                                   const float *__restrict__ ssum,
                                                                   const uint32_t *__restrict__ sync,
                                                                   float *__restrict__ a_raw)
 {
-    constexpr int LPR = D / 8, TPT = LPR, kRowBytes = D * ES;
+    constexpr int LPR = D / 8, TPT = LPR, ES = key_bytes<KF>(), kRowBytes = D * ES;
     const int nblk = tab.blk_off[tab.n];
     const uint32_t count = sync[kDeferCountWord];
     const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -1177,7 +1212,7 @@ __global__ __launch_bounds__(64 * NW) void deferred_stable_kernel(const uint8_t 
         for (int j = 0; j < TPT; ++j) raw[j] = row_load<ES>(rsrc, lane_off + j * kRowBytes);
         float ss[TPT];
 #pragma unroll
-        for (int j = 0; j < TPT; ++j) ss[j] = sumsq8(raw[j]);
+        for (int j = 0; j < TPT; ++j) ss[j] = sumsq8<KF>(raw[j]);
         const float ss_m = transpose_reduce<LPR>(ss);
         const int tok = blk_lo + 64 * w + lane;
         const float rn_m = tok < blk_hi ? inv_norm(ss_m) : 0.f;
@@ -1192,7 +1227,7 @@ __global__ __launch_bounds__(64 * NW) void deferred_stable_kernel(const uint8_t 
 #pragma unroll
         for (int j = 0; j < TPT; ++j) {
             float k[8];
-            unpack8(raw[j], k);
+            unpack8<KF>(raw[j], k);
             float acc = 0.f;
 #pragma unroll
             for (int e = 0; e < 8; ++e) acc = fmaf(k[e], S[e], acc);
@@ -1248,11 +1283,11 @@ __global__ __launch_bounds__(D) void ssum_kernel(const float *__restrict__ bsum,
 }
 
 // Stable anomaly a_s by a second touch of the keys.  grid (ceil(T/256), L*H), 4 waves of 64 tokens.
-template <int D, int ES>
+template <int D, int KF>
 __global__ __launch_bounds__(256) void stable_kernel(const uint8_t *__restrict__ keys, RowMap km, PromptTab tab,
                                                      const float *__restrict__ ssum, float *__restrict__ a_raw)
 {
-    constexpr int LPR = D / 8, TPT = LPR;
+    constexpr int LPR = D / 8, TPT = LPR, ES = key_bytes<KF>();
     const int lh = blockIdx.y;
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
     const int g = lane / LPR, c = lane % LPR;
@@ -1272,7 +1307,7 @@ __global__ __launch_bounds__(256) void stable_kernel(const uint8_t *__restrict__
         }
         float sv[8], k[8];
         load8(ssum + ((int64_t)lh * tab.n + p) * D + c * 8, sv);
-        unpack8(raw, k);
+        unpack8<KF>(raw, k);
         float ss = 0.f, sd = 0.f, sq = 0.f;
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
@@ -1292,7 +1327,7 @@ __global__ __launch_bounds__(256) void stable_kernel(const uint8_t *__restrict__
     }
 }
 
-template <int D, int NW, bool FUSED, int ES, bool MFMA = false>
+template <int D, int NW, bool FUSED, int KF, bool MFMA = false>
 void launch_scan(const uint8_t *keys, const RowMap &km, int LH, const PromptTab &tab, float *a_raw, float *bsum, float *ssum,
                  uint32_t *sync, int poll_limit, uint32_t spin_limit, hipStream_t st)
 {
@@ -1315,17 +1350,17 @@ void launch_scan(const uint8_t *keys, const RowMap &km, int LH, const PromptTab 
         scan_mfma_kernel<D, NW><<<groups, 64 * NW, 0, st>>>(keys, km, tab, plan, a_raw, bsum, ssum, sync, LH, rows,
                                                             poll_limit, spin_limit);
     else
-        scan_kernel<D, NW, FUSED, ES><<<groups, 64 * NW, 0, st>>>(keys, km, tab, plan, a_raw, bsum, ssum, sync, LH, rows,
+        scan_kernel<D, NW, FUSED, KF><<<groups, 64 * NW, 0, st>>>(keys, km, tab, plan, a_raw, bsum, ssum, sync, LH, rows,
                                                                   poll_limit, spin_limit);
 }
 
-template <int D, int NW, bool FUSED, int ES> int resident_workgroups()
+template <int D, int NW, bool FUSED, int KF> int resident_workgroups()
 {
     static int cached = -1;                                          // per instantiation; benign if raced
     if (cached < 0) {
         int per_cu = 0, dev = 0;
         hipDeviceProp_t prop;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, scan_kernel<D, NW, FUSED, ES>, 64 * NW, 0) != hipSuccess ||
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, scan_kernel<D, NW, FUSED, KF>, 64 * NW, 0) != hipSuccess ||
             hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess)
             return 0;
         cached = per_cu * prop.multiProcessorCount;
@@ -1348,7 +1383,7 @@ template <int D, int NW> int resident_workgroups_mfma()
     return cached;
 }
 
-template <int D, int NW, int ES>
+template <int D, int NW, int KF>
 hipError_t run_nw(const uint8_t *keys, const RowMap &km, int LH, const PromptTab &tab, float *a_raw, float *bsum, float *ssum,
                   void *sync_area, int mode, bool mfma, const Prof &prof, hipStream_t st)
 {
@@ -1361,15 +1396,15 @@ hipError_t run_nw(const uint8_t *keys, const RowMap &km, int LH, const PromptTab
     const int64_t items = (int64_t)LH * (tab.blk_off[tab.n] + tab.n);
     const bool allow_fused = mode != kScanTwoPass, no_unit_sums = mode == kScanRepairAll;
     const bool defer_all = mode == kScanDeferAll || no_unit_sums;
-    const bool fused = allow_fused && items < (1ll << 28) && max_unit_blocks <= resident_workgroups<D, NW, true, ES>();
-    if (ES == 2 && mfma && fused && max_unit_blocks <= resident_workgroups_mfma<D, NW>()) {
+    const bool fused = allow_fused && items < (1ll << 28) && max_unit_blocks <= resident_workgroups<D, NW, true, KF>();
+    if (KF == kKeyBF16 && mfma && fused && max_unit_blocks <= resident_workgroups_mfma<D, NW>()) {
         // the matrix-core formulation of the fused pass (same protocol, its own kernel for the deferred blocks)
         const size_t nb = (size_t)LH * tab.blk_off[tab.n] * D / 4, ns = (size_t)LH * tab.n * D / 4;
         const size_t n16 = kSyncWords / 4 + nb + ns;
         prepare_kernel<<<(unsigned)min((n16 + 255) / 256, (size_t)2048), 256, 0, st>>>(
             (uint4 *)sync_area, kSyncWords / 4, (uint4 *)bsum, nb, (uint4 *)ssum, ns);
         prof.begin(NKV_KERNEL_SCAN, st);
-        launch_scan<D, NW, true, 2, true>(keys, km, LH, tab, a_raw, bsum, ssum, (uint32_t *)sync_area,
+        launch_scan<D, NW, true, kKeyBF16, true>(keys, km, LH, tab, a_raw, bsum, ssum, (uint32_t *)sync_area,
                                           defer_all ? -1 : kPollLimit, no_unit_sums ? 0u : kSpinLimit, st);
         prof.end(NKV_KERNEL_SCAN, st);
         unit_sum_repair_kernel<D, NW><<<LH * tab.n, 64 * NW, 0, st>>>(bsum, tab, ssum);
@@ -1382,33 +1417,33 @@ hipError_t run_nw(const uint8_t *keys, const RowMap &km, int LH, const PromptTab
         prepare_kernel<<<(unsigned)min((n16 + 255) / 256, (size_t)2048), 256, 0, st>>>(
             (uint4 *)sync_area, kSyncWords / 4, (uint4 *)bsum, nb, (uint4 *)ssum, ns);
         prof.begin(NKV_KERNEL_SCAN, st);
-        launch_scan<D, NW, true, ES>(keys, km, LH, tab, a_raw, bsum, ssum, (uint32_t *)sync_area,
+        launch_scan<D, NW, true, KF>(keys, km, LH, tab, a_raw, bsum, ssum, (uint32_t *)sync_area,
                                  defer_all ? -1 : kPollLimit, no_unit_sums ? 0u : kSpinLimit, st);
         prof.end(NKV_KERNEL_SCAN, st);
         unit_sum_repair_kernel<D, NW><<<LH * tab.n, 64 * NW, 0, st>>>(bsum, tab, ssum);
-        deferred_stable_kernel<D, NW, ES><<<defer_all ? 4096 : 256, 64 * NW, 0, st>>>(keys, km, tab, ssum,
+        deferred_stable_kernel<D, NW, KF><<<defer_all ? 4096 : 256, 64 * NW, 0, st>>>(keys, km, tab, ssum,
                                                                                   (const uint32_t *)sync_area, a_raw);
     } else {
         prof.begin(NKV_KERNEL_SCAN, st);
-        launch_scan<D, NW, false, ES>(keys, km, LH, tab, a_raw, bsum, ssum, nullptr, 0, 0u, st);
+        launch_scan<D, NW, false, KF>(keys, km, LH, tab, a_raw, bsum, ssum, nullptr, 0, 0u, st);
         prof.end(NKV_KERNEL_SCAN, st);
         ssum_kernel<D><<<dim3(tab.n, LH), D, 0, st>>>(bsum, tab, ssum);
-        stable_kernel<D, ES><<<dim3((tab.T + 255) / 256, LH), 256, 0, st>>>(keys, km, tab, ssum, a_raw);
+        stable_kernel<D, KF><<<dim3((tab.T + 255) / 256, LH), 256, 0, st>>>(keys, km, tab, ssum, a_raw);
     }
     return hipGetLastError();
 }
 
-template <int D, int ES>
+template <int D, int KF>
 hipError_t run(const uint8_t *keys, const RowMap &km, int LH, const PromptTab &tab, float *a_raw, float *bsum, float *ssum,
                void *sync_area, int mode, bool mfma, const Prof &prof, hipStream_t st)
 {
     int bmax = 0;
     for (int p = 0; p < tab.n; ++p) bmax = max(bmax, tab.b[p]);
     switch ((bmax + 63) / 64) {
-    case 1: return run_nw<D, 1, ES>(keys, km, LH, tab, a_raw, bsum, ssum, sync_area, mode, mfma, prof, st);
-    case 2: return run_nw<D, 2, ES>(keys, km, LH, tab, a_raw, bsum, ssum, sync_area, mode, mfma, prof, st);
-    case 3: return run_nw<D, 3, ES>(keys, km, LH, tab, a_raw, bsum, ssum, sync_area, mode, mfma, prof, st);
-    default: return run_nw<D, 4, ES>(keys, km, LH, tab, a_raw, bsum, ssum, sync_area, mode, mfma, prof, st);
+    case 1: return run_nw<D, 1, KF>(keys, km, LH, tab, a_raw, bsum, ssum, sync_area, mode, mfma, prof, st);
+    case 2: return run_nw<D, 2, KF>(keys, km, LH, tab, a_raw, bsum, ssum, sync_area, mode, mfma, prof, st);
+    case 3: return run_nw<D, 3, KF>(keys, km, LH, tab, a_raw, bsum, ssum, sync_area, mode, mfma, prof, st);
+    default: return run_nw<D, 4, KF>(keys, km, LH, tab, a_raw, bsum, ssum, sync_area, mode, mfma, prof, st);
     }
 }
 
@@ -1416,7 +1451,7 @@ hipError_t run(const uint8_t *keys, const RowMap &km, int LH, const PromptTab &t
 
 bool fast_score_supported(int dtype, int d, int window, const PromptTab &tab)
 {
-    if ((dtype != NKV_DTYPE_BF16 && dtype != NKV_DTYPE_F8_E4M3) || (d != 64 && d != 128) || window != 64) return false;
+    if ((dtype != NKV_DTYPE_BF16 && dtype != NKV_DTYPE_F8_E4M3 && dtype != NKV_DTYPE_F16) || (d != 64 && d != 128) || window != 64) return false;
     for (int p = 0; p < tab.n; ++p)
         if (tab.b[p] > 64 * kMaxChunks) return false;
     return true;
@@ -1433,11 +1468,15 @@ hipError_t launch_score_fast(const void *keys, const RowMap &km, int dtype, int 
 {
     const uint8_t *k = (const uint8_t *)keys;
     if (dtype == NKV_DTYPE_F8_E4M3) {
-        if (d == 128) return run<128, 1>(k, km, LH, tab, a_raw, bsum, ssum, sync_area, mode, false, prof, st);
-        return run<64, 1>(k, km, LH, tab, a_raw, bsum, ssum, sync_area, mode, false, prof, st);
+        if (d == 128) return run<128, kKeyF8>(k, km, LH, tab, a_raw, bsum, ssum, sync_area, mode, false, prof, st);
+        return run<64, kKeyF8>(k, km, LH, tab, a_raw, bsum, ssum, sync_area, mode, false, prof, st);
     }
-    if (d == 128) return run<128, 2>(k, km, LH, tab, a_raw, bsum, ssum, sync_area, mode, mfma, prof, st);
-    return run<64, 2>(k, km, LH, tab, a_raw, bsum, ssum, sync_area, mode, mfma, prof, st);
+    if (dtype == NKV_DTYPE_F16) {
+        if (d == 128) return run<128, kKeyF16>(k, km, LH, tab, a_raw, bsum, ssum, sync_area, mode, false, prof, st);
+        return run<64, kKeyF16>(k, km, LH, tab, a_raw, bsum, ssum, sync_area, mode, false, prof, st);
+    }
+    if (d == 128) return run<128, kKeyBF16>(k, km, LH, tab, a_raw, bsum, ssum, sync_area, mode, mfma, prof, st);
+    return run<64, kKeyBF16>(k, km, LH, tab, a_raw, bsum, ssum, sync_area, mode, mfma, prof, st);
 }
 
 }  // namespace nkv

@@ -263,9 +263,11 @@ def test_parameter_variants(over):
     compare_end_to_end(w, K, V, 0.6, params=params, label=str(over))
 
 
-def test_generic_and_streaming_kernels_agree_with_oracle():
-    """The shape-generic scoring kernels, forced by flag, meet the same bar on a streaming-eligible shape."""
-    w = nkv_inputs.small_workload("generic", 2, 2, 128, [2000, 321])
+@pytest.mark.parametrize("dtype", ["bf16", "fp16"])
+def test_generic_and_streaming_kernels_agree_with_oracle(dtype):
+    """The shape-generic scoring kernels, forced by flag, and every route of the streaming kernels meet the same
+    bar on a streaming-eligible shape, for 16-bit keys of either format."""
+    w = nkv_inputs.small_workload("generic", 2, 2, 128, [2000, 321], dtype=dtype)
     K, V = _kv(w)
     compare_end_to_end(w, K, V, 0.5, params=nkv.params_default(flags=nkv.FLAG_GENERIC_KERNELS), label="generic")
     compare_end_to_end(w, K, V, 0.5, params=nkv.params_default(flags=nkv.FLAG_TWO_PASS_STABLE), label="two-pass")
