@@ -66,7 +66,8 @@ def bench_decode(args):
     q = nkv_inputs.make_queries(w, Hq, K)
     del K, V
     rows, P = int(pk.shape[0]), len(w.prompt_lens)
-    shape = nkv.Shape(w.L, w.H, w.d, w.d_v, nkv.DTYPE_F32 if w.dtype == "fp32" else nkv.DTYPE_BF16, w.cu_seqlens)
+    dtype = {"fp32": nkv.DTYPE_F32, "bf16": nkv.DTYPE_BF16, "fp16": nkv.DTYPE_F16, "fp8": nkv.DTYPE_F8_E4M3}[w.dtype]
+    shape = nkv.Shape(w.L, w.H, w.d, w.d_v, dtype, w.cu_seqlens)
     params = nkv.params_default()
     scale = 1.0 / float(np.sqrt(w.d))
     ws = torch.empty(max(nkv.decode_workspace_bytes(shape, Hq, rows), 256), dtype=torch.uint8, device=dev)

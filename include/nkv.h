@@ -230,7 +230,7 @@ int nkv_select_compact(const void *keys, const void *values, const float *scores
  * packed_v hold; head_off entries are clamped to it.  A unit without rows gives out = 0,
  * lse = -inf.  shape->key_strides / value_strides are not used (the packed cache is dense).
  * fp32 arithmetic: exact bf16 products accumulated in fp32, base-2 exponentials of the hardware.
- * Scratch: nkv_decode_workspace_bytes (0 for shapes outside bf16, d = dv in {64,128}, G <= 8,
+ * Scratch: nkv_decode_workspace_bytes (0 for shapes outside bf16 / fp16, d = dv in {64,128}, G <= 8,
  * which take a slower kernel).  NKV_DTYPE_F8_E4M3 caches are refused (NKV_EUNSUPPORTED): attention
  * over them needs the cache's scale factors, which this library never sees.  Asynchronous on hip_stream.
  */

@@ -12,11 +12,11 @@
 //   decode_chunk_kernel   : per chunk, running-maximum softmax in base 2: (m, l, o[0..D)) per query head
 //   decode_combine_kernel : per (unit, query head) merges the chunks' partial results
 // Lane layout in decode_chunk_kernel as in the scoring kernel: a row is spread over D/8 lanes (16 bytes each),
-// one wave load fetches 64/(D/8) rows; <q, k> uses the packed-bf16 dot instruction on the stored bits (exact
+// one wave load fetches 64/(D/8) rows; <q, k> uses the packed 16-bit dot instruction on the stored bits (exact
 // products, fp32 accumulation) and a DPP sum over the lanes of a row; every group of D/8 lanes keeps its own
 // running (m, l, o) for the rows it sees, rescaled once per batch of four rows, and the groups and waves are
 // merged through LDS at the end of the chunk.
-// Anything outside bf16 with d = dv in {64, 128} and G <= 8 goes to decode_generic_kernel (one workgroup per
+// Anything outside bf16 / fp16 with d = dv in {64, 128} and G <= 8 goes to decode_generic_kernel (one workgroup per
 // unit and query head, no scratch).
 #include "nkv_device.h"
 
@@ -45,25 +45,46 @@ template <int LPR> __device__ __forceinline__ float group_sum(float v)
 
 // <a, b> over the eight bf16 pairs of two packed 16-byte pieces.  The compiler does not see the register
 // write inside the assembly, so the wait states a DPP read of the result needs are spent here.
-__device__ __forceinline__ float dot8_for_dpp(const u32x4 &a, const u32x4 &b)
+// F16: the sixteen-bit values are fp16 instead of bf16 (the only two places that know).
+template <bool F16> __device__ __forceinline__ float dot8_for_dpp(const u32x4 &a, const u32x4 &b)
 {
     float acc = 0.f;
-    asm("v_dot2c_f32_bf16 %0, %1, %5\n\t"
-        "v_dot2c_f32_bf16 %0, %2, %6\n\t"
-        "v_dot2c_f32_bf16 %0, %3, %7\n\t"
-        "v_dot2c_f32_bf16 %0, %4, %8\n\t"
-        "s_nop 1"
-        : "+v"(acc)
-        : "v"(a.x), "v"(a.y), "v"(a.z), "v"(a.w), "v"(b.x), "v"(b.y), "v"(b.z), "v"(b.w));
+    if constexpr (F16)
+        asm("v_dot2c_f32_f16 %0, %1, %5\n\t"
+            "v_dot2c_f32_f16 %0, %2, %6\n\t"
+            "v_dot2c_f32_f16 %0, %3, %7\n\t"
+            "v_dot2c_f32_f16 %0, %4, %8\n\t"
+            "s_nop 1"
+            : "+v"(acc)
+            : "v"(a.x), "v"(a.y), "v"(a.z), "v"(a.w), "v"(b.x), "v"(b.y), "v"(b.z), "v"(b.w));
+    else
+        asm("v_dot2c_f32_bf16 %0, %1, %5\n\t"
+            "v_dot2c_f32_bf16 %0, %2, %6\n\t"
+            "v_dot2c_f32_bf16 %0, %3, %7\n\t"
+            "v_dot2c_f32_bf16 %0, %4, %8\n\t"
+            "s_nop 1"
+            : "+v"(acc)
+            : "v"(a.x), "v"(a.y), "v"(a.z), "v"(a.w), "v"(b.x), "v"(b.y), "v"(b.z), "v"(b.w));
     return acc;
 }
 
-__device__ __forceinline__ void unpack8(const u32x4 &r, float k[8])
+template <bool F16> __device__ __forceinline__ void unpack8(const u32x4 &r, float k[8])
 {
-    k[0] = __uint_as_float(r.x << 16); k[1] = __uint_as_float(r.x & 0xffff0000u);
-    k[2] = __uint_as_float(r.y << 16); k[3] = __uint_as_float(r.y & 0xffff0000u);
-    k[4] = __uint_as_float(r.z << 16); k[5] = __uint_as_float(r.z & 0xffff0000u);
-    k[6] = __uint_as_float(r.w << 16); k[7] = __uint_as_float(r.w & 0xffff0000u);
+    if constexpr (F16) {
+        using f16x2 = _Float16 __attribute__((ext_vector_type(2)));
+        const uint32_t w[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const f16x2 v = __builtin_bit_cast(f16x2, w[i]);
+            k[2 * i] = (float)v.x;
+            k[2 * i + 1] = (float)v.y;
+        }
+    } else {
+        k[0] = __uint_as_float(r.x << 16); k[1] = __uint_as_float(r.x & 0xffff0000u);
+        k[2] = __uint_as_float(r.y << 16); k[3] = __uint_as_float(r.y & 0xffff0000u);
+        k[4] = __uint_as_float(r.z << 16); k[5] = __uint_as_float(r.z & 0xffff0000u);
+        k[6] = __uint_as_float(r.w << 16); k[7] = __uint_as_float(r.w & 0xffff0000u);
+    }
 }
 
 __device__ __forceinline__ int64_t clamp_row(int64_t r, int64_t rows) { return r < 0 ? 0 : (r > rows ? rows : r); }
@@ -106,7 +127,7 @@ __global__ __launch_bounds__(1024) void decode_plan_kernel(const int64_t *__rest
 }
 
 // part: per chunk and query head D + 2 floats: running maximum (base-2 logits), sum of weights, weighted values.
-template <int D, int G>
+template <int D, int G, bool F16>
 __global__ __launch_bounds__(kDecThreads) void decode_chunk_kernel(const uint16_t *__restrict__ q,
                                                                    const uint16_t *__restrict__ pk,
                                                                    const uint16_t *__restrict__ pv,
@@ -168,7 +189,7 @@ __global__ __launch_bounds__(kDecThreads) void decode_chunk_kernel(const uint16_
                 const bool valid = row0 + i * RPW < n;
 #pragma unroll
                 for (int g = 0; g < G; ++g) {
-                    const float d = group_sum<LPR>(dot8_for_dpp(kr[i], qv[g]));
+                    const float d = group_sum<LPR>(dot8_for_dpp<F16>(kr[i], qv[g]));
                     s[i][g] = valid ? d * scale_log2 : kNone;
                 }
             }
@@ -192,7 +213,7 @@ __global__ __launch_bounds__(kDecThreads) void decode_chunk_kernel(const uint16_
 #pragma unroll
             for (int i = 0; i < U; ++i) {
                 float v[8];
-                unpack8(vr[i], v);
+                unpack8<F16>(vr[i], v);
 #pragma unroll
                 for (int g = 0; g < G; ++g)
 #pragma unroll
@@ -334,7 +355,7 @@ __global__ __launch_bounds__(kDecThreads) void decode_generic_kernel(const T *__
 
 int64_t max_chunks(int64_t n_units, int64_t rows) { return rows / kChunk + n_units; }
 
-template <int D>
+template <int D, bool F16>
 hipError_t run_fast(const uint16_t *q, const uint16_t *pk, const uint16_t *pv, const int64_t *head_off, int n_units,
                     int G, int64_t rows, float scale_log2, float *out, float *lse, void *ws, const Prof &prof,
                     hipStream_t st)
@@ -346,7 +367,7 @@ hipError_t run_fast(const uint16_t *q, const uint16_t *pk, const uint16_t *pv, c
     prof.begin(NKV_KERNEL_DECODE, st);
 #define NKV_DEC(GG)                                                                                             \
     case GG:                                                                                                   \
-        decode_chunk_kernel<D, GG><<<groups, kDecThreads, 0, st>>>(q, pk, pv, head_off, chunk_off, n_units, rows, \
+        decode_chunk_kernel<D, GG, F16><<<groups, kDecThreads, 0, st>>>(q, pk, pv, head_off, chunk_off, n_units, rows, \
                                                                    scale_log2, part);                         \
         break
     switch (G) {
@@ -383,7 +404,7 @@ hipError_t run_generic(const T *q, const T *pk, const T *pv, const int64_t *head
 
 bool decode_fast_supported(int dtype, int d, int dv, int G)
 {
-    return dtype == NKV_DTYPE_BF16 && d == dv && (d == 64 || d == 128) && G >= 1 && G <= 8;
+    return (dtype == NKV_DTYPE_BF16 || dtype == NKV_DTYPE_F16) && d == dv && (d == 64 || d == 128) && G >= 1 && G <= 8;
 }
 
 size_t decode_ws_bytes(int dtype, int d, int dv, int G, int64_t n_units, int64_t rows)
@@ -398,11 +419,13 @@ hipError_t launch_decode(const void *q, const void *pk, const void *pv, const in
 {
     const float scale_log2 = (float)(scale * 1.4426950408889634);
     if (decode_fast_supported(dtype, d, dv, G)) {
-        if (d == 128)
-            return run_fast<128>((const uint16_t *)q, (const uint16_t *)pk, (const uint16_t *)pv, head_off, n_units, G,
-                                 rows, scale_log2, out, lse, ws, prof, st);
-        return run_fast<64>((const uint16_t *)q, (const uint16_t *)pk, (const uint16_t *)pv, head_off, n_units, G, rows,
-                            scale_log2, out, lse, ws, prof, st);
+        const uint16_t *q16 = (const uint16_t *)q, *k16 = (const uint16_t *)pk, *v16 = (const uint16_t *)pv;
+        if (dtype == NKV_DTYPE_F16) {
+            if (d == 128) return run_fast<128, true>(q16, k16, v16, head_off, n_units, G, rows, scale_log2, out, lse, ws, prof, st);
+            return run_fast<64, true>(q16, k16, v16, head_off, n_units, G, rows, scale_log2, out, lse, ws, prof, st);
+        }
+        if (d == 128) return run_fast<128, false>(q16, k16, v16, head_off, n_units, G, rows, scale_log2, out, lse, ws, prof, st);
+        return run_fast<64, false>(q16, k16, v16, head_off, n_units, G, rows, scale_log2, out, lse, ws, prof, st);
     }
     if (dtype == NKV_DTYPE_F32)
         return run_generic<float>((const float *)q, (const float *)pk, (const float *)pv, head_off, n_units, G, d, dv,

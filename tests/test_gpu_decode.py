@@ -64,7 +64,9 @@ CASES = [
     ("generic_dv_differs", 1, 2, 128, 64, [500], "bf16", 4, 0.5),
     ("generic_d40", 1, 2, 40, 24, [300], "fp32", 2, 0.5),
     ("generic_g12", 1, 1, 64, 0, [300], "bf16", 12, 0.5),
-    ("generic_fp16", 1, 2, 128, 0, [600], "fp16", 4, 0.5),
+    ("fp16_g4", 1, 2, 128, 0, [1500, 300], "fp16", 8, 0.5),
+    ("fp16_d64_g2", 1, 2, 64, 0, [600], "fp16", 4, 0.5),
+    ("generic_fp16_dv", 1, 2, 128, 64, [600], "fp16", 4, 0.5),
 ]
 
 
