@@ -177,47 +177,42 @@ template <int LPR> struct StreamReduce {
 
 using u32x4 = unsigned int __attribute__((ext_vector_type(4)));
 
-// 16-byte load through a buffer descriptor: the address is one 32-bit byte offset per lane plus an
-// immediate, and an offset outside [0, num_records) (tokens before the prompt or past its end) reads zeros.
-// ES = bytes per key element.  2: bf16, the lane's 16 bytes are the packed row piece the kernels work on.
-// 1: 8-bit E4M3 (4 exponent bits, bias 7, no infinities); the lane's 8 bytes are converted on the way in to
-// that same packed bf16 form -- exactly, 4 significant bits and the exponent range both fit -- so nothing
-// after the load knows the difference.  Conversion: the hardware's pairwise E4M3 -> fp32, then the upper
-// halves of two floats put side by side by a byte permute.
 using u32x2 = unsigned int __attribute__((ext_vector_type(2)));
 using f32x2 = float __attribute__((ext_vector_type(2)));
 
-__device__ __forceinline__ uint32_t f8x2_to_bf16x2(uint32_t four, bool upper)
-{
-    const f32x2 f = upper ? __builtin_amdgcn_cvt_pk_f32_fp8((int)four, true)
-                          : __builtin_amdgcn_cvt_pk_f32_fp8((int)four, false);
-    return __builtin_amdgcn_perm(__float_as_uint(f.y), __float_as_uint(f.x), 0x07060302u);
-}
-
-__device__ __forceinline__ u32x4 f8x8_to_bf16x8(const u32x2 &v)
-{
-    const u32x4 r = {f8x2_to_bf16x2(v.x, false), f8x2_to_bf16x2(v.x, true), f8x2_to_bf16x2(v.y, false),
-                     f8x2_to_bf16x2(v.y, true)};
-    return r;
-}
-
-template <int ES> __device__ __forceinline__ u32x4 row_load(__amdgpu_buffer_rsrc_t rsrc, int byte_off)
-{
-    if constexpr (ES == 2) return __builtin_amdgcn_raw_buffer_load_b128(rsrc, byte_off, 0, 0);
-    else return f8x8_to_bf16x8(__builtin_amdgcn_raw_buffer_load_b64(rsrc, byte_off, 0, 0));
-}
-
-// Key formats of the streaming kernels (template parameter KF).  A packed row piece holds eight 16-bit values:
-// bf16 (also what 8-bit keys are converted to on the way in) or fp16; only unpacking and the sum of squares
-// know which.
+// Key formats of the streaming kernels (template parameter KF).  A lane's packed row piece holds eight values of
+// a row: 16 bytes of bf16 or fp16, or 8 bytes of 8-bit E4M3 (4 exponent bits, bias 7, no infinities).  It stays
+// packed in registers and in LDS from the first touch to the last; only the load, unpacking and the sum of
+// squares know the format.
 constexpr int kKeyF8 = 1, kKeyBF16 = 2, kKeyF16 = 3;
 template <int KF> constexpr int key_bytes() { return KF == kKeyF8 ? 1 : 2; }
+template <int KF> struct PieceOf { using type = u32x4; };
+template <> struct PieceOf<kKeyF8> { using type = u32x2; };
+template <int KF> using Piece = typename PieceOf<KF>::type;
+
+// Load of a row piece through a buffer descriptor: the address is one 32-bit byte offset per lane plus an
+// immediate, and an offset outside [0, num_records) (tokens before the prompt or past its end) reads zeros.
+template <int KF> __device__ __forceinline__ Piece<KF> row_load(__amdgpu_buffer_rsrc_t rsrc, int byte_off)
+{
+    if constexpr (KF == kKeyF8) return __builtin_amdgcn_raw_buffer_load_b64(rsrc, byte_off, 0, 0);
+    else return __builtin_amdgcn_raw_buffer_load_b128(rsrc, byte_off, 0, 0);
+}
 
 using f16x2 = _Float16 __attribute__((ext_vector_type(2)));
 
-template <int KF> __device__ __forceinline__ void unpack8(const u32x4 &r, float k[8])
+// 8-bit keys: the hardware's pairwise E4M3 -> fp32 conversion, exact.
+__device__ __forceinline__ void unpack8_f8(const u32x2 &r, float k[8])
 {
-    if constexpr (KF == kKeyF16) {
+    const f32x2 a = __builtin_amdgcn_cvt_pk_f32_fp8((int)r.x, false), b = __builtin_amdgcn_cvt_pk_f32_fp8((int)r.x, true);
+    const f32x2 c = __builtin_amdgcn_cvt_pk_f32_fp8((int)r.y, false), d = __builtin_amdgcn_cvt_pk_f32_fp8((int)r.y, true);
+    k[0] = a.x; k[1] = a.y; k[2] = b.x; k[3] = b.y; k[4] = c.x; k[5] = c.y; k[6] = d.x; k[7] = d.y;
+}
+
+template <int KF> __device__ __forceinline__ void unpack8(const Piece<KF> &r, float k[8])
+{
+    if constexpr (KF == kKeyF8) {
+        unpack8_f8(r, k);
+    } else if constexpr (KF == kKeyF16) {
         const uint32_t w[4] = {r.x, r.y, r.z, r.w};
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
@@ -235,10 +230,15 @@ template <int KF> __device__ __forceinline__ void unpack8(const u32x4 &r, float 
 
 // Sum of the squares of the eight bf16 values of a packed row piece: four dot-product instructions, each
 // adding two exact bf16 x bf16 products to an fp32 accumulator.
-template <int KF> __device__ __forceinline__ float sumsq8(const u32x4 &r)
+template <int KF> __device__ __forceinline__ float sumsq8(const Piece<KF> &r)
 {
     float acc = 0.f;
-    if constexpr (KF == kKeyF16)
+    if constexpr (KF == kKeyF8) {
+        float k[8];
+        unpack8_f8(r, k);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc = fmaf(k[e], k[e], acc);
+    } else if constexpr (KF == kKeyF16)
         asm("v_dot2c_f32_f16 %0, %1, %1\n\t"
             "v_dot2c_f32_f16 %0, %2, %2\n\t"
             "v_dot2c_f32_f16 %0, %3, %3\n\t"
@@ -257,10 +257,15 @@ template <int KF> __device__ __forceinline__ float sumsq8(const u32x4 &r)
 
 // The same for a value that compiler-generated DPP instructions read next: the compiler does not see the
 // write inside the assembly, so the two wait states a DPP read needs after it are spent here.
-template <int KF> __device__ __forceinline__ float sumsq8_for_dpp(const u32x4 &r)
+template <int KF> __device__ __forceinline__ float sumsq8_for_dpp(const Piece<KF> &r)
 {
     float acc = 0.f;
-    if constexpr (KF == kKeyF16)
+    if constexpr (KF == kKeyF8) {                                     // plain code: the compiler sees the hazard itself
+        float k[8];
+        unpack8_f8(r, k);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc = fmaf(k[e], k[e], acc);
+    } else if constexpr (KF == kKeyF16)
         asm("v_dot2c_f32_f16 %0, %1, %1\n\t"
             "v_dot2c_f32_f16 %0, %2, %2\n\t"
             "v_dot2c_f32_f16 %0, %3, %3\n\t"
@@ -282,6 +287,7 @@ template <int KF> __device__ __forceinline__ float sumsq8_for_dpp(const u32x4 &r
 // Makes the compiler forget what it knows about a packed row, so that the unpacked floats of one phase
 // are not kept alive (8 registers per token) for the next phase; costs no instruction.
 __device__ __forceinline__ void forget(u32x4 &r) { asm volatile("" : "+v"(r.x), "+v"(r.y), "+v"(r.z), "+v"(r.w)); }
+__device__ __forceinline__ void forget(u32x2 &r) { asm volatile("" : "+v"(r.x), "+v"(r.y)); }
 
 __device__ __forceinline__ void load8(const float *src, float v[8])
 {
@@ -456,10 +462,10 @@ void scan_kernel(const uint8_t *__restrict__ keys, RowMap km, PromptTab tab, Sca
     constexpr int NST = TPT / 4;                                      // 4-row steps per lane
     __shared__ float lds_rn[NW + 1][64];                              // [0]: halo chunk, [1 + w]: chunk w
     __shared__ float lds_T[NW][SG][D];                                // partial sums of the chunks, later of the halo chunk
-    __shared__ u32x4 lds_h[TPT][64];                                  // halo rows, by the window row that needs them
+    __shared__ Piece<KF> lds_h[TPT][64];                                  // halo rows, by the window row that needs them
     __shared__ float lds_C[NW][D];                                    // chunk totals
     __shared__ float lds_S[D];                                        // the unit's sum, once complete
-    __shared__ u32x4 lds_x[2][NW > 1 ? NW - 1 : 1][4][64];            // rows on their way to the next wave
+    __shared__ Piece<KF> lds_x[2][NW > 1 ? NW - 1 : 1][4][64];            // rows on their way to the next wave
     __shared__ int s_have;
 
     const int nblk = plan.nblk;
@@ -520,12 +526,12 @@ void scan_kernel(const uint8_t *__restrict__ keys, RowMap km, PromptTab tab, Sca
     const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<uint8_t *>(keys) + km.unit(layer, head, p, tab) * ES, 0, N * kRowBytes, 0x00020000);
     const int lane_off = t0 * kRowBytes + c * (8 * ES);
-    u32x4 raw[TPT], hraw[HT];
+    Piece<KF> raw[TPT], hraw[HT];
 #pragma unroll
-    for (int j = 0; j < TPT; ++j) raw[j] = row_load<ES>(rsrc, lane_off + j * kRowBytes);
+    for (int j = 0; j < TPT; ++j) raw[j] = row_load<KF>(rsrc, lane_off + j * kRowBytes);
     const int halo_off = (blk_lo - 64 + g * TPT + HT * w) * kRowBytes + c * (8 * ES);
 #pragma unroll
-    for (int jj = 0; jj < HT; ++jj) hraw[jj] = row_load<ES>(rsrc, halo_off + jj * kRowBytes);
+    for (int jj = 0; jj < HT; ++jj) hraw[jj] = row_load<KF>(rsrc, halo_off + jj * kRowBytes);
 
     // ---- norms: one token per lane (lane (g, c) reports token g*TPT + c = lane of the chunk) ----
     float rn_m, kn_m;
@@ -533,6 +539,10 @@ void scan_kernel(const uint8_t *__restrict__ keys, RowMap km, PromptTab tab, Sca
         float ss[TPT];
 #pragma unroll
         for (int j = 0; j < TPT; ++j) ss[j] = sumsq8<KF>(raw[j]);
+        if constexpr (KF == kKeyF8) {                                 // or the unpacked rows stay alive for the next phase
+#pragma unroll
+            for (int j = 0; j < TPT; ++j) forget(raw[j]);
+        }
         const float ss_m = transpose_reduce<LPR>(ss);
         rn_m = (blk_lo + 64 * w + lane < blk_hi) ? inv_norm(ss_m) : 0.f;
         kn_m = ss_m < 1e-24f ? sqrtf(ss_m) * 1e12f : 1.f;             // ||k_hat|| of this lane's own token
@@ -682,7 +692,7 @@ void scan_kernel(const uint8_t *__restrict__ keys, RowMap km, PromptTab tab, Sca
                     for (int i = 0; i < 4; ++i) lds_x[(s + 1) & 1][w][i][lane] = raw[4 * s + 4 + i];
                 }
             }
-            const u32x4 *leaving = w == 0 ? &lds_h[4 * s][lane] : &lds_x[s & 1][NW > 1 ? w - 1 : 0][0][lane];
+            const Piece<KF> *leaving = w == 0 ? &lds_h[4 * s][lane] : &lds_x[s & 1][NW > 1 ? w - 1 : 0][0][lane];
             const float4 r4 = *reinterpret_cast<const float4 *>(&lds_rn[1 + w][g * TPT + 4 * s]);
             const float4 q4 = *reinterpret_cast<const float4 *>(&lds_rn[w][g * TPT + 4 * s]);
             const float rr[4] = {r4.x, r4.y, r4.z, r4.w};
@@ -695,7 +705,7 @@ void scan_kernel(const uint8_t *__restrict__ keys, RowMap km, PromptTab tab, Sca
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 float kp[8], k[8];
-                const u32x4 pl = leaving[i * 64];
+                const Piece<KF> pl = leaving[i * 64];
                 unpack8<KF>(pl, kp);
                 unpack8<KF>(raw[4 * s + i], k);
                 float wd = 0.f, wn = 0.f, bd = 0.f;
@@ -943,7 +953,7 @@ void scan_mfma_kernel(const uint8_t *__restrict__ keys, RowMap km, PromptTab tab
     for (int set = 3; set >= 0; --set) {                              // the chunk first: the block total waits for it
         const int off = (t0 - 64 + 32 * set + r) * kRowBytes + 16 * h;
 #pragma unroll
-        for (int kk = 0; kk < KS; ++kk) X[set][kk] = row_load<2>(rsrc, off + 32 * kk);
+        for (int kk = 0; kk < KS; ++kk) X[set][kk] = row_load<kKeyBF16>(rsrc, off + 32 * kk);
     }
 
     // ---- norms ----
@@ -1151,7 +1161,7 @@ __global__ __launch_bounds__(64 * NW, 2) void deferred_stable_mfma_kernel(const 
         for (int set = 0; set < 2; ++set) {
             const int off = (t0 + 32 * set + r) * kRowBytes + 16 * h;
 #pragma unroll
-            for (int kk = 0; kk < KS; ++kk) X[set][kk] = row_load<2>(rsrc, off + 32 * kk);
+            for (int kk = 0; kk < KS; ++kk) X[set][kk] = row_load<kKeyBF16>(rsrc, off + 32 * kk);
         }
 #pragma unroll
         for (int set = 0; set < 2; ++set) {
@@ -1207,9 +1217,9 @@ __global__ __launch_bounds__(64 * NW) void deferred_stable_kernel(const uint8_t 
         const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
             const_cast<uint8_t *>(keys) + km.unit(lh, p, tab) * ES, 0, N * kRowBytes, 0x00020000);
         const int lane_off = (blk_lo + 64 * w + g * TPT) * kRowBytes + c * (8 * ES);
-        u32x4 raw[TPT];
+        Piece<KF> raw[TPT];
 #pragma unroll
-        for (int j = 0; j < TPT; ++j) raw[j] = row_load<ES>(rsrc, lane_off + j * kRowBytes);
+        for (int j = 0; j < TPT; ++j) raw[j] = row_load<KF>(rsrc, lane_off + j * kRowBytes);
         float ss[TPT];
 #pragma unroll
         for (int j = 0; j < TPT; ++j) ss[j] = sumsq8<KF>(raw[j]);
@@ -1300,11 +1310,8 @@ __global__ __launch_bounds__(256) void stable_kernel(const uint8_t *__restrict__
         const bool ok = tg < tab.T;
         const int p = prompt_of_token(tab, ok ? tg : tab.T - 1);
         const uint8_t *row = keys + (km.unit(lh, p, tab) + (int64_t)(tg - tab.tok_off[p]) * D) * ES;
-        u32x4 raw = {0u, 0u, 0u, 0u};
-        if (ok) {
-            if constexpr (ES == 2) raw = reinterpret_cast<const u32x4 *>(row)[c];
-            else raw = f8x8_to_bf16x8(reinterpret_cast<const u32x2 *>(row)[c]);
-        }
+        Piece<KF> raw = {};
+        if (ok) raw = reinterpret_cast<const Piece<KF> *>(row)[c];
         float sv[8], k[8];
         load8(ssum + ((int64_t)lh * tab.n + p) * D + c * 8, sv);
         unpack8<KF>(raw, k);
