@@ -143,6 +143,9 @@ def main():
     ap.add_argument("--mfma", action="store_true", help="matrix-core formulation of the fused scan")
     ap.add_argument("--per-layer", action="store_true",
                     help="a step is L passes with L = 1, one per layer's K/V slice, as a prefill loop would call it")
+    ap.add_argument("--layer-tensors", action="store_true",
+                    help="every layer's K and V in an allocation of its own (a framework's list of per-layer caches), "
+                         "still one call over all layers")
     ap.add_argument("--mode", choices=("pass", "decode"), default="pass",
                     help="pass: the compression pass (default); decode: attention over the compressed cache")
     ap.add_argument("--q-heads", type=int, default=0, help="decode mode: query heads (default 4 per KV head)")
@@ -172,6 +175,13 @@ def main():
     if args.per_layer:
         shape1 = nkv.Shape(1, w.H, w.d, w.d_v, shape.dtype, w.cu_seqlens)
         calls = [(nkv.Compressor(shape1, r_list, params), K[l], V[l]) for l in range(w.L)]
+    elif args.layer_tensors:
+        args.no_cpu_baseline = True                      # the oracle leg reads the one-tensor layout
+        Kl, Vl = [K[l].clone() for l in range(w.L)], [V[l].clone() for l in range(w.L)]
+        del K, V
+        shape = nkv.Shape(w.L, w.H, w.d, w.d_v, dtype, w.cu_seqlens, key_layers=Kl, value_layers=Vl)
+        K, V = Kl[0], Vl[0]
+        calls = [(nkv.Compressor(shape, r_list, params), K, V)]
     else:
         calls = [(nkv.Compressor(shape, r_list, params), K, V)]
     stream = torch.cuda.current_stream()

@@ -92,6 +92,7 @@ enum {
 #define NKV_MAX_PROMPTS 64        /* prompts per call                                   */
 #define NKV_MAX_HEAD_DIM 1024     /* d and dv; both must be multiples of 8              */
 #define NKV_MAX_HEADS 32          /* KV heads per layer                                 */
+#define NKV_MAX_LAYER_TENSORS 128 /* layers when every layer has a tensor of its own    */
 #define NKV_PIN 3.0e38f           /* score written to pinned sink positions             */
 
 /*
@@ -144,6 +145,14 @@ typedef struct nkv_shape {
     /* overlap (NKV_EINVAL).  scores, a_raw and the packed outputs keep their dense layouts.               */
     const int64_t *key_strides;
     const int64_t *value_strides;
+    /* Every layer in a tensor of its own (a framework's list of per-layer caches).  NULL, or HOST, L      */
+    /* entries: where layer l's tensor starts, in elements from the keys / values pointer handed to the   */
+    /* call, i.e. (address of layer l's tensor - address of layer 0's tensor) / element size, entry 0 = 0; */
+    /* negative entries are fine.  The layer entry of the strides is then not used (strides NULL: every    */
+    /* layer tensor is a dense [H][T][d]).  Entries must be multiples of 16 bytes, L <=                    */
+    /* NKV_MAX_LAYER_TENSORS, and layers must not overlap (NKV_EINVAL).                                    */
+    const int64_t *key_layer_offsets;
+    const int64_t *value_layer_offsets;
 } nkv_shape;
 
 /* Fills *p with the paper's constants.  Returns NKV_EINVAL if p is NULL. */

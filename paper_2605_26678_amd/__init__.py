@@ -46,7 +46,8 @@ class nkv_params(C.Structure):
 class nkv_shape(C.Structure):
     _fields_ = [("L", C.c_int32), ("H", C.c_int32), ("d", C.c_int32), ("dv", C.c_int32), ("dtype", C.c_int32),
                 ("n_prompts", C.c_int32), ("cu_seqlens", C.POINTER(C.c_int32)),
-                ("key_strides", C.POINTER(C.c_int64)), ("value_strides", C.POINTER(C.c_int64))]
+                ("key_strides", C.POINTER(C.c_int64)), ("value_strides", C.POINTER(C.c_int64)),
+                ("key_layer_offsets", C.POINTER(C.c_int64)), ("value_layer_offsets", C.POINTER(C.c_int64))]
 
 
 class NkvError(RuntimeError):
@@ -136,15 +137,29 @@ def m_p(N: int, top_frac: float = 0.10) -> int:
 class Shape:
     """Host-side description of keys[L][H][T][d] / values[L][H][T][dv] holding one or more prompts.
     ``key_strides`` / ``value_strides``: None for the dense layout, else (layer, head, prompt) strides in
-    elements as ``nkv_shape`` in nkv.h defines them."""
+    elements as ``nkv_shape`` in nkv.h defines them.  ``key_layers`` / ``value_layers``: None, or one tensor
+    (or device address) per layer when every layer has a tensor of its own; the calls are then handed layer
+    0's tensor."""
 
     def __init__(self, L: int, H: int, d: int, dv: int, dtype: int, cu_seqlens: Sequence[int],
-                 key_strides: Optional[Sequence[int]] = None, value_strides: Optional[Sequence[int]] = None):
+                 key_strides: Optional[Sequence[int]] = None, value_strides: Optional[Sequence[int]] = None,
+                 key_layers: Optional[Sequence] = None, value_layers: Optional[Sequence] = None):
         self.cu = (C.c_int32 * len(cu_seqlens))(*[int(x) for x in cu_seqlens])
         self.ks = None if key_strides is None else (C.c_int64 * 3)(*[int(x) for x in key_strides])
         self.vs = None if value_strides is None else (C.c_int64 * 3)(*[int(x) for x in value_strides])
+        esize = {DTYPE_F32: 4, DTYPE_BF16: 2, DTYPE_F16: 2, DTYPE_F8_E4M3: 1}.get(int(dtype), 1)
+
+        def offsets(layers):
+            if layers is None:
+                return None
+            addr = [int(t) if isinstance(t, int) else int(t.data_ptr()) for t in layers]
+            if len(addr) != int(L) or any((a - addr[0]) % esize for a in addr):
+                raise ValueError("one tensor per layer, element-aligned")
+            return (C.c_int64 * len(addr))(*[(a - addr[0]) // esize for a in addr])
+
+        self.klo, self.vlo = offsets(key_layers), offsets(value_layers)
         self.c = nkv_shape(int(L), int(H), int(d), int(dv), int(dtype), len(cu_seqlens) - 1, self.cu,
-                           self.ks, self.vs)
+                           self.ks, self.vs, self.klo, self.vlo)
         self.L, self.H, self.d, self.dv, self.dtype = int(L), int(H), int(d), int(dv), int(dtype)
         self.n_prompts = len(cu_seqlens) - 1
         self.T = int(cu_seqlens[-1])

@@ -28,19 +28,34 @@ int check_params(const nkv_params *p)
 
 int esize_of(int dtype) { return dtype == NKV_DTYPE_F32 ? 4 : dtype == NKV_DTYPE_F8_E4M3 ? 1 : 2; }
 
-// strides: NULL (dense [L][H][T][row]) or {layer, head, prompt} in elements
-int fill_map(const nkv_shape *s, const int64_t *strides, int row, RowMap *m)
+// strides: NULL (dense [L][H][T][row]) or {layer, head, prompt} in elements; layer_offsets: NULL or L entries
+int fill_map(const nkv_shape *s, const int64_t *strides, const int64_t *layer_offsets, int row, RowMap *m)
 {
     const int64_t T = s->cu_seqlens[s->n_prompts];
     m->H = s->H;
     m->d = row;
+    m->per_layer = layer_offsets != nullptr;
+    const int epv = 16 / esize_of(s->dtype);
+    if (layer_offsets) {
+        if (s->L > NKV_MAX_LAYER_TENSORS || layer_offsets[0] != 0) return NKV_EINVAL;
+        for (int l = 0; l < s->L; ++l) {
+            if (layer_offsets[l] % epv) return NKV_EINVAL;
+            m->layer_off[l] = layer_offsets[l];
+        }
+    }
     if (!strides) {
         m->layer = (int64_t)s->H * T * row;
         m->head = T * row;
         m->prompt = 0;
+        if (layer_offsets)                                            // dense layer tensors must not overlap
+            for (int i = 0; i < s->L; ++i)
+                for (int j = i + 1; j < s->L; ++j) {
+                    const int64_t gap = layer_offsets[i] > layer_offsets[j] ? layer_offsets[i] - layer_offsets[j]
+                                                                          : layer_offsets[j] - layer_offsets[i];
+                    if (gap < m->layer) return NKV_EINVAL;
+                }
         return NKV_OK;
     }
-    const int epv = 16 / esize_of(s->dtype);
     for (int i = 0; i < 3; ++i)
         if (strides[i] < 0 || strides[i] % epv) return NKV_EINVAL;
     // a slab must hold its unit: the longest prompt for per-prompt slabs, all prompts for concatenated ones
@@ -49,7 +64,8 @@ int fill_map(const nkv_shape *s, const int64_t *strides, int row, RowMap *m)
         nmax = nmax > s->cu_seqlens[p + 1] - s->cu_seqlens[p] ? nmax : s->cu_seqlens[p + 1] - s->cu_seqlens[p];
     // No two units may overlap: with the axes of extent > 1 ordered by stride, each stride must cover the
     // whole extent of the axis below it (the innermost one a unit's rows).
-    int64_t st[3] = {strides[0], strides[1], strides[2]}, ext[3] = {s->L, s->H, strides[2] ? s->n_prompts : 1};
+    int64_t st[3] = {strides[0], strides[1], strides[2]};
+    int64_t ext[3] = {layer_offsets ? 1 : s->L, s->H, strides[2] ? s->n_prompts : 1};
     for (int i = 0; i < 3; ++i)
         for (int j = i + 1; j < 3; ++j)
             if (st[j] < st[i]) {
@@ -63,6 +79,13 @@ int fill_map(const nkv_shape *s, const int64_t *strides, int row, RowMap *m)
         if (st[i] < cover) return NKV_EINVAL;
         cover = st[i] * ext[i];
     }
+    if (layer_offsets)                                                // cover = what one layer's tensor spans
+        for (int i = 0; i < s->L; ++i)
+            for (int j = i + 1; j < s->L; ++j) {
+                const int64_t gap = layer_offsets[i] > layer_offsets[j] ? layer_offsets[i] - layer_offsets[j]
+                                                                      : layer_offsets[j] - layer_offsets[i];
+                if (gap < cover) return NKV_EINVAL;
+            }
     m->layer = strides[0];
     m->head = strides[1];
     m->prompt = strides[2];
@@ -85,9 +108,9 @@ int check_shape(const nkv_shape *s)
     if ((int64_t)s->H * T >= (1ll << 31)) return NKV_ESHAPE;          // per-layer counters are 32-bit
     if ((int64_t)s->L * s->H * T >= (1ll << 40)) return NKV_ESHAPE;
     RowMap m;
-    int rc = fill_map(s, s->key_strides, s->d, &m);
+    int rc = fill_map(s, s->key_strides, s->key_layer_offsets, s->d, &m);
     if (rc) return rc;
-    return fill_map(s, s->value_strides, s->dv, &m);
+    return fill_map(s, s->value_strides, s->value_layer_offsets, s->dv, &m);
 }
 
 void fill_tab(const nkv_shape *s, const nkv_params *p, PromptTab *tab)
@@ -143,7 +166,7 @@ int run_raw(const void *keys, const nkv_shape *s, const nkv_params *p, const Pro
     const int LH = s->L * s->H;
     const Prof prof{p->prof_start, p->prof_stop};
     RowMap km;
-    const int rc = fill_map(s, s->key_strides, s->d, &km);
+    const int rc = fill_map(s, s->key_strides, s->key_layer_offsets, s->d, &km);
     if (rc) return rc;
     hipError_t e;
     if (!(p->flags & NKV_FLAG_GENERIC_KERNELS) && fast_score_supported(s->dtype, s->d, p->window, tab))
@@ -342,9 +365,9 @@ int nkv_select_compact(const void *keys, const void *values, const float *scores
     PromptTab tab;
     fill_tab(shape, params, &tab);
     RowMap km, vm;
-    rc = fill_map(shape, shape->key_strides, shape->d, &km);
+    rc = fill_map(shape, shape->key_strides, shape->key_layer_offsets, shape->d, &km);
     if (rc) return rc;
-    rc = fill_map(shape, shape->value_strides, shape->dv, &vm);
+    rc = fill_map(shape, shape->value_strides, shape->value_layer_offsets, shape->dv, &vm);
     if (rc) return rc;
     if (ws != nullptr) {
         rc = check_ws(ws, ws_bytes, select_wide_ws_bytes(shape->L, shape->H, tab));

@@ -27,9 +27,12 @@ struct PromptTab {
 struct RowMap {
     int64_t layer, head, prompt;
     int32_t H, d;
+    int32_t per_layer;                   // non-zero: layer l starts at layer_off[l] instead of l * layer
+    int64_t layer_off[NKV_MAX_LAYER_TENSORS];
     __host__ __device__ int64_t unit(int l, int h, int p, const PromptTab &tab) const
     {
-        return l * layer + h * head + (prompt != 0 ? p * prompt : (int64_t)tab.tok_off[p] * d);
+        return (per_layer ? layer_off[l] : l * layer) + h * head +
+               (prompt != 0 ? p * prompt : (int64_t)tab.tok_off[p] * d);
     }
     __host__ __device__ int64_t unit(int lh, int p, const PromptTab &tab) const
     {

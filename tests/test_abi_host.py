@@ -74,6 +74,19 @@ def test_argument_errors_are_reported_before_any_device_work():
     for ks in ((64 * 100 * 2 + 4, 64 * 100, 0), (0, 64 * 99, 0), (0, 64 * 100, 64 * 100), (-8, 64 * 100, 0)):
         bad = nkv.Shape(1, 2, 64, 64, 1, [0, 60, 100], key_strides=ks)
         assert L.nkv_score(fake, C.byref(bad.c), C.byref(p), fake, fake, 1 << 30, 0) == nkv.NKV_EINVAL, ks
+    # one tensor per layer: entry 0 must be 0, entries 16-byte multiples, layers apart, at most 128 of them
+    per = 2 * 100 * 64                                        # elements of one dense layer tensor
+    for off in ((8, per), (0, per + 4), (0, per - 8), (0, -per + 8)):
+        bad = nkv.Shape(2, 2, 64, 64, 1, [0, 60, 100])
+        bad.klo = (C.c_int64 * 2)(*off)
+        bad.c.key_layer_offsets = bad.klo
+        assert L.nkv_score(fake, C.byref(bad.c), C.byref(p), fake, fake, 1 << 30, 0) == nkv.NKV_EINVAL, off
+    many = nkv.Shape(129, 1, 64, 64, 1, [0, 100], key_layers=[4096 + 2 * 6400 * l for l in range(129)])
+    assert L.nkv_score(fake, C.byref(many.c), C.byref(p), fake, fake, 1 << 30, 0) == nkv.NKV_EINVAL
+    fine = nkv.Shape(3, 2, 64, 64, 1, [0, 60, 100], key_layers=[1 << 20, 1 << 16, 1 << 24],
+                     value_layers=[1 << 30, (1 << 30) + 2 * per, (1 << 30) - 2 * per])
+    assert list(fine.klo) == [0, ((1 << 16) - (1 << 20)) // 2, ((1 << 24) - (1 << 20)) // 2]
+    assert nkv.workspace_bytes(fine) > 0
     ok = nkv.Shape(3, 2, 64, 64, 1, [0, 60, 100], key_strides=(64 * 128 * 4, 64 * 128, 64 * 128 * 2),
                    value_strides=(64 * 300, 64 * 100, 0))
     assert nkv.workspace_bytes(ok) > 0

@@ -401,6 +401,34 @@ def test_strided_layouts_give_the_same_bits(flags):
     assert np.array_equal(bits(out.packed_k), bits(ref.packed_k)) and np.array_equal(bits(out.packed_v), bits(ref.packed_v))
 
 
+@pytest.mark.parametrize("flags", [0, nkv.FLAG_TWO_PASS_STABLE, nkv.FLAG_GENERIC_KERNELS, nkv.FLAG_MFMA_SCAN])
+def test_one_tensor_per_layer_gives_the_same_bits(flags):
+    """A framework's list of per-layer cache tensors, each an allocation of its own ([B][H][N_max][d] with one
+    slab per prompt for the keys, dense [H][T][d_v] for the values), allocated in an order that makes some
+    layer offsets negative: one call over all layers gives the dense layout's outputs bit for bit."""
+    w = nkv_inputs.small_workload("layer_list", 5, 2, 128, [900, 17000, 333])
+    K, V = _kv(w)
+    params = nkv.params_default(flags=flags)
+    ref, _ = run_gpu(w, K, V, 0.7, params=params)
+    L, H, d, cu = w.L, w.H, w.d, w.cu_seqlens
+    P, nmax = 3, 17024
+    order = [3, 0, 4, 1, 2]                                  # allocation order != layer order
+    Kl, Vl, pad = [None] * L, [None] * L, []
+    for l in order:
+        Kl[l] = torch.full((P, H, nmax, d), float("nan"), dtype=K.dtype, device=DEV)
+        pad.append(torch.empty(1000 + 64 * l, device=DEV))  # something else in between
+        Vl[l] = V[l].clone()
+        for p in range(P):
+            Kl[l][p, :, :cu[p + 1] - cu[p]] = K[l, :, cu[p]:cu[p + 1]]
+    shape = nkv.Shape(L, H, d, d, nkv.DTYPE_BF16, cu, key_strides=(0, nmax * d, H * nmax * d), key_layers=Kl,
+                      value_layers=Vl)
+    print("layer offsets (elements):", list(shape.klo), list(shape.vlo))
+    out = _run_with_layout(w, Kl[0], Vl[0], 0.7, shape, params)
+    for name in ("scores", "k_per_head", "head_off", "kept_idx"):
+        assert torch.equal(getattr(out, name), getattr(ref, name)), name
+    assert np.array_equal(bits(out.packed_k), bits(ref.packed_k)) and np.array_equal(bits(out.packed_v), bits(ref.packed_v))
+
+
 def test_layer_by_layer_calls_equal_the_batched_call():
     """The pass is independent per layer (Section 2, "independently at each layer"): calling it with L = 1 on
     each layer's slice, as a prefill loop would right after the layer's keys exist, gives the rows of the
