@@ -19,7 +19,9 @@
 //     the top 11 key bits) and layer_budget_kernel (one workgroup per (prompt, layer): the top digit from
 //     the heads' histograms, then two passes over the layer's scores for the 11 middle and 10 low bits,
 //     the last one with one histogram per head, which also yields step C);
-//   * anything else: budget_kernel, one workgroup per (prompt, layer), nine byte-wise passes.
+//   * layers of more than 8 heads: the kernels of nkv_budget_heads.hip, budget_kernel's passes with one
+//     workgroup per head;
+//   * anything else (no scratch given): budget_kernel, one workgroup per (prompt, layer), nine byte-wise passes.
 #include "nkv_blocksel.h"
 
 namespace nkv {
@@ -369,7 +371,7 @@ size_t budget_ws_bytes(int L, int H, const PromptTab &tab)
 {
     const size_t units = (size_t)tab.n * L * H;
     const size_t per_head = units * sizeof(HeadSafe) + units * 2048 * sizeof(uint32_t);
-    const size_t wide = budget_wide_supported(H) ? budget_wide_ws_bytes(L, H, tab) : 0;
+    const size_t wide = budget_wide_supported(H) ? budget_wide_ws_bytes(L, H, tab) : budget_heads_ws_bytes(L, H, tab);
     return per_head > wide ? per_head : wide;
 }
 
@@ -398,6 +400,9 @@ hipError_t launch_budget(const float *scores, int L, int H, const PromptTab &tab
             else head_safe_kernel<32><<<n, kSelThreads, 0, st>>>(scores, L, H, tab, u0, safe, pool_hist);
         });
         layer_budget_kernel<<<(unsigned)(tab.n * L), kThreads, 0, st>>>(scores, L, H, tab, safe, pool_hist, k_per_head);
+    } else if (ws != nullptr && H > kFastHeads && !per_head_route) {
+        const hipError_t e = launch_budget_heads(scores, L, H, tab, k_per_head, ws, st);
+        if (e != hipSuccess) return e;
     } else {
         budget_kernel<<<(unsigned)(tab.n * L), kThreads, 0, st>>>(scores, L, H, tab, nullptr, k_per_head);
     }

@@ -117,6 +117,10 @@ size_t budget_ws_bytes(int L, int H, const PromptTab &tab);
 hipError_t launch_budget(const float *scores, int L, int H, const PromptTab &tab, int32_t *k_per_head, void *ws,
                          bool per_head_route, const Prof &prof, hipStream_t st);
 // slice-wise kernels (nkv_budget_wide.hip)
+// heads-parallel budget kernels for layers of more than 8 heads (nkv_budget_heads.hip)
+size_t budget_heads_ws_bytes(int L, int H, const PromptTab &tab);
+hipError_t launch_budget_heads(const float *scores, int L, int H, const PromptTab &tab, int32_t *k_per_head, void *ws,
+                               hipStream_t st);
 bool budget_wide_supported(int H);
 size_t budget_wide_ws_bytes(int L, int H, const PromptTab &tab);
 hipError_t launch_budget_wide(const float *scores, int L, int H, const PromptTab &tab, int32_t *k_per_head, void *ws,

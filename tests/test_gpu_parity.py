@@ -83,7 +83,9 @@ SWEEP = [
     ("fp8_d128", 1, 2, 128, [2000, 130], "fp8", 0),       # 8-bit E4M3 keys and values
     ("fp8_d64_dv", 2, 3, 64, [900], "fp8", 32),
     ("long_prompt", 1, 2, 64, [40000], "bf16", 0),        # beyond the register-resident per-head kernels
-    ("many_heads", 1, 12, 64, [600, 90], "bf16", 0),      # beyond the 8-head layer budget kernel
+    ("many_heads", 1, 12, 64, [600, 90], "bf16", 0),      # beyond the 8-head layer budget kernels
+    ("heads_32", 2, 32, 64, [1500, 90], "bf16", 0),       # the most heads a layer may have
+    ("heads_16_long", 1, 16, 128, [20000], "bf16", 0),
     ("slice_edges", 1, 2, 128, [8193, 16385, 100, 24576], "bf16", 0),   # one token past a slice, exact slices
     ("slices_d64", 1, 3, 64, [17000], "bf16", 0),
     ("nine_slices", 1, 2, 128, [70000, 9000], "bf16", 0), # 274 blocks in the unit: two rounds of the dies' runs
@@ -163,10 +165,12 @@ def test_constant_keys_ties_resolve_by_index():
     assert torch.all(out.scores[:, :, 4:] == 0)
 
 
-def test_heavy_ties_stage_parity():
-    """Quantised scores (many exact ties, also across heads) fed straight into budget and selection."""
+@pytest.mark.parametrize("H,flags", [(4, 0), (12, 0), (12, nkv.FLAG_BUDGET_PER_HEAD), (32, 0)])
+def test_heavy_ties_stage_parity(H, flags):
+    """Quantised scores (many exact ties, also across heads) fed straight into budget and selection; with more
+    than 8 heads the heads-parallel budget kernels, or (flag) the one-workgroup-per-layer kernel."""
     rng = np.random.default_rng(0)
-    w = nkv_inputs.small_workload("ties", 2, 4, 64, [257, 1500])
+    w = nkv_inputs.small_workload("ties", 2, H, 64, [257, 1500])
     K, V = _kv(w)
     sc = (np.round(rng.random((w.L, w.H, w.T)) * 8) / 8).astype(np.float32)
     sc[:, :, 0:4] = oracle.PIN
@@ -175,7 +179,7 @@ def test_heavy_ties_stage_parity():
     op = oracle.Params()
     for r in (0.3, 0.75, 0.97):
         ref = oracle.compress(K.float().cpu().numpy(), bits(K), bits(V), w.cu_seqlens, [r, r], op, scores=sc)
-        out, _ = run_gpu(w, K, V, r, scores=torch.from_numpy(sc).to(DEV))
+        out, _ = run_gpu(w, K, V, r, params=nkv.params_default(flags=flags), scores=torch.from_numpy(sc).to(DEV))
         assert np.array_equal(out.k_per_head.cpu().numpy(), ref.k_per_head)
         assert np.array_equal(out.kept_idx.cpu().numpy(), ref.kept_idx)
         assert np.array_equal(bits(out.packed_k), ref.packed_k) and np.array_equal(bits(out.packed_v), ref.packed_v)
