@@ -382,10 +382,10 @@ hipError_t launch_budget(const float *scores, int L, int H, const PromptTab &tab
     for (int p = 0; p < tab.n; ++p) nmax = max(nmax, tab.tok_off[p + 1] - tab.tok_off[p]);
     const unsigned units = (unsigned)(tab.n * L * H);
     prof.begin(NKV_KERNEL_BUDGET, st);
-    // Slice-wise kernels where a head has more than one slice (five small launches); below that the two
-    // per-head launches are quicker.
+    // Slice-wise kernels where a head has more than one slice or there are many units (five small launches);
+    // for a few short units the two per-head launches are quicker.
     const bool per_head_ok = ws != nullptr && H <= kFastHeads && nmax <= 32 * kSelThreads;
-    if (ws != nullptr && budget_wide_supported(H) && !(per_head_ok && (per_head_route || nmax <= 8192))) {
+    if (ws != nullptr && budget_wide_supported(H) && !(per_head_ok && (per_head_route || (nmax <= 8192 && units < 256)))) {
         const uint32_t *failed = nullptr;
         hipError_t e = launch_budget_wide(scores, L, H, tab, k_per_head, ws, &failed, st);
         if (e != hipSuccess) return e;

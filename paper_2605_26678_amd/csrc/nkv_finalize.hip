@@ -311,9 +311,10 @@ hipError_t launch_finalize(const float *a_raw, int L, int H, const PromptTab &ta
     for (int p = 0; p < tab.n; ++p) nmax = max(nmax, tab.tok_off[p + 1] - tab.tok_off[p]);
     const unsigned units = (unsigned)(tab.n * L * H);
     prof.begin(NKV_KERNEL_FINALIZE, st);
-    if (wide_ws != nullptr && nmax > 8192 && !per_head_route) {
-        // Slice-wise kernels where a head has more than one slice (any length); below that the per-head kernels
-        // are quicker.
+    if (wide_ws != nullptr && (nmax > 8192 || units >= 256) && !per_head_route) {
+        // Slice-wise kernels where a head has more than one slice (any length) or there are many units (their
+        // 256-thread workgroups pack the chip four times as densely); for a few short units the per-head
+        // kernels are quicker.
         hipError_t e = launch_stats_wide(a_raw, L, H, tab, stats, wide_ws, st);
         if (e != hipSuccess) return e;
         e = launch_route_wide(a_raw, L, H, tab, lc, stats, wide_ws, scores, st);

@@ -315,9 +315,9 @@ hipError_t launch_select_compact(const void *keys, const void *values, const Row
 #define NKV_SELECT_FAST(EPT)                                                                              \
     select_fast_kernel<EPT><<<(unsigned)n, kSelThreads, 0, st>>>(scores, k_per_head, L, H, tab, u0, near_tol, \
                                                                  head_off, row_capacity, kept_idx, near_count)
-    // Slice-wise kernels where a head has more than two slices and the caller gave scratch (at two slices the
-    // six launches cost what they save).
-    if (wide_ws != nullptr && nmax > 16384) {
+    // Slice-wise kernels where a head has more than two slices or there are thousands of units, and the caller
+    // gave scratch (for a few hundred units of up to two slices the six launches cost what they save).
+    if (wide_ws != nullptr && (nmax > 16384 || n_units >= 2048)) {
         const hipError_t e = launch_select_wide(scores, k_per_head, L, H, tab, near_tol, head_off, row_capacity,
                                                 kept_idx, near_count, wide_ws, st);
         if (e != hipSuccess) return e;
