@@ -219,7 +219,8 @@ int nkv_budget(const float *scores, const nkv_shape *shape, const nkv_params *pa
  * of their head's selection threshold (the B_h-th highest score), summed over all
  * units with 0 < B_h < N_p; these are the positions whose fate can change under
  * score perturbations of that size.  `ws` may be NULL (ws_bytes 0): the selection then runs one workgroup per
- * unit; with scratch (nkv_workspace_bytes) prompts of more than 16384 tokens are selected slice-wise.
+ * unit; with scratch (nkv_workspace_bytes) prompts of more than 16384 tokens, and batches of 2048 units and
+ * more, are selected slice-wise (same result, quicker).
  */
 int nkv_select_compact(const void *keys, const void *values, const float *scores,
                        const int32_t *k_per_head, const nkv_shape *shape, const nkv_params *params,
