@@ -1459,8 +1459,11 @@ hipError_t run(const uint8_t *keys, const RowMap &km, int LH, const PromptTab &t
 bool fast_score_supported(int dtype, int d, int window, const PromptTab &tab)
 {
     if ((dtype != NKV_DTYPE_BF16 && dtype != NKV_DTYPE_F8_E4M3 && dtype != NKV_DTYPE_F16) || (d != 64 && d != 128) || window != 64) return false;
-    for (int p = 0; p < tab.n; ++p)
+    for (int p = 0; p < tab.n; ++p) {
         if (tab.b[p] > 64 * kMaxChunks) return false;
+        // a prompt's rows are addressed by 32-bit byte offsets from its first row
+        if ((int64_t)(tab.tok_off[p + 1] - tab.tok_off[p] + 256) * d * 2 >= (1ll << 31)) return false;
+    }
     return true;
 }
 
