@@ -452,7 +452,7 @@ __device__ __forceinline__ bool add_unit_up(const float *bsum_unit, int unblk, f
 
 // NW wavefronts = chunks per block.  grid: one workgroup per (layer*head, block), 1-D.
 template <int D, int NW, bool FUSED, int KF>
-__global__ __launch_bounds__(64 * NW, 3)
+__global__ __launch_bounds__(64 * NW, NW == 1 ? 2 : 3)               // one-wave blocks (b <= 64) need more registers
 void scan_kernel(const uint8_t *__restrict__ keys, RowMap km, PromptTab tab, ScanPlan plan, float *__restrict__ a_raw,
                  float *__restrict__ bsum, float *__restrict__ ssum, uint32_t *__restrict__ sync, int LH,
                  int64_t rows, int poll_limit, uint32_t spin_limit)

@@ -253,6 +253,7 @@ VARIANTS = [
     dict(gate_mode=1), dict(gate_mode=2), dict(surprise_mode=1), dict(beta=0.0),
     dict(prior=(1.0, 0.0, 0.0), beta=0.0, gate_mode=1), dict(n_sink=0), dict(n_sink=9),
     dict(window=16), dict(window=200), dict(block_min=32, block_max=96, block_div=8),
+    dict(block_min=16, block_max=64, block_div=64),      # blocks of one wavefront
     dict(block_min=300, block_max=512), dict(top_frac=0.25, safeguard=0.5), dict(safeguard=1.0),
     dict(kappa=25.0, tau=0.2),
 ]
