@@ -137,6 +137,27 @@ def test_matrix_core_scan(name, route):
     _report(f"mfma {name} route={route}", st)
 
 
+LIMITS = [
+    # the most prompts, head dims, heads and (layer, head) pairs a call accepts
+    ("prompts_64", 1, 2, 64, [61 + 37 * (i % 9) + 500 * (i % 3 == 0) for i in range(64)], "bf16", 0),
+    ("d_1024", 1, 1, 1024, [400], "bf16", 8),
+    ("dv_1024", 1, 1, 64, [700], "bf16", 1024),
+    ("d_1024_fp32", 1, 2, 1024, [300, 40], "fp32", 1024),
+    ("units_65535", 2114, 31, 64, [5], "bf16", 0),        # L * H = 65534
+]
+
+
+@pytest.mark.parametrize("case", LIMITS, ids=[c[0] for c in LIMITS])
+def test_documented_limits(case):
+    name, L, H, d, lens, dtype, dv = case
+    w = nkv_inputs.small_workload(name, L, H, d, lens, dtype=dtype, dv=dv, n_out=0, sinks=False)
+    K, V = _kv(w)
+    layers = None if L <= 4 else [0, 1, L // 2, L - 1]
+    if layers is None:
+        compare_stages(w, K, V, 0.5, label=name)
+    compare_end_to_end(w, K, V, 0.5, layers=layers, label=name)
+
+
 @pytest.mark.parametrize("r", [0.0, 1.0])
 def test_keep_everything_and_keep_nothing(r):
     w = nkv_inputs.small_workload("extremes", 2, 2, 128, [300, 77])
