@@ -452,7 +452,7 @@ __device__ __forceinline__ bool add_unit_up(const float *bsum_unit, int unblk, f
 
 // NW wavefronts = chunks per block.  grid: one workgroup per (layer*head, block), 1-D.
 template <int D, int NW, bool FUSED, int KF>
-__global__ __launch_bounds__(64 * NW, NW == 1 ? 2 : 3)               // one-wave blocks (b <= 64) need more registers
+__global__ __launch_bounds__(64 * NW, NW == 1 ? 2 : (D == 64 ? 4 : 3)) // one-wave blocks (b <= 64) need more registers
 void scan_kernel(const uint8_t *__restrict__ keys, RowMap km, PromptTab tab, ScanPlan plan, float *__restrict__ a_raw,
                  float *__restrict__ bsum, float *__restrict__ ssum, uint32_t *__restrict__ sync, int LH,
                  int64_t rows, int poll_limit, uint32_t spin_limit)
@@ -465,7 +465,10 @@ void scan_kernel(const uint8_t *__restrict__ keys, RowMap km, PromptTab tab, Sca
     __shared__ Piece<KF> lds_h[TPT][64];                                  // halo rows, by the window row that needs them
     __shared__ float lds_C[NW][D];                                    // chunk totals
     __shared__ float lds_S[D];                                        // the unit's sum, once complete
-    __shared__ Piece<KF> lds_x[2][NW > 1 ? NW - 1 : 1][4][64];            // rows on their way to the next wave
+    // Rows on their way to the next wave: two buffers, or one at head dim 64, where a second barrier per step
+    // costs less than the fourth workgroup per compute unit that the smaller LDS footprint admits is worth.
+    constexpr int kXBuf = D == 64 ? 1 : 2;
+    __shared__ Piece<KF> lds_x[kXBuf][NW > 1 ? NW - 1 : 1][4][64];
     __shared__ int s_have;
 
     const int nblk = plan.nblk;
@@ -685,14 +688,22 @@ void scan_kernel(const uint8_t *__restrict__ keys, RowMap km, PromptTab tab, Sca
         // and its reads from the writes two steps later.
 #pragma unroll
         for (int s = 0; s < NST; ++s) {
-            if (NW > 1) {
+            if (NW > 1 && kXBuf == 2) {
                 if (s > 0) __syncthreads();
                 if (s + 1 < NST && w < NW - 1) {
 #pragma unroll
                     for (int i = 0; i < 4; ++i) lds_x[(s + 1) & 1][w][i][lane] = raw[4 * s + 4 + i];
                 }
             }
-            const Piece<KF> *leaving = w == 0 ? &lds_h[4 * s][lane] : &lds_x[s & 1][NW > 1 ? w - 1 : 0][0][lane];
+            if (NW > 1 && kXBuf == 1 && s > 0) {                      // one buffer: reads of step s - 1, then the writes
+                __syncthreads();
+                if (w < NW - 1) {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) lds_x[0][w][i][lane] = raw[4 * s + i];
+                }
+                __syncthreads();
+            }
+            const Piece<KF> *leaving = w == 0 ? &lds_h[4 * s][lane] : &lds_x[s & (kXBuf - 1)][NW > 1 ? w - 1 : 0][0][lane];
             const float4 r4 = *reinterpret_cast<const float4 *>(&lds_rn[1 + w][g * TPT + 4 * s]);
             const float4 q4 = *reinterpret_cast<const float4 *>(&lds_rn[w][g * TPT + 4 * s]);
             const float rr[4] = {r4.x, r4.y, r4.z, r4.w};
