@@ -272,6 +272,7 @@ def main():
             if spent > 30.0:
                 break
         threads = int(os.environ.get("OMP_NUM_THREADS", "0")) or (os.cpu_count() or 1)
+        threads = min(threads, w.H)                      # the oracle's only parallel loop runs over a layer's heads
         cpu = {"value": round(tokens / (spent * w.L / done), 1), "unit": "prompt tokens/s", "cores": threads,
                "kind": "oracle", "seconds": round(spent, 2),
                "sample": f"{done} of {w.L} layers of the same workload (all heads, all prompts), scaled by L/{done}; "
