@@ -881,27 +881,27 @@ __device__ __forceinline__ void split3(float x, uint16_t &hi, uint16_t &mid, uin
     lo = (uint16_t)(__float_as_uint(r2) >> 16);
 }
 
-// <k, anchor> for the 64 tokens of a chunk (token = lane): the anchor's three terms (terms[3][D] bf16 in LDS,
-// written by this wave) are rows 0-2 and 4-6 of the left operand, so that the result registers 0-2 hold them for
+// <k, anchor> for the 64 tokens of a chunk (token = lane): the anchor's three terms (terms[4][D] bf16 in LDS,
+// written by this wave, row 3 zeros) are rows 0-2 and 4-6 of the left operand, so that the result registers 0-2 hold them for
 // columns n in lanes h = 0 (rows 0-2) and h = 1 (rows 4-6) alike; the low half takes the chunk's first 32
 // tokens, the high half the other 32.
 template <int D> __device__ __forceinline__ float anchor_dot(const uint16_t *terms, const u32x4 (&c0)[D / 16],
                                                              const u32x4 (&c1)[D / 16], int r, int h)
 {
     constexpr int KS = D / 16;
-    u32x4 a[KS];
-    const bool has = r < 8 && (r & 3) < 3;
+    const uint16_t *mine = terms + (r < 8 ? (r & 3) : 3) * D + 8 * h;  // row 3 holds zeros
+    f32x16 d0 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f}, d1 = d0;
 #pragma unroll
     for (int kk = 0; kk < KS; ++kk) {
-        const u32x4 zero = {0u, 0u, 0u, 0u};
-        a[kk] = has ? *reinterpret_cast<const u32x4 *>(terms + (r & 3) * D + 16 * kk + 8 * h) : zero;
+        const bf16x8 a = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(mine + 16 * kk));
+        d0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, __builtin_bit_cast(bf16x8, c0[kk]), d0, 0, 0, 0);
+        d1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, __builtin_bit_cast(bf16x8, c1[kk]), d1, 0, 0, 0);
     }
-    const f32x16 d0 = mm_tile<KS>(a, c0), d1 = mm_tile<KS>(a, c1);
     return h ? (d1[0] + d1[1]) + d1[2] : (d0[0] + d0[1]) + d0[2];
 }
 
 template <int D, int NW>
-__global__ __launch_bounds__(64 * NW, 2)
+__global__ __launch_bounds__(64 * NW, 3)
 void scan_mfma_kernel(const uint8_t *__restrict__ keys, RowMap km, PromptTab tab, ScanPlan plan, float *__restrict__ a_raw,
                       float *__restrict__ bsum, float *__restrict__ ssum, uint32_t *__restrict__ sync, int LH, int64_t rows,
                       int poll_limit, uint32_t spin_limit)
@@ -910,7 +910,7 @@ void scan_mfma_kernel(const uint8_t *__restrict__ keys, RowMap km, PromptTab tab
     __shared__ float lds_rn[NW][128];                                 // 1/||k|| of a wave's 128 rows (0: no such token)
     __shared__ float lds_wb[NW][64];                                  // the same for the chunk, 0 outside the block
     __shared__ float lds_C[NW][D];                                    // chunk totals
-    __shared__ __attribute__((aligned(16))) uint16_t lds_terms[NW][3][D];   // an anchor's bf16 terms, per wave
+    __shared__ __attribute__((aligned(16))) uint16_t lds_terms[NW][4][D];   // an anchor's bf16 terms and a row of zeros, per wave
     __shared__ float lds_S[D];
     __shared__ float lds_T[NW * SG * D];                              // scratch of a summing workgroup
     __shared__ int s_have;
@@ -955,28 +955,33 @@ void scan_mfma_kernel(const uint8_t *__restrict__ keys, RowMap km, PromptTab tab
     const int r = lane & 31, h = lane >> 5;
     const int t0 = blk_lo + 64 * w;                                   // first token of this wave's chunk
 
-    // ---- first touch: rows t0 - 64 .. t0 + 63 as four sets of 32; rows outside the prompt read as zeros ----
+    // ---- first touch: the chunk (two sets of 32 rows) and the 32 rows in front of it; rows outside the prompt
+    // read as zeros.  Three sets are held at a time: the columns are taken in two halves, the second half of
+    // the chunk makes room for the first half of the halo in between and is read again (from L2) at the end.
     constexpr int kRowBytes = D * 2;
     const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<uint8_t *>(keys) + km.unit(layer, head, p, tab) * 2, 0, N * kRowBytes, 0x00020000);
-    u32x4 X[4][KS];
+    u32x4 XA[KS], XB[KS], XH[KS];                                     // C0; C1, later H0, later C1 again; H1
+    const int lane_off = (t0 + r) * kRowBytes + 16 * h;               // row r of set C0
 #pragma unroll
-    for (int set = 3; set >= 0; --set) {                              // the chunk first: the block total waits for it
-        const int off = (t0 - 64 + 32 * set + r) * kRowBytes + 16 * h;
+    for (int kk = 0; kk < KS; ++kk) XA[kk] = row_load<kKeyBF16>(rsrc, lane_off + 32 * kk);
 #pragma unroll
-        for (int kk = 0; kk < KS; ++kk) X[set][kk] = row_load<kKeyBF16>(rsrc, off + 32 * kk);
-    }
+    for (int kk = 0; kk < KS; ++kk) XB[kk] = row_load<kKeyBF16>(rsrc, lane_off + 32 * kRowBytes + 32 * kk);
+#pragma unroll
+    for (int kk = 0; kk < KS; ++kk) XH[kk] = row_load<kKeyBF16>(rsrc, lane_off - 32 * kRowBytes + 32 * kk);
 
-    // ---- norms ----
-    float rn[4], gd[4], ssv[4];                                       // 1/||k||, ||k^||^2, ||k||^2 of row r of each set
-#pragma unroll
-    for (int set = 0; set < 4; ++set) {
-        ssv[set] = row_sumsq<KS>(X[set]);
-        const int tk = t0 - 64 + 32 * set + r;
-        rn[set] = (tk >= 0 && tk < N) ? inv_norm(ssv[set]) : 0.f;
-        gd[set] = rn[set] * rn[set] * ssv[set];
-        if (h == 0) lds_rn[w][32 * set + r] = rn[set];
-    }
+    // ---- norms of the chunk ----
+    float rn[4], gd[4], ssv[4];                                       // 1/||k||, ||k^||^2, ||k||^2 of row r of H0, H1, C0, C1
+#define NKV_NORM_SET(set, x)                                          \
+    do {                                                              \
+        ssv[set] = row_sumsq<KS>(x);                                  \
+        const int tk = t0 - 64 + 32 * (set) + r;                      \
+        rn[set] = (tk >= 0 && tk < N) ? inv_norm(ssv[set]) : 0.f;     \
+        gd[set] = rn[set] * rn[set] * ssv[set];                       \
+        if (h == 0) lds_rn[w][32 * (set) + r] = rn[set];              \
+    } while (0)
+    NKV_NORM_SET(2, XA);
+    NKV_NORM_SET(3, XB);
     if (h == 0) {
         lds_wb[w][r] = t0 + r < blk_hi ? rn[2] : 0.f;
         lds_wb[w][32 + r] = t0 + 32 + r < blk_hi ? rn[3] : 0.f;
@@ -1005,10 +1010,11 @@ void scan_mfma_kernel(const uint8_t *__restrict__ keys, RowMap km, PromptTab tab
 #pragma unroll
             for (int set = 2; set < 4; ++set) {
                 f32x16 c = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-                c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, X[set][2 * q]),
+                c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, set == 2 ? XA[2 * q] : XB[2 * q]),
                                                             __builtin_bit_cast(bf16x8, ident[0]), c, 0, 0, 0);
-                c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, X[set][2 * q + 1]),
-                                                            __builtin_bit_cast(bf16x8, ident[1]), c, 0, 0, 0);
+                c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                    __builtin_bit_cast(bf16x8, set == 2 ? XA[2 * q + 1] : XB[2 * q + 1]), __builtin_bit_cast(bf16x8, ident[1]),
+                    c, 0, 0, 0);
                 part += col_sum<0>(c, &lds_wb[w][32 * (set - 2)], r, h);
             }
             part += __shfl_xor(part, 32, 64);
@@ -1040,6 +1046,7 @@ void scan_mfma_kernel(const uint8_t *__restrict__ keys, RowMap km, PromptTab tab
             lds_terms[w][0][dim] = t0b;
             lds_terms[w][1][dim] = t1b;
             lds_terms[w][2][dim] = t2b;
+            lds_terms[w][3][dim] = 0;                                 // the row the other lanes of the left operand read
         }
         bsq = wave_sum(bsq);
         if (w == blk % NW) {                                          // one wave stores the block total
@@ -1057,29 +1064,49 @@ void scan_mfma_kernel(const uint8_t *__restrict__ keys, RowMap km, PromptTab tab
     __builtin_amdgcn_wave_barrier();
     const int tok = t0 + lane;
     {
-        const float bd = anchor_dot<D>(&lds_terms[w][0][0], X[2], X[3], r, h);
+        const float bd = anchor_dot<D>(&lds_terms[w][0][0], XA, XB, r, h);
         if (tok < blk_hi) a_raw[rows + row0 + tok] = neg_cos(rn_m * bd, kn_m, bsq);
     }
 
-    // ---- current window: bands of the Gram matrix ----
+    // ---- current window: bands of the Gram matrix, the chunk's second half of columns first ----
     {
         const float *wH0 = &lds_rn[w][0], *wH1 = &lds_rn[w][32], *wC0 = &lds_rn[w][64], *wC1 = &lds_rn[w][96];
-        // backward band of the chunk's tokens
-        float c0 = col_sum<1>(mm_tile<KS>(X[0], X[2]), wH0, r, h);
-        c0 += col_sum<0>(mm_tile<KS>(X[1], X[2]), wH1, r, h);
-        c0 += col_sum<2>(mm_tile<KS>(X[2], X[2]), wC0, r, h);
-        float c1 = col_sum<1>(mm_tile<KS>(X[1], X[3]), wH1, r, h);
-        c1 += col_sum<0>(mm_tile<KS>(X[2], X[3]), wC0, r, h);
-        c1 += col_sum<2>(mm_tile<KS>(X[3], X[3]), wC1, r, h);
-        // forward band of the 64 tokens in front of the chunk
-        float f0 = col_sum<3>(mm_tile<KS>(X[0], X[0]), wH0, r, h);
-        f0 += col_sum<0>(mm_tile<KS>(X[1], X[0]), wH1, r, h);
-        const float sq0 = f0;                                         // the part inside the 64 x 64 square
-        f0 += col_sum<4>(mm_tile<KS>(X[2], X[0]), wC0, r, h);
-        float f1 = col_sum<3>(mm_tile<KS>(X[1], X[1]), wH1, r, h);
-        const float sq1 = f1;
-        f1 += col_sum<0>(mm_tile<KS>(X[2], X[1]), wC0, r, h);
-        f1 += col_sum<4>(mm_tile<KS>(X[3], X[1]), wC1, r, h);
+        NKV_NORM_SET(1, XH);
+        __builtin_amdgcn_wave_barrier();
+        // One tile at a time (the scheduling barriers): twelve tiles' worth of result registers would not fit.
+#define NKV_TILE(acc, MASK, A, B, W)                                  \
+    do {                                                              \
+        acc += col_sum<MASK>(mm_tile<KS>(A, B), W, r, h);             \
+        asm volatile("" : "+v"(acc));                                 \
+    } while (0)
+        // backward band of tokens t0 + 32 .., forward band of tokens t0 - 32 ..
+        float c1 = 0.f, f1 = 0.f, c0 = 0.f, f0 = 0.f;
+        NKV_TILE(c1, 1, XH, XB, wH1);
+        NKV_TILE(c1, 0, XA, XB, wC0);
+        NKV_TILE(c1, 2, XB, XB, wC1);
+        NKV_TILE(f1, 3, XH, XH, wH1);
+        const float sq1 = f1;                                         // the part inside the 64 x 64 square
+        NKV_TILE(f1, 0, XA, XH, wC0);
+        NKV_TILE(f1, 4, XB, XH, wC1);
+        // the chunk's second half makes room for the first half of the halo
+#pragma unroll
+        for (int kk = 0; kk < KS; ++kk) XB[kk] = row_load<kKeyBF16>(rsrc, lane_off - 64 * kRowBytes + 32 * kk);
+        __builtin_amdgcn_sched_barrier(0);
+        NKV_TILE(c0, 0, XH, XA, wH1);
+        NKV_TILE(c0, 2, XA, XA, wC0);
+        NKV_NORM_SET(0, XB);
+        __builtin_amdgcn_wave_barrier();
+        NKV_TILE(c0, 1, XB, XA, wH0);
+        NKV_TILE(f0, 3, XB, XB, wH0);
+        NKV_TILE(f0, 0, XH, XB, wH1);
+        const float sq0 = f0;
+        NKV_TILE(f0, 4, XA, XB, wC0);
+#undef NKV_TILE
+#undef NKV_NORM_SET
+        // and comes back for the stable dots while this wave waits for the unit sum
+#pragma unroll
+        for (int kk = 0; kk < KS; ++kk) XB[kk] = row_load<kKeyBF16>(rsrc, lane_off + 32 * kRowBytes + 32 * kk);
+        __builtin_amdgcn_sched_barrier(0);
         float v[6] = {c0, c1, f0, f1, sq0, sq1};
 #pragma unroll
         for (int i = 0; i < 6; ++i) v[i] += __shfl_xor(v[i], 32, 64);
@@ -1139,7 +1166,7 @@ void scan_mfma_kernel(const uint8_t *__restrict__ keys, RowMap km, PromptTab tab
         }
         ssq = wave_sum(ssq);
         __builtin_amdgcn_wave_barrier();
-        const float sd = anchor_dot<D>(&lds_terms[w][0][0], X[2], X[3], r, h);
+        const float sd = anchor_dot<D>(&lds_terms[w][0][0], XA, XB, r, h);
         if (tok < blk_hi) a_raw[row0 + tok] = neg_cos(rn_m * sd, kn_m, ssq);
     }
 }
@@ -1152,7 +1179,7 @@ __global__ __launch_bounds__(64 * NW, 2) void deferred_stable_mfma_kernel(const 
                                                                           float *__restrict__ a_raw)
 {
     constexpr int KS = D / 16, kRowBytes = D * 2, DPL = D / 64;
-    __shared__ __attribute__((aligned(16))) uint16_t lds_terms[NW][3][D];
+    __shared__ __attribute__((aligned(16))) uint16_t lds_terms[NW][4][D];
     const int nblk = tab.blk_off[tab.n];
     const uint32_t count = sync[kDeferCountWord];
     const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -1195,6 +1222,7 @@ __global__ __launch_bounds__(64 * NW, 2) void deferred_stable_mfma_kernel(const 
             lds_terms[w][0][dim] = t0b;
             lds_terms[w][1][dim] = t1b;
             lds_terms[w][2][dim] = t2b;
+            lds_terms[w][3][dim] = 0;
         }
         ssq = wave_sum(ssq);
         __builtin_amdgcn_wave_barrier();
