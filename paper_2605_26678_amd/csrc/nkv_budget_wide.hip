@@ -241,7 +241,7 @@ __global__ __launch_bounds__(1024) void layer_finish_kernel(int L, int H, Prompt
     __shared__ uint32_t cT[kMaxSeg], cL[kMaxSeg], oT[kMaxSeg];       // segment counts and offsets
     __shared__ uint32_t nPool, s_TL, s_gtAll, s_bad;
     const int pl = blockIdx.x, l = pl % L, p = pl / L;
-    const LayerPick pk = picks[pl];
+    const LayerPick &pk = picks[pl];                                 // read in place: a private copy would sit in scratch
     if (pk.done) return;
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int N = tab.tok_off[p + 1] - tab.tok_off[p];
