@@ -50,7 +50,9 @@ typedef enum nkv_status {
     NKV_ESHAPE = -2,       /* bad L/H/d/dv, non-monotone cu_seqlens, empty prompt     */
     NKV_EWORKSPACE = -3,   /* ws is NULL, misaligned or smaller than required         */
     NKV_EHIP = -4,         /* a HIP call failed (launch error)                        */
-    NKV_EUNSUPPORTED = -5  /* valid request outside what the kernels cover            */
+    NKV_EUNSUPPORTED = -5, /* valid request outside what the kernels cover            */
+    NKV_ESCRATCH = -6      /* nkv_budget_noalloc: the shape needs more scratch than   */
+                           /* NKV_STATIC_SCRATCH_BYTES                                */
 } nkv_status;
 
 /* Element type of keys and values (and of the packed outputs, whose rows are copies).                  */
@@ -94,6 +96,7 @@ enum {
 #define NKV_MAX_HEADS 32          /* KV heads per layer                                 */
 #define NKV_MAX_LAYER_TENSORS 128 /* layers when every layer has a tensor of its own    */
 #define NKV_PIN 3.0e38f           /* score written to pinned sink positions             */
+#define NKV_STATIC_SCRATCH_BYTES (32u << 20) /* scratch array inside the library, see nkv_budget_noalloc */
 
 /*
  * Fixed policy constants (Appendix A "Hyperparameters").  nkv_params_default()
@@ -204,6 +207,22 @@ int nkv_score_raw(const void *keys, const nkv_shape *shape, const nkv_params *pa
 int nkv_budget(const float *scores, const nkv_shape *shape, const nkv_params *params,
                const double *r_per_prompt, int32_t *k_per_head, void *ws, size_t ws_bytes,
                void *hip_stream);
+
+/*
+ * nkv_budget for callers that cannot allocate device memory or hand over scratch: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same inputs, same k_per_head, same kernels;
+ * the scratch is an array of NKV_STATIC_SCRATCH_BYTES (32 MiB) that lives inside the library's code object
+ * (one copy per GPU the library runs on, held until the process ends), so the call takes no ws argument and
+ * calls no allocating routine.  A shape whose budget kernels need more than that (about 4000 (prompt, layer,
+ * head) units, or about 44 million (head, token) scores in prompts of more than 8192 tokens) is refused with
+ * NKV_ESCRATCH before anything is enqueued.  The first call on a device looks the array's address up (a
+ * host-side runtime query): make that call outside a capture.  All calls on one GPU share the array: calls
+ * that overlap in time on one GPU (different streams or threads) race and give undefined budgets; calls on
+ * one stream, or otherwise ordered, are safe.  Nothing in the array has to survive or be cleared between
+ * calls.
+ */
+int nkv_budget_noalloc(const float *scores, const nkv_shape *shape, const nkv_params *params,
+                       const double *r_per_prompt, int32_t *k_per_head, void *hip_stream);
 
 /*
  * Compression operator (Section 2.5).  For every unit u keep the k_per_head[u]

@@ -15,7 +15,8 @@ from typing import Optional, Sequence, Tuple
 from . import build as _build
 
 NKV_OK = 0
-NKV_EINVAL, NKV_ESHAPE, NKV_EWORKSPACE, NKV_EHIP, NKV_EUNSUPPORTED = -1, -2, -3, -4, -5
+NKV_EINVAL, NKV_ESHAPE, NKV_EWORKSPACE, NKV_EHIP, NKV_EUNSUPPORTED, NKV_ESCRATCH = -1, -2, -3, -4, -5, -6
+STATIC_SCRATCH_BYTES = 32 << 20
 DTYPE_F32, DTYPE_BF16, DTYPE_F16, DTYPE_F8_E4M3 = 0, 1, 2, 3
 FLAG_GENERIC_KERNELS = 1
 FLAG_TWO_PASS_STABLE = 2
@@ -28,7 +29,7 @@ FLAG_SELECT_PER_HEAD = 64
 PIN = 3.0e38
 
 EXPORTS = ("nkv_params_default", "nkv_block_size", "nkv_k0", "nkv_m_safe", "nkv_m_p", "nkv_packed_rows",
-           "nkv_workspace_bytes", "nkv_score", "nkv_score_raw", "nkv_budget", "nkv_select_compact",
+           "nkv_workspace_bytes", "nkv_score", "nkv_score_raw", "nkv_budget", "nkv_budget_noalloc", "nkv_select_compact",
            "nkv_decode_workspace_bytes", "nkv_decode_attention", "nkv_copy_probe", "nkv_strerror", "nkv_version")
 KERNELS = ("scan", "finalize", "budget", "select", "gather", "decode")
 PASS_KERNELS = KERNELS[:5]          # the kernels of the compression pass itself
@@ -83,6 +84,7 @@ def lib() -> C.CDLL:
         L.nkv_score_raw.argtypes = [vp, C.POINTER(nkv_shape), C.POINTER(nkv_params), vp, vp, C.c_size_t, vp]
         L.nkv_budget.argtypes = [vp, C.POINTER(nkv_shape), C.POINTER(nkv_params), C.POINTER(f64), vp, vp,
                                  C.c_size_t, vp]
+        L.nkv_budget_noalloc.argtypes = [vp, C.POINTER(nkv_shape), C.POINTER(nkv_params), C.POINTER(f64), vp, vp]
         L.nkv_select_compact.argtypes = [vp, vp, vp, vp, C.POINTER(nkv_shape), C.POINTER(nkv_params), vp, vp, vp,
                                          vp, i64, vp, vp, C.c_size_t, vp]
         L.nkv_decode_workspace_bytes.argtypes = [C.POINTER(nkv_shape), C.c_int32, i64, C.POINTER(C.c_size_t)]
@@ -223,6 +225,16 @@ def budget(scores, shape: Shape, params: nkv_params, r_per_prompt: Sequence[floa
                           0 if ws is None else ws.numel() * ws.element_size(), _stream(stream))
     if rc:
         raise NkvError(rc, "nkv_budget")
+
+
+def budget_noalloc(scores, shape: Shape, params: nkv_params, r_per_prompt: Sequence[float], k_per_head,
+                   stream=None) -> None:
+    """``budget`` on the library's own static scratch array (no workspace argument, nothing allocated)."""
+    r = (C.c_double * shape.n_prompts)(*[float(x) for x in r_per_prompt])
+    rc = lib().nkv_budget_noalloc(_ptr(scores), C.byref(shape.c), C.byref(params), r, _ptr(k_per_head),
+                                  _stream(stream))
+    if rc:
+        raise NkvError(rc, "nkv_budget_noalloc")
 
 
 def select_compact(keys, values, scores, k_per_head, shape: Shape, params: nkv_params, packed_k, packed_v,

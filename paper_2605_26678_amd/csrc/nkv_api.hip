@@ -2,7 +2,14 @@
 #include <math.h>
 #include <string.h>
 
+#include <mutex>
+
 #include "nkv_internal.h"
+
+// Scratch of nkv_budget_noalloc, the entry point for callers that cannot allocate.  Every device the library
+// runs on holds its own copy at its own address until the process ends.  In host code the array's name is
+// only a handle for hipGetSymbolAddress; every use of the memory goes through the address that call returns.
+static __device__ __align__(256) unsigned char scratch[NKV_STATIC_SCRATCH_BYTES];
 
 namespace nkv {
 namespace {
@@ -182,6 +189,46 @@ int run_raw(const void *keys, const nkv_shape *s, const nkv_params *p, const Pro
     return e == hipSuccess ? NKV_OK : NKV_EHIP;
 }
 
+// The address of the static scratch array on the current device: looked up once per device, with that device
+// current, and kept.
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_lock;
+void *g_scratch_ptr[kMaxDevices];
+
+int static_scratch(void **out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return NKV_EHIP;
+    std::lock_guard<std::mutex> guard(g_scratch_lock);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return NKV_EHIP;
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return NKV_OK;
+}
+
+// argument checks and per-prompt integers shared by nkv_budget and nkv_budget_noalloc
+int prepare_budget(const float *scores, const nkv_shape *shape, const nkv_params *params, const double *r_per_prompt,
+                   const int32_t *k_per_head, PromptTab *tab)
+{
+    if (!scores || !r_per_prompt || !k_per_head) return NKV_EINVAL;
+    int rc = check_shape(shape);
+    if (rc) return rc;
+    rc = check_params(params);
+    if (rc) return rc;
+    fill_tab(shape, params, tab);
+    for (int p = 0; p < shape->n_prompts; ++p) {
+        const int64_t N = shape->cu_seqlens[p + 1] - shape->cu_seqlens[p];
+        const int64_t k0 = nkv_k0(N, r_per_prompt[p]);
+        if (k0 < 0) return NKV_EINVAL;
+        tab->k0[p] = (int32_t)k0;
+        tab->m_safe[p] = (int32_t)nkv_m_safe(k0, params->safeguard);
+    }
+    return NKV_OK;
+}
+
 }  // namespace
 }  // namespace nkv
 
@@ -325,24 +372,31 @@ int nkv_score(const void *keys, const nkv_shape *shape, const nkv_params *params
 int nkv_budget(const float *scores, const nkv_shape *shape, const nkv_params *params, const double *r_per_prompt,
                int32_t *k_per_head, void *ws, size_t ws_bytes, void *hip_stream)
 {
-    if (!scores || !r_per_prompt || !k_per_head) return NKV_EINVAL;
-    int rc = check_shape(shape);
-    if (rc) return rc;
-    rc = check_params(params);
-    if (rc) return rc;
     PromptTab tab;
-    fill_tab(shape, params, &tab);
-    for (int p = 0; p < shape->n_prompts; ++p) {
-        const int64_t N = shape->cu_seqlens[p + 1] - shape->cu_seqlens[p];
-        const int64_t k0 = nkv_k0(N, r_per_prompt[p]);
-        if (k0 < 0) return NKV_EINVAL;
-        tab.k0[p] = (int32_t)k0;
-        tab.m_safe[p] = (int32_t)nkv_m_safe(k0, params->safeguard);
-    }
+    int rc = prepare_budget(scores, shape, params, r_per_prompt, k_per_head, &tab);
+    if (rc) return rc;
     if (ws != nullptr) {
         rc = check_ws(ws, ws_bytes, budget_ws_bytes(shape->L, shape->H, tab));
         if (rc) return rc;
     }
+    const Prof prof{params->prof_start, params->prof_stop};
+    return launch_budget(scores, shape->L, shape->H, tab, k_per_head, ws,
+                         (params->flags & NKV_FLAG_BUDGET_PER_HEAD) != 0, prof, (hipStream_t)hip_stream) == hipSuccess
+               ? NKV_OK : NKV_EHIP;
+}
+
+int nkv_budget_noalloc(const float *scores, const nkv_shape *shape, const nkv_params *params,
+                       const double *r_per_prompt, int32_t *k_per_head, void *hip_stream)
+{
+    PromptTab tab;
+    int rc = prepare_budget(scores, shape, params, r_per_prompt, k_per_head, &tab);
+    if (rc) return rc;
+    if (budget_ws_bytes(shape->L, shape->H, tab) > (size_t)NKV_STATIC_SCRATCH_BYTES) return NKV_ESCRATCH;
+    void *ws = nullptr;
+    rc = static_scratch(&ws);
+    if (rc) return rc;
+    // The budget kernels write every word of their scratch before they read it, so nothing of the previous
+    // call's contents has to be cleared.
     const Prof prof{params->prof_start, params->prof_stop};
     return launch_budget(scores, shape->L, shape->H, tab, k_per_head, ws,
                          (params->flags & NKV_FLAG_BUDGET_PER_HEAD) != 0, prof, (hipStream_t)hip_stream) == hipSuccess
@@ -432,6 +486,7 @@ const char *nkv_strerror(int status)
     case NKV_EWORKSPACE: return "workspace missing, misaligned or too small";
     case NKV_EHIP: return "HIP runtime error while enqueuing kernels";
     case NKV_EUNSUPPORTED: return "request not covered by the kernels";
+    case NKV_ESCRATCH: return "shape needs more scratch than the library's static array holds (NKV_STATIC_SCRATCH_BYTES)";
     default: return "unknown status";
     }
 }
