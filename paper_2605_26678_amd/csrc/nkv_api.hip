@@ -182,7 +182,7 @@ int run_raw(const void *keys, const nkv_shape *s, const nkv_params *p, const Pro
                               (p->flags & NKV_FLAG_TWO_PASS_STABLE)  ? kScanTwoPass
                               : (p->flags & NKV_FLAG_NO_UNIT_SUMS)  ? kScanRepairAll
                               : (p->flags & NKV_FLAG_DEFER_STABLE)  ? kScanDeferAll : kScanFused,
-                              (p->flags & NKV_FLAG_MFMA_SCAN) != 0, prof, st);
+                              prof, st);
     else
         e = launch_score_generic(keys, km, s->dtype, LH, s->d, p->window, tab, a_raw, (float *)(ws + lay.rnorm),
                                  (float *)(ws + lay.bsum), (float *)(ws + lay.ssum), prof, st);

@@ -78,8 +78,7 @@ size_t fast_score_sync_bytes(int LH, const PromptTab &tab);
 // kScanRepairAll: in addition no unit sum is formed inside the pass, all come from the repair kernel.
 enum { kScanFused = 0, kScanTwoPass = 1, kScanDeferAll = 2, kScanRepairAll = 3 };
 hipError_t launch_score_fast(const void *keys, const RowMap &km, int dtype, int LH, int d, const PromptTab &tab, float *a_raw,
-                             float *bsum, float *ssum, void *sync_area, int mode, bool mfma, const Prof &prof,
-                             hipStream_t st);
+                             float *bsum, float *ssum, void *sync_area, int mode, const Prof &prof, hipStream_t st);
 
 // Units are numbered prompt by prompt, so the units of consecutive prompts of similar length form one
 // range.  Calls f(ept, unit0, units) for every maximal run of prompts whose lengths need the same number
