@@ -12,7 +12,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libnkv.so")
 
-SOURCES = ["nkv_api.hip", "nkv_score_generic.hip", "nkv_score_fast.hip", "nkv_finalize.hip", "nkv_finalize_wide.hip", "nkv_budget.hip",
+SOURCES = ["nkv_api.hip", "nkv_score_generic.hip", "nkv_score_fast.hip", "nkv_score_tile.hip", "nkv_finalize.hip", "nkv_finalize_wide.hip", "nkv_budget.hip",
            "nkv_budget_wide.hip", "nkv_budget_heads.hip", "nkv_select.hip", "nkv_select_wide.hip", "nkv_decode.hip"]
 
 # -packed-fp32-ops is switched off on purpose: packed fp32 instructions are not to be generated.

@@ -176,13 +176,16 @@ int run_raw(const void *keys, const nkv_shape *s, const nkv_params *p, const Pro
     const int rc = fill_map(s, s->key_strides, s->key_layer_offsets, s->d, &km);
     if (rc) return rc;
     hipError_t e;
-    if (!(p->flags & NKV_FLAG_GENERIC_KERNELS) && fast_score_supported(s->dtype, s->d, p->window, tab))
+    const int mode = (p->flags & NKV_FLAG_TWO_PASS_STABLE)  ? kScanTwoPass
+                     : (p->flags & NKV_FLAG_NO_UNIT_SUMS)  ? kScanRepairAll
+                     : (p->flags & NKV_FLAG_DEFER_STABLE)  ? kScanDeferAll : kScanFused;
+    if (!(p->flags & NKV_FLAG_GENERIC_KERNELS) && (p->flags & NKV_FLAG_MFMA_SCAN) && mode != kScanTwoPass &&
+        tile_score_supported(s->dtype, s->d, p->window, tab, LH))
+        e = launch_score_tile(keys, km, LH, tab, a_raw, (float *)(ws + lay.bsum), (float *)(ws + lay.ssum), ws + lay.sync,
+                              mode, prof, st);
+    else if (!(p->flags & NKV_FLAG_GENERIC_KERNELS) && fast_score_supported(s->dtype, s->d, p->window, tab))
         e = launch_score_fast(keys, km, s->dtype, LH, s->d, tab, a_raw, (float *)(ws + lay.bsum), (float *)(ws + lay.ssum),
-                              ws + lay.sync,
-                              (p->flags & NKV_FLAG_TWO_PASS_STABLE)  ? kScanTwoPass
-                              : (p->flags & NKV_FLAG_NO_UNIT_SUMS)  ? kScanRepairAll
-                              : (p->flags & NKV_FLAG_DEFER_STABLE)  ? kScanDeferAll : kScanFused,
-                              prof, st);
+                              ws + lay.sync, mode, prof, st);
     else
         e = launch_score_generic(keys, km, s->dtype, LH, s->d, p->window, tab, a_raw, (float *)(ws + lay.rnorm),
                                  (float *)(ws + lay.bsum), (float *)(ws + lay.ssum), prof, st);

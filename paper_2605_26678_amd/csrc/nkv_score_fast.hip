@@ -471,39 +471,6 @@ __global__ __launch_bounds__(64 * NW) void deferred_stable_kernel(const uint8_t 
     }
 }
 
-// Unit sums that the scan left unwritten (its summing workgroup gave up waiting, which the scheduling of
-// workgroups makes possible in principle): formed here, after the scan, from the block totals, with the
-// additions in the same order.  grid: one workgroup of 64 * NW threads per (layer*head, prompt).
-template <int D, int NW>
-__global__ __launch_bounds__(64 * NW) void unit_sum_repair_kernel(const float *__restrict__ bsum, PromptTab tab,
-                                                                  float *__restrict__ ssum)
-{
-    __shared__ float part[64 * NW / (D / 4) * D];
-    const int lh = blockIdx.x / tab.n, p = blockIdx.x - lh * tab.n;
-    float *ssum_unit = ssum + ((int64_t)lh * tab.n + p) * D;
-    bool missing = false;
-    for (int i = threadIdx.x; i < D; i += 64 * NW) missing = missing || __float_as_uint(ssum_unit[i]) == kUnwritten;
-    if (!__syncthreads_or(missing)) return;
-    const int nblk = tab.blk_off[tab.n];
-    add_unit_up<D, NW, false>(bsum + ((int64_t)lh * nblk + tab.blk_off[p]) * D, tab.blk_off[p + 1] - tab.blk_off[p],
-                              ssum_unit, part, 0u);
-}
-
-// What the fused pass expects to find in memory, in one launch: counters at zero, block totals and unit sums
-// "unwritten".  16-byte stores, grid-stride over the three areas one after the other.
-__global__ __launch_bounds__(256) void prepare_kernel(uint4 *sync, size_t n_sync, uint4 *bsum, size_t n_bsum,
-                                                      uint4 *ssum, size_t n_ssum)
-{
-    const uint4 zero = make_uint4(0u, 0u, 0u, 0u);
-    const uint4 none = make_uint4(kUnwritten, kUnwritten, kUnwritten, kUnwritten);
-    const size_t total = n_sync + n_bsum + n_ssum;
-    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
-        if (i < n_sync) sync[i] = zero;
-        else if (i < n_sync + n_bsum) bsum[i - n_sync] = none;
-        else ssum[i - n_sync - n_bsum] = none;
-    }
-}
-
 // grid (prompts, L*H): stable anchor (up to length) = sum of the prompt's block totals, in block order
 template <int D>
 __global__ __launch_bounds__(D) void ssum_kernel(const float *__restrict__ bsum, PromptTab tab, float *__restrict__ ssum)
@@ -562,20 +529,9 @@ void launch_scan(const uint8_t *keys, const RowMap &km, int LH, const PromptTab 
                  uint32_t *sync, int poll_limit, uint32_t spin_limit, hipStream_t st)
 {
     const int64_t rows = (int64_t)LH * tab.T;
-    unsigned groups = (unsigned)(tab.blk_off[tab.n] * LH);
     ScanPlan plan;
-    plan.nblk = tab.blk_off[tab.n];
-    plan.run = run_length(plan.nblk);
-    plan.inv_run = 1.0f / (float)plan.run;
-    plan.inv_H = 1.0f / (float)km.H;
-    uint32_t longest = 0;
-    for (int x = 0; x < kDies; ++x) {                                 // 8 queues of (nearly) equal length, interleaved
-        plan.len[x] = die_blocks(plan.nblk, plan.run, x);
-        plan.inv_items[x] = (float)kDies / (float)(kDies * plan.len[x] + tab.n);
-        const uint32_t items = queue_start(LH, plan.len[x], tab.n, x);
-        longest = items > longest ? items : longest;
-    }
-    if (FUSED) groups = longest * kDies;
+    const unsigned queued = fill_scan_plan(LH, tab, km.H, &plan);
+    const unsigned groups = FUSED ? queued : (unsigned)(tab.blk_off[tab.n] * LH);
     scan_kernel<D, NW, FUSED, KF><<<groups, 64 * NW, 0, st>>>(keys, km, tab, plan, a_raw, bsum, ssum, sync, LH, rows,
                                                               poll_limit, spin_limit);
 }

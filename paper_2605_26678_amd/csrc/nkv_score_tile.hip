@@ -1,0 +1,526 @@
+// Streaming scoring kernel for bf16 keys of head dim 128, window 64, episodic block size <= 256 (paper Sections
+// 2.1-2.3), with every dot product of the pass formed by the matrix cores.
+//
+// The pass is a stream over the keys and nothing else is read from memory, but written for the vector unit it
+// needs ~2300 instructions per 64 tokens and is bound by their issue.  Here the vector unit keeps only the work
+// that is a sum over tokens (the partial sums of normalised keys that the anchors are made of); everything that
+// is a contraction over the head dimension goes through v_mfma_f32_16x16x32_bf16, whose products of bf16 values
+// are exact and whose sums are fp32:
+//
+//   * a block is cut into groups of 16 tokens.  T_q = sum of k_hat over group q (vector unit).  The window sum in
+//     front of group q's first token is exact in terms of groups: Seed_q = T_{q-4} + ... + T_{q-1}.
+//   * for token i of group G, with P the group 64 tokens earlier (token i' = i - 64 leaves as i enters),
+//         W_i = Seed_G + sum_{j in G, j <= i} k_hat_j - sum_{j' in P, j' <= i'} k_hat_j',
+//     so <k_i, W_i> = <k_i, Seed_G> + sum_{j <= i} w_j A[i][j] - sum_{j' <= i'} w_j' X[i][j'] with the Gram tiles
+//     A = K_G K_G^T and X = K_G K_P^T of the raw keys and w = 1 / ||k||.
+//   * ||W_i||^2 follows the window inside the group: it is ||Seed_G||^2 plus the running sum of
+//         ||W_i||^2 - ||W_{i-1}||^2 = 2 <W_i, d_i> - ||d_i||^2,   d_i = k_hat_i - k_hat_i',
+//     which needs <k_i', W_i> (same tiles, the other triangle) and X[i][i'].  At most 16 terms are added up.
+//   * <k, anchor> for the anchors that are vectors (Seed_G, the block total, the unit sum): the fp32 anchor is
+//     split into three bf16 terms (8 + 8 + 8 mantissa bits, exact) that form rows of the left operand.
+//
+// Layouts.  A wave owns the groups q = w, w + 4, w + 8, w + 12 of the block (so the group 64 tokens earlier is
+// its own previous group) and the group of the halo in front of them.  A group is loaded row-wise (lane (g, c):
+// rows 4g .. 4g+3, dims 8c .. 8c+7; four contiguous 256-byte pieces per load instruction), which is the layout
+// the partial sums want, and passes through 4 KB of LDS private to the wave to become a matrix operand (lane
+// (q, n): token n, dims 32 kk + 8q .. + 7 in operand register kk).  Operands stay in registers until the unit's
+// sum has arrived.  A 16 x 16 result leaves lane (q, n) with column n, rows 4q .. 4q+3: sums over rows are four
+// multiply-adds per lane followed by a sum over the four lanes n, n+16, n+32, n+48.
+//
+// Protocol (block totals, unit sums, bounded waits, deferred blocks): as in nkv_score_fast.hip.
+#include "nkv_scan_common.h"
+
+namespace nkv {
+namespace {
+
+using bf16x8 = __bf16 __attribute__((ext_vector_type(8)));
+using f32x4 = float __attribute__((ext_vector_type(4)));
+
+constexpr int kGroup = 16;                       // tokens per group
+constexpr int kPitch = 272;                      // bytes between the rows of a staged group: 16 lanes that read the
+                                                 // same piece of 16 rows touch every LDS bank once
+constexpr int kStageBytes = kGroup * kPitch;
+constexpr int kTileWaves = 4;
+
+__device__ __forceinline__ f32x4 mma(const u32x4 &a, const u32x4 &b, f32x4 c)
+{
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+}
+
+// D[m][n] = sum over the head dimension of a's row m and b's row n
+template <int KS> __device__ __forceinline__ f32x4 tile(const u32x4 (&a)[KS], const u32x4 (&b)[KS])
+{
+    f32x4 c = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int kk = 0; kk < KS; ++kk) c = mma(a[kk], b[kk], c);
+    return c;
+}
+
+// x summed over the four lanes n, n + 16, n + 32, n + 48; every lane receives the total.
+// permlane32_swap(x, x) = (x of the lower half in both halves, x of the upper half in both halves); the 16-lane
+// swap does the same with even and odd rows of 16 lanes.
+__device__ __forceinline__ float sum_over_rows16(float x)
+{
+    const uint32_t u = __float_as_uint(x);
+    const auto a = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    const float s = __uint_as_float(a[0]) + __uint_as_float(a[1]);
+    const uint32_t v = __float_as_uint(s);
+    const auto b = __builtin_amdgcn_permlane16_swap(v, v, false, false);
+    return __uint_as_float(b[0]) + __uint_as_float(b[1]);
+}
+
+// T[e], e < 8: partial sums of dims 8c + e held by lane (g, c).  Summed over g; lane (g, c) receives the totals
+// of dims 8c + 2g and 8c + 2g + 1.  Each step halves the number of live values.
+__device__ __forceinline__ float2 sum_over_rows16_transposing(const float (&T)[8])
+{
+    float U[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {                // lower half: dim e, upper half: dim e + 4
+        const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(T[e]), __float_as_uint(T[e + 4]), false, false);
+        U[e] = __uint_as_float(r[0]) + __uint_as_float(r[1]);
+    }
+    float V[2];
+#pragma unroll
+    for (int e = 0; e < 2; ++e) {                // rows 0..3 of 16 lanes: dims e, e + 2, e + 4, e + 6
+        const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(U[e]), __float_as_uint(U[e + 2]), false, false);
+        V[e] = __uint_as_float(r[0]) + __uint_as_float(r[1]);
+    }
+    return make_float2(V[0], V[1]);
+}
+
+// inclusive running sum over the 16 lanes of a row (lanes n = 0 .. 15 of every group of 16)
+__device__ __forceinline__ float row_prefix_sum(float x)
+{
+    x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x111, 0xf, 0xf, true));   // row_shr:1
+    x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x112, 0xf, 0xf, true));   // row_shr:2
+    x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x114, 0xf, 0xf, true));   // row_shr:4
+    x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x118, 0xf, 0xf, true));   // row_shr:8
+    return x;
+}
+
+// fp32 -> three bf16 terms whose sum is the value (each takes the next 8 mantissa bits)
+__device__ __forceinline__ void split3(float x, uint32_t &hi, uint32_t &mid, uint32_t &lo)
+{
+    const uint32_t b0 = __float_as_uint(x) & 0xffff0000u;
+    const float r1 = x - __uint_as_float(b0);
+    const uint32_t b1 = __float_as_uint(r1) & 0xffff0000u;
+    const float r2 = r1 - __uint_as_float(b1);
+    hi = b0 >> 16;
+    mid = b1 >> 16;
+    lo = __float_as_uint(r2) >> 16;
+}
+
+// A vector of which this lane holds dims 2 lane and 2 lane + 1, as the three bf16 terms of rows row0 .. row0 + 2
+// of a staged left operand.
+__device__ __forceinline__ void stage_anchor(uint8_t *stage, int row0, int lane, float v0, float v1)
+{
+    uint32_t h0, m0, l0, h1, m1, l1;
+    split3(v0, h0, m0, l0);
+    split3(v1, h1, m1, l1);
+    *reinterpret_cast<uint32_t *>(stage + (row0 + 0) * kPitch + 4 * lane) = h0 | (h1 << 16);
+    *reinterpret_cast<uint32_t *>(stage + (row0 + 1) * kPitch + 4 * lane) = m0 | (m1 << 16);
+    *reinterpret_cast<uint32_t *>(stage + (row0 + 2) * kPitch + 4 * lane) = l0 | (l1 << 16);
+}
+
+// The staged 16 rows as a matrix operand: lane (q, n) takes dims 32 kk + 8 q .. + 7 of row n.
+__device__ __forceinline__ void read_operand(const uint8_t *stage, int lane, u32x4 (&x)[4])
+{
+    const uint8_t *mine = stage + (lane & 15) * kPitch + 16 * (lane >> 4);
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) x[kk] = *reinterpret_cast<const u32x4 *>(mine + 64 * kk);
+}
+
+// ||k||^2 of the operand's token n, in all four lanes that hold a quarter of it.  The compiler does not see
+// what the assembly writes, so the wait states that a read by another kind of vector instruction needs after a
+// dot-product instruction are spent inside the block.
+__device__ __forceinline__ float operand_sumsq(const u32x4 (&x)[4])
+{
+    float acc = 0.f;
+    asm("v_dot2c_f32_bf16 %0, %1, %1\n\t"
+        "v_dot2c_f32_bf16 %0, %2, %2\n\t"
+        "v_dot2c_f32_bf16 %0, %3, %3\n\t"
+        "v_dot2c_f32_bf16 %0, %4, %4\n\t"
+        "v_dot2c_f32_bf16 %0, %5, %5\n\t"
+        "v_dot2c_f32_bf16 %0, %6, %6\n\t"
+        "v_dot2c_f32_bf16 %0, %7, %7\n\t"
+        "v_dot2c_f32_bf16 %0, %8, %8\n\t"
+        "v_dot2c_f32_bf16 %0, %9, %9\n\t"
+        "v_dot2c_f32_bf16 %0, %10, %10\n\t"
+        "v_dot2c_f32_bf16 %0, %11, %11\n\t"
+        "v_dot2c_f32_bf16 %0, %12, %12\n\t"
+        "v_dot2c_f32_bf16 %0, %13, %13\n\t"
+        "v_dot2c_f32_bf16 %0, %14, %14\n\t"
+        "v_dot2c_f32_bf16 %0, %15, %15\n\t"
+        "v_dot2c_f32_bf16 %0, %16, %16\n\t"
+        "s_nop 3"
+        : "+v"(acc)
+        : "v"(x[0].x), "v"(x[0].y), "v"(x[0].z), "v"(x[0].w), "v"(x[1].x), "v"(x[1].y), "v"(x[1].z), "v"(x[1].w),
+          "v"(x[2].x), "v"(x[2].y), "v"(x[2].z), "v"(x[2].w), "v"(x[3].x), "v"(x[3].y), "v"(x[3].z), "v"(x[3].w));
+    return sum_over_rows16(acc);
+}
+
+__device__ __forceinline__ float sum3(const f32x4 &d) { return (d[0] + d[1]) + d[2]; }
+
+// sum over this lane's four rows of wm[rho] * d[rho]
+__device__ __forceinline__ float weighted(const f32x4 &d, const float (&wm)[4])
+{
+    return fmaf(wm[3], d[3], fmaf(wm[2], d[2], fmaf(wm[1], d[1], wm[0] * d[0])));
+}
+
+__device__ __forceinline__ void agent_store8(__amdgpu_buffer_rsrc_t rsrc, int byte_off, float a, float b)
+{
+    const u32x2 v = {__float_as_uint(a), __float_as_uint(b)};
+    __builtin_amdgcn_raw_buffer_store_b64(v, rsrc, byte_off, 0, 16);
+}
+
+// grid: the dies' queues of the fused pass (see nkv_score_fast.hip), 256 threads.
+__global__ __launch_bounds__(64 * kTileWaves, 3)
+void scan_tile_kernel(const uint8_t *__restrict__ keys, RowMap km, PromptTab tab, ScanPlan plan, float *__restrict__ a_raw,
+                      float *__restrict__ bsum, float *__restrict__ ssum, uint32_t *__restrict__ sync, int LH,
+                      int64_t rows, int poll_limit, uint32_t spin_limit)
+{
+    constexpr int D = 128, NW = kTileWaves, kRowBytes = D * 2;
+    __shared__ __attribute__((aligned(16))) uint8_t lds_stage[NW][kStageBytes];   // a wave's group on its way to operand layout, later its anchors
+    __shared__ __attribute__((aligned(16))) float lds_T[4 + 16][D];               // group sums: 4 halo groups, then the block's
+    __shared__ __attribute__((aligned(16))) float lds_w[NW][5][kGroup];           // 1/||k|| per token of a wave's groups (0: no such token)
+    __shared__ __attribute__((aligned(16))) float lds_S[D];                       // the unit's sum, once complete
+    __shared__ int s_have;
+
+    const int nblk = plan.nblk;
+    int lh, blk, layer, head;
+    {
+        // Static assignment of blocks to workgroups, as in scan_kernel.
+        const int x = (int)(blockIdx.x & (kDies - 1));
+        const uint32_t t = blockIdx.x >> 3;
+        const int run = plan.run, len = plan.len[x];
+        if (t >= queue_start(LH, len, tab.n, x)) return;
+        int l = min(LH - 1, (int)((float)t * plan.inv_items[x]));
+        while (l > 0 && queue_start(l, len, tab.n, x) > t) --l;
+        while (l + 1 < LH && queue_start(l + 1, len, tab.n, x) <= t) ++l;
+        const int r = (int)(t - queue_start(l, len, tab.n, x));
+        lh = l;
+        const int nsum = l % kDies == x ? tab.n : 0;
+        {
+            const int rb = max(r - nsum, 0), cyc = div_by(rb, run, plan.inv_run);
+            blk = (cyc * kDies + x) * run + (rb - cyc * run);
+        }
+        layer = div_by(lh, km.H, plan.inv_H);
+        head = lh - layer * km.H;
+        if (r < nsum) {                                              // this workgroup adds a unit up
+            const int p = r;
+            static_assert(64 * NW / (D / 4) * D <= 20 * D, "partial sums of the unit do not fit the LDS scratch");
+            if (!add_unit_up<D, NW, true>(bsum + ((int64_t)lh * nblk + tab.blk_off[p]) * D,
+                                          tab.blk_off[p + 1] - tab.blk_off[p], ssum + ((int64_t)lh * tab.n + p) * D,
+                                          &lds_T[0][0], spin_limit) &&
+                threadIdx.x == 0)
+                atomicAdd(sync + kTimeoutWord, 1u);
+            return;
+        }
+    }
+    const int p = prompt_of_block(tab, blk);
+    const int b = tab.b[p];
+    const int N = tab.tok_off[p + 1] - tab.tok_off[p];
+    const int blk_lo = (blk - tab.blk_off[p]) * b;
+    const int blk_hi = min(blk_lo + b, N);
+    const int ng = (blk_hi - blk_lo + kGroup - 1) / kGroup;           // groups of the block, <= 16
+    const int64_t row0 = (int64_t)lh * tab.T + tab.tok_off[p];        // row of the prompt's token 0
+
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+    const int g = lane >> 4, c = lane & 15;                           // row-wise layout: rows 4g .., dims 8c ..
+    const int qq = g, n = c;                                          // operand / result layout: token n, quarter qq
+    uint8_t *stage = lds_stage[w];
+
+    // ---- first touch: this wave's groups, halo group first.  Rows outside the prompt read as zeros. ----
+    const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint8_t *>(keys) + km.unit(layer, head, p, tab) * 2, 0, N * kRowBytes, 0x00020000);
+    u32x4 raw[5][4];
+    bool ex[5];                                                       // group m - 1 of the chain exists
+#pragma unroll
+    for (int m = 0; m < 5; ++m) {
+        const int q = w + 4 * (m - 1);                                // block-local group index, < 0: halo
+        ex[m] = q < ng;
+        if (ex[m]) {
+            const int off = (blk_lo + kGroup * q + 4 * g) * kRowBytes + 16 * c;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) raw[m][j] = row_load<kKeyBF16>(rsrc, off + j * kRowBytes);
+        }
+    }
+
+    // ---- per group: operand layout, norms, partial sum ----
+    u32x4 X[5][4];
+    float wv[5], ssv[5];                                              // 1/||k|| (0: no such token), ||k||^2 of token n
+#pragma unroll
+    for (int m = 0; m < 5; ++m) {
+        wv[m] = 0.f;
+        ssv[m] = 0.f;
+        if (ex[m]) {
+            const int q = w + 4 * (m - 1);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) *reinterpret_cast<u32x4 *>(stage + (4 * g + j) * kPitch + 16 * c) = raw[m][j];
+            __builtin_amdgcn_wave_barrier();
+            read_operand(stage, lane, X[m]);
+            const float ss = operand_sumsq(X[m]);
+            const int tok = blk_lo + kGroup * q + n;
+            wv[m] = (tok >= 0 && tok < blk_hi) ? inv_norm(ss) : 0.f;
+            ssv[m] = ss;
+            if (qq == 0) lds_w[w][m][n] = wv[m];
+            __builtin_amdgcn_wave_barrier();
+            const float4 w4 = *reinterpret_cast<const float4 *>(&lds_w[w][m][4 * g]);
+            const float ww[4] = {w4.x, w4.y, w4.z, w4.w};
+            float T[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) T[e] = 0.f;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                float k[8];
+                unpack8<kKeyBF16>(raw[m][j], k);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) T[e] = fmaf(ww[j], k[e], T[e]);
+            }
+            const float2 t2 = sum_over_rows16_transposing(T);
+            *reinterpret_cast<float2 *>(&lds_T[4 + q][8 * c + 2 * g]) = t2;
+            __builtin_amdgcn_wave_barrier();                          // the next group reuses the staging rows
+        }
+    }
+    __syncthreads();
+
+    // ---- block total = episodic anchor (up to length); lane: dims 2 lane, 2 lane + 1 ----
+    const int unblk = tab.blk_off[p + 1] - tab.blk_off[p];
+    float *bsum_unit = bsum + ((int64_t)lh * nblk + tab.blk_off[p]) * D;
+    float *S_unit = ssum + ((int64_t)lh * tab.n + p) * D;
+    float bsq;
+    {
+        float b0 = 0.f, b1 = 0.f;
+        for (int q = 0; q < ng; ++q) {
+            const float2 t2 = *reinterpret_cast<const float2 *>(&lds_T[4 + q][2 * lane]);
+            b0 += t2.x;
+            b1 += t2.y;
+        }
+        bsq = sum_over_rows16(row_sum<16>(fmaf(b0, b0, b1 * b1)));
+        if (w == blk % NW) {                                          // one wave stores the block total
+            const __amdgpu_buffer_rsrc_t brs = __builtin_amdgcn_make_buffer_rsrc(bsum_unit, 0, unblk * D * 4, 0x00020000);
+            agent_store8(brs, ((blk - tab.blk_off[p]) * D + 2 * lane) * 4, b0, b1);
+        }
+        stage_anchor(stage, 4, lane, b0, b1);                         // rows 4 .. 6: the block total's three terms
+    }
+
+    // ---- the chain of this wave's groups ----
+    // lane (qq, n) of a result holds rows 4 qq + rho, column n.  Masked weights of the rows: rows j <= n count.
+    const __amdgpu_buffer_rsrc_t out_c = __builtin_amdgcn_make_buffer_rsrc(a_raw + 2 * rows + row0, 0, blk_hi * 4, 0x00020000);
+    const __amdgpu_buffer_rsrc_t out_e = __builtin_amdgcn_make_buffer_rsrc(a_raw + rows + row0, 0, blk_hi * 4, 0x00020000);
+    const __amdgpu_buffer_rsrc_t out_s = __builtin_amdgcn_make_buffer_rsrc(a_raw + row0, 0, blk_hi * 4, 0x00020000);
+    constexpr int kNoStore = 0x40000000;                              // an offset past any buffer, also with a block's offset added: the store is dropped
+    const int off_q0 = qq == 0 ? 4 * n : kNoStore, off_q1 = qq == 1 ? 4 * n : kNoStore;
+    float wm_prev[4], alpha_prev;
+    {
+        const float4 w4 = *reinterpret_cast<const float4 *>(&lds_w[w][0][4 * qq]);
+        const float ww[4] = {w4.x, w4.y, w4.z, w4.w};
+#pragma unroll
+        for (int rho = 0; rho < 4; ++rho) wm_prev[rho] = 4 * qq + rho <= n ? ww[rho] : 0.f;
+        alpha_prev = weighted(tile<4>(X[0], X[0]), wm_prev);          // halo group: its own triangle only
+    }
+#pragma unroll
+    for (int m = 1; m < 5; ++m) {
+        if (ex[m]) {
+            const int q = w + 4 * (m - 1);
+            // window sum in front of the group = the four groups before it
+            float s0, s1;
+            {
+                const float2 t0 = *reinterpret_cast<const float2 *>(&lds_T[q][2 * lane]);
+                const float2 t1 = *reinterpret_cast<const float2 *>(&lds_T[q + 1][2 * lane]);
+                const float2 t2 = *reinterpret_cast<const float2 *>(&lds_T[q + 2][2 * lane]);
+                const float2 t3 = *reinterpret_cast<const float2 *>(&lds_T[q + 3][2 * lane]);
+                s0 = ((t0.x + t1.x) + t2.x) + t3.x;
+                s1 = ((t0.y + t1.y) + t2.y) + t3.y;
+            }
+            const float P0 = sum_over_rows16(row_sum<16>(fmaf(s0, s0, s1 * s1)));
+            stage_anchor(stage, 0, lane, s0, s1);                     // rows 0 .. 2: the seed's three terms
+            __builtin_amdgcn_wave_barrier();
+            u32x4 An[4];
+            read_operand(stage, lane, An);
+            __builtin_amdgcn_wave_barrier();                          // the next group rewrites rows 0 .. 2
+            const f32x4 AT = tile<4>(X[m], X[m]);                     // [j in G][i in G]
+            const f32x4 XT = tile<4>(X[m - 1], X[m]);                 // [j' in P][i in G]
+            const f32x4 XX = tile<4>(X[m], X[m - 1]);                 // [j in G][i' in P]
+            const f32x4 AG = tile<4>(An, X[m]);                       // [anchor row][i in G]
+            const f32x4 AP = tile<4>(An, X[m - 1]);                   // [anchor row][i' in P]
+            float wm[4];
+            {
+                const float4 w4 = *reinterpret_cast<const float4 *>(&lds_w[w][m][4 * qq]);
+                const float ww[4] = {w4.x, w4.y, w4.z, w4.w};
+#pragma unroll
+                for (int rho = 0; rho < 4; ++rho) wm[rho] = 4 * qq + rho <= n ? ww[rho] : 0.f;
+            }
+            const float alpha = weighted(AT, wm);                     // <k_i, entered rows of G>, partial
+            const float beta = weighted(XT, wm_prev);                 // <k_i, left rows of P>, partial
+            const float gamma = weighted(XX, wm);                     // <k_i', entered rows of G>, partial
+            // X[i][i']: row i of this lane's column i' = n sits in lane group n / 4, register n % 4
+            float xd = (n & 2) ? ((n & 1) ? XX[3] : XX[2]) : ((n & 1) ? XX[1] : XX[0]);
+            xd = (n >> 2) == qq ? xd : 0.f;
+            const float wn = wv[m], wp = wv[m - 1];
+            const float c_part = (qq == 0 ? sum3(AG) : 0.f) + (alpha - beta);
+            const float e_part = (qq == 0 ? sum3(AP) : 0.f) + (gamma - alpha_prev);
+            const float gsum = qq == 0 ? wn * wn * ssv[m] + wp * wp * ssv[m - 1] : 0.f;
+            const float d_part = 2.f * (wn * c_part - wp * e_part) + (2.f * wn * wp * xd - gsum);
+            const float cdot = sum_over_rows16(c_part);               // <k_i, W_i>
+            const float Pn = P0 + row_prefix_sum(sum_over_rows16(d_part));
+            const float knn = ssv[m] < 1e-24f ? sqrtf(ssv[m]) * 1e12f : 1.f;
+            const float ac = neg_cos(wn * cdot, knn, Pn);
+            const float ae = neg_cos(wn * sum3(AG), knn, bsq);        // meaningful in lane group 1 (rows 4 .. 6)
+            const int soff = (blk_lo + kGroup * q) * 4;                // (an offset that was past the buffer stays past it)
+            __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(ac), out_c, off_q0 + soff, 0, 0);
+            __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(ae), out_e, off_q1 + soff, 0, 0);
+#pragma unroll
+            for (int rho = 0; rho < 4; ++rho) wm_prev[rho] = wm[rho];
+            alpha_prev = alpha;
+            __builtin_amdgcn_sched_barrier(0);                        // one group at a time
+        }
+    }
+
+    // ---- stable dots against the unit's sum ----
+    const __amdgpu_buffer_rsrc_t srs = __builtin_amdgcn_make_buffer_rsrc(S_unit, 0, D * 4, 0x00020000);
+    if (w == 0) {                                                     // 16 lanes poll, the other waves sit at the barrier
+        u32x4 sv0 = {kUnwritten, kUnwritten, kUnwritten, kUnwritten}, sv1 = sv0;
+        bool got = false;
+        for (int polls = 0; poll_limit >= 0; ++polls) {               // poll_limit < 0: defer without looking
+            if (lane < 16) {
+                sv0 = agent_load16(srs, lane * 32);
+                sv1 = agent_load16(srs, lane * 32 + 16);
+            }
+            const bool ok = lane >= 16 || (all_written(sv0) && all_written(sv1));
+            got = __all(ok);
+            if (got || polls >= poll_limit) break;
+            __builtin_amdgcn_s_sleep(8);
+        }
+        if (got && lane < 16) {
+            *reinterpret_cast<u32x4 *>(&lds_S[lane * 8]) = sv0;
+            *reinterpret_cast<u32x4 *>(&lds_S[lane * 8 + 4]) = sv1;
+        }
+        if (lane == 0) {
+            s_have = got ? 1 : 0;
+            if (!got) sync[kSyncWords + atomicAdd(sync + kDeferCountWord, 1u)] = (uint32_t)(lh * nblk + blk);
+        }
+    }
+    __syncthreads();
+    if (s_have != 0) {
+        const float2 s2 = *reinterpret_cast<const float2 *>(&lds_S[2 * lane]);
+        const float ssq = sum_over_rows16(row_sum<16>(fmaf(s2.x, s2.x, s2.y * s2.y)));
+        stage_anchor(stage, 0, lane, s2.x, s2.y);
+        __builtin_amdgcn_wave_barrier();
+        u32x4 An[4];
+        read_operand(stage, lane, An);
+#pragma unroll
+        for (int m = 1; m < 5; ++m) {
+            if (ex[m]) {
+                const int q = w + 4 * (m - 1);
+                const f32x4 AS = tile<4>(An, X[m]);
+                const float knn = ssv[m] < 1e-24f ? sqrtf(ssv[m]) * 1e12f : 1.f;
+                const float as = neg_cos(wv[m] * sum3(AS), knn, ssq);
+                __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(as), out_s, off_q0 + (blk_lo + kGroup * q) * 4, 0, 0);
+            }
+        }
+    }
+}
+
+// a_s of the blocks whose workgroups did not wait for their unit's sum: the same operands (loaded in operand
+// layout directly), norms, split and product as in scan_tile_kernel, so the values are the ones it would have
+// stored.
+__global__ __launch_bounds__(64 * kTileWaves) void deferred_stable_tile_kernel(const uint8_t *__restrict__ keys, RowMap km,
+                                                                               PromptTab tab, const float *__restrict__ ssum,
+                                                                               const uint32_t *__restrict__ sync,
+                                                                               float *__restrict__ a_raw)
+{
+    constexpr int D = 128, NW = kTileWaves, kRowBytes = D * 2;
+    __shared__ __attribute__((aligned(16))) uint8_t lds_stage[NW][kStageBytes];
+    const int nblk = tab.blk_off[tab.n];
+    const uint32_t count = sync[kDeferCountWord];
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+    const int qq = lane >> 4, n = lane & 15;
+    uint8_t *stage = lds_stage[w];
+    constexpr int kNoStore = 0x40000000;
+    const int off_q0 = qq == 0 ? 4 * n : kNoStore;
+    for (uint32_t i = blockIdx.x; i < count; i += gridDim.x) {
+        const int id = (int)sync[kSyncWords + i], lh = id / nblk, blk = id - lh * nblk;
+        const int p = prompt_of_block(tab, blk);
+        const int b = tab.b[p], N = tab.tok_off[p + 1] - tab.tok_off[p];
+        const int blk_lo = (blk - tab.blk_off[p]) * b, blk_hi = min(blk_lo + b, N);
+        const int ng = (blk_hi - blk_lo + kGroup - 1) / kGroup;
+        const int64_t row0 = (int64_t)lh * tab.T + tab.tok_off[p];
+        const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<uint8_t *>(keys) + km.unit(lh, p, tab) * 2, 0, N * kRowBytes, 0x00020000);
+        const __amdgpu_buffer_rsrc_t out_s = __builtin_amdgcn_make_buffer_rsrc(a_raw + row0, 0, blk_hi * 4, 0x00020000);
+        const float2 s2 = *reinterpret_cast<const float2 *>(ssum + ((int64_t)lh * tab.n + p) * D + 2 * lane);
+        const float ssq = sum_over_rows16(row_sum<16>(fmaf(s2.x, s2.x, s2.y * s2.y)));
+        __builtin_amdgcn_wave_barrier();                              // the previous block's reads of the staged rows
+        stage_anchor(stage, 0, lane, s2.x, s2.y);
+        __builtin_amdgcn_wave_barrier();
+        u32x4 An[4];
+        read_operand(stage, lane, An);
+        for (int q = w; q < ng; q += 4) {
+            u32x4 X[4];
+            const int off = (blk_lo + kGroup * q + n) * kRowBytes + 16 * qq;
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk) X[kk] = row_load<kKeyBF16>(rsrc, off + 64 * kk);
+            const float ss = operand_sumsq(X);
+            const int tok = blk_lo + kGroup * q + n;
+            const float wn = tok < blk_hi ? inv_norm(ss) : 0.f;
+            const float knn = ss < 1e-24f ? sqrtf(ss) * 1e12f : 1.f;
+            const f32x4 AS = tile<4>(An, X);
+            const float as = neg_cos(wn * sum3(AS), knn, ssq);
+            __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(as), out_s, off_q0 + (blk_lo + kGroup * q) * 4, 0, 0);
+        }
+    }
+}
+
+int resident_tile_workgroups()
+{
+    static int cached = -1;                                          // benign if raced
+    if (cached < 0) {
+        int per_cu = 0, dev = 0;
+        hipDeviceProp_t prop;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, scan_tile_kernel, 64 * kTileWaves, 0) != hipSuccess ||
+            hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess)
+            return 0;
+        cached = per_cu * prop.multiProcessorCount;
+    }
+    return cached;
+}
+
+}  // namespace
+
+bool tile_score_supported(int dtype, int d, int window, const PromptTab &tab, int LH)
+{
+    if (dtype != NKV_DTYPE_BF16 || d != 128 || window != 64) return false;
+    int max_unit_blocks = 0;
+    for (int p = 0; p < tab.n; ++p) {
+        if (tab.b[p] > 256) return false;
+        if ((int64_t)(tab.tok_off[p + 1] - tab.tok_off[p] + 256) * d * 2 >= (1ll << 31)) return false;
+        max_unit_blocks = max(max_unit_blocks, tab.blk_off[p + 1] - tab.blk_off[p]);
+    }
+    const int64_t items = (int64_t)LH * (tab.blk_off[tab.n] + tab.n);
+    return items < (1ll << 28) && max_unit_blocks <= resident_tile_workgroups();
+}
+
+hipError_t launch_score_tile(const void *keys, const RowMap &km, int LH, const PromptTab &tab, float *a_raw, float *bsum,
+                             float *ssum, void *sync_area, int mode, const Prof &prof, hipStream_t st)
+{
+    constexpr int D = 128;
+    const bool no_unit_sums = mode == kScanRepairAll, defer_all = mode == kScanDeferAll || no_unit_sums;
+    const size_t nb = (size_t)LH * tab.blk_off[tab.n] * D / 4, ns = (size_t)LH * tab.n * D / 4;
+    const size_t n16 = kSyncWords / 4 + nb + ns;
+    prepare_kernel<<<(unsigned)min((n16 + 255) / 256, (size_t)2048), 256, 0, st>>>((uint4 *)sync_area, kSyncWords / 4,
+                                                                                 (uint4 *)bsum, nb, (uint4 *)ssum, ns);
+    ScanPlan plan;
+    const unsigned groups = fill_scan_plan(LH, tab, km.H, &plan);
+    prof.begin(NKV_KERNEL_SCAN, st);
+    scan_tile_kernel<<<groups, 64 * kTileWaves, 0, st>>>((const uint8_t *)keys, km, tab, plan, a_raw, bsum, ssum,
+                                                         (uint32_t *)sync_area, LH, (int64_t)LH * tab.T,
+                                                         defer_all ? -1 : kPollLimit, no_unit_sums ? 0u : kSpinLimit);
+    prof.end(NKV_KERNEL_SCAN, st);
+    unit_sum_repair_kernel<D, kTileWaves><<<LH * tab.n, 64 * kTileWaves, 0, st>>>(bsum, tab, ssum);
+    deferred_stable_tile_kernel<<<defer_all ? 4096 : 256, 64 * kTileWaves, 0, st>>>((const uint8_t *)keys, km, tab, ssum,
+                                                                                   (const uint32_t *)sync_area, a_raw);
+    return hipGetLastError();
+}
+
+}  // namespace nkv

@@ -124,6 +124,23 @@ def test_8bit_keys_of_every_finite_code(flags):
     _report(f"fp8 codes flags={flags}", st)
 
 
+TILE_CASES = ["below_window", "one_short_block", "block_tail", "b_between", "b_255", "ragged_small", "dv_differs",
+              "slice_edges", "nine_slices"]
+
+
+@pytest.mark.parametrize("route", [0, nkv.FLAG_DEFER_STABLE, nkv.FLAG_NO_UNIT_SUMS])
+@pytest.mark.parametrize("name", TILE_CASES)
+def test_matrix_core_scan(name, route):
+    """The matrix-core formulation of the fused scan on the sweep's bf16, d = 128 shapes, on its three routes (unit
+    sum found in time, every block deferred, every unit sum from the repair kernel), against the oracle."""
+    _, L, H, d, lens, dtype, dv = next(c for c in SWEEP if c[0] == name)
+    w = nkv_inputs.small_workload(name, L, H, d, lens, dtype=dtype, dv=dv, n_out=min(8, max(min(lens) - 4, 0)))
+    K, V = _kv(w)
+    st = compare_end_to_end(w, K, V, 0.5, params=nkv.params_default(flags=nkv.FLAG_MFMA_SCAN | route),
+                            label=f"tile {name} route={route}")
+    _report(f"tile {name} route={route}", st)
+
+
 LIMITS = [
     # the most prompts, head dims, heads and (layer, head) pairs a call accepts
     ("prompts_64", 1, 2, 64, [61 + 37 * (i % 9) + 500 * (i % 3 == 0) for i in range(64)], "bf16", 0),
