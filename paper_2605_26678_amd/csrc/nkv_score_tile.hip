@@ -42,6 +42,19 @@ constexpr int kPitch = 272;                      // bytes between the rows of a 
 constexpr int kStageBytes = kGroup * kPitch;
 constexpr int kTileWaves = 4;
 
+// Development aid (compiled in with -DNKV_TILE_STAMPS only): wave 0 of every workgroup adds the cycles it spent
+// between marks to 64-bit counters in the spare words of the sync area.
+#if defined(NKV_TILE_STAMPS) && NKV_TILE_STAMPS == 1
+#define NKV_STAMP(i)                                                                                         \
+    do {                                                                                                     \
+        const uint64_t now_ = __builtin_readcyclecounter();                                                  \
+        if (threadIdx.x == 0) atomicAdd(reinterpret_cast<unsigned long long *>(sync + 8) + (i), (unsigned long long)(now_ - stamp_)); \
+        stamp_ = now_;                                                                                       \
+    } while (0)
+#else
+#define NKV_STAMP(i) do { } while (0)
+#endif
+
 __device__ __forceinline__ f32x4 mma(const u32x4 &a, const u32x4 &b, f32x4 c)
 {
     return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
@@ -159,6 +172,58 @@ __device__ __forceinline__ float operand_sumsq(const u32x4 (&x)[4])
     return sum_over_rows16(acc);
 }
 
+// Sum of the squares of a lane's eight values of a row, ready to be read by any vector instruction (see above).
+__device__ __forceinline__ float piece_sumsq(const u32x4 &r)
+{
+    float acc = 0.f;
+    asm("v_dot2c_f32_bf16 %0, %1, %1\n\t"
+        "v_dot2c_f32_bf16 %0, %2, %2\n\t"
+        "v_dot2c_f32_bf16 %0, %3, %3\n\t"
+        "v_dot2c_f32_bf16 %0, %4, %4\n\t"
+        "s_nop 3"
+        : "+v"(acc)
+        : "v"(r.x), "v"(r.y), "v"(r.z), "v"(r.w));
+    return acc;
+}
+
+// One group of 16 tokens in row-wise layout (lane (g, c): rows 4g .. 4g+3, dims 8c .. 8c+7; tok0 = the group's
+// first token, which may lie in front of the prompt): ||k||^2 and the weight 1/||k|| of every row (0 for tokens
+// outside [0, tok_end)) go to ss_out / w_out, and to ww for this lane's own rows.
+__device__ __forceinline__ void group_norms(const u32x4 (&raw)[4], int tok0, int tok_end, int g, int c, float *w_out,
+                                            float *ss_out, float (&ww)[4])
+{
+    float ss[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        ss[j] = row_sum<16>(piece_sumsq(raw[j]));
+        const int tok = tok0 + 4 * g + j;
+        ww[j] = (tok >= 0 && tok < tok_end) ? inv_norm(ss[j]) : 0.f;
+    }
+    if (c == 0) {
+        *reinterpret_cast<float4 *>(w_out + 4 * g) = make_float4(ww[0], ww[1], ww[2], ww[3]);
+        *reinterpret_cast<float4 *>(ss_out + 4 * g) = make_float4(ss[0], ss[1], ss[2], ss[3]);
+    }
+}
+
+// The same, and the weighted sum of the group's rows to sum_out (D floats).
+__device__ __forceinline__ void group_sum(const u32x4 (&raw)[4], int tok0, int tok_end, int g, int c, float *w_out,
+                                          float *ss_out, float *sum_out)
+{
+    float ww[4];
+    group_norms(raw, tok0, tok_end, g, c, w_out, ss_out, ww);
+    float T[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) T[e] = 0.f;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        float k[8];
+        unpack8<kKeyBF16>(raw[j], k);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) T[e] = fmaf(ww[j], k[e], T[e]);
+    }
+    *reinterpret_cast<float2 *>(sum_out + 8 * c + 2 * g) = sum_over_rows16_transposing(T);
+}
+
 __device__ __forceinline__ float sum3(const f32x4 &d) { return (d[0] + d[1]) + d[2]; }
 
 // sum over this lane's four rows of wm[rho] * d[rho]
@@ -174,7 +239,7 @@ __device__ __forceinline__ void agent_store8(__amdgpu_buffer_rsrc_t rsrc, int by
 }
 
 // grid: the dies' queues of the fused pass (see nkv_score_fast.hip), 256 threads.
-__global__ __launch_bounds__(64 * kTileWaves, 3)
+__global__ __launch_bounds__(64 * kTileWaves, 4)
 void scan_tile_kernel(const uint8_t *__restrict__ keys, RowMap km, PromptTab tab, ScanPlan plan, float *__restrict__ a_raw,
                       float *__restrict__ bsum, float *__restrict__ ssum, uint32_t *__restrict__ sync, int LH,
                       int64_t rows, int poll_limit, uint32_t spin_limit)
@@ -183,6 +248,7 @@ void scan_tile_kernel(const uint8_t *__restrict__ keys, RowMap km, PromptTab tab
     __shared__ __attribute__((aligned(16))) uint8_t lds_stage[NW][kStageBytes];   // a wave's group on its way to operand layout, later its anchors
     __shared__ __attribute__((aligned(16))) float lds_T[4 + 16][D];               // group sums: 4 halo groups, then the block's
     __shared__ __attribute__((aligned(16))) float lds_w[NW][5][kGroup];           // 1/||k|| per token of a wave's groups (0: no such token)
+    __shared__ __attribute__((aligned(16))) float lds_ss[NW][5][kGroup];          // ||k||^2
     __shared__ __attribute__((aligned(16))) float lds_S[D];                       // the unit's sum, once complete
     __shared__ int s_have;
 
@@ -217,6 +283,11 @@ void scan_tile_kernel(const uint8_t *__restrict__ keys, RowMap km, PromptTab tab
             return;
         }
     }
+#ifdef NKV_TILE_STAMPS
+    uint64_t stamp_ = __builtin_readcyclecounter();
+    uint32_t rt_[4], rt_issue_ = 0, rt_data_ = 0;
+    rt_[0] = (uint32_t)__builtin_amdgcn_s_memrealtime();
+#endif
     const int p = prompt_of_block(tab, blk);
     const int b = tab.b[p];
     const int N = tab.tok_off[p + 1] - tab.tok_off[p];
@@ -230,13 +301,14 @@ void scan_tile_kernel(const uint8_t *__restrict__ keys, RowMap km, PromptTab tab
     const int qq = g, n = c;                                          // operand / result layout: token n, quarter qq
     uint8_t *stage = lds_stage[w];
 
-    // ---- first touch: this wave's groups, halo group first.  Rows outside the prompt read as zeros. ----
+    // ---- first touch: this wave's groups, then its group of the halo.  Rows outside the prompt read as zeros. ----
     const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<uint8_t *>(keys) + km.unit(layer, head, p, tab) * 2, 0, N * kRowBytes, 0x00020000);
     u32x4 raw[5][4];
-    bool ex[5];                                                       // group m - 1 of the chain exists
+    bool ex[5];                                                       // group m - 1 of the chain exists (m = 0: halo)
 #pragma unroll
-    for (int m = 0; m < 5; ++m) {
+    for (int mm = 0; mm < 5; ++mm) {
+        const int m = (mm + 1) % 5;                                   // the halo is needed last
         const int q = w + 4 * (m - 1);                                // block-local group index, < 0: halo
         ex[m] = q < ng;
         if (ex[m]) {
@@ -245,8 +317,45 @@ void scan_tile_kernel(const uint8_t *__restrict__ keys, RowMap km, PromptTab tab
             for (int j = 0; j < 4; ++j) raw[m][j] = row_load<kKeyBF16>(rsrc, off + j * kRowBytes);
         }
     }
+    NKV_STAMP(0);
+#ifdef NKV_TILE_STAMPS
+    rt_issue_ = (uint32_t)__builtin_amdgcn_s_memrealtime();
+#endif
 
-    // ---- per group: operand layout, norms, partial sum ----
+    // ---- the block's own groups: norms and partial sums, nothing else in front of the block total ----
+#pragma unroll
+    for (int m = 1; m < 5; ++m)
+        if (ex[m]) group_sum(raw[m], blk_lo + kGroup * (w + 4 * (m - 1)), blk_hi, g, c, lds_w[w][m], lds_ss[w][m], lds_T[4 + w + 4 * (m - 1)]);
+    NKV_STAMP(1);
+#ifdef NKV_TILE_STAMPS
+    rt_data_ = (uint32_t)__builtin_amdgcn_s_memrealtime();
+#endif
+    __syncthreads();
+    NKV_STAMP(2);
+
+    // ---- block total = episodic anchor (up to length); lane: dims 2 lane, 2 lane + 1 ----
+    const int unblk = tab.blk_off[p + 1] - tab.blk_off[p];
+    float *bsum_unit = bsum + ((int64_t)lh * nblk + tab.blk_off[p]) * D;
+    float *S_unit = ssum + ((int64_t)lh * tab.n + p) * D;
+    float bsq, b0 = 0.f, b1 = 0.f;
+    for (int q = 0; q < ng; ++q) {
+        const float2 t2 = *reinterpret_cast<const float2 *>(&lds_T[4 + q][2 * lane]);
+        b0 += t2.x;
+        b1 += t2.y;
+    }
+    if (w == blk % NW) {                                              // one wave stores the block total
+        const __amdgpu_buffer_rsrc_t brs = __builtin_amdgcn_make_buffer_rsrc(bsum_unit, 0, unblk * D * 4, 0x00020000);
+        agent_store8(brs, ((blk - tab.blk_off[p]) * D + 2 * lane) * 4, b0, b1);
+    }
+#ifdef NKV_TILE_STAMPS
+    rt_[1] = (uint32_t)__builtin_amdgcn_s_memrealtime();
+#endif
+    bsq = sum_over_rows16(row_sum<16>(fmaf(b0, b0, b1 * b1)));
+
+    // ---- the halo group's sum (the window sums in front of the block's first groups need it) ----
+    group_sum(raw[0], blk_lo + kGroup * (w - 4), blk_hi, g, c, lds_w[w][0], lds_ss[w][0], lds_T[w]);
+
+    // ---- every group through the staging rows into operand layout ----
     u32x4 X[5][4];
     float wv[5], ssv[5];                                              // 1/||k|| (0: no such token), ||k||^2 of token n
 #pragma unroll
@@ -254,56 +363,20 @@ void scan_tile_kernel(const uint8_t *__restrict__ keys, RowMap km, PromptTab tab
         wv[m] = 0.f;
         ssv[m] = 0.f;
         if (ex[m]) {
-            const int q = w + 4 * (m - 1);
 #pragma unroll
             for (int j = 0; j < 4; ++j) *reinterpret_cast<u32x4 *>(stage + (4 * g + j) * kPitch + 16 * c) = raw[m][j];
             __builtin_amdgcn_wave_barrier();
             read_operand(stage, lane, X[m]);
-            const float ss = operand_sumsq(X[m]);
-            const int tok = blk_lo + kGroup * q + n;
-            wv[m] = (tok >= 0 && tok < blk_hi) ? inv_norm(ss) : 0.f;
-            ssv[m] = ss;
-            if (qq == 0) lds_w[w][m][n] = wv[m];
-            __builtin_amdgcn_wave_barrier();
-            const float4 w4 = *reinterpret_cast<const float4 *>(&lds_w[w][m][4 * g]);
-            const float ww[4] = {w4.x, w4.y, w4.z, w4.w};
-            float T[8];
-#pragma unroll
-            for (int e = 0; e < 8; ++e) T[e] = 0.f;
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                float k[8];
-                unpack8<kKeyBF16>(raw[m][j], k);
-#pragma unroll
-                for (int e = 0; e < 8; ++e) T[e] = fmaf(ww[j], k[e], T[e]);
-            }
-            const float2 t2 = sum_over_rows16_transposing(T);
-            *reinterpret_cast<float2 *>(&lds_T[4 + q][8 * c + 2 * g]) = t2;
+            wv[m] = lds_w[w][m][n];
+            ssv[m] = lds_ss[w][m][n];
             __builtin_amdgcn_wave_barrier();                          // the next group reuses the staging rows
         }
     }
-    __syncthreads();
+    stage_anchor(stage, 4, lane, b0, b1);                             // rows 4 .. 6: the block total's three terms
+    NKV_STAMP(3);
+    __syncthreads();                                                  // the halo groups' sums
 
-    // ---- block total = episodic anchor (up to length); lane: dims 2 lane, 2 lane + 1 ----
-    const int unblk = tab.blk_off[p + 1] - tab.blk_off[p];
-    float *bsum_unit = bsum + ((int64_t)lh * nblk + tab.blk_off[p]) * D;
-    float *S_unit = ssum + ((int64_t)lh * tab.n + p) * D;
-    float bsq;
-    {
-        float b0 = 0.f, b1 = 0.f;
-        for (int q = 0; q < ng; ++q) {
-            const float2 t2 = *reinterpret_cast<const float2 *>(&lds_T[4 + q][2 * lane]);
-            b0 += t2.x;
-            b1 += t2.y;
-        }
-        bsq = sum_over_rows16(row_sum<16>(fmaf(b0, b0, b1 * b1)));
-        if (w == blk % NW) {                                          // one wave stores the block total
-            const __amdgpu_buffer_rsrc_t brs = __builtin_amdgcn_make_buffer_rsrc(bsum_unit, 0, unblk * D * 4, 0x00020000);
-            agent_store8(brs, ((blk - tab.blk_off[p]) * D + 2 * lane) * 4, b0, b1);
-        }
-        stage_anchor(stage, 4, lane, b0, b1);                         // rows 4 .. 6: the block total's three terms
-    }
-
+    NKV_STAMP(4);
     // ---- the chain of this wave's groups ----
     // lane (qq, n) of a result holds rows 4 qq + rho, column n.  Masked weights of the rows: rows j <= n count.
     const __amdgpu_buffer_rsrc_t out_c = __builtin_amdgcn_make_buffer_rsrc(a_raw + 2 * rows + row0, 0, blk_hi * 4, 0x00020000);
@@ -377,6 +450,7 @@ void scan_tile_kernel(const uint8_t *__restrict__ keys, RowMap km, PromptTab tab
         }
     }
 
+    NKV_STAMP(5);
     // ---- stable dots against the unit's sum ----
     const __amdgpu_buffer_rsrc_t srs = __builtin_amdgcn_make_buffer_rsrc(S_unit, 0, D * 4, 0x00020000);
     if (w == 0) {                                                     // 16 lanes poll, the other waves sit at the barrier
@@ -402,6 +476,10 @@ void scan_tile_kernel(const uint8_t *__restrict__ keys, RowMap km, PromptTab tab
         }
     }
     __syncthreads();
+#ifdef NKV_TILE_STAMPS
+    rt_[2] = (uint32_t)__builtin_amdgcn_s_memrealtime();
+#endif
+    NKV_STAMP(6);
     if (s_have != 0) {
         const float2 s2 = *reinterpret_cast<const float2 *>(&lds_S[2 * lane]);
         const float ssq = sum_over_rows16(row_sum<16>(fmaf(s2.x, s2.x, s2.y * s2.y)));
@@ -420,6 +498,17 @@ void scan_tile_kernel(const uint8_t *__restrict__ keys, RowMap km, PromptTab tab
             }
         }
     }
+    NKV_STAMP(7);
+#ifdef NKV_TILE_STAMPS
+    rt_[3] = (uint32_t)__builtin_amdgcn_s_memrealtime();
+    if (threadIdx.x == 0 && blk_hi - blk_lo >= 8) {                   // development aid: the block's times replace four a_s values
+        float *dbg = a_raw + row0 + blk_lo;
+        for (int i = 0; i < 4; ++i) dbg[i] = __uint_as_float(rt_[i]);
+        dbg[4] = __uint_as_float((uint32_t)s_have);
+        dbg[5] = __uint_as_float(rt_issue_);
+        dbg[6] = __uint_as_float(rt_data_);
+    }
+#endif
 }
 
 // a_s of the blocks whose workgroups did not wait for their unit's sum: the same operands (loaded in operand
@@ -432,10 +521,11 @@ __global__ __launch_bounds__(64 * kTileWaves) void deferred_stable_tile_kernel(c
 {
     constexpr int D = 128, NW = kTileWaves, kRowBytes = D * 2;
     __shared__ __attribute__((aligned(16))) uint8_t lds_stage[NW][kStageBytes];
+    __shared__ __attribute__((aligned(16))) float lds_w[NW][kGroup], lds_ss[NW][kGroup];
     const int nblk = tab.blk_off[tab.n];
     const uint32_t count = sync[kDeferCountWord];
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
-    const int qq = lane >> 4, n = lane & 15;
+    const int qq = lane >> 4, n = lane & 15, g = qq, c = n;
     uint8_t *stage = lds_stage[w];
     constexpr int kNoStore = 0x40000000;
     const int off_q0 = qq == 0 ? 4 * n : kNoStore;
@@ -457,17 +547,22 @@ __global__ __launch_bounds__(64 * kTileWaves) void deferred_stable_tile_kernel(c
         u32x4 An[4];
         read_operand(stage, lane, An);
         for (int q = w; q < ng; q += 4) {
-            u32x4 X[4];
-            const int off = (blk_lo + kGroup * q + n) * kRowBytes + 16 * qq;
+            const int tok0 = blk_lo + kGroup * q;
+            u32x4 raw[4], X[4];                                       // the group row-wise (norms) and as an operand
+            const int roff = (tok0 + 4 * g) * kRowBytes + 16 * c, off = (tok0 + n) * kRowBytes + 16 * qq;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) raw[j] = row_load<kKeyBF16>(rsrc, roff + j * kRowBytes);
 #pragma unroll
             for (int kk = 0; kk < 4; ++kk) X[kk] = row_load<kKeyBF16>(rsrc, off + 64 * kk);
-            const float ss = operand_sumsq(X);
-            const int tok = blk_lo + kGroup * q + n;
-            const float wn = tok < blk_hi ? inv_norm(ss) : 0.f;
+            float ww[4];
+            group_norms(raw, tok0, blk_hi, g, c, lds_w[w], lds_ss[w], ww);
+            __builtin_amdgcn_wave_barrier();
+            const float wn = lds_w[w][n], ss = lds_ss[w][n];
+            __builtin_amdgcn_wave_barrier();                          // the next group rewrites them
             const float knn = ss < 1e-24f ? sqrtf(ss) * 1e12f : 1.f;
             const f32x4 AS = tile<4>(An, X);
             const float as = neg_cos(wn * sum3(AS), knn, ssq);
-            __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(as), out_s, off_q0 + (blk_lo + kGroup * q) * 4, 0, 0);
+            __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(as), out_s, off_q0 + tok0 * 4, 0, 0);
         }
     }
 }
