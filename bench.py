@@ -140,7 +140,7 @@ def main():
     ap.add_argument("--cpu-layers", type=int, default=0, help="layers the oracle is timed on (0 = choose)")
     ap.add_argument("--generic", action="store_true", help="force the shape-generic scoring kernels")
     ap.add_argument("--two-pass", action="store_true", help="stable anomaly in a second pass over the keys")
-    ap.add_argument("--mfma", action="store_true", help="matrix-core formulation of the fused scan")
+    ap.add_argument("--vector-scan", action="store_true", help="vector-unit formulation of the fused scan also where the matrix-core one applies")
     ap.add_argument("--per-layer", action="store_true",
                     help="a step is L passes with L = 1, one per layer's K/V slice, as a prefill loop would call it")
     ap.add_argument("--layer-tensors", action="store_true",
@@ -170,7 +170,7 @@ def main():
     shape = nkv.Shape(w.L, w.H, w.d, w.d_v, dtype, w.cu_seqlens)
     params = nkv.params_default(flags=(nkv.FLAG_GENERIC_KERNELS if args.generic else 0)
                                 | (nkv.FLAG_TWO_PASS_STABLE if args.two_pass else 0)
-                                | (nkv.FLAG_MFMA_SCAN if args.mfma else 0))
+                                | (nkv.FLAG_VECTOR_SCAN if args.vector_scan else 0))
     r_list = [r] * shape.n_prompts
     if args.per_layer:
         shape1 = nkv.Shape(1, w.H, w.d, w.d_v, shape.dtype, w.cu_seqlens)

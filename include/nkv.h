@@ -77,8 +77,9 @@ enum {
                                       /* instead of the slice-wise ones                                      */
     NKV_FLAG_STATS_PER_HEAD = 32u,    /* nkv_score: the same choice for the per-head statistics              */
     NKV_FLAG_SELECT_PER_HEAD = 64u,   /* nkv_select_compact: the same choice for the top-B_h selection       */
-    NKV_FLAG_MFMA_SCAN = 128u         /* streaming kernels, bf16: the matrix-core formulation of the fused   */
-                                      /* pass                                                                */
+    NKV_FLAG_VECTOR_SCAN = 128u       /* streaming kernels: the vector-unit formulation of the fused pass    */
+                                      /* also for bf16 keys of head dim 128, where the matrix-core one is   */
+                                      /* the default                                                         */
 };
 /* Kernels a caller can ask to have timed, see nkv_params.prof_start. */
 enum {

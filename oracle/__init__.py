@@ -35,7 +35,8 @@ def build(force: bool = False) -> str:
 class _Params(C.Structure):
     _fields_ = [("window", C.c_int32), ("block_div", C.c_int32), ("block_min", C.c_int32),
                 ("block_max", C.c_int32), ("n_sink", C.c_int32), ("gate_mode", C.c_int32),
-                ("surprise_mode", C.c_int32), ("std_ddof", C.c_int32), ("top_frac", C.c_double),
+                ("surprise_mode", C.c_int32), ("std_ddof", C.c_int32), ("scale_mask", C.c_int32), ("pad_", C.c_int32),
+                ("top_frac", C.c_double),
                 ("prior", C.c_double * 3), ("beta", C.c_double), ("tau", C.c_double), ("kappa", C.c_double)]
 
 
@@ -54,6 +55,7 @@ class Params:
     gate_mode: int = 0
     surprise_mode: int = 0
     std_ddof: int = 0
+    scale_mask: int = 7       # bits 0..2: stable, episodic, current take part
     top_frac: float = 0.10
     prior: Tuple[float, float, float] = (0.4, 0.4, 0.2)
     beta: float = 3.0
@@ -64,7 +66,7 @@ class Params:
     def _c(self) -> _Params:
         p = _Params()
         for n in ("window", "block_div", "block_min", "block_max", "n_sink", "gate_mode", "surprise_mode",
-                  "std_ddof", "top_frac", "beta", "tau", "kappa"):
+                  "std_ddof", "scale_mask", "top_frac", "beta", "tau", "kappa"):
             setattr(p, n, getattr(self, n))
         p.prior = (C.c_double * 3)(*self.prior)
         return p

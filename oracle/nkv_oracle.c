@@ -23,6 +23,9 @@
  *     zeros (a division by such a range would only amplify rounding noise);
  *   - top/bottom sets of the reliability gap hold m_p = max(1, floor(p*N+1e-9));
  *   - std is the population one (ddof = 0) unless told otherwise;
+ *   - scale_mask (bit k set: scale k takes part; stable, episodic, current = bits 0, 1, 2): a scale that is
+ *     switched off is left out of the blend (the softmax runs over the others), of the winner and of the
+ *     standard deviation alike: the Appendix's component ablation "Stable + episodic (no current)" is mask 3;
  *   - surprise_mode 0: min-max within the head, subtract the head mean, clamp
  *     at zero (Appendix A), then gate; surprise_mode 1: gate the raw std
  *     (Section 2.4 taken literally);
@@ -56,6 +59,8 @@ typedef struct {
     int32_t gate_mode;     /* 0 surprise gate, 1 only average, 2 only max    */
     int32_t surprise_mode; /* see header                                     */
     int32_t std_ddof;      /* 0 population, 1 sample                         */
+    int32_t scale_mask;    /* bits 0..2: stable, episodic, current take part */
+    int32_t pad_;
     double top_frac;       /* p = 0.10, Section 2.4                          */
     double prior[3];       /* (0.4, 0.4, 0.2) order stable, episodic, current*/
     double beta, tau, kappa; /* 3.0, 0.60, 10.0, Appendix A                  */
@@ -80,6 +85,7 @@ void nkvo_params_default(nkvo_params *p)
 {
     p->window = 64; p->block_div = 32; p->block_min = 128; p->block_max = 256;
     p->n_sink = 4; p->gate_mode = 0; p->surprise_mode = 0; p->std_ddof = 0;
+    p->scale_mask = 7; p->pad_ = 0;
     p->top_frac = 0.10;
     p->prior[0] = 0.4; p->prior[1] = 0.4; p->prior[2] = 0.2;
     p->beta = 3.0; p->tau = 0.60; p->kappa = 10.0;
@@ -206,8 +212,10 @@ static int score_head(const float *K, int64_t N, int d, const nkvo_params *p, fl
         if (dbg && dbg->a_tilde) memcpy(dbg->a_tilde + ((size_t)k * H + h) * N, at[k], sizeof(double) * N);
     }
 
-    /* Section 2.4: reliability gaps and head-adaptive weights. */
+    /* Section 2.4: reliability gaps and head-adaptive weights, over the scales that take part. */
     const int64_t mp = nkvo_m_p(N, p->top_frac) > N ? N : nkvo_m_p(N, p->top_frac);
+    int on[3], n_on = 0;
+    for (int k = 0; k < 3; ++k) { on[k] = (p->scale_mask >> k) & 1; n_on += on[k]; }
     double delta[3], w[3], z[3], zmax = -INFINITY, zsum = 0.0;
     for (int k = 0; k < 3; ++k) {
         memcpy(srt, at[k], sizeof(double) * N);
@@ -215,19 +223,21 @@ static int score_head(const float *K, int64_t N, int d, const nkvo_params *p, fl
         double top = 0.0, bot = 0.0;
         for (int64_t j = 0; j < mp; ++j) { bot += srt[j]; top += srt[N - 1 - j]; }
         delta[k] = top / (double)mp - bot / (double)mp;
-        z[k] = log(p->prior[k]) + p->beta * delta[k];
+        z[k] = on[k] ? log(p->prior[k]) + p->beta * delta[k] : -INFINITY;
         if (z[k] > zmax) zmax = z[k];
     }
-    for (int k = 0; k < 3; ++k) { w[k] = exp(z[k] - zmax); zsum += w[k]; }
+    for (int k = 0; k < 3; ++k) { w[k] = on[k] ? exp(z[k] - zmax) : 0.0; zsum += w[k]; }
     for (int k = 0; k < 3; ++k) w[k] /= zsum;
     if (dbg && dbg->delta) memcpy(dbg->delta + (size_t)h * 3, delta, sizeof(delta));
     if (dbg && dbg->w) memcpy(dbg->w + (size_t)h * 3, w, sizeof(w));
 
-    /* Compression-induced surprise: std over the three normalised readings. */
+    /* Compression-induced surprise: std over the normalised readings that take part. */
     for (int64_t i = 0; i < N; ++i) {
-        double m = (at[0][i] + at[1][i] + at[2][i]) / 3.0, v = 0.0;
-        for (int k = 0; k < 3; ++k) v += (at[k][i] - m) * (at[k][i] - m);
-        s[i] = sqrt(v / (double)(3 - p->std_ddof));
+        double m = 0.0, v = 0.0;
+        for (int k = 0; k < 3; ++k) if (on[k]) m += at[k][i];
+        m /= (double)n_on;
+        for (int k = 0; k < 3; ++k) if (on[k]) v += (at[k][i] - m) * (at[k][i] - m);
+        s[i] = n_on - p->std_ddof > 0 ? sqrt(v / (double)(n_on - p->std_ddof)) : 0.0;
     }
     if (p->surprise_mode == 0) {
         minmax_normalise(s, s, N);
@@ -239,10 +249,12 @@ static int score_head(const float *K, int64_t N, int d, const nkvo_params *p, fl
 
     /* Routed score. */
     for (int64_t i = 0; i < N; ++i) {
-        double blend = w[0] * at[0][i] + w[1] * at[1][i] + w[2] * at[2][i];
-        double win = at[0][i];
-        if (at[1][i] > win) win = at[1][i];
-        if (at[2][i] > win) win = at[2][i];
+        double blend = 0.0, win = -INFINITY;
+        for (int k = 0; k < 3; ++k) {
+            if (!on[k]) continue;
+            blend += w[k] * at[k][i];
+            if (at[k][i] > win) win = at[k][i];
+        }
         double alpha = 1.0 / (1.0 + exp(-p->kappa * (s[i] - p->tau)));
         double star;
         if (p->gate_mode == 1) star = blend;
@@ -266,7 +278,7 @@ static int score_head(const float *K, int64_t N, int d, const nkvo_params *p, fl
 int nkvo_score_layer(const float *keys, int H, int64_t N, int d, const nkvo_params *p,
                      float *scores, const nkvo_debug *dbg)
 {
-    if (!keys || !p || !scores || H < 1 || N < 1 || d < 1) return -2;
+    if (!keys || !p || !scores || H < 1 || N < 1 || d < 1 || (p->scale_mask & 7) == 0) return -2;
     int err = 0;
 #pragma omp parallel for schedule(dynamic, 1)
     for (int h = 0; h < H; ++h) {

@@ -24,7 +24,7 @@ FLAG_DEFER_STABLE = 4
 FLAG_NO_UNIT_SUMS = 8
 FLAG_BUDGET_PER_HEAD = 16
 FLAG_STATS_PER_HEAD = 32
-FLAG_MFMA_SCAN = 128
+FLAG_VECTOR_SCAN = 128
 FLAG_SELECT_PER_HEAD = 64
 PIN = 3.0e38
 

@@ -179,7 +179,7 @@ int run_raw(const void *keys, const nkv_shape *s, const nkv_params *p, const Pro
     const int mode = (p->flags & NKV_FLAG_TWO_PASS_STABLE)  ? kScanTwoPass
                      : (p->flags & NKV_FLAG_NO_UNIT_SUMS)  ? kScanRepairAll
                      : (p->flags & NKV_FLAG_DEFER_STABLE)  ? kScanDeferAll : kScanFused;
-    if (!(p->flags & NKV_FLAG_GENERIC_KERNELS) && (p->flags & NKV_FLAG_MFMA_SCAN) && mode != kScanTwoPass &&
+    if (!(p->flags & NKV_FLAG_GENERIC_KERNELS) && !(p->flags & NKV_FLAG_VECTOR_SCAN) && mode != kScanTwoPass &&
         tile_score_supported(s->dtype, s->d, p->window, tab, LH))
         e = launch_score_tile(keys, km, LH, tab, a_raw, (float *)(ws + lay.bsum), (float *)(ws + lay.ssum), ws + lay.sync,
                               mode, prof, st);

@@ -42,18 +42,6 @@ constexpr int kPitch = 272;                      // bytes between the rows of a 
 constexpr int kStageBytes = kGroup * kPitch;
 constexpr int kTileWaves = 4;
 
-// Development aid (compiled in with -DNKV_TILE_STAMPS only): wave 0 of every workgroup adds the cycles it spent
-// between marks to 64-bit counters in the spare words of the sync area.
-#if defined(NKV_TILE_STAMPS) && NKV_TILE_STAMPS == 1
-#define NKV_STAMP(i)                                                                                         \
-    do {                                                                                                     \
-        const uint64_t now_ = __builtin_readcyclecounter();                                                  \
-        if (threadIdx.x == 0) atomicAdd(reinterpret_cast<unsigned long long *>(sync + 8) + (i), (unsigned long long)(now_ - stamp_)); \
-        stamp_ = now_;                                                                                       \
-    } while (0)
-#else
-#define NKV_STAMP(i) do { } while (0)
-#endif
 
 __device__ __forceinline__ f32x4 mma(const u32x4 &a, const u32x4 &b, f32x4 c)
 {
@@ -283,11 +271,6 @@ void scan_tile_kernel(const uint8_t *__restrict__ keys, RowMap km, PromptTab tab
             return;
         }
     }
-#ifdef NKV_TILE_STAMPS
-    uint64_t stamp_ = __builtin_readcyclecounter();
-    uint32_t rt_[4], rt_issue_ = 0, rt_data_ = 0;
-    rt_[0] = (uint32_t)__builtin_amdgcn_s_memrealtime();
-#endif
     const int p = prompt_of_block(tab, blk);
     const int b = tab.b[p];
     const int N = tab.tok_off[p + 1] - tab.tok_off[p];
@@ -317,21 +300,12 @@ void scan_tile_kernel(const uint8_t *__restrict__ keys, RowMap km, PromptTab tab
             for (int j = 0; j < 4; ++j) raw[m][j] = row_load<kKeyBF16>(rsrc, off + j * kRowBytes);
         }
     }
-    NKV_STAMP(0);
-#ifdef NKV_TILE_STAMPS
-    rt_issue_ = (uint32_t)__builtin_amdgcn_s_memrealtime();
-#endif
 
     // ---- the block's own groups: norms and partial sums, nothing else in front of the block total ----
 #pragma unroll
     for (int m = 1; m < 5; ++m)
         if (ex[m]) group_sum(raw[m], blk_lo + kGroup * (w + 4 * (m - 1)), blk_hi, g, c, lds_w[w][m], lds_ss[w][m], lds_T[4 + w + 4 * (m - 1)]);
-    NKV_STAMP(1);
-#ifdef NKV_TILE_STAMPS
-    rt_data_ = (uint32_t)__builtin_amdgcn_s_memrealtime();
-#endif
     __syncthreads();
-    NKV_STAMP(2);
 
     // ---- block total = episodic anchor (up to length); lane: dims 2 lane, 2 lane + 1 ----
     const int unblk = tab.blk_off[p + 1] - tab.blk_off[p];
@@ -347,9 +321,6 @@ void scan_tile_kernel(const uint8_t *__restrict__ keys, RowMap km, PromptTab tab
         const __amdgpu_buffer_rsrc_t brs = __builtin_amdgcn_make_buffer_rsrc(bsum_unit, 0, unblk * D * 4, 0x00020000);
         agent_store8(brs, ((blk - tab.blk_off[p]) * D + 2 * lane) * 4, b0, b1);
     }
-#ifdef NKV_TILE_STAMPS
-    rt_[1] = (uint32_t)__builtin_amdgcn_s_memrealtime();
-#endif
     bsq = sum_over_rows16(row_sum<16>(fmaf(b0, b0, b1 * b1)));
 
     // ---- the halo group's sum (the window sums in front of the block's first groups need it) ----
@@ -373,10 +344,7 @@ void scan_tile_kernel(const uint8_t *__restrict__ keys, RowMap km, PromptTab tab
         }
     }
     stage_anchor(stage, 4, lane, b0, b1);                             // rows 4 .. 6: the block total's three terms
-    NKV_STAMP(3);
     __syncthreads();                                                  // the halo groups' sums
-
-    NKV_STAMP(4);
     // ---- the chain of this wave's groups ----
     // lane (qq, n) of a result holds rows 4 qq + rho, column n.  Masked weights of the rows: rows j <= n count.
     const __amdgpu_buffer_rsrc_t out_c = __builtin_amdgcn_make_buffer_rsrc(a_raw + 2 * rows + row0, 0, blk_hi * 4, 0x00020000);
@@ -449,8 +417,6 @@ void scan_tile_kernel(const uint8_t *__restrict__ keys, RowMap km, PromptTab tab
             __builtin_amdgcn_sched_barrier(0);                        // one group at a time
         }
     }
-
-    NKV_STAMP(5);
     // ---- stable dots against the unit's sum ----
     const __amdgpu_buffer_rsrc_t srs = __builtin_amdgcn_make_buffer_rsrc(S_unit, 0, D * 4, 0x00020000);
     if (w == 0) {                                                     // 16 lanes poll, the other waves sit at the barrier
@@ -476,10 +442,6 @@ void scan_tile_kernel(const uint8_t *__restrict__ keys, RowMap km, PromptTab tab
         }
     }
     __syncthreads();
-#ifdef NKV_TILE_STAMPS
-    rt_[2] = (uint32_t)__builtin_amdgcn_s_memrealtime();
-#endif
-    NKV_STAMP(6);
     if (s_have != 0) {
         const float2 s2 = *reinterpret_cast<const float2 *>(&lds_S[2 * lane]);
         const float ssq = sum_over_rows16(row_sum<16>(fmaf(s2.x, s2.x, s2.y * s2.y)));
@@ -498,17 +460,6 @@ void scan_tile_kernel(const uint8_t *__restrict__ keys, RowMap km, PromptTab tab
             }
         }
     }
-    NKV_STAMP(7);
-#ifdef NKV_TILE_STAMPS
-    rt_[3] = (uint32_t)__builtin_amdgcn_s_memrealtime();
-    if (threadIdx.x == 0 && blk_hi - blk_lo >= 8) {                   // development aid: the block's times replace four a_s values
-        float *dbg = a_raw + row0 + blk_lo;
-        for (int i = 0; i < 4; ++i) dbg[i] = __uint_as_float(rt_[i]);
-        dbg[4] = __uint_as_float((uint32_t)s_have);
-        dbg[5] = __uint_as_float(rt_issue_);
-        dbg[6] = __uint_as_float(rt_data_);
-    }
-#endif
 }
 
 // a_s of the blocks whose workgroups did not wait for their unit's sum: the same operands (loaded in operand

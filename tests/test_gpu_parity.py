@@ -130,15 +130,17 @@ TILE_CASES = ["below_window", "one_short_block", "block_tail", "b_between", "b_2
 
 @pytest.mark.parametrize("route", [0, nkv.FLAG_DEFER_STABLE, nkv.FLAG_NO_UNIT_SUMS])
 @pytest.mark.parametrize("name", TILE_CASES)
-def test_matrix_core_scan(name, route):
-    """The matrix-core formulation of the fused scan on the sweep's bf16, d = 128 shapes, on its three routes (unit
-    sum found in time, every block deferred, every unit sum from the repair kernel), against the oracle."""
+def test_vector_scan_where_the_matrix_core_scan_is_the_default(name, route):
+    """bf16 keys of head dim 128 take the matrix-core formulation of the fused scan by default (the sweep and the
+    named workloads exercise it); the vector-unit formulation, forced by flag, on the same shapes and on its
+    three routes (unit sum found in time, every block deferred, every unit sum from the repair kernel), against
+    the oracle."""
     _, L, H, d, lens, dtype, dv = next(c for c in SWEEP if c[0] == name)
     w = nkv_inputs.small_workload(name, L, H, d, lens, dtype=dtype, dv=dv, n_out=min(8, max(min(lens) - 4, 0)))
     K, V = _kv(w)
-    st = compare_end_to_end(w, K, V, 0.5, params=nkv.params_default(flags=nkv.FLAG_MFMA_SCAN | route),
-                            label=f"tile {name} route={route}")
-    _report(f"tile {name} route={route}", st)
+    st = compare_end_to_end(w, K, V, 0.5, params=nkv.params_default(flags=nkv.FLAG_VECTOR_SCAN | route),
+                            label=f"vector {name} route={route}")
+    _report(f"vector {name} route={route}", st)
 
 
 LIMITS = [

@@ -242,6 +242,64 @@ def test_std_convention_is_immaterial_after_minmax():
     np.testing.assert_allclose(s0[:, 4:], s1[:, 4:], atol=1e-7)
 
 
+def test_two_scale_variant_is_the_two_reading_computation():
+    """Appendix "Component and Scale Ablations", row "Stable + episodic (no current)": with the current scale
+    switched off (scale_mask 3) blend, winner and surprise are those of the two remaining readings -- scipy
+    softmax over two logits, numpy maximum and numpy std over two rows, scipy expit gate.  The reading of the
+    switched-off scale must not enter anywhere: replacing it changes nothing."""
+    keys = _rand_keys(2, 900, 16, seed=31)
+    p = Params(scale_mask=3)
+    s, dbg = oracle.score_layer(keys, p, debug=("a_tilde", "delta", "w"))
+    at = dbg["a_tilde"][:2]                                  # stable, episodic
+    w = scipy.special.softmax(np.log([0.4, 0.4])[None, :] + p.beta * dbg["delta"][:, :2], axis=1)
+    np.testing.assert_allclose(dbg["w"][:, :2], w, atol=1e-15)
+    np.testing.assert_array_equal(dbg["w"][:, 2], 0.0)
+    blend = np.einsum("hk,khn->hn", w, at)
+    win = np.maximum(at[0], at[1])
+    sd = np.std(at, axis=0)                                  # population std of two numbers = |x - y| / 2
+    np.testing.assert_allclose(sd, np.abs(at[0] - at[1]) / 2, atol=1e-15)
+    sd = (sd - sd.min(1, keepdims=True)) / np.ptp(sd, axis=1, keepdims=True)
+    sp = np.maximum(sd - sd.mean(1, keepdims=True), 0.0)
+    alpha = scipy.special.expit(p.kappa * (sp - p.tau))
+    star = (1 - alpha) * blend + alpha * win
+    np.testing.assert_allclose(s[:, 4:], star[:, 4:], atol=1e-7)
+    # the switched-off reading does not enter: window 1 makes every current anomaly -1 (a flat scale)
+    s_flat, _ = oracle.score_layer(keys, Params(scale_mask=3, window=1))
+    np.testing.assert_array_equal(s, s_flat)
+    # and it differs from merely giving the scale a zero prior weight, which still lets it win and surprise
+    s_prior0, _ = oracle.score_layer(keys, Params(prior=(0.4, 0.4, 0.0)))
+    assert np.abs(s_prior0[:, 4:] - s[:, 4:]).max() > 1e-3
+    # all three scales on is the default, bit for bit
+    np.testing.assert_array_equal(oracle.score_layer(keys, Params(scale_mask=7))[0], oracle.score_layer(keys)[0])
+
+
+def test_single_scale_mask_is_the_single_anchor_score():
+    """One scale left: std of one reading is 0, blend = winner = that reading ("Single-scale stable score")."""
+    keys = _rand_keys(1, 300, 16, seed=32)
+    for k in range(3):
+        s, dbg = oracle.score_layer(keys, Params(scale_mask=1 << k, n_sink=0), debug=("a_tilde",))
+        np.testing.assert_allclose(s[0], dbg["a_tilde"][k, 0], atol=1e-7)
+    with pytest.raises(RuntimeError):
+        oracle.score_layer(keys, Params(scale_mask=0))
+
+
+def test_flat_range_rule():
+    """Min-max of a range below 1e-6 gives all zeros, of a range above it the plain (a - min) / (max - min).
+    The bound is this build's own constant (the paper says only "min-max normalized within its head").  Keys on
+    a narrow arc of the unit circle make the spread of a scale as small as wanted: for angles within +-t of the
+    mean direction the stable anomalies -cos span about t^2 / 2."""
+    for t, flat in ((1.0e-3, True), (2.5e-3, False)):         # ranges ~5e-7 and ~3e-6
+        ang = np.linspace(-t, t, 41)
+        keys = np.stack([np.cos(ang), np.sin(ang)], axis=-1)[None].astype(np.float32)
+        p = Params(block_div=1000, block_min=64, block_max=64, window=41, n_sink=0)
+        _, dbg = oracle.score_layer(keys, p, debug=("a_raw", "a_tilde"))
+        a = dbg["a_raw"][0, 0]
+        rng_ = a.max() - a.min()
+        assert (rng_ < 1e-6) == flat, rng_
+        want = np.zeros_like(a) if flat else (a - a.min()) / (a.max() - a.min())
+        np.testing.assert_allclose(dbg["a_tilde"][0, 0], want, atol=1e-12)
+
+
 # --------------------------------------------------------------------------- special cases (ablation variants)
 def test_single_anchor_variant_is_minmaxed_negative_cosine_to_mean():
     """Prior (1,0,0), beta = 0, 'only average' -> the single-anchor key-distinctiveness score of the
