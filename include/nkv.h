@@ -115,7 +115,11 @@ typedef struct nkv_params {
     int32_t  surprise_mode;   /* NORMALISED: min-max within the head, mean-centre, rectify, then   */
                               /* gate (Appendix A); RAW: gate the std itself (Section 2.4 literal) */
     uint32_t flags;           /* NKV_FLAG_*                                                        */
-    int32_t  reserved;
+    int32_t  scale_mask;      /* bit 0 / 1 / 2 set: the stable / episodic / current scale takes part; 0 is  */
+                              /* read as 7 (all three).  A scale that is off is left out of the blend, the   */
+                              /* winner and the standard deviation alike: 3 is the Appendix's component     */
+                              /* ablation "Stable + episodic (no current)", 1 its "Single-scale stable       */
+                              /* score".  (A prior weight of 0 only removes a scale from the blend.)         */
     double   top_frac;        /* p = 0.10: top/bottom sets hold max(1, floor(p*N)) tokens          */
     double   prior[3];        /* (0.4, 0.4, 0.2): stable, episodic, current (Section 2.4)          */
     double   beta;            /* 3.0  blend temperature                                            */

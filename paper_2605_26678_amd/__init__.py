@@ -39,7 +39,7 @@ class nkv_params(C.Structure):
     _fields_ = [("struct_size", C.c_uint32), ("window", C.c_int32), ("block_div", C.c_int32),
                 ("block_min", C.c_int32), ("block_max", C.c_int32), ("n_sink", C.c_int32),
                 ("gate_mode", C.c_int32), ("surprise_mode", C.c_int32), ("flags", C.c_uint32),
-                ("reserved", C.c_int32), ("top_frac", C.c_double), ("prior", C.c_double * 3),
+                ("scale_mask", C.c_int32), ("top_frac", C.c_double), ("prior", C.c_double * 3),
                 ("beta", C.c_double), ("tau", C.c_double), ("kappa", C.c_double), ("safeguard", C.c_double),
                 ("near_tol", C.c_double), ("prof_start", C.c_void_p * 6), ("prof_stop", C.c_void_p * 6)]
 

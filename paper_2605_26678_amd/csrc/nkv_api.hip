@@ -26,7 +26,13 @@ int check_params(const nkv_params *p)
     if (!(p->top_frac > 0.0 && p->top_frac <= 1.0)) return NKV_EINVAL;
     for (int k = 0; k < 3; ++k)
         if (!(p->prior[k] >= 0.0) || !isfinite(p->prior[k])) return NKV_EINVAL;
-    if (!(p->prior[0] + p->prior[1] + p->prior[2] > 0.0)) return NKV_EINVAL;
+    if (p->scale_mask < 0 || p->scale_mask > 7) return NKV_EINVAL;
+    {
+        const int mask = p->scale_mask ? p->scale_mask : 7;
+        double on = 0.0;
+        for (int k = 0; k < 3; ++k) on += (mask >> k) & 1 ? p->prior[k] : 0.0;
+        if (!(on > 0.0)) return NKV_EINVAL;                           // the scales that take part need prior weight
+    }
     if (!isfinite(p->beta) || !isfinite(p->tau) || !isfinite(p->kappa)) return NKV_EINVAL;
     if (!(p->safeguard >= 0.0 && p->safeguard <= 1.0)) return NKV_EINVAL;
     if (!(p->near_tol >= 0.0) || !isfinite(p->near_tol)) return NKV_EINVAL;
@@ -251,6 +257,7 @@ int nkv_params_default(nkv_params *p)
     p->n_sink = 4;
     p->gate_mode = NKV_GATE_SURPRISE;
     p->surprise_mode = NKV_SURPRISE_NORMALISED;
+    p->scale_mask = 7;
     p->top_frac = 0.10;
     p->prior[0] = 0.4; p->prior[1] = 0.4; p->prior[2] = 0.2;
     p->beta = 3.0;
@@ -358,7 +365,9 @@ int nkv_score(const void *keys, const nkv_shape *shape, const nkv_params *params
     rc = run_raw(keys, shape, params, tab, a_raw, (char *)ws, lay, st);
     if (rc) return rc;
     LearnerConsts lc;
-    for (int k = 0; k < 3; ++k) lc.log_prior[k] = log(params->prior[k]);   // log 0 = -inf: scale switched off
+    lc.scale_mask = params->scale_mask ? params->scale_mask : 7;
+    for (int k = 0; k < 3; ++k)                                            // -inf: no weight in the blend
+        lc.log_prior[k] = (lc.scale_mask >> k) & 1 ? log(params->prior[k]) : -INFINITY;
     lc.beta = params->beta;
     lc.tau = (float)params->tau;
     lc.kappa = (float)params->kappa;

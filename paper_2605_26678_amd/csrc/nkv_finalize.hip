@@ -112,7 +112,7 @@ __global__ __launch_bounds__(kThreads) void finalize_kernel(const float *__restr
                 if (key < thr[2 * k + 1]) sums[2 * k + 1] += (double)av[k];
             }
             normalised(av, st, at);
-            const float s = std3(at);
+            const float s = surprise_std(at, lc.scale_mask);
             smin = fminf(smin, s);
             smax = fmaxf(smax, s);
             ssum += (double)s;
@@ -266,7 +266,7 @@ __global__ __launch_bounds__(kSelThreads) void route_kernel(const float *__restr
             if (i0 + q * kSelThreads < N) {
                 float at[3];
                 normalised(av[q], st, at);
-                const float s = std3(at);
+                const float s = surprise_std(at, lc.scale_mask);
                 smin = fminf(smin, s);
                 smax = fmaxf(smax, s);
                 ssum += (double)s;
@@ -315,7 +315,7 @@ hipError_t launch_finalize(const float *a_raw, int L, int H, const PromptTab &ta
         // Slice-wise kernels where a head has more than one slice (any length) or there are many units (their
         // 256-thread workgroups pack the chip four times as densely); for a few short units the per-head
         // kernels are quicker.
-        hipError_t e = launch_stats_wide(a_raw, L, H, tab, stats, wide_ws, st);
+        hipError_t e = launch_stats_wide(a_raw, L, H, tab, lc.scale_mask, stats, wide_ws, st);
         if (e != hipSuccess) return e;
         e = launch_route_wide(a_raw, L, H, tab, lc, stats, wide_ws, scores, st);
         if (e != hipSuccess) return e;

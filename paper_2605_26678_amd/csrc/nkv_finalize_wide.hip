@@ -166,7 +166,7 @@ __global__ __launch_bounds__(kWideThreads) void stats_pick_kernel(int L, int H, 
 // the ranges being known -- min, max and sum of the surprise statistic of the slice's tokens.
 __global__ __launch_bounds__(kWideThreads) void stats_collect_kernel(const float *__restrict__ a_raw, int64_t rows,
                                                                      int L, int H, PromptTab tab, SliceTab st,
-                                                                     int n_slices,
+                                                                     int n_slices, int scale_mask,
                                                                      const StatPick *__restrict__ picks,
                                                                      uint32_t *__restrict__ segTop,
                                                                      uint32_t *__restrict__ segBot,
@@ -226,7 +226,7 @@ __global__ __launch_bounds__(kWideThreads) void stats_collect_kernel(const float
                 const float raw[3] = {v[0][j], v[1][j], v[2][j]};
                 float at[3];
                 normalised(raw, hs, at);
-                const float sv = std3(at);
+                const float sv = surprise_std(at, scale_mask);
                 smin = fminf(smin, sv);
                 smax = fmaxf(smax, sv);
                 ssum32 += sv;
@@ -453,7 +453,7 @@ WideWs wide_ws(int L, int H, const PromptTab &tab)
 size_t stats_wide_ws_bytes(int L, int H, const PromptTab &tab) { return wide_ws(L, H, tab).total; }
 
 // Enqueues the four kernels that fill `stats`.
-hipError_t launch_stats_wide(const float *a_raw, int L, int H, const PromptTab &tab, float *stats, void *ws,
+hipError_t launch_stats_wide(const float *a_raw, int L, int H, const PromptTab &tab, int scale_mask, float *stats, void *ws,
                              hipStream_t st)
 {
     SliceTab stab;
@@ -470,7 +470,7 @@ hipError_t launch_stats_wide(const float *a_raw, int L, int H, const PromptTab &
     stats_hist_kernel<<<dim3((unsigned)slices, 3), kWideThreads, 0, st>>>(a_raw, rows, tab, stab, slices, part, sp);
     SliceSurprise *sur = (SliceSurprise *)(base + lay.sur);
     stats_pick_kernel<<<dim3(units, 3), kWideThreads, 0, st>>>(L, H, tab, stab, slices, part, sp, picks, failed);
-    stats_collect_kernel<<<(unsigned)slices, kWideThreads, 0, st>>>(a_raw, rows, L, H, tab, stab, slices, picks, segTop,
+    stats_collect_kernel<<<(unsigned)slices, kWideThreads, 0, st>>>(a_raw, rows, L, H, tab, stab, slices, scale_mask, picks, segTop,
                                                                    segBot, sp, sur, failed);
     stats_finish_kernel<<<dim3(units, 3), 64, 0, st>>>(a_raw, rows, L, H, tab, stab, slices, picks, segTop, segBot,
                                                        sp, failed, stats);

@@ -47,6 +47,7 @@ struct LearnerConsts {
     double beta;
     float tau, kappa;
     int32_t n_sink, gate_mode, surprise_mode;
+    int32_t scale_mask;                  // bit k set: scale k (stable, episodic, current) takes part
 };
 
 // Optional event pair around one kernel launch (nkv_params.prof_start / prof_stop).
@@ -109,7 +110,7 @@ hipError_t launch_finalize(const float *a_raw, int L, int H, const PromptTab &ta
                            hipStream_t st);
 // slice-wise statistics (nkv_finalize_wide.hip)
 size_t stats_wide_ws_bytes(int L, int H, const PromptTab &tab);
-hipError_t launch_stats_wide(const float *a_raw, int L, int H, const PromptTab &tab, float *stats, void *ws,
+hipError_t launch_stats_wide(const float *a_raw, int L, int H, const PromptTab &tab, int scale_mask, float *stats, void *ws,
                              hipStream_t st);
 hipError_t launch_route_wide(const float *a_raw, int L, int H, const PromptTab &tab, const LearnerConsts &lc,
                              const float *stats, void *ws, float *scores, hipStream_t st);

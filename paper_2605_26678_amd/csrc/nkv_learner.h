@@ -28,12 +28,25 @@ __device__ __forceinline__ float std3(const float at[3])
     return __builtin_amdgcn_sqrtf((x * x + y * y + z * z) * (1.0f / 3.0f));      // hardware square root, 1 ulp
 }
 
+// Population standard deviation over the readings of the scales that take part (Section 2.4; Appendix,
+// component ablation: a scale that is switched off is left out of blend, winner and deviation alike).
+// mask: bit k set = scale k takes part; uniform across a launch.
+__device__ __forceinline__ float surprise_std(const float at[3], int mask)
+{
+    if (mask == 7) return std3(at);
+    if (mask == 1 || mask == 2 || mask == 4) return 0.f;
+    const float x = at[mask & 1 ? 0 : 1], y = at[mask & 4 ? 2 : 1];
+    const float m = (x + y) * 0.5f, dx = x - m, dy = y - m;
+    return __builtin_amdgcn_sqrtf((dx * dx + dy * dy) * 0.5f);
+}
+
 // blend, surprise, gate and route of one token from its three normalised readings (Section 2.4)
 __device__ __forceinline__ float routed_score(const float at[3], const HeadStats &st, const LearnerConsts &lc)
 {
-    const float blend = st.w[0] * at[0] + st.w[1] * at[1] + st.w[2] * at[2];
-    const float win = fmaxf(at[0], fmaxf(at[1], at[2]));
-    float s = std3(at);
+    const float blend = st.w[0] * at[0] + st.w[1] * at[1] + st.w[2] * at[2];   // a scale that is off has weight 0
+    const int mask = lc.scale_mask;
+    const float win = fmaxf(mask & 1 ? at[0] : -INFINITY, fmaxf(mask & 2 ? at[1] : -INFINITY, mask & 4 ? at[2] : -INFINITY));
+    float s = surprise_std(at, mask);
     if (lc.surprise_mode == NKV_SURPRISE_NORMALISED) s = fmaxf((s - st.s_lo) * st.s_inv_range - st.s_mean, 0.f);
     // logistic gate with the hardware's base-2 exponential and reciprocal (1 ulp each; the argument is at
     // most a few tens, so alpha is good to ~1e-6)

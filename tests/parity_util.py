@@ -29,7 +29,7 @@ NEAR_BAND = 1e-5
 def oracle_params(params: nkv.nkv_params) -> oracle.Params:
     return oracle.Params(window=params.window, block_div=params.block_div, block_min=params.block_min,
                          block_max=params.block_max, n_sink=params.n_sink, gate_mode=params.gate_mode,
-                         surprise_mode=params.surprise_mode, top_frac=params.top_frac,
+                         surprise_mode=params.surprise_mode, scale_mask=params.scale_mask or 7, top_frac=params.top_frac,
                          prior=tuple(params.prior), beta=params.beta, tau=params.tau, kappa=params.kappa,
                          safeguard=params.safeguard)
 

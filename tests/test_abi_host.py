@@ -27,6 +27,7 @@ def test_params_default_are_the_papers_constants():
     assert (p.window, p.block_div, p.block_min, p.block_max, p.n_sink) == (64, 32, 128, 256, 4)
     assert list(p.prior) == [0.4, 0.4, 0.2]
     assert (p.beta, p.tau, p.kappa, p.safeguard, p.top_frac) == (3.0, 0.60, 10.0, 0.20, 0.10)
+    assert p.scale_mask == 7
     assert nkv.lib().nkv_params_default(None) == nkv.NKV_EINVAL
 
 
@@ -67,7 +68,7 @@ def test_argument_errors_are_reported_before_any_device_work():
     assert L.nkv_score(fake, C.byref(nkv.Shape(1, 2, 64, 64, 7, [0, 100]).c), C.byref(p), fake, fake, 1 << 30,
                        0) == nkv.NKV_EINVAL
     for field, val in (("window", 0), ("block_max", 1), ("gate_mode", 3), ("top_frac", 0.0), ("safeguard", 1.5),
-                       ("beta", float("nan")), ("struct_size", 8), ("n_sink", -1)):
+                       ("beta", float("nan")), ("struct_size", 8), ("n_sink", -1), ("scale_mask", 8), ("scale_mask", -1)):
         q = nkv.params_default(**{field: val})
         assert L.nkv_score(fake, C.byref(good.c), C.byref(q), fake, fake, 1 << 30, 0) == nkv.NKV_EINVAL, field
     # strided layouts: misaligned strides, overlapping units

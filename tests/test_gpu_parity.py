@@ -230,6 +230,7 @@ def test_statistics_routes_meet_the_score_bar(flags):
     w = nkv_inputs.small_workload("stat_routes", 1, 3, 128, [20000, 700, 16384])
     K, V = _kv(w)
     compare_end_to_end(w, K, V, 0.75, params=nkv.params_default(flags=flags), label=f"stats flags={flags}")
+    compare_end_to_end(w, K, V, 0.75, params=nkv.params_default(flags=flags, scale_mask=3), label=f"stats two scales flags={flags}")
     Kc = K.clone()
     Kc[:, 1] = Kc[:, 1, :1]                                   # head 1: one key repeated
     compare_end_to_end(w, Kc, V, 0.75, params=nkv.params_default(flags=flags), label=f"stats const flags={flags}")
@@ -283,6 +284,8 @@ VARIANTS = [
     dict(block_min=16, block_max=64, block_div=64),      # blocks of one wavefront
     dict(block_min=300, block_max=512), dict(top_frac=0.25, safeguard=0.5), dict(safeguard=1.0),
     dict(kappa=25.0, tau=0.2),
+    dict(scale_mask=3), dict(scale_mask=5), dict(scale_mask=6), dict(scale_mask=1), dict(scale_mask=4, gate_mode=2),
+    dict(scale_mask=3, surprise_mode=1), dict(scale_mask=0),
 ]
 
 
