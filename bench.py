@@ -248,6 +248,13 @@ def main():
     b.record(stream)
     torch.cuda.synchronize()
     roofline["copy_probe_GBs"] = round(2 * src.numel() * 10 / (a.elapsed_ms(b) * 1e-3) / 1e9, 1)
+    nkv.copy_probe(None, src, stream)                                  # the loads alone
+    a.record(stream)
+    for _ in range(10):
+        nkv.copy_probe(None, src, stream)
+    b.record(stream)
+    torch.cuda.synchronize()
+    roofline["read_probe_GBs"] = round(src.numel() * 10 / (a.elapsed_ms(b) * 1e-3) / 1e9, 1)
     del src, dst
 
     cpu = None

@@ -22,7 +22,9 @@
  *     A "unit" is one (prompt, layer, head); units are numbered
  *     u = (p * L + l) * H + h.
  *   - Calls only enqueue work on `hip_stream` (a hipStream_t, NULL = default
- *     stream) and never synchronise or allocate; the library keeps no state.
+ *     stream) and never synchronise or allocate.  The only state the library keeps is what it asked the
+ *     runtime once per process: the occupancy of its scan kernels (first nkv_score on a device) and, for
+ *     nkv_budget_noalloc, the address of its static scratch array.
  *     Scratch memory is the caller's `ws` (device, 256-byte aligned, at least
  *     nkv_workspace_bytes() bytes); its contents are undefined afterwards.
  *     The calls can be recorded into a HIP graph; nkv_score asks the runtime for a
@@ -133,6 +135,12 @@ typedef struct nkv_params {
     /* after that launch.  The caller owns the events and reads them after synchronising.              */
     void    *prof_start[NKV_KERNEL_COUNT];
     void    *prof_stop[NKV_KERNEL_COUNT];
+    /* Optional health counters of the fused streaming scan: NULL, or a DEVICE pointer to two uint32 that        */
+    /* nkv_score / nkv_score_raw fill on their stream: [0] workgroups that gave up adding a unit's block totals  */
+    /* up inside the pass (the unit's sum was then formed afterwards; 0 in normal operation), [1] blocks whose   */
+    /* stable anomaly was computed after the pass because the unit's sum did not arrive within the bounded       */
+    /* wait.  Neither affects the result.  Both are 0 on the routes that do not use the fused pass.              */
+    void    *scan_counters;
 } nkv_params;
 
 typedef struct nkv_shape {
@@ -274,9 +282,11 @@ int nkv_decode_attention(const void *q, const void *packed_k, const void *packed
                          double scale, float *out, float *lse, void *ws, size_t ws_bytes, void *hip_stream);
 
 /*
- * Plain device-to-device copy of `bytes` bytes (a multiple of 16, both pointers 16-byte aligned) by a
- * grid-stride kernel of 16-byte loads and stores.  Not part of the pass: it is the yardstick the
- * benchmark measures attainable HBM bandwidth with and calibrates hardware byte counters against.
+ * Plain device-to-device copy of `bytes` bytes (a multiple of 16, both pointers 16-byte aligned): contiguous
+ * 16 KB pieces per workgroup, non-temporal 16-byte loads and stores -- the access pattern of the K/V gather
+ * without its indirection.  dst == NULL: the loads only (what a pure reader can reach).  Not part of the pass:
+ * it is the yardstick the benchmark measures attainable HBM bandwidth with and calibrates hardware byte
+ * counters against.
  */
 int nkv_copy_probe(void *dst, const void *src, size_t bytes, void *hip_stream);
 

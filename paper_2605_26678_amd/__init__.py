@@ -41,7 +41,8 @@ class nkv_params(C.Structure):
                 ("gate_mode", C.c_int32), ("surprise_mode", C.c_int32), ("flags", C.c_uint32),
                 ("scale_mask", C.c_int32), ("top_frac", C.c_double), ("prior", C.c_double * 3),
                 ("beta", C.c_double), ("tau", C.c_double), ("kappa", C.c_double), ("safeguard", C.c_double),
-                ("near_tol", C.c_double), ("prof_start", C.c_void_p * 6), ("prof_stop", C.c_void_p * 6)]
+                ("near_tol", C.c_double), ("prof_start", C.c_void_p * 6), ("prof_stop", C.c_void_p * 6),
+                ("scan_counters", C.c_void_p)]
 
 
 class nkv_shape(C.Structure):
@@ -269,7 +270,7 @@ def decode_attention(q, packed_k, packed_v, head_off, rows: int, shape: Shape, p
 
 
 def copy_probe(dst, src, stream=None) -> None:
-    """Plain device copy src -> dst (same byte size), the bandwidth yardstick."""
+    """Plain device copy src -> dst (same byte size), the bandwidth yardstick; dst None: loads only."""
     rc = lib().nkv_copy_probe(_ptr(dst), _ptr(src), src.numel() * src.element_size(), _stream(stream))
     if rc:
         raise NkvError(rc, "nkv_copy_probe")

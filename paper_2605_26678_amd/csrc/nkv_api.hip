@@ -173,6 +173,12 @@ int check_ws(const void *ws, size_t have, size_t need)
     return NKV_OK;
 }
 
+// The fused scan's health counters (first words of its sync area), or zeros, to the caller's two words.
+__global__ void scan_counters_kernel(const uint32_t *sync, uint32_t *out)
+{
+    if (threadIdx.x < 2) out[threadIdx.x] = sync ? sync[threadIdx.x] : 0u;
+}
+
 int run_raw(const void *keys, const nkv_shape *s, const nkv_params *p, const PromptTab &tab, float *a_raw,
             char *ws, const ScoreWs &lay, hipStream_t st)
 {
@@ -182,6 +188,7 @@ int run_raw(const void *keys, const nkv_shape *s, const nkv_params *p, const Pro
     const int rc = fill_map(s, s->key_strides, s->key_layer_offsets, s->d, &km);
     if (rc) return rc;
     hipError_t e;
+    bool streaming = true;                                            // the sync area starts with this call's counters
     const int mode = (p->flags & NKV_FLAG_TWO_PASS_STABLE)  ? kScanTwoPass
                      : (p->flags & NKV_FLAG_NO_UNIT_SUMS)  ? kScanRepairAll
                      : (p->flags & NKV_FLAG_DEFER_STABLE)  ? kScanDeferAll : kScanFused;
@@ -192,9 +199,16 @@ int run_raw(const void *keys, const nkv_shape *s, const nkv_params *p, const Pro
     else if (!(p->flags & NKV_FLAG_GENERIC_KERNELS) && fast_score_supported(s->dtype, s->d, p->window, tab))
         e = launch_score_fast(keys, km, s->dtype, LH, s->d, tab, a_raw, (float *)(ws + lay.bsum), (float *)(ws + lay.ssum),
                               ws + lay.sync, mode, prof, st);
-    else
+    else {
+        streaming = false;
         e = launch_score_generic(keys, km, s->dtype, LH, s->d, p->window, tab, a_raw, (float *)(ws + lay.rnorm),
                                  (float *)(ws + lay.bsum), (float *)(ws + lay.ssum), prof, st);
+    }
+    if (e == hipSuccess && p->scan_counters) {
+        scan_counters_kernel<<<1, 64, 0, st>>>(streaming ? (const uint32_t *)(ws + lay.sync) : nullptr,
+                                               (uint32_t *)p->scan_counters);
+        e = hipGetLastError();
+    }
     return e == hipSuccess ? NKV_OK : NKV_EHIP;
 }
 
@@ -485,7 +499,7 @@ int nkv_decode_attention(const void *q, const void *packed_k, const void *packed
 
 int nkv_copy_probe(void *dst, const void *src, size_t bytes, void *hip_stream)
 {
-    if (!dst || !src || bytes % 16 || (uintptr_t)dst % 16 || (uintptr_t)src % 16) return NKV_EINVAL;
+    if (!src || bytes % 16 || (uintptr_t)dst % 16 || (uintptr_t)src % 16) return NKV_EINVAL;
     return launch_copy_probe(dst, src, bytes, (hipStream_t)hip_stream) == hipSuccess ? NKV_OK : NKV_EHIP;
 }
 

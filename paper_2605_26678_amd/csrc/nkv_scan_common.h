@@ -283,7 +283,8 @@ __device__ __forceinline__ bool all_written(const u32x4 &v)
 }
 
 constexpr int kMaxChunks = 4;                    // chunks per block: block size <= 256
-constexpr uint32_t kSpinLimit = 1u << 22;        // polls of a summing workgroup before it gives up (~seconds)
+constexpr uint32_t kSpinLimit = 1u << 13;        // polls of a summing workgroup before it gives up (~20 ms); the
+                                                 // unit's sum is then formed after the pass
 constexpr int kPollLimit = 48;                   // polls of a block's workgroup before it defers its a_s (~0.1 ms)
 constexpr int kDies = 8;                         // queues (one per XCD of an MI355X)
 

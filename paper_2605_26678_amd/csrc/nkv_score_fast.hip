@@ -579,6 +579,8 @@ hipError_t run_nw(const uint8_t *keys, const RowMap &km, int LH, const PromptTab
         deferred_stable_kernel<D, NW, KF><<<defer_all ? 4096 : 256, 64 * NW, 0, st>>>(keys, km, tab, ssum,
                                                                                   (const uint32_t *)sync_area, a_raw);
     } else {
+        // (the counters a caller may ask for read as zero on this route)
+        prepare_kernel<<<1, 256, 0, st>>>((uint4 *)sync_area, kSyncWords / 4, nullptr, 0, nullptr, 0);
         prof.begin(NKV_KERNEL_SCAN, st);
         launch_scan<D, NW, false, KF>(keys, km, LH, tab, a_raw, bsum, ssum, nullptr, 0, 0u, st);
         prof.end(NKV_KERNEL_SCAN, st);

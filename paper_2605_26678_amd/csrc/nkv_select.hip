@@ -282,10 +282,33 @@ __global__ __launch_bounds__(256) void gather_kernel(const uint4 *__restrict__ k
     }
 }
 
+// The yardstick: every workgroup moves contiguous 16 KB pieces with non-temporal 16-byte loads and stores, four
+// loads in flight per thread -- the access pattern of the gather above without its indirection.  dst == nullptr:
+// loads only (what a pure reader such as the decode consumer can reach); an empty assembly statement that takes
+// the loaded registers keeps the compiler from dropping the loads.
 __global__ __launch_bounds__(256) void copy_kernel(uint4 *__restrict__ dst, const uint4 *__restrict__ src, size_t n)
 {
-    const size_t stride = (size_t)gridDim.x * blockDim.x;
-    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) dst[i] = src[i];
+    using v4 = unsigned int __attribute__((ext_vector_type(4)));
+    constexpr size_t kPiece = 1024;                                   // 16-byte vectors per piece
+    const v4 *s = reinterpret_cast<const v4 *>(src);
+    v4 *d = reinterpret_cast<v4 *>(dst);
+    for (size_t p0 = (size_t)blockIdx.x * kPiece; p0 < n; p0 += (size_t)gridDim.x * kPiece) {
+        v4 v[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const size_t i = p0 + j * 256 + threadIdx.x;
+            v[j] = i < n ? __builtin_nontemporal_load(s + i) : v4{0u, 0u, 0u, 0u};
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const size_t i = p0 + j * 256 + threadIdx.x;
+            if (d) {
+                if (i < n) __builtin_nontemporal_store(v[j], d + i);
+            } else {
+                asm volatile("" ::"v"(v[j].x), "v"(v[j].y), "v"(v[j].z), "v"(v[j].w));
+            }
+        }
+    }
 }
 
 }  // namespace
@@ -294,8 +317,8 @@ hipError_t launch_copy_probe(void *dst, const void *src, size_t bytes, hipStream
 {
     const size_t n = bytes / 16;
     if (n == 0) return hipSuccess;
-    const size_t want = (n + 255) / 256;
-    const unsigned groups = (unsigned)(want < 256 * 32 ? want : 256 * 32);     // 32 workgroups per CU
+    const size_t want = (n + 1023) / 1024;
+    const unsigned groups = (unsigned)(want < 256 * 64 ? want : 256 * 64);     // up to 64 workgroups per CU
     copy_kernel<<<groups, 256, 0, st>>>((uint4 *)dst, (const uint4 *)src, n);
     return hipGetLastError();
 }

@@ -383,6 +383,31 @@ def test_deferred_stable_route_gives_the_same_bits():
         assert torch.equal(a.scores, c.scores) and torch.equal(a.kept_idx, c.kept_idx)
 
 
+@pytest.mark.parametrize("d", [128, 64])
+def test_scan_counters_report_the_route_taken(d):
+    """The optional health counters of the fused scan: no summing workgroup gives up and few blocks take the
+    deferred route in normal operation; the flags that force those routes show up in them exactly."""
+    w = nkv_inputs.small_workload("counters", 2, 3, d, [3000, 500, 129])
+    K, _ = _kv(w)
+    shape = shape_of(w)
+    blocks = sum((n + nkv.block_size(n) - 1) // nkv.block_size(n) for n in w.prompt_lens) * w.L * w.H
+    units = len(w.prompt_lens) * w.L * w.H
+    cnt = torch.full((2,), 77, dtype=torch.int32, device=DEV)
+    sc = torch.empty(w.L, w.H, w.T, dtype=torch.float32, device=DEV)
+    for flags, want in ((0, None), (nkv.FLAG_DEFER_STABLE, (0, blocks)), (nkv.FLAG_NO_UNIT_SUMS, (units, blocks)),
+                        (nkv.FLAG_TWO_PASS_STABLE, (0, 0)), (nkv.FLAG_GENERIC_KERNELS, (0, 0))):
+        p = nkv.params_default(flags=flags, scan_counters=cnt.data_ptr())
+        ws = torch.empty(nkv.workspace_bytes(shape, p), dtype=torch.uint8, device=DEV)
+        cnt.fill_(77)
+        nkv.score(K, shape, p, sc, ws)
+        torch.cuda.synchronize()
+        got = tuple(cnt.tolist())
+        if want is None:
+            assert got[0] == 0 and got[1] <= blocks // 2, got
+        else:
+            assert got == want, (flags, got, want)
+
+
 def test_ragged_batch_is_reproducible():
     """The ragged serving shape, several times over: identical bits every time (no wait may run out)."""
     w = nkv_inputs.WORKLOADS["llama3b_ragged"]
