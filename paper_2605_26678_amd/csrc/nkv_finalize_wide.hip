@@ -164,6 +164,7 @@ __global__ __launch_bounds__(kWideThreads) void stats_pick_kernel(int L, int H, 
 
 // grid: slices.  All three scales of the slice in one pass: what stats_finish_kernel needs of each scale, and --
 // the ranges being known -- min, max and sum of the surprise statistic of the slice's tokens.
+template <bool ALL>
 __global__ __launch_bounds__(kWideThreads) void stats_collect_kernel(const float *__restrict__ a_raw, int64_t rows,
                                                                      int L, int H, PromptTab tab, SliceTab st,
                                                                      int n_slices, int scale_mask,
@@ -226,7 +227,7 @@ __global__ __launch_bounds__(kWideThreads) void stats_collect_kernel(const float
                 const float raw[3] = {v[0][j], v[1][j], v[2][j]};
                 float at[3];
                 normalised(raw, hs, at);
-                const float sv = surprise_std(at, scale_mask);
+                const float sv = surprise_std<ALL>(at, scale_mask);
                 smin = fminf(smin, sv);
                 smax = fmaxf(smax, sv);
                 ssum32 += sv;
@@ -266,6 +267,7 @@ __global__ __launch_bounds__(kWideThreads) void stats_collect_kernel(const float
 
 // grid: slices.  Blend, gate, route and pinning of the slice's tokens (Section 2.4); every workgroup forms its
 // head's weights and surprise statistics itself from the few numbers they depend on.
+template <bool ALL>
 __global__ __launch_bounds__(kWideThreads) void route_slice_kernel(const float *__restrict__ a_raw, int64_t rows,
                                                                    int L, int H, PromptTab tab, SliceTab st,
                                                                    LearnerConsts lc, const float *__restrict__ stats,
@@ -319,7 +321,7 @@ __global__ __launch_bounds__(kWideThreads) void route_slice_kernel(const float *
                 const float raw[3] = {v[0][j], v[1][j], v[2][j]};
                 float at[3];
                 normalised(raw, h, at);
-                out[i] = i < lc.n_sink ? NKV_PIN : routed_score(at, h, lc);
+                out[i] = i < lc.n_sink ? NKV_PIN : routed_score<ALL>(at, h, lc);
             }
         }
     }
@@ -470,8 +472,12 @@ hipError_t launch_stats_wide(const float *a_raw, int L, int H, const PromptTab &
     stats_hist_kernel<<<dim3((unsigned)slices, 3), kWideThreads, 0, st>>>(a_raw, rows, tab, stab, slices, part, sp);
     SliceSurprise *sur = (SliceSurprise *)(base + lay.sur);
     stats_pick_kernel<<<dim3(units, 3), kWideThreads, 0, st>>>(L, H, tab, stab, slices, part, sp, picks, failed);
-    stats_collect_kernel<<<(unsigned)slices, kWideThreads, 0, st>>>(a_raw, rows, L, H, tab, stab, slices, scale_mask, picks, segTop,
-                                                                   segBot, sp, sur, failed);
+    if (scale_mask == 7)
+        stats_collect_kernel<true><<<(unsigned)slices, kWideThreads, 0, st>>>(a_raw, rows, L, H, tab, stab, slices, scale_mask,
+                                                                             picks, segTop, segBot, sp, sur, failed);
+    else
+        stats_collect_kernel<false><<<(unsigned)slices, kWideThreads, 0, st>>>(a_raw, rows, L, H, tab, stab, slices, scale_mask,
+                                                                              picks, segTop, segBot, sp, sur, failed);
     stats_finish_kernel<<<dim3(units, 3), 64, 0, st>>>(a_raw, rows, L, H, tab, stab, slices, picks, segTop, segBot,
                                                        sp, failed, stats);
     return hipGetLastError();
@@ -486,8 +492,12 @@ hipError_t launch_route_wide(const float *a_raw, int L, int H, const PromptTab &
     const int slices = fill_slices(L, H, tab, &stab);
     const WideWs lay = wide_ws(L, H, tab);
     const SliceSurprise *sur = (const SliceSurprise *)((char *)ws + lay.sur);
-    route_slice_kernel<<<(unsigned)slices, kWideThreads, 0, st>>>(a_raw, (int64_t)L * H * tab.T, L, H, tab, stab, lc,
-                                                                 stats, sur, scores);
+    if (lc.scale_mask == 7)
+        route_slice_kernel<true><<<(unsigned)slices, kWideThreads, 0, st>>>(a_raw, (int64_t)L * H * tab.T, L, H, tab, stab,
+                                                                           lc, stats, sur, scores);
+    else
+        route_slice_kernel<false><<<(unsigned)slices, kWideThreads, 0, st>>>(a_raw, (int64_t)L * H * tab.T, L, H, tab, stab,
+                                                                            lc, stats, sur, scores);
     return hipGetLastError();
 }
 

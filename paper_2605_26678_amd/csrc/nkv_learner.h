@@ -31,9 +31,9 @@ __device__ __forceinline__ float std3(const float at[3])
 // Population standard deviation over the readings of the scales that take part (Section 2.4; Appendix,
 // component ablation: a scale that is switched off is left out of blend, winner and deviation alike).
 // mask: bit k set = scale k takes part; uniform across a launch.
-__device__ __forceinline__ float surprise_std(const float at[3], int mask)
+template <bool ALL = false> __device__ __forceinline__ float surprise_std(const float at[3], int mask)
 {
-    if (mask == 7) return std3(at);
+    if (ALL || mask == 7) return std3(at);
     if (mask == 1 || mask == 2 || mask == 4) return 0.f;
     const float x = at[mask & 1 ? 0 : 1], y = at[mask & 4 ? 2 : 1];
     const float m = (x + y) * 0.5f, dx = x - m, dy = y - m;
@@ -41,12 +41,14 @@ __device__ __forceinline__ float surprise_std(const float at[3], int mask)
 }
 
 // blend, surprise, gate and route of one token from its three normalised readings (Section 2.4)
+// ALL: every scale takes part (known at compile time: the slice-wise kernels are instantiated for that case).
+template <bool ALL = false>
 __device__ __forceinline__ float routed_score(const float at[3], const HeadStats &st, const LearnerConsts &lc)
 {
     const float blend = st.w[0] * at[0] + st.w[1] * at[1] + st.w[2] * at[2];   // a scale that is off has weight 0
-    const int mask = lc.scale_mask;
+    const int mask = ALL ? 7 : lc.scale_mask;
     const float win = fmaxf(mask & 1 ? at[0] : -INFINITY, fmaxf(mask & 2 ? at[1] : -INFINITY, mask & 4 ? at[2] : -INFINITY));
-    float s = surprise_std(at, mask);
+    float s = surprise_std<ALL>(at, mask);
     if (lc.surprise_mode == NKV_SURPRISE_NORMALISED) s = fmaxf((s - st.s_lo) * st.s_inv_range - st.s_mean, 0.f);
     // logistic gate with the hardware's base-2 exponential and reciprocal (1 ulp each; the argument is at
     // most a few tens, so alpha is good to ~1e-6)

@@ -415,22 +415,21 @@ inline unsigned fill_scan_plan(int LH, const PromptTab &tab, int H, ScanPlan *pl
     return longest * kDies;
 }
 
-// Unit sums that the scan left unwritten (its summing workgroup gave up waiting, which the scheduling of
-// workgroups makes possible in principle): formed here, after the scan, from the block totals, with the
-// additions in the same order.  grid: one workgroup of 64 * NW threads per (layer*head, prompt).
+// The unit's sum for a kernel that runs after the pass.  If the pass left it unwritten (its summing workgroup gave
+// up waiting, which the scheduling of workgroups makes possible in principle) the calling workgroup -- all of its
+// 64 * NW threads -- forms it now from the block totals, with the additions in the pass's order; several
+// workgroups doing so at once store the same bits.  Afterwards the sum is to be read with agent-scope loads.
+// part: LDS as for add_unit_up.
 template <int D, int NW>
-__global__ __launch_bounds__(64 * NW) void unit_sum_repair_kernel(const float *__restrict__ bsum, PromptTab tab,
-                                                                  float *__restrict__ ssum)
+__device__ __forceinline__ void ensure_unit_sum(const float *bsum_unit, int unblk, float *ssum_unit, float *part)
 {
-    __shared__ float part[64 * NW / (D / 4) * D];
-    const int lh = blockIdx.x / tab.n, p = blockIdx.x - lh * tab.n;
-    float *ssum_unit = ssum + ((int64_t)lh * tab.n + p) * D;
+    const __amdgpu_buffer_rsrc_t srs = __builtin_amdgcn_make_buffer_rsrc(ssum_unit, 0, D * 4, 0x00020000);
     bool missing = false;
-    for (int i = threadIdx.x; i < D; i += 64 * NW) missing = missing || __float_as_uint(ssum_unit[i]) == kUnwritten;
+    if (threadIdx.x < D / 4) missing = !all_written(agent_load16(srs, threadIdx.x * 16));
     if (!__syncthreads_or(missing)) return;
-    const int nblk = tab.blk_off[tab.n];
-    add_unit_up<D, NW, false>(bsum + ((int64_t)lh * nblk + tab.blk_off[p]) * D, tab.blk_off[p + 1] - tab.blk_off[p],
-                              ssum_unit, part, 0u);
+    add_unit_up<D, NW, false>(bsum_unit, unblk, ssum_unit, part, 0u);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
 }
 
 // What the fused pass expects to find in memory, in one launch: counters at zero, block totals and unit sums

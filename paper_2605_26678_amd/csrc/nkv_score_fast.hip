@@ -421,12 +421,13 @@ void scan_kernel(const uint8_t *__restrict__ keys, RowMap km, PromptTab tab, Sca
 // cosine as scan_kernel, so the values are the ones scan_kernel would have stored.
 template <int D, int NW, int KF>
 __global__ __launch_bounds__(64 * NW) void deferred_stable_kernel(const uint8_t *__restrict__ keys, RowMap km,
-                                                                  PromptTab tab,
-                                                                  const float *__restrict__ ssum,
+                                                                  PromptTab tab, const float *__restrict__ bsum,
+                                                                  float *__restrict__ ssum,
                                                                   const uint32_t *__restrict__ sync,
                                                                   float *__restrict__ a_raw)
 {
     constexpr int LPR = D / 8, TPT = LPR, ES = key_bytes<KF>(), kRowBytes = D * ES;
+    __shared__ float part[64 * NW / (D / 4) * D];
     const int nblk = tab.blk_off[tab.n];
     const uint32_t count = sync[kDeferCountWord];
     const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -437,6 +438,9 @@ __global__ __launch_bounds__(64 * NW) void deferred_stable_kernel(const uint8_t 
         const int b = tab.b[p], N = tab.tok_off[p + 1] - tab.tok_off[p];
         const int blk_lo = (blk - tab.blk_off[p]) * b, blk_hi = min(blk_lo + b, N);
         const int64_t row0 = (int64_t)lh * tab.T + tab.tok_off[p];
+        float *S_unit = ssum + ((int64_t)lh * tab.n + p) * D;
+        ensure_unit_sum<D, NW>(bsum + ((int64_t)lh * nblk + tab.blk_off[p]) * D, tab.blk_off[p + 1] - tab.blk_off[p], S_unit, part);
+        const __amdgpu_buffer_rsrc_t srs = __builtin_amdgcn_make_buffer_rsrc(S_unit, 0, D * 4, 0x00020000);
         const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
             const_cast<uint8_t *>(keys) + km.unit(lh, p, tab) * ES, 0, N * kRowBytes, 0x00020000);
         const int lane_off = (blk_lo + 64 * w + g * TPT) * kRowBytes + c * (8 * ES);
@@ -451,7 +455,11 @@ __global__ __launch_bounds__(64 * NW) void deferred_stable_kernel(const uint8_t 
         const float rn_m = tok < blk_hi ? inv_norm(ss_m) : 0.f;
         const float kn_m = ss_m < 1e-24f ? sqrtf(ss_m) * 1e12f : 1.f;
         float S[8];
-        load8(ssum + ((int64_t)lh * tab.n + p) * D + c * 8, S);
+        {
+            const u32x4 s0 = agent_load16(srs, c * 32), s1 = agent_load16(srs, c * 32 + 16);
+            S[0] = __uint_as_float(s0.x); S[1] = __uint_as_float(s0.y); S[2] = __uint_as_float(s0.z); S[3] = __uint_as_float(s0.w);
+            S[4] = __uint_as_float(s1.x); S[5] = __uint_as_float(s1.y); S[6] = __uint_as_float(s1.z); S[7] = __uint_as_float(s1.w);
+        }
         float ssq = 0.f;
 #pragma unroll
         for (int e = 0; e < 8; ++e) ssq = fmaf(S[e], S[e], ssq);
@@ -575,8 +583,7 @@ hipError_t run_nw(const uint8_t *keys, const RowMap &km, int LH, const PromptTab
         launch_scan<D, NW, true, KF>(keys, km, LH, tab, a_raw, bsum, ssum, (uint32_t *)sync_area,
                                  defer_all ? -1 : kPollLimit, no_unit_sums ? 0u : kSpinLimit, st);
         prof.end(NKV_KERNEL_SCAN, st);
-        unit_sum_repair_kernel<D, NW><<<LH * tab.n, 64 * NW, 0, st>>>(bsum, tab, ssum);
-        deferred_stable_kernel<D, NW, KF><<<defer_all ? 4096 : 256, 64 * NW, 0, st>>>(keys, km, tab, ssum,
+        deferred_stable_kernel<D, NW, KF><<<defer_all ? 4096 : 256, 64 * NW, 0, st>>>(keys, km, tab, bsum, ssum,
                                                                                   (const uint32_t *)sync_area, a_raw);
     } else {
         // (the counters a caller may ask for read as zero on this route)

@@ -466,13 +466,15 @@ void scan_tile_kernel(const uint8_t *__restrict__ keys, RowMap km, PromptTab tab
 // layout directly), norms, split and product as in scan_tile_kernel, so the values are the ones it would have
 // stored.
 __global__ __launch_bounds__(64 * kTileWaves) void deferred_stable_tile_kernel(const uint8_t *__restrict__ keys, RowMap km,
-                                                                               PromptTab tab, const float *__restrict__ ssum,
+                                                                               PromptTab tab, const float *__restrict__ bsum,
+                                                                               float *__restrict__ ssum,
                                                                                const uint32_t *__restrict__ sync,
                                                                                float *__restrict__ a_raw)
 {
     constexpr int D = 128, NW = kTileWaves, kRowBytes = D * 2;
     __shared__ __attribute__((aligned(16))) uint8_t lds_stage[NW][kStageBytes];
     __shared__ __attribute__((aligned(16))) float lds_w[NW][kGroup], lds_ss[NW][kGroup];
+    __shared__ float part[64 * NW / (D / 4) * D];
     const int nblk = tab.blk_off[tab.n];
     const uint32_t count = sync[kDeferCountWord];
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
@@ -490,7 +492,12 @@ __global__ __launch_bounds__(64 * kTileWaves) void deferred_stable_tile_kernel(c
         const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
             const_cast<uint8_t *>(keys) + km.unit(lh, p, tab) * 2, 0, N * kRowBytes, 0x00020000);
         const __amdgpu_buffer_rsrc_t out_s = __builtin_amdgcn_make_buffer_rsrc(a_raw + row0, 0, blk_hi * 4, 0x00020000);
-        const float2 s2 = *reinterpret_cast<const float2 *>(ssum + ((int64_t)lh * tab.n + p) * D + 2 * lane);
+        float *S_unit = ssum + ((int64_t)lh * tab.n + p) * D;
+        ensure_unit_sum<D, NW>(bsum + ((int64_t)lh * nblk + tab.blk_off[p]) * D, tab.blk_off[p + 1] - tab.blk_off[p], S_unit, part);
+        const __amdgpu_buffer_rsrc_t srs = __builtin_amdgcn_make_buffer_rsrc(S_unit, 0, D * 4, 0x00020000);
+        asm volatile("" ::: "memory");
+        const u32x2 sbits = __builtin_amdgcn_raw_buffer_load_b64(srs, 8 * lane, 0, 16);
+        const float2 s2 = make_float2(__uint_as_float(sbits.x), __uint_as_float(sbits.y));
         const float ssq = sum_over_rows16(row_sum<16>(fmaf(s2.x, s2.x, s2.y * s2.y)));
         __builtin_amdgcn_wave_barrier();                              // the previous block's reads of the staged rows
         stage_anchor(stage, 0, lane, s2.x, s2.y);
@@ -563,8 +570,7 @@ hipError_t launch_score_tile(const void *keys, const RowMap &km, int LH, const P
                                                          (uint32_t *)sync_area, LH, (int64_t)LH * tab.T,
                                                          defer_all ? -1 : kPollLimit, no_unit_sums ? 0u : kSpinLimit);
     prof.end(NKV_KERNEL_SCAN, st);
-    unit_sum_repair_kernel<D, kTileWaves><<<LH * tab.n, 64 * kTileWaves, 0, st>>>(bsum, tab, ssum);
-    deferred_stable_tile_kernel<<<defer_all ? 4096 : 256, 64 * kTileWaves, 0, st>>>((const uint8_t *)keys, km, tab, ssum,
+    deferred_stable_tile_kernel<<<defer_all ? 4096 : 256, 64 * kTileWaves, 0, st>>>((const uint8_t *)keys, km, tab, bsum, ssum,
                                                                                    (const uint32_t *)sync_area, a_raw);
     return hipGetLastError();
 }
