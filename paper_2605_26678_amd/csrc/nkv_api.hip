@@ -159,7 +159,7 @@ ScoreWs score_ws(const nkv_shape *s, const PromptTab &tab, bool with_a_raw)
     w.a_raw = off;  off += with_a_raw ? align_up(3 * rows * 4) : 0;
     w.rnorm = off;  off += align_up(rows * 4);
     w.bsum = off;   off += align_up(LH * tab.blk_off[tab.n] * s->d * 4);
-    w.ssum = off;   off += align_up(LH * tab.n * s->d * 4);
+    w.ssum = off;   off += align_up(LH * tab.n * s->d * 8);                      // unit sums: fp32, or 64-bit accumulators
     w.stats = off;  off += align_up(LH * tab.n * 3 * 4 * 4);                 // per unit and scale: min, 1/range, gap
     w.wide = off;   off += with_a_raw ? align_up(stats_wide_ws_bytes(s->L, s->H, tab)) : 0;
     w.total_bytes = off;
@@ -194,7 +194,7 @@ int run_raw(const void *keys, const nkv_shape *s, const nkv_params *p, const Pro
                      : (p->flags & NKV_FLAG_DEFER_STABLE)  ? kScanDeferAll : kScanFused;
     if (!(p->flags & NKV_FLAG_GENERIC_KERNELS) && !(p->flags & NKV_FLAG_VECTOR_SCAN) && mode != kScanTwoPass &&
         tile_score_supported(s->dtype, s->d, p->window, tab, LH))
-        e = launch_score_tile(keys, km, LH, tab, a_raw, (float *)(ws + lay.bsum), (float *)(ws + lay.ssum), ws + lay.sync,
+        e = launch_score_tile(keys, km, LH, tab, a_raw, ws + lay.ssum, ws + lay.sync,
                               mode, prof, st);
     else if (!(p->flags & NKV_FLAG_GENERIC_KERNELS) && fast_score_supported(s->dtype, s->d, p->window, tab))
         e = launch_score_fast(keys, km, s->dtype, LH, s->d, tab, a_raw, (float *)(ws + lay.bsum), (float *)(ws + lay.ssum),

@@ -399,8 +399,9 @@ __device__ __forceinline__ bool add_unit_up(const float *bsum_unit, int unblk, f
 
 // The constants of one launch of the fused pass; returns the number of workgroups to launch (the longest of the
 // dies' queues, times the number of dies).
-inline unsigned fill_scan_plan(int LH, const PromptTab &tab, int H, ScanPlan *plan)
+inline unsigned fill_scan_plan(int LH, const PromptTab &tab, int H, ScanPlan *plan, bool sum_items = true)
 {
+    const int nsum = sum_items ? tab.n : 0;                           // "add the unit up" items per (layer, head)
     plan->nblk = tab.blk_off[tab.n];
     plan->run = run_length(plan->nblk);
     plan->inv_run = 1.0f / (float)plan->run;
@@ -408,8 +409,8 @@ inline unsigned fill_scan_plan(int LH, const PromptTab &tab, int H, ScanPlan *pl
     uint32_t longest = 0;
     for (int x = 0; x < kDies; ++x) {                                 // 8 queues of (nearly) equal length, interleaved
         plan->len[x] = die_blocks(plan->nblk, plan->run, x);
-        plan->inv_items[x] = (float)kDies / (float)(kDies * plan->len[x] + tab.n);
-        const uint32_t items = queue_start(LH, plan->len[x], tab.n, x);
+        plan->inv_items[x] = (float)kDies / (float)(kDies * plan->len[x] + nsum);
+        const uint32_t items = queue_start(LH, plan->len[x], nsum, x);
         longest = items > longest ? items : longest;
     }
     return longest * kDies;
@@ -430,6 +431,36 @@ __device__ __forceinline__ void ensure_unit_sum(const float *bsum_unit, int unbl
     add_unit_up<D, NW, false>(bsum_unit, unblk, ssum_unit, part, 0u);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
+}
+
+// ---- self-counting accumulators (matrix-core pass) -------------------------------------------------------
+// The unit's sum as 64-bit integers, one per head dimension: every block adds (its total in 2^-31 fixed point)
+// * 2^12 + 1 with one integer atomic per dimension, so the low 12 bits of a word count the blocks that have
+// added to it and a word is complete when they equal the unit's number of blocks.  Integer additions commute:
+// the sum does not depend on the order the blocks arrive in, and nothing has to be ordered or fenced -- every
+// word says by itself whether it is complete.  Range: a component of a normalised key is at most 1, so
+// |total| <= 256 per block and |sum| < 2^20 for the at most 4095 blocks of a unit: 20 + 31 bits and the sign
+// above the 12 count bits fill the word exactly.
+constexpr int kCountBits = 12;
+constexpr int kMaxUnitBlocks = (1 << kCountBits) - 1;
+constexpr int kAccumFrac = 31;                   // fraction bits of the fixed-point sum
+
+// what a block adds for its total v
+__device__ __forceinline__ unsigned long long accum_term(float v)
+{
+    const float fl = floorf(v);                                      // v - floor(v) is exact in fp32
+    const long long hi = (long long)(int)fl;
+    const long long lo = (long long)(uint32_t)((v - fl) * (float)(1u << kAccumFrac));   // < 2^31, truncated
+    const long long q = hi * (1ll << kAccumFrac) + lo;               // v in units of 2^-31
+    return ((unsigned long long)q << kCountBits) + 1ull;
+}
+__device__ __forceinline__ bool accum_complete(unsigned long long a, int blocks) { return (int)(a & kMaxUnitBlocks) == blocks; }
+// the sum, rounded once to fp32
+__device__ __forceinline__ float accum_value(unsigned long long a)
+{
+    const long long q = (long long)a >> kCountBits;                  // arithmetic shift: units of 2^-31
+    const double d = (double)(int)(q >> 32) * 4294967296.0 + (double)(uint32_t)q;
+    return (float)(d * (1.0 / (double)(1u << kAccumFrac)));
 }
 
 // What the fused pass expects to find in memory, in one launch: counters at zero, block totals and unit sums

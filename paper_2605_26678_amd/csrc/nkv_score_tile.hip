@@ -27,7 +27,12 @@
 // sum has arrived.  A 16 x 16 result leaves lane (q, n) with column n, rows 4q .. 4q+3: sums over rows are four
 // multiply-adds per lane followed by a sum over the four lanes n, n+16, n+32, n+48.
 //
-// Protocol (block totals, unit sums, bounded waits, deferred blocks): as in nkv_score_fast.hip.
+// Protocol.  A block's workgroup adds its total to the unit's self-counting accumulators (nkv_scan_common.h) as
+// soon as it has it, works through its window phase, and then looks at the accumulators: if all of the unit's
+// blocks have added by then it forms a_s from the operands still in its registers; if not after a bounded
+// number of looks, it puts its block on a list and leaves, and deferred_stable_tile_kernel computes a_s of the
+// listed blocks after the pass, when every accumulator is complete.  No workgroup ever waits for anything but
+// atomics that workgroups already running (or finished) issue unconditionally, and every wait is bounded.
 #include "nkv_scan_common.h"
 
 namespace nkv {
@@ -220,17 +225,10 @@ __device__ __forceinline__ float weighted(const f32x4 &d, const float (&wm)[4])
     return fmaf(wm[3], d[3], fmaf(wm[2], d[2], fmaf(wm[1], d[1], wm[0] * d[0])));
 }
 
-__device__ __forceinline__ void agent_store8(__amdgpu_buffer_rsrc_t rsrc, int byte_off, float a, float b)
-{
-    const u32x2 v = {__float_as_uint(a), __float_as_uint(b)};
-    __builtin_amdgcn_raw_buffer_store_b64(v, rsrc, byte_off, 0, 16);
-}
-
 // grid: the dies' queues of the fused pass (see nkv_score_fast.hip), 256 threads.
 __global__ __launch_bounds__(64 * kTileWaves, 4)
 void scan_tile_kernel(const uint8_t *__restrict__ keys, RowMap km, PromptTab tab, ScanPlan plan, float *__restrict__ a_raw,
-                      float *__restrict__ bsum, float *__restrict__ ssum, uint32_t *__restrict__ sync, int LH,
-                      int64_t rows, int poll_limit, uint32_t spin_limit)
+                      unsigned long long *__restrict__ acc, uint32_t *__restrict__ sync, int LH, int64_t rows, int poll_limit)
 {
     constexpr int D = 128, NW = kTileWaves, kRowBytes = D * 2;
     __shared__ __attribute__((aligned(16))) uint8_t lds_stage[NW][kStageBytes];   // a wave's group on its way to operand layout, later its anchors
@@ -243,33 +241,23 @@ void scan_tile_kernel(const uint8_t *__restrict__ keys, RowMap km, PromptTab tab
     const int nblk = plan.nblk;
     int lh, blk, layer, head;
     {
-        // Static assignment of blocks to workgroups, as in scan_kernel.
+        // Static assignment of blocks to workgroups: the dies' queues of scan_kernel (nkv_score_fast.hip) without
+        // the items that add a unit up, so die x's queue is, for every (layer, head) in turn, its len blocks.
         const int x = (int)(blockIdx.x & (kDies - 1));
         const uint32_t t = blockIdx.x >> 3;
         const int run = plan.run, len = plan.len[x];
-        if (t >= queue_start(LH, len, tab.n, x)) return;
+        if (t >= queue_start(LH, len, 0, x)) return;
         int l = min(LH - 1, (int)((float)t * plan.inv_items[x]));
-        while (l > 0 && queue_start(l, len, tab.n, x) > t) --l;
-        while (l + 1 < LH && queue_start(l + 1, len, tab.n, x) <= t) ++l;
-        const int r = (int)(t - queue_start(l, len, tab.n, x));
+        while (l > 0 && queue_start(l, len, 0, x) > t) --l;
+        while (l + 1 < LH && queue_start(l + 1, len, 0, x) <= t) ++l;
+        const int r = (int)(t - queue_start(l, len, 0, x));
         lh = l;
-        const int nsum = l % kDies == x ? tab.n : 0;
         {
-            const int rb = max(r - nsum, 0), cyc = div_by(rb, run, plan.inv_run);
-            blk = (cyc * kDies + x) * run + (rb - cyc * run);
+            const int cyc = div_by(r, run, plan.inv_run);
+            blk = (cyc * kDies + x) * run + (r - cyc * run);
         }
         layer = div_by(lh, km.H, plan.inv_H);
         head = lh - layer * km.H;
-        if (r < nsum) {                                              // this workgroup adds a unit up
-            const int p = r;
-            static_assert(64 * NW / (D / 4) * D <= 20 * D, "partial sums of the unit do not fit the LDS scratch");
-            if (!add_unit_up<D, NW, true>(bsum + ((int64_t)lh * nblk + tab.blk_off[p]) * D,
-                                          tab.blk_off[p + 1] - tab.blk_off[p], ssum + ((int64_t)lh * tab.n + p) * D,
-                                          &lds_T[0][0], spin_limit) &&
-                threadIdx.x == 0)
-                atomicAdd(sync + kTimeoutWord, 1u);
-            return;
-        }
     }
     const int p = prompt_of_block(tab, blk);
     const int b = tab.b[p];
@@ -309,17 +297,16 @@ void scan_tile_kernel(const uint8_t *__restrict__ keys, RowMap km, PromptTab tab
 
     // ---- block total = episodic anchor (up to length); lane: dims 2 lane, 2 lane + 1 ----
     const int unblk = tab.blk_off[p + 1] - tab.blk_off[p];
-    float *bsum_unit = bsum + ((int64_t)lh * nblk + tab.blk_off[p]) * D;
-    float *S_unit = ssum + ((int64_t)lh * tab.n + p) * D;
+    unsigned long long *acc_unit = acc + ((int64_t)lh * tab.n + p) * D;
     float bsq, b0 = 0.f, b1 = 0.f;
     for (int q = 0; q < ng; ++q) {
         const float2 t2 = *reinterpret_cast<const float2 *>(&lds_T[4 + q][2 * lane]);
         b0 += t2.x;
         b1 += t2.y;
     }
-    if (w == blk % NW) {                                              // one wave stores the block total
-        const __amdgpu_buffer_rsrc_t brs = __builtin_amdgcn_make_buffer_rsrc(bsum_unit, 0, unblk * D * 4, 0x00020000);
-        agent_store8(brs, ((blk - tab.blk_off[p]) * D + 2 * lane) * 4, b0, b1);
+    if (w == blk % NW) {                                              // one wave adds the block total to the unit's sum
+        __hip_atomic_fetch_add(acc_unit + 2 * lane, accum_term(b0), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_fetch_add(acc_unit + 2 * lane + 1, accum_term(b1), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     bsq = sum_over_rows16(row_sum<16>(fmaf(b0, b0, b1 * b1)));
 
@@ -418,23 +405,19 @@ void scan_tile_kernel(const uint8_t *__restrict__ keys, RowMap km, PromptTab tab
         }
     }
     // ---- stable dots against the unit's sum ----
-    const __amdgpu_buffer_rsrc_t srs = __builtin_amdgcn_make_buffer_rsrc(S_unit, 0, D * 4, 0x00020000);
-    if (w == 0) {                                                     // 16 lanes poll, the other waves sit at the barrier
-        u32x4 sv0 = {kUnwritten, kUnwritten, kUnwritten, kUnwritten}, sv1 = sv0;
+    if (w == 0) {                                                     // one wave looks, the others sit at the barrier
+        const __amdgpu_buffer_rsrc_t srs = __builtin_amdgcn_make_buffer_rsrc(acc_unit, 0, D * 8, 0x00020000);
         bool got = false;
         for (int polls = 0; poll_limit >= 0; ++polls) {               // poll_limit < 0: defer without looking
-            if (lane < 16) {
-                sv0 = agent_load16(srs, lane * 32);
-                sv1 = agent_load16(srs, lane * 32 + 16);
+            const u32x4 sv = agent_load16(srs, lane * 16);            // dims 2 lane, 2 lane + 1
+            const unsigned long long a0 = ((unsigned long long)sv.y << 32) | sv.x, a1 = ((unsigned long long)sv.w << 32) | sv.z;
+            got = __all(accum_complete(a0, unblk) && accum_complete(a1, unblk));
+            if (got) {
+                *reinterpret_cast<float2 *>(&lds_S[2 * lane]) = make_float2(accum_value(a0), accum_value(a1));
+                break;
             }
-            const bool ok = lane >= 16 || (all_written(sv0) && all_written(sv1));
-            got = __all(ok);
-            if (got || polls >= poll_limit) break;
+            if (polls >= poll_limit) break;
             __builtin_amdgcn_s_sleep(8);
-        }
-        if (got && lane < 16) {
-            *reinterpret_cast<u32x4 *>(&lds_S[lane * 8]) = sv0;
-            *reinterpret_cast<u32x4 *>(&lds_S[lane * 8 + 4]) = sv1;
         }
         if (lane == 0) {
             s_have = got ? 1 : 0;
@@ -466,15 +449,14 @@ void scan_tile_kernel(const uint8_t *__restrict__ keys, RowMap km, PromptTab tab
 // layout directly), norms, split and product as in scan_tile_kernel, so the values are the ones it would have
 // stored.
 __global__ __launch_bounds__(64 * kTileWaves) void deferred_stable_tile_kernel(const uint8_t *__restrict__ keys, RowMap km,
-                                                                               PromptTab tab, const float *__restrict__ bsum,
-                                                                               float *__restrict__ ssum,
+                                                                               PromptTab tab,
+                                                                               const unsigned long long *__restrict__ acc,
                                                                                const uint32_t *__restrict__ sync,
                                                                                float *__restrict__ a_raw)
 {
     constexpr int D = 128, NW = kTileWaves, kRowBytes = D * 2;
     __shared__ __attribute__((aligned(16))) uint8_t lds_stage[NW][kStageBytes];
     __shared__ __attribute__((aligned(16))) float lds_w[NW][kGroup], lds_ss[NW][kGroup];
-    __shared__ float part[64 * NW / (D / 4) * D];
     const int nblk = tab.blk_off[tab.n];
     const uint32_t count = sync[kDeferCountWord];
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
@@ -492,12 +474,9 @@ __global__ __launch_bounds__(64 * kTileWaves) void deferred_stable_tile_kernel(c
         const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
             const_cast<uint8_t *>(keys) + km.unit(lh, p, tab) * 2, 0, N * kRowBytes, 0x00020000);
         const __amdgpu_buffer_rsrc_t out_s = __builtin_amdgcn_make_buffer_rsrc(a_raw + row0, 0, blk_hi * 4, 0x00020000);
-        float *S_unit = ssum + ((int64_t)lh * tab.n + p) * D;
-        ensure_unit_sum<D, NW>(bsum + ((int64_t)lh * nblk + tab.blk_off[p]) * D, tab.blk_off[p + 1] - tab.blk_off[p], S_unit, part);
-        const __amdgpu_buffer_rsrc_t srs = __builtin_amdgcn_make_buffer_rsrc(S_unit, 0, D * 4, 0x00020000);
-        asm volatile("" ::: "memory");
-        const u32x2 sbits = __builtin_amdgcn_raw_buffer_load_b64(srs, 8 * lane, 0, 16);
-        const float2 s2 = make_float2(__uint_as_float(sbits.x), __uint_as_float(sbits.y));
+        // every block of the pass has added to the accumulators by now (the pass has ended)
+        const unsigned long long *acc_unit = acc + ((int64_t)lh * tab.n + p) * D;
+        const float2 s2 = make_float2(accum_value(acc_unit[2 * lane]), accum_value(acc_unit[2 * lane + 1]));
         const float ssq = sum_over_rows16(row_sum<16>(fmaf(s2.x, s2.x, s2.y * s2.y)));
         __builtin_amdgcn_wave_barrier();                              // the previous block's reads of the staged rows
         stage_anchor(stage, 0, lane, s2.x, s2.y);
@@ -522,6 +501,16 @@ __global__ __launch_bounds__(64 * kTileWaves) void deferred_stable_tile_kernel(c
             const float as = neg_cos(wn * sum3(AS), knn, ssq);
             __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(as), out_s, off_q0 + tok0 * 4, 0, 0);
         }
+    }
+}
+
+// counters and accumulators start a pass at zero
+__global__ __launch_bounds__(256) void clear_kernel(uint4 *sync, size_t n_sync, uint4 *accum, size_t n_accum)
+{
+    const uint4 zero = make_uint4(0u, 0u, 0u, 0u);
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n_sync + n_accum; i += (size_t)gridDim.x * blockDim.x) {
+        if (i < n_sync) sync[i] = zero;
+        else accum[i - n_sync] = zero;
     }
 }
 
@@ -551,27 +540,26 @@ bool tile_score_supported(int dtype, int d, int window, const PromptTab &tab, in
         max_unit_blocks = max(max_unit_blocks, tab.blk_off[p + 1] - tab.blk_off[p]);
     }
     const int64_t items = (int64_t)LH * (tab.blk_off[tab.n] + tab.n);
-    return items < (1ll << 28) && max_unit_blocks <= resident_tile_workgroups();
+    return items < (1ll << 28) && max_unit_blocks <= min(resident_tile_workgroups(), kMaxUnitBlocks);
 }
 
-hipError_t launch_score_tile(const void *keys, const RowMap &km, int LH, const PromptTab &tab, float *a_raw, float *bsum,
-                             float *ssum, void *sync_area, int mode, const Prof &prof, hipStream_t st)
+hipError_t launch_score_tile(const void *keys, const RowMap &km, int LH, const PromptTab &tab, float *a_raw, void *accum,
+                             void *sync_area, int mode, const Prof &prof, hipStream_t st)
 {
     constexpr int D = 128;
-    const bool no_unit_sums = mode == kScanRepairAll, defer_all = mode == kScanDeferAll || no_unit_sums;
-    const size_t nb = (size_t)LH * tab.blk_off[tab.n] * D / 4, ns = (size_t)LH * tab.n * D / 4;
-    const size_t n16 = kSyncWords / 4 + nb + ns;
-    prepare_kernel<<<(unsigned)min((n16 + 255) / 256, (size_t)2048), 256, 0, st>>>((uint4 *)sync_area, kSyncWords / 4,
-                                                                                 (uint4 *)bsum, nb, (uint4 *)ssum, ns);
+    const bool defer_all = mode == kScanDeferAll || mode == kScanRepairAll;   // no unit is added up by a workgroup of its own here
+    const size_t na = (size_t)LH * tab.n * D * 8 / 16;                        // accumulators, in 16-byte pieces
+    clear_kernel<<<(unsigned)min((kSyncWords / 4 + na + 255) / 256, (size_t)2048), 256, 0, st>>>((uint4 *)sync_area, kSyncWords / 4,
+                                                                                                (uint4 *)accum, na);
     ScanPlan plan;
-    const unsigned groups = fill_scan_plan(LH, tab, km.H, &plan);
+    const unsigned groups = fill_scan_plan(LH, tab, km.H, &plan, false);
     prof.begin(NKV_KERNEL_SCAN, st);
-    scan_tile_kernel<<<groups, 64 * kTileWaves, 0, st>>>((const uint8_t *)keys, km, tab, plan, a_raw, bsum, ssum,
-                                                         (uint32_t *)sync_area, LH, (int64_t)LH * tab.T,
-                                                         defer_all ? -1 : kPollLimit, no_unit_sums ? 0u : kSpinLimit);
+    scan_tile_kernel<<<groups, 64 * kTileWaves, 0, st>>>((const uint8_t *)keys, km, tab, plan, a_raw,
+                                                         (unsigned long long *)accum, (uint32_t *)sync_area, LH,
+                                                         (int64_t)LH * tab.T, defer_all ? -1 : kPollLimit);
     prof.end(NKV_KERNEL_SCAN, st);
-    deferred_stable_tile_kernel<<<defer_all ? 4096 : 256, 64 * kTileWaves, 0, st>>>((const uint8_t *)keys, km, tab, bsum, ssum,
-                                                                                   (const uint32_t *)sync_area, a_raw);
+    deferred_stable_tile_kernel<<<defer_all ? 4096 : 256, 64 * kTileWaves, 0, st>>>(
+        (const uint8_t *)keys, km, tab, (const unsigned long long *)accum, (const uint32_t *)sync_area, a_raw);
     return hipGetLastError();
 }
 

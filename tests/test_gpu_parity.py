@@ -394,7 +394,9 @@ def test_scan_counters_report_the_route_taken(d):
     units = len(w.prompt_lens) * w.L * w.H
     cnt = torch.full((2,), 77, dtype=torch.int32, device=DEV)
     sc = torch.empty(w.L, w.H, w.T, dtype=torch.float32, device=DEV)
-    for flags, want in ((0, None), (nkv.FLAG_DEFER_STABLE, (0, blocks)), (nkv.FLAG_NO_UNIT_SUMS, (units, blocks)),
+    # head dim 128 takes the matrix-core scan, whose units are added up by integer atomics: nothing there can give up
+    gave_up = 0 if d == 128 else units
+    for flags, want in ((0, None), (nkv.FLAG_DEFER_STABLE, (0, blocks)), (nkv.FLAG_NO_UNIT_SUMS, (gave_up, blocks)),
                         (nkv.FLAG_TWO_PASS_STABLE, (0, 0)), (nkv.FLAG_GENERIC_KERNELS, (0, 0))):
         p = nkv.params_default(flags=flags, scan_counters=cnt.data_ptr())
         ws = torch.empty(nkv.workspace_bytes(shape, p), dtype=torch.uint8, device=DEV)
