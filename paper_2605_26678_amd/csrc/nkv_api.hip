@@ -146,7 +146,7 @@ void fill_tab(const nkv_shape *s, const nkv_params *p, PromptTab *tab)
 
 // Workspace of the scoring call, in floats from the (aligned) start.
 struct ScoreWs {
-    size_t sync, a_raw, rnorm, bsum, ssum, stats, wide, total_bytes;
+    size_t sync, plan, a_raw, rnorm, bsum, ssum, stats, wide, total_bytes;
 };
 
 ScoreWs score_ws(const nkv_shape *s, const PromptTab &tab, bool with_a_raw)
@@ -156,6 +156,7 @@ ScoreWs score_ws(const nkv_shape *s, const PromptTab &tab, bool with_a_raw)
     ScoreWs w;
     size_t off = 0;
     w.sync = off;   off += align_up(fast_score_sync_bytes((int)LH, tab));
+    w.plan = off;   off += align_up(tile_score_plan_bytes((int)LH, tab));
     w.a_raw = off;  off += with_a_raw ? align_up(3 * rows * 4) : 0;
     w.rnorm = off;  off += align_up(rows * 4);
     w.bsum = off;   off += align_up(LH * tab.blk_off[tab.n] * s->d * 4);
@@ -194,7 +195,7 @@ int run_raw(const void *keys, const nkv_shape *s, const nkv_params *p, const Pro
                      : (p->flags & NKV_FLAG_DEFER_STABLE)  ? kScanDeferAll : kScanFused;
     if (!(p->flags & NKV_FLAG_GENERIC_KERNELS) && !(p->flags & NKV_FLAG_VECTOR_SCAN) && mode != kScanTwoPass &&
         tile_score_supported(s->dtype, s->d, p->window, tab, LH))
-        e = launch_score_tile(keys, km, LH, tab, a_raw, ws + lay.ssum, ws + lay.sync,
+        e = launch_score_tile(keys, km, LH, tab, a_raw, ws + lay.ssum, ws + lay.sync, ws + lay.plan,
                               mode, prof, st);
     else if (!(p->flags & NKV_FLAG_GENERIC_KERNELS) && fast_score_supported(s->dtype, s->d, p->window, tab))
         e = launch_score_fast(keys, km, s->dtype, LH, s->d, tab, a_raw, (float *)(ws + lay.bsum), (float *)(ws + lay.ssum),

@@ -225,10 +225,68 @@ __device__ __forceinline__ float weighted(const f32x4 &d, const float (&wm)[4])
     return fmaf(wm[3], d[3], fmaf(wm[2], d[2], fmaf(wm[1], d[1], wm[0] * d[0])));
 }
 
-// grid: the dies' queues of the fused pass (see nkv_score_fast.hip), 256 threads.
+// One item of the pass: a block of one (layer, head, prompt) unit with everything a workgroup needs to know about
+// it, worked out once by plan_kernel so that the pass itself starts an item with one scalar load instead of a
+// chain of dependent ones (kernel arguments, per-prompt tables, divisions).
+struct TileItem {
+    int64_t key_off;                     // element offset of the unit's first row
+    int64_t row0;                        // the unit's first row in the planes of a_raw
+    int32_t N;                           // tokens of the unit; < 0: this slot of the die's queue is empty
+    int32_t blk_lo, blk_hi;              // the block's tokens, unit-local
+    int32_t unit;                        // index of the unit's accumulators
+    int32_t unblk;                       // blocks of the unit
+    int32_t id;                          // (layer, head) * blocks per head + block: what the deferred list holds
+    int32_t pad[2];
+};
+static_assert(sizeof(TileItem) == 48, "items are read as three 16-byte pieces");
+
+// Items in launch order: item i belongs to die i % 8 and is entry i / 8 of that die's queue (the queues of
+// scan_kernel in nkv_score_fast.hip without the items that add a unit up: for every (layer, head) in turn the
+// die's runs of consecutive blocks).  Also clears the counters and the accumulators.
+__global__ __launch_bounds__(256) void plan_kernel(TileItem *__restrict__ items, uint32_t n_items, RowMap km, PromptTab tab,
+                                                   ScanPlan plan, int LH, uint4 *sync, size_t n_sync, uint4 *accum, size_t n_accum)
+{
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const uint4 zero = make_uint4(0u, 0u, 0u, 0u);
+    for (size_t k = i; k < n_sync + n_accum; k += (size_t)gridDim.x * blockDim.x) {
+        if (k < n_sync) sync[k] = zero;
+        else accum[k - n_sync] = zero;
+    }
+    for (size_t k = i; k < n_items; k += (size_t)gridDim.x * blockDim.x) {
+        const int x = (int)(k & (kDies - 1));
+        const uint32_t t = (uint32_t)(k >> 3);
+        const int len = plan.len[x];
+        TileItem it;
+        it.pad[0] = it.pad[1] = 0;
+        const int lh = len > 0 ? (int)(t / (uint32_t)len) : LH;
+        if (lh >= LH) {
+            it.key_off = it.row0 = 0;
+            it.N = -1;
+            it.blk_lo = it.blk_hi = it.unit = it.unblk = it.id = 0;
+        } else {
+            const int r = (int)(t - (uint32_t)lh * (uint32_t)len);
+            const int blk = die_block(plan.run, x, r);
+            const int p = prompt_of_block(tab, blk);
+            const int b = tab.b[p];
+            it.N = tab.tok_off[p + 1] - tab.tok_off[p];
+            it.blk_lo = (blk - tab.blk_off[p]) * b;
+            it.blk_hi = min(it.blk_lo + b, it.N);
+            it.key_off = km.unit(lh, p, tab);
+            it.row0 = (int64_t)lh * tab.T + tab.tok_off[p];
+            it.unit = lh * tab.n + p;
+            it.unblk = tab.blk_off[p + 1] - tab.blk_off[p];
+            it.id = lh * plan.nblk + blk;
+        }
+        items[k] = it;
+    }
+}
+
+// grid: one workgroup of 256 threads per item, in the items' order.  (Resident workgroups that loop over the items
+// instead were tried: without the hardware handing out blocks as slots fall free, all workgroups of the chip move
+// through their loading and computing phases in step, and the pass takes 0.90 ms instead of 0.77.)
 __global__ __launch_bounds__(64 * kTileWaves, 4)
-void scan_tile_kernel(const uint8_t *__restrict__ keys, RowMap km, PromptTab tab, ScanPlan plan, float *__restrict__ a_raw,
-                      unsigned long long *__restrict__ acc, uint32_t *__restrict__ sync, int LH, int64_t rows, int poll_limit)
+void scan_tile_kernel(const uint8_t *__restrict__ keys, const TileItem *__restrict__ items, float *__restrict__ a_raw,
+                      unsigned long long *__restrict__ acc, uint32_t *__restrict__ sync, int64_t rows, int poll_limit)
 {
     constexpr int D = 128, NW = kTileWaves, kRowBytes = D * 2;
     __shared__ __attribute__((aligned(16))) uint8_t lds_stage[NW][kStageBytes];   // a wave's group on its way to operand layout, later its anchors
@@ -238,43 +296,20 @@ void scan_tile_kernel(const uint8_t *__restrict__ keys, RowMap km, PromptTab tab
     __shared__ __attribute__((aligned(16))) float lds_S[D];                       // the unit's sum, once complete
     __shared__ int s_have;
 
-    const int nblk = plan.nblk;
-    int lh, blk, layer, head;
-    {
-        // Static assignment of blocks to workgroups: the dies' queues of scan_kernel (nkv_score_fast.hip) without
-        // the items that add a unit up, so die x's queue is, for every (layer, head) in turn, its len blocks.
-        const int x = (int)(blockIdx.x & (kDies - 1));
-        const uint32_t t = blockIdx.x >> 3;
-        const int run = plan.run, len = plan.len[x];
-        if (t >= queue_start(LH, len, 0, x)) return;
-        int l = min(LH - 1, (int)((float)t * plan.inv_items[x]));
-        while (l > 0 && queue_start(l, len, 0, x) > t) --l;
-        while (l + 1 < LH && queue_start(l + 1, len, 0, x) <= t) ++l;
-        const int r = (int)(t - queue_start(l, len, 0, x));
-        lh = l;
-        {
-            const int cyc = div_by(r, run, plan.inv_run);
-            blk = (cyc * kDies + x) * run + (r - cyc * run);
-        }
-        layer = div_by(lh, km.H, plan.inv_H);
-        head = lh - layer * km.H;
-    }
-    const int p = prompt_of_block(tab, blk);
-    const int b = tab.b[p];
-    const int N = tab.tok_off[p + 1] - tab.tok_off[p];
-    const int blk_lo = (blk - tab.blk_off[p]) * b;
-    const int blk_hi = min(blk_lo + b, N);
-    const int ng = (blk_hi - blk_lo + kGroup - 1) / kGroup;           // groups of the block, <= 16
-    const int64_t row0 = (int64_t)lh * tab.T + tab.tok_off[p];        // row of the prompt's token 0
-
+    const TileItem it = items[blockIdx.x];
+    if (it.N < 0) return;
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     const int g = lane >> 4, c = lane & 15;                           // row-wise layout: rows 4g .., dims 8c ..
     const int qq = g, n = c;                                          // operand / result layout: token n, quarter qq
     uint8_t *stage = lds_stage[w];
 
+    const int N = it.N, blk_lo = it.blk_lo, blk_hi = it.blk_hi, unblk = it.unblk;
+    const int ng = (blk_hi - blk_lo + kGroup - 1) / kGroup;           // groups of the block, <= 16
+    const int64_t row0 = it.row0;                                     // row of the prompt's token 0
+
     // ---- first touch: this wave's groups, then its group of the halo.  Rows outside the prompt read as zeros. ----
     const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<uint8_t *>(keys) + km.unit(layer, head, p, tab) * 2, 0, N * kRowBytes, 0x00020000);
+        const_cast<uint8_t *>(keys) + it.key_off * 2, 0, N * kRowBytes, 0x00020000);
     u32x4 raw[5][4];
     bool ex[5];                                                       // group m - 1 of the chain exists (m = 0: halo)
 #pragma unroll
@@ -296,15 +331,14 @@ void scan_tile_kernel(const uint8_t *__restrict__ keys, RowMap km, PromptTab tab
     __syncthreads();
 
     // ---- block total = episodic anchor (up to length); lane: dims 2 lane, 2 lane + 1 ----
-    const int unblk = tab.blk_off[p + 1] - tab.blk_off[p];
-    unsigned long long *acc_unit = acc + ((int64_t)lh * tab.n + p) * D;
+    unsigned long long *acc_unit = acc + (int64_t)it.unit * D;
     float bsq, b0 = 0.f, b1 = 0.f;
     for (int q = 0; q < ng; ++q) {
         const float2 t2 = *reinterpret_cast<const float2 *>(&lds_T[4 + q][2 * lane]);
         b0 += t2.x;
         b1 += t2.y;
     }
-    if (w == blk % NW) {                                              // one wave adds the block total to the unit's sum
+    if (w == (it.id & (NW - 1))) {                                    // one wave adds the block total to the unit's sum
         __hip_atomic_fetch_add(acc_unit + 2 * lane, accum_term(b0), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         __hip_atomic_fetch_add(acc_unit + 2 * lane + 1, accum_term(b1), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
@@ -421,7 +455,7 @@ void scan_tile_kernel(const uint8_t *__restrict__ keys, RowMap km, PromptTab tab
         }
         if (lane == 0) {
             s_have = got ? 1 : 0;
-            if (!got) sync[kSyncWords + atomicAdd(sync + kDeferCountWord, 1u)] = (uint32_t)(lh * nblk + blk);
+            if (!got) sync[kSyncWords + atomicAdd(sync + kDeferCountWord, 1u)] = (uint32_t)it.id;
         }
     }
     __syncthreads();
@@ -504,16 +538,6 @@ __global__ __launch_bounds__(64 * kTileWaves) void deferred_stable_tile_kernel(c
     }
 }
 
-// counters and accumulators start a pass at zero
-__global__ __launch_bounds__(256) void clear_kernel(uint4 *sync, size_t n_sync, uint4 *accum, size_t n_accum)
-{
-    const uint4 zero = make_uint4(0u, 0u, 0u, 0u);
-    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n_sync + n_accum; i += (size_t)gridDim.x * blockDim.x) {
-        if (i < n_sync) sync[i] = zero;
-        else accum[i - n_sync] = zero;
-    }
-}
-
 int resident_tile_workgroups()
 {
     static int cached = -1;                                          // benign if raced
@@ -543,19 +567,25 @@ bool tile_score_supported(int dtype, int d, int window, const PromptTab &tab, in
     return items < (1ll << 28) && max_unit_blocks <= min(resident_tile_workgroups(), kMaxUnitBlocks);
 }
 
+size_t tile_score_plan_bytes(int LH, const PromptTab &tab)
+{
+    ScanPlan plan;
+    return (size_t)fill_scan_plan(LH, tab, 1, &plan, false) * sizeof(TileItem);
+}
+
 hipError_t launch_score_tile(const void *keys, const RowMap &km, int LH, const PromptTab &tab, float *a_raw, void *accum,
-                             void *sync_area, int mode, const Prof &prof, hipStream_t st)
+                             void *sync_area, void *plan_area, int mode, const Prof &prof, hipStream_t st)
 {
     constexpr int D = 128;
     const bool defer_all = mode == kScanDeferAll || mode == kScanRepairAll;   // no unit is added up by a workgroup of its own here
     const size_t na = (size_t)LH * tab.n * D * 8 / 16;                        // accumulators, in 16-byte pieces
-    clear_kernel<<<(unsigned)min((kSyncWords / 4 + na + 255) / 256, (size_t)2048), 256, 0, st>>>((uint4 *)sync_area, kSyncWords / 4,
-                                                                                                (uint4 *)accum, na);
     ScanPlan plan;
-    const unsigned groups = fill_scan_plan(LH, tab, km.H, &plan, false);
+    const unsigned n_items = fill_scan_plan(LH, tab, km.H, &plan, false);
+    plan_kernel<<<(unsigned)min(((size_t)n_items + 255) / 256, (size_t)2048), 256, 0, st>>>(
+        (TileItem *)plan_area, n_items, km, tab, plan, LH, (uint4 *)sync_area, kSyncWords / 4, (uint4 *)accum, na);
     prof.begin(NKV_KERNEL_SCAN, st);
-    scan_tile_kernel<<<groups, 64 * kTileWaves, 0, st>>>((const uint8_t *)keys, km, tab, plan, a_raw,
-                                                         (unsigned long long *)accum, (uint32_t *)sync_area, LH,
+    scan_tile_kernel<<<n_items, 64 * kTileWaves, 0, st>>>((const uint8_t *)keys, (const TileItem *)plan_area, a_raw,
+                                                         (unsigned long long *)accum, (uint32_t *)sync_area,
                                                          (int64_t)LH * tab.T, defer_all ? -1 : kPollLimit);
     prof.end(NKV_KERNEL_SCAN, st);
     deferred_stable_tile_kernel<<<defer_all ? 4096 : 256, 64 * kTileWaves, 0, st>>>(
