@@ -349,18 +349,13 @@ void scan_tile_kernel(const uint8_t *__restrict__ keys, const TileItem *__restri
 
     // ---- every group through the staging rows into operand layout ----
     u32x4 X[5][4];
-    float wv[5], ssv[5];                                              // 1/||k|| (0: no such token), ||k||^2 of token n
 #pragma unroll
     for (int m = 0; m < 5; ++m) {
-        wv[m] = 0.f;
-        ssv[m] = 0.f;
         if (ex[m]) {
 #pragma unroll
             for (int j = 0; j < 4; ++j) *reinterpret_cast<u32x4 *>(stage + (4 * g + j) * kPitch + 16 * c) = raw[m][j];
             __builtin_amdgcn_wave_barrier();
             read_operand(stage, lane, X[m]);
-            wv[m] = lds_w[w][m][n];
-            ssv[m] = lds_ss[w][m][n];
             __builtin_amdgcn_wave_barrier();                          // the next group reuses the staging rows
         }
     }
@@ -419,14 +414,15 @@ void scan_tile_kernel(const uint8_t *__restrict__ keys, const TileItem *__restri
             // X[i][i']: row i of this lane's column i' = n sits in lane group n / 4, register n % 4
             float xd = (n & 2) ? ((n & 1) ? XX[3] : XX[2]) : ((n & 1) ? XX[1] : XX[0]);
             xd = (n >> 2) == qq ? xd : 0.f;
-            const float wn = wv[m], wp = wv[m - 1];
+            // 1/||k|| (0: no such token) and ||k||^2 of token n of this group and of the one 64 tokens earlier
+            const float wn = lds_w[w][m][n], wp = lds_w[w][m - 1][n], ssn = lds_ss[w][m][n], ssp = lds_ss[w][m - 1][n];
             const float c_part = (qq == 0 ? sum3(AG) : 0.f) + (alpha - beta);
             const float e_part = (qq == 0 ? sum3(AP) : 0.f) + (gamma - alpha_prev);
-            const float gsum = qq == 0 ? wn * wn * ssv[m] + wp * wp * ssv[m - 1] : 0.f;
+            const float gsum = qq == 0 ? wn * wn * ssn + wp * wp * ssp : 0.f;
             const float d_part = 2.f * (wn * c_part - wp * e_part) + (2.f * wn * wp * xd - gsum);
             const float cdot = sum_over_rows16(c_part);               // <k_i, W_i>
             const float Pn = P0 + row_prefix_sum(sum_over_rows16(d_part));
-            const float knn = ssv[m] < 1e-24f ? sqrtf(ssv[m]) * 1e12f : 1.f;
+            const float knn = ssn < 1e-24f ? sqrtf(ssn) * 1e12f : 1.f;
             const float ac = neg_cos(wn * cdot, knn, Pn);
             const float ae = neg_cos(wn * sum3(AG), knn, bsq);        // meaningful in lane group 1 (rows 4 .. 6)
             const int soff = (blk_lo + kGroup * q) * 4;                // (an offset that was past the buffer stays past it)
@@ -471,8 +467,9 @@ void scan_tile_kernel(const uint8_t *__restrict__ keys, const TileItem *__restri
             if (ex[m]) {
                 const int q = w + 4 * (m - 1);
                 const f32x4 AS = tile<4>(An, X[m]);
-                const float knn = ssv[m] < 1e-24f ? sqrtf(ssv[m]) * 1e12f : 1.f;
-                const float as = neg_cos(wv[m] * sum3(AS), knn, ssq);
+                const float wn = lds_w[w][m][n], ssn = lds_ss[w][m][n];
+                const float knn = ssn < 1e-24f ? sqrtf(ssn) * 1e12f : 1.f;
+                const float as = neg_cos(wn * sum3(AS), knn, ssq);
                 __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(as), out_s, off_q0 + (blk_lo + kGroup * q) * 4, 0, 0);
             }
         }
