@@ -85,7 +85,7 @@ hipError_t launch_score_fast(const void *keys, const RowMap &km, int dtype, int 
 bool tile_score_supported(int dtype, int d, int window, const PromptTab &tab, int LH);
 size_t tile_score_plan_bytes(int LH, const PromptTab &tab);    // the list of items the pass works through
 hipError_t launch_score_tile(const void *keys, const RowMap &km, int LH, const PromptTab &tab, float *a_raw, void *accum,
-                             void *sync_area, void *plan_area, int mode, const Prof &prof, hipStream_t st);
+                             float *ssum, void *sync_area, void *plan_area, int mode, const Prof &prof, hipStream_t st);
 
 // Units are numbered prompt by prompt, so the units of consecutive prompts of similar length form one
 // range.  Calls f(ept, unit0, units) for every maximal run of prompts whose lengths need the same number

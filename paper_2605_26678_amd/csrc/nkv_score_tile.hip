@@ -28,11 +28,15 @@
 // multiply-adds per lane followed by a sum over the four lanes n, n+16, n+32, n+48.
 //
 // Protocol.  A block's workgroup adds its total to the unit's self-counting accumulators (nkv_scan_common.h) as
-// soon as it has it, works through its window phase, and then looks at the accumulators: if all of the unit's
-// blocks have added by then it forms a_s from the operands still in its registers; if not after a bounded
-// number of looks, it puts its block on a list and leaves, and deferred_stable_tile_kernel computes a_s of the
-// listed blocks after the pass, when every accumulator is complete.  No workgroup ever waits for anything but
-// atomics that workgroups already running (or finished) issue unconditionally, and every wait is bounded.
+// soon as it has it; the add returns the word's previous contents, and whoever finds that it was the last of the
+// unit's blocks to add to a word stores the word's final value, as fp32, into the unit's sum -- memory that
+// starts out "unwritten" and in which every word is stored exactly once.  After its window phase a workgroup looks
+// at the unit's sum: if it is complete it forms a_s from the operands still in its registers; if not after a
+// bounded number of looks, it puts its block on a list and leaves, and deferred_stable_tile_kernel computes a_s
+// of the listed blocks after the pass, when every sum is complete.  No workgroup ever waits for anything but
+// stores that workgroups already running (or finished) issue unconditionally, and every wait is bounded.
+// (Looking at the accumulators themselves instead of a copy stored once was tried: loads of words that other
+// workgroups are adding to cost the pass a quarter of its time under sustained load.)
 #include "nkv_scan_common.h"
 
 namespace nkv {
@@ -242,15 +246,17 @@ static_assert(sizeof(TileItem) == 48, "items are read as three 16-byte pieces");
 
 // Items in launch order: item i belongs to die i % 8 and is entry i / 8 of that die's queue (the queues of
 // scan_kernel in nkv_score_fast.hip without the items that add a unit up: for every (layer, head) in turn the
-// die's runs of consecutive blocks).  Also clears the counters and the accumulators.
+// die's runs of consecutive blocks).  Also clears the counters and the accumulators and marks the units' sums unwritten.
 __global__ __launch_bounds__(256) void plan_kernel(TileItem *__restrict__ items, uint32_t n_items, RowMap km, PromptTab tab,
-                                                   ScanPlan plan, int LH, uint4 *sync, size_t n_sync, uint4 *accum, size_t n_accum)
+                                                   ScanPlan plan, int LH, uint4 *sync, size_t n_sync, uint4 *accum, size_t n_accum,
+                                                   uint4 *sums, size_t n_sums)
 {
     const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    const uint4 zero = make_uint4(0u, 0u, 0u, 0u);
-    for (size_t k = i; k < n_sync + n_accum; k += (size_t)gridDim.x * blockDim.x) {
+    const uint4 zero = make_uint4(0u, 0u, 0u, 0u), none = make_uint4(kUnwritten, kUnwritten, kUnwritten, kUnwritten);
+    for (size_t k = i; k < n_sync + n_accum + n_sums; k += (size_t)gridDim.x * blockDim.x) {
         if (k < n_sync) sync[k] = zero;
-        else accum[k - n_sync] = zero;
+        else if (k < n_sync + n_accum) accum[k - n_sync] = zero;
+        else sums[k - n_sync - n_accum] = none;
     }
     for (size_t k = i; k < n_items; k += (size_t)gridDim.x * blockDim.x) {
         const int x = (int)(k & (kDies - 1));
@@ -286,7 +292,8 @@ __global__ __launch_bounds__(256) void plan_kernel(TileItem *__restrict__ items,
 // through their loading and computing phases in step, and the pass takes 0.90 ms instead of 0.77.)
 __global__ __launch_bounds__(64 * kTileWaves, 4)
 void scan_tile_kernel(const uint8_t *__restrict__ keys, const TileItem *__restrict__ items, float *__restrict__ a_raw,
-                      unsigned long long *__restrict__ acc, uint32_t *__restrict__ sync, int64_t rows, int poll_limit)
+                      unsigned long long *__restrict__ acc, float *__restrict__ ssum, uint32_t *__restrict__ sync, int64_t rows,
+                      int poll_limit)
 {
     constexpr int D = 128, NW = kTileWaves, kRowBytes = D * 2;
     __shared__ __attribute__((aligned(16))) uint8_t lds_stage[NW][kStageBytes];   // a wave's group on its way to operand layout, later its anchors
@@ -338,9 +345,12 @@ void scan_tile_kernel(const uint8_t *__restrict__ keys, const TileItem *__restri
         b0 += t2.x;
         b1 += t2.y;
     }
-    if (w == (it.id & (NW - 1))) {                                    // one wave adds the block total to the unit's sum
-        __hip_atomic_fetch_add(acc_unit + 2 * lane, accum_term(b0), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __hip_atomic_fetch_add(acc_unit + 2 * lane + 1, accum_term(b1), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const bool poster = w == (it.id & (NW - 1));                      // one wave adds the block total to the unit's sum
+    unsigned long long after0 = 0ull, after1 = 0ull;                  // the accumulators right after this block's add
+    if (poster) {
+        const unsigned long long t0 = accum_term(b0), t1 = accum_term(b1);
+        after0 = __hip_atomic_fetch_add(acc_unit + 2 * lane, t0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + t0;
+        after1 = __hip_atomic_fetch_add(acc_unit + 2 * lane + 1, t1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + t1;
     }
     bsq = sum_over_rows16(row_sum<16>(fmaf(b0, b0, b1 * b1)));
 
@@ -360,6 +370,16 @@ void scan_tile_kernel(const uint8_t *__restrict__ keys, const TileItem *__restri
         }
     }
     stage_anchor(stage, 4, lane, b0, b1);                             // rows 4 .. 6: the block total's three terms
+    float *S_unit = ssum + (int64_t)it.unit * D;
+    if (poster) {                                                     // (the adds have had the staging to come back)
+        const __amdgpu_buffer_rsrc_t prs = __builtin_amdgcn_make_buffer_rsrc(S_unit, 0, D * 4, 0x00020000);
+        constexpr int kNoStore = 0x40000000;
+        // the last block to add to a word stores the word's final value; a word's adds take turns, so exactly one does
+        __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(accum_value(after0)), prs,
+                                              accum_complete(after0, unblk) ? 8 * lane : kNoStore, 0, 16);
+        __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(accum_value(after1)), prs,
+                                              accum_complete(after1, unblk) ? 8 * lane + 4 : kNoStore, 0, 16);
+    }
     __syncthreads();                                                  // the halo groups' sums
     // ---- the chain of this wave's groups ----
     // lane (qq, n) of a result holds rows 4 qq + rho, column n.  Masked weights of the rows: rows j <= n count.
@@ -435,15 +455,15 @@ void scan_tile_kernel(const uint8_t *__restrict__ keys, const TileItem *__restri
         }
     }
     // ---- stable dots against the unit's sum ----
-    if (w == 0) {                                                     // one wave looks, the others sit at the barrier
-        const __amdgpu_buffer_rsrc_t srs = __builtin_amdgcn_make_buffer_rsrc(acc_unit, 0, D * 8, 0x00020000);
+    if (w == 0) {                                                     // 32 lanes look, the other waves sit at the barrier
+        const __amdgpu_buffer_rsrc_t srs = __builtin_amdgcn_make_buffer_rsrc(S_unit, 0, D * 4, 0x00020000);
         bool got = false;
         for (int polls = 0; poll_limit >= 0; ++polls) {               // poll_limit < 0: defer without looking
-            const u32x4 sv = agent_load16(srs, lane * 16);            // dims 2 lane, 2 lane + 1
-            const unsigned long long a0 = ((unsigned long long)sv.y << 32) | sv.x, a1 = ((unsigned long long)sv.w << 32) | sv.z;
-            got = __all(accum_complete(a0, unblk) && accum_complete(a1, unblk));
+            u32x4 sv = {0u, 0u, 0u, 0u};
+            if (lane < 32) sv = agent_load16(srs, lane * 16);
+            got = __all(all_written(sv));
             if (got) {
-                *reinterpret_cast<float2 *>(&lds_S[2 * lane]) = make_float2(accum_value(a0), accum_value(a1));
+                if (lane < 32) *reinterpret_cast<u32x4 *>(&lds_S[4 * lane]) = sv;
                 break;
             }
             if (polls >= poll_limit) break;
@@ -481,7 +501,7 @@ void scan_tile_kernel(const uint8_t *__restrict__ keys, const TileItem *__restri
 // stored.
 __global__ __launch_bounds__(64 * kTileWaves) void deferred_stable_tile_kernel(const uint8_t *__restrict__ keys, RowMap km,
                                                                                PromptTab tab,
-                                                                               const unsigned long long *__restrict__ acc,
+                                                                               const float *__restrict__ ssum,
                                                                                const uint32_t *__restrict__ sync,
                                                                                float *__restrict__ a_raw)
 {
@@ -505,9 +525,8 @@ __global__ __launch_bounds__(64 * kTileWaves) void deferred_stable_tile_kernel(c
         const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
             const_cast<uint8_t *>(keys) + km.unit(lh, p, tab) * 2, 0, N * kRowBytes, 0x00020000);
         const __amdgpu_buffer_rsrc_t out_s = __builtin_amdgcn_make_buffer_rsrc(a_raw + row0, 0, blk_hi * 4, 0x00020000);
-        // every block of the pass has added to the accumulators by now (the pass has ended)
-        const unsigned long long *acc_unit = acc + ((int64_t)lh * tab.n + p) * D;
-        const float2 s2 = make_float2(accum_value(acc_unit[2 * lane]), accum_value(acc_unit[2 * lane + 1]));
+        // every word of the unit's sum has been stored by now (the pass has ended)
+        const float2 s2 = *reinterpret_cast<const float2 *>(ssum + ((int64_t)lh * tab.n + p) * D + 2 * lane);
         const float ssq = sum_over_rows16(row_sum<16>(fmaf(s2.x, s2.x, s2.y * s2.y)));
         __builtin_amdgcn_wave_barrier();                              // the previous block's reads of the staged rows
         stage_anchor(stage, 0, lane, s2.x, s2.y);
@@ -571,7 +590,7 @@ size_t tile_score_plan_bytes(int LH, const PromptTab &tab)
 }
 
 hipError_t launch_score_tile(const void *keys, const RowMap &km, int LH, const PromptTab &tab, float *a_raw, void *accum,
-                             void *sync_area, void *plan_area, int mode, const Prof &prof, hipStream_t st)
+                             float *ssum, void *sync_area, void *plan_area, int mode, const Prof &prof, hipStream_t st)
 {
     constexpr int D = 128;
     const bool defer_all = mode == kScanDeferAll || mode == kScanRepairAll;   // no unit is added up by a workgroup of its own here
@@ -579,14 +598,15 @@ hipError_t launch_score_tile(const void *keys, const RowMap &km, int LH, const P
     ScanPlan plan;
     const unsigned n_items = fill_scan_plan(LH, tab, km.H, &plan, false);
     plan_kernel<<<(unsigned)min(((size_t)n_items + 255) / 256, (size_t)2048), 256, 0, st>>>(
-        (TileItem *)plan_area, n_items, km, tab, plan, LH, (uint4 *)sync_area, kSyncWords / 4, (uint4 *)accum, na);
+        (TileItem *)plan_area, n_items, km, tab, plan, LH, (uint4 *)sync_area, kSyncWords / 4, (uint4 *)accum, na, (uint4 *)ssum,
+        na / 2);
     prof.begin(NKV_KERNEL_SCAN, st);
     scan_tile_kernel<<<n_items, 64 * kTileWaves, 0, st>>>((const uint8_t *)keys, (const TileItem *)plan_area, a_raw,
-                                                         (unsigned long long *)accum, (uint32_t *)sync_area,
+                                                         (unsigned long long *)accum, ssum, (uint32_t *)sync_area,
                                                          (int64_t)LH * tab.T, defer_all ? -1 : kPollLimit);
     prof.end(NKV_KERNEL_SCAN, st);
     deferred_stable_tile_kernel<<<defer_all ? 4096 : 256, 64 * kTileWaves, 0, st>>>(
-        (const uint8_t *)keys, km, tab, (const unsigned long long *)accum, (const uint32_t *)sync_area, a_raw);
+        (const uint8_t *)keys, km, tab, ssum, (const uint32_t *)sync_area, a_raw);
     return hipGetLastError();
 }
 
