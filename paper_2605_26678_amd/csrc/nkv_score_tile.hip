@@ -357,6 +357,17 @@ void scan_tile_kernel(const uint8_t *__restrict__ keys, const TileItem *__restri
     // ---- the halo group's sum (the window sums in front of the block's first groups need it) ----
     group_sum(raw[0], blk_lo + kGroup * (w - 4), blk_hi, g, c, lds_w[w][0], lds_ss[w][0], lds_T[w]);
 
+    float *S_unit = ssum + (int64_t)it.unit * D;
+    if (poster) {                                                     // (the adds have had the halo group to come back)
+        const __amdgpu_buffer_rsrc_t prs = __builtin_amdgcn_make_buffer_rsrc(S_unit, 0, D * 4, 0x00020000);
+        constexpr int kNoStore = 0x40000000;
+        // the last block to add to a word stores the word's final value; a word's adds take turns, so exactly one does
+        __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(accum_value(after0)), prs,
+                                              accum_complete(after0, unblk) ? 8 * lane : kNoStore, 0, 16);
+        __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(accum_value(after1)), prs,
+                                              accum_complete(after1, unblk) ? 8 * lane + 4 : kNoStore, 0, 16);
+    }
+
     // ---- every group through the staging rows into operand layout ----
     u32x4 X[5][4];
 #pragma unroll
@@ -370,16 +381,6 @@ void scan_tile_kernel(const uint8_t *__restrict__ keys, const TileItem *__restri
         }
     }
     stage_anchor(stage, 4, lane, b0, b1);                             // rows 4 .. 6: the block total's three terms
-    float *S_unit = ssum + (int64_t)it.unit * D;
-    if (poster) {                                                     // (the adds have had the staging to come back)
-        const __amdgpu_buffer_rsrc_t prs = __builtin_amdgcn_make_buffer_rsrc(S_unit, 0, D * 4, 0x00020000);
-        constexpr int kNoStore = 0x40000000;
-        // the last block to add to a word stores the word's final value; a word's adds take turns, so exactly one does
-        __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(accum_value(after0)), prs,
-                                              accum_complete(after0, unblk) ? 8 * lane : kNoStore, 0, 16);
-        __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(accum_value(after1)), prs,
-                                              accum_complete(after1, unblk) ? 8 * lane + 4 : kNoStore, 0, 16);
-    }
     __syncthreads();                                                  // the halo groups' sums
     // ---- the chain of this wave's groups ----
     // lane (qq, n) of a result holds rows 4 qq + rho, column n.  Masked weights of the rows: rows j <= n count.
