@@ -196,9 +196,9 @@ def main():
         run_all()
     torch.cuda.synchronize()
 
-    # Timed region: K steps; the two kernels that can dominate (key scan, K/V gather) are bracketed by their
-    # own event pairs, recorded by the library on the launch stream.  An event pair costs a few microseconds of
-    # pipeline bubble, so the other kernels are timed in K more steps after the timed region.
+    # Timed region: K steps; the kernel that dominates (the key scan) is bracketed by an event pair of its own,
+    # recorded by the library on the launch stream.  An event pair costs a few microseconds of pipeline bubble,
+    # so the other kernels are timed in K more steps after the timed region.
     def run_steps(names):
         evs = [[{name: (nkv.HipEvent(), nkv.HipEvent()) for name in names} for _ in calls] for _ in range(args.steps)]
         timed = [[nkv.with_kernel_timers(params, evs[i][c]) for c in range(len(calls))] for i in range(args.steps)]
@@ -214,8 +214,8 @@ def main():
         return wall, ms
 
     base_params = params
-    wall, kern_ms = run_steps(("scan", "gather"))
-    _, rest_ms = run_steps(tuple(k for k in nkv.PASS_KERNELS if k not in ("scan", "gather")))
+    wall, kern_ms = run_steps(("scan",))
+    _, rest_ms = run_steps(tuple(k for k in nkv.PASS_KERNELS if k != "scan"))
     kern_ms.update(rest_ms)
     kern_ms = {name: kern_ms[name] for name in nkv.PASS_KERNELS}
     ms_per_step = wall * 1e3 / args.steps
@@ -230,6 +230,9 @@ def main():
     roofline = {"bound": "hbm", "kernel": dominant, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                 "traffic": None if args.per_layer else read_traffic(dominant, w.name),
+                "traffic_source": None if args.per_layer or read_traffic(dominant, w.name) is None
+                else f"profiles/{dominant}_{w.name}_pmc.txt (rocprofv3 FETCH_SIZE + WRITE_SIZE of an earlier run of this "
+                     f"build, not measured in this run)",
                 "bytes_per_launch": ab[dominant] * head_tokens,
                 "kernel_ms": {k: round(v, 4) for k, v in kern_ms.items()},
                 "whole_pass": {"algorithmic_bytes": ab["total"] * head_tokens,

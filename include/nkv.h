@@ -79,9 +79,11 @@ enum {
                                       /* instead of the slice-wise ones                                      */
     NKV_FLAG_STATS_PER_HEAD = 32u,    /* nkv_score: the same choice for the per-head statistics              */
     NKV_FLAG_SELECT_PER_HEAD = 64u,   /* nkv_select_compact: the same choice for the top-B_h selection       */
-    NKV_FLAG_VECTOR_SCAN = 128u       /* streaming kernels: the vector-unit formulation of the fused pass    */
+    NKV_FLAG_VECTOR_SCAN = 128u,      /* streaming kernels: the vector-unit formulation of the fused pass    */
                                       /* also for bf16 keys of head dim 128, where the matrix-core one is   */
                                       /* the default                                                         */
+    NKV_FLAG_COMPACT_IN_PLACE = 256u  /* nkv_select_compact: the kept rows of a unit move to the front of    */
+                                      /* the unit's own rows in keys / values (no packed buffers)            */
 };
 /* Kernels a caller can ask to have timed, see nkv_params.prof_start. */
 enum {
@@ -253,6 +255,13 @@ int nkv_budget_noalloc(const float *scores, const nkv_shape *shape, const nkv_pa
  * score perturbations of that size.  `ws` may be NULL (ws_bytes 0): the selection then runs one workgroup per
  * unit; with scratch (nkv_workspace_bytes) prompts of more than 16384 tokens, and batches of 2048 units and
  * more, are selected slice-wise (same result, quicker).
+ *
+ * In place (params->flags & NKV_FLAG_COMPACT_IN_PLACE; Appendix A lists in-place compaction as what an
+ * implementation may do instead of a second cache): packed_k and packed_v must be NULL, and the kept rows of
+ * unit u are moved to rows 0 .. B_u - 1 of the unit's own rows inside `keys` and `values`, which this call
+ * therefore WRITES (the rows behind them keep stale contents).  head_off and kept_idx are written as above;
+ * row_capacity then only bounds kept_idx.  A kept row never moves backwards (the j-th kept token has index >= j),
+ * and a unit is moved by one workgroup front to back, so no row is overwritten before it has been read.
  */
 int nkv_select_compact(const void *keys, const void *values, const float *scores,
                        const int32_t *k_per_head, const nkv_shape *shape, const nkv_params *params,

@@ -26,6 +26,7 @@ FLAG_BUDGET_PER_HEAD = 16
 FLAG_STATS_PER_HEAD = 32
 FLAG_VECTOR_SCAN = 128
 FLAG_SELECT_PER_HEAD = 64
+FLAG_COMPACT_IN_PLACE = 256
 PIN = 3.0e38
 
 EXPORTS = ("nkv_params_default", "nkv_block_size", "nkv_k0", "nkv_m_safe", "nkv_m_p", "nkv_packed_rows",

@@ -436,11 +436,17 @@ int nkv_select_compact(const void *keys, const void *values, const float *scores
                        void *ws, size_t ws_bytes, void *hip_stream)
 {
     if (!keys || !values || !scores || !k_per_head || !head_off || row_capacity < 0) return NKV_EINVAL;
-    if (row_capacity > 0 && (!packed_k || !packed_v || !kept_idx)) return NKV_EINVAL;
     int rc = check_shape(shape);
     if (rc) return rc;
     rc = check_params(params);
     if (rc) return rc;
+    const bool in_place = (params->flags & NKV_FLAG_COMPACT_IN_PLACE) != 0;
+    if (in_place ? (packed_k || packed_v) : (row_capacity > 0 && (!packed_k || !packed_v))) return NKV_EINVAL;
+    if (row_capacity > 0 && !kept_idx) return NKV_EINVAL;
+    if (in_place) {                                                   // rows of 32 .. 1024 bytes, a power of two
+        for (const int bytes : {shape->d * esize_of(shape->dtype), shape->dv * esize_of(shape->dtype)})
+            if (bytes < 32 || bytes > 1024 || (bytes & (bytes - 1))) return NKV_EUNSUPPORTED;
+    }
     if ((uintptr_t)keys % 16 || (uintptr_t)values % 16 || (uintptr_t)packed_k % 16 || (uintptr_t)packed_v % 16)
         return NKV_EINVAL;
     PromptTab tab;
@@ -457,7 +463,7 @@ int nkv_select_compact(const void *keys, const void *values, const float *scores
     return launch_select_compact(keys, values, km, vm, (params->flags & NKV_FLAG_SELECT_PER_HEAD) ? nullptr : ws,
                                  scores, k_per_head, shape->L, shape->H, shape->d, shape->dv,
                                  esize_of(shape->dtype), tab, (float)params->near_tol, packed_k, packed_v,
-                                 kept_idx, head_off, row_capacity, near_threshold_count,
+                                 kept_idx, head_off, row_capacity, near_threshold_count, in_place,
                                  Prof{params->prof_start, params->prof_stop}, (hipStream_t)hip_stream) == hipSuccess
                ? NKV_OK : NKV_EHIP;
 }

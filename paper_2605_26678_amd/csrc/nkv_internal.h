@@ -143,7 +143,7 @@ hipError_t launch_select_compact(const void *keys, const void *values, const Row
                                  const int32_t *k_per_head, int L, int H, int d, int dv, int esize,
                                  const PromptTab &tab, float near_tol, void *packed_k, void *packed_v,
                                  int32_t *kept_idx, int64_t *head_off, int64_t row_capacity,
-                                 int64_t *near_count, const Prof &prof, hipStream_t st);
+                                 int64_t *near_count, bool in_place, const Prof &prof, hipStream_t st);
 
 // ---- decode-side consumer: attention of one new token over the packed cache ----
 bool decode_fast_supported(int dtype, int d, int dv, int G);

@@ -282,6 +282,46 @@ __global__ __launch_bounds__(256) void gather_kernel(const uint4 *__restrict__ k
     }
 }
 
+// In-place compaction: grid (units, 2); workgroup (u, 0) moves the kept K rows of unit u to the front of the unit's
+// own rows, workgroup (u, 1) the V rows.  The j-th kept row comes from row kept_idx[j] >= j, so rows only move
+// forwards; a workgroup takes its unit's rows in pieces of 128, front to back, and loads a whole piece into
+// registers before it stores any of it: a piece's sources lie at or behind its own destinations (so no earlier
+// piece's store has touched them), and what it overwrites are rows that this and earlier pieces have already read.
+constexpr int kInPlaceRows = 128, kInPlaceThreads = 256;
+template <int VPT>                       // 16-byte vectors per thread and piece: 128 rows x row16 / 256 threads
+__global__ __launch_bounds__(kInPlaceThreads) void compact_inplace_kernel(uint4 *__restrict__ keys, uint4 *__restrict__ values,
+                                                                          RowMap km, RowMap vm, int epv, int L, int H,
+                                                                          int krow16, int vrow16, PromptTab tab,
+                                                                          const int64_t *__restrict__ head_off,
+                                                                          const int32_t *__restrict__ kept_idx,
+                                                                          int64_t row_capacity)
+{
+    using v4 = unsigned int __attribute__((ext_vector_type(4)));
+    const int u = blockIdx.x, which = blockIdx.y;
+    const int h = u % H, l = (u / H) % L, p = u / (H * L);
+    const int row16 = which == 0 ? krow16 : vrow16;
+    if (VPT * kInPlaceThreads != kInPlaceRows * row16) return;        // (the host launches the matching instance)
+    v4 *base = reinterpret_cast<v4 *>(which == 0 ? keys : values) +
+               (which == 0 ? km.unit(l * H + h, p, tab) : vm.unit(l * H + h, p, tab)) / epv;
+    const int64_t r0 = head_off[u];
+    const int64_t B = min(head_off[u + 1], row_capacity) - r0;        // rows whose index the caller's kept_idx holds
+    for (int64_t j0 = 0; j0 < B; j0 += kInPlaceRows) {
+        const int nr = (int)min((int64_t)kInPlaceRows, B - j0);
+        v4 v[VPT];
+#pragma unroll
+        for (int i = 0; i < VPT; ++i) {
+            const int j = i * kInPlaceThreads + threadIdx.x, r = j / row16, c = j - r * row16;
+            if (r < nr) v[i] = __builtin_nontemporal_load(base + (int64_t)kept_idx[r0 + j0 + r] * row16 + c);
+        }
+        __syncthreads();                                              // every row of the piece is in registers
+#pragma unroll
+        for (int i = 0; i < VPT; ++i) {
+            const int j = i * kInPlaceThreads + threadIdx.x, r = j / row16, c = j - r * row16;
+            if (r < nr) __builtin_nontemporal_store(v[i], base + (j0 + r) * row16 + c);
+        }
+    }
+}
+
 // The yardstick: every workgroup moves contiguous 16 KB pieces with non-temporal 16-byte loads and stores, four
 // loads in flight per thread -- the access pattern of the gather above without its indirection.  dst == nullptr:
 // loads only (what a pure reader such as the decode consumer can reach); an empty assembly statement that takes
@@ -328,7 +368,7 @@ hipError_t launch_select_compact(const void *keys, const void *values, const Row
                                  const int32_t *k_per_head, int L, int H, int d, int dv, int esize,
                                  const PromptTab &tab, float near_tol, void *packed_k, void *packed_v,
                                  int32_t *kept_idx, int64_t *head_off, int64_t row_capacity,
-                                 int64_t *near_count, const Prof &prof, hipStream_t st)
+                                 int64_t *near_count, bool in_place, const Prof &prof, hipStream_t st)
 {
     const int n_units = tab.n * L * H;
     head_off_kernel<<<1, kThreads, 0, st>>>(k_per_head, L, H, tab, head_off, near_count);
@@ -358,7 +398,33 @@ hipError_t launch_select_compact(const void *keys, const void *values, const Row
     prof.end(NKV_KERNEL_SELECT, st);
     // no unit keeps more than its prompt length, so the row count is bounded by L*H*T as well
     const int64_t max_rows = row_capacity < (int64_t)L * H * tab.T ? row_capacity : (int64_t)L * H * tab.T;
-    if (max_rows > 0) {
+    if (max_rows > 0 && in_place) {
+        const int krow16 = d * esize / 16, vrow16 = dv * esize / 16;
+        prof.begin(NKV_KERNEL_GATHER, st);
+        // one instance per row width; K and V rows of different widths take a launch each
+        for (int which = 0; which < 2; ++which) {
+            const int row16 = which == 0 ? krow16 : vrow16;
+            if (which == 1 && vrow16 == krow16) break;                // both were moved by the first launch
+            const dim3 grid((unsigned)n_units, vrow16 == krow16 ? 2u : 1u);
+            uint4 *k4 = (uint4 *)const_cast<void *>(keys), *v4p = (uint4 *)const_cast<void *>(values);
+            uint4 *a = which == 0 ? k4 : v4p, *b = which == 0 ? v4p : k4;          // blockIdx.y == 0 moves `a`
+            const RowMap &am = which == 0 ? km : vm, &bm = which == 0 ? vm : km;
+#define NKV_INPLACE(VPT)                                                                                             \
+    compact_inplace_kernel<VPT><<<grid, kInPlaceThreads, 0, st>>>(a, b, am, bm, 16 / esize, L, H, row16, row16, tab, \
+                                                                  head_off, kept_idx, row_capacity)
+            switch (row16 * kInPlaceRows / kInPlaceThreads) {
+            case 1: NKV_INPLACE(1); break;
+            case 2: NKV_INPLACE(2); break;
+            case 4: NKV_INPLACE(4); break;
+            case 8: NKV_INPLACE(8); break;
+            case 16: NKV_INPLACE(16); break;
+            case 32: NKV_INPLACE(32); break;
+            default: return hipErrorInvalidValue;                     // (refused by the caller: see in_place_supported)
+            }
+#undef NKV_INPLACE
+        }
+        prof.end(NKV_KERNEL_GATHER, st);
+    } else if (max_rows > 0) {
         const unsigned groups = (unsigned)((max_rows + kRowsPerGroup - 1) / kRowsPerGroup);
         prof.begin(NKV_KERNEL_GATHER, st);
         gather_kernel<<<groups, 256, 0, st>>>((const uint4 *)keys, (const uint4 *)values, km, vm, 16 / esize, L, H,

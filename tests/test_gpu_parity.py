@@ -276,6 +276,45 @@ def test_given_budgets_are_clamped_and_capacity_is_respected():
     assert np.array_equal(bits(pk[:30]), bits(K[0, 0, :30])) and torch.all(pk[30:] == 7.0)
 
 
+@pytest.mark.parametrize("dtype,d,dv", [("bf16", 128, 128), ("fp32", 64, 32), ("fp8", 128, 64)])
+@pytest.mark.parametrize("r", [0.75, 0.05, 0.999])
+def test_compaction_in_place_against_the_oracle(dtype, d, dv, r):
+    """NKV_FLAG_COMPACT_IN_PLACE, fed the oracle's scores and budgets: rows 0 .. B_u - 1 of every unit inside the
+    caller's own K and V tensors hold the oracle's packed rows of that unit bit for bit, the rows behind them are
+    untouched, head_off and kept_idx are the oracle's.  Ratios that keep a quarter, nearly all (rows barely move,
+    sources and destinations of neighbouring pieces interleave) and nearly nothing."""
+    w = nkv_inputs.small_workload("inplace", 2, 3, d, [9000, 700, 130, 4097], dtype=dtype, dv=dv)
+    K, V = _kv(w)
+    shape, op = shape_of(w), oracle_params(nkv.params_default())
+    r_list = [r] * shape.n_prompts
+    ref = oracle.compress(K.cpu().float().numpy(), bits(K), bits(V), w.cu_seqlens, r_list, op)
+    p = nkv.params_default(flags=nkv.FLAG_COMPACT_IN_PLACE)
+    Kw, Vw = K.clone(), V.clone()
+    rows = int(ref.head_off[-1])
+    idx = torch.empty(max(rows, 1), dtype=torch.int32, device=DEV)
+    off = torch.empty(shape.n_units + 1, dtype=torch.int64, device=DEV)
+    ws = torch.empty(nkv.workspace_bytes(shape, p), dtype=torch.uint8, device=DEV)
+    nkv.select_compact(Kw, Vw, torch.from_numpy(ref.scores).to(DEV), torch.from_numpy(ref.k_per_head).to(DEV), shape, p,
+                       None, None, idx, off, rows, None, ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(off.cpu().numpy(), ref.head_off) and np.array_equal(idx[:rows].cpu().numpy(), ref.kept_idx)
+    Kb, Vb, K0, V0, cu = bits(Kw), bits(Vw), bits(K), bits(V), w.cu_seqlens
+    for pr in range(shape.n_prompts):
+        for l in range(w.L):
+            for h in range(w.H):
+                u = (pr * w.L + l) * w.H + h
+                a, b = int(ref.head_off[u]), int(ref.head_off[u + 1])
+                lo, hi = cu[pr], cu[pr + 1]
+                assert np.array_equal(Kb[l, h, lo:lo + b - a], ref.packed_k[a:b]), f"unit {u}: K rows"
+                assert np.array_equal(Vb[l, h, lo:lo + b - a], ref.packed_v[a:b]), f"unit {u}: V rows"
+                assert np.array_equal(Kb[l, h, lo + b - a:hi], K0[l, h, lo + b - a:hi]), f"unit {u}: K rows behind"
+                assert np.array_equal(Vb[l, h, lo + b - a:hi], V0[l, h, lo + b - a:hi]), f"unit {u}: V rows behind"
+    # packed buffers together with the flag, and row widths the in-place kernels do not take, are refused
+    with pytest.raises(nkv.NkvError):
+        nkv.select_compact(Kw, Vw, torch.from_numpy(ref.scores).to(DEV), torch.from_numpy(ref.k_per_head).to(DEV), shape, p,
+                           Kw, Vw, idx, off, rows, None, ws)
+
+
 # ------------------------------------------------------------------ parameters and variants
 VARIANTS = [
     dict(gate_mode=1), dict(gate_mode=2), dict(surprise_mode=1), dict(beta=0.0),
