@@ -256,8 +256,9 @@ int nkv_budget_noalloc(const float *scores, const nkv_shape *shape, const nkv_pa
  * unit; with scratch (nkv_workspace_bytes) prompts of more than 16384 tokens, and batches of 2048 units and
  * more, are selected slice-wise (same result, quicker).
  *
- * In place (params->flags & NKV_FLAG_COMPACT_IN_PLACE; Appendix A lists in-place compaction as what an
- * implementation may do instead of a second cache): packed_k and packed_v must be NULL, and the kept rows of
+ * In place (params->flags & NKV_FLAG_COMPACT_IN_PLACE): the method only removes cached positions and leaves the
+ * retained keys and values unchanged (Appendix A, "Scoring cost"), so the cache can shrink where it lies instead
+ * of being copied into a second one.  packed_k and packed_v must be NULL, and the kept rows of
  * unit u are moved to rows 0 .. B_u - 1 of the unit's own rows inside `keys` and `values`, which this call
  * therefore WRITES (the rows behind them keep stale contents).  head_off and kept_idx are written as above;
  * row_capacity then only bounds kept_idx.  A kept row never moves backwards (the j-th kept token has index >= j),
