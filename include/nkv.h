@@ -139,7 +139,8 @@ typedef struct nkv_params {
     void    *prof_stop[NKV_KERNEL_COUNT];
     /* Optional health counters of the fused streaming scan: NULL, or a DEVICE pointer to two uint32 that        */
     /* nkv_score / nkv_score_raw fill on their stream: [0] workgroups that gave up adding a unit's block totals  */
-    /* up inside the pass (the unit's sum was then formed afterwards; 0 in normal operation), [1] blocks whose   */
+    /* up inside the pass (the unit's sum was then formed afterwards; 0 in normal operation, and always 0 for    */
+    /* bf16 keys of head dim 128, whose pass adds every block straight into the unit's sum), [1] blocks whose    */
     /* stable anomaly was computed after the pass because the unit's sum did not arrive within the bounded       */
     /* wait.  Neither affects the result.  Both are 0 on the routes that do not use the fused pass.              */
     void    *scan_counters;

@@ -92,7 +92,9 @@ SWEEP = [
     ("heads_16_long", 1, 16, 128, [20000], "bf16", 0),
     ("slice_edges", 1, 2, 128, [8193, 16385, 100, 24576], "bf16", 0),   # one token past a slice, exact slices
     ("slices_d64", 1, 3, 64, [17000], "bf16", 0),
-    ("nine_slices", 1, 2, 128, [70000, 9000], "bf16", 0), # 274 blocks in the unit: two rounds of the dies' runs
+    ("nine_slices", 1, 2, 128, [70000, 9000], "bf16", 0), # 274 blocks in the unit: two rounds of the dies' runs;
+                                                          # more than the matrix-core scan takes: vector scan
+    ("unit_256_blocks", 1, 2, 128, [65533, 300], "bf16", 0),   # the longest unit the matrix-core scan takes
 ]
 
 
@@ -125,7 +127,7 @@ def test_8bit_keys_of_every_finite_code(flags):
 
 
 TILE_CASES = ["below_window", "one_short_block", "block_tail", "b_between", "b_255", "ragged_small", "dv_differs",
-              "slice_edges", "nine_slices"]
+              "slice_edges", "unit_256_blocks"]
 
 
 @pytest.mark.parametrize("route", [0, nkv.FLAG_DEFER_STABLE, nkv.FLAG_NO_UNIT_SUMS])
