@@ -193,8 +193,9 @@ __global__ __launch_bounds__(kWideThreads) void slice_collect_kernel(const float
     const float *sc = scores + (int64_t)lh * tab.T + tab.tok_off[p];
     const int tid = threadIdx.x;
     float v[kPerThread];
+    const __amdgpu_buffer_rsrc_t vals = slice_values(sc, s, N);
 #pragma unroll
-    for (int j = 0; j < kPerThread; ++j) v[j] = sc[min(s * kSlice + j * kWideThreads + tid, N - 1)];
+    for (int j = 0; j < kPerThread; ++j) v[j] = slice_value(vals, tid, j);
     const LayerPick *pk = picks + pl;
     const int bT = pk->bT[h], bL = pk->bL;
     const uint32_t done = pk->done;

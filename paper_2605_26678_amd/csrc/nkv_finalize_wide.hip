@@ -60,15 +60,18 @@ __global__ __launch_bounds__(kWideThreads) void stats_hist_kernel(const float *_
     const int tid = threadIdx.x;
     for (int j = tid; j < kBins; j += kWideThreads) hist[j] = 0u;
     float v[kPerThread];
+    const __amdgpu_buffer_rsrc_t vals = slice_values(a, s, N);
 #pragma unroll
-    for (int j = 0; j < kPerThread; ++j) v[j] = a[min(s * kSlice + j * kWideThreads + tid, N - 1)];
+    for (int j = 0; j < kPerThread; ++j) v[j] = slice_value(vals, tid, j);
     __syncthreads();
-    float lo = INFINITY, hi = -INFINITY;                             // the clamped duplicates do not change min / max
+    float lo = INFINITY, hi = -INFINITY;
 #pragma unroll
     for (int j = 0; j < kPerThread; ++j) {
-        lo = fminf(lo, v[j]);
-        hi = fmaxf(hi, v[j]);
-        if (s * kSlice + j * kWideThreads + tid < N) atomicAdd(&hist[anomaly_bin(v[j])], 1u);
+        if (s * kSlice + j * kWideThreads + tid < N) {
+            lo = fminf(lo, v[j]);
+            hi = fmaxf(hi, v[j]);
+            atomicAdd(&hist[anomaly_bin(v[j])], 1u);
+        }
     }
     lo = wave_min(lo);
     hi = wave_max(hi);
@@ -165,7 +168,7 @@ __global__ __launch_bounds__(kWideThreads) void stats_pick_kernel(int L, int H, 
 // grid: slices.  All three scales of the slice in one pass: what stats_finish_kernel needs of each scale, and --
 // the ranges being known -- min, max and sum of the surprise statistic of the slice's tokens.
 template <bool ALL>
-__global__ __launch_bounds__(kWideThreads) void stats_collect_kernel(const float *__restrict__ a_raw, int64_t rows,
+__global__ __launch_bounds__(kWideThreads, 5) void stats_collect_kernel(const float *__restrict__ a_raw, int64_t rows,
                                                                      int L, int H, PromptTab tab, SliceTab st,
                                                                      int n_slices, int scale_mask,
                                                                      const StatPick *__restrict__ picks,
@@ -195,6 +198,7 @@ __global__ __launch_bounds__(kWideThreads) void stats_collect_kernel(const float
     }
     if (tid < 3) { nTop[tid] = 0u; nBot[tid] = 0u; }
     __syncthreads();
+    const __amdgpu_buffer_rsrc_t vals[3] = {slice_values(a, s, N), slice_values(a + rows, s, N), slice_values(a + 2 * rows, s, N)};
     float pt[3] = {0.f, 0.f, 0.f}, pb[3] = {0.f, 0.f, 0.f};          // a few dozen terms of magnitude <= 1 each
     float smin = INFINITY, smax = -INFINITY;
     float ssum32 = 0.f;                                              // 32 terms of magnitude <= 0.5
@@ -204,8 +208,7 @@ __global__ __launch_bounds__(kWideThreads) void stats_collect_kernel(const float
 #pragma unroll
         for (int k = 0; k < 3; ++k)
 #pragma unroll
-            for (int j = 0; j < HALF; ++j)
-                v[k][j] = a[(int64_t)k * rows + min(s * kSlice + (half * HALF + j) * kWideThreads + tid, N - 1)];
+            for (int j = 0; j < HALF; ++j) v[k][j] = slice_value(vals[k], tid, half * HALF + j);
 #pragma unroll
         for (int j = 0; j < HALF; ++j) {
             if (s * kSlice + (half * HALF + j) * kWideThreads + tid < N) {
@@ -268,7 +271,7 @@ __global__ __launch_bounds__(kWideThreads) void stats_collect_kernel(const float
 // grid: slices.  Blend, gate, route and pinning of the slice's tokens (Section 2.4); every workgroup forms its
 // head's weights and surprise statistics itself from the few numbers they depend on.
 template <bool ALL>
-__global__ __launch_bounds__(kWideThreads) void route_slice_kernel(const float *__restrict__ a_raw, int64_t rows,
+__global__ __launch_bounds__(kWideThreads, 5) void route_slice_kernel(const float *__restrict__ a_raw, int64_t rows,
                                                                    int L, int H, PromptTab tab, SliceTab st,
                                                                    LearnerConsts lc, const float *__restrict__ stats,
                                                                    const SliceSurprise *__restrict__ sur,
@@ -283,10 +286,11 @@ __global__ __launch_bounds__(kWideThreads) void route_slice_kernel(const float *
     const int tid = threadIdx.x;
     constexpr int HALF = kPerThread / 2;
     float v[3][HALF];
+    const __amdgpu_buffer_rsrc_t vals[3] = {slice_values(a, s, N), slice_values(a + rows, s, N), slice_values(a + 2 * rows, s, N)};
 #pragma unroll
     for (int k = 0; k < 3; ++k)
 #pragma unroll
-        for (int j = 0; j < HALF; ++j) v[k][j] = a[(int64_t)k * rows + min(s * kSlice + j * kWideThreads + tid, N - 1)];
+        for (int j = 0; j < HALF; ++j) v[k][j] = slice_value(vals[k], tid, j);
     if (tid == 0) {
         head_weights(stats + ((int64_t)p * L * H + lh) * 12, lc, hs);
         float smin = INFINITY, smax = -INFINITY;
@@ -311,8 +315,7 @@ __global__ __launch_bounds__(kWideThreads) void route_slice_kernel(const float *
 #pragma unroll
             for (int k = 0; k < 3; ++k)
 #pragma unroll
-                for (int j = 0; j < HALF; ++j)
-                    v[k][j] = a[(int64_t)k * rows + min(s * kSlice + (HALF + j) * kWideThreads + tid, N - 1)];
+                for (int j = 0; j < HALF; ++j) v[k][j] = slice_value(vals[k], tid, HALF + j);
         }
 #pragma unroll
         for (int j = 0; j < HALF; ++j) {

@@ -125,8 +125,9 @@ __global__ __launch_bounds__(kWideThreads) void sel_collect_kernel(const float *
     const float *sc = scores + (int64_t)lh * tab.T + tab.tok_off[p];
     const int tid = threadIdx.x;
     float v[kPerThread];
+    const __amdgpu_buffer_rsrc_t vals = slice_values(sc, s, N);
 #pragma unroll
-    for (int j = 0; j < kPerThread; ++j) v[j] = sc[min(s * kSlice + j * kWideThreads + tid, N - 1)];
+    for (int j = 0; j < kPerThread; ++j) v[j] = slice_value(vals, tid, j);
     const int bT = picks[u].bT;
     if (tid == 0) n_hit = 0u;
     __syncthreads();
@@ -228,6 +229,12 @@ __global__ __launch_bounds__(64) void sel_finish_kernel(const float *__restrict_
     }
 }
 
+// set bits of m in the lanes below this one
+__device__ __forceinline__ uint32_t lanes_below(unsigned long long m)
+{
+    return __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
+}
+
 // grid: slices
 __global__ __launch_bounds__(kWideThreads) void sel_compact_kernel(const float *__restrict__ scores, int L, int H,
                                                                    PromptTab tab, SliceTab st,
@@ -248,28 +255,35 @@ __global__ __launch_bounds__(kWideThreads) void sel_compact_kernel(const float *
     const float *sc = scores + (int64_t)lh * tab.T + tab.tok_off[p];
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     float v[kPerThread];
+    const __amdgpu_buffer_rsrc_t vals = slice_values(sc, s, N);
 #pragma unroll
-    for (int j = 0; j < kPerThread; ++j) v[j] = sc[min(s * kSlice + j * kWideThreads + tid, N - 1)];
+    for (int j = 0; j < kPerThread; ++j) v[j] = slice_value(vals, tid, j);
     const SelUnit su = sel[u];
     const SelSlice sl = ss[blockIdx.x];
     if (su.mode >= 2u) return;                                       // nothing kept
     const bool all = su.mode == 1u;
     const uint32_t T = su.T, rem = su.rem;
     // population of every 64-token group (chunk j, wave w) = tokens s*kSlice + j*256 + w*64 ...
-    unsigned long long near = 0;
+    uint32_t near = 0u;
     const float tv = key_value(T);
+    uint32_t gmask = 0u, emask = 0u;                                 // bit j: slot j is kept for sure / is tied at T
 #pragma unroll
     for (int j = 0; j < kPerThread; ++j) {
         const bool in = s * kSlice + j * kWideThreads + tid < N;
         const uint32_t key = ord_key(v[j]);
         const bool gt = in && (all || key > T);
         const bool eq = in && !all && key == T;
+        gmask |= (gt ? 1u : 0u) << j;
+        emask |= (eq ? 1u : 0u) << j;
         const unsigned long long mg = __ballot(gt), me = __ballot(eq);
         if (lane == 0) {
             cnt_gt[j * (kWideThreads / 64) + w] = (uint32_t)__popcll(mg);
             cnt_eq[j * (kWideThreads / 64) + w] = (uint32_t)__popcll(me);
         }
         if (near_count && in && !all && fabsf(v[j] - tv) <= near_tol) ++near;
+        // one group at a time, its flags folded into the words right away: a condition kept for later is two scalar
+        // registers, and 128 of them do not fit
+        asm volatile("" : "+v"(gmask), "+v"(emask), "+v"(near));
     }
     __syncthreads();
     if (w == 0) {                                                    // exclusive scan over the groups: 2 per lane
@@ -298,27 +312,26 @@ __global__ __launch_bounds__(kWideThreads) void sel_compact_kernel(const float *
         }
     }
     __syncthreads();
+    // The two flag words are all the second pass needs of the values (and the compiler is kept from carrying the
+    // first pass's 64 ballots over instead, which costs it more registers than it has).
+    asm volatile("" : "+v"(gmask), "+v"(emask));
     const int64_t out0 = head_off[u];
-    const unsigned long long below = (1ull << lane) - 1ull;
 #pragma unroll
     for (int j = 0; j < kPerThread; ++j) {
         const int i = s * kSlice + j * kWideThreads + tid;
-        const bool in = i < N;
-        const uint32_t key = ord_key(v[j]);
-        const bool gt = in && (all || key > T);
-        const bool eq = in && !all && key == T;
+        const bool gt = (gmask >> j) & 1u, eq = (emask >> j) & 1u;
         const unsigned long long mg = __ballot(gt), me = __ballot(eq);
         const int grp = j * (kWideThreads / 64) + w;
-        const uint32_t gt_before = sl.gt_before + cnt_gt[grp] + (uint32_t)__popcll(mg & below);
-        const uint32_t eq_before = sl.eq_before + cnt_eq[grp] + (uint32_t)__popcll(me & below);
+        const uint32_t gt_before = sl.gt_before + cnt_gt[grp] + lanes_below(mg);
+        const uint32_t eq_before = sl.eq_before + cnt_eq[grp] + lanes_below(me);
         if (gt || (eq && eq_before < rem)) {
             const int64_t row = out0 + gt_before + min(eq_before, rem);
             if (row < row_capacity) kept_idx[row] = i;
         }
     }
     if (near_count) {
-        near = wave_sum(near);
-        if (lane == 0) near_acc[w] = near;
+        const unsigned long long near_w = wave_sum((unsigned long long)near);
+        if (lane == 0) near_acc[w] = near_w;
         __syncthreads();
         if (tid == 0) {
             unsigned long long t = 0;

@@ -52,6 +52,20 @@ __device__ __forceinline__ void locate(const SliceTab &st, const PromptTab &tab,
     s = local - lh * S;
 }
 
+// The values of slice s of a head of N tokens, as the hardware's bounds-checked buffer: slot j of thread tid is
+// element j * 256 + tid of the slice (one instruction of a wavefront reads one contiguous 256-byte piece, the
+// address is one register and a constant), and elements past the head's last token read as 0.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t slice_values(const float *head, int s, int N)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(head + (int64_t)s * kSlice), 0,
+                                             min(N - s * kSlice, kSlice) * 4, 0x00020000);
+}
+
+__device__ __forceinline__ float slice_value(__amdgpu_buffer_rsrc_t r, int tid, int j)
+{
+    return __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(r, tid * 4, j * (kWideThreads * 4), 0));
+}
+
 // Scores: floor(2046 v) for 0 <= v <= 1, 0 below, 2047 above 1 (the pinned positions).  Monotone in v.
 __device__ __forceinline__ int score_bin(float v)
 {
@@ -86,8 +100,9 @@ __global__ __launch_bounds__(kWideThreads) void slice_hist_kernel(const float *_
     const int tid = threadIdx.x;
     for (int j = tid; j < kBins; j += kWideThreads) hist[j] = 0u;
     float v[kPerThread];
+    const __amdgpu_buffer_rsrc_t vals = slice_values(sc, s, N);
 #pragma unroll
-    for (int j = 0; j < kPerThread; ++j) v[j] = sc[min(s * kSlice + j * kWideThreads + tid, N - 1)];
+    for (int j = 0; j < kPerThread; ++j) v[j] = slice_value(vals, tid, j);
     __syncthreads();
 #pragma unroll
     for (int j = 0; j < kPerThread; ++j)
