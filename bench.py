@@ -129,6 +129,92 @@ def bench_decode(args):
     return 0
 
 
+def bench_prefill_overlap(args):
+    """How much a prefill loop lengthens when every layer's K/V are compressed as soon as they exist (Section 2.1:
+    the method runs once after prefill, layer by layer; Section 4.4 reports prefill time with and without it).
+
+    The layer's own work is a stand-in: the four projection GEMMs of a Qwen3-4B-shaped decoder layer over the
+    whole prompt in bf16 (torch.matmul; attention itself is left out, so a real layer takes longer and hides
+    more).  Three runs over all layers: the GEMMs alone; the GEMMs with the layer's compression pass (L = 1 calls
+    of the three entry points) on a second stream, started when the layer's K/V projection is done; and the
+    same calls in line on the GEMMs' stream."""
+    import torch
+    import nkv_inputs
+    import paper_2605_26678_amd as nkv
+
+    nkv.lib()
+    w = nkv_inputs.WORKLOADS[args.workload]
+    r = args.ratio if args.ratio is not None else w.ratios[0]
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    K, V = nkv_inputs.make_kv(w, dev)
+    dtype = {"fp32": nkv.DTYPE_F32, "bf16": nkv.DTYPE_BF16, "fp16": nkv.DTYPE_F16, "fp8": nkv.DTYPE_F8_E4M3}[w.dtype]
+    params = nkv.params_default()
+    r_list = [r] * (len(w.cu_seqlens) - 1)
+    shape1 = nkv.Shape(1, w.H, w.d, w.d_v, dtype, w.cu_seqlens)
+    comps = [nkv.Compressor(shape1, r_list, params) for _ in range(w.L)]
+    hidden, inter, q_dim, kv_dim = 2560, 9728, 4096, 2 * w.H * w.d
+    g = torch.Generator(device=dev).manual_seed(0)
+    def mat(m, n):
+        return (torch.randn(m, n, device=dev, dtype=torch.float32, generator=g) * (m ** -0.5)).to(torch.bfloat16)
+    Wqkv, Wo, Wgu, Wd = mat(hidden, q_dim + kv_dim), mat(q_dim, hidden), mat(hidden, 2 * inter), mat(inter, hidden)
+    x = mat(w.T, hidden)
+    flops_layer = 2.0 * w.T * (hidden * (q_dim + kv_dim) + q_dim * hidden + hidden * 2 * inter + inter * hidden)
+    main, side = torch.cuda.current_stream(), torch.cuda.Stream()
+    kv_ready = [torch.cuda.Event() for _ in range(w.L)]
+    side_done = torch.cuda.Event()
+
+    def layer_gemms(l, after_kv):
+        qkv = x @ Wqkv
+        after_kv(l)
+        h = qkv[:, :q_dim] @ Wo
+        gu = h @ Wgu
+        return gu[:, :inter] @ Wd
+
+    def none(l):
+        pass
+
+    def on_side(l):
+        kv_ready[l].record(main)
+        side.wait_event(kv_ready[l])
+        comps[l].run(K[l], V[l], side)
+
+    def in_line(l):
+        comps[l].run(K[l], V[l], main)
+
+    def run(after_kv):
+        for l in range(w.L):
+            layer_gemms(l, after_kv)
+        if after_kv is on_side:
+            side_done.record(side)
+            main.wait_event(side_done)
+
+    out = {}
+    for name, fn in (("gemms_alone", none), ("compression_on_second_stream", on_side), ("compression_in_line", in_line)):
+        for _ in range(max(args.warmup, 1)):
+            run(fn)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            run(fn)
+        torch.cuda.synchronize()
+        out[name] = (time.perf_counter() - t0) / args.steps * 1e3
+    base = out["gemms_alone"]
+    res = {"metric": "prefill time added by compressing every layer's K/V as it is produced", "unit": "percent",
+           "value": round((out["compression_on_second_stream"] - base) / base * 100, 3),
+           "in_line_percent": round((out["compression_in_line"] - base) / base * 100, 3),
+           "ms_per_step": {k: round(v, 3) for k, v in out.items()}, "n_gpus": 1, "steps": args.steps,
+           "warmup": args.warmup, "higher_is_better": False, "dtype": "f32", "data": "synthetic",
+           "config": {"workload": f"{w.name}: per layer {w.H} KV heads x {list(w.prompt_lens)} tokens x d={w.d}, {w.dtype} K/V, "
+                                  f"r={r}; {w.L} layers",
+                      "layer_stand_in": f"bf16 GEMMs [T,{hidden}]x[{hidden},{q_dim + kv_dim}], [T,{q_dim}]x[{q_dim},{hidden}], "
+                                        f"[T,{hidden}]x[{hidden},{2 * inter}], [T,{inter}]x[{inter},{hidden}] (no attention)",
+                      "stand_in_tflops": round(flops_layer * w.L / (base * 1e-3) / 1e12, 1),
+                      "inputs": nkv_inputs.recipe(w)}}
+    print(json.dumps(res))
+    return 0
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -146,8 +232,9 @@ def main():
     ap.add_argument("--layer-tensors", action="store_true",
                     help="every layer's K and V in an allocation of its own (a framework's list of per-layer caches), "
                          "still one call over all layers")
-    ap.add_argument("--mode", choices=("pass", "decode"), default="pass",
-                    help="pass: the compression pass (default); decode: attention over the compressed cache")
+    ap.add_argument("--mode", choices=("pass", "decode", "prefill-overlap"), default="pass",
+                    help="pass: the compression pass (default); decode: attention over the compressed cache; "
+                         "prefill-overlap: layer-by-layer calls beside a stand-in for the layers' own GEMMs")
     ap.add_argument("--q-heads", type=int, default=0, help="decode mode: query heads (default 4 per KV head)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -155,6 +242,8 @@ def main():
         return 2
     if args.mode == "decode":
         return bench_decode(args)
+    if args.mode == "prefill-overlap":
+        return bench_prefill_overlap(args)
 
     import torch
     import nkv_inputs

@@ -195,7 +195,7 @@ int run_raw(const void *keys, const nkv_shape *s, const nkv_params *p, const Pro
                      : (p->flags & NKV_FLAG_DEFER_STABLE)  ? kScanDeferAll : kScanFused;
     if (!(p->flags & NKV_FLAG_GENERIC_KERNELS) && !(p->flags & NKV_FLAG_VECTOR_SCAN) && mode != kScanTwoPass &&
         tile_score_supported(s->dtype, s->d, p->window, tab, LH))
-        e = launch_score_tile(keys, km, LH, tab, a_raw, ws + lay.ssum, (float *)(ws + lay.bsum), ws + lay.sync, ws + lay.plan,
+        e = launch_score_tile(keys, km, s->dtype, LH, tab, a_raw, ws + lay.ssum, (float *)(ws + lay.bsum), ws + lay.sync, ws + lay.plan,
                               mode, prof, st);
     else if (!(p->flags & NKV_FLAG_GENERIC_KERNELS) && fast_score_supported(s->dtype, s->d, p->window, tab))
         e = launch_score_fast(keys, km, s->dtype, LH, s->d, tab, a_raw, (float *)(ws + lay.bsum), (float *)(ws + lay.ssum),

@@ -81,11 +81,12 @@ enum { kScanFused = 0, kScanTwoPass = 1, kScanDeferAll = 2, kScanRepairAll = 3 }
 hipError_t launch_score_fast(const void *keys, const RowMap &km, int dtype, int LH, int d, const PromptTab &tab, float *a_raw,
                              float *bsum, float *ssum, void *sync_area, int mode, const Prof &prof, hipStream_t st);
 
-// ---- scoring, matrix-core formulation of the fused streaming pass (bf16, d = 128, window 64, block size <= 256) ----
+// ---- scoring, matrix-core formulation of the fused streaming pass (bf16 or fp16, d = 128, window 64, block size <= 256) ----
 bool tile_score_supported(int dtype, int d, int window, const PromptTab &tab, int LH);
 size_t tile_score_plan_bytes(int LH, const PromptTab &tab);    // the list of items the pass works through
-hipError_t launch_score_tile(const void *keys, const RowMap &km, int LH, const PromptTab &tab, float *a_raw, void *accum,
-                             float *ssum, void *sync_area, void *plan_area, int mode, const Prof &prof, hipStream_t st);
+hipError_t launch_score_tile(const void *keys, const RowMap &km, int dtype, int LH, const PromptTab &tab, float *a_raw,
+                             void *accum, float *ssum, void *sync_area, void *plan_area, int mode, const Prof &prof,
+                             hipStream_t st);
 
 // Units are numbered prompt by prompt, so the units of consecutive prompts of similar length form one
 // range.  Calls f(ept, unit0, units) for every maximal run of prompts whose lengths need the same number

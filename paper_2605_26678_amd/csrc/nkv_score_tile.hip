@@ -43,6 +43,7 @@ namespace nkv {
 namespace {
 
 using bf16x8 = __bf16 __attribute__((ext_vector_type(8)));
+using f16x8 = _Float16 __attribute__((ext_vector_type(8)));
 using f32x4 = float __attribute__((ext_vector_type(4)));
 
 constexpr int kGroup = 16;                       // tokens per group
@@ -52,17 +53,21 @@ constexpr int kStageBytes = kGroup * kPitch;
 constexpr int kTileWaves = 4;
 
 
-__device__ __forceinline__ f32x4 mma(const u32x4 &a, const u32x4 &b, f32x4 c)
+// KF: the keys' 16-bit format (kKeyBF16 or kKeyF16), which is also the format the anchors' terms are staged in
+template <int KF> __device__ __forceinline__ f32x4 mma(const u32x4 &a, const u32x4 &b, f32x4 c)
 {
-    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+    if constexpr (KF == kKeyF16)
+        return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+    else
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
 }
 
 // D[m][n] = sum over the head dimension of a's row m and b's row n
-template <int KS> __device__ __forceinline__ f32x4 tile(const u32x4 (&a)[KS], const u32x4 (&b)[KS])
+template <int KF, int KS> __device__ __forceinline__ f32x4 tile(const u32x4 (&a)[KS], const u32x4 (&b)[KS])
 {
     f32x4 c = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int kk = 0; kk < KS; ++kk) c = mma(a[kk], b[kk], c);
+    for (int kk = 0; kk < KS; ++kk) c = mma<KF>(a[kk], b[kk], c);
     return c;
 }
 
@@ -108,9 +113,22 @@ __device__ __forceinline__ float row_prefix_sum(float x)
     return x;
 }
 
-// fp32 -> three bf16 terms whose sum is the value (each takes the next 8 mantissa bits)
-__device__ __forceinline__ void split3(float x, uint32_t &hi, uint32_t &mid, uint32_t &lo)
+// fp32 -> three 16-bit terms whose sum is the value.  bf16: each term takes the next 8 mantissa bits, exact.  fp16:
+// each term is the rounded remainder (11 bits each; the remainders are exact, the last term is off by at most 2^-33
+// of the value or by fp16's smallest step, 6e-8, whichever is larger); the value must be below fp16's largest, 65504.
+template <int KF> __device__ __forceinline__ void split3(float x, uint32_t &hi, uint32_t &mid, uint32_t &lo)
 {
+    if constexpr (KF == kKeyF16) {
+        const _Float16 h = (_Float16)x;
+        const float r1 = x - (float)h;
+        const _Float16 m = (_Float16)r1;
+        const float r2 = r1 - (float)m;
+        const _Float16 l = (_Float16)r2;
+        hi = __builtin_bit_cast(unsigned short, h);
+        mid = __builtin_bit_cast(unsigned short, m);
+        lo = __builtin_bit_cast(unsigned short, l);
+        return;
+    }
     const uint32_t b0 = __float_as_uint(x) & 0xffff0000u;
     const float r1 = x - __uint_as_float(b0);
     const uint32_t b1 = __float_as_uint(r1) & 0xffff0000u;
@@ -120,13 +138,13 @@ __device__ __forceinline__ void split3(float x, uint32_t &hi, uint32_t &mid, uin
     lo = __float_as_uint(r2) >> 16;
 }
 
-// A vector of which this lane holds dims 2 lane and 2 lane + 1, as the three bf16 terms of rows row0 .. row0 + 2
+// A vector of which this lane holds dims 2 lane and 2 lane + 1, as the three terms of rows row0 .. row0 + 2
 // of a staged left operand.
-__device__ __forceinline__ void stage_anchor(uint8_t *stage, int row0, int lane, float v0, float v1)
+template <int KF> __device__ __forceinline__ void stage_anchor(uint8_t *stage, int row0, int lane, float v0, float v1)
 {
     uint32_t h0, m0, l0, h1, m1, l1;
-    split3(v0, h0, m0, l0);
-    split3(v1, h1, m1, l1);
+    split3<KF>(v0, h0, m0, l0);
+    split3<KF>(v1, h1, m1, l1);
     *reinterpret_cast<uint32_t *>(stage + (row0 + 0) * kPitch + 4 * lane) = h0 | (h1 << 16);
     *reinterpret_cast<uint32_t *>(stage + (row0 + 1) * kPitch + 4 * lane) = m0 | (m1 << 16);
     *reinterpret_cast<uint32_t *>(stage + (row0 + 2) * kPitch + 4 * lane) = l0 | (l1 << 16);
@@ -140,59 +158,39 @@ __device__ __forceinline__ void read_operand(const uint8_t *stage, int lane, u32
     for (int kk = 0; kk < 4; ++kk) x[kk] = *reinterpret_cast<const u32x4 *>(mine + 64 * kk);
 }
 
-// ||k||^2 of the operand's token n, in all four lanes that hold a quarter of it.  The compiler does not see
-// what the assembly writes, so the wait states that a read by another kind of vector instruction needs after a
-// dot-product instruction are spent inside the block.
-__device__ __forceinline__ float operand_sumsq(const u32x4 (&x)[4])
-{
-    float acc = 0.f;
-    asm("v_dot2c_f32_bf16 %0, %1, %1\n\t"
-        "v_dot2c_f32_bf16 %0, %2, %2\n\t"
-        "v_dot2c_f32_bf16 %0, %3, %3\n\t"
-        "v_dot2c_f32_bf16 %0, %4, %4\n\t"
-        "v_dot2c_f32_bf16 %0, %5, %5\n\t"
-        "v_dot2c_f32_bf16 %0, %6, %6\n\t"
-        "v_dot2c_f32_bf16 %0, %7, %7\n\t"
-        "v_dot2c_f32_bf16 %0, %8, %8\n\t"
-        "v_dot2c_f32_bf16 %0, %9, %9\n\t"
-        "v_dot2c_f32_bf16 %0, %10, %10\n\t"
-        "v_dot2c_f32_bf16 %0, %11, %11\n\t"
-        "v_dot2c_f32_bf16 %0, %12, %12\n\t"
-        "v_dot2c_f32_bf16 %0, %13, %13\n\t"
-        "v_dot2c_f32_bf16 %0, %14, %14\n\t"
-        "v_dot2c_f32_bf16 %0, %15, %15\n\t"
-        "v_dot2c_f32_bf16 %0, %16, %16\n\t"
-        "s_nop 3"
-        : "+v"(acc)
-        : "v"(x[0].x), "v"(x[0].y), "v"(x[0].z), "v"(x[0].w), "v"(x[1].x), "v"(x[1].y), "v"(x[1].z), "v"(x[1].w),
-          "v"(x[2].x), "v"(x[2].y), "v"(x[2].z), "v"(x[2].w), "v"(x[3].x), "v"(x[3].y), "v"(x[3].z), "v"(x[3].w));
-    return sum_over_rows16(acc);
-}
-
 // Sum of the squares of a lane's eight values of a row, ready to be read by any vector instruction (see above).
-__device__ __forceinline__ float piece_sumsq(const u32x4 &r)
+template <int KF> __device__ __forceinline__ float piece_sumsq(const u32x4 &r)
 {
     float acc = 0.f;
-    asm("v_dot2c_f32_bf16 %0, %1, %1\n\t"
-        "v_dot2c_f32_bf16 %0, %2, %2\n\t"
-        "v_dot2c_f32_bf16 %0, %3, %3\n\t"
-        "v_dot2c_f32_bf16 %0, %4, %4\n\t"
-        "s_nop 3"
-        : "+v"(acc)
-        : "v"(r.x), "v"(r.y), "v"(r.z), "v"(r.w));
+    if constexpr (KF == kKeyF16)
+        asm("v_dot2c_f32_f16 %0, %1, %1\n\t"
+            "v_dot2c_f32_f16 %0, %2, %2\n\t"
+            "v_dot2c_f32_f16 %0, %3, %3\n\t"
+            "v_dot2c_f32_f16 %0, %4, %4\n\t"
+            "s_nop 3"
+            : "+v"(acc)
+            : "v"(r.x), "v"(r.y), "v"(r.z), "v"(r.w));
+    else
+        asm("v_dot2c_f32_bf16 %0, %1, %1\n\t"
+            "v_dot2c_f32_bf16 %0, %2, %2\n\t"
+            "v_dot2c_f32_bf16 %0, %3, %3\n\t"
+            "v_dot2c_f32_bf16 %0, %4, %4\n\t"
+            "s_nop 3"
+            : "+v"(acc)
+            : "v"(r.x), "v"(r.y), "v"(r.z), "v"(r.w));
     return acc;
 }
 
 // One group of 16 tokens in row-wise layout (lane (g, c): rows 4g .. 4g+3, dims 8c .. 8c+7; tok0 = the group's
 // first token, which may lie in front of the prompt): ||k||^2 and the weight 1/||k|| of every row (0 for tokens
 // outside [0, tok_end)) go to ss_out / w_out, and to ww for this lane's own rows.
-__device__ __forceinline__ void group_norms(const u32x4 (&raw)[4], int tok0, int tok_end, int g, int c, float *w_out,
+template <int KF> __device__ __forceinline__ void group_norms(const u32x4 (&raw)[4], int tok0, int tok_end, int g, int c, float *w_out,
                                             float *ss_out, float (&ww)[4])
 {
     float ss[4];
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-        ss[j] = row_sum<16>(piece_sumsq(raw[j]));
+        ss[j] = row_sum<16>(piece_sumsq<KF>(raw[j]));
         const int tok = tok0 + 4 * g + j;
         ww[j] = (tok >= 0 && tok < tok_end) ? inv_norm(ss[j]) : 0.f;
     }
@@ -203,18 +201,18 @@ __device__ __forceinline__ void group_norms(const u32x4 (&raw)[4], int tok0, int
 }
 
 // The same, and the weighted sum of the group's rows to sum_out (D floats).
-__device__ __forceinline__ void group_sum(const u32x4 (&raw)[4], int tok0, int tok_end, int g, int c, float *w_out,
+template <int KF> __device__ __forceinline__ void group_sum(const u32x4 (&raw)[4], int tok0, int tok_end, int g, int c, float *w_out,
                                           float *ss_out, float *sum_out)
 {
     float ww[4];
-    group_norms(raw, tok0, tok_end, g, c, w_out, ss_out, ww);
+    group_norms<KF>(raw, tok0, tok_end, g, c, w_out, ss_out, ww);
     float T[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) T[e] = 0.f;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
         float k[8];
-        unpack8<kKeyBF16>(raw[j], k);
+        unpack8<KF>(raw[j], k);
 #pragma unroll
         for (int e = 0; e < 8; ++e) T[e] = fmaf(ww[j], k[e], T[e]);
     }
@@ -290,7 +288,7 @@ __global__ __launch_bounds__(256) void plan_kernel(TileItem *__restrict__ items,
 // grid: one workgroup of 256 threads per item, in the items' order.  (Resident workgroups that loop over the items
 // instead were tried: without the hardware handing out blocks as slots fall free, all workgroups of the chip move
 // through their loading and computing phases in step, and the pass takes 0.90 ms instead of 0.77.)
-__global__ __launch_bounds__(64 * kTileWaves, 4)
+template <int KF> __global__ __launch_bounds__(64 * kTileWaves, 4)
 void scan_tile_kernel(const uint8_t *__restrict__ keys, const TileItem *__restrict__ items, float *__restrict__ a_raw,
                       unsigned long long *__restrict__ acc, float *__restrict__ ssum, uint32_t *__restrict__ sync, int64_t rows,
                       int poll_limit)
@@ -327,14 +325,14 @@ void scan_tile_kernel(const uint8_t *__restrict__ keys, const TileItem *__restri
         if (ex[m]) {
             const int off = (blk_lo + kGroup * q + 4 * g) * kRowBytes + 16 * c;
 #pragma unroll
-            for (int j = 0; j < 4; ++j) raw[m][j] = row_load<kKeyBF16>(rsrc, off + j * kRowBytes);
+            for (int j = 0; j < 4; ++j) raw[m][j] = row_load<KF>(rsrc, off + j * kRowBytes);
         }
     }
 
     // ---- the block's own groups: norms and partial sums, nothing else in front of the block total ----
 #pragma unroll
     for (int m = 1; m < 5; ++m)
-        if (ex[m]) group_sum(raw[m], blk_lo + kGroup * (w + 4 * (m - 1)), blk_hi, g, c, lds_w[w][m], lds_ss[w][m], lds_T[4 + w + 4 * (m - 1)]);
+        if (ex[m]) group_sum<KF>(raw[m], blk_lo + kGroup * (w + 4 * (m - 1)), blk_hi, g, c, lds_w[w][m], lds_ss[w][m], lds_T[4 + w + 4 * (m - 1)]);
     __syncthreads();
 
     // ---- block total = episodic anchor (up to length); lane: dims 2 lane, 2 lane + 1 ----
@@ -355,7 +353,7 @@ void scan_tile_kernel(const uint8_t *__restrict__ keys, const TileItem *__restri
     bsq = sum_over_rows16(row_sum<16>(fmaf(b0, b0, b1 * b1)));
 
     // ---- the halo group's sum (the window sums in front of the block's first groups need it) ----
-    group_sum(raw[0], blk_lo + kGroup * (w - 4), blk_hi, g, c, lds_w[w][0], lds_ss[w][0], lds_T[w]);
+    group_sum<KF>(raw[0], blk_lo + kGroup * (w - 4), blk_hi, g, c, lds_w[w][0], lds_ss[w][0], lds_T[w]);
 
     float *S_unit = ssum + (int64_t)it.unit * D;
     if (poster) {                                                     // (the adds have had the halo group to come back)
@@ -380,7 +378,7 @@ void scan_tile_kernel(const uint8_t *__restrict__ keys, const TileItem *__restri
             __builtin_amdgcn_wave_barrier();                          // the next group reuses the staging rows
         }
     }
-    stage_anchor(stage, 4, lane, b0, b1);                             // rows 4 .. 6: the block total's three terms
+    stage_anchor<KF>(stage, 4, lane, b0, b1);                             // rows 4 .. 6: the block total's three terms
     __syncthreads();                                                  // the halo groups' sums
     // ---- the chain of this wave's groups ----
     // lane (qq, n) of a result holds rows 4 qq + rho, column n.  Masked weights of the rows: rows j <= n count.
@@ -395,7 +393,7 @@ void scan_tile_kernel(const uint8_t *__restrict__ keys, const TileItem *__restri
         const float ww[4] = {w4.x, w4.y, w4.z, w4.w};
 #pragma unroll
         for (int rho = 0; rho < 4; ++rho) wm_prev[rho] = 4 * qq + rho <= n ? ww[rho] : 0.f;
-        alpha_prev = weighted(tile<4>(X[0], X[0]), wm_prev);          // halo group: its own triangle only
+        alpha_prev = weighted(tile<KF, 4>(X[0], X[0]), wm_prev);          // halo group: its own triangle only
     }
 #pragma unroll
     for (int m = 1; m < 5; ++m) {
@@ -412,16 +410,16 @@ void scan_tile_kernel(const uint8_t *__restrict__ keys, const TileItem *__restri
                 s1 = ((t0.y + t1.y) + t2.y) + t3.y;
             }
             const float P0 = sum_over_rows16(row_sum<16>(fmaf(s0, s0, s1 * s1)));
-            stage_anchor(stage, 0, lane, s0, s1);                     // rows 0 .. 2: the seed's three terms
+            stage_anchor<KF>(stage, 0, lane, s0, s1);                     // rows 0 .. 2: the seed's three terms
             __builtin_amdgcn_wave_barrier();
             u32x4 An[4];
             read_operand(stage, lane, An);
             __builtin_amdgcn_wave_barrier();                          // the next group rewrites rows 0 .. 2
-            const f32x4 AT = tile<4>(X[m], X[m]);                     // [j in G][i in G]
-            const f32x4 XT = tile<4>(X[m - 1], X[m]);                 // [j' in P][i in G]
-            const f32x4 XX = tile<4>(X[m], X[m - 1]);                 // [j in G][i' in P]
-            const f32x4 AG = tile<4>(An, X[m]);                       // [anchor row][i in G]
-            const f32x4 AP = tile<4>(An, X[m - 1]);                   // [anchor row][i' in P]
+            const f32x4 AT = tile<KF, 4>(X[m], X[m]);                     // [j in G][i in G]
+            const f32x4 XT = tile<KF, 4>(X[m - 1], X[m]);                 // [j' in P][i in G]
+            const f32x4 XX = tile<KF, 4>(X[m], X[m - 1]);                 // [j in G][i' in P]
+            const f32x4 AG = tile<KF, 4>(An, X[m]);                       // [anchor row][i in G]
+            const f32x4 AP = tile<KF, 4>(An, X[m - 1]);                   // [anchor row][i' in P]
             float wm[4];
             {
                 const float4 w4 = *reinterpret_cast<const float4 *>(&lds_w[w][m][4 * qq]);
@@ -477,9 +475,10 @@ void scan_tile_kernel(const uint8_t *__restrict__ keys, const TileItem *__restri
     }
     __syncthreads();
     if (s_have != 0) {
-        const float2 s2 = *reinterpret_cast<const float2 *>(&lds_S[2 * lane]);
+        float2 s2 = *reinterpret_cast<const float2 *>(&lds_S[2 * lane]);
+        if constexpr (KF == kKeyF16) { s2.x *= 0.25f; s2.y *= 0.25f; }   // a sum over 65 536 unit vectors stays inside fp16's range; the cosine does not see the factor
         const float ssq = sum_over_rows16(row_sum<16>(fmaf(s2.x, s2.x, s2.y * s2.y)));
-        stage_anchor(stage, 0, lane, s2.x, s2.y);
+        stage_anchor<KF>(stage, 0, lane, s2.x, s2.y);
         __builtin_amdgcn_wave_barrier();
         u32x4 An[4];
         read_operand(stage, lane, An);
@@ -487,7 +486,7 @@ void scan_tile_kernel(const uint8_t *__restrict__ keys, const TileItem *__restri
         for (int m = 1; m < 5; ++m) {
             if (ex[m]) {
                 const int q = w + 4 * (m - 1);
-                const f32x4 AS = tile<4>(An, X[m]);
+                const f32x4 AS = tile<KF, 4>(An, X[m]);
                 const float wn = lds_w[w][m][n], ssn = lds_ss[w][m][n];
                 const float knn = ssn < 1e-24f ? sqrtf(ssn) * 1e12f : 1.f;
                 const float as = neg_cos(wn * sum3(AS), knn, ssq);
@@ -500,6 +499,7 @@ void scan_tile_kernel(const uint8_t *__restrict__ keys, const TileItem *__restri
 // a_s of the blocks whose workgroups did not wait for their unit's sum: the same operands (loaded in operand
 // layout directly), norms, split and product as in scan_tile_kernel, so the values are the ones it would have
 // stored.
+template <int KF>
 __global__ __launch_bounds__(64 * kTileWaves) void deferred_stable_tile_kernel(const uint8_t *__restrict__ keys, RowMap km,
                                                                                PromptTab tab,
                                                                                const float *__restrict__ ssum,
@@ -527,10 +527,11 @@ __global__ __launch_bounds__(64 * kTileWaves) void deferred_stable_tile_kernel(c
             const_cast<uint8_t *>(keys) + km.unit(lh, p, tab) * 2, 0, N * kRowBytes, 0x00020000);
         const __amdgpu_buffer_rsrc_t out_s = __builtin_amdgcn_make_buffer_rsrc(a_raw + row0, 0, blk_hi * 4, 0x00020000);
         // every word of the unit's sum has been stored by now (the pass has ended)
-        const float2 s2 = *reinterpret_cast<const float2 *>(ssum + ((int64_t)lh * tab.n + p) * D + 2 * lane);
+        float2 s2 = *reinterpret_cast<const float2 *>(ssum + ((int64_t)lh * tab.n + p) * D + 2 * lane);
+        if constexpr (KF == kKeyF16) { s2.x *= 0.25f; s2.y *= 0.25f; }   // as in scan_tile_kernel
         const float ssq = sum_over_rows16(row_sum<16>(fmaf(s2.x, s2.x, s2.y * s2.y)));
         __builtin_amdgcn_wave_barrier();                              // the previous block's reads of the staged rows
-        stage_anchor(stage, 0, lane, s2.x, s2.y);
+        stage_anchor<KF>(stage, 0, lane, s2.x, s2.y);
         __builtin_amdgcn_wave_barrier();
         u32x4 An[4];
         read_operand(stage, lane, An);
@@ -539,16 +540,16 @@ __global__ __launch_bounds__(64 * kTileWaves) void deferred_stable_tile_kernel(c
             u32x4 raw[4], X[4];                                       // the group row-wise (norms) and as an operand
             const int roff = (tok0 + 4 * g) * kRowBytes + 16 * c, off = (tok0 + n) * kRowBytes + 16 * qq;
 #pragma unroll
-            for (int j = 0; j < 4; ++j) raw[j] = row_load<kKeyBF16>(rsrc, roff + j * kRowBytes);
+            for (int j = 0; j < 4; ++j) raw[j] = row_load<KF>(rsrc, roff + j * kRowBytes);
 #pragma unroll
-            for (int kk = 0; kk < 4; ++kk) X[kk] = row_load<kKeyBF16>(rsrc, off + 64 * kk);
+            for (int kk = 0; kk < 4; ++kk) X[kk] = row_load<KF>(rsrc, off + 64 * kk);
             float ww[4];
-            group_norms(raw, tok0, blk_hi, g, c, lds_w[w], lds_ss[w], ww);
+            group_norms<KF>(raw, tok0, blk_hi, g, c, lds_w[w], lds_ss[w], ww);
             __builtin_amdgcn_wave_barrier();
             const float wn = lds_w[w][n], ss = lds_ss[w][n];
             __builtin_amdgcn_wave_barrier();                          // the next group rewrites them
             const float knn = ss < 1e-24f ? sqrtf(ss) * 1e12f : 1.f;
-            const f32x4 AS = tile<4>(An, X);
+            const f32x4 AS = tile<KF, 4>(An, X);
             const float as = neg_cos(wn * sum3(AS), knn, ssq);
             __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(as), out_s, off_q0 + tok0 * 4, 0, 0);
         }
@@ -561,7 +562,7 @@ int resident_tile_workgroups()
     if (cached < 0) {
         int per_cu = 0, dev = 0;
         hipDeviceProp_t prop;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, scan_tile_kernel, 64 * kTileWaves, 0) != hipSuccess ||
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, scan_tile_kernel<kKeyBF16>, 64 * kTileWaves, 0) != hipSuccess ||
             hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess)
             return 0;
         cached = per_cu * prop.multiProcessorCount;
@@ -573,7 +574,7 @@ int resident_tile_workgroups()
 
 bool tile_score_supported(int dtype, int d, int window, const PromptTab &tab, int LH)
 {
-    if (dtype != NKV_DTYPE_BF16 || d != 128 || window != 64) return false;
+    if ((dtype != NKV_DTYPE_BF16 && dtype != NKV_DTYPE_F16) || d != 128 || window != 64) return false;
     int max_unit_blocks = 0;
     for (int p = 0; p < tab.n; ++p) {
         if (tab.b[p] > 256) return false;
@@ -593,8 +594,9 @@ size_t tile_score_plan_bytes(int LH, const PromptTab &tab)
     return (size_t)fill_scan_plan(LH, tab, 1, &plan, false) * sizeof(TileItem);
 }
 
-hipError_t launch_score_tile(const void *keys, const RowMap &km, int LH, const PromptTab &tab, float *a_raw, void *accum,
-                             float *ssum, void *sync_area, void *plan_area, int mode, const Prof &prof, hipStream_t st)
+hipError_t launch_score_tile(const void *keys, const RowMap &km, int dtype, int LH, const PromptTab &tab, float *a_raw,
+                             void *accum, float *ssum, void *sync_area, void *plan_area, int mode, const Prof &prof,
+                             hipStream_t st)
 {
     constexpr int D = 128;
     const bool defer_all = mode == kScanDeferAll || mode == kScanRepairAll;   // no unit is added up by a workgroup of its own here
@@ -604,13 +606,23 @@ hipError_t launch_score_tile(const void *keys, const RowMap &km, int LH, const P
     plan_kernel<<<(unsigned)min(((size_t)n_items + 255) / 256, (size_t)2048), 256, 0, st>>>(
         (TileItem *)plan_area, n_items, km, tab, plan, LH, (uint4 *)sync_area, kSyncWords / 4, (uint4 *)accum, na, (uint4 *)ssum,
         na / 2);
+    const unsigned n_deferred = defer_all ? 4096 : 256;
     prof.begin(NKV_KERNEL_SCAN, st);
-    scan_tile_kernel<<<n_items, 64 * kTileWaves, 0, st>>>((const uint8_t *)keys, (const TileItem *)plan_area, a_raw,
-                                                         (unsigned long long *)accum, ssum, (uint32_t *)sync_area,
-                                                         (int64_t)LH * tab.T, defer_all ? -1 : kPollLimit);
+    if (dtype == NKV_DTYPE_F16)
+        scan_tile_kernel<kKeyF16><<<n_items, 64 * kTileWaves, 0, st>>>((const uint8_t *)keys, (const TileItem *)plan_area, a_raw,
+                                                                      (unsigned long long *)accum, ssum, (uint32_t *)sync_area,
+                                                                      (int64_t)LH * tab.T, defer_all ? -1 : kPollLimit);
+    else
+        scan_tile_kernel<kKeyBF16><<<n_items, 64 * kTileWaves, 0, st>>>((const uint8_t *)keys, (const TileItem *)plan_area, a_raw,
+                                                                       (unsigned long long *)accum, ssum, (uint32_t *)sync_area,
+                                                                       (int64_t)LH * tab.T, defer_all ? -1 : kPollLimit);
     prof.end(NKV_KERNEL_SCAN, st);
-    deferred_stable_tile_kernel<<<defer_all ? 4096 : 256, 64 * kTileWaves, 0, st>>>(
-        (const uint8_t *)keys, km, tab, ssum, (const uint32_t *)sync_area, a_raw);
+    if (dtype == NKV_DTYPE_F16)
+        deferred_stable_tile_kernel<kKeyF16><<<n_deferred, 64 * kTileWaves, 0, st>>>((const uint8_t *)keys, km, tab, ssum,
+                                                                                    (const uint32_t *)sync_area, a_raw);
+    else
+        deferred_stable_tile_kernel<kKeyBF16><<<n_deferred, 64 * kTileWaves, 0, st>>>((const uint8_t *)keys, km, tab, ssum,
+                                                                                     (const uint32_t *)sync_area, a_raw);
     return hipGetLastError();
 }
 

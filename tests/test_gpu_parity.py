@@ -84,6 +84,7 @@ SWEEP = [
     ("wide_head", 1, 1, 256, [600], "bf16", 0),
     ("d_40", 1, 2, 40, [500], "fp32", 24),
     ("fp16_ragged", 2, 2, 128, [700, 300], "fp16", 0),
+    ("fp16_long", 1, 2, 128, [20000, 4133, 6400], "fp16", 0),   # fp16 keys through the matrix-core scan: several slices, b = 200
     ("fp8_d128", 1, 2, 128, [2000, 130], "fp8", 0),       # 8-bit E4M3 keys and values
     ("fp8_d64_dv", 2, 3, 64, [900], "fp8", 32),
     ("long_prompt", 1, 2, 64, [40000], "bf16", 0),        # beyond the register-resident per-head kernels
@@ -127,13 +128,13 @@ def test_8bit_keys_of_every_finite_code(flags):
 
 
 TILE_CASES = ["below_window", "one_short_block", "block_tail", "b_between", "b_255", "ragged_small", "dv_differs",
-              "slice_edges", "unit_256_blocks"]
+              "slice_edges", "unit_256_blocks", "fp16_ragged", "fp16_long"]
 
 
 @pytest.mark.parametrize("route", [0, nkv.FLAG_DEFER_STABLE, nkv.FLAG_NO_UNIT_SUMS])
 @pytest.mark.parametrize("name", TILE_CASES)
 def test_vector_scan_where_the_matrix_core_scan_is_the_default(name, route):
-    """bf16 keys of head dim 128 take the matrix-core formulation of the fused scan by default (the sweep and the
+    """bf16 and fp16 keys of head dim 128 take the matrix-core formulation of the fused scan by default (the sweep and the
     named workloads exercise it); the vector-unit formulation, forced by flag, on the same shapes and on its
     three routes (unit sum found in time, every block deferred, every unit sum from the repair kernel), against
     the oracle."""
@@ -192,6 +193,23 @@ def test_constant_keys_ties_resolve_by_index():
     assert out.k_per_head.reshape(-1).tolist() == [36, 4]
     assert out.kept_idx.tolist() == list(range(36)) + [0, 1, 2, 3]
     assert torch.all(out.scores[:, :, 4:] == 0)
+
+
+def test_fp16_unit_sum_beyond_the_formats_range():
+    """65 533 fp16 keys that all point along one axis: that component of the unit's sum is 65 533, more than fp16
+    holds, and the matrix-core scan stages its anchors as fp16 terms.  The stable anomaly of every token is -1."""
+    N = 65533
+    w = nkv_inputs.small_workload("fp16_axis", 1, 1, 128, [N], dtype="fp16")
+    K = torch.zeros(1, 1, N, 128, dtype=torch.float16, device=DEV)
+    K[..., 5] = torch.linspace(0.5, 3.0, N, device=DEV).to(torch.float16)
+    shape = shape_of(w)
+    p = nkv.params_default()
+    a = torch.empty(3, 1, 1, N, dtype=torch.float32, device=DEV)
+    ws = torch.empty(nkv.workspace_bytes(shape, p), dtype=torch.uint8, device=DEV)
+    nkv.score_raw(K, shape, p, a, ws)
+    torch.cuda.synchronize()
+    assert torch.isfinite(a).all()
+    assert (a + 1.0).abs().max().item() < 2e-6
 
 
 @pytest.mark.parametrize("H,flags", [(4, 0), (12, 0), (12, nkv.FLAG_BUDGET_PER_HEAD), (32, 0)])
@@ -413,8 +431,9 @@ def test_deterministic_and_untouched_neighbours():
 def test_deferred_stable_route_gives_the_same_bits():
     """A block whose workgroup does not wait for its unit's sum gets its stable anomaly from a later kernel;
     which of the two routes a block takes depends on timing, so both must produce identical scores."""
-    for name, L, H, d, lens in (("defer128", 2, 3, 128, [3000, 500, 129]), ("defer64", 1, 4, 64, [2500, 64])):
-        w = nkv_inputs.small_workload(name, L, H, d, lens)
+    for name, L, H, d, lens, dtype in (("defer128", 2, 3, 128, [3000, 500, 129], "bf16"), ("defer64", 1, 4, 64, [2500, 64], "bf16"),
+                                       ("defer128_fp16", 2, 2, 128, [2100, 300], "fp16")):
+        w = nkv_inputs.small_workload(name, L, H, d, lens, dtype=dtype)
         K, V = _kv(w)
         a, _ = run_gpu(w, K, V, 0.6)
         b, _ = run_gpu(w, K, V, 0.6, params=nkv.params_default(flags=nkv.FLAG_DEFER_STABLE))
