@@ -54,7 +54,8 @@ __device__ __forceinline__ void locate(const SliceTab &st, const PromptTab &tab,
 
 // The values of slice s of a head of N tokens, as the hardware's bounds-checked buffer: slot j of thread tid is
 // element j * 256 + tid of the slice (one instruction of a wavefront reads one contiguous 256-byte piece, the
-// address is one register and a constant), and elements past the head's last token read as 0.
+// address is a 32-bit register and a constant), and elements past the head's last token read as 0.  The whole
+// offset goes into the per-lane offset, which the range check is sure to cover.
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t slice_values(const float *head, int s, int N)
 {
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(head + (int64_t)s * kSlice), 0,
@@ -63,7 +64,7 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t slice_values(const float *head
 
 __device__ __forceinline__ float slice_value(__amdgpu_buffer_rsrc_t r, int tid, int j)
 {
-    return __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(r, tid * 4, j * (kWideThreads * 4), 0));
+    return __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(r, tid * 4 + j * (kWideThreads * 4), 0, 0));
 }
 
 // Scores: floor(2046 v) for 0 <= v <= 1, 0 below, 2047 above 1 (the pinned positions).  Monotone in v.
