@@ -305,15 +305,25 @@ __global__ __launch_bounds__(kInPlaceThreads) void compact_inplace_kernel(uint4 
                (which == 0 ? km.unit(l * H + h, p, tab) : vm.unit(l * H + h, p, tab)) / epv;
     const int64_t r0 = head_off[u];
     const int64_t B = min(head_off[u + 1], row_capacity) - r0;        // rows whose index the caller's kept_idx holds
+    // Loads are unconditional (rows past the piece's end repeat its last row), so that a thread's index loads, and
+    // then its row loads, are all in flight together instead of one after the other.
     for (int64_t j0 = 0; j0 < B; j0 += kInPlaceRows) {
         const int nr = (int)min((int64_t)kInPlaceRows, B - j0);
+        int src[VPT];
         v4 v[VPT];
 #pragma unroll
         for (int i = 0; i < VPT; ++i) {
-            const int j = i * kInPlaceThreads + threadIdx.x, r = j / row16, c = j - r * row16;
-            if (r < nr) v[i] = __builtin_nontemporal_load(base + (int64_t)kept_idx[r0 + j0 + r] * row16 + c);
+            const int j = i * kInPlaceThreads + threadIdx.x, r = min(j / row16, nr - 1);
+            src[i] = kept_idx[r0 + j0 + r];
         }
-        __syncthreads();                                              // every row of the piece is in registers
+#pragma unroll
+        for (int i = 0; i < VPT; ++i) {
+            const int j = i * kInPlaceThreads + threadIdx.x, c = j % row16;
+            v[i] = __builtin_nontemporal_load(base + (int64_t)src[i] * row16 + c);
+        }
+        // every thread's loads of the piece have returned before any thread stores into the piece's range
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
 #pragma unroll
         for (int i = 0; i < VPT; ++i) {
             const int j = i * kInPlaceThreads + threadIdx.x, r = j / row16, c = j - r * row16;
