@@ -80,7 +80,7 @@ enum {
     NKV_FLAG_STATS_PER_HEAD = 32u,    /* nkv_score: the same choice for the per-head statistics              */
     NKV_FLAG_SELECT_PER_HEAD = 64u,   /* nkv_select_compact: the same choice for the top-B_h selection       */
     NKV_FLAG_VECTOR_SCAN = 128u,      /* streaming kernels: the vector-unit formulation of the fused pass    */
-                                      /* also for bf16 keys of head dim 128, where the matrix-core one is   */
+                                      /* also for 16-bit keys of head dim 128, where the matrix-core one is  */
                                       /* the default                                                         */
     NKV_FLAG_COMPACT_IN_PLACE = 256u  /* nkv_select_compact: the kept rows of a unit move to the front of    */
                                       /* the unit's own rows in keys / values (no packed buffers)            */
@@ -140,7 +140,7 @@ typedef struct nkv_params {
     /* Optional health counters of the fused streaming scan: NULL, or a DEVICE pointer to two uint32 that        */
     /* nkv_score / nkv_score_raw fill on their stream: [0] workgroups that gave up adding a unit's block totals  */
     /* up inside the pass (the unit's sum was then formed afterwards; 0 in normal operation, and always 0 for    */
-    /* bf16 keys of head dim 128, whose pass adds every block straight into the unit's sum), [1] blocks whose    */
+    /* 16-bit keys of head dim 128, whose pass adds every block straight into the unit's sum), [1] blocks whose  */
     /* stable anomaly was computed after the pass because the unit's sum did not arrive within the bounded       */
     /* wait.  Neither affects the result.  Both are 0 on the routes that do not use the fused pass.              */
     void    *scan_counters;

@@ -1,5 +1,6 @@
-// Streaming scoring kernel for bf16 keys of head dim 128, window 64, episodic block size <= 256 (paper Sections
-// 2.1-2.3), with every dot product of the pass formed by the matrix cores.
+// Streaming scoring kernel for bf16 or fp16 keys of head dim 128, window 64, episodic block size <= 256 (paper
+// Sections 2.1-2.3), with every dot product of the pass formed by the matrix cores.  (Written out below for bf16;
+// fp16 differs in the product instruction, in unpacking, and in how an fp32 anchor is cut into three terms.)
 //
 // The pass is a stream over the keys and nothing else is read from memory, but written for the vector unit it
 // needs ~2300 instructions per 64 tokens and is bound by their issue.  Here the vector unit keeps only the work
