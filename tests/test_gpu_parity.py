@@ -583,6 +583,31 @@ def test_layer_by_layer_calls_equal_the_batched_call():
                 assert np.array_equal(bits(out.packed_v[a:b]), bits(ref.packed_v[o:o + b - a]))
 
 
+def test_recompression_of_a_uniformly_compressed_cache():
+    """Decode-time recompression, in the one form the calls express as they are: with a uniform budget
+    (safeguard = 1) every head of a layer keeps k0 rows, so the packed cache is a dense [L][H][k0][d] tensor; new rows
+    appended per head make a dense [L][H][k0 + m][d] one, and compressing that again is the same three calls on it
+    (the retained rows, in cache order, are the sequence that windows and blocks run over -- the paper leaves the
+    incremental update open, this is this build's reading).  Both passes against the oracle."""
+    w = nkv_inputs.small_workload("recompress", 2, 4, 128, [9000], n_out=8)
+    K, V = _kv(w)
+    p = nkv.params_default(safeguard=1.0)
+    first, _ = run_gpu(w, K, V, 0.5, params=p)
+    check_against_oracle(w, K, V, first, 0.5, p, label="recompress, first pass")
+    k0 = nkv.k0(9000, 0.5)
+    assert first.k_per_head.reshape(-1).tolist() == [k0] * (w.L * w.H)
+    m = 700
+    g = torch.Generator().manual_seed(5)
+    grow = lambda packed: torch.cat([packed.reshape(w.L, w.H, k0, 128),
+                                     torch.randn(w.L, w.H, m, 128, generator=g).to(torch.bfloat16).to(DEV)], dim=2).contiguous()
+    K2, V2 = grow(first.packed_k), grow(first.packed_v)
+    w2 = nkv_inputs.small_workload("recompress2", 2, 4, 128, [k0 + m], n_out=0)
+    second, _ = run_gpu(w2, K2, V2, 0.3, params=p)
+    st = check_against_oracle(w2, K2, V2, second, 0.3, p, label="recompress, second pass")
+    _report("recompress second pass", st)
+    assert second.k_per_head.reshape(-1).tolist() == [nkv.k0(k0 + m, 0.3)] * (w.L * w.H)
+
+
 def test_the_three_calls_can_be_captured_in_a_hip_graph_and_replayed():
     """The calls only enqueue kernels on the given stream (no allocation, no synchronisation, no memset
     nodes), so a serving loop can record them once and replay: every replay, with eager work and
