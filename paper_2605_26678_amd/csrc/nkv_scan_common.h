@@ -138,10 +138,11 @@ template <int KF> using Piece = typename PieceOf<KF>::type;
 
 // Load of a row piece through a buffer descriptor: the address is one 32-bit byte offset per lane plus an
 // immediate, and an offset outside [0, num_records) (tokens before the prompt or past its end) reads zeros.
-template <int KF> __device__ __forceinline__ Piece<KF> row_load(__amdgpu_buffer_rsrc_t rsrc, int byte_off)
+// AUX: cache policy bits of the instruction (0: default, 2: non-temporal, for rows nobody reads again).
+template <int KF, int AUX = 0> __device__ __forceinline__ Piece<KF> row_load(__amdgpu_buffer_rsrc_t rsrc, int byte_off)
 {
-    if constexpr (KF == kKeyF8) return __builtin_amdgcn_raw_buffer_load_b64(rsrc, byte_off, 0, 0);
-    else return __builtin_amdgcn_raw_buffer_load_b128(rsrc, byte_off, 0, 0);
+    if constexpr (KF == kKeyF8) return __builtin_amdgcn_raw_buffer_load_b64(rsrc, byte_off, 0, AUX);
+    else return __builtin_amdgcn_raw_buffer_load_b128(rsrc, byte_off, 0, AUX);
 }
 
 using f16x2 = _Float16 __attribute__((ext_vector_type(2)));

@@ -142,8 +142,15 @@ void scan_kernel(const uint8_t *__restrict__ keys, RowMap km, PromptTab tab, Sca
         const_cast<uint8_t *>(keys) + km.unit(layer, head, p, tab) * ES, 0, N * kRowBytes, 0x00020000);
     const int lane_off = t0 * kRowBytes + c * (8 * ES);
     Piece<KF> raw[TPT], hraw[HT];
+    // a full block's last 64 tokens (the last wave's) are read again as the next block's halo: they stay in the L2;
+    // the other waves' rows are marked non-temporal
+    if (w < NW - 1) {
 #pragma unroll
-    for (int j = 0; j < TPT; ++j) raw[j] = row_load<KF>(rsrc, lane_off + j * kRowBytes);
+        for (int j = 0; j < TPT; ++j) raw[j] = row_load<KF, 2>(rsrc, lane_off + j * kRowBytes);
+    } else {
+#pragma unroll
+        for (int j = 0; j < TPT; ++j) raw[j] = row_load<KF>(rsrc, lane_off + j * kRowBytes);
+    }
     const int halo_off = (blk_lo - 64 + g * TPT + HT * w) * kRowBytes + c * (8 * ES);
 #pragma unroll
     for (int jj = 0; jj < HT; ++jj) hraw[jj] = row_load<KF>(rsrc, halo_off + jj * kRowBytes);

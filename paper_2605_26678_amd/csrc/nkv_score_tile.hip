@@ -329,8 +329,7 @@ void scan_tile_kernel(const uint8_t *__restrict__ keys, const TileItem *__restri
             // a full block's last 64 tokens (m = 4) are read again, as the next block's halo, and the halo has just
             // been read by the block in front: those stay in the L2; the other rows are marked non-temporal (aux 2)
             for (int j = 0; j < 4; ++j)
-                raw[m][j] = (m >= 1 && m <= 3) ? (u32x4)__builtin_amdgcn_raw_buffer_load_b128(rsrc, off + j * kRowBytes, 0, 2)
-                                               : row_load<KF>(rsrc, off + j * kRowBytes);
+                raw[m][j] = (m >= 1 && m <= 3) ? row_load<KF, 2>(rsrc, off + j * kRowBytes) : row_load<KF>(rsrc, off + j * kRowBytes);
         }
     }
 
