@@ -268,18 +268,27 @@ __global__ __launch_bounds__(256) void gather_kernel(const uint4 *__restrict__ k
         srcv[threadIdx.x] = vm.unit(l * H + h, p, tab) / epv + i * vrow16;
     }
     __syncthreads();
-    for (int j = threadIdx.x; j < nr * krow16; j += blockDim.x) {
-        const int r = j / krow16, c = j - r * krow16;
-        using v4 = unsigned int __attribute__((ext_vector_type(4)));
-        __builtin_nontemporal_store(__builtin_nontemporal_load(reinterpret_cast<const v4 *>(keys) + srck[r] + c),
-                                    reinterpret_cast<v4 *>(packed_k) + (r0 + r) * krow16 + c);
-    }
-    for (int j = threadIdx.x; j < nr * vrow16; j += blockDim.x) {
-        const int r = j / vrow16, c = j - r * vrow16;
-        using v4 = unsigned int __attribute__((ext_vector_type(4)));
-        __builtin_nontemporal_store(__builtin_nontemporal_load(reinterpret_cast<const v4 *>(values) + srcv[r] + c),
-                                    reinterpret_cast<v4 *>(packed_v) + (r0 + r) * vrow16 + c);
-    }
+    using v4 = unsigned int __attribute__((ext_vector_type(4)));
+    // four vectors of a tensor per thread in flight at a time: the loads are unconditional (a slot past the end
+    // repeats the last vector), so that they go out together, and only the stores are guarded
+    auto move = [&](const uint4 *src, uint4 *dst, const int64_t *first, int row16) {
+        const int total = nr * row16;
+        for (int j0 = threadIdx.x; j0 < total; j0 += 4 * 256) {
+            v4 v[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int j = min(j0 + i * 256, total - 1), r = j / row16, c = j - r * row16;
+                v[i] = __builtin_nontemporal_load(reinterpret_cast<const v4 *>(src) + first[r] + c);
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int j = j0 + i * 256, r = j / row16, c = j - r * row16;
+                if (j < total) __builtin_nontemporal_store(v[i], reinterpret_cast<v4 *>(dst) + (r0 + r) * row16 + c);
+            }
+        }
+    };
+    move(keys, packed_k, srck, krow16);
+    move(values, packed_v, srcv, vrow16);
 }
 
 // In-place compaction: grid (units, 2); workgroup (u, 0) moves the kept K rows of unit u to the front of the unit's
