@@ -264,6 +264,8 @@ int nkv_budget_noalloc(const float *scores, const nkv_shape *shape, const nkv_pa
  * therefore WRITES (the rows behind them keep stale contents).  head_off and kept_idx are written as above;
  * row_capacity then only bounds kept_idx.  A kept row never moves backwards (the j-th kept token has index >= j),
  * and a unit is moved by one workgroup front to back, so no row is overwritten before it has been read.
+ * K and V rows must be 32, 64, ..., 1024 bytes long (a power of two); other widths are refused with
+ * NKV_EUNSUPPORTED, packed buffers given together with the flag with NKV_EINVAL.
  */
 int nkv_select_compact(const void *keys, const void *values, const float *scores,
                        const int32_t *k_per_head, const nkv_shape *shape, const nkv_params *params,
