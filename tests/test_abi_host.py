@@ -98,6 +98,13 @@ def test_argument_errors_are_reported_before_any_device_work():
                                 0, 0, 0, 0) == nkv.NKV_EINVAL
     assert L.nkv_select_compact(fake, fake, fake, fake, C.byref(good.c), C.byref(p), 0, fake, fake, fake, 10,
                                 0, 0, 0, 0) == nkv.NKV_EINVAL
+    # compaction in place: no packed buffers with the flag, and only rows of 32 .. 1024 bytes, a power of two
+    pin = nkv.params_default(flags=nkv.FLAG_COMPACT_IN_PLACE)
+    assert L.nkv_select_compact(fake, fake, fake, fake, C.byref(good.c), C.byref(pin), fake, fake, fake, fake, 10,
+                                0, 0, 0, 0) == nkv.NKV_EINVAL
+    odd = nkv.Shape(1, 2, 96, 64, nkv.DTYPE_BF16, [0, 100])              # 192-byte key rows
+    assert L.nkv_select_compact(fake, fake, fake, fake, C.byref(odd.c), C.byref(pin), 0, 0, fake, fake, 10,
+                                0, 0, 0, 0) == nkv.NKV_EUNSUPPORTED
     # 8-bit caches: rows are moved as 16-byte vectors, attention over them is refused
     f8 = nkv.DTYPE_F8_E4M3
     assert L.nkv_score(fake, C.byref(nkv.Shape(1, 2, 72, 64, f8, [0, 100]).c), C.byref(p), fake, fake, 1 << 30,
