@@ -127,6 +127,38 @@ def test_8bit_keys_of_every_finite_code(flags):
     _report(f"fp8 codes flags={flags}", st)
 
 
+@pytest.mark.parametrize("case", range(16))
+def test_random_shapes_dtypes_and_routes(case):
+    """Seeded random draws of layers, heads, head dim, value dim, element type, prompt lengths (from a single token to
+    40 000, one to five prompts), eviction ratio (0 and 1 included) and code route: end to end and stage-wise
+    against the oracle."""
+    import random
+    rnd = random.Random(7000 + case)
+    dtype = rnd.choice(["bf16", "bf16", "fp16", "fp8", "fp32"])
+    d = rnd.choice([64, 128, 128])
+    L, H = rnd.randint(1, 3), rnd.choice([1, 2, 3, 4, 8])
+    lens = []
+    for _ in range(rnd.choice([1, 1, 2, 3, 5])):
+        kind = rnd.random()
+        lens.append(rnd.randint(1, 300) if kind < 0.2 else rnd.randint(300, 9000) if kind < 0.7 else rnd.randint(9000, 40000))
+    if sum(lens) * L * H > 600000:
+        L, H = 1, min(H, 2)
+    dv = rnd.choice([0, 0, 64, 32]) if dtype != "fp8" else rnd.choice([0, 32])
+    r = rnd.choice([0.0, 0.3, 0.5, 0.75, 0.9, 0.97, 1.0])
+    flags = rnd.choice([0, 0, 0, nkv.FLAG_VECTOR_SCAN, nkv.FLAG_DEFER_STABLE, nkv.FLAG_TWO_PASS_STABLE,
+                        nkv.FLAG_SELECT_PER_HEAD, nkv.FLAG_STATS_PER_HEAD, nkv.FLAG_BUDGET_PER_HEAD])
+    if flags in (nkv.FLAG_SELECT_PER_HEAD, nkv.FLAG_STATS_PER_HEAD, nkv.FLAG_BUDGET_PER_HEAD) and max(lens) > 32768:
+        flags = 0
+    label = f"random {case}: L={L} H={H} d={d} dv={dv} {dtype} lens={lens} r={r} flags={flags}"
+    print(label, flush=True)
+    w = nkv_inputs.small_workload(f"random{case}", L, H, d, lens, dtype=dtype, dv=dv, n_out=min(8, max(min(lens) - 4, 0)),
+                                  seed=7000 + case)
+    K, V = _kv(w)
+    p = nkv.params_default(flags=flags)
+    compare_end_to_end(w, K, V, r, params=p, label=label)
+    compare_stages(w, K, V, r, params=p, label=label)
+
+
 TILE_CASES = ["below_window", "one_short_block", "block_tail", "b_between", "b_255", "ragged_small", "dv_differs",
               "slice_edges", "unit_256_blocks", "fp16_ragged", "fp16_long"]
 
