@@ -59,18 +59,21 @@ __global__ __launch_bounds__(kWideThreads) void stats_hist_kernel(const float *_
     const float *a = a_raw + (int64_t)k * rows + (int64_t)lh * tab.T + tab.tok_off[p];
     const int tid = threadIdx.x;
     for (int j = tid; j < kBins; j += kWideThreads) hist[j] = 0u;
-    float v[kPerThread];
+    float v[kPerThread / 4][4];
     const __amdgpu_buffer_rsrc_t vals = slice_values(a, s, N);
 #pragma unroll
-    for (int j = 0; j < kPerThread; ++j) v[j] = slice_value(vals, tid, j);
+    for (int j = 0; j < kPerThread / 4; ++j) slice_values4(vals, tid, j, v[j]);
     __syncthreads();
     float lo = INFINITY, hi = -INFINITY;
 #pragma unroll
-    for (int j = 0; j < kPerThread; ++j) {
-        if (s * kSlice + j * kWideThreads + tid < N) {
-            lo = fminf(lo, v[j]);
-            hi = fmaxf(hi, v[j]);
-            atomicAdd(&hist[anomaly_bin(v[j])], 1u);
+    for (int j = 0; j < kPerThread / 4; ++j) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            if (s * kSlice + 4 * (j * kWideThreads + tid) + e < N) {
+                lo = fminf(lo, v[j][e]);
+                hi = fmaxf(hi, v[j][e]);
+                atomicAdd(&hist[anomaly_bin(v[j][e])], 1u);
+            }
         }
     }
     lo = wave_min(lo);

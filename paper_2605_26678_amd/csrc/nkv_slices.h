@@ -67,6 +67,15 @@ __device__ __forceinline__ float slice_value(__amdgpu_buffer_rsrc_t r, int tid, 
     return __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(r, tid * 4 + j * (kWideThreads * 4), 0, 0));
 }
 
+// Four consecutive values per thread and load, for kernels that do not care which thread holds which value
+// (histograms, minima): slot j of thread tid holds elements 4 (j * 256 + tid) .. + 3 of the slice.  The range check
+// is per 32-bit word, so a head's last values are delivered and the words behind them read as 0.
+__device__ __forceinline__ void slice_values4(__amdgpu_buffer_rsrc_t r, int tid, int j, float (&v)[4])
+{
+    const auto q = __builtin_amdgcn_raw_buffer_load_b128(r, (j * kWideThreads + tid) * 16, 0, 0);
+    v[0] = __uint_as_float(q[0]); v[1] = __uint_as_float(q[1]); v[2] = __uint_as_float(q[2]); v[3] = __uint_as_float(q[3]);
+}
+
 // Scores: floor(2046 v) for 0 <= v <= 1, 0 below, 2047 above 1 (the pinned positions).  Monotone in v.
 __device__ __forceinline__ int score_bin(float v)
 {
@@ -100,14 +109,16 @@ __global__ __launch_bounds__(kWideThreads) void slice_hist_kernel(const float *_
     const float *sc = scores + (int64_t)lh * tab.T + tab.tok_off[p];
     const int tid = threadIdx.x;
     for (int j = tid; j < kBins; j += kWideThreads) hist[j] = 0u;
-    float v[kPerThread];
+    float v[kPerThread / 4][4];
     const __amdgpu_buffer_rsrc_t vals = slice_values(sc, s, N);
 #pragma unroll
-    for (int j = 0; j < kPerThread; ++j) v[j] = slice_value(vals, tid, j);
+    for (int j = 0; j < kPerThread / 4; ++j) slice_values4(vals, tid, j, v[j]);
     __syncthreads();
 #pragma unroll
-    for (int j = 0; j < kPerThread; ++j)
-        if (s * kSlice + j * kWideThreads + tid < N) atomicAdd(&hist[score_bin(v[j])], 1u);
+    for (int j = 0; j < kPerThread / 4; ++j)
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            if (s * kSlice + 4 * (j * kWideThreads + tid) + e < N) atomicAdd(&hist[score_bin(v[j][e])], 1u);
     __syncthreads();
     store_hist16(hist, part + (int64_t)blockIdx.x * kBins);
 }
