@@ -229,6 +229,8 @@ def main():
     ap.add_argument("--vector-scan", action="store_true", help="vector-unit formulation of the fused scan also where the matrix-core one applies")
     ap.add_argument("--per-layer", action="store_true",
                     help="a step is L passes with L = 1, one per layer's K/V slice, as a prefill loop would call it")
+    ap.add_argument("--layers-per-call", type=int, default=1,
+                    help="with --per-layer: layers handed to one call (must divide the workload's layers)")
     ap.add_argument("--layer-tensors", action="store_true",
                     help="every layer's K and V in an allocation of its own (a framework's list of per-layer caches), "
                          "still one call over all layers")
@@ -265,8 +267,12 @@ def main():
                                 | (nkv.FLAG_VECTOR_SCAN if args.vector_scan else 0))
     r_list = [r] * shape.n_prompts
     if args.per_layer:
-        shape1 = nkv.Shape(1, w.H, w.d, w.d_v, shape.dtype, w.cu_seqlens)
-        calls = [(nkv.Compressor(shape1, r_list, params), K[l], V[l]) for l in range(w.L)]
+        lpc = args.layers_per_call
+        if lpc < 1 or w.L % lpc:
+            print(f"bench.py: --layers-per-call must divide {w.L}", file=sys.stderr)
+            return 2
+        shape1 = nkv.Shape(lpc, w.H, w.d, w.d_v, shape.dtype, w.cu_seqlens)
+        calls = [(nkv.Compressor(shape1, r_list, params), K[l:l + lpc], V[l:l + lpc]) for l in range(0, w.L, lpc)]
     elif args.layer_tensors:
         args.no_cpu_baseline = True                      # the oracle leg reads the one-tensor layout
         Kl, Vl = [K[l].clone() for l in range(w.L)], [V[l].clone() for l in range(w.L)]
