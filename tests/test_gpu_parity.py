@@ -557,6 +557,79 @@ def test_strided_layouts_give_the_same_bits(flags):
     assert np.array_equal(bits(out.packed_k), bits(ref.packed_k)) and np.array_equal(bits(out.packed_v), bits(ref.packed_v))
 
 
+@pytest.mark.parametrize("case", range(12))
+def test_random_layouts_types_and_masks(case):
+    """Seeded random draws of shape, element type (bf16, fp16, 8-bit, fp32), scale mask and code route in one of four
+    layouts -- per-prompt slabs with NaN padding, heads padded apart, one tensor per layer, or dense with the
+    compaction done in place -- against the oracle on the dense tensors."""
+    import random
+    rnd = random.Random(9000 + case)
+    dtype = rnd.choice(["bf16", "fp16", "fp8", "fp32"])
+    tdt, ndt = {"bf16": (torch.bfloat16, nkv.DTYPE_BF16), "fp16": (torch.float16, nkv.DTYPE_F16),
+                "fp32": (torch.float32, nkv.DTYPE_F32), "fp8": (torch.float8_e4m3fn, nkv.DTYPE_F8_E4M3)}[dtype]
+    d = rnd.choice([64, 128, 128])
+    L, H, P = rnd.randint(1, 3), rnd.choice([1, 2, 4, 8]), rnd.choice([1, 2, 3])
+    lens = [rnd.choice([rnd.randint(1, 400), rnd.randint(400, 9000), rnd.randint(9000, 30000)]) for _ in range(P)]
+    if sum(lens) * L * H > 400000:
+        L, H = 1, min(H, 2)
+    r = rnd.choice([0.3, 0.5, 0.75, 0.95])
+    mask = rnd.choice([7, 7, 7, 3, 5, 6, 1])
+    flags = rnd.choice([0, 0, nkv.FLAG_VECTOR_SCAN, nkv.FLAG_DEFER_STABLE])
+    layout = ["slabs", "padded_heads", "layer_tensors", "in_place"][case % 4]
+    label = f"random layout {case}: {layout} L={L} H={H} d={d} {dtype} lens={lens} r={r} mask={mask} flags={flags}"
+    print(label, flush=True)
+    w = nkv_inputs.small_workload(f"layout{case}", L, H, d, lens, dtype=dtype, n_out=min(8, max(min(lens) - 4, 0)), seed=9000 + case)
+    K, V = _kv(w)
+    cu, T = w.cu_seqlens, w.T
+    p = nkv.params_default(flags=flags, scale_mask=mask)
+
+    def padding(*shape):
+        if tdt == torch.float8_e4m3fn:
+            return torch.full(shape, 0x7f, dtype=torch.uint8, device=DEV).view(tdt)      # the format's NaN code
+        return torch.full(shape, float("nan"), dtype=tdt, device=DEV)
+
+    if layout == "slabs":
+        nmax = max(lens) + rnd.choice([0, 8, 40])
+        Kp, Vp = padding(L, P, H, nmax, d), padding(L, P, H, nmax, d)
+        for q in range(P):
+            Kp[:, q, :, :lens[q]] = K[:, :, cu[q]:cu[q + 1]]
+            Vp[:, q, :, :lens[q]] = V[:, :, cu[q]:cu[q + 1]]
+        st = (P * H * nmax * d, nmax * d, H * nmax * d)
+        out = _run_with_layout(w, Kp, Vp, r, nkv.Shape(L, H, d, d, ndt, cu, key_strides=st, value_strides=st), p)
+    elif layout == "padded_heads":
+        pad = rnd.choice([8, 24, 64])
+        Kh = padding(L, H, T + pad, d)
+        Kh[:, :, :T] = K
+        out = _run_with_layout(w, Kh, V, r, nkv.Shape(L, H, d, d, ndt, cu, key_strides=(H * (T + pad) * d, (T + pad) * d, 0)), p)
+    elif layout == "layer_tensors":
+        order = list(range(L))
+        rnd.shuffle(order)                                       # allocation order: some offsets come out negative
+        Kl, Vl = [None] * L, [None] * L
+        for l in order:
+            Kl[l], Vl[l] = K[l].clone(), V[l].clone()
+        out = _run_with_layout(w, Kl[0], Vl[0], r, nkv.Shape(L, H, d, d, ndt, cu, key_layers=Kl, value_layers=Vl), p)
+    else:
+        shape = shape_of(w)
+        comp = nkv.Compressor(shape, [r] * P, p)
+        out = comp.run(K, V)
+        torch.cuda.synchronize()
+        K2, V2 = K.clone(), V.clone()
+        nkv.select_compact(K2, V2, comp.scores, comp.k_per_head, shape,
+                           nkv.params_default(flags=flags | nkv.FLAG_COMPACT_IN_PLACE, scale_mask=mask), None, None,
+                           comp.kept_idx, comp.head_off, comp.rows, comp.near, comp.ws)
+        torch.cuda.synchronize()
+        ho, pk, pv, K2b, V2b = comp.head_off.cpu().numpy(), bits(out.packed_k), bits(out.packed_v), bits(K2), bits(V2)
+        u = 0
+        for q in range(P):
+            for l in range(L):
+                for h in range(H):
+                    B = int(ho[u + 1] - ho[u])
+                    assert np.array_equal(K2b[l, h, cu[q]:cu[q] + B], pk[ho[u]:ho[u + 1]]), (label, "K rows", q, l, h)
+                    assert np.array_equal(V2b[l, h, cu[q]:cu[q] + B], pv[ho[u]:ho[u + 1]]), (label, "V rows", q, l, h)
+                    u += 1
+    check_against_oracle(w, K, V, out, r, p, label=label)
+
+
 @pytest.mark.parametrize("flags", [0, nkv.FLAG_TWO_PASS_STABLE, nkv.FLAG_GENERIC_KERNELS, nkv.FLAG_DEFER_STABLE])
 def test_one_tensor_per_layer_gives_the_same_bits(flags):
     """A framework's list of per-layer cache tensors, each an allocation of its own ([B][H][N_max][d] with one
