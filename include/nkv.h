@@ -123,7 +123,8 @@ typedef struct nkv_params {
                               /* read as 7 (all three).  A scale that is off is left out of the blend, the   */
                               /* winner and the standard deviation alike: 3 is the Appendix's component     */
                               /* ablation "Stable + episodic (no current)", 1 its "Single-scale stable       */
-                              /* score".  (A prior weight of 0 only removes a scale from the blend.)         */
+                              /* score".  (A prior weight of 0 only removes a scale from the blend.)  At     */
+                              /* least one scale that takes part needs a positive prior weight (NKV_EINVAL). */
     double   top_frac;        /* p = 0.10: top/bottom sets hold max(1, floor(p*N)) tokens          */
     double   prior[3];        /* (0.4, 0.4, 0.2): stable, episodic, current (Section 2.4)          */
     double   beta;            /* 3.0  blend temperature                                            */
