@@ -2,9 +2,9 @@
 // select_fast_kernel / select_kernel of nkv_select.hip, but a head's scores are cut into slices of 8192 tokens
 // and every step that touches them runs on one small workgroup per slice (see nkv_slices.h).
 //   slice_hist_kernel   (per slice)  2048-bin value histogram of the slice
-//   sel_pick_kernel     (per unit)   the bin that holds the B_h-th best score; per slice how many scores lie
-//                                    in bins above it
-//   sel_collect_kernel  (per slice)  the keys of that bin -> the slice's segment
+//   sel_collect_kernel  (per slice)  the bin that holds the unit's B_h-th best score (found by every slice's workgroup
+//                                    from the unit's histograms); how many of the slice's scores lie in bins above
+//                                    it; the keys of that bin -> the slice's segment
 //   sel_finish_kernel   (per unit)   one wavefront: exact threshold T inside the bin, how many of the scores
 //                                    tied at T are kept, and per slice how many kept / tied scores precede it
 //   sel_compact_kernel  (per slice)  ballots over 64 consecutive tokens + a scan over the slice's groups give
@@ -35,34 +35,18 @@ struct SelSlice {
     uint32_t gt_before, eq_before;       // kept-for-sure / tied scores of the unit in the slices before this one
 };
 
-// grid: units; 256 threads, 8 bins each
-__global__ __launch_bounds__(kWideThreads) void sel_pick_kernel(const int32_t *__restrict__ k_per_head, int L, int H,
-                                                                PromptTab tab, SliceTab st,
-                                                                const uint16_t *__restrict__ part,
-                                                                SelPick *__restrict__ picks,
-                                                                SelSlice *__restrict__ ss,
-                                                                uint32_t *__restrict__ failed)
+// The boundary bin of unit u: the bin that holds its B-th best score, and how many of that bin's entries are kept
+// (B = 0: {kBins, 0}, nothing is kept; B = N: {-1, 0}, everything is).  Called by all 256 threads of a workgroup,
+// 8 bins each; c_own[i] receives the count of bin 8 tid + i in slice `own` of the unit (own < 0: not asked for).
+// wtot: 4 words, s_pick: 2 words of LDS; the result is valid for every thread after the call.
+__device__ __forceinline__ SelPick pick_boundary_bin(const uint16_t *__restrict__ part, int64_t slice0, int S, int B, int N, int own,
+                                                     uint32_t (&c_own)[8], uint32_t *wtot, int32_t *s_pick)
 {
-    __shared__ uint32_t wtot[kWideThreads / 64];
-    __shared__ int32_t s_bT;
-    __shared__ uint32_t s_need;
-    const int u = blockIdx.x;
-    const int lh = u % (L * H), p = u / (L * H);
-    const int N = tab.tok_off[p + 1] - tab.tok_off[p];
-    const int S = (N + kSlice - 1) / kSlice;
-    const int B = min(max(k_per_head[u], 0), N);
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-    const int64_t slice0 = (int64_t)st.off[p] + (int64_t)lh * S;
-    if (tid == 0) failed[u] = 0u;
-    if (B == 0 || B == N) {                                          // no threshold to find
-        if (tid == 0) picks[u] = SelPick{B == 0 ? kBins : -1, 0u};
-        for (int s = tid; s < S; s += kWideThreads) ss[slice0 + s].above = B == 0 ? 0u : (uint32_t)min(kSlice, N - s * kSlice);
-        return;
-    }
     const uint4 *rows = reinterpret_cast<const uint4 *>(part + slice0 * kBins);
     uint32_t c[8];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) c[i] = 0u;
+    for (int i = 0; i < 8; ++i) { c[i] = 0u; c_own[i] = 0u; }
     for (int s0 = 0; s0 < S; s0 += 4) {
         uint4 r[4];
 #pragma unroll
@@ -70,11 +54,17 @@ __global__ __launch_bounds__(kWideThreads) void sel_pick_kernel(const int32_t *_
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             if (s0 + i < S) {
-                c[0] += r[i].x & 0xffffu; c[1] += r[i].x >> 16; c[2] += r[i].y & 0xffffu; c[3] += r[i].y >> 16;
-                c[4] += r[i].z & 0xffffu; c[5] += r[i].z >> 16; c[6] += r[i].w & 0xffffu; c[7] += r[i].w >> 16;
+                const uint32_t t[8] = {r[i].x & 0xffffu, r[i].x >> 16, r[i].y & 0xffffu, r[i].y >> 16,
+                                       r[i].z & 0xffffu, r[i].z >> 16, r[i].w & 0xffffu, r[i].w >> 16};
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    c[e] += t[e];
+                    if (s0 + i == own) c_own[e] = t[e];
+                }
             }
         }
     }
+    if (B == 0 || B == N) return SelPick{B == 0 ? kBins : -1, 0u};  // no threshold to find (uniform in the workgroup)
     uint32_t group = 0u;
 #pragma unroll
     for (int i = 0; i < 8; ++i) group += c[i];
@@ -92,32 +82,29 @@ __global__ __launch_bounds__(kWideThreads) void sel_pick_kernel(const int32_t *_
     if (cum < want && want <= incl) {
 #pragma unroll
         for (int i = 7; i >= 0; --i) {
-            if (cum < want && want <= cum + c[i]) { s_bT = tid * 8 + i; s_need = want - cum; }
+            if (cum < want && want <= cum + c[i]) { s_pick[0] = tid * 8 + i; s_pick[1] = (int32_t)(want - cum); }
             cum += c[i];
         }
     }
     __syncthreads();
-    const int bT = s_bT;
-    if (tid == 0) picks[u] = SelPick{bT, s_need};
-    // per slice: scores in bins above bT (wave w takes the slices w, w + 4, ...; lane = 32 bins)
-    for (int s = w; s < S; s += kWideThreads / 64) {
-        const uint16_t *row = part + (slice0 + s) * kBins;
-        uint32_t a = 0u;
-        for (int b = lane; b < kBins; b += 64) a += b > bT ? (uint32_t)row[b] : 0u;
-        a = wave_sum(a);
-        if (lane == 0) ss[slice0 + s].above = a;
-    }
+    return SelPick{s_pick[0], (uint32_t)s_pick[1]};
 }
 
-// grid: slices
-__global__ __launch_bounds__(kWideThreads) void sel_collect_kernel(const float *__restrict__ scores, int L, int H,
+// grid: slices.  Every slice's workgroup finds the boundary bin of its unit itself from the unit's slice histograms
+// (a few 4 KB rows that the histogram kernel has just written: cheaper than a kernel of its own in between), counts
+// its own slice's scores above that bin, and copies its scores of that bin into its segment.  The first slice's
+// workgroup records the unit's pick.
+__global__ __launch_bounds__(kWideThreads) void sel_collect_kernel(const float *__restrict__ scores,
+                                                                   const int32_t *__restrict__ k_per_head, int L, int H,
                                                                    PromptTab tab, SliceTab st,
-                                                                   const SelPick *__restrict__ picks,
+                                                                   const uint16_t *__restrict__ part,
+                                                                   SelPick *__restrict__ picks,
                                                                    uint32_t *__restrict__ seg,
-                                                                   SelSlice *__restrict__ ss,
-                                                                   uint32_t *__restrict__ failed)
+                                                                   SelSlice *__restrict__ ss)
 {
     __shared__ uint32_t n_hit;
+    __shared__ uint32_t wtot[kWideThreads / 64];
+    __shared__ int32_t s_pick[2];
     int p, lh, s, S;
     locate(st, tab, blockIdx.x, p, lh, s, S);
     const int u = p * L * H + lh;
@@ -128,9 +115,23 @@ __global__ __launch_bounds__(kWideThreads) void sel_collect_kernel(const float *
     const __amdgpu_buffer_rsrc_t vals = slice_values(sc, s, N);
 #pragma unroll
     for (int j = 0; j < kPerThread; ++j) v[j] = slice_value(vals, tid, j);
-    const int bT = picks[u].bT;
+    uint32_t c_own[8];
+    const SelPick pk = pick_boundary_bin(part, blockIdx.x - s, S, min(max(k_per_head[u], 0), N), N, s, c_own, wtot, s_pick);
+    const int bT = pk.bT;
+    {                                                                // this slice's scores in bins above bT
+        uint32_t a = 0u;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) a += tid * 8 + i > bT ? c_own[i] : 0u;
+        a = wave_sum(a);
+        __syncthreads();                                             // (wtot is free again)
+        if ((tid & 63) == 0) wtot[tid >> 6] = a;
+    }
     if (tid == 0) n_hit = 0u;
     __syncthreads();
+    if (tid == 0) {
+        ss[blockIdx.x].above = (wtot[0] + wtot[1]) + (wtot[2] + wtot[3]);
+        if (s == 0) picks[u] = pk;
+    }
     uint32_t *out = seg + (int64_t)blockIdx.x * kSeg;
     if (bT >= 0 && bT < kBins) {
 #pragma unroll
@@ -142,10 +143,7 @@ __global__ __launch_bounds__(kWideThreads) void sel_collect_kernel(const float *
         }
     }
     __syncthreads();
-    if (tid == 0) {
-        ss[blockIdx.x].n = n_hit;
-        if (n_hit > (uint32_t)kSeg) failed[u] = 1u;
-    }
+    if (tid == 0) ss[blockIdx.x].n = n_hit;                          // more than kSeg: the finishing kernel sees it and walks the scores
 }
 
 // grid: units; one wavefront
@@ -154,7 +152,7 @@ __global__ __launch_bounds__(64) void sel_finish_kernel(const float *__restrict_
                                                         PromptTab tab, SliceTab st,
                                                         const SelPick *__restrict__ picks,
                                                         const uint32_t *__restrict__ seg, SelSlice *__restrict__ ss,
-                                                        uint32_t *__restrict__ failed, SelUnit *__restrict__ sel)
+                                                        SelUnit *__restrict__ sel)
 {
     __shared__ uint32_t keys[kList];
     __shared__ uint32_t hist[256];
@@ -174,7 +172,7 @@ __global__ __launch_bounds__(64) void sel_finish_kernel(const float *__restrict_
         if (lane == 0) sel[u] = SelUnit{0u, 0u, pk.bT < 0 ? 1u : 2u, 0u};
         return;
     }
-    bool bad = failed[u] != 0u;
+    bool bad = false;
     uint32_t n = 0u;
     for (int s = 0; s < S && !bad; ++s) {
         const uint32_t c = ss[slice0 + s].n;
@@ -342,7 +340,7 @@ __global__ __launch_bounds__(kWideThreads) void sel_compact_kernel(const float *
 }
 
 struct WideWs {
-    size_t part, picks, ss, seg, sel, failed, total;
+    size_t part, picks, ss, seg, sel, total;
 };
 
 WideWs wide_ws(int L, int H, const PromptTab &tab)
@@ -356,7 +354,6 @@ WideWs wide_ws(int L, int H, const PromptTab &tab)
     w.ss = off;      off += align256(slices * sizeof(SelSlice));
     w.seg = off;     off += align256(slices * kSeg * sizeof(uint32_t));
     w.sel = off;     off += align256(units * sizeof(SelUnit));
-    w.failed = off;  off += align256(units * sizeof(uint32_t));
     w.total = off;
     return w;
 }
@@ -380,12 +377,10 @@ hipError_t launch_select_wide(const float *scores, const int32_t *k_per_head, in
     SelSlice *ss = (SelSlice *)(base + lay.ss);
     uint32_t *seg = (uint32_t *)(base + lay.seg);
     SelUnit *sel = (SelUnit *)(base + lay.sel);
-    uint32_t *failed = (uint32_t *)(base + lay.failed);
     const unsigned units = (unsigned)(tab.n * L * H);
     slice_hist_kernel<<<(unsigned)slices, kWideThreads, 0, st>>>(scores, tab, stab, part);
-    sel_pick_kernel<<<units, kWideThreads, 0, st>>>(k_per_head, L, H, tab, stab, part, picks, ss, failed);
-    sel_collect_kernel<<<(unsigned)slices, kWideThreads, 0, st>>>(scores, L, H, tab, stab, picks, seg, ss, failed);
-    sel_finish_kernel<<<units, 64, 0, st>>>(scores, k_per_head, L, H, tab, stab, picks, seg, ss, failed, sel);
+    sel_collect_kernel<<<(unsigned)slices, kWideThreads, 0, st>>>(scores, k_per_head, L, H, tab, stab, part, picks, seg, ss);
+    sel_finish_kernel<<<units, 64, 0, st>>>(scores, k_per_head, L, H, tab, stab, picks, seg, ss, sel);
     sel_compact_kernel<<<(unsigned)slices, kWideThreads, 0, st>>>(scores, L, H, tab, stab, sel, ss, head_off, row_capacity,
                                                                  near_tol, kept_idx, near_count);
     return hipGetLastError();
