@@ -136,9 +136,10 @@ hipError_t launch_budget_wide(const float *scores, int L, int H, const PromptTab
 // ---- selection, ordered compaction, gather ----
 // wide_ws: scratch of select_wide_ws_bytes() for the slice-wise selection (NULL: per-unit kernels only)
 size_t select_wide_ws_bytes(int L, int H, const PromptTab &tab);
+bool select_wide_places_units(int n_units);           // launch_select_wide can fill head_off and zero near_count itself
 hipError_t launch_select_wide(const float *scores, const int32_t *k_per_head, int L, int H, const PromptTab &tab,
-                              float near_tol, const int64_t *head_off, int64_t row_capacity, int32_t *kept_idx,
-                              int64_t *near_count, void *ws, hipStream_t st);
+                              float near_tol, int64_t *head_off, int64_t row_capacity, int32_t *kept_idx,
+                              int64_t *near_count, bool with_head_off, void *ws, hipStream_t st);
 hipError_t launch_select_compact(const void *keys, const void *values, const RowMap &km, const RowMap &vm,
                                  void *wide_ws, const float *scores,
                                  const int32_t *k_per_head, int L, int H, int d, int dv, int esize,

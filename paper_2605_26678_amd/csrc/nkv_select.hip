@@ -390,18 +390,20 @@ hipError_t launch_select_compact(const void *keys, const void *values, const Row
                                  int64_t *near_count, bool in_place, const Prof &prof, hipStream_t st)
 {
     const int n_units = tab.n * L * H;
-    head_off_kernel<<<1, kThreads, 0, st>>>(k_per_head, L, H, tab, head_off, near_count);
     int nmax = 0;
     for (int p = 0; p < tab.n; ++p) nmax = max(nmax, tab.tok_off[p + 1] - tab.tok_off[p]);
+    const bool wide = wide_ws != nullptr && (nmax > 16384 || n_units >= 2048);
+    const bool wide_places = wide && select_wide_places_units(n_units);
+    if (!wide_places) head_off_kernel<<<1, kThreads, 0, st>>>(k_per_head, L, H, tab, head_off, near_count);
     prof.begin(NKV_KERNEL_SELECT, st);
 #define NKV_SELECT_FAST(EPT)                                                                              \
     select_fast_kernel<EPT><<<(unsigned)n, kSelThreads, 0, st>>>(scores, k_per_head, L, H, tab, u0, near_tol, \
                                                                  head_off, row_capacity, kept_idx, near_count)
     // Slice-wise kernels where a head has more than two slices or there are thousands of units, and the caller
     // gave scratch (for a few hundred units of up to two slices the six launches cost what they save).
-    if (wide_ws != nullptr && (nmax > 16384 || n_units >= 2048)) {
+    if (wide) {
         const hipError_t e = launch_select_wide(scores, k_per_head, L, H, tab, near_tol, head_off, row_capacity,
-                                                kept_idx, near_count, wide_ws, st);
+                                                kept_idx, near_count, wide_places, wide_ws, st);
         if (e != hipSuccess) return e;
     } else if (nmax <= 32 * kSelThreads)
         for_each_length_class(tab, L * H, [&](int ept, int u0, int n) {

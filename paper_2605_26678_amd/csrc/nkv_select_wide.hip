@@ -152,13 +152,30 @@ __global__ __launch_bounds__(64) void sel_finish_kernel(const float *__restrict_
                                                         PromptTab tab, SliceTab st,
                                                         const SelPick *__restrict__ picks,
                                                         const uint32_t *__restrict__ seg, SelSlice *__restrict__ ss,
-                                                        SelUnit *__restrict__ sel)
+                                                        SelUnit *__restrict__ sel, int64_t *__restrict__ head_off,
+                                                        int64_t *__restrict__ near_count)
 {
     __shared__ uint32_t keys[kList];
     __shared__ uint32_t hist[256];
     const int u = blockIdx.x, lane = threadIdx.x;
     const int lh = u % (L * H), p = u / (L * H);
     const int N = tab.tok_off[p + 1] - tab.tok_off[p];
+    if (head_off) {
+        // With a few thousand units at most, this wavefront also places its unit in the output -- the rows the
+        // units in front of it keep -- which saves the scan kernel that otherwise runs first.
+        const int n_units = tab.n * L * H;
+        unsigned long long run = 0ull;
+        for (int v = lane; v < u; v += 64) {
+            const int pv = v / (L * H);
+            run += (unsigned long long)min(max(k_per_head[v], 0), tab.tok_off[pv + 1] - tab.tok_off[pv]);
+        }
+        run = wave_sum(run);
+        if (lane == 0) {
+            head_off[u] = (int64_t)run;
+            if (u == n_units - 1) head_off[n_units] = (int64_t)run + min(max(k_per_head[u], 0), N);
+            if (u == 0 && near_count) *near_count = 0;               // the compaction kernel, next on the stream, adds to it
+        }
+    }
     const int S = (N + kSlice - 1) / kSlice;
     const int64_t slice0 = (int64_t)st.off[p] + (int64_t)lh * S;
     const SelPick pk = picks[u];
@@ -362,11 +379,13 @@ WideWs wide_ws(int L, int H, const PromptTab &tab)
 
 size_t select_wide_ws_bytes(int L, int H, const PromptTab &tab) { return wide_ws(L, H, tab).total; }
 
-// Enqueues the five kernels (head_off must already be on the stream).  near_count, if given, must have been
-// zeroed on the stream (head_off_kernel does).
+// Enqueues the four kernels.  with_head_off: head_off and the zeroing of near_count are not on the stream yet and
+// the finishing kernel does them (select_wide_places_units() says when it can).
+bool select_wide_places_units(int n_units) { return n_units <= 4096; }
+
 hipError_t launch_select_wide(const float *scores, const int32_t *k_per_head, int L, int H, const PromptTab &tab,
-                              float near_tol, const int64_t *head_off, int64_t row_capacity, int32_t *kept_idx,
-                              int64_t *near_count, void *ws, hipStream_t st)
+                              float near_tol, int64_t *head_off, int64_t row_capacity, int32_t *kept_idx,
+                              int64_t *near_count, bool with_head_off, void *ws, hipStream_t st)
 {
     SliceTab stab;
     const int slices = fill_slices(L, H, tab, &stab);
@@ -380,7 +399,8 @@ hipError_t launch_select_wide(const float *scores, const int32_t *k_per_head, in
     const unsigned units = (unsigned)(tab.n * L * H);
     slice_hist_kernel<<<(unsigned)slices, kWideThreads, 0, st>>>(scores, tab, stab, part);
     sel_collect_kernel<<<(unsigned)slices, kWideThreads, 0, st>>>(scores, k_per_head, L, H, tab, stab, part, picks, seg, ss);
-    sel_finish_kernel<<<units, 64, 0, st>>>(scores, k_per_head, L, H, tab, stab, picks, seg, ss, sel);
+    sel_finish_kernel<<<units, 64, 0, st>>>(scores, k_per_head, L, H, tab, stab, picks, seg, ss, sel,
+                                            with_head_off ? head_off : nullptr, near_count);
     sel_compact_kernel<<<(unsigned)slices, kWideThreads, 0, st>>>(scores, L, H, tab, stab, sel, ss, head_off, row_capacity,
                                                                  near_tol, kept_idx, near_count);
     return hipGetLastError();

@@ -96,6 +96,8 @@ SWEEP = [
     ("nine_slices", 1, 2, 128, [70000, 9000], "bf16", 0), # 274 blocks in the unit: two rounds of the dies' runs;
                                                           # more than the matrix-core scan takes: vector scan
     ("unit_256_blocks", 1, 2, 128, [65533, 300], "bf16", 0),   # the longest unit the matrix-core scan takes
+    ("units_4096", 16, 8, 64, [60] * 31 + [9000], "bf16", 0),  # slice-wise selection, which also places the units in the output
+    ("units_4224", 33, 8, 64, [50 + i for i in range(16)], "bf16", 0),   # more units than it places: the scan kernel in front
 ]
 
 
